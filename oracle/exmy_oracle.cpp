@@ -1,0 +1,402 @@
+// eXmY CPU oracle: TEST INFRASTRUCTURE ONLY.
+//
+// A plain, slow, scalar implementation of what the eXmY tensor codec computes,
+// written from the paper's definitions in real-number terms (double precision,
+// frexp / ldexp / nearbyint), with plain loops for the bit packing.  It shares
+// no code, header, table or constant with the HIP library and must never be
+// called from the product path: only tests, the smoke check and the
+// cpu_baseline leg of the benchmark may use it.
+//
+// Paper passages followed (arxiv 2405.13938):
+//   * Section 2 "Format", "Subnormals": 1 sign bit, X exponent bits, Y mantissa
+//     bits; exponent field 0 with non-zero mantissa is a subnormal; every code
+//     is a finite value (Section 5).
+//   * Section 2 "Exponent Bias", "Metadata": the bias is software defined; the
+//     metadatum is the maximum biased (fp32/bf16, bias 127) exponent, max_exp,
+//     which is the exponent the top eXmY exponent code stands for.
+//   * Section 2 "Rounding": round-to-nearest-even to Y mantissa bits.
+//   * Section 2.1 "Emulation": outcomes saturate / round / subnormal / flush;
+//     NaN and Inf are preserved.
+//   * Section 2.2.1 "Type Conversion" and 2.2.2 "Bit Packing & Unpacking:
+//     Power-of-2 Decomposition", Fig. 2.
+//   * Section 3.1 "Exponent Distribution": 256-bin histogram of the biased
+//     exponent; keeping the top 2^X-1 exponents plus zero.
+//
+// Readings where the paper is silent (documented in the repository's design
+// notes):
+//   - code bit order is sign | exponent | mantissa (IEEE order);
+//   - the binary expansion of W = 1+X+Y is walked from its largest power of two
+//     s downwards while the code is walked from bit 0 upwards, so the widest
+//     plane holds the least significant bits (Fig. 2 drawn MSB-left);
+//   - a group is 8 consecutive elements; element j of a group sits at bits
+//     [s*j, s*j+s) of a little-endian 8s-bit word; planes are laid back to
+//     back, widest first; a ragged last group is padded with zero codes;
+//   - a rounding tie goes to the even multiple of the quantum of x's binade
+//     (round-half-even on the significand, what nearbyint gives below): the
+//     even code whenever Y >= 1; with Y = 0 a tie 1.5 * 2^e goes up to 2^(e+1);
+//   - encode maps +-Inf and NaN to sign + largest magnitude code (parity
+//     unpinned by the paper: a convention of this repository);
+//   - X = 8 forces max_exp = 255 (identity exponent map); exponent code 255 is
+//     not produced and decodes to the largest finite value (parity unpinned);
+//   - ragged n (n % 8 != 0) handling is likewise parity unpinned.
+//
+// Pinned by tests/test_oracle_pins.py and tests/test_oracle_pack.py against the
+// paper's worked examples, library float8 / bfloat16 / float16 conversions and a
+// brute-force nearest-value search.
+
+#include <cmath>
+#include <cstdint>
+#include <cstdlib>
+#include <cstring>
+#include <thread>
+#include <vector>
+#include <algorithm>
+
+extern "C" {
+
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum {
+  ORACLE_OK = 0,
+  ORACLE_ERR_NULL = 1,
+  ORACLE_ERR_FORMAT = 2,
+  ORACLE_ERR_MAX_EXP = 3,
+};
+
+}  // extern "C"
+
+namespace {
+
+struct Format {
+  int X, Y, max_exp;
+  int emin8;       // biased (127) exponent of the binade with exponent code 1
+  int64_t cmax;    // largest magnitude code that encode may produce
+  int W;
+};
+
+// Mantissa bits the float container itself stores.
+int container_mantissa(int dt) { return dt == ORACLE_F32 ? 23 : 7; }
+
+// Section 2.1: a format can be emulated in (and therefore converted from / to)
+// a float container when its exponent and mantissa fit.  With X = 0 a code has
+// only Y significant bits, one fewer than a normal with Y mantissa bits, so one
+// more is allowed.
+int check_format(int dt, int X, int Y, int max_exp, bool packed, Format* f) {
+  if (dt != ORACLE_F32 && dt != ORACLE_BF16) return ORACLE_ERR_FORMAT;
+  if (X < 0 || X > 8 || Y < 0) return ORACLE_ERR_FORMAT;
+  const int P = container_mantissa(dt);
+  if (X >= 1 ? (Y > P) : (Y > P + 1)) return ORACLE_ERR_FORMAT;
+  if (packed && 1 + X + Y > 16) return ORACLE_ERR_FORMAT;
+  if (X == 8) {
+    if (max_exp != 255) return ORACLE_ERR_MAX_EXP;
+  } else if (X == 0) {
+    if (max_exp < 0 || max_exp > 253) return ORACLE_ERR_MAX_EXP;
+    // the quantum 2^(max_exp + 1 - 127 - Y) must be a value of the container
+    if (Y == P + 1 && max_exp < 1) return ORACLE_ERR_MAX_EXP;
+  } else {
+    if (max_exp < (1 << X) - 1 || max_exp > 254) return ORACLE_ERR_MAX_EXP;
+  }
+  f->X = X;
+  f->Y = Y;
+  f->max_exp = max_exp;
+  f->W = 1 + X + Y;
+  f->emin8 = max_exp - (1 << X) + 2;
+  f->cmax = ((int64_t)1 << (X + Y)) - 1;
+  if (X == 8) f->cmax = ((int64_t)254 << Y) | (((int64_t)1 << Y) - 1);
+  return ORACLE_OK;
+}
+
+// The value a magnitude code stands for (Section 2 "Format", "Subnormals",
+// "Exponent Bias").
+double code_magnitude(const Format& f, int64_t c) {
+  if (f.X == 8 && c > f.cmax) c = f.cmax;
+  const int64_t E = c >> f.Y;
+  const int64_t M = c & (((int64_t)1 << f.Y) - 1);
+  if (E == 0) return std::ldexp((double)M, f.emin8 - 127 - f.Y);
+  return std::ldexp((double)(((int64_t)1 << f.Y) + M), (int)(E - 1) + f.emin8 - 127 - f.Y);
+}
+
+// Magnitude code of a finite, non-negative real a (Section 2 "Rounding",
+// Section 2.1 outcomes).
+int64_t magnitude_code(const Format& f, double a) {
+  const double smallest_normal = std::ldexp(1.0, f.emin8 - 127);
+  int64_t c;
+  if (a < smallest_normal) {
+    // subnormal range: fixed quantum; may round to 0 (flush) or up to the
+    // smallest normal, whose code is 2^Y.
+    c = (int64_t)std::nearbyint(std::ldexp(a, -(f.emin8 - 127 - f.Y)));
+  } else {
+    int ee;
+    (void)std::frexp(a, &ee);  // a = m * 2^ee, m in [0.5, 1)
+    int e = ee - 1;            // floor(log2 a)
+    int64_t k = (int64_t)std::nearbyint(std::ldexp(a, -(e - f.Y)));  // in [2^Y, 2^(Y+1)]
+    if (k == ((int64_t)1 << (f.Y + 1))) {
+      e += 1;
+      k = (int64_t)1 << f.Y;
+    }
+    const int64_t E = (int64_t)e + 127 - f.emin8 + 1;
+    c = (E << f.Y) + (k - ((int64_t)1 << f.Y));
+  }
+  return std::min(c, f.cmax);  // saturate to the largest normal
+}
+
+inline uint32_t load_bits(const void* src, int dt, uint64_t i) {
+  if (dt == ORACLE_F32) return ((const uint32_t*)src)[i];
+  return (uint32_t)((const uint16_t*)src)[i] << 16;  // bf16 = upper half of fp32
+}
+
+inline void store_bits(void* dst, int dt, uint64_t i, uint32_t bits) {
+  if (dt == ORACLE_F32)
+    ((uint32_t*)dst)[i] = bits;
+  else {
+    if (bits & 0xFFFFu) std::abort();  // every decoded value must be exact in bf16
+    ((uint16_t*)dst)[i] = (uint16_t)(bits >> 16);
+  }
+}
+
+inline float bits_to_float(uint32_t b) {
+  float f;
+  std::memcpy(&f, &b, 4);
+  return f;
+}
+inline uint32_t float_to_bits(float f) {
+  uint32_t b;
+  std::memcpy(&b, &f, 4);
+  return b;
+}
+
+// Full W-bit code of one element.
+uint32_t encode_one(const Format& f, uint32_t bits) {
+  const uint32_t sign = bits >> 31;
+  const float x = bits_to_float(bits);
+  int64_t c;
+  if (std::isnan(x) || std::isinf(x))
+    c = f.cmax;
+  else
+    c = magnitude_code(f, std::fabs((double)x));
+  return (uint32_t)((sign << (f.X + f.Y)) | (uint32_t)c);
+}
+
+// fp32 bit pattern of the value of a full code (exact by construction).
+uint32_t decode_one(const Format& f, uint32_t code) {
+  const uint32_t sign = (code >> (f.X + f.Y)) & 1u;
+  const int64_t c = code & (uint32_t)((((int64_t)1) << (f.X + f.Y)) - 1);
+  const float v = (float)code_magnitude(f, c);
+  return float_to_bits(v) | (sign << 31);
+}
+
+// Segment widths of the power-of-2 decomposition of W, widest first
+// (Section 2.2.2: 7 = 4 + 2 + 1, 5 = 4 + 1).
+int plane_list(int W, int seg[8]) {
+  int n = 0;
+  for (int s = 16; s >= 1; s >>= 1)
+    if (W & s) seg[n++] = s;
+  return n;
+}
+
+template <class Fn>
+void parallel_ranges(uint64_t n_items, int threads, Fn fn) {
+  if (threads <= 1 || n_items < 4096) {
+    fn((uint64_t)0, n_items);
+    return;
+  }
+  std::vector<std::thread> pool;
+  const uint64_t per = (n_items + threads - 1) / threads;
+  for (int t = 0; t < threads; ++t) {
+    const uint64_t a = std::min(n_items, per * t), b = std::min(n_items, per * (t + 1));
+    if (a < b) pool.emplace_back([=] { fn(a, b); });
+  }
+  for (auto& th : pool) th.join();
+}
+
+// Bit packing, Fig. 2: the codes of groups [g0, g1) go to every plane.
+// codes[i - base] is the code of element i.
+void pack_groups(const uint32_t* codes, uint64_t base, uint64_t n, int W, uint8_t* out, uint64_t g0, uint64_t g1) {
+  const uint64_t G = (n + 7) / 8;
+  int seg[8];
+  const int np = plane_list(W, seg);
+  uint64_t plane_off = 0;
+  int lo = 0;
+  for (int p = 0; p < np; ++p) {
+    const int s = seg[p];
+    uint8_t* plane = out + plane_off;
+    for (uint64_t g = g0; g < g1; ++g) {
+      // one 8s-bit little-endian word per group: element j at bits [s*j, s*j+s)
+      for (int b = 0; b < s; ++b) plane[g * s + b] = 0;
+      for (int j = 0; j < 8; ++j) {
+        const uint64_t i = g * 8 + j;
+        const uint32_t code = i < n ? codes[i - base] : 0u;
+        const uint32_t field = (code >> lo) & ((1u << s) - 1u);
+        for (int b = 0; b < s; ++b) {
+          const int bit = s * j + b;
+          if ((field >> b) & 1u) plane[g * s + bit / 8] |= (uint8_t)(1u << (bit % 8));
+        }
+      }
+    }
+    plane_off += G * (uint64_t)s;
+    lo += s;
+  }
+}
+
+void unpack_groups(const uint8_t* in, uint64_t n, int W, uint32_t* codes, uint64_t base, uint64_t g0, uint64_t g1) {
+  const uint64_t G = (n + 7) / 8;
+  int seg[8];
+  const int np = plane_list(W, seg);
+  for (uint64_t g = g0; g < g1; ++g)
+    for (int j = 0; j < 8; ++j)
+      if (g * 8 + j < n) codes[g * 8 + j - base] = 0;
+  uint64_t plane_off = 0;
+  int lo = 0;
+  for (int p = 0; p < np; ++p) {
+    const int s = seg[p];
+    const uint8_t* plane = in + plane_off;
+    for (uint64_t g = g0; g < g1; ++g) {
+      for (int j = 0; j < 8; ++j) {
+        const uint64_t i = g * 8 + j;
+        if (i >= n) continue;
+        uint32_t field = 0;
+        for (int b = 0; b < s; ++b) {
+          const int bit = s * j + b;
+          if ((plane[g * s + bit / 8] >> (bit % 8)) & 1u) field |= 1u << b;
+        }
+        codes[i - base] |= field << lo;
+      }
+    }
+    plane_off += G * (uint64_t)s;
+    lo += s;
+  }
+}
+
+}  // namespace
+
+extern "C" {
+
+// ceil(n/8) * W bytes: perfect compression (Section 2.2.2).
+uint64_t exmy_oracle_packed_bytes(uint64_t n, int X, int Y) { return ((n + 7) / 8) * (uint64_t)(1 + X + Y); }
+
+int exmy_oracle_check_format(int dt, int X, int Y, int max_exp, int packed) {
+  Format f;
+  return check_format(dt, X, Y, max_exp, packed != 0, &f);
+}
+
+// Real value of a full code (sign included), for value-set enumeration.
+double exmy_oracle_code_value(int X, int Y, int max_exp, uint32_t code) {
+  Format f;
+  if (check_format(ORACLE_F32, X, Y, max_exp, false, &f) != ORACLE_OK) return NAN;
+  const uint32_t sign = (code >> (X + Y)) & 1u;
+  const double m = code_magnitude(f, code & (uint32_t)((((int64_t)1) << (X + Y)) - 1));
+  return sign ? -m : m;
+}
+
+// Step 1 of the codec (Section 2.2.1): float -> eXmY code in a 32-bit container.
+int exmy_oracle_to_codes(const void* src, int dt, uint64_t n, int X, int Y, int max_exp, uint32_t* codes,
+                         int threads) {
+  if ((!src || !codes) && n) return ORACLE_ERR_NULL;
+  Format f;
+  if (int rc = check_format(dt, X, Y, max_exp, true, &f)) return rc;
+  parallel_ranges(n, threads, [&](uint64_t a, uint64_t b) {
+    for (uint64_t i = a; i < b; ++i) codes[i] = encode_one(f, load_bits(src, dt, i));
+  });
+  return ORACLE_OK;
+}
+
+// Inverse of step 1: code -> float of type dt.
+int exmy_oracle_from_codes(const uint32_t* codes, int dt, uint64_t n, int X, int Y, int max_exp, void* dst,
+                           int threads) {
+  if ((!dst || !codes) && n) return ORACLE_ERR_NULL;
+  Format f;
+  if (int rc = check_format(dt, X, Y, max_exp, true, &f)) return rc;
+  parallel_ranges(n, threads, [&](uint64_t a, uint64_t b) {
+    for (uint64_t i = a; i < b; ++i) store_bits(dst, dt, i, decode_one(f, codes[i]));
+  });
+  return ORACLE_OK;
+}
+
+// Step 2 of the codec (Section 2.2.2): W-bit codes -> planes.
+int exmy_oracle_pack(const uint32_t* codes, uint64_t n, int W, uint8_t* out, int threads) {
+  if ((!codes || !out) && n) return ORACLE_ERR_NULL;
+  if (W < 1 || W > 16) return ORACLE_ERR_FORMAT;
+  parallel_ranges((n + 7) / 8, threads, [&](uint64_t a, uint64_t b) { pack_groups(codes, 0, n, W, out, a, b); });
+  return ORACLE_OK;
+}
+
+int exmy_oracle_unpack(const uint8_t* in, uint64_t n, int W, uint32_t* codes, int threads) {
+  if ((!codes || !in) && n) return ORACLE_ERR_NULL;
+  if (W < 1 || W > 16) return ORACLE_ERR_FORMAT;
+  parallel_ranges((n + 7) / 8, threads, [&](uint64_t a, uint64_t b) { unpack_groups(in, n, W, codes, 0, a, b); });
+  return ORACLE_OK;
+}
+
+// encode = step 1 then step 2.
+int exmy_oracle_encode(const void* src, int dt, uint64_t n, int X, int Y, int max_exp, uint8_t* dst_packed,
+                       int threads) {
+  if ((!src || !dst_packed) && n) return ORACLE_ERR_NULL;
+  Format f;
+  if (int rc = check_format(dt, X, Y, max_exp, true, &f)) return rc;
+  parallel_ranges((n + 7) / 8, threads, [&](uint64_t g0, uint64_t g1) {
+    // convert this range of groups, then pack it; ranges touch disjoint bytes
+    const uint64_t a = g0 * 8, b = std::min(n, g1 * 8);
+    std::vector<uint32_t> codes(b - a);
+    for (uint64_t i = a; i < b; ++i) codes[i - a] = encode_one(f, load_bits(src, dt, i));
+    pack_groups(codes.data(), a, n, f.W, dst_packed, g0, g1);
+  });
+  return ORACLE_OK;
+}
+
+int exmy_oracle_decode(const uint8_t* src_packed, int dt, uint64_t n, int X, int Y, int max_exp, void* dst,
+                       int threads) {
+  if ((!src_packed || !dst) && n) return ORACLE_ERR_NULL;
+  Format f;
+  if (int rc = check_format(dt, X, Y, max_exp, true, &f)) return rc;
+  parallel_ranges((n + 7) / 8, threads, [&](uint64_t g0, uint64_t g1) {
+    const uint64_t a = g0 * 8, b = std::min(n, g1 * 8);
+    std::vector<uint32_t> codes(b - a);
+    unpack_groups(src_packed, n, f.W, codes.data(), a, g0, g1);
+    for (uint64_t i = a; i < b; ++i) store_bits(dst, dt, i, decode_one(f, codes[i - a]));
+  });
+  return ORACLE_OK;
+}
+
+// Emulation (Section 2.1): quantise and dequantise in the element's own type;
+// NaN and +-Inf are returned bit-identical.
+int exmy_oracle_emulate(void* data, int dt, uint64_t n, int X, int Y, int max_exp, int threads) {
+  if (!data && n) return ORACLE_ERR_NULL;
+  Format f;
+  if (int rc = check_format(dt, X, Y, max_exp, false, &f)) return rc;
+  parallel_ranges(n, threads, [&](uint64_t a, uint64_t b) {
+    for (uint64_t i = a; i < b; ++i) {
+      const uint32_t bits = load_bits(data, dt, i);
+      const float x = bits_to_float(bits);
+      if (std::isnan(x) || std::isinf(x)) continue;
+      const int64_t c = magnitude_code(f, std::fabs((double)x));
+      const float v = (float)code_magnitude(f, c);
+      store_bits(data, dt, i, float_to_bits(v) | (bits & 0x80000000u));
+    }
+  });
+  return ORACLE_OK;
+}
+
+// 256-bin histogram of the biased exponent field (Section 3.1, Fig. 3): +-0 and
+// denormals fall in bin 0, Inf / NaN in bin 255.  Accumulates into hist.
+int exmy_oracle_exponent_histogram(const void* src, int dt, uint64_t n, uint64_t* hist256) {
+  if ((!src && n) || !hist256) return ORACLE_ERR_NULL;
+  if (dt != ORACLE_F32 && dt != ORACLE_BF16) return ORACLE_ERR_FORMAT;
+  for (uint64_t i = 0; i < n; ++i) hist256[(load_bits(src, dt, i) >> 23) & 0xFFu] += 1;
+  return ORACLE_OK;
+}
+
+// Smallest biased exponent e (0..254) such that at least `coverage` of the
+// finite elements have an exponent <= e (Section 3.1: keep the top exponents,
+// let the rest saturate or flush).  Returns -1 for an empty histogram.
+int exmy_oracle_max_exp_from_histogram(const uint64_t* hist256, double coverage) {
+  uint64_t total = 0;
+  for (int e = 0; e < 255; ++e) total += hist256[e];
+  if (total == 0) return -1;
+  uint64_t cum = 0;
+  for (int e = 0; e < 255; ++e) {
+    cum += hist256[e];
+    if ((double)cum >= coverage * (double)total) return e;
+  }
+  return 254;
+}
+
+}  // extern "C"

@@ -1,0 +1,153 @@
+"""ctypes binding of the scalar C++ oracle (``exmy_oracle.cpp``).
+
+Test infrastructure only.  Arrays are numpy: fp32 tensors as ``float32`` (or
+``uint32`` bit patterns), bf16 tensors as ``uint16`` bit patterns.
+"""
+import ctypes
+import os
+
+import numpy as np
+
+from . import build as _build
+
+F32, BF16 = 0, 1
+_STATUS = {0: "ok", 1: "null pointer", 2: "bad format", 3: "bad max_exp"}
+
+_lib = None
+
+
+def lib():
+    global _lib
+    if _lib is None:
+        path = _build.LIB
+        if not os.path.exists(path):
+            _build.build()
+        L = ctypes.CDLL(path)
+        u64, i32, vp, dbl = ctypes.c_uint64, ctypes.c_int, ctypes.c_void_p, ctypes.c_double
+        L.exmy_oracle_packed_bytes.restype = u64
+        L.exmy_oracle_packed_bytes.argtypes = [u64, i32, i32]
+        L.exmy_oracle_check_format.restype = i32
+        L.exmy_oracle_check_format.argtypes = [i32, i32, i32, i32, i32]
+        L.exmy_oracle_code_value.restype = dbl
+        L.exmy_oracle_code_value.argtypes = [i32, i32, i32, ctypes.c_uint32]
+        L.exmy_oracle_to_codes.argtypes = [vp, i32, u64, i32, i32, i32, vp, i32]
+        L.exmy_oracle_from_codes.argtypes = [vp, i32, u64, i32, i32, i32, vp, i32]
+        L.exmy_oracle_pack.argtypes = [vp, u64, i32, vp, i32]
+        L.exmy_oracle_unpack.argtypes = [vp, u64, i32, vp, i32]
+        L.exmy_oracle_encode.argtypes = [vp, i32, u64, i32, i32, i32, vp, i32]
+        L.exmy_oracle_decode.argtypes = [vp, i32, u64, i32, i32, i32, vp, i32]
+        L.exmy_oracle_emulate.argtypes = [vp, i32, u64, i32, i32, i32, i32]
+        L.exmy_oracle_exponent_histogram.argtypes = [vp, i32, u64, vp]
+        L.exmy_oracle_max_exp_from_histogram.restype = i32
+        L.exmy_oracle_max_exp_from_histogram.argtypes = [vp, dbl]
+        _lib = L
+    return _lib
+
+
+class OracleError(ValueError):
+    pass
+
+
+def _check(rc):
+    if rc != 0:
+        raise OracleError(_STATUS.get(rc, "status %d" % rc))
+
+
+def default_threads():
+    return len(os.sched_getaffinity(0)) if hasattr(os, "sched_getaffinity") else (os.cpu_count() or 1)
+
+
+def _src(a):
+    """Return (contiguous array, dtype enum) for an fp32 / bf16-bits array."""
+    a = np.ascontiguousarray(a)
+    if a.dtype == np.float32 or a.dtype == np.uint32:
+        return a, F32
+    if a.dtype == np.uint16:
+        return a, BF16
+    raise TypeError("expected float32/uint32 (fp32) or uint16 (bf16 bits), got %s" % a.dtype)
+
+
+def _ptr(a):
+    return a.ctypes.data_as(ctypes.c_void_p)
+
+
+def _out_dtype(dt):
+    return np.float32 if dt == F32 else np.uint16
+
+
+def packed_bytes(n, X, Y):
+    return int(lib().exmy_oracle_packed_bytes(n, X, Y))
+
+
+def check_format(dt, X, Y, max_exp, packed=True):
+    return int(lib().exmy_oracle_check_format(dt, X, Y, max_exp, int(packed)))
+
+
+def code_value(X, Y, max_exp, code):
+    return float(lib().exmy_oracle_code_value(X, Y, max_exp, int(code)))
+
+
+def to_codes(src, X, Y, max_exp, threads=1):
+    a, dt = _src(src)
+    codes = np.empty(a.size, dtype=np.uint32)
+    _check(lib().exmy_oracle_to_codes(_ptr(a), dt, a.size, X, Y, max_exp, _ptr(codes), threads))
+    return codes
+
+
+def from_codes(codes, dt, X, Y, max_exp, threads=1):
+    codes = np.ascontiguousarray(codes, dtype=np.uint32)
+    out = np.empty(codes.size, dtype=_out_dtype(dt))
+    _check(lib().exmy_oracle_from_codes(_ptr(codes), dt, codes.size, X, Y, max_exp, _ptr(out), threads))
+    return out
+
+
+def pack(codes, W, threads=1):
+    codes = np.ascontiguousarray(codes, dtype=np.uint32)
+    out = np.empty(((codes.size + 7) // 8) * W, dtype=np.uint8)
+    _check(lib().exmy_oracle_pack(_ptr(codes), codes.size, W, _ptr(out), threads))
+    return out
+
+
+def unpack(packed, n, W, threads=1):
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    assert packed.size == ((n + 7) // 8) * W
+    codes = np.empty(n, dtype=np.uint32)
+    _check(lib().exmy_oracle_unpack(_ptr(packed), n, W, _ptr(codes), threads))
+    return codes
+
+
+def encode(src, X, Y, max_exp, threads=1):
+    a, dt = _src(src)
+    out = np.empty(packed_bytes(a.size, X, Y), dtype=np.uint8)
+    _check(lib().exmy_oracle_encode(_ptr(a), dt, a.size, X, Y, max_exp, _ptr(out), threads))
+    return out
+
+
+def decode(packed, dt, n, X, Y, max_exp, threads=1):
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    assert packed.size == packed_bytes(n, X, Y)
+    out = np.empty(n, dtype=_out_dtype(dt))
+    _check(lib().exmy_oracle_decode(_ptr(packed), dt, n, X, Y, max_exp, _ptr(out), threads))
+    return out
+
+
+def emulate(src, X, Y, max_exp, threads=1):
+    """Returns a new array; the input is left alone."""
+    a, dt = _src(src)
+    out = a.copy()
+    _check(lib().exmy_oracle_emulate(_ptr(out), dt, out.size, X, Y, max_exp, threads))
+    return out
+
+
+def exponent_histogram(src, hist=None):
+    a, dt = _src(src)
+    if hist is None:
+        hist = np.zeros(256, dtype=np.uint64)
+    _check(lib().exmy_oracle_exponent_histogram(_ptr(a), dt, a.size, _ptr(hist)))
+    return hist
+
+
+def max_exp_from_histogram(hist, coverage):
+    hist = np.ascontiguousarray(hist, dtype=np.uint64)
+    assert hist.size == 256
+    return int(lib().exmy_oracle_max_exp_from_histogram(_ptr(hist), float(coverage)))
