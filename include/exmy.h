@@ -1,0 +1,121 @@
+/*
+ * exmy.h - C ABI of the MI355X (gfx950) eXmY tensor codec.
+ *
+ * eXmY (arxiv 2405.13938) is a float format with 1 sign bit, X exponent bits
+ * and Y mantissa bits, any width W = 1 + X + Y, subnormals, a software-defined
+ * exponent bias and no code points reserved for Inf / NaN (Section 2 "Format",
+ * "Subnormals", "Exponent Bias"; Section 5).  This library converts bf16 / fp32
+ * tensors to packed W-bit codes and back, and emulates the format in place.
+ *
+ * Conventions shared by every entry point
+ * ---------------------------------------
+ *  - All data pointers are DEVICE pointers owned by the caller.  The library
+ *    allocates nothing, frees nothing and never synchronises: work is enqueued
+ *    on `stream` (a hipStream_t passed as void*; NULL = the default stream) and
+ *    the call returns at once.  Arguments are validated on the host before any
+ *    launch; a failed validation launches nothing.
+ *  - Element pointers and packed pointers must be 16-byte aligned.
+ *  - `max_exp` is the paper's metadatum (Section 2 "Metadata"): the biased
+ *    (bias 127, as in fp32 / bf16) exponent that the top exponent code of the
+ *    format stands for.  The paper's exponent bias is 2^X - 1 + 127 - max_exp.
+ *    Valid: 2^X - 1 <= max_exp <= 254 for 1 <= X <= 7; 0 <= max_exp <= 253 for
+ *    X = 0 (and >= 1 when Y is one more than the container's mantissa);
+ *    max_exp = 255 exactly for X = 8 (identity exponent map).
+ *  - A format fits a container when X <= 8 and Y <= 7 (bf16) / 23 (fp32)
+ *    (Section 2.1); with X = 0 one more mantissa bit is allowed.  Packed codes
+ *    are limited to W <= 16.
+ *  - Rounding is round-to-nearest-even to Y mantissa bits (Section 2
+ *    "Rounding"); a tie goes to the even multiple of the quantum of the value's
+ *    binade.  Values under the smallest normal are rounded on the subnormal
+ *    grid and may flush to (signed) zero; values over the largest normal
+ *    saturate to it (Section 2.1).
+ *  - Code bit order: sign at bit W-1, then exponent, mantissa in the low Y
+ *    bits.
+ *
+ * Packed layout (Section 2.2.2 "Power-of-2 Decomposition", Fig. 2)
+ * ----------------------------------------------------------------
+ *  Elements are taken in groups of 8 consecutive values; G = ceil(n / 8); a
+ *  ragged last group is padded with zero codes.  W is split into its powers of
+ *  two, s_0 > s_1 > ... (7 = 4 + 2 + 1).  Walking the code from bit 0 upwards,
+ *  the widest segment takes the lowest bits.  Plane p is an array of G
+ *  little-endian words of s_p bytes (8 elements x s_p bits), element j of the
+ *  group at bits [s_p*j, s_p*j + s_p).  The planes lie back to back, widest
+ *  first: total G * W bytes.  For W = 7: G int32, then G int16, then G int8.
+ *  A shard [a, b) of the elements (a, b multiples of 8) is the slice
+ *  [a/8, b/8) of every plane.
+ */
+#ifndef EXMY_H_
+#define EXMY_H_
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum { EXMY_F32 = 0, EXMY_BF16 = 1 } exmy_dtype_t;
+
+typedef enum {
+  EXMY_OK = 0,
+  EXMY_ERR_NULL = 1,    /* a required pointer is NULL (and n > 0) */
+  EXMY_ERR_FORMAT = 2,  /* X, Y, W or dtype out of domain, or the dtype cannot hold the format */
+  EXMY_ERR_MAX_EXP = 3, /* max_exp outside the range valid for X */
+  EXMY_ERR_COUNT = 4,   /* n above EXMY_MAX_ELEMENTS */
+  EXMY_ERR_ALIGN = 5,   /* a pointer is not 16-byte aligned */
+  EXMY_ERR_DEVICE = 6   /* the HIP runtime reported an error at launch */
+} exmy_status_t;
+
+#define EXMY_MAX_ELEMENTS ((uint64_t)1 << 40)
+
+/* Bytes of the packed form of n elements: ceil(n / 8) * (1 + X + Y)
+ * (perfect compression, Section 2.2.2).  Host only; no validation. */
+size_t exmy_packed_bytes(uint64_t n, int X, int Y);
+
+/* Host-side validation of (dtype, X, Y, max_exp) as described above.  `packed`
+ * non-zero also applies the W <= 16 limit of the packed form. */
+exmy_status_t exmy_check_format(exmy_dtype_t dt, int X, int Y, int max_exp, int packed);
+
+/* Encode (Sections 2.2.1 + 2.2.2 fused): round n elements of type dt at `src`
+ * to eXmY codes and write the packed planes to `dst_packed`
+ * (exmy_packed_bytes(n, X, Y) bytes).  +-Inf and NaN become sign + largest
+ * magnitude code.  src and dst_packed must not overlap. */
+exmy_status_t exmy_encode(const void* src, exmy_dtype_t dt, uint64_t n, int X, int Y, int max_exp,
+                          void* dst_packed, void* stream);
+
+/* Decode (inverse of the above): unpack n codes from `src_packed` and write
+ * their values as type dt_out to `dst` (n elements).  Every code is a finite
+ * value, exactly representable in dt_out.  With X = 8 an exponent code of 255
+ * decodes to the largest finite value. */
+exmy_status_t exmy_decode(const void* src_packed, exmy_dtype_t dt_out, uint64_t n, int X, int Y, int max_exp,
+                          void* dst, void* stream);
+
+/* Emulate (Section 2.1): replace each of the n elements at `data_inout` by the
+ * eXmY value nearest to it, kept in the same type; NaN and +-Inf are left
+ * bit-identical.  No width limit beyond the container's (Y <= 7 / 23). */
+exmy_status_t exmy_emulate(void* data_inout, exmy_dtype_t dt, uint64_t n, int X, int Y, int max_exp, void* stream);
+
+/* 256-bin histogram of the biased exponent field (Section 3.1, Fig. 3): +-0 and
+ * denormals count in bin 0, Inf / NaN in bin 255.  ACCUMULATES into
+ * hist256_dev (256 uint64 on the device, 8-byte aligned): the caller zeroes it. */
+exmy_status_t exmy_exponent_histogram(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t* hist256_dev,
+                                      void* stream);
+
+/* exmy_encode and exmy_exponent_histogram in one pass over src. */
+exmy_status_t exmy_encode_with_histogram(const void* src, exmy_dtype_t dt, uint64_t n, int X, int Y, int max_exp,
+                                         void* dst_packed, uint64_t* hist256_dev, void* stream);
+
+/* Host helper for Section 3.1's technique (keep the top exponents, let the
+ * tail go): the smallest biased exponent e in [0, 254] such that at least
+ * `coverage` (0..1) of the finite elements counted in the HOST array
+ * hist256_host have an exponent <= e.  Returns -1 when no finite element was
+ * counted or the pointer is NULL. */
+int exmy_max_exp_from_histogram(const uint64_t* hist256_host, double coverage);
+
+const char* exmy_status_string(exmy_status_t status);
+
+#ifdef __cplusplus
+}
+#endif
+
+#endif /* EXMY_H_ */

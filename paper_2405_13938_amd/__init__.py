@@ -1,0 +1,17 @@
+"""MI355X (gfx950) eXmY tensor codec: encode / decode / emulate behind a C ABI.
+
+``binding`` wraps the shared library; ``synth`` makes seeded synthetic inputs.
+"""
+from . import binding  # noqa: F401
+from .binding import (  # noqa: F401
+    BF16,
+    F32,
+    ExmyError,
+    decode,
+    emulate,
+    encode,
+    encode_with_histogram,
+    exponent_histogram,
+    max_exp_from_histogram,
+    packed_bytes,
+)

@@ -1,0 +1,189 @@
+"""Thin ctypes binding of ``libexmy.so`` (the C ABI of ``include/exmy.h``).
+
+Argument marshalling only: every step of the codec runs in the HIP kernels.
+PyTorch is used for device memory and streams.  There is no fallback: if the
+library is not built, or a call fails, an exception is raised.
+"""
+import ctypes
+import os
+
+import torch
+
+HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(HERE, "libexmy.so")
+
+F32, BF16 = 0, 1
+SYMBOLS = [
+    "exmy_packed_bytes",
+    "exmy_check_format",
+    "exmy_encode",
+    "exmy_decode",
+    "exmy_emulate",
+    "exmy_exponent_histogram",
+    "exmy_encode_with_histogram",
+    "exmy_max_exp_from_histogram",
+    "exmy_status_string",
+]
+
+_lib = None
+
+
+class ExmyError(RuntimeError):
+    def __init__(self, status, text):
+        super().__init__("exmy: %s (status %d)" % (text, status))
+        self.status = status
+
+
+def lib():
+    """Load the shared library (building it first if it has never been built)."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            from . import build as _build
+
+            _build.build()
+        L = ctypes.CDLL(LIB_PATH)
+        u64, i32, vp, dbl = ctypes.c_uint64, ctypes.c_int, ctypes.c_void_p, ctypes.c_double
+        L.exmy_packed_bytes.restype = ctypes.c_size_t
+        L.exmy_packed_bytes.argtypes = [u64, i32, i32]
+        L.exmy_check_format.restype = i32
+        L.exmy_check_format.argtypes = [i32, i32, i32, i32, i32]
+        L.exmy_encode.restype = i32
+        L.exmy_encode.argtypes = [vp, i32, u64, i32, i32, i32, vp, vp]
+        L.exmy_decode.restype = i32
+        L.exmy_decode.argtypes = [vp, i32, u64, i32, i32, i32, vp, vp]
+        L.exmy_emulate.restype = i32
+        L.exmy_emulate.argtypes = [vp, i32, u64, i32, i32, i32, vp]
+        L.exmy_exponent_histogram.restype = i32
+        L.exmy_exponent_histogram.argtypes = [vp, i32, u64, vp, vp]
+        L.exmy_encode_with_histogram.restype = i32
+        L.exmy_encode_with_histogram.argtypes = [vp, i32, u64, i32, i32, i32, vp, vp, vp]
+        L.exmy_max_exp_from_histogram.restype = i32
+        L.exmy_max_exp_from_histogram.argtypes = [vp, dbl]
+        L.exmy_status_string.restype = ctypes.c_char_p
+        L.exmy_status_string.argtypes = [i32]
+        _lib = L
+    return _lib
+
+
+def _check(status):
+    if status != 0:
+        raise ExmyError(status, lib().exmy_status_string(status).decode())
+
+
+def _dtype_enum(t):
+    if t.dtype == torch.float32:
+        return F32
+    if t.dtype == torch.bfloat16:
+        return BF16
+    raise TypeError("exmy: tensors must be float32 or bfloat16, got %s" % t.dtype)
+
+
+def _torch_dtype(dt):
+    return torch.float32 if dt in (F32, torch.float32) else torch.bfloat16
+
+
+def _device_tensor(t, name):
+    if not t.is_cuda:
+        raise ValueError("exmy: %s must be a GPU tensor (no CPU path exists)" % name)
+    if not t.is_contiguous():
+        raise ValueError("exmy: %s must be contiguous" % name)
+    return t
+
+
+def _stream():
+    return ctypes.c_void_p(torch.cuda.current_stream().cuda_stream)
+
+
+def packed_bytes(n, X, Y):
+    return int(lib().exmy_packed_bytes(n, X, Y))
+
+
+def check_format(dt, X, Y, max_exp, packed=True):
+    """Status code of the host-side validation (0 = valid)."""
+    return int(lib().exmy_check_format(dt, X, Y, max_exp, int(packed)))
+
+
+def status_string(status):
+    return lib().exmy_status_string(status).decode()
+
+
+def encode(src, X, Y, max_exp, out=None):
+    """exmy_encode: returns the packed uint8 tensor (``out`` if given)."""
+    _device_tensor(src, "src")
+    n = src.numel()
+    nbytes = packed_bytes(n, X, Y)
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.uint8, device=src.device)
+    else:
+        _device_tensor(out, "out")
+        if out.dtype != torch.uint8 or out.numel() != nbytes:
+            raise ValueError("exmy: out must be uint8 with %d elements" % nbytes)
+    _check(lib().exmy_encode(src.data_ptr(), _dtype_enum(src), n, X, Y, max_exp, out.data_ptr(), _stream()))
+    return out
+
+
+def decode(packed, dtype, n, X, Y, max_exp, out=None):
+    """exmy_decode: returns a flat tensor of ``n`` values of ``dtype``."""
+    _device_tensor(packed, "packed")
+    tdt = _torch_dtype(dtype)
+    if packed.dtype != torch.uint8 or packed.numel() != packed_bytes(n, X, Y):
+        raise ValueError("exmy: packed must be uint8 with %d elements" % packed_bytes(n, X, Y))
+    if out is None:
+        out = torch.empty(n, dtype=tdt, device=packed.device)
+    else:
+        _device_tensor(out, "out")
+        if out.dtype != tdt or out.numel() != n:
+            raise ValueError("exmy: out must be %s with %d elements" % (tdt, n))
+    _check(lib().exmy_decode(packed.data_ptr(), _dtype_enum(out), n, X, Y, max_exp, out.data_ptr(), _stream()))
+    return out
+
+
+def emulate(data, X, Y, max_exp):
+    """exmy_emulate: in place; returns ``data``."""
+    _device_tensor(data, "data")
+    _check(lib().exmy_emulate(data.data_ptr(), _dtype_enum(data), data.numel(), X, Y, max_exp, _stream()))
+    return data
+
+
+def _hist_tensor(hist, device):
+    if hist is None:
+        return torch.zeros(256, dtype=torch.int64, device=device)
+    _device_tensor(hist, "hist")
+    if hist.dtype != torch.int64 or hist.numel() != 256:
+        raise ValueError("exmy: hist must be int64 with 256 elements")
+    return hist
+
+
+def exponent_histogram(src, hist=None):
+    """exmy_exponent_histogram: accumulates into ``hist`` (int64[256] on the GPU;
+    a zeroed one is made if None) and returns it."""
+    _device_tensor(src, "src")
+    hist = _hist_tensor(hist, src.device)
+    _check(lib().exmy_exponent_histogram(src.data_ptr(), _dtype_enum(src), src.numel(), hist.data_ptr(), _stream()))
+    return hist
+
+
+def encode_with_histogram(src, X, Y, max_exp, out=None, hist=None):
+    """exmy_encode_with_histogram: returns (packed, hist)."""
+    _device_tensor(src, "src")
+    n = src.numel()
+    nbytes = packed_bytes(n, X, Y)
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.uint8, device=src.device)
+    else:
+        _device_tensor(out, "out")
+        if out.dtype != torch.uint8 or out.numel() != nbytes:
+            raise ValueError("exmy: out must be uint8 with %d elements" % nbytes)
+    hist = _hist_tensor(hist, src.device)
+    _check(lib().exmy_encode_with_histogram(src.data_ptr(), _dtype_enum(src), n, X, Y, max_exp, out.data_ptr(),
+                                            hist.data_ptr(), _stream()))
+    return out, hist
+
+
+def max_exp_from_histogram(hist, coverage):
+    """exmy_max_exp_from_histogram on a host copy of ``hist``."""
+    h = hist.detach().to("cpu", torch.int64).contiguous()
+    if h.numel() != 256:
+        raise ValueError("exmy: hist must have 256 elements")
+    return int(lib().exmy_max_exp_from_histogram(h.data_ptr(), float(coverage)))

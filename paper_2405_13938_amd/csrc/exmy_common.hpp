@@ -1,0 +1,142 @@
+// Shared declarations of the gfx950 eXmY codec kernels: wave-uniform format
+// constants, the per-element conversion routines and the plane gather / scatter
+// helpers.  Notation follows arxiv 2405.13938: X exponent bits, Y mantissa bits,
+// W = 1 + X + Y, max_exp = the metadatum of Section 2 "Metadata".
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "../../include/exmy.h"
+
+namespace exmy {
+
+// Everything a kernel needs to know about one (X, Y, max_exp), derived on the
+// host once per call and passed by value (lands in SGPRs).
+//
+// emin8 = max_exp - 2^X + 2 is the biased exponent of the binade with exponent
+// code 1; values under 2^(emin8-127) are rounded on the subnormal grid whose
+// quantum is 2^(emin8-127-Y) (Section 2 "Subnormals").
+struct FormatConsts {
+  // ---- encode / emulate
+  uint32_t sat_bits;    // fp32 bits of the largest normal; larger magnitudes (and Inf / NaN) clamp to it
+  uint32_t emin_bits;   // emin8 << 23
+  float magic_scale;    // 2^(23-Y): exponent-only float * this = the magic addend of the rounding step
+  int32_t wide_exp;     // wide path: 1023 - 127 + 52 - Y, the fp64 exponent offset of the magic addend
+  // The encoder builds the code left-aligned in a 32-bit register (sign, if it is
+  // part of the register, at bit 31) so that plane fields can be peeled off the top.
+  uint32_t left_shift;  // L: position of code bit 0 in that register
+  uint32_t exp_lshift;  // L - (23 - Y): moves (clamped exponent << 23) to (exponent << (Y + L))
+  uint32_t bias_left;   // -(emin8 << (Y + L)) mod 2^32
+  // ---- decode
+  uint32_t exp_shift;  // 23 - Y
+  uint32_t dec_bias;   // (emin8 - 1) << 23
+  float fix_mul;       // subnormal fix r = min(g, g * fix_mul + fix_add): (2, -2^(emin8-127)), or (1, 0) if emin8 = 1
+  float fix_add;
+  uint32_t g_clamp;    // X = 8 only: bits of the largest finite value, the cap for exponent code 255
+  // ---- layout
+  uint32_t xy;         // X + Y: position of the sign bit in a code
+  uint32_t mag_mask;   // 2^(X+Y) - 1
+  uint32_t y;          // Y
+};
+
+// Host: validate and fill.  `packed` applies the W <= 16 limit.
+exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, bool packed, FormatConsts* fc,
+                          bool* needs_wide);
+
+#if defined(__HIPCC__)
+
+__device__ __forceinline__ float as_f32(uint32_t u) { return __uint_as_float(u); }
+__device__ __forceinline__ uint32_t as_u32(float f) { return __float_as_uint(f); }
+
+// (a << shift) + c in one VALU instruction.  The compiler would otherwise
+// re-associate chains of these into separate shifts and a three-way add.
+__device__ __forceinline__ uint32_t lshl_add(uint32_t a, uint32_t shift, uint32_t c) {
+  uint32_t d;
+  asm("v_lshl_add_u32 %0, %1, %2, %3" : "=v"(d) : "v"(a), "s"(shift), "v"(c));
+  return d;
+}
+
+// Magnitude code of one value given its fp32 bit pattern u (sign ignored),
+// returned left-aligned: code << fc.left_shift (mod 2^32).
+//
+// Rounding (Section 2 "Rounding", Section 2.1 outcomes a-d) is done by the
+// floating point adder: with ec = max(exponent of |x|, emin8), adding
+// 2^(ec-127+23-Y) to |x| leaves the sum with an ulp of 2^(ec-127-Y), so the
+// hardware's round-to-nearest-even produces k = round(|x| / quantum) in the low
+// bits of the sum: the significand with its leading one in the normal range,
+// the subnormal mantissa (possibly 0 = flushed, or 2^Y = rounded up to the
+// smallest normal) below it.  A carry into the next binade needs no special
+// case: the code is (ec - emin8) * 2^Y + k.  Saturation is applied on the way
+// in: magnitudes above the largest normal, Inf and NaN patterns compare larger
+// as unsigned integers and clamp to it.
+//
+// The three terms are summed already shifted left by L; everything in the sum
+// above bit Y+1 belongs to the addend's exponent field and is shifted out, so
+// no mask is needed: code << L = (sum << L) + (ec << (Y + L)) - (emin8 << (Y + L)).
+//
+// kWide = false needs max(max_exp, emin8) + 23 - Y <= 254 so that the addend is
+// a finite fp32; kWide = true does the same sum in fp64 and has no such limit.
+template <bool kWide>
+__device__ __forceinline__ uint32_t magnitude_code_left(uint32_t u, const FormatConsts& fc) {
+  uint32_t a = u & 0x7FFFFFFFu;
+  a = min(a, fc.sat_bits);
+  const uint32_t te = max(a, fc.emin_bits) & 0x7F800000u;  // ec << 23
+  uint32_t k;
+  if constexpr (!kWide) {
+    k = as_u32(__builtin_fmaf(as_f32(te), fc.magic_scale, as_f32(a)));
+  } else {
+    const uint32_t hi = ((te >> 23) + (uint32_t)fc.wide_exp) << 20;
+    const double m = __hiloint2double((int)hi, 0);
+    const double s = (double)as_f32(a) + m;
+    k = (uint32_t)__double2loint(s);
+  }
+  const uint32_t q = lshl_add(te, fc.exp_lshift, fc.bias_left);
+  return lshl_add(k, fc.left_shift, q);
+}
+
+// Value of a magnitude code from g = (code << (23 - Y)) + ((emin8 - 1) << 23),
+// as fp32 bits with the sign clear.
+//
+// For exponent codes >= 1, g is already the bit pattern of the value (an affine
+// map of the code).  For exponent code 0, g reads as (2^Y + M) * quantum / 2
+// while the value is M * quantum = 2g - 2^(emin8-127); for every other code
+// 2g - that constant is >= g, so one fused multiply-add and a minimum pick the
+// right one without a branch.  When emin8 = 1, g is an fp32 denormal and already
+// the value: the constants (1, 0) then make the second operand equal g.
+// g is never a NaN pattern here (X = 8 callers clamp it first), so the minimum
+// is taken with the bare instruction, without a canonicalising pre-pass.
+__device__ __forceinline__ uint32_t finish_magnitude(uint32_t g_bits, const FormatConsts& fc) {
+  const float g = as_f32(g_bits);
+  const float t = __builtin_fmaf(g, fc.fix_mul, fc.fix_add);
+  float r;
+  asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(g), "v"(t));
+  return as_u32(r);
+}
+
+// ---------------------------------------------------------------- planes
+
+// Number of planes and their segment widths, widest first (7 -> 4, 2, 1).
+template <int W>
+struct Planes {
+  static constexpr int count = __builtin_popcount(W);
+  __host__ __device__ static constexpr int seg(int p) {
+    int s = 16, i = 0;
+    while (true) {
+      if (W & s) {
+        if (i == p) return s;
+        ++i;
+      }
+      s >>= 1;
+    }
+  }
+  __host__ __device__ static constexpr int lo(int p) {  // lowest code bit of plane p
+    int l = 0;
+    for (int i = 0; i < p; ++i) l += seg(i);
+    return l;
+  }
+};
+
+#endif  // __HIPCC__
+
+}  // namespace exmy

@@ -1,0 +1,99 @@
+"""CPU-only checks of the C-ABI library: it loads, exports every symbol that
+include/exmy.h declares, and its host-side logic (sizes, validation, error
+codes, the histogram helper) agrees with the oracle.  No kernel is launched."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+from oracle import exmy_oracle as O
+from paper_2405_13938_amd import binding as B
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def declared_symbols():
+    text = open(os.path.join(ROOT, "include", "exmy.h")).read()
+    text = re.sub(r"/\*.*?\*/", "", text, flags=re.S)
+    return sorted(set(re.findall(r"\b(exmy_[a-z0-9_]+)\s*\(", text)))
+
+
+def test_library_exports_every_declared_symbol():
+    names = declared_symbols()
+    assert set(names) == set(B.SYMBOLS)
+    L = B.lib()
+    for name in names:
+        assert getattr(L, name) is not None
+
+
+def test_packed_bytes():
+    for n in (0, 1, 7, 8, 9, 1 << 20, (1 << 40) - 3):
+        for X, Y in ((3, 3), (0, 2), (8, 7), (4, 0)):
+            assert B.packed_bytes(n, X, Y) == ((n + 7) // 8) * (1 + X + Y) == O.packed_bytes(n, X, Y)
+    assert B.packed_bytes(1 << 20, 3, 3) == 917504  # configuration 1
+
+
+def test_format_validation_matches_oracle_over_the_whole_domain():
+    for dt in (B.F32, B.BF16):
+        for X in range(-1, 10):
+            for Y in range(-1, 26):
+                for max_exp in (-1, 0, 1, (1 << max(X, 0)) - 2, (1 << max(X, 0)) - 1, 127, 253, 254, 255, 256):
+                    for packed in (False, True):
+                        got = B.check_format(dt, X, Y, max_exp, packed)
+                        want = O.check_format(dt, X, Y, max_exp, packed)
+                        assert (got == 0) == (want == 0), (dt, X, Y, max_exp, packed)
+                        if got and want:
+                            assert got == want, (dt, X, Y, max_exp, packed)  # same error class (format / max_exp)
+
+
+def test_error_codes_without_launch():
+    L = B.lib()
+    ok_ptr = ctypes.c_void_p(0x1000)
+    odd_ptr = ctypes.c_void_p(0x1004)
+    assert L.exmy_encode(ok_ptr, B.F32, 0, 3, 3, 130, ok_ptr, None) == 0  # n = 0: nothing to do
+    assert L.exmy_encode(None, B.F32, 8, 3, 3, 130, ok_ptr, None) == 1
+    assert L.exmy_decode(ok_ptr, B.F32, 8, 3, 3, 130, None, None) == 1
+    assert L.exmy_emulate(None, B.BF16, 8, 3, 3, 130, None) == 1
+    assert L.exmy_encode(ok_ptr, B.F32, 8, 9, 3, 130, ok_ptr, None) == 2
+    assert L.exmy_encode(ok_ptr, 7, 8, 3, 3, 130, ok_ptr, None) == 2
+    assert L.exmy_encode(ok_ptr, B.BF16, 8, 3, 8, 130, ok_ptr, None) == 2  # bf16 cannot hold 8 mantissa bits
+    assert L.exmy_encode(ok_ptr, B.F32, 8, 4, 12, 130, ok_ptr, None) == 2  # W = 17
+    assert L.exmy_emulate(ok_ptr, B.F32, 0, 4, 12, 130, None) == 0  # emulate has no width limit
+    assert L.exmy_encode(ok_ptr, B.F32, 8, 3, 3, 6, ok_ptr, None) == 3
+    assert L.exmy_decode(ok_ptr, B.F32, 8, 8, 3, 254, ok_ptr, None) == 3
+    assert L.exmy_encode(ok_ptr, B.F32, (1 << 40) + 1, 3, 3, 130, ok_ptr, None) == 4
+    assert L.exmy_encode(odd_ptr, B.F32, 8, 3, 3, 130, ok_ptr, None) == 5
+    assert L.exmy_encode(ok_ptr, B.F32, 8, 3, 3, 130, odd_ptr, None) == 5
+    assert L.exmy_decode(odd_ptr, B.BF16, 8, 3, 3, 130, ok_ptr, None) == 5
+    assert L.exmy_emulate(odd_ptr, B.BF16, 8, 3, 3, 130, None) == 5
+    assert L.exmy_exponent_histogram(ok_ptr, B.F32, 8, None, None) == 1
+    assert L.exmy_exponent_histogram(ok_ptr, B.F32, 8, odd_ptr, None) == 5
+    assert L.exmy_encode_with_histogram(ok_ptr, B.F32, 8, 3, 3, 130, ok_ptr, None, None) == 1
+    for st in range(0, 7):
+        assert B.status_string(st)
+    assert "max_exp" in B.status_string(3)
+
+
+def test_max_exp_from_histogram_matches_oracle():
+    import torch
+
+    rng = np.random.default_rng(5)
+    for _ in range(50):
+        hist = np.zeros(256, dtype=np.uint64)
+        idx = rng.integers(0, 256, size=rng.integers(1, 40))
+        hist[idx] = rng.integers(1, 1 << 40, size=idx.size, dtype=np.uint64)
+        for cov in (0.0, 0.5, 0.9, 0.99, 0.999, 1.0):
+            got = B.max_exp_from_histogram(torch.from_numpy(hist.view(np.int64)), cov)
+            assert got == O.max_exp_from_histogram(hist, cov)
+    assert B.max_exp_from_histogram(torch.zeros(256, dtype=torch.int64), 0.5) == -1
+
+
+def test_cpu_tensors_are_rejected():
+    import torch
+
+    with pytest.raises(ValueError):
+        B.encode(torch.zeros(8), 3, 3, 130)
+    with pytest.raises(TypeError):
+        B._dtype_enum(torch.zeros(8, dtype=torch.float16))
