@@ -1,0 +1,332 @@
+#!/usr/bin/env python3
+"""Throughput of the eXmY codec hot path on one MI355X.
+
+A step is one pass of the whole path over one batch of synthetic input that is
+already resident in HBM: encode every tensor of the workload to packed eXmY
+codes, then decode all of it back.  The default workload is the checkpoint-shaped
+batch (288 bf16 tensors of a 7B-class decoder, 6.48 G elements) at e3m3 (7 bits),
+each tensor with its own max_exp, written into one sharded-by-tensor buffer.  The
+tensors go through exmy_encode_batch / exmy_decode_batch (one C call per direction,
+a handful of launches on one stream); `--mode calls` issues one exmy_encode /
+exmy_decode call per tensor instead, and the default run reports that figure too.
+
+Prints ONE JSON line: `value` = (bytes read + bytes written by encode and decode)
+per second, in GB/s; `roofline` for the slower of the two kernels against the HBM
+peak; `cpu_baseline` = the CPU oracle timed on a bounded sample of the same data.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E datasheet peak
+
+# HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
+# runs scaled by a copy kernel of known size (profiles/*hbm_traffic*.txt).  None = not measured.
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {}
+
+
+def parse_args():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=10)
+    ap.add_argument("--warmup", type=int, default=2)
+    ap.add_argument("--workload", default="cfg5", choices=["cfg5", "cfg3", "cfg4", "cfg2"],
+                    help="cfg5 = checkpoint batch bf16 e3m3 (default); cfg3 = 1 GiB fp32 e4m2; "
+                         "cfg4 = bf16 activations e4m3; cfg2 = 8192x8192 bf16 e3m3")
+    ap.add_argument("--mode", default="batch", choices=["batch", "calls"],
+                    help="batch = exmy_encode_batch / exmy_decode_batch (default); calls = one call per tensor")
+    ap.add_argument("--layers", type=int, default=32, help="cfg5 only: decoder layers (32 = the full workload)")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-extras", action="store_true", help="skip the short runs of the other workloads")
+    return ap.parse_args()
+
+
+def clamp_max_exp(m, X):
+    if X == 8:
+        return 255
+    if X == 0:
+        return min(max(m, 1), 253)
+    return min(max(m, (1 << X) - 1), 254)
+
+
+def tensor_max_exp(t, X):
+    """The paper's per-tensor metadatum, 'maximum exponent before rounding': biased exponent
+    of the largest finite magnitude (an input to the codec, computed outside the timed region)."""
+    import torch
+
+    a = t.detach().reshape(-1)
+    if a.dtype == torch.bfloat16:
+        e = (a.view(torch.int16).to(torch.int32) >> 7) & 0xFF
+    else:
+        e = (a.view(torch.int32) >> 23) & 0xFF
+    e = torch.where(e == 255, torch.zeros_like(e), e)
+    return clamp_max_exp(int(e.max().item()), X)
+
+
+class Workload:
+    """A list of (src tensor, packed out, decoded out, X, Y, max_exp) jobs."""
+
+    def __init__(self, name, desc):
+        self.name, self.desc, self.jobs = name, desc, []
+
+    def add(self, src, X, Y, max_exp, packed, out):
+        self.jobs.append((src, X, Y, max_exp, packed, out))
+
+    @property
+    def elements(self):
+        return sum(j[0].numel() for j in self.jobs)
+
+    @property
+    def bytes_one_way(self):
+        return sum(j[0].numel() * j[0].element_size() + j[4].numel() for j in self.jobs)
+
+    def prepare(self, exmy, mode):
+        """mode 'batch': build the descriptor arrays once (host-side marshalling, like the
+        per-tensor slices above, is not part of the codec)."""
+        self.mode = mode
+        if mode == "batch":
+            X, Y = self.jobs[0][1], self.jobs[0][2]
+            srcs = [j[0] for j in self.jobs]
+            self.enc_batch = exmy.Batch(srcs, [j[4] for j in self.jobs], [j[3] for j in self.jobs], X, Y, decode=False)
+            self.dec_batch = exmy.Batch([j[5] for j in self.jobs], [j[4] for j in self.jobs], [j[3] for j in self.jobs],
+                                        X, Y, decode=True)
+
+    def encode_all(self, exmy):
+        if self.mode == "batch":
+            self.enc_batch.run()
+            return
+        for src, X, Y, max_exp, packed, _ in self.jobs:
+            exmy.encode(src, X, Y, max_exp, out=packed)
+
+    def decode_all(self, exmy):
+        if self.mode == "batch":
+            self.dec_batch.run()
+            return
+        for src, X, Y, max_exp, packed, out in self.jobs:
+            exmy.decode(packed, src.dtype, src.numel(), X, Y, max_exp, out=out)
+
+
+def build_workload(name, exmy, synth, dev, layers=32):
+    import torch
+
+    if name == "cfg5":
+        X, Y = 3, 3
+        flat, table = synth.cfg5(layers=layers, device=dev)
+        total = sum(exmy.packed_bytes(sz, X, Y) for _, _, sz in table)
+        buf = torch.empty(total, dtype=torch.uint8, device=dev)
+        out = torch.empty_like(flat)
+        wl = Workload("cfg5", "checkpoint batch: %d layers x 9 bf16 tensors N(0,0.02^2), seed 4, e3m3 (7-bit), "
+                              "one call per tensor into one sharded-by-tensor buffer" % layers)
+        poff = 0
+        for _, off, sz in table:
+            nb = exmy.packed_bytes(sz, X, Y)
+            src = flat[off:off + sz]
+            wl.add(src, X, Y, tensor_max_exp(src, X), buf[poff:poff + nb], out[off:off + sz])
+            poff += nb
+        return wl
+    if name == "cfg3":
+        x = synth.cfg3(device=dev)
+        wl = Workload("cfg3", "fp32 2^28 elements, log-normal magnitudes, seed 2, e4m2 (7-bit)")
+        X, Y = 4, 2
+        wl.add(x, X, Y, tensor_max_exp(x, X), torch.empty(exmy.packed_bytes(x.numel(), X, Y), dtype=torch.uint8, device=dev),
+               torch.empty_like(x))
+        return wl
+    if name == "cfg4":
+        x = synth.cfg4(device=dev).reshape(-1)
+        wl = Workload("cfg4", "bf16 16384x14336 Student-t activations with outliers, seed 3, e4m3 (8-bit)")
+        X, Y = 4, 3
+        hist = exmy.exponent_histogram(x)
+        m = clamp_max_exp(exmy.max_exp_from_histogram(hist, 0.99), X)
+        wl.add(x, X, Y, m, torch.empty(exmy.packed_bytes(x.numel(), X, Y), dtype=torch.uint8, device=dev),
+               torch.empty_like(x))
+        return wl
+    if name == "cfg2":
+        x = synth.cfg2(device=dev).reshape(-1)
+        wl = Workload("cfg2", "bf16 8192x8192 N(0,0.02^2), seed 1, e3m3 (7-bit)")
+        X, Y = 3, 3
+        wl.add(x, X, Y, tensor_max_exp(x, X), torch.empty(exmy.packed_bytes(x.numel(), X, Y), dtype=torch.uint8, device=dev),
+               torch.empty_like(x))
+        return wl
+    raise ValueError(name)
+
+
+def time_phases(wl, exmy, steps, warmup):
+    """Run warmup + steps passes; returns (wall seconds over the timed steps,
+    mean encode-phase ms, mean decode-phase ms) with the phases timed by HIP events
+    on the stream the kernels are launched on (torch's current stream)."""
+    import torch
+
+    for _ in range(warmup):
+        wl.encode_all(exmy)
+        wl.decode_all(exmy)
+    ev = [[torch.cuda.Event(enable_timing=True) for _ in range(3)] for _ in range(steps)]
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for s in range(steps):
+        ev[s][0].record()
+        wl.encode_all(exmy)
+        ev[s][1].record()
+        wl.decode_all(exmy)
+        ev[s][2].record()
+    torch.cuda.synchronize()
+    wall = time.perf_counter() - t0
+    enc_ms = sum(e[0].elapsed_time(e[1]) for e in ev) / steps
+    dec_ms = sum(e[1].elapsed_time(e[2]) for e in ev) / steps
+    return wall, enc_ms, dec_ms
+
+
+def count_launches(wl):
+    """Launches that one batched call makes: tensors are walked by size, a launch holds at
+    most 64 of them and is cut when a tensor is more than a quarter smaller than its largest."""
+    sizes = sorted((j[0].numel() for j in wl.jobs if j[0].numel()), reverse=True)
+    launches, count, hi = 0, 0, 0
+    for n in sizes:
+        if count == 64 or (count and n < hi - hi // 4):
+            launches, count = launches + 1, 0
+        if count == 0:
+            hi = n
+        count += 1
+    return launches + (1 if count else 0)
+
+
+def cpu_baseline(wl, synth, budget_elems=1 << 27):
+    """The oracle, as it stands, on the host cores over a bounded prefix of the workload."""
+    from oracle import exmy_oracle as O
+
+    threads = O.default_threads()
+    jobs, total = [], 0
+    for src, X, Y, max_exp, _, _ in wl.jobs:
+        take = min(src.numel(), budget_elems - total)
+        take -= take % 8
+        if take <= 0:
+            break
+        jobs.append((synth.bits_numpy(src[:take]), X, Y, max_exp, O.BF16 if src.element_size() == 2 else O.F32))
+        total += take
+    O.encode(jobs[0][0][:4096], jobs[0][1], jobs[0][2], jobs[0][3])  # load the library outside the clock
+    t0 = time.perf_counter()
+    nbytes = 0
+    for host, X, Y, max_exp, dt in jobs:
+        p = O.encode(host, X, Y, max_exp, threads=threads)
+        d = O.decode(p, dt, host.size, X, Y, max_exp, threads=threads)
+        nbytes += 2 * (host.nbytes + p.nbytes)
+        del d
+    dt_s = time.perf_counter() - t0
+    return {
+        "value": round(nbytes / dt_s / 1e9, 3),
+        "unit": "GB/s",
+        "cores": threads,
+        "kind": "oracle",
+        "sample": "first %d elements (%d tensors) of the workload, encode + decode, %.1f s wall" % (total, len(jobs), dt_s),
+    }
+
+
+def main():
+    args = parse_args()
+    world = int(os.environ.get("WORLD_SIZE", "1"))
+    if args.gpus != 1 or world != 1:
+        print("bench.py: this build measures one GPU only (the codec shards with no communication; "
+              "see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+
+    import paper_2405_13938_amd as exmy
+    from paper_2405_13938_amd import synth
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible; the HIP path has no CPU fallback.", file=sys.stderr)
+        sys.exit(2)
+    dev = "cuda:0"
+    torch.cuda.set_device(0)
+    exmy.binding.lib()
+
+    wl = build_workload(args.workload, exmy, synth, dev, args.layers)
+    wl.prepare(exmy, args.mode)
+    torch.cuda.synchronize()
+    wall, enc_ms, dec_ms = time_phases(wl, exmy, args.steps, args.warmup)
+    one_way = wl.bytes_one_way
+    step_bytes = 2 * one_way
+    value = step_bytes * args.steps / wall / 1e9
+    enc_gbps = one_way / (enc_ms * 1e-3) / 1e9
+    dec_gbps = one_way / (dec_ms * 1e-3) / 1e9
+
+    # roofline of the slower kernel: algorithmic bytes per launch / mean launch duration
+    launches = len(wl.jobs) if args.mode == "calls" else count_launches(wl)
+    slow = "encode" if enc_gbps <= dec_gbps else "decode"
+    slow_ms = enc_ms if slow == "encode" else dec_ms
+    achieved = min(enc_gbps, dec_gbps)
+    src0 = wl.jobs[0][0]
+    W = 1 + wl.jobs[0][1] + wl.jobs[0][2]
+    kernel = "%s_kernel<%s, W=%d>" % (slow, "bf16" if src0.element_size() == 2 else "fp32", W)
+    traffic = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((args.workload, slow))
+    roofline = {
+        "bound": "hbm",
+        "kernel": kernel,
+        "achieved": round(achieved, 1),
+        "peak": HBM_PEAK_GBPS,
+        "unit": "GB/s",
+        "frac": round(achieved / HBM_PEAK_GBPS, 4),
+        "traffic": traffic,
+        "launches_per_step": launches,
+        "algorithmic_bytes_per_launch": one_way // launches,
+        "avg_launch_us": round(slow_ms * 1e3 / launches, 2),
+        "encode_GBps": round(enc_gbps, 1),
+        "decode_GBps": round(dec_gbps, 1),
+        "encode_frac": round(enc_gbps / HBM_PEAK_GBPS, 4),
+        "decode_frac": round(dec_gbps / HBM_PEAK_GBPS, 4),
+    }
+
+    line = {
+        "metric": "encode / decode GB/s (bytes in+out) and % of MI355X HBM peak, e3m3 7-bit",
+        "value": round(value, 1),
+        "unit": "GB/s",
+        "n_gpus": 1,
+        "steps": args.steps,
+        "warmup": args.warmup,
+        "ms_per_step": round(wall * 1e3 / args.steps, 4),
+        "higher_is_better": True,
+        "scaling": "weak",
+        "vs_baseline": None,
+        "dtype": "u32",
+        "data": "synthetic",
+        "config": {"workload": wl.name, "description": wl.desc, "elements": wl.elements, "tensors": len(wl.jobs),
+                   "bytes_in_plus_out_per_direction": one_way, "mode": args.mode,
+                   "launches_per_step": 2 * launches},
+        "roofline": roofline,
+    }
+
+    if not args.no_extras and args.workload == "cfg5":
+        extras = {}
+        if args.mode == "batch":  # the same workload as one exmy_encode / exmy_decode call per tensor
+            wl.prepare(exmy, "calls")
+            w_c, e_c, d_c = time_phases(wl, exmy, max(2, args.steps // 2), 1)
+            extras["cfg5_one_call_per_tensor"] = {
+                "value_GBps": round(step_bytes * max(2, args.steps // 2) / w_c / 1e9, 1),
+                "encode_GBps": round(one_way / e_c / 1e6, 1), "decode_GBps": round(one_way / d_c / 1e6, 1)}
+        del wl
+        torch.cuda.empty_cache()
+        for other in ("cfg3", "cfg4"):
+            w2 = build_workload(other, exmy, synth, dev)
+            w2.prepare(exmy, "calls")
+            _, e_ms, d_ms = time_phases(w2, exmy, 20, 3)
+            b = w2.bytes_one_way
+            extras[other] = {"description": w2.desc, "encode_GBps": round(b / e_ms / 1e6, 1),
+                             "decode_GBps": round(b / d_ms / 1e6, 1)}
+            del w2
+            torch.cuda.empty_cache()
+        line["other_workloads"] = extras
+        wl = build_workload(args.workload, exmy, synth, dev, min(args.layers, 1)) if not args.no_cpu_baseline else None
+
+    if not args.no_cpu_baseline:
+        line["cpu_baseline"] = cpu_baseline(wl, synth)
+    print(json.dumps(line))
+
+
+if __name__ == "__main__":
+    main()

@@ -10,7 +10,7 @@
  * Conventions shared by every entry point
  * ---------------------------------------
  *  - All data pointers are DEVICE pointers owned by the caller.  The library
- *    allocates nothing, frees nothing and never synchronises: work is enqueued
+ *    allocates and frees no device memory and never synchronises: work is enqueued
  *    on `stream` (a hipStream_t passed as void*; NULL = the default stream) and
  *    the call returns at once.  Arguments are validated on the host before any
  *    launch; a failed validation launches nothing.
@@ -89,6 +89,30 @@ exmy_status_t exmy_encode(const void* src, exmy_dtype_t dt, uint64_t n, int X, i
  * decodes to the largest finite value. */
 exmy_status_t exmy_decode(const void* src_packed, exmy_dtype_t dt_out, uint64_t n, int X, int Y, int max_exp,
                           void* dst, void* stream);
+
+/* One tensor of a batched call.  For exmy_encode_batch `src` holds n elements
+ * and `dst` receives exmy_packed_bytes(n, X, Y) bytes; for exmy_decode_batch
+ * `src` holds the packed bytes and `dst` receives n elements.  Both are device
+ * pointers, 16-byte aligned; the array of descriptors itself is HOST memory and
+ * is read before the call returns. */
+typedef struct {
+  const void* src;
+  void* dst;
+  uint64_t n;
+  int32_t max_exp; /* this tensor's metadatum (Section 2 "Metadata": one per block; here block = tensor) */
+} exmy_tensor_t;
+
+/* exmy_encode / exmy_decode over `count` tensors that share dtype, X and Y but
+ * carry their own max_exp: a checkpoint-shaped stream (the paper names tensor
+ * and checkpoint codecs) enqueued as a few launches instead of one per tensor,
+ * so that small tensors do not pay a launch each.  Results are identical to
+ * calling the single-tensor entry point on every tensor in order.  All tensors
+ * are validated first; on any error nothing is launched.  Tensors with n = 0 are
+ * skipped. */
+exmy_status_t exmy_encode_batch(const exmy_tensor_t* tensors, size_t count, exmy_dtype_t dt, int X, int Y,
+                                void* stream);
+exmy_status_t exmy_decode_batch(const exmy_tensor_t* tensors, size_t count, exmy_dtype_t dt_out, int X, int Y,
+                                void* stream);
 
 /* Emulate (Section 2.1): replace each of the n elements at `data_inout` by the
  * eXmY value nearest to it, kept in the same type; NaN and +-Inf are left

@@ -6,10 +6,13 @@ from . import binding  # noqa: F401
 from .binding import (  # noqa: F401
     BF16,
     F32,
+    Batch,
     ExmyError,
     decode,
+    decode_batch,
     emulate,
     encode,
+    encode_batch,
     encode_with_histogram,
     exponent_histogram,
     max_exp_from_histogram,

@@ -18,6 +18,8 @@ SYMBOLS = [
     "exmy_check_format",
     "exmy_encode",
     "exmy_decode",
+    "exmy_encode_batch",
+    "exmy_decode_batch",
     "exmy_emulate",
     "exmy_exponent_histogram",
     "exmy_encode_with_histogram",
@@ -26,6 +28,13 @@ SYMBOLS = [
 ]
 
 _lib = None
+
+
+class TensorDesc(ctypes.Structure):
+    """exmy_tensor_t"""
+
+    _fields_ = [("src", ctypes.c_void_p), ("dst", ctypes.c_void_p), ("n", ctypes.c_uint64),
+                ("max_exp", ctypes.c_int32)]
 
 
 class ExmyError(RuntimeError):
@@ -52,6 +61,10 @@ def lib():
         L.exmy_encode.argtypes = [vp, i32, u64, i32, i32, i32, vp, vp]
         L.exmy_decode.restype = i32
         L.exmy_decode.argtypes = [vp, i32, u64, i32, i32, i32, vp, vp]
+        L.exmy_encode_batch.restype = i32
+        L.exmy_encode_batch.argtypes = [vp, ctypes.c_size_t, i32, i32, i32, vp]
+        L.exmy_decode_batch.restype = i32
+        L.exmy_decode_batch.argtypes = [vp, ctypes.c_size_t, i32, i32, i32, vp]
         L.exmy_emulate.restype = i32
         L.exmy_emulate.argtypes = [vp, i32, u64, i32, i32, i32, vp]
         L.exmy_exponent_histogram.restype = i32
@@ -137,6 +150,55 @@ def decode(packed, dtype, n, X, Y, max_exp, out=None):
             raise ValueError("exmy: out must be %s with %d elements" % (tdt, n))
     _check(lib().exmy_decode(packed.data_ptr(), _dtype_enum(out), n, X, Y, max_exp, out.data_ptr(), _stream()))
     return out
+
+
+class Batch:
+    """A prepared array of exmy_tensor_t descriptors (host memory), reusable across
+    calls.  Holds references to the tensors so their memory stays alive."""
+
+    def __init__(self, elems, packeds, max_exps, X, Y, decode=False):
+        elems, packeds, max_exps = list(elems), list(packeds), list(max_exps)
+        if not (len(elems) == len(packeds) == len(max_exps)):
+            raise ValueError("exmy: batch lists differ in length")
+        self.count = len(elems)
+        self.X, self.Y, self.decode = X, Y, decode
+        self.dtype = elems[0].dtype if elems else torch.bfloat16
+        self._keep = (elems, packeds)
+        self.array = (TensorDesc * max(self.count, 1))()
+        for i, (e, p, m) in enumerate(zip(elems, packeds, max_exps)):
+            _device_tensor(e, "element tensor")
+            _device_tensor(p, "packed tensor")
+            if e.dtype != self.dtype:
+                raise TypeError("exmy: all tensors of a batch share one dtype")
+            if p.dtype != torch.uint8 or p.numel() != packed_bytes(e.numel(), X, Y):
+                raise ValueError("exmy: packed tensor %d must be uint8 with %d elements" % (i, packed_bytes(e.numel(), X, Y)))
+            d = self.array[i]
+            d.src, d.dst = (p.data_ptr(), e.data_ptr()) if decode else (e.data_ptr(), p.data_ptr())
+            d.n, d.max_exp = e.numel(), int(m)
+
+    def run(self):
+        L = lib()
+        fn = L.exmy_decode_batch if self.decode else L.exmy_encode_batch
+        dt = F32 if self.dtype == torch.float32 else BF16
+        _check(fn(ctypes.cast(self.array, ctypes.c_void_p), self.count, dt, self.X, self.Y, _stream()))
+
+
+def encode_batch(srcs, X, Y, max_exps, outs=None):
+    """exmy_encode_batch over a list of tensors; returns the list of packed tensors."""
+    srcs = [s.reshape(-1) for s in srcs]
+    if outs is None:
+        outs = [torch.empty(packed_bytes(s.numel(), X, Y), dtype=torch.uint8, device=s.device) for s in srcs]
+    Batch(srcs, outs, max_exps, X, Y, decode=False).run()
+    return outs
+
+
+def decode_batch(packeds, dtype, ns, X, Y, max_exps, outs=None):
+    """exmy_decode_batch over a list of packed tensors; returns the list of decoded tensors."""
+    tdt = _torch_dtype(dtype)
+    if outs is None:
+        outs = [torch.empty(n, dtype=tdt, device=p.device) for p, n in zip(packeds, ns)]
+    Batch(outs, packeds, max_exps, X, Y, decode=True).run()
+    return outs
 
 
 def emulate(data, X, Y, max_exp):

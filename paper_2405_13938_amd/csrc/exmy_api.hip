@@ -4,7 +4,9 @@
 #include <math.h>
 #include <string.h>
 
+#include <algorithm>
 #include <atomic>
+#include <vector>
 
 #include "exmy_common.hpp"
 #include "exmy_launch.hpp"
@@ -37,7 +39,7 @@ int compute_units() {
 }
 
 exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, bool packed, FormatConsts* fc,
-                          bool* needs_wide) {
+                          TensorConsts* tc, bool* needs_wide) {
   if (dt != EXMY_F32 && dt != EXMY_BF16) return EXMY_ERR_FORMAT;
   if (X < 0 || X > 8 || Y < 0) return EXMY_ERR_FORMAT;
   // Section 2.1: bf16 holds Y <= 7, fp32 Y <= 23; a sign-magnitude format (X = 0) has
@@ -53,45 +55,46 @@ exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, bool packe
   } else {
     if (max_exp < (1 << X) - 1 || max_exp > 254) return EXMY_ERR_MAX_EXP;
   }
-  if (!fc) return EXMY_OK;
 
   const int emin8 = max_exp - (1 << X) + 2;
-  const uint32_t ones_y = (1u << Y) - 1u;
-  memset(fc, 0, sizeof(*fc));
-  fc->xy = (uint32_t)(X + Y);
-  fc->y = (uint32_t)Y;
-  fc->mag_mask = (uint32_t)((1ull << (X + Y)) - 1ull);
-  fc->exp_shift = (uint32_t)(23 - Y);  // Y = 24 cannot occur with X >= 1; X = 0, Y = 24 handled below
-  fc->emin_bits = (uint32_t)emin8 << 23;
+  const uint32_t ones_y = (uint32_t)((1ull << Y) - 1ull);
   // Odd widths end in a 1-bit plane that holds exactly the sign: the encoder takes
   // it from the source bits and left-aligns the magnitude alone.
   const int W = 1 + X + Y;
   const int L = ((W & 1) ? 32 : 31) - (X + Y);
-  fc->left_shift = (uint32_t)(L & 31);  // L = 32 only for W = 1, where no magnitude bits exist
-  fc->exp_lshift = (uint32_t)((L - (23 - Y)) & 31);
-  fc->bias_left = (uint32_t)(0ull - ((uint64_t)emin8 << (Y + L)));
-  fc->magic_scale = ldexpf(1.0f, 23 - Y);
-  fc->wide_exp = 1023 - 127 + 52 - Y;
-
   // Largest value: (2 - 2^-Y) * 2^(max_exp-127) with X >= 1 (X = 8: exponent 254, the
   // largest finite float); (2^Y - 1) quanta with X = 0.
+  uint32_t sat_bits;
   if (X == 0) {
-    fc->sat_bits = float_bits(ldexpf((float)ones_y, emin8 - 127 - Y));
+    sat_bits = float_bits(ldexpf((float)ones_y, emin8 - 127 - Y));
   } else {
     const uint32_t top = X == 8 ? 254u : (uint32_t)max_exp;
-    fc->sat_bits = (top << 23) | (Y <= 23 ? (ones_y << (23 - Y)) : 0u);
-  }
-  fc->g_clamp = fc->sat_bits;
-
-  fc->dec_bias = (uint32_t)(emin8 - 1) << 23;
-  if (emin8 == 1) {
-    fc->fix_mul = 1.0f;
-    fc->fix_add = 0.0f;
-  } else {
-    fc->fix_mul = 2.0f;
-    fc->fix_add = -ldexpf(1.0f, emin8 - 127);
+    sat_bits = (top << 23) | (ones_y << (23 - Y));
   }
 
+  if (fc) {
+    memset(fc, 0, sizeof(*fc));
+    fc->magic_scale = ldexpf(1.0f, 23 - Y);
+    fc->wide_exp = 1023 - 127 + 52 - Y;
+    fc->left_shift = (uint32_t)(L & 31);  // L = 32 only for W = 1, where no magnitude bits exist
+    fc->exp_lshift = (uint32_t)((L - (23 - Y)) & 31);
+    fc->exp_shift = (uint32_t)((23 - Y) & 31);  // Y = 24 (X = 0, fp32) is reachable by emulate only, which does not use it
+    fc->g_clamp = sat_bits;
+  }
+  if (tc) {
+    memset(tc, 0, sizeof(*tc));
+    tc->sat_bits = sat_bits;
+    tc->emin_bits = (uint32_t)emin8 << 23;
+    tc->bias_left = (uint32_t)(0ull - ((uint64_t)emin8 << (Y + L)));
+    tc->dec_bias = (uint32_t)(emin8 - 1) << 23;
+    if (emin8 == 1) {
+      tc->fix_mul = 1.0f;
+      tc->fix_add = 0.0f;
+    } else {
+      tc->fix_mul = 2.0f;
+      tc->fix_add = -ldexpf(1.0f, emin8 - 127);
+    }
+  }
   // The fp32 magic addend 2^(ec-127+23-Y) must be finite for the largest clamped
   // exponent ec, and the sum must stay in the addend's binade (Y <= 21).
   const int ec_max = X == 0 ? emin8 : (X == 8 ? 254 : max_exp);
@@ -103,61 +106,121 @@ exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, bool packe
 
 using namespace exmy;
 
+namespace {
+
+enum class Op { kEncode, kDecode };
+
+// Validate every tensor of a batch, then launch it in pieces of at most kMaxBatch
+// tensors whose chunk counts are alike (a launch's grid is as wide as its largest
+// tensor, so very different sizes do not share one).  Nothing is launched if any
+// tensor fails validation.
+exmy_status_t run_batch(Op op, const exmy_tensor_t* tensors, size_t count, exmy_dtype_t dt, int X, int Y,
+                        uint64_t* hist, bool with_hist, void* stream) {
+  if (count == 0) return exmy_check_format(dt, X, Y, X == 8 ? 255 : (X == 0 ? 1 : 254), 1);
+  if (!tensors) return EXMY_ERR_NULL;
+  FormatConsts fc;
+  bool any_wide = false;
+  for (size_t i = 0; i < count; ++i) {
+    const exmy_tensor_t& t = tensors[i];
+    bool wide = false;
+    if (exmy_status_t st = make_format(dt, X, Y, t.max_exp, true, &fc, nullptr, &wide)) return st;
+    any_wide = any_wide || wide;
+    if (t.n > EXMY_MAX_ELEMENTS) return EXMY_ERR_COUNT;
+    if (t.n == 0) continue;
+    if (!t.src || !t.dst) return EXMY_ERR_NULL;
+    if (!aligned16(t.src) || !aligned16(t.dst)) return EXMY_ERR_ALIGN;
+  }
+  if (with_hist) {
+    if (!hist) return EXMY_ERR_NULL;
+    if (reinterpret_cast<uintptr_t>(hist) & 7u) return EXMY_ERR_ALIGN;
+  }
+
+  const int W = 1 + X + Y;
+  BatchArgs args;
+  args.fc = fc;
+  args.hist = reinterpret_cast<unsigned long long*>(hist);
+  args.count = 0;
+  uint64_t hi = 0;  // largest element count in the pending launch
+  auto flush = [&]() -> hipError_t {
+    if (args.count == 0) return hipSuccess;
+    const hipError_t e = op == Op::kEncode
+                             ? encode_dispatch(dt, W, any_wide, with_hist, args, hi, static_cast<hipStream_t>(stream))
+                             : decode_dispatch(dt, W, X == 8, args, hi, static_cast<hipStream_t>(stream));
+    args.count = 0;
+    return e;
+  };
+  // Tensors are independent, so they may be launched in any order: walk them by size
+  // (stable, so equal sizes keep their memory order) and cut a launch when it is full
+  // or when more than a quarter of its blocks would fall off the end of a tensor.
+  std::vector<uint32_t> order;
+  order.reserve(count);
+  for (size_t i = 0; i < count; ++i)
+    if (tensors[i].n) order.push_back((uint32_t)i);
+  std::stable_sort(order.begin(), order.end(),
+                   [&](uint32_t a, uint32_t b) { return tensors[a].n > tensors[b].n; });
+  for (uint32_t i : order) {
+    const exmy_tensor_t& t = tensors[i];
+    if (args.count == kMaxBatch || (args.count && t.n < hi - hi / 4)) {
+      if (flush() != hipSuccess) return EXMY_ERR_DEVICE;
+    }
+    if (args.count == 0) hi = t.n;  // sizes only shrink from here
+    TensorArgs& ta = args.t[args.count++];
+    ta.src = t.src;
+    ta.dst = t.dst;
+    ta.n = t.n;
+    make_format(dt, X, Y, t.max_exp, true, nullptr, &ta.tc, nullptr);
+  }
+  return flush() == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
+}
+
+}  // namespace
+
 extern "C" {
 
 size_t exmy_packed_bytes(uint64_t n, int X, int Y) { return (size_t)(((n + 7) / 8) * (uint64_t)(1 + X + Y)); }
 
 exmy_status_t exmy_check_format(exmy_dtype_t dt, int X, int Y, int max_exp, int packed) {
-  return make_format(dt, X, Y, max_exp, packed != 0, nullptr, nullptr);
-}
-
-static exmy_status_t encode_common(const void* src, exmy_dtype_t dt, uint64_t n, int X, int Y, int max_exp,
-                                   void* dst_packed, uint64_t* hist, bool with_hist, void* stream) {
-  FormatConsts fc;
-  bool wide = false;
-  if (exmy_status_t st = make_format(dt, X, Y, max_exp, true, &fc, &wide)) return st;
-  if (n > EXMY_MAX_ELEMENTS) return EXMY_ERR_COUNT;
-  if (with_hist && !hist) return EXMY_ERR_NULL;
-  if (n == 0) return EXMY_OK;
-  if (!src || !dst_packed) return EXMY_ERR_NULL;
-  if (!aligned16(src) || !aligned16(dst_packed)) return EXMY_ERR_ALIGN;
-  if (with_hist && (reinterpret_cast<uintptr_t>(hist) & 7u)) return EXMY_ERR_ALIGN;
-  const hipError_t e = encode_dispatch(dt, 1 + X + Y, wide, with_hist, src, dst_packed, n, fc, hist,
-                                       static_cast<hipStream_t>(stream));
-  return e == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
+  return make_format(dt, X, Y, max_exp, packed != 0, nullptr, nullptr, nullptr);
 }
 
 exmy_status_t exmy_encode(const void* src, exmy_dtype_t dt, uint64_t n, int X, int Y, int max_exp,
                           void* dst_packed, void* stream) {
-  return encode_common(src, dt, n, X, Y, max_exp, dst_packed, nullptr, false, stream);
+  const exmy_tensor_t t = {src, dst_packed, n, max_exp};
+  return run_batch(Op::kEncode, &t, 1, dt, X, Y, nullptr, false, stream);
 }
 
 exmy_status_t exmy_encode_with_histogram(const void* src, exmy_dtype_t dt, uint64_t n, int X, int Y, int max_exp,
                                          void* dst_packed, uint64_t* hist256_dev, void* stream) {
-  return encode_common(src, dt, n, X, Y, max_exp, dst_packed, hist256_dev, true, stream);
+  const exmy_tensor_t t = {src, dst_packed, n, max_exp};
+  return run_batch(Op::kEncode, &t, 1, dt, X, Y, hist256_dev, true, stream);
 }
 
 exmy_status_t exmy_decode(const void* src_packed, exmy_dtype_t dt_out, uint64_t n, int X, int Y, int max_exp,
                           void* dst, void* stream) {
-  FormatConsts fc;
-  if (exmy_status_t st = make_format(dt_out, X, Y, max_exp, true, &fc, nullptr)) return st;
-  if (n > EXMY_MAX_ELEMENTS) return EXMY_ERR_COUNT;
-  if (n == 0) return EXMY_OK;
-  if (!src_packed || !dst) return EXMY_ERR_NULL;
-  if (!aligned16(src_packed) || !aligned16(dst)) return EXMY_ERR_ALIGN;
-  const hipError_t e = decode_dispatch(dt_out, 1 + X + Y, X == 8, src_packed, dst, n, fc, static_cast<hipStream_t>(stream));
-  return e == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
+  const exmy_tensor_t t = {src_packed, dst, n, max_exp};
+  return run_batch(Op::kDecode, &t, 1, dt_out, X, Y, nullptr, false, stream);
+}
+
+exmy_status_t exmy_encode_batch(const exmy_tensor_t* tensors, size_t count, exmy_dtype_t dt, int X, int Y,
+                                void* stream) {
+  return run_batch(Op::kEncode, tensors, count, dt, X, Y, nullptr, false, stream);
+}
+
+exmy_status_t exmy_decode_batch(const exmy_tensor_t* tensors, size_t count, exmy_dtype_t dt_out, int X, int Y,
+                                void* stream) {
+  return run_batch(Op::kDecode, tensors, count, dt_out, X, Y, nullptr, false, stream);
 }
 
 exmy_status_t exmy_emulate(void* data_inout, exmy_dtype_t dt, uint64_t n, int X, int Y, int max_exp, void* stream) {
   FormatConsts fc;
+  TensorConsts tc;
   bool wide = false;
-  if (exmy_status_t st = make_format(dt, X, Y, max_exp, false, &fc, &wide)) return st;
+  if (exmy_status_t st = make_format(dt, X, Y, max_exp, false, &fc, &tc, &wide)) return st;
   if (n > EXMY_MAX_ELEMENTS) return EXMY_ERR_COUNT;
   if (n == 0) return EXMY_OK;
   if (!data_inout) return EXMY_ERR_NULL;
   if (!aligned16(data_inout)) return EXMY_ERR_ALIGN;
-  const hipError_t e = emulate_dispatch(dt, wide, data_inout, n, fc, static_cast<hipStream_t>(stream));
+  const hipError_t e = emulate_dispatch(dt, wide, data_inout, n, fc, tc, static_cast<hipStream_t>(stream));
   return e == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
 }
 

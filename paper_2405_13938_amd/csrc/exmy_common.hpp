@@ -11,43 +11,100 @@
 
 namespace exmy {
 
-// Everything a kernel needs to know about one (X, Y, max_exp), derived on the
-// host once per call and passed by value (lands in SGPRs).
+// Wave-uniform constants of a call, derived on the host and passed by value in
+// the kernel arguments (they land in SGPRs).  FormatConsts depends on (X, Y)
+// only and is shared by every tensor of a batch; TensorConsts also depends on
+// the tensor's max_exp.
 //
 // emin8 = max_exp - 2^X + 2 is the biased exponent of the binade with exponent
 // code 1; values under 2^(emin8-127) are rounded on the subnormal grid whose
 // quantum is 2^(emin8-127-Y) (Section 2 "Subnormals").
 struct FormatConsts {
-  // ---- encode / emulate
-  uint32_t sat_bits;    // fp32 bits of the largest normal; larger magnitudes (and Inf / NaN) clamp to it
-  uint32_t emin_bits;   // emin8 << 23
   float magic_scale;    // 2^(23-Y): exponent-only float * this = the magic addend of the rounding step
   int32_t wide_exp;     // wide path: 1023 - 127 + 52 - Y, the fp64 exponent offset of the magic addend
   // The encoder builds the code left-aligned in a 32-bit register (sign, if it is
   // part of the register, at bit 31) so that plane fields can be peeled off the top.
   uint32_t left_shift;  // L: position of code bit 0 in that register
   uint32_t exp_lshift;  // L - (23 - Y): moves (clamped exponent << 23) to (exponent << (Y + L))
-  uint32_t bias_left;   // -(emin8 << (Y + L)) mod 2^32
+  uint32_t exp_shift;   // 23 - Y
+  uint32_t g_clamp;     // X = 8 only: bits of the largest finite value, the cap for exponent code 255
+};
+
+struct TensorConsts {
+  // ---- encode / emulate
+  uint32_t sat_bits;   // fp32 bits of the largest normal; larger magnitudes (and Inf / NaN) clamp to it
+  uint32_t emin_bits;  // emin8 << 23
+  uint32_t bias_left;  // -(emin8 << (Y + L)) mod 2^32
   // ---- decode
-  uint32_t exp_shift;  // 23 - Y
   uint32_t dec_bias;   // (emin8 - 1) << 23
   float fix_mul;       // subnormal fix r = min(g, g * fix_mul + fix_add): (2, -2^(emin8-127)), or (1, 0) if emin8 = 1
   float fix_add;
-  uint32_t g_clamp;    // X = 8 only: bits of the largest finite value, the cap for exponent code 255
-  // ---- layout
-  uint32_t xy;         // X + Y: position of the sign bit in a code
-  uint32_t mag_mask;   // 2^(X+Y) - 1
-  uint32_t y;          // Y
 };
 
-// Host: validate and fill.  `packed` applies the W <= 16 limit.
+// One tensor of a batched launch.  For encode src holds n elements and dst the
+// packed planes; for decode the other way round; emulate uses src == dst.
+struct TensorArgs {
+  const void* src;
+  void* dst;
+  uint64_t n;
+  TensorConsts tc;
+};
+
+// A launch covers up to kMaxBatch tensors: blockIdx.y selects the tensor,
+// blockIdx.x the chunk of tiles inside it.
+constexpr int kMaxBatch = 64;
+struct BatchArgs {
+  FormatConsts fc;
+  uint32_t count;
+  unsigned long long* hist;  // encode with histogram only (single tensor), else null
+  TensorArgs t[kMaxBatch];
+};
+
+// Host: validate (dtype, X, Y, max_exp) and fill the constants (either may be
+// null).  `packed` applies the W <= 16 limit of the packed form.
 exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, bool packed, FormatConsts* fc,
-                          bool* needs_wide);
+                          TensorConsts* tc, bool* needs_wide);
 
 #if defined(__HIPCC__)
 
 __device__ __forceinline__ float as_f32(uint32_t u) { return __uint_as_float(u); }
 __device__ __forceinline__ uint32_t as_u32(float f) { return __float_as_uint(f); }
+
+// Global memory is reached through buffer instructions: a wave-uniform
+// descriptor (base pointer in SGPRs) plus a 32-bit per-lane byte offset and a
+// wave-uniform byte offset.  All 64-bit address arithmetic then stays on the
+// scalar unit; a lane only ever computes lane * element_size once per block.
+// Descriptors are rebuilt per chunk of tiles, so 32-bit offsets always suffice.
+// kNT adds the non-temporal hint: the data is streamed once, and keeping it out
+// of the caches' way leaves them to the other stream.
+typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
+typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+typedef __amdgpu_buffer_rsrc_t rsrc_t;
+
+__device__ __forceinline__ rsrc_t make_rsrc(const void* base) {
+  // raw buffer, 32-bit data format, whole 4 GiB window: callers never form an offset outside their tensor
+  return __builtin_amdgcn_make_buffer_rsrc(const_cast<void*>(base), 0, 0xFFFFFFFFu, 0x00020000);
+}
+
+constexpr int kAuxNT = 2;  // cache-policy bit of the non-temporal hint
+
+template <bool kNT>
+__device__ __forceinline__ uint4 load16(rsrc_t r, uint32_t voffset, uint32_t soffset) {
+  const u32x4_t v = __builtin_amdgcn_raw_buffer_load_b128(r, voffset, soffset, kNT ? kAuxNT : 0);
+  return make_uint4(v.x, v.y, v.z, v.w);
+}
+// The wave-uniform part of the offset is added into the per-lane offset here,
+// not passed in the instruction's scalar-offset field: a 16-byte buffer store
+// that takes its offset from an SGPR was seen, on gfx950, to pick up a VALU
+// write to its data registers issued in the very next cycle (wrong third dword
+// in memory).  The compiler only spaces such a pair when the scalar-offset field
+// is not a register, so the field is kept at zero.  Stores of 8 bytes or less
+// read their data in one pass and are not affected.
+template <bool kNT>
+__device__ __forceinline__ void store16(rsrc_t r, uint32_t voffset, uint32_t soffset, uint4 v) {
+  const u32x4_t w = {v.x, v.y, v.z, v.w};
+  __builtin_amdgcn_raw_buffer_store_b128(w, r, voffset + soffset, 0, kNT ? kAuxNT : 0);
+}
 
 // (a << shift) + c in one VALU instruction.  The compiler would otherwise
 // re-associate chains of these into separate shifts and a three-way add.
@@ -78,10 +135,10 @@ __device__ __forceinline__ uint32_t lshl_add(uint32_t a, uint32_t shift, uint32_
 // kWide = false needs max(max_exp, emin8) + 23 - Y <= 254 so that the addend is
 // a finite fp32; kWide = true does the same sum in fp64 and has no such limit.
 template <bool kWide>
-__device__ __forceinline__ uint32_t magnitude_code_left(uint32_t u, const FormatConsts& fc) {
+__device__ __forceinline__ uint32_t magnitude_code_left(uint32_t u, const FormatConsts& fc, const TensorConsts& tc) {
   uint32_t a = u & 0x7FFFFFFFu;
-  a = min(a, fc.sat_bits);
-  const uint32_t te = max(a, fc.emin_bits) & 0x7F800000u;  // ec << 23
+  a = min(a, tc.sat_bits);
+  const uint32_t te = max(a, tc.emin_bits) & 0x7F800000u;  // ec << 23
   uint32_t k;
   if constexpr (!kWide) {
     k = as_u32(__builtin_fmaf(as_f32(te), fc.magic_scale, as_f32(a)));
@@ -91,7 +148,7 @@ __device__ __forceinline__ uint32_t magnitude_code_left(uint32_t u, const Format
     const double s = (double)as_f32(a) + m;
     k = (uint32_t)__double2loint(s);
   }
-  const uint32_t q = lshl_add(te, fc.exp_lshift, fc.bias_left);
+  const uint32_t q = lshl_add(te, fc.exp_lshift, tc.bias_left);
   return lshl_add(k, fc.left_shift, q);
 }
 
@@ -106,9 +163,9 @@ __device__ __forceinline__ uint32_t magnitude_code_left(uint32_t u, const Format
 // the value: the constants (1, 0) then make the second operand equal g.
 // g is never a NaN pattern here (X = 8 callers clamp it first), so the minimum
 // is taken with the bare instruction, without a canonicalising pre-pass.
-__device__ __forceinline__ uint32_t finish_magnitude(uint32_t g_bits, const FormatConsts& fc) {
+__device__ __forceinline__ uint32_t finish_magnitude(uint32_t g_bits, const TensorConsts& tc) {
   const float g = as_f32(g_bits);
-  const float t = __builtin_fmaf(g, fc.fix_mul, fc.fix_add);
+  const float t = __builtin_fmaf(g, tc.fix_mul, tc.fix_add);
   float r;
   asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(g), "v"(t));
   return as_u32(r);

@@ -1,0 +1,229 @@
+// Fused decode: power-of-2 planes -> eXmY codes (Section 2.2.2, Fig. 2 read right
+// to left) -> bf16 / fp32 values (Section 2.2.1 "and vice versa").
+//
+// One lane produces one 16-byte store: a whole group of 8 bf16 values, or half a
+// group (4 values) of fp32, so that the lanes of a wavefront always write one
+// contiguous span.  The lane reads just the part of each plane word that holds
+// its elements (S bytes per plane for a group, S/2 for half a group; two lanes
+// share a byte of a 1-bit plane).  The code itself is never assembled: each
+// plane field is extracted and added straight into the fp32 bit pattern at the
+// position it has there.  Tiles, chunks and launch order are as in the encoder.
+#pragma once
+
+#include "exmy_common.hpp"
+
+namespace exmy {
+namespace dec {
+
+// The plane bits of the E consecutive elements one lane decodes (E = 8 or 4):
+// plane p uses w[p][0 .. ceil(E*S/32)).
+template <int W>
+struct UnitWords {
+  uint32_t w[Planes<W>::count][4];
+};
+
+// The source of one chunk: a descriptor per plane, based at the plane bits of the
+// chunk's first unit (a unit is E elements; chunks start on even units).
+template <int W>
+struct PlaneSrc {
+  rsrc_t plane[Planes<W>::count];
+};
+
+template <int W, int E, int P = 0>
+__device__ __forceinline__ void make_plane_src(const uint8_t* src, uint64_t G, uint64_t u0, PlaneSrc<W>& ps) {
+  if constexpr (P < Planes<W>::count) {
+    constexpr uint64_t kBits = E * Planes<W>::seg(P);
+    constexpr uint64_t LO = Planes<W>::lo(P);
+    ps.plane[P] = make_rsrc(src + (G * LO + (u0 * kBits) / 8));
+    make_plane_src<W, E, P + 1>(src, G, u0, ps);
+  }
+}
+
+// Plane bits of the unit number tile_unit + lane_unit of the chunk (tile_unit is
+// wave-uniform and even).
+template <int W, int E, int P = 0>
+__device__ __forceinline__ void load_unit(const PlaneSrc<W>& ps, uint32_t lane_unit, uint32_t tile_unit,
+                                          UnitWords<W>& uw) {
+  if constexpr (P < Planes<W>::count) {
+    constexpr int S = Planes<W>::seg(P);
+    constexpr int kBits = E * S;  // plane bits per unit: 128, 64, 32, 16, 8 or 4
+    const rsrc_t r = ps.plane[P];
+    if constexpr (kBits == 128) {
+      const uint4 o = load16<false>(r, lane_unit * 16, tile_unit * 16);
+      uw.w[P][0] = o.x; uw.w[P][1] = o.y; uw.w[P][2] = o.z; uw.w[P][3] = o.w;
+    } else if constexpr (kBits == 64) {
+      const u32x2_t o = __builtin_amdgcn_raw_buffer_load_b64(r, lane_unit * 8, tile_unit * 8, 0);
+      uw.w[P][0] = o.x; uw.w[P][1] = o.y;
+    } else if constexpr (kBits == 32) {
+      uw.w[P][0] = __builtin_amdgcn_raw_buffer_load_b32(r, lane_unit * 4, tile_unit * 4, 0);
+    } else if constexpr (kBits == 16) {
+      uw.w[P][0] = __builtin_amdgcn_raw_buffer_load_b16(r, lane_unit * 2, tile_unit * 2, 0);
+    } else if constexpr (kBits == 8) {
+      uw.w[P][0] = __builtin_amdgcn_raw_buffer_load_b8(r, lane_unit, tile_unit, 0);
+    } else {  // 4 bits: the low or high nibble of a byte shared with the neighbouring lane
+      uw.w[P][0] = (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(r, lane_unit >> 1, tile_unit >> 1, 0) >> (4 * (lane_unit & 1));
+    }
+    load_unit<W, E, P + 1>(ps, lane_unit, tile_unit, uw);
+  }
+}
+
+// Add the magnitude bits that plane P holds for element j of the unit into g, at
+// the place they have in the fp32 pattern.  The top plane's most significant bit
+// is the sign and is left out here.
+template <int W, int P>
+__device__ __forceinline__ uint32_t add_fields(const UnitWords<W>& uw, int j, uint32_t g, const FormatConsts& fc) {
+  if constexpr (P < Planes<W>::count) {
+    constexpr int S = Planes<W>::seg(P);
+    constexpr int LO = Planes<W>::lo(P);
+    constexpr bool top = P == Planes<W>::count - 1;
+    constexpr int width = top ? S - 1 : S;
+    if constexpr (width > 0) {
+      const int bit = S * j;
+      const uint32_t field = __builtin_amdgcn_ubfe(uw.w[P][bit / 32], bit % 32, width);
+      g = lshl_add(field, fc.exp_shift + LO, g);
+    }
+    return add_fields<W, P + 1>(uw, j, g, fc);
+  } else {
+    return g;
+  }
+}
+
+// fp32 bit pattern of element j of the unit.
+template <int W, bool kX8>
+__device__ __forceinline__ uint32_t element_bits(const UnitWords<W>& uw, int j, const FormatConsts& fc,
+                                                 const TensorConsts& tc) {
+  uint32_t g = add_fields<W, 0>(uw, j, tc.dec_bias, fc);
+  if constexpr (kX8) g = min(g, fc.g_clamp);  // exponent code 255 is not a value: largest finite instead
+  const uint32_t mag = finish_magnitude(g, tc);
+  constexpr int PT = Planes<W>::count - 1;
+  constexpr int ST = Planes<W>::seg(PT);
+  const int bit = ST * j + ST - 1;  // the sign: top bit of the top plane's field
+  const uint32_t s = uw.w[PT][bit / 32] << (31 - bit % 32);
+  return (s & 0x80000000u) | mag;
+}
+
+// Values of one unit, stored to 16-byte vector lane_unit + tile_unit of `out`.
+template <typename T, int W, bool kX8, bool kNT>
+__device__ __forceinline__ void decode_unit(const UnitWords<W>& uw, const FormatConsts& fc, const TensorConsts& tc,
+                                            rsrc_t out, uint32_t lane_unit, uint32_t tile_unit) {
+  constexpr int E = 16 / sizeof(T);
+  uint32_t b[E];
+#pragma unroll
+  for (int j = 0; j < E; ++j) b[j] = element_bits<W, kX8>(uw, j, fc, tc);
+  if constexpr (sizeof(T) == 4) {
+    store16<kNT>(out, lane_unit * 16, tile_unit * 16, make_uint4(b[0], b[1], b[2], b[3]));
+  } else {
+    // every value is exact in bf16: keep the upper halves
+    uint4 o;
+    o.x = __builtin_amdgcn_perm(b[1], b[0], 0x07060302u);
+    o.y = __builtin_amdgcn_perm(b[3], b[2], 0x07060302u);
+    o.z = __builtin_amdgcn_perm(b[5], b[4], 0x07060302u);
+    o.w = __builtin_amdgcn_perm(b[7], b[6], 0x07060302u);
+    store16<kNT>(out, lane_unit * 16, tile_unit * 16, o);
+  }
+}
+
+template <int W, int kUnroll>
+struct TileWords {
+  UnitWords<W> u[kUnroll];
+};
+
+// Loads of the tile whose first unit, relative to the chunk, is tile_unit (wave-
+// uniform, even).  kGuard: only the first `rem` units of the tile exist.
+template <int W, int E, int kBlock, int kUnroll, bool kGuard>
+__device__ __forceinline__ void load_tile(const PlaneSrc<W>& ps, uint32_t tile_unit, uint32_t rem,
+                                          TileWords<W, kUnroll>& tw) {
+#pragma unroll
+  for (int r = 0; r < kUnroll; ++r) {
+    if (!kGuard || r * kBlock + threadIdx.x < rem) load_unit<W, E>(ps, threadIdx.x, tile_unit + r * kBlock, tw.u[r]);
+  }
+}
+
+template <typename T, int W, int kBlock, int kUnroll, bool kX8, bool kNT, bool kGuard>
+__device__ __forceinline__ void decode_tile(const TileWords<W, kUnroll>& tw, rsrc_t out, uint32_t tile_unit,
+                                            uint32_t rem, const FormatConsts& fc, const TensorConsts& tc) {
+#pragma unroll
+  for (int r = 0; r < kUnroll; ++r) {
+    if (!kGuard || r * kBlock + threadIdx.x < rem)
+      decode_unit<T, W, kX8, kNT>(tw.u[r], fc, tc, out, threadIdx.x, tile_unit + r * kBlock);
+  }
+}
+
+// One element straight from memory (the few elements after the last whole unit).
+template <int W, bool kX8>
+__device__ __forceinline__ uint32_t element_bits_slow(const uint8_t* __restrict__ src, uint64_t G, uint64_t idx,
+                                                      const FormatConsts& fc, const TensorConsts& tc) {
+  PlaneSrc<W> ps;
+  make_plane_src<W, 8>(src, G, idx / 8, ps);  // the whole group that holds the element
+  UnitWords<W> uw;
+  load_unit<W, 8>(ps, 0, 0, uw);
+  uint32_t b = 0;
+#pragma unroll
+  for (int j = 0; j < 8; ++j)
+    if ((int)(idx % 8) == j) b = element_bits<W, kX8>(uw, j, fc, tc);
+  return b;
+}
+
+// Grid: x = one block per chunk of kChunk tiles of the largest tensor (any
+// smaller x also works), y = tensor of the batch.  Chunks of whole tiles take a
+// straight-line path with the next tile's loads issued ahead; the chunk that
+// holds the end of the tensor takes a guarded loop.
+template <typename T, int W, int kBlock, int kUnroll, int kChunk, bool kX8, bool kNT>
+__global__ __launch_bounds__(kBlock) void decode_kernel(const BatchArgs batch) {
+  constexpr uint32_t TU = kBlock * kUnroll;
+  static_assert(TU % 2 == 0, "a tile must start on a byte of the 1-bit plane");
+  static_assert(TU * (16 / sizeof(T)) >= 512, "tile counts must fit 32 bits for n <= 2^40");
+  const TensorArgs& ta = batch.t[blockIdx.y];
+  const uint8_t* __restrict__ src = static_cast<const uint8_t*>(ta.src);
+  T* __restrict__ dst = static_cast<T*>(ta.dst);
+  const uint64_t n = ta.n;
+  const FormatConsts fc = batch.fc;
+  const TensorConsts tc = ta.tc;
+  constexpr int E = 16 / sizeof(T);  // elements per lane
+  const uint64_t G = (n + 7) / 8;
+  const uint64_t Ufull = n / E;  // units with all E elements present
+  const uint32_t full_tiles = (uint32_t)(Ufull / TU);
+  const uint32_t rem_units = (uint32_t)(Ufull - (uint64_t)full_tiles * TU);
+  const uint32_t tiles = full_tiles + (rem_units ? 1u : 0u);
+  const uint32_t full_chunks = full_tiles / kChunk;
+  const uint32_t chunks = (tiles + kChunk - 1) / kChunk;
+
+  for (uint32_t chunk = blockIdx.x; chunk < chunks; chunk += gridDim.x) {
+    const uint64_t u0 = (uint64_t)chunk * (kChunk * TU);  // first unit of the chunk (even)
+    PlaneSrc<W> ps;
+    make_plane_src<W, E>(src, G, u0, ps);
+    const rsrc_t out = make_rsrc(reinterpret_cast<uint4*>(dst) + u0);
+    if (chunk < full_chunks) {
+      TileWords<W, kUnroll> tw[2];
+      load_tile<W, E, kBlock, kUnroll, false>(ps, 0, 0, tw[0]);
+#pragma unroll
+      for (int c = 0; c < kChunk; ++c) {
+        if (c + 1 < kChunk) load_tile<W, E, kBlock, kUnroll, false>(ps, (c + 1) * TU, 0, tw[(c + 1) & 1]);
+        decode_tile<T, W, kBlock, kUnroll, kX8, kNT, false>(tw[c & 1], out, c * TU, 0, fc, tc);
+      }
+    } else {
+      for (uint32_t tile = chunk * kChunk; tile < tiles; ++tile) {
+        const uint32_t tile_unit = (tile - chunk * kChunk) * TU;
+        const uint32_t rem = tile < full_tiles ? TU : rem_units;
+        TileWords<W, kUnroll> tw;
+        load_tile<W, E, kBlock, kUnroll, true>(ps, tile_unit, rem, tw);
+        decode_tile<T, W, kBlock, kUnroll, kX8, kNT, true>(tw, out, tile_unit, rem, fc, tc);
+      }
+    }
+  }
+
+  // The n % E elements after the last whole unit, one lane each.
+  if (blockIdx.x == 0 && threadIdx.x < E) {
+    const uint64_t i = Ufull * E + threadIdx.x;
+    if (i < n) {
+      const uint32_t b = element_bits_slow<W, kX8>(src, G, i, fc, tc);
+      if constexpr (sizeof(T) == 4)
+        reinterpret_cast<uint32_t*>(dst)[i] = b;
+      else
+        reinterpret_cast<uint16_t*>(dst)[i] = (uint16_t)(b >> 16);
+    }
+  }
+}
+
+}  // namespace dec
+}  // namespace exmy

@@ -15,10 +15,10 @@ constexpr int kBlock = 256;
 // quantum), but the rounded magnitude is recovered as a float by subtracting
 // the addend again instead of being re-biased into a code.
 template <bool kWide>
-__device__ __forceinline__ uint32_t emulate_bits(uint32_t u, const FormatConsts& fc) {
+__device__ __forceinline__ uint32_t emulate_bits(uint32_t u, const FormatConsts& fc, const TensorConsts& tc) {
   const uint32_t a0 = u & 0x7FFFFFFFu;
-  const uint32_t a = min(a0, fc.sat_bits);
-  const uint32_t te = max(a, fc.emin_bits) & 0x7F800000u;
+  const uint32_t a = min(a0, tc.sat_bits);
+  const uint32_t te = max(a, tc.emin_bits) & 0x7F800000u;
   uint32_t r;
   if constexpr (!kWide) {
     const float m = as_f32(te) * fc.magic_scale;
@@ -35,7 +35,8 @@ __device__ __forceinline__ uint32_t emulate_bits(uint32_t u, const FormatConsts&
 }
 
 template <typename T, int kUnroll, bool kWide>
-__global__ __launch_bounds__(kBlock) void emulate_kernel(T* __restrict__ data, uint64_t n, FormatConsts fc) {
+__global__ __launch_bounds__(kBlock) void emulate_kernel(T* __restrict__ data, uint64_t n, FormatConsts fc,
+                                                          TensorConsts tc) {
   constexpr int kPer = 16 / sizeof(T);  // elements per 16-byte vector
   const uint64_t V = n / kPer;          // whole vectors
   uint4* __restrict__ d4 = reinterpret_cast<uint4*>(data);
@@ -59,10 +60,10 @@ __global__ __launch_bounds__(kBlock) void emulate_kernel(T* __restrict__ data, u
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
           if constexpr (sizeof(T) == 4) {
-            w[k] = emulate_bits<kWide>(w[k], fc);
+            w[k] = emulate_bits<kWide>(w[k], fc, tc);
           } else {
-            const uint32_t lo = emulate_bits<kWide>(w[k] << 16, fc);
-            const uint32_t hi = emulate_bits<kWide>(w[k] & 0xFFFF0000u, fc);
+            const uint32_t lo = emulate_bits<kWide>(w[k] << 16, fc, tc);
+            const uint32_t hi = emulate_bits<kWide>(w[k] & 0xFFFF0000u, fc, tc);
             w[k] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
           }
         }
@@ -77,35 +78,37 @@ __global__ __launch_bounds__(kBlock) void emulate_kernel(T* __restrict__ data, u
     if (i < n) {
       if constexpr (sizeof(T) == 4) {
         uint32_t* p = reinterpret_cast<uint32_t*>(data) + i;
-        *p = emulate_bits<kWide>(*p, fc);
+        *p = emulate_bits<kWide>(*p, fc, tc);
       } else {
         uint16_t* p = reinterpret_cast<uint16_t*>(data) + i;
-        *p = (uint16_t)(emulate_bits<kWide>((uint32_t)*p << 16, fc) >> 16);
+        *p = (uint16_t)(emulate_bits<kWide>((uint32_t)*p << 16, fc, tc) >> 16);
       }
     }
   }
 }
 
 template <typename T, bool kWide>
-hipError_t launch_emulate(void* data, uint64_t n, const FormatConsts& fc, hipStream_t stream) {
+hipError_t launch_emulate(void* data, uint64_t n, const FormatConsts& fc, const TensorConsts& tc,
+                          hipStream_t stream) {
   constexpr int kUnroll = 4;
   constexpr int kPer = 16 / sizeof(T);
   const uint64_t tile_vecs = (uint64_t)kBlock * kUnroll;
   const uint64_t tiles = (n / kPer + tile_vecs - 1) / tile_vecs;
   const uint32_t grid = grid_for_tiles(tiles, 16);
   hipLaunchKernelGGL((emulate_kernel<T, kUnroll, kWide>), dim3(grid), dim3(kBlock), 0, stream,
-                     static_cast<T*>(data), n, fc);
+                     static_cast<T*>(data), n, fc, tc);
   return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t emulate_dispatch(exmy_dtype_t dt, bool wide, void* data, uint64_t n, const FormatConsts& fc,
-                            hipStream_t stream) {
+                            const TensorConsts& tc, hipStream_t stream) {
   if (dt == EXMY_F32)
-    return wide ? launch_emulate<float, true>(data, n, fc, stream) : launch_emulate<float, false>(data, n, fc, stream);
-  return wide ? launch_emulate<uint16_t, true>(data, n, fc, stream)
-              : launch_emulate<uint16_t, false>(data, n, fc, stream);
+    return wide ? launch_emulate<float, true>(data, n, fc, tc, stream)
+                : launch_emulate<float, false>(data, n, fc, tc, stream);
+  return wide ? launch_emulate<uint16_t, true>(data, n, fc, tc, stream)
+              : launch_emulate<uint16_t, false>(data, n, fc, tc, stream);
 }
 
 }  // namespace exmy

@@ -1,0 +1,285 @@
+// Fused encode: float -> eXmY code (Section 2.2.1) -> power-of-2 planes
+// (Section 2.2.2, Fig. 2), optionally with the exponent histogram of Section 3.1
+// taken from the same registers.
+//
+// Work decomposition: one lane owns whole groups of 8 consecutive elements, so
+// every plane word it produces is complete and byte aligned.  A bf16 group is
+// one 16-byte load, an fp32 group two adjacent ones; lane i of a block takes
+// group (tile base + i), so a wavefront reads one contiguous span per load
+// instruction.  A tile is kBlock * kUnroll groups; a block walks kChunk
+// consecutive tiles and issues the loads of the next tile before converting the
+// current one, so that bytes stay in flight while the ALUs work.  Blocks are
+// launched one per chunk, in address order: the hardware dispatcher then keeps
+// the set of active blocks on a compact, moving window of memory, which
+// measured faster here than a grid-stride loop of resident blocks.
+#pragma once
+
+#include "exmy_common.hpp"
+
+namespace exmy {
+namespace enc {
+
+// Histogram bins are replicated kHistCopies times in LDS, copy chosen by lane,
+// so that the few hot exponents of a real tensor do not serialise on one bank.
+constexpr int kHistCopies = 8;
+
+// 32-bit LDS bins are folded into the 64-bit global bins after this many tiles,
+// long before 2^32 elements have been counted by one block.
+constexpr uint32_t kTilesPerFlush = 1u << 15;
+
+// Fold the block's LDS histogram copies into the global 64-bit bins and clear them.
+template <int kBlock>
+__device__ __forceinline__ void flush_bins(uint32_t* bins, unsigned long long* __restrict__ hist) {
+  __syncthreads();
+  for (int bin = threadIdx.x; bin < 256; bin += kBlock) {
+    uint32_t c = 0;
+#pragma unroll
+    for (int r = 0; r < kHistCopies; ++r) {
+      c += bins[bin * kHistCopies + r];
+      bins[bin * kHistCopies + r] = 0;
+    }
+    if (c) atomicAdd(&hist[bin], (unsigned long long)c);
+  }
+  __syncthreads();
+}
+
+// fp32-position bit patterns of the 8 elements of a group held in 16-byte vectors.
+template <typename T>
+__device__ __forceinline__ void group_bits(const uint4* v, uint32_t u[8]) {
+  if constexpr (sizeof(T) == 4) {
+    u[0] = v[0].x; u[1] = v[0].y; u[2] = v[0].z; u[3] = v[0].w;
+    u[4] = v[1].x; u[5] = v[1].y; u[6] = v[1].z; u[7] = v[1].w;
+  } else {
+    const uint32_t w[4] = {v[0].x, v[0].y, v[0].z, v[0].w};
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      u[2 * i] = w[i] << 16;
+      u[2 * i + 1] = w[i] & 0xFFFF0000u;
+    }
+  }
+}
+
+// (hi : lo) >> shift, low 32 bits: with shift = 32 - S this appends the top S bits
+// of lo under hi << S in one instruction.
+__device__ __forceinline__ uint32_t append_top(uint32_t hi, uint32_t lo, int S) {
+  return __builtin_amdgcn_alignbit(hi, lo, 32 - S);
+}
+
+// The destination of one chunk: a descriptor per plane, based at the plane word
+// of the chunk's first group.
+template <int W>
+struct PlaneDst {
+  rsrc_t plane[Planes<W>::count];
+};
+
+template <int W, int P = 0>
+__device__ __forceinline__ void make_plane_dst(uint8_t* dst, uint64_t G, uint64_t g0, PlaneDst<W>& pd) {
+  if constexpr (P < Planes<W>::count) {
+    constexpr uint64_t S = Planes<W>::seg(P);
+    constexpr uint64_t LO = Planes<W>::lo(P);  // planes before P hold LO bits per element = LO bytes per group
+    pd.plane[P] = make_rsrc(dst + (G * LO + g0 * S));
+    make_plane_dst<W, P + 1>(dst, G, g0, pd);
+  }
+}
+
+// Write one plane word: the S-bit fields that sit at the TOP of t[0..7], element
+// j at bits [S*j, S*j + S) of the little-endian plane word (Fig. 2).  The word
+// goes to byte lane_group * S + tile_off of the plane descriptor.
+template <int S>
+__device__ __forceinline__ void store_plane_from_top(const uint32_t t[8], rsrc_t plane, uint32_t lane_group,
+                                                     uint32_t tile_off) {
+  const uint32_t voff = lane_group * S;
+  if constexpr (S == 16) {
+    uint4 o;
+    o.x = append_top(t[1] >> 16, t[0], 16);
+    o.y = append_top(t[3] >> 16, t[2], 16);
+    o.z = append_top(t[5] >> 16, t[4], 16);
+    o.w = append_top(t[7] >> 16, t[6], 16);
+    store16<false>(plane, voff, tile_off, o);
+  } else if constexpr (S == 8) {
+    u32x2_t o;
+    o.x = append_top(append_top(append_top(t[3] >> 24, t[2], 8), t[1], 8), t[0], 8);
+    o.y = append_top(append_top(append_top(t[7] >> 24, t[6], 8), t[5], 8), t[4], 8);
+    __builtin_amdgcn_raw_buffer_store_b64(o, plane, voff, tile_off, 0);
+  } else {
+    uint32_t word = t[7] >> (32 - S);
+#pragma unroll
+    for (int j = 6; j >= 0; --j) word = append_top(word, t[j], S);
+    if constexpr (S == 4) __builtin_amdgcn_raw_buffer_store_b32(word, plane, voff, tile_off, 0);
+    if constexpr (S == 2) __builtin_amdgcn_raw_buffer_store_b16((uint16_t)word, plane, voff, tile_off, 0);
+    if constexpr (S == 1) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)word, plane, voff, tile_off, 0);
+  }
+}
+
+// Peel the planes off the left-aligned codes from the most significant segment
+// down.  With an odd W the top plane is 1 bit wide and is exactly the sign: it is
+// taken from the source bits u, and f holds the magnitude alone.
+// `lane_group` is the lane's group within the tile, `tile_group` the tile's first
+// group relative to the chunk (wave-uniform).
+template <int W, int P>
+__device__ __forceinline__ void peel_planes(uint32_t f[8], const uint32_t u[8], const PlaneDst<W>& pd,
+                                            uint32_t lane_group, uint32_t tile_group) {
+  constexpr int S = Planes<W>::seg(P);
+  constexpr bool sign_plane = (W & 1) && P == Planes<W>::count - 1;
+  if constexpr (sign_plane) {
+    store_plane_from_top<S>(u, pd.plane[P], lane_group, tile_group * S);
+  } else {
+    store_plane_from_top<S>(f, pd.plane[P], lane_group, tile_group * S);
+    if constexpr (P > 0) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) f[j] <<= S;
+    }
+  }
+  if constexpr (P > 0) peel_planes<W, P - 1>(f, u, pd, lane_group, tile_group);
+}
+
+// Convert the 8 elements of one group (fp32-position bits u) and write its planes.
+template <int W, bool kWide>
+__device__ __forceinline__ void encode_group(const uint32_t u[8], const FormatConsts& fc, const TensorConsts& tc,
+                                             const PlaneDst<W>& pd, uint32_t lane_group, uint32_t tile_group) {
+  uint32_t f[8];
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const uint32_t m = magnitude_code_left<kWide>(u[j], fc, tc);
+    f[j] = (W & 1) ? m : ((u[j] & 0x80000000u) | m);  // even W: the sign rides at bit 31
+  }
+  peel_planes<W, Planes<W>::count - 1>(f, u, pd, lane_group, tile_group);
+}
+
+template <typename T, int kUnroll>
+struct TileRegs {
+  static constexpr int kLoads = sizeof(T) == 4 ? 2 : 1;  // 16-byte loads per group of 8
+  uint4 v[kUnroll][kLoads];
+};
+
+// Loads of one tile: `src` is the descriptor of the chunk, tile_group the tile's
+// first group relative to it (wave-uniform); lane i takes groups r*kBlock + i.
+// kGuard: only the first `rem` groups of the tile exist.
+template <typename T, int kBlock, int kUnroll, bool kNT, bool kGuard>
+__device__ __forceinline__ void load_tile(rsrc_t src, uint32_t tile_group, uint32_t rem, TileRegs<T, kUnroll>& regs) {
+  constexpr int kLoads = TileRegs<T, kUnroll>::kLoads;
+  constexpr uint32_t kGroupBytes = 16 * kLoads;
+  const uint32_t lane_off = threadIdx.x * kGroupBytes;
+#pragma unroll
+  for (int r = 0; r < kUnroll; ++r) {
+    if (!kGuard || r * kBlock + threadIdx.x < rem) {
+#pragma unroll
+      for (int l = 0; l < kLoads; ++l)
+        regs.v[r][l] = load16<kNT>(src, lane_off, (tile_group + r * kBlock) * kGroupBytes + l * 16);
+    }
+  }
+}
+
+// Convert and store one tile.
+template <typename T, int W, int kBlock, int kUnroll, bool kWide, bool kHist, bool kGuard>
+__device__ __forceinline__ void encode_tile(const TileRegs<T, kUnroll>& regs, const PlaneDst<W>& pd,
+                                            uint32_t tile_group, uint32_t rem, const FormatConsts& fc,
+                                            const TensorConsts& tc, uint32_t* lds_hist) {
+#pragma unroll
+  for (int r = 0; r < kUnroll; ++r) {
+    if (!kGuard || r * kBlock + threadIdx.x < rem) {
+      uint32_t u[8];
+      group_bits<T>(regs.v[r], u);
+      if constexpr (kHist) {
+        const uint32_t copy = threadIdx.x & (kHistCopies - 1);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) atomicAdd(&lds_hist[((u[j] >> 23) & 0xFFu) * kHistCopies + copy], 1u);
+      }
+      encode_group<W, kWide>(u, fc, tc, pd, threadIdx.x, tile_group + r * kBlock);
+    }
+  }
+}
+
+// Grid: x = one block per chunk of kChunk tiles of the largest tensor (any
+// smaller x also works: blocks then stride over the chunks), y = tensor of the
+// batch.  Blocks past the end of a smaller tensor find nothing to do.
+//
+// A chunk made of whole tiles takes the straight-line path: the loads of tile
+// c + 1 are issued before tile c is converted, with no bounds checks and only
+// wave-uniform address arithmetic.  The chunk that holds the end of the tensor
+// takes a guarded loop.
+template <typename T, int W, int kBlock, int kUnroll, int kChunk, bool kWide, bool kHist, bool kNT>
+__global__ __launch_bounds__(kBlock) void encode_kernel(const BatchArgs batch) {
+  constexpr uint32_t TG = kBlock * kUnroll;
+  constexpr int kLoads = TileRegs<T, kUnroll>::kLoads;
+  static_assert(TG >= 64, "tile counts must fit 32 bits for n <= 2^40");
+  const TensorArgs& ta = batch.t[blockIdx.y];
+  const uint4* __restrict__ src4 = static_cast<const uint4*>(ta.src);
+  uint8_t* __restrict__ dst = static_cast<uint8_t*>(ta.dst);
+  const uint64_t n = ta.n;
+  const FormatConsts fc = batch.fc;
+  const TensorConsts tc = ta.tc;
+  unsigned long long* __restrict__ hist = batch.hist;
+  const uint64_t G = (n + 7) / 8;  // groups, the last one possibly ragged
+  const uint64_t Gfull = n / 8;    // groups with all 8 elements present
+  const uint32_t full_tiles = (uint32_t)(Gfull / TG);
+  const uint32_t rem_groups = (uint32_t)(Gfull - (uint64_t)full_tiles * TG);  // groups of the partial tile
+  const uint32_t tiles = full_tiles + (rem_groups ? 1u : 0u);
+  const uint32_t full_chunks = full_tiles / kChunk;
+  const uint32_t chunks = (tiles + kChunk - 1) / kChunk;
+
+  __shared__ uint32_t lds_hist[kHist ? 256 * kHistCopies : 1];
+  if constexpr (kHist) {
+    for (int i = threadIdx.x; i < 256 * kHistCopies; i += kBlock) lds_hist[i] = 0;
+    __syncthreads();
+  }
+
+  uint32_t since_flush = 0;
+  for (uint32_t chunk = blockIdx.x; chunk < chunks; chunk += gridDim.x) {
+    const uint64_t g0 = (uint64_t)chunk * (kChunk * TG);  // first group of the chunk
+    const rsrc_t src = make_rsrc(src4 + g0 * kLoads);
+    PlaneDst<W> pd;
+    make_plane_dst<W>(dst, G, g0, pd);
+    if (chunk < full_chunks) {
+      TileRegs<T, kUnroll> regs[2];
+      load_tile<T, kBlock, kUnroll, kNT, false>(src, 0, 0, regs[0]);
+#pragma unroll
+      for (int c = 0; c < kChunk; ++c) {
+        if (c + 1 < kChunk) load_tile<T, kBlock, kUnroll, kNT, false>(src, (c + 1) * TG, 0, regs[(c + 1) & 1]);
+        encode_tile<T, W, kBlock, kUnroll, kWide, kHist, false>(regs[c & 1], pd, c * TG, 0, fc, tc, lds_hist);
+      }
+    } else {
+      for (uint32_t tile = chunk * kChunk; tile < tiles; ++tile) {
+        const uint32_t tile_group = (tile - chunk * kChunk) * TG;
+        const uint32_t rem = tile < full_tiles ? TG : rem_groups;
+        TileRegs<T, kUnroll> regs;
+        load_tile<T, kBlock, kUnroll, kNT, true>(src, tile_group, rem, regs);
+        encode_tile<T, W, kBlock, kUnroll, kWide, kHist, true>(regs, pd, tile_group, rem, fc, tc, lds_hist);
+      }
+    }
+    if constexpr (kHist) {
+      since_flush += kChunk;
+      if (since_flush >= kTilesPerFlush) {
+        flush_bins<kBlock>(lds_hist, hist);
+        since_flush = 0;
+      }
+    }
+  }
+
+  // Ragged last group: one lane reads the n % 8 elements one by one and pads
+  // with +0, which encodes to code 0.
+  if (Gfull != G && blockIdx.x == 0 && threadIdx.x == 0) {
+    const T* __restrict__ src = static_cast<const T*>(ta.src);
+    uint32_t u[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const uint64_t i = Gfull * 8 + j;
+      u[j] = 0;
+      if (i < n) {
+        if constexpr (sizeof(T) == 4)
+          u[j] = reinterpret_cast<const uint32_t*>(src)[i];
+        else
+          u[j] = (uint32_t) reinterpret_cast<const uint16_t*>(src)[i] << 16;
+        if constexpr (kHist) atomicAdd(&lds_hist[((u[j] >> 23) & 0xFFu) * kHistCopies], 1u);
+      }
+    }
+    PlaneDst<W> pd;
+    make_plane_dst<W>(dst, G, Gfull, pd);
+    encode_group<W, kWide>(u, fc, tc, pd, 0, 0);
+  }
+
+  if constexpr (kHist) flush_bins<kBlock>(lds_hist, hist);
+}
+
+}  // namespace enc
+}  // namespace exmy

@@ -19,12 +19,23 @@ inline uint32_t grid_for_tiles(uint64_t tiles, int blocks_per_cu) {
   return (uint32_t)(g ? g : 1);
 }
 
-hipError_t encode_dispatch(exmy_dtype_t dt, int W, bool wide, bool with_hist, const void* src, void* dst,
-                           uint64_t n, const FormatConsts& fc, uint64_t* hist, hipStream_t stream);
-hipError_t decode_dispatch(exmy_dtype_t dt, int W, bool x8, const void* src, void* dst, uint64_t n,
-                           const FormatConsts& fc, hipStream_t stream);
+// Grid size for one block per chunk of `chunk` tiles.  A launch that would need
+// more blocks than a grid dimension can hold is capped; the kernels then stride.
+// (The dispatch packet counts work-items in 32 bits: blocks * block_size < 2^32.)
+inline uint32_t grid_for_chunks(uint64_t tiles, int chunk, int block_size) {
+  const uint64_t blocks = (tiles + (uint64_t)chunk - 1) / (uint64_t)chunk;
+  const uint64_t cap = 0xFFFFFFFFull / (uint64_t)block_size;
+  const uint64_t g = blocks < cap ? blocks : cap;
+  return (uint32_t)(g ? g : 1);
+}
+
+// `n_max` is the largest element count among the batch's tensors (sizes the grid).
+hipError_t encode_dispatch(exmy_dtype_t dt, int W, bool wide, bool with_hist, const BatchArgs& args, uint64_t n_max,
+                           hipStream_t stream);
+hipError_t decode_dispatch(exmy_dtype_t dt, int W, bool x8, const BatchArgs& args, uint64_t n_max,
+                           hipStream_t stream);
 hipError_t emulate_dispatch(exmy_dtype_t dt, bool wide, void* data, uint64_t n, const FormatConsts& fc,
-                            hipStream_t stream);
+                            const TensorConsts& tc, hipStream_t stream);
 hipError_t histogram_dispatch(exmy_dtype_t dt, const void* src, uint64_t n, uint64_t* hist, hipStream_t stream);
 
 }  // namespace exmy

