@@ -28,7 +28,11 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E datasheet peak
 
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs scaled by a copy kernel of known size (profiles/*hbm_traffic*.txt).  None = not measured.
-MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {}
+MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
+    # profiles/cfg5_bf16_e3m3_encode_decode_hbm_traffic.txt: mean over the 5 launches of a batched call
+    ("cfg5", "batch", "encode"): 3723911859,
+    ("cfg5", "batch", "decode"): 3723935679,
+}
 
 
 def parse_args():
@@ -42,6 +46,9 @@ def parse_args():
     ap.add_argument("--mode", default="batch", choices=["batch", "calls"],
                     help="batch = exmy_encode_batch / exmy_decode_batch (default); calls = one call per tensor")
     ap.add_argument("--layers", type=int, default=32, help="cfg5 only: decoder layers (32 = the full workload)")
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="run only a plain 1 GiB-in / 1 GiB-out elementwise copy kernel (the known-size kernel that "
+                         "the rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE readings are scaled by) and exit")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-extras", action="store_true", help="skip the short runs of the other workloads")
     return ap.parse_args()
@@ -246,6 +253,16 @@ def main():
     torch.cuda.set_device(0)
     exmy.binding.lib()
 
+    if args.calibrate_copy:
+        a = torch.randn(1 << 28, dtype=torch.float32, device=dev)
+        b = torch.empty_like(a)
+        for _ in range(5):
+            torch.mul(a, 1.0, out=b)  # one vectorised elementwise kernel: reads 1 GiB, writes 1 GiB
+        torch.cuda.synchronize()
+        print(json.dumps({"calibration": "torch.mul(a, 1.0, out=b)", "bytes_read": a.numel() * 4,
+                          "bytes_written": a.numel() * 4, "launches": 5}))
+        return
+
     wl = build_workload(args.workload, exmy, synth, dev, args.layers)
     wl.prepare(exmy, args.mode)
     torch.cuda.synchronize()
@@ -264,7 +281,7 @@ def main():
     src0 = wl.jobs[0][0]
     W = 1 + wl.jobs[0][1] + wl.jobs[0][2]
     kernel = "%s_kernel<%s, W=%d>" % (slow, "bf16" if src0.element_size() == 2 else "fp32", W)
-    traffic = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((args.workload, slow))
+    traffic = MEASURED_TRAFFIC_BYTES_PER_LAUNCH.get((args.workload, args.mode, slow)) if args.layers == 32 else None
     roofline = {
         "bound": "hbm",
         "kernel": kernel,

@@ -6,20 +6,20 @@ namespace exmy {
 
 namespace {
 
-// Launch shapes, from a sweep of block size x groups per lane x tiles per block x
-// non-temporal stores on MI355X with 1 GiB outputs.
+// Launch shapes, from a sweep of block size x units per lane x tiles per block x
+// non-temporal stores on MI355X over 32 MiB, 86 MiB and 1 GiB tensors.
 template <typename T>
 struct Shape;
 template <>
 struct Shape<uint16_t> {
-  static constexpr int kBlock = 64;
+  static constexpr int kBlock = 128;
   static constexpr int kUnroll = 2;
   static constexpr int kChunk = 1;
   static constexpr bool kNT = true;
 };
 template <>
 struct Shape<float> {
-  static constexpr int kBlock = 64;
+  static constexpr int kBlock = 256;
   static constexpr int kUnroll = 2;
   static constexpr int kChunk = 1;
   static constexpr bool kNT = true;
