@@ -9,21 +9,22 @@ namespace {
 // Launch shapes, from a sweep of block size x groups per lane x tiles per block x
 // non-temporal loads on MI355X over 32 MiB, 86 MiB and 1 GiB tensors (back-to-back
 // launches on rotating buffers): one tile per block, two bf16 groups or one fp32
-// group per lane.  The histogram variant walks long chunks so that a block's LDS
-// bins are folded into the global bins rarely.
+// group per lane.  The histogram variant uses large blocks that walk chunks of 8
+// tiles, so that a block's LDS bins are folded into the global bins once per
+// 65536 elements.
 template <typename T, bool kHist>
 struct Shape;
 template <bool kHist>
 struct Shape<uint16_t, kHist> {
-  static constexpr int kBlock = 64;
+  static constexpr int kBlock = kHist ? 512 : 64;
   static constexpr int kUnroll = 2;
   static constexpr int kChunk = kHist ? 8 : 1;
   static constexpr bool kNT = true;
 };
 template <bool kHist>
 struct Shape<float, kHist> {
-  static constexpr int kBlock = 128;
-  static constexpr int kUnroll = 1;
+  static constexpr int kBlock = kHist ? 512 : 128;
+  static constexpr int kUnroll = kHist ? 2 : 1;
   static constexpr int kChunk = kHist ? 8 : 1;
   static constexpr bool kNT = true;
 };
@@ -33,12 +34,7 @@ hipError_t launch_encode(const BatchArgs& args, uint64_t n_max, hipStream_t stre
   using S = Shape<T, kHist>;
   const uint64_t tile_groups = (uint64_t)S::kBlock * S::kUnroll;
   const uint64_t tiles = (n_max / 8 + tile_groups - 1) / tile_groups;
-  uint32_t gx = grid_for_chunks(tiles, S::kChunk, S::kBlock);
-  if (kHist) {  // resident blocks that stride over the chunks: few folds of the LDS bins
-    const uint32_t cap = (uint32_t)compute_units() * 16u;
-    gx = gx < cap ? gx : cap;
-  }
-  const dim3 grid(gx, args.count);
+  const dim3 grid(grid_for_chunks(tiles, S::kChunk, S::kBlock), args.count);
   hipLaunchKernelGGL((enc::encode_kernel<T, W, S::kBlock, S::kUnroll, S::kChunk, kWide, kHist, S::kNT>), grid,
                      dim3(S::kBlock), 0, stream, args);
   return hipGetLastError();

@@ -21,7 +21,7 @@ namespace enc {
 
 // Histogram bins are replicated kHistCopies times in LDS, copy chosen by lane,
 // so that the few hot exponents of a real tensor do not serialise on one bank.
-constexpr int kHistCopies = 8;
+constexpr int kHistCopies = 16;
 
 // 32-bit LDS bins are folded into the 64-bit global bins after this many tiles,
 // long before 2^32 elements have been counted by one block.
@@ -35,8 +35,10 @@ __device__ __forceinline__ void flush_bins(uint32_t* bins, unsigned long long* _
     uint32_t c = 0;
 #pragma unroll
     for (int r = 0; r < kHistCopies; ++r) {
-      c += bins[bin * kHistCopies + r];
-      bins[bin * kHistCopies + r] = 0;
+      // rotate the start so that the lanes of a pass read different banks
+      const int rr = (r + threadIdx.x) & (kHistCopies - 1);
+      c += bins[bin * kHistCopies + rr];
+      bins[bin * kHistCopies + rr] = 0;
     }
     if (c) atomicAdd(&hist[bin], (unsigned long long)c);
   }
