@@ -63,10 +63,12 @@ typedef enum {
   EXMY_ERR_MAX_EXP = 3, /* max_exp outside the range valid for X */
   EXMY_ERR_COUNT = 4,   /* n above EXMY_MAX_ELEMENTS */
   EXMY_ERR_ALIGN = 5,   /* a pointer is not 16-byte aligned */
-  EXMY_ERR_DEVICE = 6   /* the HIP runtime reported an error at launch */
+  EXMY_ERR_DEVICE = 6,  /* the HIP runtime reported an error at launch */
+  EXMY_ERR_BLOCK = 7    /* metadata block size not a multiple of 8 in [8, EXMY_MAX_BLOCK], or too many blocks */
 } exmy_status_t;
 
 #define EXMY_MAX_ELEMENTS ((uint64_t)1 << 40)
+#define EXMY_MAX_BLOCK ((uint64_t)1 << 31)
 
 /* Bytes of the packed form of n elements: ceil(n / 8) * (1 + X + Y)
  * (perfect compression, Section 2.2.2).  Host only; no validation. */
@@ -128,6 +130,46 @@ exmy_status_t exmy_exponent_histogram(const void* src, exmy_dtype_t dt, uint64_t
 /* exmy_encode and exmy_exponent_histogram in one pass over src. */
 exmy_status_t exmy_encode_with_histogram(const void* src, exmy_dtype_t dt, uint64_t n, int X, int Y, int max_exp,
                                          void* dst_packed, uint64_t* hist256_dev, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Per-block metadata (Section 2 "Metadata" and "Block Size"; Section 2.2.1: the
+ * encoded tensor is the codes plus one 8-bit max_exp per block).
+ *
+ * The n elements are cut into consecutive blocks of `block` elements; the last
+ * block may be short; there are exmy_block_count(n, block) of them.  With a
+ * row-major matrix, block = the row length gives per-row (per-channel)
+ * metadata, a divisor of it gives sub-row blocks (e.g. 32 or 64 elements).
+ * `block` is a multiple of 8 in [8, EXMY_MAX_BLOCK], else EXMY_ERR_BLOCK.
+ * Blocks of 8, 16, ..., 512 elements are handled inside flat tiles; any other
+ * block size gets workgroups of its own and is limited to 65535^2 blocks
+ * (EXMY_ERR_BLOCK beyond).
+ *
+ * max_exp_dev is a DEVICE array of one byte per block.  Valid metadata here is
+ * 2^X <= max_exp <= 254 for 1 <= X <= 7 and 1 <= max_exp <= 253 for X = 0 (the
+ * smallest binade of every block is then a normal of the container); bytes
+ * outside are read as the nearest valid value, so no byte is an error.  X = 8
+ * has nothing for a block to choose and is EXMY_ERR_FORMAT here.  The packed
+ * layout is the per-tensor one: block b's codes are groups
+ * [b*block/8, (b+1)*block/8) of every plane.  Results equal the per-tensor
+ * entry points applied to each block with its own max_exp.
+ * Pointers, alignment, n = 0, streams and errors as for exmy_encode. */
+
+/* Number of blocks (bytes of metadata): ceil(n / block); 0 if block = 0.  Host only. */
+size_t exmy_block_count(uint64_t n, uint64_t block);
+
+/* "Maximum exponent before rounding" (Section 2 "Metadata"): max_exp_dev[b] =
+ * the largest biased exponent among the finite elements of block b (0 if none),
+ * brought into the valid range for X given above.  Writes every byte. */
+exmy_status_t exmy_block_max_exp(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X,
+                                 uint8_t* max_exp_dev, void* stream);
+
+/* exmy_encode / exmy_decode / exmy_emulate with block b using max_exp_dev[b]. */
+exmy_status_t exmy_encode_blocks(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
+                                 const uint8_t* max_exp_dev, void* dst_packed, void* stream);
+exmy_status_t exmy_decode_blocks(const void* src_packed, exmy_dtype_t dt_out, uint64_t n, uint64_t block, int X,
+                                 int Y, const uint8_t* max_exp_dev, void* dst, void* stream);
+exmy_status_t exmy_emulate_blocks(void* data_inout, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
+                                  const uint8_t* max_exp_dev, void* stream);
 
 /* Host helper for Section 3.1's technique (keep the top exponents, let the
  * tail go): the smallest biased exponent e in [0, 254] such that at least

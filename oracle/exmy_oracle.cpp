@@ -38,7 +38,11 @@
 //     unpinned by the paper: a convention of this repository);
 //   - X = 8 forces max_exp = 255 (identity exponent map); exponent code 255 is
 //     not produced and decodes to the largest finite value (parity unpinned);
-//   - ragged n (n % 8 != 0) handling is likewise parity unpinned.
+//   - ragged n (n % 8 != 0) handling is likewise parity unpinned;
+//   - per-block metadata: blocks are runs of `block` consecutive elements
+//     (a multiple of 8), the metadatum is the maximum biased exponent of the
+//     block's finite values ("before rounding"), clamped into [2^X, 254]
+//     ([1, 253] for X = 0).
 //
 // Pinned by tests/test_oracle_pins.py and tests/test_oracle_pack.py against the
 // paper's worked examples, library float8 / bfloat16 / float16 conversions and a
@@ -397,6 +401,98 @@ int exmy_oracle_max_exp_from_histogram(const uint64_t* hist256, double coverage)
     if ((double)cum >= coverage * (double)total) return e;
   }
   return 254;
+}
+
+
+// ---------------------------------------------------------------------------
+// Per-block metadata (Section 2 "Metadata", "Block Size"; Section 2.2.1: a tensor
+// of codes plus one 8-bit maximum exponent per block).  The tensor is cut into
+// consecutive blocks of `block` elements (a multiple of 8; a row of a row-major
+// matrix, or a part of one); the last block may be short.  Valid metadata in
+// block mode: 2^X <= max_exp <= 254 for 1 <= X <= 7, 1 <= max_exp <= 253 for
+// X = 0 (so that the smallest binade of every block is a normal of the
+// container); values outside are clamped into that range.  X = 8 has no
+// per-block metadata.
+
+static int block_meta_range(int X, int* lo, int* hi) {
+  if (X < 0 || X > 7) return ORACLE_ERR_FORMAT;
+  *lo = X == 0 ? 1 : (1 << X);
+  *hi = X == 0 ? 253 : 254;
+  return ORACLE_OK;
+}
+
+static int clamp_meta(int m, int lo, int hi) { return m < lo ? lo : (m > hi ? hi : m); }
+
+// "Maximum exponent before rounding": the largest biased exponent among the
+// finite elements of each block, clamped into the valid range.
+int exmy_oracle_block_max_exp(const void* src, int dt, uint64_t n, uint64_t block, int X, uint8_t* max_exp_out) {
+  if ((!src || !max_exp_out) && n) return ORACLE_ERR_NULL;
+  if (dt != ORACLE_F32 && dt != ORACLE_BF16) return ORACLE_ERR_FORMAT;
+  if (block == 0 || block % 8) return ORACLE_ERR_FORMAT;
+  int lo, hi;
+  if (int rc = block_meta_range(X, &lo, &hi)) return rc;
+  const uint64_t nb = (n + block - 1) / block;
+  for (uint64_t b = 0; b < nb; ++b) {
+    int m = 0;
+    for (uint64_t i = b * block; i < std::min(n, (b + 1) * block); ++i) {
+      const int e = (int)((load_bits(src, dt, i) >> 23) & 0xFFu);
+      if (e != 255 && e > m) m = e;
+    }
+    max_exp_out[b] = (uint8_t)clamp_meta(m, lo, hi);
+  }
+  return ORACLE_OK;
+}
+
+// what: 0 = encode (src -> packed), 1 = decode (packed -> dst), 2 = emulate in place (data = src)
+static int blocks_op(int what, const void* src, void* dst, int dt, uint64_t n, uint64_t block, int X, int Y,
+                     const uint8_t* max_exp, int threads) {
+  if (n && (!src || !dst || !max_exp)) return ORACLE_ERR_NULL;
+  if (block == 0 || block % 8) return ORACLE_ERR_FORMAT;
+  int lo, hi;
+  if (int rc = block_meta_range(X, &lo, &hi)) return rc;
+  Format f0;
+  if (int rc = check_format(dt, X, Y, hi, what != 2, &f0)) return rc;
+  const uint64_t nb = (n + block - 1) / block;
+  const int W = 1 + X + Y;
+  std::vector<uint32_t> codes;
+  if (what != 2) codes.resize(n);
+  if (what == 1) unpack_groups((const uint8_t*)src, n, W, codes.data(), 0, 0, (n + 7) / 8);
+  parallel_ranges(nb, threads, [&](uint64_t b0, uint64_t b1) {
+    for (uint64_t b = b0; b < b1; ++b) {
+      Format f;
+      check_format(dt, X, Y, clamp_meta(max_exp[b], lo, hi), what != 2, &f);
+      for (uint64_t i = b * block; i < std::min(n, (b + 1) * block); ++i) {
+        if (what == 0) {
+          codes[i] = encode_one(f, load_bits(src, dt, i));
+        } else if (what == 1) {
+          store_bits(dst, dt, i, decode_one(f, codes[i]));
+        } else {
+          const uint32_t bits = load_bits(src, dt, i);
+          const float x = bits_to_float(bits);
+          if (std::isnan(x) || std::isinf(x)) continue;
+          const float v = (float)code_magnitude(f, magnitude_code(f, std::fabs((double)x)));
+          store_bits(dst, dt, i, float_to_bits(v) | (bits & 0x80000000u));
+        }
+      }
+    }
+  });
+  if (what == 0) pack_groups(codes.data(), 0, n, W, (uint8_t*)dst, 0, (n + 7) / 8);
+  return ORACLE_OK;
+}
+
+int exmy_oracle_encode_blocks(const void* src, int dt, uint64_t n, uint64_t block, int X, int Y,
+                              const uint8_t* max_exp, uint8_t* dst_packed, int threads) {
+  return blocks_op(0, src, dst_packed, dt, n, block, X, Y, max_exp, threads);
+}
+
+int exmy_oracle_decode_blocks(const uint8_t* src_packed, int dt, uint64_t n, uint64_t block, int X, int Y,
+                              const uint8_t* max_exp, void* dst, int threads) {
+  return blocks_op(1, src_packed, dst, dt, n, block, X, Y, max_exp, threads);
+}
+
+int exmy_oracle_emulate_blocks(void* data, int dt, uint64_t n, uint64_t block, int X, int Y, const uint8_t* max_exp,
+                               int threads) {
+  return blocks_op(2, data, data, dt, n, block, X, Y, max_exp, threads);
 }
 
 }  // extern "C"

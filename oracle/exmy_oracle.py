@@ -38,6 +38,10 @@ def lib():
         L.exmy_oracle_decode.argtypes = [vp, i32, u64, i32, i32, i32, vp, i32]
         L.exmy_oracle_emulate.argtypes = [vp, i32, u64, i32, i32, i32, i32]
         L.exmy_oracle_exponent_histogram.argtypes = [vp, i32, u64, vp]
+        L.exmy_oracle_block_max_exp.argtypes = [vp, i32, u64, u64, i32, vp]
+        L.exmy_oracle_encode_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, i32]
+        L.exmy_oracle_decode_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, i32]
+        L.exmy_oracle_emulate_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, i32]
         L.exmy_oracle_max_exp_from_histogram.restype = i32
         L.exmy_oracle_max_exp_from_histogram.argtypes = [vp, dbl]
         _lib = L
@@ -151,3 +155,44 @@ def max_exp_from_histogram(hist, coverage):
     hist = np.ascontiguousarray(hist, dtype=np.uint64)
     assert hist.size == 256
     return int(lib().exmy_oracle_max_exp_from_histogram(_ptr(hist), float(coverage)))
+
+
+# ------------------------------------------------------------ per-block metadata
+
+
+def block_max_exp(src, block, X):
+    a, dt = _src(src)
+    out = np.empty((a.size + block - 1) // block, dtype=np.uint8)
+    _check(lib().exmy_oracle_block_max_exp(_ptr(a), dt, a.size, block, X, _ptr(out)))
+    return out
+
+
+def _meta(max_exp, n, block):
+    m = np.ascontiguousarray(max_exp, dtype=np.uint8)
+    assert m.size == (n + block - 1) // block
+    return m
+
+
+def encode_blocks(src, block, X, Y, max_exp, threads=1):
+    a, dt = _src(src)
+    m = _meta(max_exp, a.size, block)
+    out = np.empty(packed_bytes(a.size, X, Y), dtype=np.uint8)
+    _check(lib().exmy_oracle_encode_blocks(_ptr(a), dt, a.size, block, X, Y, _ptr(m), _ptr(out), threads))
+    return out
+
+
+def decode_blocks(packed, dt, n, block, X, Y, max_exp, threads=1):
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    assert packed.size == packed_bytes(n, X, Y)
+    m = _meta(max_exp, n, block)
+    out = np.empty(n, dtype=_out_dtype(dt))
+    _check(lib().exmy_oracle_decode_blocks(_ptr(packed), dt, n, block, X, Y, _ptr(m), _ptr(out), threads))
+    return out
+
+
+def emulate_blocks(src, block, X, Y, max_exp, threads=1):
+    a, dt = _src(src)
+    m = _meta(max_exp, a.size, block)
+    out = a.copy()
+    _check(lib().exmy_oracle_emulate_blocks(_ptr(out), dt, out.size, block, X, Y, _ptr(m), threads))
+    return out

@@ -8,11 +8,16 @@ from .binding import (  # noqa: F401
     F32,
     Batch,
     ExmyError,
+    block_count,
+    block_max_exp,
     decode,
     decode_batch,
+    decode_blocks,
     emulate,
+    emulate_blocks,
     encode,
     encode_batch,
+    encode_blocks,
     encode_with_histogram,
     exponent_histogram,
     max_exp_from_histogram,

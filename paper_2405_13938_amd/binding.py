@@ -24,6 +24,11 @@ SYMBOLS = [
     "exmy_exponent_histogram",
     "exmy_encode_with_histogram",
     "exmy_max_exp_from_histogram",
+    "exmy_block_count",
+    "exmy_block_max_exp",
+    "exmy_encode_blocks",
+    "exmy_decode_blocks",
+    "exmy_emulate_blocks",
     "exmy_status_string",
 ]
 
@@ -73,6 +78,16 @@ def lib():
         L.exmy_encode_with_histogram.argtypes = [vp, i32, u64, i32, i32, i32, vp, vp, vp]
         L.exmy_max_exp_from_histogram.restype = i32
         L.exmy_max_exp_from_histogram.argtypes = [vp, dbl]
+        L.exmy_block_count.restype = ctypes.c_size_t
+        L.exmy_block_count.argtypes = [u64, u64]
+        L.exmy_block_max_exp.restype = i32
+        L.exmy_block_max_exp.argtypes = [vp, i32, u64, u64, i32, vp, vp]
+        L.exmy_encode_blocks.restype = i32
+        L.exmy_encode_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, vp]
+        L.exmy_decode_blocks.restype = i32
+        L.exmy_decode_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, vp]
+        L.exmy_emulate_blocks.restype = i32
+        L.exmy_emulate_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp]
         L.exmy_status_string.restype = ctypes.c_char_p
         L.exmy_status_string.argtypes = [i32]
         _lib = L
@@ -249,3 +264,73 @@ def max_exp_from_histogram(hist, coverage):
     if h.numel() != 256:
         raise ValueError("exmy: hist must have 256 elements")
     return int(lib().exmy_max_exp_from_histogram(h.data_ptr(), float(coverage)))
+
+
+# ------------------------------------------------------------ per-block metadata
+
+
+def block_count(n, block):
+    return int(lib().exmy_block_count(n, block))
+
+
+def _meta_tensor(meta, n, block, name="max_exps"):
+    _device_tensor(meta, name)
+    if meta.dtype != torch.uint8 or meta.numel() != block_count(n, block):
+        raise ValueError("exmy: %s must be uint8 with %d elements" % (name, block_count(n, block)))
+    return meta
+
+
+def block_max_exp(src, block, X, out=None):
+    """exmy_block_max_exp: returns the uint8 tensor of one max_exp per block."""
+    _device_tensor(src, "src")
+    n = src.numel()
+    if out is None:
+        out = torch.empty(block_count(n, block), dtype=torch.uint8, device=src.device)
+    else:
+        _meta_tensor(out, n, block, "out")
+    _check(lib().exmy_block_max_exp(src.data_ptr(), _dtype_enum(src), n, block, X, out.data_ptr(), _stream()))
+    return out
+
+
+def encode_blocks(src, block, X, Y, max_exps, out=None):
+    """exmy_encode_blocks: returns the packed uint8 tensor (``out`` if given)."""
+    _device_tensor(src, "src")
+    n = src.numel()
+    _meta_tensor(max_exps, n, block)
+    nbytes = packed_bytes(n, X, Y)
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.uint8, device=src.device)
+    else:
+        _device_tensor(out, "out")
+        if out.dtype != torch.uint8 or out.numel() != nbytes:
+            raise ValueError("exmy: out must be uint8 with %d elements" % nbytes)
+    _check(lib().exmy_encode_blocks(src.data_ptr(), _dtype_enum(src), n, block, X, Y, max_exps.data_ptr(),
+                                    out.data_ptr(), _stream()))
+    return out
+
+
+def decode_blocks(packed, dtype, n, block, X, Y, max_exps, out=None):
+    """exmy_decode_blocks: returns a flat tensor of ``n`` values of ``dtype``."""
+    _device_tensor(packed, "packed")
+    _meta_tensor(max_exps, n, block)
+    tdt = _torch_dtype(dtype)
+    if packed.dtype != torch.uint8 or packed.numel() != packed_bytes(n, X, Y):
+        raise ValueError("exmy: packed must be uint8 with %d elements" % packed_bytes(n, X, Y))
+    if out is None:
+        out = torch.empty(n, dtype=tdt, device=packed.device)
+    else:
+        _device_tensor(out, "out")
+        if out.dtype != tdt or out.numel() != n:
+            raise ValueError("exmy: out must be %s with %d elements" % (tdt, n))
+    _check(lib().exmy_decode_blocks(packed.data_ptr(), _dtype_enum(out), n, block, X, Y, max_exps.data_ptr(),
+                                    out.data_ptr(), _stream()))
+    return out
+
+
+def emulate_blocks(data, block, X, Y, max_exps):
+    """exmy_emulate_blocks: in place; returns ``data``."""
+    _device_tensor(data, "data")
+    _meta_tensor(max_exps, data.numel(), block)
+    _check(lib().exmy_emulate_blocks(data.data_ptr(), _dtype_enum(data), data.numel(), block, X, Y,
+                                     max_exps.data_ptr(), _stream()))
+    return data

@@ -102,6 +102,30 @@ exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, bool packe
   return EXMY_OK;
 }
 
+exmy_status_t make_block_format(exmy_dtype_t dt, int X, int Y, bool packed, FormatConsts* fc, BlockConsts* bc) {
+  if (X == 8) return EXMY_ERR_FORMAT;  // identity exponent map: nothing for a block to choose
+  const int hi = X == 0 ? 253 : 254;
+  if (exmy_status_t st = make_format(dt, X, Y, hi, packed, fc, nullptr, nullptr)) return st;
+  if (bc) {
+    const int W = 1 + X + Y;
+    const int L = ((W & 1) ? 32 : 31) - (X + Y);
+    bc->meta_lo = X == 0 ? 1u : (1u << X);
+    bc->meta_hi = (uint32_t)hi;
+    bc->emin_off = (1u << X) - 2u;  // X = 0: 2^0 - 2 = -1, i.e. emin8 = max_exp + 1 (wraps as intended)
+    // largest value: exponent field max_exp; mantissa all ones with X >= 1; with X = 0 it is
+    // (2^Y - 1) quanta = 1.1...1b (Y - 1 ones) * 2^(max_exp - 127)
+    if (X >= 1)
+      bc->sat_mant = (uint32_t)(((1ull << Y) - 1ull) << (23 - Y));
+    else
+      bc->sat_mant = Y >= 1 ? (uint32_t)(((1ull << (Y - 1)) - 1ull) << (24 - Y)) : 0u;
+    bc->sat_mask = (X == 0 && Y == 0) ? 0u : 0xFFFFFFFFu;
+    bc->bias_shift = (uint32_t)((Y + L) & 31);
+    bc->bias_mask = (Y + L) >= 32 ? 0u : 0xFFFFFFFFu;
+    bc->wide_above = (uint32_t)(231 + Y - (X == 0 ? 1 : 0));  // largest clamped exponent is max_exp (+1 for X = 0)
+  }
+  return EXMY_OK;
+}
+
 }  // namespace exmy
 
 using namespace exmy;
@@ -173,6 +197,60 @@ exmy_status_t run_batch(Op op, const exmy_tensor_t* tensors, size_t count, exmy_
   return flush() == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
 }
 
+enum class BlockOp { kMaxExp, kEncode, kDecode, kEmulate };
+
+// Shared validation and launch of the per-block-metadata entry points.  `elems` is
+// the bf16 / fp32 side, `packed` the plane side (unused by kMaxExp and kEmulate).
+exmy_status_t run_blocks(BlockOp op, const void* elems, const void* packed, exmy_dtype_t dt, uint64_t n,
+                         uint64_t block, int X, int Y, const uint8_t* meta, void* stream) {
+  BlockArgs args;
+  const bool is_packed = op == BlockOp::kEncode || op == BlockOp::kDecode;
+  if (exmy_status_t st = make_block_format(dt, X, Y, is_packed, &args.fc, &args.bc)) return st;
+  if (block < 8 || block % 8 || block > EXMY_MAX_BLOCK) return EXMY_ERR_BLOCK;
+  if (n > EXMY_MAX_ELEMENTS) return EXMY_ERR_COUNT;
+  if (n == 0) return EXMY_OK;
+  if (!elems || !meta || (is_packed && !packed)) return EXMY_ERR_NULL;
+  if (!aligned16(elems) || (is_packed && !aligned16(packed))) return EXMY_ERR_ALIGN;
+
+  args.n = n;
+  args.n_blocks = (n + block - 1) / block;
+  args.block_groups = (uint32_t)(block / 8);
+  args.block_groups_log2 = 0;
+  args.meta = const_cast<uint8_t*>(meta);
+  const bool pow2 = (args.block_groups & (args.block_groups - 1)) == 0;
+  const bool rows = !(pow2 && args.block_groups <= kSmallBlockGroups);
+  if (!rows) {
+    while ((1u << args.block_groups_log2) < args.block_groups) ++args.block_groups_log2;
+  } else if (args.n_blocks > kMaxRows) {
+    return EXMY_ERR_BLOCK;
+  }
+  const hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = hipSuccess;
+  switch (op) {
+    case BlockOp::kMaxExp:
+      args.src = elems;
+      args.dst = nullptr;
+      e = block_max_exp_dispatch(dt, args, rows, s);
+      break;
+    case BlockOp::kEncode:
+      args.src = elems;
+      args.dst = const_cast<void*>(packed);
+      e = encode_blocks_dispatch(dt, 1 + X + Y, args, rows, s);
+      break;
+    case BlockOp::kDecode:
+      args.src = packed;
+      args.dst = const_cast<void*>(elems);
+      e = decode_blocks_dispatch(dt, 1 + X + Y, args, rows, s);
+      break;
+    case BlockOp::kEmulate:
+      args.src = elems;
+      args.dst = nullptr;
+      e = emulate_blocks_dispatch(dt, args, rows, Y > 21, s);
+      break;
+  }
+  return e == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
+}
+
 }  // namespace
 
 extern "C" {
@@ -236,6 +314,28 @@ exmy_status_t exmy_exponent_histogram(const void* src, exmy_dtype_t dt, uint64_t
   return e == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
 }
 
+size_t exmy_block_count(uint64_t n, uint64_t block) { return block ? (size_t)((n + block - 1) / block) : 0; }
+
+exmy_status_t exmy_block_max_exp(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X,
+                                 uint8_t* max_exp_dev, void* stream) {
+  return run_blocks(BlockOp::kMaxExp, src, nullptr, dt, n, block, X, 0, max_exp_dev, stream);
+}
+
+exmy_status_t exmy_encode_blocks(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
+                                 const uint8_t* max_exp_dev, void* dst_packed, void* stream) {
+  return run_blocks(BlockOp::kEncode, src, dst_packed, dt, n, block, X, Y, max_exp_dev, stream);
+}
+
+exmy_status_t exmy_decode_blocks(const void* src_packed, exmy_dtype_t dt_out, uint64_t n, uint64_t block, int X, int Y,
+                                 const uint8_t* max_exp_dev, void* dst, void* stream) {
+  return run_blocks(BlockOp::kDecode, dst, src_packed, dt_out, n, block, X, Y, max_exp_dev, stream);
+}
+
+exmy_status_t exmy_emulate_blocks(void* data_inout, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
+                                  const uint8_t* max_exp_dev, void* stream) {
+  return run_blocks(BlockOp::kEmulate, data_inout, nullptr, dt, n, block, X, Y, max_exp_dev, stream);
+}
+
 int exmy_max_exp_from_histogram(const uint64_t* hist256_host, double coverage) {
   if (!hist256_host) return -1;
   uint64_t finite = 0;
@@ -259,6 +359,7 @@ const char* exmy_status_string(exmy_status_t status) {
     case EXMY_ERR_COUNT: return "element count too large";
     case EXMY_ERR_ALIGN: return "pointer not 16-byte aligned";
     case EXMY_ERR_DEVICE: return "HIP launch error";
+    case EXMY_ERR_BLOCK: return "block size not a multiple of 8 in [8, 2^31], or too many blocks";
   }
   return "unknown status";
 }

@@ -60,10 +60,46 @@ struct BatchArgs {
   TensorArgs t[kMaxBatch];
 };
 
+// Per-block metadata (Section 2 "Metadata", "Block Size"): the tensor is cut into
+// consecutive blocks of `block` elements, each with its own 8-bit max_exp held
+// in device memory, so TensorConsts are derived on the device.  BlockConsts is
+// what that derivation needs beyond the metadatum; it depends on (X, Y) only.
+struct BlockConsts {
+  uint32_t meta_lo;     // metadata is clamped into [meta_lo, meta_hi]: [2^X, 254], or [1, 253] for X = 0
+  uint32_t meta_hi;
+  uint32_t emin_off;    // emin8 = max_exp - emin_off (= 2^X - 2)
+  uint32_t sat_mant;    // mantissa field of the largest value
+  uint32_t sat_mask;    // all ones; 0 for e0m0, whose only magnitude is 0
+  uint32_t bias_shift;  // Y + L, taken modulo 32 ...
+  uint32_t bias_mask;   // ... with the result masked to 0 when Y + L = 32
+  uint32_t wide_above;  // metadata above this needs the fp64 rounding path (231 + Y)
+};
+
+// Kernel arguments of the per-block-metadata kernels (one tensor per launch).
+struct BlockArgs {
+  FormatConsts fc;
+  BlockConsts bc;
+  const void* src;      // encode / emulate: elements; decode: packed planes
+  void* dst;            // encode: packed planes; decode: elements; emulate: unused
+  uint8_t* meta;        // one byte per block (read; written by the max-exponent kernel)
+  uint64_t n;           // elements
+  uint64_t n_blocks;    // ceil(n / block)
+  uint32_t block_groups;       // block / 8
+  uint32_t block_groups_log2;  // log2 of it when the lanes of a tile look their block up by shifting
+};
+
+// Blocks of a power-of-two number of groups up to this many (512 elements) are
+// looked up per lane inside flat tiles; every other block size gets workgroups of
+// its own.  Every kernel's tile holds at least this many groups.
+constexpr uint32_t kSmallBlockGroups = 64;
+
 // Host: validate (dtype, X, Y, max_exp) and fill the constants (either may be
 // null).  `packed` applies the W <= 16 limit of the packed form.
 exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, bool packed, FormatConsts* fc,
                           TensorConsts* tc, bool* needs_wide);
+
+// Host: validate (dtype, X, Y) for per-block metadata and fill fc / bc.
+exmy_status_t make_block_format(exmy_dtype_t dt, int X, int Y, bool packed, FormatConsts* fc, BlockConsts* bc);
 
 #if defined(__HIPCC__)
 
@@ -169,6 +205,21 @@ __device__ __forceinline__ uint32_t finish_magnitude(uint32_t g_bits, const Tens
   float r;
   asm("v_min_f32 %0, %1, %2" : "=v"(r) : "v"(g), "v"(t));
   return as_u32(r);
+}
+
+// TensorConsts of a block from its metadata byte (see make_format on the host for
+// the same derivation from a host-side max_exp).
+__device__ __forceinline__ TensorConsts derive_tc(uint32_t max_exp, const BlockConsts& bc) {
+  const uint32_t me = min(max(max_exp, bc.meta_lo), bc.meta_hi);
+  const uint32_t emin8 = me - bc.emin_off;
+  TensorConsts tc;
+  tc.sat_bits = ((me << 23) | bc.sat_mant) & bc.sat_mask;
+  tc.emin_bits = emin8 << 23;
+  tc.bias_left = ((0u - emin8) << bc.bias_shift) & bc.bias_mask;
+  tc.dec_bias = (emin8 - 1u) << 23;  // emin8 >= 2 in block mode: never an fp32-denormal pattern
+  tc.fix_mul = 2.0f;
+  tc.fix_add = as_f32(0x80000000u | (emin8 << 23));  // -2^(emin8-127)
+  return tc;
 }
 
 // ---------------------------------------------------------------- planes

@@ -175,6 +175,14 @@ def f32_edge_sweep(device="cpu", seed=7, n_random=1 << 16):
     return bits.view(torch.float32)
 
 
+def shuffled(t, seed):
+    """The elements of ``t`` (flattened) in a seeded random order, so that
+    neighbouring elements (one metadata block) mix magnitudes."""
+    t = t.reshape(-1)
+    perm = torch.randperm(t.numel(), generator=_gen(seed, "cpu")).to(t.device)
+    return t[perm]
+
+
 def bits_numpy(t):
     """Host numpy view of a tensor's bits in the form the oracle takes:
     float32 for fp32 tensors, uint16 bit patterns for bf16 tensors."""

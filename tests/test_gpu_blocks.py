@@ -1,0 +1,178 @@
+"""Parity of the per-block-metadata entry points (through the C ABI) with the CPU
+oracle, tolerance 0: metadata bytes, packed bytes, decoded and emulated bit patterns."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2405_13938_amd as exmy
+from oracle import exmy_oracle as O
+from paper_2405_13938_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+THREADS = min(O.default_threads(), 16)
+
+
+def odt(t):
+    return O.F32 if t.dtype == torch.float32 else O.BF16
+
+
+def ubits(a):
+    return a.view(np.uint32) if a.dtype == np.float32 else a
+
+
+def tbits(t):
+    return ubits(synth.bits_numpy(t))
+
+
+def formats_of_width(W, dtype):
+    P = 23 if dtype == torch.float32 else 7
+    return [(X, W - 1 - X) for X in range(0, min(W - 1, 7) + 1) if W - 1 - X <= (P if X >= 1 else P + 1)]
+
+
+def metadata(kind, host, block, X, seed=0):
+    nb = (host.size + block - 1) // block
+    if kind == "before_rounding":
+        return O.block_max_exp(host, block, X)
+    rng = np.random.default_rng(seed + block)
+    if kind == "any_byte":  # out-of-range bytes, and ones that need the fp64 rounding path, included
+        return rng.integers(0, 256, nb).astype(np.uint8)
+    if kind == "near_before_rounding":  # the block maximum, moved by up to two binades either way
+        m = O.block_max_exp(host, block, X).astype(np.int64) + rng.integers(-2, 3, nb)
+        return np.clip(m, 0, 255).astype(np.uint8)
+    raise ValueError(kind)
+
+
+def check_blocks(x_dev, block, X, Y, kind, host=None, what=("max", "encode", "decode", "emulate"), seed=0):
+    x_dev = x_dev.reshape(-1)
+    n = x_dev.numel()
+    if host is None:
+        host = synth.bits_numpy(x_dev)
+    dt = odt(x_dev)
+    label = "e%dm%d block=%d n=%d %s %s" % (X, Y, block, n, x_dev.dtype, kind)
+    if "max" in what:
+        got = exmy.block_max_exp(x_dev, block, X)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy(), O.block_max_exp(host, block, X)), "block_max_exp " + label
+    meta = metadata(kind, host, block, X, seed)
+    meta_dev = torch.from_numpy(meta).to(DEV)
+    if 1 + X + Y <= 16 and ("encode" in what or "decode" in what):
+        want_packed = O.encode_blocks(host, block, X, Y, meta, threads=THREADS)
+        if "encode" in what:
+            got = exmy.encode_blocks(x_dev, block, X, Y, meta_dev)
+            torch.cuda.synchronize()
+            assert np.array_equal(got.cpu().numpy(), want_packed), "encode_blocks " + label
+        if "decode" in what:
+            pd = torch.from_numpy(want_packed).to(DEV)
+            got = exmy.decode_blocks(pd, x_dev.dtype, n, block, X, Y, meta_dev)
+            torch.cuda.synchronize()
+            want = O.decode_blocks(want_packed, dt, n, block, X, Y, meta, threads=THREADS)
+            assert np.array_equal(tbits(got), ubits(want)), "decode_blocks " + label
+    if "emulate" in what:
+        got = exmy.emulate_blocks(x_dev.clone(), block, X, Y, meta_dev)
+        torch.cuda.synchronize()
+        want = O.emulate_blocks(host, block, X, Y, meta, threads=THREADS)
+        assert np.array_equal(tbits(got), ubits(want)), "emulate_blocks " + label
+
+
+SMALL_BLOCKS = [8, 16, 32, 64, 128, 256, 512]  # looked up per lane inside flat tiles
+ROW_BLOCKS = [24, 520, 1024, 4096, 11008]      # workgroups of their own
+
+
+@pytest.mark.parametrize("W", range(1, 17))
+def test_every_bf16_pattern_every_width(W):
+    # all 65536 bf16 bit patterns (shuffled, so every block mixes binades), every (X, Y) of the width,
+    # one small and one row block size per format, metadata of every kind
+    x = synth.shuffled(synth.all_bf16_patterns(), W).to(DEV)
+    host = synth.bits_numpy(x)
+    for i, (X, Y) in enumerate(formats_of_width(W, torch.bfloat16)):
+        sb = SMALL_BLOCKS[(W + i) % len(SMALL_BLOCKS)]
+        rb = ROW_BLOCKS[(W + i) % len(ROW_BLOCKS)]
+        check_blocks(x, sb, X, Y, "any_byte", host, seed=i)
+        check_blocks(x, rb, X, Y, "any_byte", host, seed=i)
+        check_blocks(x, sb, X, Y, "before_rounding", host, what=("encode", "decode", "emulate"))
+        check_blocks(x, rb, X, Y, "near_before_rounding", host, what=("encode", "decode", "emulate"))
+
+
+@pytest.mark.parametrize("W", range(1, 17))
+def test_fp32_sweep_every_width(W):
+    x = synth.shuffled(synth.f32_edge_sweep(seed=W), W).to(DEV)
+    host = synth.bits_numpy(x)
+    for i, (X, Y) in enumerate(formats_of_width(W, torch.float32)):
+        sb = SMALL_BLOCKS[(W + i + 3) % len(SMALL_BLOCKS)]
+        rb = ROW_BLOCKS[(W + i + 2) % len(ROW_BLOCKS)]
+        check_blocks(x, sb, X, Y, "any_byte", host, seed=i)
+        check_blocks(x, rb, X, Y, "any_byte", host, seed=i)
+        check_blocks(x, rb, X, Y, "before_rounding", host, what=("encode", "decode", "emulate"))
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_emulate_only_formats(dtype):
+    # wider than the packed form allows, fp64 rounding path for the whole format (Y > 21) included
+    x = synth.shuffled(synth.f32_edge_sweep(seed=3) if dtype == torch.float32 else synth.all_bf16_patterns(), 3).to(DEV)
+    host = synth.bits_numpy(x)
+    fmts = [(7, 7), (5, 7), (0, 8)] if dtype == torch.bfloat16 else [(7, 23), (2, 22), (4, 21), (0, 24), (7, 12), (3, 20)]
+    for X, Y in fmts:
+        for block in (32, 512, 1000, 4096):
+            for kind in ("any_byte", "before_rounding"):
+                check_blocks(x, block, X, Y, kind, host, what=("emulate",))
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("block", [8, 32, 512, 24, 4096])
+def test_every_block_size_at_ragged_lengths(dtype, block):
+    # lengths around multiples of the block, of the group of 8 and of the kernels' tiles
+    g = torch.Generator().manual_seed(block)
+    lengths = sorted({1, 3, 7, 8, 9, 15, 17, block - 1, block, block + 1, block + 8, 2 * block + 5, 3 * block - 3,
+                      1023, 1025, 2047, 2048 + 4, 4096 + 12, 5 * 4096 + 8 * 7 + 3, 33 * 1024 + 1})
+    for n in lengths:
+        x = (torch.randn(n, generator=g) * torch.exp2(torch.randint(-10, 10, (n,), generator=g).float())).to(dtype).to(DEV)
+        for X, Y in ((3, 3), (2, 1), (0, 4)):
+            check_blocks(x, block, X, Y, "near_before_rounding", seed=n)
+
+
+def test_no_finite_value_in_a_block_and_empty_input():
+    x = torch.randn(4096).to(torch.bfloat16)
+    x[64:128] = float("nan")
+    x[128:192] = float("inf")
+    x[192:256] = 0.0
+    x[256:320] = 1e-40  # below the normals of the container (flushes to 0 in bf16; kept tiny in fp32)
+    for dtype in (torch.bfloat16, torch.float32):
+        xd = x.to(dtype).to(DEV)
+        for block in (64, 1024):
+            check_blocks(xd, block, 3, 2, "before_rounding")
+        empty = torch.empty(0, dtype=dtype, device=DEV)
+        meta = torch.empty(0, dtype=torch.uint8, device=DEV)
+        assert exmy.block_max_exp(empty, 32, 3).numel() == 0
+        assert exmy.encode_blocks(empty, 32, 3, 3, meta).numel() == 0
+        assert exmy.decode_blocks(torch.empty(0, dtype=torch.uint8, device=DEV), dtype, 0, 32, 3, 3, meta).numel() == 0
+        assert exmy.emulate_blocks(empty, 32, 3, 3, meta).numel() == 0
+
+
+@pytest.mark.parametrize("block", [64, 4096, 11008])
+def test_weight_matrix_rows_and_sub_rows(block):
+    # Section 4.1: one metadatum per row of the weight matrix, or per sub-row block
+    x = synth.gaussian_bf16(1024 * 11008 if block == 11008 else 4096 * 4096, seed=block).to(DEV)
+    host = synth.bits_numpy(x)
+    for X, Y in ((3, 2), (2, 1), (1, 2)):
+        check_blocks(x, block, X, Y, "before_rounding", host)
+
+
+def test_more_rows_than_one_grid_dimension():
+    # 70000 rows of 1024: the row index spans grid y and z
+    x = synth.gaussian_bf16(70000 * 1024 + 100, seed=17).to(DEV)
+    check_blocks(x, 1024, 3, 3, "before_rounding")
+
+
+def test_uniform_metadata_equals_per_tensor_entry_points():
+    x = synth.gaussian_bf16(1 << 20, seed=4).to(DEV)
+    for block in (32, 4096):
+        meta = torch.full((exmy.block_count(x.numel(), block),), 127, dtype=torch.uint8, device=DEV)
+        a = exmy.encode_blocks(x, block, 3, 3, meta)
+        b = exmy.encode(x, 3, 3, 127)
+        assert torch.equal(a, b)
+        assert torch.equal(exmy.decode_blocks(a, torch.bfloat16, x.numel(), block, 3, 3, meta).view(torch.int16),
+                           exmy.decode(b, torch.bfloat16, x.numel(), 3, 3, 127).view(torch.int16))
+        assert torch.equal(exmy.emulate_blocks(x.clone(), block, 3, 3, meta).view(torch.int16),
+                           exmy.emulate(x.clone(), 3, 3, 127).view(torch.int16))

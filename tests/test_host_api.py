@@ -112,3 +112,39 @@ def test_cpu_tensors_are_rejected():
         B.encode(torch.zeros(8), 3, 3, 130)
     with pytest.raises(TypeError):
         B._dtype_enum(torch.zeros(8, dtype=torch.float16))
+
+
+def test_block_entry_points_validate_without_launch():
+    L = B.lib()
+    ok, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1008)
+    for n, block in ((0, 8), (1, 8), (100, 32), (4096, 4096), (4097, 4096)):
+        assert B.block_count(n, block) == (n + block - 1) // block
+    assert B.block_count(5, 0) == 0
+    enc = lambda *a: L.exmy_encode_blocks(*a)
+    assert enc(ok, B.BF16, 0, 32, 3, 3, ok, ok, None) == 0  # n = 0: nothing to do
+    assert enc(None, B.BF16, 64, 32, 3, 3, ok, ok, None) == 1
+    assert enc(ok, B.BF16, 64, 32, 3, 3, None, ok, None) == 1
+    assert enc(ok, B.BF16, 64, 32, 3, 3, ok, None, None) == 1
+    assert enc(odd, B.BF16, 64, 32, 3, 3, ok, ok, None) == 5
+    assert enc(ok, B.BF16, 64, 32, 3, 3, ok, odd, None) == 5
+    assert enc(ok, B.BF16, 64, 32, 8, 3, ok, ok, None) == 2  # X = 8 has no per-block metadata
+    assert enc(ok, B.BF16, 64, 32, 3, 8, ok, ok, None) == 2  # bf16 holds 7 mantissa bits
+    assert enc(ok, B.F32, 64, 32, 3, 13, ok, ok, None) == 2  # packed form stops at 16 bits
+    for block in (0, 4, 12, 33, (1 << 31) + 8, 1 << 32):
+        assert enc(ok, B.BF16, 64, block, 3, 3, ok, ok, None) == 7
+        assert L.exmy_block_max_exp(ok, B.BF16, 64, block, 3, ok, None) == 7
+        assert L.exmy_decode_blocks(ok, B.BF16, 64, block, 3, 3, ok, ok, None) == 7
+        assert L.exmy_emulate_blocks(ok, B.BF16, 64, block, 3, 3, ok, None) == 7
+    assert enc(ok, B.BF16, (1 << 40) + 1, 32, 3, 3, ok, ok, None) == 4
+    # more row-mode blocks than the two grid dimensions hold
+    assert enc(ok, B.BF16, 1 << 40, 24, 3, 3, ok, ok, None) == 7
+    assert L.exmy_emulate_blocks(ok, B.F32, 0, 32, 2, 22, ok, None) == 0  # emulation has no width limit
+    assert L.exmy_emulate_blocks(None, B.F32, 8, 32, 2, 22, ok, None) == 1
+    assert L.exmy_block_max_exp(ok, B.F32, 8, 8, 9, ok, None) == 2
+    assert L.exmy_block_max_exp(ok, B.F32, 8, 8, 3, None, None) == 1
+    assert B.status_string(7).startswith("block size")
+    # the oracle rejects the same block sizes and X = 8
+    x = np.zeros(64, dtype=np.float32)
+    for block in (0, 4, 12, 33):
+        with pytest.raises(Exception):
+            O.block_max_exp(x, block, 3)

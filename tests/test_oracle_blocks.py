@@ -1,0 +1,142 @@
+"""Pins of the CPU oracle's per-block-metadata functions: the paper's printed
+block-dependent outcomes, a numpy definition of the block maximum exponent, and
+reduction to the (separately pinned) per-tensor functions block by block."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import exmy_oracle as O
+from paper_2405_13938_amd import synth
+
+F32, BF16 = O.F32, O.BF16
+
+
+def as_np(t):
+    return synth.bits_numpy(t)
+
+
+def test_block_outcomes_e2m1(golden):
+    # Section 2.1: outcomes (a)-(d) for one input value, by its block's maximum
+    rows = golden("e2m1_block_outcomes.txt")
+    block = 16
+    for dtype in (torch.float32, torch.bfloat16):
+        vals = torch.zeros(len(rows) * block, dtype=torch.float32)
+        for r, (v, bmax, _, _) in enumerate(rows):
+            vals[r * block + 5] = float(v)
+            vals[r * block + 11] = float(bmax)
+        x = vals.to(dtype)
+        me = O.block_max_exp(as_np(x), block, 2)
+        out = O.emulate_blocks(as_np(x), block, 2, 1, me)
+        out_t = torch.from_numpy(out.view(np.int16 if dtype == torch.bfloat16 else np.int32)).view(dtype).float()
+        for r, (v, bmax, want, _) in enumerate(rows):
+            got = out_t[r * block + 5].item()
+            assert got == float(want), (dtype, v, bmax, got, want)
+            # the block maximum itself (a power of two times 1 or 1.25) lands on the grid's top binade
+            assert abs(out_t[r * block + 11].item()) <= 1.5 * 2 ** np.floor(np.log2(abs(float(bmax))))
+
+
+def test_staircase_one_step_per_binade():
+    # Section 2.1: with e2m1 there is one step between consecutive powers of two
+    g = torch.Generator().manual_seed(5)
+    x = (torch.rand(1 << 14, generator=g) * 3.0 + 1.0).float()  # [1, 4): top two binades of blocks whose max is in [2, 4)
+    x[::16] = 3.5  # every block's maximum exponent is that of 2^1
+    me = O.block_max_exp(as_np(x), 16, 2)
+    assert (me == 128).all()
+    out = torch.from_numpy(O.emulate_blocks(as_np(x), 16, 2, 1, me).view(np.float32))
+    assert sorted(set(out.tolist())) == [1.0, 1.5, 2.0, 3.0]
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("block,X", [(8, 0), (16, 2), (32, 4), (40, 3), (4096, 5), (1 << 20, 7)])
+def test_block_max_exp_definition(dtype, block, X):
+    g = torch.Generator().manual_seed(100 + block + X)
+    n = 3 * 4096 + 1234
+    # exponents spread over the whole fp32 range, with zeros, denormals, Inf and NaN mixed in
+    x = torch.randn(n, generator=g) * torch.exp2(torch.randint(-140, 128, (n,), generator=g).float())
+    x[torch.rand(n, generator=g) < 0.05] = 0.0
+    x[torch.rand(n, generator=g) < 0.02] = float("inf")
+    x[torch.rand(n, generator=g) < 0.02] = float("nan")
+    x[torch.rand(n, generator=g) < 0.02] = 1e-41
+    x[block: 2 * block] = float("nan") if n >= 2 * block else x[block: 2 * block]  # a block with no finite value
+    x = x.to(dtype)
+    got = O.block_max_exp(as_np(x), block, X)
+    # definition: floor(log2 |x|) + 127 of the largest finite magnitude, 0 below the normals
+    v = x.double().numpy()
+    v = np.where(np.isfinite(v), np.abs(v), 0.0)
+    nb = (n + block - 1) // block
+    lo, hi = (1, 253) if X == 0 else (1 << X, 254)
+    want = np.empty(nb, dtype=np.uint8)
+    for b in range(nb):
+        m = v[b * block: (b + 1) * block].max()
+        _, e = np.frexp(m)  # m = f * 2^e, f in [0.5, 1)
+        biased = int(e) - 1 + 127 if m >= 2.0 ** -126 else 0
+        want[b] = min(max(biased, lo), hi)
+    assert np.array_equal(got, want)
+
+
+def per_block_reference(x_np, dt, n, block, X, Y, meta):
+    """Codes from the per-tensor oracle applied to each block with its own metadatum."""
+    lo, hi = (1, 253) if X == 0 else (1 << X, 254)
+    codes = np.empty(n, dtype=np.uint32)
+    for b in range((n + block - 1) // block):
+        s = slice(b * block, min(n, (b + 1) * block))
+        codes[s] = O.to_codes(x_np[s], X, Y, int(min(max(int(meta[b]), lo), hi)))
+    return codes
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("X,Y,block", [(2, 1, 16), (3, 3, 32), (1, 2, 64), (0, 3, 8), (4, 3, 24), (3, 2, 4096),
+                                       (5, 2, 520), (2, 3, 512), (7, 0, 1024), (0, 0, 8), (4, 7, 128)])
+def test_blocks_reduce_to_per_tensor_functions(dtype, X, Y, block):
+    g = torch.Generator().manual_seed(1000 * X + 10 * Y + block)
+    n = 5 * block + 8 * 3 + 5 if block <= 1024 else 2 * block + 77
+    x = torch.randn(n, generator=g) * torch.exp2(torch.randint(-12, 6, (n,), generator=g).float())
+    x[::97] = float("inf")
+    x[::89] = float("-inf")
+    x[::83] = float("nan")
+    x = x.to(dtype)
+    xn = as_np(x)
+    dt = F32 if dtype == torch.float32 else BF16
+    nb = (n + block - 1) // block
+    for kind in ("before_rounding", "random_bytes"):
+        if kind == "before_rounding":
+            meta = O.block_max_exp(xn, block, X)
+        else:  # any byte is accepted and read as the nearest valid metadatum
+            meta = np.random.default_rng(block).integers(0, 256, nb).astype(np.uint8)
+        codes = per_block_reference(xn, dt, n, block, X, Y, meta)
+        packed = O.encode_blocks(xn, block, X, Y, meta)
+        assert np.array_equal(packed, O.pack(codes, 1 + X + Y))
+        # decode: per block through the per-tensor function
+        dec = O.decode_blocks(packed, dt, n, block, X, Y, meta)
+        lo, hi = (1, 253) if X == 0 else (1 << X, 254)
+        for b in range(nb):
+            s = slice(b * block, min(n, (b + 1) * block))
+            want = O.from_codes(codes[s], dt, X, Y, int(min(max(int(meta[b]), lo), hi)))
+            assert np.array_equal(dec[s].view(np.uint8), want.view(np.uint8))
+        # emulate = decode(encode) away from Inf / NaN, which stay bit-identical
+        emu = O.emulate_blocks(xn, block, X, Y, meta)
+        fin = torch.isfinite(x.float()).numpy()
+        u = np.uint32 if dtype == torch.float32 else np.uint16
+        assert np.array_equal(emu.view(u)[fin], dec.view(u)[fin])
+        assert np.array_equal(emu.view(u)[~fin], xn.view(u)[~fin])
+
+
+def test_uniform_metadata_equals_per_tensor():
+    x = synth.gaussian_bf16(40000, seed=9)
+    xn = as_np(x)
+    for X, Y, me in [(3, 3, 127), (2, 1, 129), (0, 4, 126)]:
+        meta = np.full((xn.size + 63) // 64, me, dtype=np.uint8)
+        assert np.array_equal(O.encode_blocks(xn, 64, X, Y, meta), O.encode(xn, X, Y, me))
+
+
+def test_block_validation():
+    x = as_np(torch.zeros(64))
+    meta = np.zeros(8, dtype=np.uint8)
+    with pytest.raises(Exception):
+        O.block_max_exp(x, 12, 3)  # not a multiple of 8
+    with pytest.raises(Exception):
+        O.block_max_exp(x, 8, 8)  # X = 8 has no per-block metadata
+    with pytest.raises(Exception):
+        O.encode_blocks(x, 0, 3, 3, meta)
+    with pytest.raises(Exception):
+        O.encode_blocks(x, 8, 8, 3, meta)
