@@ -64,7 +64,7 @@ typedef enum {
   EXMY_ERR_COUNT = 4,   /* n above EXMY_MAX_ELEMENTS */
   EXMY_ERR_ALIGN = 5,   /* a pointer is not 16-byte aligned */
   EXMY_ERR_DEVICE = 6,  /* the HIP runtime reported an error at launch */
-  EXMY_ERR_BLOCK = 7    /* metadata block size not a multiple of 8 in [8, EXMY_MAX_BLOCK], or too many blocks */
+  EXMY_ERR_BLOCK = 7    /* metadata block size not a multiple of 8 in [8, EXMY_MAX_BLOCK] */
 } exmy_status_t;
 
 #define EXMY_MAX_ELEMENTS ((uint64_t)1 << 40)
@@ -141,8 +141,8 @@ exmy_status_t exmy_encode_with_histogram(const void* src, exmy_dtype_t dt, uint6
  * metadata, a divisor of it gives sub-row blocks (e.g. 32 or 64 elements).
  * `block` is a multiple of 8 in [8, EXMY_MAX_BLOCK], else EXMY_ERR_BLOCK.
  * Blocks of 8, 16, ..., 512 elements are handled inside flat tiles; any other
- * block size gets workgroups of its own and is limited to 65535^2 blocks
- * (EXMY_ERR_BLOCK beyond).
+ * block size gets workgroups of its own (fastest when a block is a few thousand
+ * elements or more).
  *
  * max_exp_dev is a DEVICE array of one byte per block.  Valid metadata here is
  * 2^X <= max_exp <= 254 for 1 <= X <= 7 and 1 <= max_exp <= 253 for X = 0 (the

@@ -215,37 +215,30 @@ exmy_status_t run_blocks(BlockOp op, const void* elems, const void* packed, exmy
   args.n = n;
   args.n_blocks = (n + block - 1) / block;
   args.block_groups = (uint32_t)(block / 8);
-  args.block_groups_log2 = 0;
+  args.bi = make_block_index(args.block_groups);  // dispatchers rescale it to their kernel's units
   args.meta = const_cast<uint8_t*>(meta);
-  const bool pow2 = (args.block_groups & (args.block_groups - 1)) == 0;
-  const bool rows = !(pow2 && args.block_groups <= kSmallBlockGroups);
-  if (!rows) {
-    while ((1u << args.block_groups_log2) < args.block_groups) ++args.block_groups_log2;
-  } else if (args.n_blocks > kMaxRows) {
-    return EXMY_ERR_BLOCK;
-  }
   const hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = hipSuccess;
   switch (op) {
     case BlockOp::kMaxExp:
       args.src = elems;
       args.dst = nullptr;
-      e = block_max_exp_dispatch(dt, args, rows, s);
+      e = block_max_exp_dispatch(dt, args, s);
       break;
     case BlockOp::kEncode:
       args.src = elems;
       args.dst = const_cast<void*>(packed);
-      e = encode_blocks_dispatch(dt, 1 + X + Y, args, rows, s);
+      e = encode_blocks_dispatch(dt, 1 + X + Y, args, s);
       break;
     case BlockOp::kDecode:
       args.src = packed;
       args.dst = const_cast<void*>(elems);
-      e = decode_blocks_dispatch(dt, 1 + X + Y, args, rows, s);
+      e = decode_blocks_dispatch(dt, 1 + X + Y, args, s);
       break;
     case BlockOp::kEmulate:
       args.src = elems;
       args.dst = nullptr;
-      e = emulate_blocks_dispatch(dt, args, rows, Y > 21, s);
+      e = emulate_blocks_dispatch(dt, args, Y > 21, s);
       break;
   }
   return e == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
@@ -359,7 +352,7 @@ const char* exmy_status_string(exmy_status_t status) {
     case EXMY_ERR_COUNT: return "element count too large";
     case EXMY_ERR_ALIGN: return "pointer not 16-byte aligned";
     case EXMY_ERR_DEVICE: return "HIP launch error";
-    case EXMY_ERR_BLOCK: return "block size not a multiple of 8 in [8, 2^31], or too many blocks";
+    case EXMY_ERR_BLOCK: return "block size not a multiple of 8 in [8, 2^31]";
   }
   return "unknown status";
 }

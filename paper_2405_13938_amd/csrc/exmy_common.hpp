@@ -75,23 +75,49 @@ struct BlockConsts {
   uint32_t wide_above;  // metadata above this needs the fp64 rounding path (231 + Y)
 };
 
+// How a kernel finds the metadata block of a piece of work.  Work is counted in
+// the kernel's own units (groups of 8 elements, or 16-byte vectors); a block is
+// `size` of them.  Tiles run flat over the tensor and may straddle blocks: the
+// tile's first block and its offset inside it are wave-uniform (a shift for
+// power-of-two sizes, else a multiplication by recip64 = ceil(2^64 / size), exact
+// for every offset below 2^37); a lane then adds the blocks that start between
+// the tile's first unit and its own.
+struct BlockIndex {
+  uint32_t size;     // units per block
+  uint32_t log2;     // log2(size) if a power of two, else kNotPow2
+  uint64_t recip64;  // ceil(2^64 / size); unused for powers of two
+  uint32_t recip32;  // floor(2^32 / size) + 1: (j * recip32) >> 32 = j / size for j * size < 2^32
+};
+constexpr uint32_t kNotPow2 = 0xFFFFFFFFu;
+
 // Kernel arguments of the per-block-metadata kernels (one tensor per launch).
 struct BlockArgs {
   FormatConsts fc;
   BlockConsts bc;
+  BlockIndex bi;        // in the launched kernel's units (set by its dispatcher)
   const void* src;      // encode / emulate: elements; decode: packed planes
   void* dst;            // encode: packed planes; decode: elements; emulate: unused
   uint8_t* meta;        // one byte per block (read; written by the max-exponent kernel)
   uint64_t n;           // elements
   uint64_t n_blocks;    // ceil(n / block)
-  uint32_t block_groups;       // block / 8
-  uint32_t block_groups_log2;  // log2 of it when the lanes of a tile look their block up by shifting
+  uint32_t block_groups;  // block / 8
 };
 
-// Blocks of a power-of-two number of groups up to this many (512 elements) are
-// looked up per lane inside flat tiles; every other block size gets workgroups of
-// its own.  Every kernel's tile holds at least this many groups.
-constexpr uint32_t kSmallBlockGroups = 64;
+inline BlockIndex make_block_index(uint64_t size) {
+  BlockIndex bi;
+  bi.size = (uint32_t)size;
+  bi.log2 = kNotPow2;
+  bi.recip64 = 0;
+  bi.recip32 = 0;
+  if ((size & (size - 1)) == 0) {
+    bi.log2 = 0;
+    while ((1ull << bi.log2) < size) ++bi.log2;
+  } else {
+    bi.recip64 = ~0ull / size + 1;  // size is not a power of two: this is ceil(2^64 / size)
+    bi.recip32 = (uint32_t)(0xFFFFFFFFull / size + 1);
+  }
+  return bi;
+}
 
 // Host: validate (dtype, X, Y, max_exp) and fill the constants (either may be
 // null).  `packed` applies the W <= 16 limit of the packed form.
@@ -220,6 +246,26 @@ __device__ __forceinline__ TensorConsts derive_tc(uint32_t max_exp, const BlockC
   tc.fix_mul = 2.0f;
   tc.fix_add = as_f32(0x80000000u | (emin8 << 23));  // -2^(emin8-127)
   return tc;
+}
+
+// First block touched by the tile whose first unit is w0, and w0's offset inside it.
+__device__ __forceinline__ void tile_first_block(uint64_t w0, const BlockIndex& bi, uint64_t& blk0, uint32_t& off) {
+  if (bi.log2 != kNotPow2) {
+    blk0 = w0 >> bi.log2;
+    off = (uint32_t)w0 & (bi.size - 1u);
+  } else {
+    blk0 = __umul64hi(w0, bi.recip64);
+    off = (uint32_t)(w0 - blk0 * bi.size);
+  }
+}
+
+// Block of the unit j = off + (the lane's unit inside the tile), relative to the
+// tile's first block.  kTile = units per tile.
+template <uint32_t kTile>
+__device__ __forceinline__ uint32_t lane_block(uint32_t j, const BlockIndex& bi) {
+  if (bi.log2 != kNotPow2) return j >> bi.log2;
+  if (bi.size >= kTile) return j >= bi.size ? 1u : 0u;  // a tile straddles at most one boundary
+  return __umulhi(j, bi.recip32);                       // j < 2 * kTile
 }
 
 // ---------------------------------------------------------------- planes

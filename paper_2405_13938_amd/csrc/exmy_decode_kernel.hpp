@@ -226,79 +226,63 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(const BatchArgs batch) {
 }
 
 // ---------------------------------------------------------------------------
-// Per-block metadata: see the encoder for the two launch modes.  A unit is one
-// lane's 16 bytes of output (E elements); blocks hold block_groups * 8 / E units.
+// Per-block metadata: flat tiles with a per-lane metadata lookup, as in the
+// encoder.  A unit is one lane's 16 bytes of output (E elements).
 
-template <typename T, int W, int kBlock, int kUnroll, bool kRows, bool kNT>
+template <typename T, int W, int kBlock, int kUnroll, bool kNT>
 __global__ __launch_bounds__(kBlock) void decode_blocks_kernel(const BlockArgs args) {
   constexpr uint32_t TU = kBlock * kUnroll;
   constexpr int E = 16 / sizeof(T);
-  constexpr int kUnitsPerGroupLog2 = sizeof(T) == 4 ? 1 : 0;
   const uint8_t* __restrict__ src = static_cast<const uint8_t*>(args.src);
   T* __restrict__ dst = static_cast<T*>(args.dst);
   const uint8_t* __restrict__ meta = args.meta;
   const uint64_t n = args.n;
   const FormatConsts fc = args.fc;
   const BlockConsts bc = args.bc;
+  const BlockIndex bi = args.bi;  // in units
   const uint64_t G = (n + 7) / 8;
   const uint64_t Ufull = n / E;
+  const uint32_t full_tiles = (uint32_t)(Ufull / TU);
+  const uint32_t rem_units = (uint32_t)(Ufull - (uint64_t)full_tiles * TU);
+  const uint32_t tiles = full_tiles + (rem_units ? 1u : 0u);
 
-  if constexpr (kRows) {
-    const uint64_t row = blockIdx.y + (uint64_t)blockIdx.z * gridDim.y;
-    if (row >= args.n_blocks) return;
-    const TensorConsts tc = derive_tc(__builtin_amdgcn_readfirstlane((uint32_t)meta[row]), bc);
-    const uint32_t block_units = args.block_groups << kUnitsPerGroupLog2;
-    const uint64_t row_u0 = row * block_units;
-    const uint64_t left = Ufull - row_u0;
-    const uint32_t row_units = left < block_units ? (uint32_t)left : block_units;
-    const uint32_t full_tiles = row_units / TU;
-    const uint32_t rem_units = row_units - full_tiles * TU;
-    const uint32_t tiles = full_tiles + (rem_units ? 1u : 0u);
-    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-      const uint64_t u0 = row_u0 + (uint64_t)tile * TU;  // even: rows hold whole groups
-      PlaneSrc<W> ps;
-      make_plane_src<W, E>(src, G, u0, ps);
-      const rsrc_t out = make_rsrc(reinterpret_cast<uint4*>(dst) + u0);
-      TileWords<W, kUnroll> tw;
-      if (tile < full_tiles) {
-        load_tile<W, E, kBlock, kUnroll, false>(ps, 0, 0, tw);
-        decode_tile<T, W, kBlock, kUnroll, false, kNT, false>(tw, out, 0, 0, fc, tc);
-      } else {
-        load_tile<W, E, kBlock, kUnroll, true>(ps, 0, rem_units, tw);
-        decode_tile<T, W, kBlock, kUnroll, false, kNT, true>(tw, out, 0, rem_units, fc, tc);
-      }
-    }
-  } else {
-    const uint32_t lg = args.block_groups_log2 + kUnitsPerGroupLog2;  // log2 of units per block
-    const uint32_t full_tiles = (uint32_t)(Ufull / TU);
-    const uint32_t rem_units = (uint32_t)(Ufull - (uint64_t)full_tiles * TU);
-    const uint32_t tiles = full_tiles + (rem_units ? 1u : 0u);
-    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-      const uint64_t u0 = (uint64_t)tile * TU;  // a multiple of the block size in units
-      PlaneSrc<W> ps;
-      make_plane_src<W, E>(src, G, u0, ps);
-      const rsrc_t out = make_rsrc(reinterpret_cast<uint4*>(dst) + u0);
-      const rsrc_t mt = make_rsrc(meta + (u0 >> lg));
-      const uint32_t rem = tile < full_tiles ? TU : rem_units;
-      TileWords<W, kUnroll> tw;
-      uint32_t me[kUnroll];
-      load_tile<W, E, kBlock, kUnroll, true>(ps, 0, rem, tw);
+  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const uint64_t u0 = (uint64_t)tile * TU;  // even
+    uint64_t blk0;
+    uint32_t off;
+    tile_first_block(u0, bi, blk0, off);
+    PlaneSrc<W> ps;
+    make_plane_src<W, E>(src, G, u0, ps);
+    const rsrc_t out = make_rsrc(reinterpret_cast<uint4*>(dst) + u0);
+    const rsrc_t mt = make_rsrc(meta + blk0);
+    TileWords<W, kUnroll> tw;
+    uint32_t me[kUnroll];
+    if (tile < full_tiles) {
+      load_tile<W, E, kBlock, kUnroll, false>(ps, 0, 0, tw);
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r)
-        me[r] = (r * kBlock + threadIdx.x < rem)
-                    ? (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(mt, (r * kBlock + threadIdx.x) >> lg, 0, 0)
+        me[r] = __builtin_amdgcn_raw_buffer_load_b8(mt, lane_block<TU>(off + r * kBlock + threadIdx.x, bi), 0, 0);
+#pragma unroll
+      for (int r = 0; r < kUnroll; ++r)
+        decode_unit<T, W, false, kNT>(tw.u[r], fc, derive_tc(me[r], bc), out, threadIdx.x, r * kBlock);
+    } else {
+      load_tile<W, E, kBlock, kUnroll, true>(ps, 0, rem_units, tw);
+#pragma unroll
+      for (int r = 0; r < kUnroll; ++r)
+        me[r] = (r * kBlock + threadIdx.x < rem_units)
+                    ? (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(
+                          mt, lane_block<TU>(off + r * kBlock + threadIdx.x, bi), 0, 0)
                     : bc.meta_lo;
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r) {
-        if (r * kBlock + threadIdx.x < rem)
+        if (r * kBlock + threadIdx.x < rem_units)
           decode_unit<T, W, false, kNT>(tw.u[r], fc, derive_tc(me[r], bc), out, threadIdx.x, r * kBlock);
       }
     }
   }
 
   // The n % E elements after the last whole unit belong to the last block.
-  const bool last = kRows ? (blockIdx.y + (uint64_t)blockIdx.z * gridDim.y == args.n_blocks - 1) : true;
-  if (last && blockIdx.x == 0 && threadIdx.x < E) {
+  if (blockIdx.x == 0 && threadIdx.x < E) {
     const uint64_t i = Ufull * E + threadIdx.x;
     if (i < n) {
       const TensorConsts tc = derive_tc(meta[args.n_blocks - 1], bc);

@@ -98,8 +98,8 @@ __global__ __launch_bounds__(kBlock) void emulate_kernel(T* __restrict__ data, u
 }
 
 // ---------------------------------------------------------------------------
-// Per-block metadata: see the encoder for the two launch modes.  Work is counted
-// in 16-byte vectors of kPer elements; blocks hold block_groups * 8 / kPer of them.
+// Per-block metadata: flat tiles with a per-lane metadata lookup, as in the
+// encoder.  Work is counted in 16-byte vectors of kPer elements.
 
 template <typename T>
 __device__ __forceinline__ uint4 emulate_vector_meta(uint4 v, uint32_t me, bool wide_format, const FormatConsts& fc,
@@ -110,68 +110,46 @@ __device__ __forceinline__ uint4 emulate_vector_meta(uint4 v, uint32_t me, bool 
 }
 
 // wide_format: the format itself needs the fp64 path (Y > 21), whatever the metadata.
-template <typename T, int kBlock, int kUnroll, bool kRows, bool kNT>
+template <typename T, int kBlock, int kUnroll, bool kNT>
 __global__ __launch_bounds__(kBlock) void emulate_blocks_kernel(const BlockArgs args, bool wide_format) {
   constexpr int kPer = 16 / sizeof(T);
-  constexpr int kVecsPerGroupLog2 = sizeof(T) == 4 ? 1 : 0;
   constexpr uint32_t TV = kBlock * kUnroll;
   T* __restrict__ data = static_cast<T*>(const_cast<void*>(args.src));
   const uint8_t* __restrict__ meta = args.meta;
   const uint64_t n = args.n;
   const FormatConsts fc = args.fc;
   const BlockConsts bc = args.bc;
+  const BlockIndex bi = args.bi;  // in vectors
   const uint64_t V = n / kPer;
   const uint32_t lane_off = threadIdx.x * 16;
+  const uint32_t tiles = (uint32_t)((V + TV - 1) / TV);
 
-  if constexpr (kRows) {
-    const uint64_t row = blockIdx.y + (uint64_t)blockIdx.z * gridDim.y;
-    if (row >= args.n_blocks) return;
-    const uint32_t me = __builtin_amdgcn_readfirstlane((uint32_t)meta[row]);
-    const uint32_t block_vecs = args.block_groups << kVecsPerGroupLog2;
-    const uint64_t row_v0 = row * block_vecs;
-    const uint64_t left = V - row_v0;
-    const uint32_t row_vecs = left < block_vecs ? (uint32_t)left : block_vecs;
-    const uint32_t tiles = (row_vecs + TV - 1) / TV;
-    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-      const rsrc_t buf = make_rsrc(reinterpret_cast<uint4*>(data) + row_v0 + (uint64_t)tile * TV);
-      const uint32_t rem = row_vecs - tile * TV;  // >= TV on whole tiles
-      uint4 v[kUnroll];
+  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const uint64_t v0 = (uint64_t)tile * TV;
+    uint64_t blk0;
+    uint32_t off;
+    tile_first_block(v0, bi, blk0, off);
+    const rsrc_t buf = make_rsrc(reinterpret_cast<uint4*>(data) + v0);
+    const rsrc_t mt = make_rsrc(meta + blk0);
+    const uint64_t left = V - v0;
+    const uint32_t rem = left < TV ? (uint32_t)left : TV;
+    uint4 v[kUnroll];
+    uint32_t me[kUnroll];
 #pragma unroll
-      for (int r = 0; r < kUnroll; ++r)
-        if (r * kBlock + threadIdx.x < rem) v[r] = load16<kNT>(buf, lane_off, r * kBlock * 16);
-#pragma unroll
-      for (int r = 0; r < kUnroll; ++r)
-        if (r * kBlock + threadIdx.x < rem)
-          store16<kNT>(buf, lane_off, r * kBlock * 16, emulate_vector_meta<T>(v[r], me, wide_format, fc, bc));
-    }
-  } else {
-    const uint32_t lg = args.block_groups_log2 + kVecsPerGroupLog2;
-    const uint32_t tiles = (uint32_t)((V + TV - 1) / TV);
-    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-      const uint64_t v0 = (uint64_t)tile * TV;
-      const rsrc_t buf = make_rsrc(reinterpret_cast<uint4*>(data) + v0);
-      const rsrc_t mt = make_rsrc(meta + (v0 >> lg));
-      const uint64_t left = V - v0;
-      const uint32_t rem = left < TV ? (uint32_t)left : TV;
-      uint4 v[kUnroll];
-      uint32_t me[kUnroll];
-#pragma unroll
-      for (int r = 0; r < kUnroll; ++r) {
-        if (r * kBlock + threadIdx.x < rem) {
-          v[r] = load16<kNT>(buf, lane_off, r * kBlock * 16);
-          me[r] = __builtin_amdgcn_raw_buffer_load_b8(mt, (r * kBlock + threadIdx.x) >> lg, 0, 0);
-        }
+    for (int r = 0; r < kUnroll; ++r) {
+      if (r * kBlock + threadIdx.x < rem) {
+        v[r] = load16<kNT>(buf, lane_off, r * kBlock * 16);
+        me[r] = __builtin_amdgcn_raw_buffer_load_b8(mt, lane_block<TV>(off + r * kBlock + threadIdx.x, bi), 0, 0);
       }
-#pragma unroll
-      for (int r = 0; r < kUnroll; ++r)
-        if (r * kBlock + threadIdx.x < rem)
-          store16<kNT>(buf, lane_off, r * kBlock * 16, emulate_vector_meta<T>(v[r], me[r], wide_format, fc, bc));
     }
+#pragma unroll
+    for (int r = 0; r < kUnroll; ++r)
+      if (r * kBlock + threadIdx.x < rem)
+        store16<kNT>(buf, lane_off, r * kBlock * 16, emulate_vector_meta<T>(v[r], me[r], wide_format, fc, bc));
   }
 
   // Elements past the last whole 16-byte vector belong to the last block.
-  const bool last = kRows ? (blockIdx.y + (uint64_t)blockIdx.z * gridDim.y == args.n_blocks - 1) : true;
-  if (last && blockIdx.x == 0 && threadIdx.x < kPer) {
+  if (blockIdx.x == 0 && threadIdx.x < kPer) {
     const uint64_t i = V * kPer + threadIdx.x;
     if (i < n) {
       const uint32_t me = meta[args.n_blocks - 1];
@@ -226,55 +204,113 @@ __device__ __forceinline__ uint8_t key_to_meta(int32_t key, const BlockConsts& b
   return (uint8_t)min(max(e, bc.meta_lo), bc.meta_hi);
 }
 
-template <typename T, int kBlock, bool kRows>
-__global__ __launch_bounds__(kBlock) void block_max_exp_kernel(const BlockArgs args) {
+// Maximum over the 2^lg lanes (lg <= 6) that share all lane-index bits above the
+// low lg; every lane of the wavefront must call it.  Steps inside a row of 16
+// lanes are data-parallel-primitive moves: after the two quad permutes every
+// lane of a quad holds the quad's maximum, so mirroring 8 and then 16 lanes
+// brings in exactly the other half each time.
+__device__ __forceinline__ int32_t max_over_lanes(int32_t m, uint32_t lg) {
+  if (lg >= 1) m = max(m, __builtin_amdgcn_update_dpp(m, m, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+  if (lg >= 2) m = max(m, __builtin_amdgcn_update_dpp(m, m, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+  if (lg >= 3) m = max(m, __builtin_amdgcn_update_dpp(m, m, 0x141, 0xF, 0xF, false));  // row_half_mirror
+  if (lg >= 4) m = max(m, __builtin_amdgcn_update_dpp(m, m, 0x140, 0xF, 0xF, false));  // row_mirror
+  if (lg >= 5) m = max(m, __shfl_xor(m, 16, 64));
+  if (lg >= 6) m = max(m, __shfl_xor(m, 32, 64));
+  return m;
+}
+
+// Blocks of 2^lg vectors, lg <= 6: flat tiles of kBlock * kUnroll vectors, one
+// vector per lane and step; the lanes of a block combine with a butterfly.
+template <typename T, int kBlock, int kUnroll>
+__global__ __launch_bounds__(kBlock) void block_max_exp_small_kernel(const BlockArgs args) {
   constexpr int kPer = 16 / sizeof(T);
-  constexpr int kVecsPerGroupLog2 = sizeof(T) == 4 ? 1 : 0;
+  constexpr uint32_t TV = kBlock * kUnroll;
+  const T* __restrict__ src = static_cast<const T*>(args.src);
+  const uint4* __restrict__ src4 = static_cast<const uint4*>(args.src);
+  uint8_t* __restrict__ meta = args.meta;
+  const uint64_t n = args.n;
+  const BlockConsts bc = args.bc;
+  const uint32_t lg = args.bi.log2;  // of vectors per block
+  const uint64_t V = n / kPer;                  // whole vectors
+  const uint64_t Vall = (n + kPer - 1) / kPer;  // the last one may be partial
+  const uint32_t tiles = (uint32_t)((Vall + TV - 1) / TV);
+  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const uint64_t v0 = (uint64_t)tile * TV;
+    const rsrc_t buf = make_rsrc(src4 + v0);
+    const uint64_t whole = V - (v0 < V ? v0 : V);  // whole vectors from v0 on
+    int32_t m[kUnroll];
+#pragma unroll
+    for (int r = 0; r < kUnroll; ++r) {
+      const uint32_t i = r * kBlock + threadIdx.x;
+      m[r] = (int32_t)0x80000000;
+      if (i < whole) {
+        m[r] = vector_exp_key<T>(load16<true>(buf, i * 16, 0));
+      } else if (v0 + i < Vall) {
+        for (uint64_t e = (v0 + i) * kPer; e < n; ++e) m[r] = max(m[r], element_exp_key<T>(src + e));
+      }
+    }
+#pragma unroll
+    for (int r = 0; r < kUnroll; ++r) {
+      const uint64_t i = v0 + r * kBlock + threadIdx.x;
+      const int32_t mm = max_over_lanes(m[r], lg);
+      if (i < Vall && (threadIdx.x & ((1u << lg) - 1u)) == 0) meta[i >> lg] = key_to_meta(mm, bc);
+    }
+  }
+}
+
+// Any other block size: a team of kTeam lanes per block, kTeam = 64 (a wavefront;
+// blocks of up to about a thousand vectors) or kTeam = kBlock (the workgroup).
+template <typename T, int kBlock, int kTeam>
+__global__ __launch_bounds__(kBlock) void block_max_exp_team_kernel(const BlockArgs args) {
+  static_assert(kTeam == 64 || kTeam == kBlock, "a team is a wavefront or the workgroup");
+  constexpr int kPer = 16 / sizeof(T);
+  constexpr uint32_t kTeams = kBlock / kTeam;
+  __shared__ int32_t part[kBlock / 64];
   const T* __restrict__ src = static_cast<const T*>(args.src);
   const uint4* __restrict__ src4 = static_cast<const uint4*>(args.src);
   uint8_t* __restrict__ meta = args.meta;
   const uint64_t n = args.n;
   const BlockConsts bc = args.bc;
   const uint64_t V = n / kPer;  // whole vectors
+  const uint32_t block_vecs = args.bi.size;
+  const uint32_t team = kTeams > 1 ? __builtin_amdgcn_readfirstlane(threadIdx.x >> 6) : 0;
+  const uint32_t lane = threadIdx.x % kTeam;
 
-  if constexpr (kRows) {
-    __shared__ int32_t part[kBlock / 64];
-    const uint64_t row = blockIdx.y + (uint64_t)blockIdx.z * gridDim.y;
-    if (row >= args.n_blocks) return;
-    const uint32_t block_vecs = args.block_groups << kVecsPerGroupLog2;
-    const uint64_t row_v0 = row * block_vecs;
-    const uint64_t left = V - row_v0;
-    const uint32_t row_vecs = left < block_vecs ? (uint32_t)left : block_vecs;
-    const rsrc_t buf = make_rsrc(src4 + row_v0);
+  for (uint64_t first = (uint64_t)blockIdx.x * kTeams; first < args.n_blocks; first += (uint64_t)gridDim.x * kTeams) {
+    const uint64_t row = first + team;  // uniform over the team
     int32_t m = (int32_t)0x80000000;
-    for (uint32_t i = threadIdx.x; i < row_vecs; i += kBlock) m = max(m, vector_exp_key<T>(load16<true>(buf, i * 16, 0)));
-    if (row == args.n_blocks - 1 && threadIdx.x < kPer) {  // elements past the last whole vector
-      const uint64_t i = V * kPer + threadIdx.x;
-      if (i < n) m = max(m, element_exp_key<T>(src + i));
-    }
-#pragma unroll
-    for (int d = 32; d >= 1; d >>= 1) m = max(m, __shfl_xor(m, d, 64));
-    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-#pragma unroll
-      for (int w = 1; w < kBlock / 64; ++w) m = max(m, part[w]);
-      meta[row] = key_to_meta(m, bc);
-    }
-  } else {
-    // a block is 2^lg vectors, at most one wavefront wide: butterfly over its lanes
-    const uint32_t lg = args.block_groups_log2 + kVecsPerGroupLog2;
-    const uint64_t Vall = (n + kPer - 1) / kPer;  // the last vector may be partial
-    for (uint64_t base = (uint64_t)blockIdx.x * kBlock; base < Vall; base += (uint64_t)gridDim.x * kBlock) {
-      const uint64_t i = base + threadIdx.x;
-      int32_t m = (int32_t)0x80000000;
-      if (i < V) {
-        m = vector_exp_key<T>(__builtin_nontemporal_load(reinterpret_cast<const u32x4_t*>(src4) + i));
-      } else if (i < Vall) {
-        for (uint64_t e = i * kPer; e < n; ++e) m = max(m, element_exp_key<T>(src + e));
+    if (row < args.n_blocks) {
+      const uint64_t row_v0 = row * block_vecs;
+      const uint64_t left = V - row_v0;
+      const uint32_t row_vecs = left < block_vecs ? (uint32_t)left : block_vecs;
+      const rsrc_t buf = make_rsrc(src4 + row_v0);
+      uint32_t i = lane;
+      for (; i + 3 * kTeam < row_vecs; i += 4 * kTeam) {  // four loads in flight per lane
+        const uint4 a = load16<true>(buf, i * 16, 0);
+        const uint4 b = load16<true>(buf, (i + kTeam) * 16, 0);
+        const uint4 c = load16<true>(buf, (i + 2 * kTeam) * 16, 0);
+        const uint4 d = load16<true>(buf, (i + 3 * kTeam) * 16, 0);
+        m = max(max(m, vector_exp_key<T>(a)), vector_exp_key<T>(b));
+        m = max(max(m, vector_exp_key<T>(c)), vector_exp_key<T>(d));
       }
-      for (uint32_t d = 1; d < (1u << lg); d <<= 1) m = max(m, __shfl_xor(m, (int)d, 64));
-      if (i < Vall && (threadIdx.x & ((1u << lg) - 1u)) == 0) meta[i >> lg] = key_to_meta(m, bc);
+      for (; i < row_vecs; i += kTeam) m = max(m, vector_exp_key<T>(load16<true>(buf, i * 16, 0)));
+      if (row == args.n_blocks - 1 && lane < kPer) {  // elements past the last whole vector
+        const uint64_t e = V * kPer + lane;
+        if (e < n) m = max(m, element_exp_key<T>(src + e));
+      }
+    }
+    m = max_over_lanes(m, 6);
+    if constexpr (kTeam == 64) {
+      if (lane == 0 && row < args.n_blocks) meta[row] = key_to_meta(m, bc);
+    } else {
+      if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
+      __syncthreads();
+      if (threadIdx.x == 0) {
+#pragma unroll
+        for (int w = 1; w < kBlock / 64; ++w) m = max(m, part[w]);
+        meta[row] = key_to_meta(m, bc);
+      }
+      __syncthreads();  // part is reused by the next block
     }
   }
 }

@@ -19,32 +19,24 @@ struct Shape<float> {
   static constexpr int kBlock = 128;
   static constexpr int kUnroll = 1;
 };
-static_assert(Shape<uint16_t>::kBlock * Shape<uint16_t>::kUnroll >= kSmallBlockGroups, "a tile holds whole small blocks");
-static_assert(Shape<float>::kBlock * Shape<float>::kUnroll >= kSmallBlockGroups, "a tile holds whole small blocks");
 
 template <typename T, int W>
-hipError_t launch(const BlockArgs& args, bool rows, hipStream_t stream) {
+hipError_t launch(BlockArgs args, hipStream_t stream) {
   using S = Shape<T>;
   const uint64_t tile_groups = (uint64_t)S::kBlock * S::kUnroll;
-  if (rows) {
-    const uint64_t tiles = (args.block_groups + tile_groups - 1) / tile_groups;
-    const dim3 grid = grid_for_rows(tiles, args.n_blocks, S::kBlock);
-    hipLaunchKernelGGL((enc::encode_blocks_kernel<T, W, S::kBlock, S::kUnroll, true, true>), grid, dim3(S::kBlock), 0,
-                       stream, args);
-  } else {
-    const uint64_t tiles = (args.n / 8 + tile_groups - 1) / tile_groups;
-    hipLaunchKernelGGL((enc::encode_blocks_kernel<T, W, S::kBlock, S::kUnroll, false, true>),
-                       dim3(grid_for_chunks(tiles, 1, S::kBlock)), dim3(S::kBlock), 0, stream, args);
-  }
+  const uint64_t tiles = (args.n / 8 + tile_groups - 1) / tile_groups;
+  args.bi = make_block_index(args.block_groups);
+  hipLaunchKernelGGL((enc::encode_blocks_kernel<T, W, S::kBlock, S::kUnroll, true>),
+                     dim3(grid_for_chunks(tiles, 1, S::kBlock)), dim3(S::kBlock), 0, stream, args);
   return hipGetLastError();
 }
 
 template <typename T>
-hipError_t dispatch_w(int W, const BlockArgs& args, bool rows, hipStream_t stream) {
+hipError_t dispatch_w(int W, const BlockArgs& args, hipStream_t stream) {
   switch (W) {
 #define EXMY_CASE(w) \
   case w:            \
-    return launch<T, w>(args, rows, stream);
+    return launch<T, w>(args, stream);
     EXMY_CASE(1) EXMY_CASE(2) EXMY_CASE(3) EXMY_CASE(4) EXMY_CASE(5) EXMY_CASE(6) EXMY_CASE(7) EXMY_CASE(8)
     EXMY_CASE(9) EXMY_CASE(10) EXMY_CASE(11) EXMY_CASE(12) EXMY_CASE(13) EXMY_CASE(14) EXMY_CASE(15) EXMY_CASE(16)
 #undef EXMY_CASE
@@ -54,8 +46,8 @@ hipError_t dispatch_w(int W, const BlockArgs& args, bool rows, hipStream_t strea
 
 }  // namespace
 
-hipError_t encode_blocks_dispatch(exmy_dtype_t dt, int W, const BlockArgs& args, bool rows, hipStream_t stream) {
-  return dt == EXMY_F32 ? dispatch_w<float>(W, args, rows, stream) : dispatch_w<uint16_t>(W, args, rows, stream);
+hipError_t encode_blocks_dispatch(exmy_dtype_t dt, int W, const BlockArgs& args, hipStream_t stream) {
+  return dt == EXMY_F32 ? dispatch_w<float>(W, args, stream) : dispatch_w<uint16_t>(W, args, stream);
 }
 
 }  // namespace exmy

@@ -286,13 +286,9 @@ __global__ __launch_bounds__(kBlock) void encode_kernel(const BatchArgs batch) {
 // ---------------------------------------------------------------------------
 // Per-block metadata (Section 2 "Metadata", "Block Size"; Section 2.2.1).
 //
-// kRows = true: a metadata block is a long run (a row of a matrix, or any size
-// that is not a small power of two).  Grid y/z enumerate the blocks, grid x the
-// tiles inside one; the metadatum is wave-uniform, so the constants derived from
-// it stay in SGPRs and the per-element work is the same as in the per-tensor
-// kernel.
-// kRows = false: a block is 2^k groups, at most one tile; tiles run flat over the
-// tensor and every lane looks up the metadatum of its own group.
+// Tiles run flat over the tensor exactly as in the per-tensor kernel, whatever the
+// block size: every lane looks up the metadatum of the block its own group lies
+// in (see BlockIndex) and derives the block's constants in registers.
 
 // One group with the rounding variant its block's metadatum needs.  The branch is
 // taken for a whole wavefront at once (any lane that needs the fp64 path sends
@@ -308,7 +304,7 @@ __device__ __forceinline__ void encode_group_meta(const uint32_t u[8], uint32_t 
     encode_group<W, false>(u, fc, tc, pd, lane_group, tile_group);
 }
 
-template <typename T, int W, int kBlock, int kUnroll, bool kRows, bool kNT>
+template <typename T, int W, int kBlock, int kUnroll, bool kNT>
 __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs args) {
   constexpr uint32_t TG = kBlock * kUnroll;
   constexpr int kLoads = TileRegs<T, kUnroll>::kLoads;
@@ -318,68 +314,46 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
   const uint64_t n = args.n;
   const FormatConsts fc = args.fc;
   const BlockConsts bc = args.bc;
+  const BlockIndex bi = args.bi;  // in groups
   const uint64_t G = (n + 7) / 8;
   const uint64_t Gfull = n / 8;
+  const uint32_t full_tiles = (uint32_t)(Gfull / TG);
+  const uint32_t rem_groups = (uint32_t)(Gfull - (uint64_t)full_tiles * TG);
+  const uint32_t tiles = full_tiles + (rem_groups ? 1u : 0u);
 
-  if constexpr (kRows) {
-    const uint64_t row = blockIdx.y + (uint64_t)blockIdx.z * gridDim.y;
-    if (row >= args.n_blocks) return;
-    const uint32_t me = __builtin_amdgcn_readfirstlane((uint32_t)meta[row]);
-    const uint64_t row_g0 = row * args.block_groups;
-    const uint64_t left = Gfull - row_g0;  // whole groups from the start of this row to the end of the tensor
-    const uint32_t row_groups = left < args.block_groups ? (uint32_t)left : args.block_groups;
-    const uint32_t full_tiles = row_groups / TG;
-    const uint32_t rem_groups = row_groups - full_tiles * TG;
-    const uint32_t tiles = full_tiles + (rem_groups ? 1u : 0u);
-    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-      const uint64_t g0 = row_g0 + (uint64_t)tile * TG;
-      const rsrc_t src = make_rsrc(src4 + g0 * kLoads);
-      PlaneDst<W> pd;
-      make_plane_dst<W>(dst, G, g0, pd);
-      TileRegs<T, kUnroll> regs;
-      if (tile < full_tiles) {
-        load_tile<T, kBlock, kUnroll, kNT, false>(src, 0, 0, regs);
-#pragma unroll
-        for (int r = 0; r < kUnroll; ++r) {
-          uint32_t u[8];
-          group_bits<T>(regs.v[r], u);
-          encode_group_meta<W>(u, me, fc, bc, pd, threadIdx.x, r * kBlock);
-        }
-      } else {
-        load_tile<T, kBlock, kUnroll, kNT, true>(src, 0, rem_groups, regs);
-#pragma unroll
-        for (int r = 0; r < kUnroll; ++r) {
-          if (r * kBlock + threadIdx.x < rem_groups) {
-            uint32_t u[8];
-            group_bits<T>(regs.v[r], u);
-            encode_group_meta<W>(u, me, fc, bc, pd, threadIdx.x, r * kBlock);
-          }
-        }
-      }
-    }
-  } else {
-    const uint32_t lg = args.block_groups_log2;
-    const uint32_t full_tiles = (uint32_t)(Gfull / TG);
-    const uint32_t rem_groups = (uint32_t)(Gfull - (uint64_t)full_tiles * TG);
-    const uint32_t tiles = full_tiles + (rem_groups ? 1u : 0u);
-    for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
-      const uint64_t g0 = (uint64_t)tile * TG;  // a multiple of the block size in groups
-      const rsrc_t src = make_rsrc(src4 + g0 * kLoads);
-      const rsrc_t mt = make_rsrc(meta + (g0 >> lg));
-      PlaneDst<W> pd;
-      make_plane_dst<W>(dst, G, g0, pd);
-      const uint32_t rem = tile < full_tiles ? TG : rem_groups;
-      TileRegs<T, kUnroll> regs;
-      uint32_t me[kUnroll];
-      load_tile<T, kBlock, kUnroll, kNT, true>(src, 0, rem, regs);
+  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const uint64_t g0 = (uint64_t)tile * TG;
+    uint64_t blk0;
+    uint32_t off;
+    tile_first_block(g0, bi, blk0, off);
+    const rsrc_t src = make_rsrc(src4 + g0 * kLoads);
+    const rsrc_t mt = make_rsrc(meta + blk0);
+    PlaneDst<W> pd;
+    make_plane_dst<W>(dst, G, g0, pd);
+    TileRegs<T, kUnroll> regs;
+    uint32_t me[kUnroll];
+    if (tile < full_tiles) {
+      load_tile<T, kBlock, kUnroll, kNT, false>(src, 0, 0, regs);
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r)
-        me[r] = (r * kBlock + threadIdx.x < rem)
-                    ? (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(mt, (r * kBlock + threadIdx.x) >> lg, 0, 0)
+        me[r] = __builtin_amdgcn_raw_buffer_load_b8(mt, lane_block<TG>(off + r * kBlock + threadIdx.x, bi), 0, 0);
+#pragma unroll
+      for (int r = 0; r < kUnroll; ++r) {
+        uint32_t u[8];
+        group_bits<T>(regs.v[r], u);
+        encode_group_meta<W>(u, me[r], fc, bc, pd, threadIdx.x, r * kBlock);
+      }
+    } else {
+      load_tile<T, kBlock, kUnroll, kNT, true>(src, 0, rem_groups, regs);
+#pragma unroll
+      for (int r = 0; r < kUnroll; ++r)
+        me[r] = (r * kBlock + threadIdx.x < rem_groups)
+                    ? (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(
+                          mt, lane_block<TG>(off + r * kBlock + threadIdx.x, bi), 0, 0)
                     : bc.meta_lo;
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r) {
-        if (r * kBlock + threadIdx.x < rem) {  // the rounding-variant vote is among the lanes that get here
+        if (r * kBlock + threadIdx.x < rem_groups) {  // the rounding-variant vote is among the lanes that get here
           uint32_t u[8];
           group_bits<T>(regs.v[r], u);
           encode_group_meta<W>(u, me[r], fc, bc, pd, threadIdx.x, r * kBlock);
@@ -389,8 +363,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
   }
 
   // Ragged last group: it belongs to the last block.
-  const bool last = kRows ? (blockIdx.y + (uint64_t)blockIdx.z * gridDim.y == args.n_blocks - 1) : true;
-  if (Gfull != G && last && blockIdx.x == 0 && threadIdx.x == 0) {
+  if (Gfull != G && blockIdx.x == 0 && threadIdx.x == 0) {
     const T* __restrict__ src = static_cast<const T*>(args.src);
     uint32_t u[8];
 #pragma unroll

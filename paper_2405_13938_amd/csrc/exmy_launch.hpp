@@ -29,18 +29,6 @@ inline uint32_t grid_for_chunks(uint64_t tiles, int chunk, int block_size) {
   return (uint32_t)(g ? g : 1);
 }
 
-// Grid for kernels that give every metadata block (row) workgroups of its own:
-// x = tiles inside a row, y and z together enumerate the rows (row = y + z * grid.y;
-// the host has checked that rows <= kMaxRows).
-constexpr uint64_t kMaxGridYZ = 65535;
-constexpr uint64_t kMaxRows = kMaxGridYZ * kMaxGridYZ;
-inline dim3 grid_for_rows(uint64_t tiles_per_row, uint64_t rows, int block_size) {
-  const uint32_t x = grid_for_chunks(tiles_per_row, 1, block_size);
-  const uint64_t y = rows < kMaxGridYZ ? (rows ? rows : 1) : kMaxGridYZ;
-  const uint64_t z = (rows + y - 1) / y;
-  return dim3(x, (uint32_t)y, (uint32_t)(z ? z : 1));
-}
-
 // `n_max` is the largest element count among the batch's tensors (sizes the grid).
 hipError_t encode_dispatch(exmy_dtype_t dt, int W, bool wide, bool with_hist, const BatchArgs& args, uint64_t n_max,
                            hipStream_t stream);
@@ -48,13 +36,11 @@ hipError_t decode_dispatch(exmy_dtype_t dt, int W, bool x8, const BatchArgs& arg
                            hipStream_t stream);
 hipError_t emulate_dispatch(exmy_dtype_t dt, bool wide, void* data, uint64_t n, const FormatConsts& fc,
                             const TensorConsts& tc, hipStream_t stream);
-// Per-block metadata.  `rows`: every block gets workgroups of its own; otherwise blocks
-// are a power-of-two number of groups <= kSmallBlockGroups and args.block_groups_log2 is set.
-hipError_t encode_blocks_dispatch(exmy_dtype_t dt, int W, const BlockArgs& args, bool rows, hipStream_t stream);
-hipError_t decode_blocks_dispatch(exmy_dtype_t dt, int W, const BlockArgs& args, bool rows, hipStream_t stream);
-hipError_t emulate_blocks_dispatch(exmy_dtype_t dt, const BlockArgs& args, bool rows, bool wide_format,
-                                   hipStream_t stream);
-hipError_t block_max_exp_dispatch(exmy_dtype_t dt, const BlockArgs& args, bool rows, hipStream_t stream);
+// Per-block metadata (args.bi is filled in by the dispatcher from args.block_groups).
+hipError_t encode_blocks_dispatch(exmy_dtype_t dt, int W, const BlockArgs& args, hipStream_t stream);
+hipError_t decode_blocks_dispatch(exmy_dtype_t dt, int W, const BlockArgs& args, hipStream_t stream);
+hipError_t emulate_blocks_dispatch(exmy_dtype_t dt, const BlockArgs& args, bool wide_format, hipStream_t stream);
+hipError_t block_max_exp_dispatch(exmy_dtype_t dt, const BlockArgs& args, hipStream_t stream);
 hipError_t histogram_dispatch(exmy_dtype_t dt, const void* src, uint64_t n, uint64_t* hist, hipStream_t stream);
 
 }  // namespace exmy

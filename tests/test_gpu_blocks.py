@@ -159,8 +159,8 @@ def test_weight_matrix_rows_and_sub_rows(block):
         check_blocks(x, block, X, Y, "before_rounding", host)
 
 
-def test_more_rows_than_one_grid_dimension():
-    # 70000 rows of 1024: the row index spans grid y and z
+def test_many_short_rows():
+    # 70000 rows of 1024 elements, each less than a tile of some kernels
     x = synth.gaussian_bf16(70000 * 1024 + 100, seed=17).to(DEV)
     check_blocks(x, 1024, 3, 3, "before_rounding")
 

@@ -136,8 +136,6 @@ def test_block_entry_points_validate_without_launch():
         assert L.exmy_decode_blocks(ok, B.BF16, 64, block, 3, 3, ok, ok, None) == 7
         assert L.exmy_emulate_blocks(ok, B.BF16, 64, block, 3, 3, ok, None) == 7
     assert enc(ok, B.BF16, (1 << 40) + 1, 32, 3, 3, ok, ok, None) == 4
-    # more row-mode blocks than the two grid dimensions hold
-    assert enc(ok, B.BF16, 1 << 40, 24, 3, 3, ok, ok, None) == 7
     assert L.exmy_emulate_blocks(ok, B.F32, 0, 32, 2, 22, ok, None) == 0  # emulation has no width limit
     assert L.exmy_emulate_blocks(None, B.F32, 8, 32, 2, 22, ok, None) == 1
     assert L.exmy_block_max_exp(ok, B.F32, 8, 8, 9, ok, None) == 2
