@@ -163,6 +163,16 @@ size_t exmy_block_count(uint64_t n, uint64_t block);
 exmy_status_t exmy_block_max_exp(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X,
                                  uint8_t* max_exp_dev, void* stream);
 
+/* "Maximum exponent after rounding" (Section 2 "Metadata"; Section 2.1: with
+ * it 3.9 in e2m1 always becomes 4.0): as above, but the block's largest finite
+ * magnitude is first rounded to nearest (ties to even) to the mantissa width
+ * of the format's top binade (Y bits; Y - 1 for X = 0), so the block maximum
+ * is rounded like any other value and never cut off by saturation.  Differs
+ * from the scheme above (by +1) only where that rounding carries into the next
+ * binade.  No width limit on Y beyond the container's. */
+exmy_status_t exmy_block_max_exp_after_rounding(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X,
+                                                int Y, uint8_t* max_exp_dev, void* stream);
+
 /* exmy_encode / exmy_decode / exmy_emulate with block b using max_exp_dev[b]. */
 exmy_status_t exmy_encode_blocks(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
                                  const uint8_t* max_exp_dev, void* dst_packed, void* stream);
@@ -170,6 +180,13 @@ exmy_status_t exmy_decode_blocks(const void* src_packed, exmy_dtype_t dt_out, ui
                                  int Y, const uint8_t* max_exp_dev, void* dst, void* stream);
 exmy_status_t exmy_emulate_blocks(void* data_inout, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
                                   const uint8_t* max_exp_dev, void* stream);
+
+/* The pipeline of Section 2.2.1 in one call: the metadata of `scheme` is
+ * computed from src into max_exp_dev (an OUTPUT here, one byte per block), then
+ * src is encoded with it; two launches on `stream`, src is read twice. */
+typedef enum { EXMY_MAX_EXP_BEFORE_ROUNDING = 0, EXMY_MAX_EXP_AFTER_ROUNDING = 1 } exmy_scheme_t;
+exmy_status_t exmy_encode_blocks_auto(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
+                                      exmy_scheme_t scheme, uint8_t* max_exp_dev, void* dst_packed, void* stream);
 
 /* Host helper for Section 3.1's technique (keep the top exponents, let the
  * tail go): the smallest biased exponent e in [0, 254] such that at least

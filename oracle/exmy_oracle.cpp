@@ -42,9 +42,14 @@
 //   - per-block metadata: blocks are runs of `block` consecutive elements
 //     (a multiple of 8), the metadatum is the maximum biased exponent of the
 //     block's finite values ("before rounding"), clamped into [2^X, 254]
-//     ([1, 253] for X = 0).
+//     ([1, 253] for X = 0);
+//   - "maximum exponent after rounding": the exponent of the block's largest
+//     finite magnitude once that value is rounded (ties to even) to as many
+//     mantissa bits as the format's top binade has (Y, or Y - 1 when X = 0), so
+//     that the block maximum is rounded and never cut off by saturation.
 //
-// Pinned by tests/test_oracle_pins.py and tests/test_oracle_pack.py against the
+// Pinned by tests/test_oracle_pins.py, tests/test_oracle_pack.py and
+// tests/test_oracle_blocks.py against the
 // paper's worked examples, library float8 / bfloat16 / float16 conversions and a
 // brute-force nearest-value search.
 
@@ -439,6 +444,39 @@ int exmy_oracle_block_max_exp(const void* src, int dt, uint64_t n, uint64_t bloc
       if (e != 255 && e > m) m = e;
     }
     max_exp_out[b] = (uint8_t)clamp_meta(m, lo, hi);
+  }
+  return ORACLE_OK;
+}
+
+// "Maximum exponent after rounding" (Section 2 "Metadata"; Section 2.1: with this
+// scheme 3.9 in e2m1 always rounds up to 4.0).  The block's largest finite
+// magnitude is rounded to nearest, ties to even, to the mantissa width of the
+// format's top binade; the metadatum is the biased exponent of the result.
+int exmy_oracle_block_max_exp_after_rounding(const void* src, int dt, uint64_t n, uint64_t block, int X, int Y,
+                                             uint8_t* max_exp_out) {
+  if ((!src || !max_exp_out) && n) return ORACLE_ERR_NULL;
+  if (block == 0 || block % 8) return ORACLE_ERR_FORMAT;
+  int lo, hi;
+  if (int rc = block_meta_range(X, &lo, &hi)) return rc;
+  Format f0;
+  if (int rc = check_format(dt, X, Y, hi, false, &f0)) return rc;
+  const int bits = X == 0 ? (Y > 0 ? Y - 1 : 0) : Y;  // mantissa bits of the top binade
+  const uint64_t nb = (n + block - 1) / block;
+  for (uint64_t b = 0; b < nb; ++b) {
+    double m = 0.0;
+    for (uint64_t i = b * block; i < std::min(n, (b + 1) * block); ++i) {
+      const double a = std::fabs((double)bits_to_float(load_bits(src, dt, i)));
+      if (std::isfinite(a) && a > m) m = a;
+    }
+    int biased = 0;
+    if (m >= std::ldexp(1.0, -126)) {
+      int e;
+      const double frac = std::frexp(m, &e);                         // m = frac * 2^e, frac in [0.5, 1)
+      const double k = std::nearbyint(std::ldexp(frac, bits + 1));    // significand with `bits` fraction bits
+      std::frexp(std::ldexp(k, e - bits - 1), &e);                   // the rounded value may be 2^e
+      biased = e - 1 + 127;
+    }
+    max_exp_out[b] = (uint8_t)clamp_meta(biased, lo, hi);
   }
   return ORACLE_OK;
 }

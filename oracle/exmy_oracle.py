@@ -39,6 +39,7 @@ def lib():
         L.exmy_oracle_emulate.argtypes = [vp, i32, u64, i32, i32, i32, i32]
         L.exmy_oracle_exponent_histogram.argtypes = [vp, i32, u64, vp]
         L.exmy_oracle_block_max_exp.argtypes = [vp, i32, u64, u64, i32, vp]
+        L.exmy_oracle_block_max_exp_after_rounding.argtypes = [vp, i32, u64, u64, i32, i32, vp]
         L.exmy_oracle_encode_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, i32]
         L.exmy_oracle_decode_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, i32]
         L.exmy_oracle_emulate_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, i32]
@@ -164,6 +165,13 @@ def block_max_exp(src, block, X):
     a, dt = _src(src)
     out = np.empty((a.size + block - 1) // block, dtype=np.uint8)
     _check(lib().exmy_oracle_block_max_exp(_ptr(a), dt, a.size, block, X, _ptr(out)))
+    return out
+
+
+def block_max_exp_after_rounding(src, block, X, Y):
+    a, dt = _src(src)
+    out = np.empty((a.size + block - 1) // block, dtype=np.uint8)
+    _check(lib().exmy_oracle_block_max_exp_after_rounding(_ptr(a), dt, a.size, block, X, Y, _ptr(out)))
     return out
 
 

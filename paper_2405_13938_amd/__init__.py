@@ -10,6 +10,7 @@ from .binding import (  # noqa: F401
     ExmyError,
     block_count,
     block_max_exp,
+    block_max_exp_after_rounding,
     decode,
     decode_batch,
     decode_blocks,
@@ -18,6 +19,7 @@ from .binding import (  # noqa: F401
     encode,
     encode_batch,
     encode_blocks,
+    encode_blocks_auto,
     encode_with_histogram,
     exponent_histogram,
     max_exp_from_histogram,

@@ -26,6 +26,8 @@ SYMBOLS = [
     "exmy_max_exp_from_histogram",
     "exmy_block_count",
     "exmy_block_max_exp",
+    "exmy_block_max_exp_after_rounding",
+    "exmy_encode_blocks_auto",
     "exmy_encode_blocks",
     "exmy_decode_blocks",
     "exmy_emulate_blocks",
@@ -82,6 +84,10 @@ def lib():
         L.exmy_block_count.argtypes = [u64, u64]
         L.exmy_block_max_exp.restype = i32
         L.exmy_block_max_exp.argtypes = [vp, i32, u64, u64, i32, vp, vp]
+        L.exmy_block_max_exp_after_rounding.restype = i32
+        L.exmy_block_max_exp_after_rounding.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp]
+        L.exmy_encode_blocks_auto.restype = i32
+        L.exmy_encode_blocks_auto.argtypes = [vp, i32, u64, u64, i32, i32, i32, vp, vp, vp]
         L.exmy_encode_blocks.restype = i32
         L.exmy_encode_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, vp]
         L.exmy_decode_blocks.restype = i32
@@ -290,6 +296,42 @@ def block_max_exp(src, block, X, out=None):
         _meta_tensor(out, n, block, "out")
     _check(lib().exmy_block_max_exp(src.data_ptr(), _dtype_enum(src), n, block, X, out.data_ptr(), _stream()))
     return out
+
+
+BEFORE_ROUNDING, AFTER_ROUNDING = 0, 1
+
+
+def block_max_exp_after_rounding(src, block, X, Y, out=None):
+    """exmy_block_max_exp_after_rounding: returns the uint8 tensor of one max_exp per block."""
+    _device_tensor(src, "src")
+    n = src.numel()
+    if out is None:
+        out = torch.empty(block_count(n, block), dtype=torch.uint8, device=src.device)
+    else:
+        _meta_tensor(out, n, block, "out")
+    _check(lib().exmy_block_max_exp_after_rounding(src.data_ptr(), _dtype_enum(src), n, block, X, Y, out.data_ptr(),
+                                                   _stream()))
+    return out
+
+
+def encode_blocks_auto(src, block, X, Y, scheme=BEFORE_ROUNDING, max_exps=None, out=None):
+    """exmy_encode_blocks_auto: returns (packed, max_exps)."""
+    _device_tensor(src, "src")
+    n = src.numel()
+    if max_exps is None:
+        max_exps = torch.empty(block_count(n, block), dtype=torch.uint8, device=src.device)
+    else:
+        _meta_tensor(max_exps, n, block)
+    nbytes = packed_bytes(n, X, Y)
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.uint8, device=src.device)
+    else:
+        _device_tensor(out, "out")
+        if out.dtype != torch.uint8 or out.numel() != nbytes:
+            raise ValueError("exmy: out must be uint8 with %d elements" % nbytes)
+    _check(lib().exmy_encode_blocks_auto(src.data_ptr(), _dtype_enum(src), n, block, X, Y, int(scheme),
+                                         max_exps.data_ptr(), out.data_ptr(), _stream()))
+    return out, max_exps
 
 
 def encode_blocks(src, block, X, Y, max_exps, out=None):

@@ -102,7 +102,8 @@ exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, bool packe
   return EXMY_OK;
 }
 
-exmy_status_t make_block_format(exmy_dtype_t dt, int X, int Y, bool packed, FormatConsts* fc, BlockConsts* bc) {
+exmy_status_t make_block_format(exmy_dtype_t dt, int X, int Y, bool packed, bool after_rounding, FormatConsts* fc,
+                                BlockConsts* bc) {
   if (X == 8) return EXMY_ERR_FORMAT;  // identity exponent map: nothing for a block to choose
   const int hi = X == 0 ? 253 : 254;
   if (exmy_status_t st = make_format(dt, X, Y, hi, packed, fc, nullptr, nullptr)) return st;
@@ -122,6 +123,16 @@ exmy_status_t make_block_format(exmy_dtype_t dt, int X, int Y, bool packed, Form
     bc->bias_shift = (uint32_t)((Y + L) & 31);
     bc->bias_mask = (Y + L) >= 32 ? 0u : 0xFFFFFFFFu;
     bc->wide_above = (uint32_t)(231 + Y - (X == 0 ? 1 : 0));  // largest clamped exponent is max_exp (+1 for X = 0)
+    // mantissa bits of the top binade: Y, or Y - 1 for X = 0 (see sat_mant)
+    const int top_bits = X >= 1 ? Y : (Y >= 1 ? Y - 1 : 0);
+    bc->round_half = bc->round_shift = bc->round_odd = 0;
+    if (after_rounding && top_bits == 0) {
+      bc->round_half = 1u << 22;  // the kept significand is the leading one, always odd: a tie goes up
+    } else if (after_rounding && top_bits < 23) {
+      bc->round_half = (1u << (22 - top_bits)) - 1u;
+      bc->round_shift = (uint32_t)(23 - top_bits);
+      bc->round_odd = 1u;
+    }
   }
   return EXMY_OK;
 }
@@ -197,7 +208,7 @@ exmy_status_t run_batch(Op op, const exmy_tensor_t* tensors, size_t count, exmy_
   return flush() == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
 }
 
-enum class BlockOp { kMaxExp, kEncode, kDecode, kEmulate };
+enum class BlockOp { kMaxExp, kMaxExpRounded, kEncode, kDecode, kEmulate };
 
 // Shared validation and launch of the per-block-metadata entry points.  `elems` is
 // the bf16 / fp32 side, `packed` the plane side (unused by kMaxExp and kEmulate).
@@ -205,7 +216,8 @@ exmy_status_t run_blocks(BlockOp op, const void* elems, const void* packed, exmy
                          uint64_t block, int X, int Y, const uint8_t* meta, void* stream) {
   BlockArgs args;
   const bool is_packed = op == BlockOp::kEncode || op == BlockOp::kDecode;
-  if (exmy_status_t st = make_block_format(dt, X, Y, is_packed, &args.fc, &args.bc)) return st;
+  if (exmy_status_t st = make_block_format(dt, X, Y, is_packed, op == BlockOp::kMaxExpRounded, &args.fc, &args.bc))
+    return st;
   if (block < 8 || block % 8 || block > EXMY_MAX_BLOCK) return EXMY_ERR_BLOCK;
   if (n > EXMY_MAX_ELEMENTS) return EXMY_ERR_COUNT;
   if (n == 0) return EXMY_OK;
@@ -221,6 +233,7 @@ exmy_status_t run_blocks(BlockOp op, const void* elems, const void* packed, exmy
   hipError_t e = hipSuccess;
   switch (op) {
     case BlockOp::kMaxExp:
+    case BlockOp::kMaxExpRounded:
       args.src = elems;
       args.dst = nullptr;
       e = block_max_exp_dispatch(dt, args, s);
@@ -312,6 +325,23 @@ size_t exmy_block_count(uint64_t n, uint64_t block) { return block ? (size_t)((n
 exmy_status_t exmy_block_max_exp(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X,
                                  uint8_t* max_exp_dev, void* stream) {
   return run_blocks(BlockOp::kMaxExp, src, nullptr, dt, n, block, X, 0, max_exp_dev, stream);
+}
+
+exmy_status_t exmy_block_max_exp_after_rounding(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X,
+                                                int Y, uint8_t* max_exp_dev, void* stream) {
+  return run_blocks(BlockOp::kMaxExpRounded, src, nullptr, dt, n, block, X, Y, max_exp_dev, stream);
+}
+
+exmy_status_t exmy_encode_blocks_auto(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
+                                      exmy_scheme_t scheme, uint8_t* max_exp_dev, void* dst_packed, void* stream) {
+  if (scheme != EXMY_MAX_EXP_BEFORE_ROUNDING && scheme != EXMY_MAX_EXP_AFTER_ROUNDING) return EXMY_ERR_FORMAT;
+  // validate the second launch before the first, so that an error leaves both outputs untouched
+  if (exmy_status_t st = make_block_format(dt, X, Y, true, false, nullptr, nullptr)) return st;
+  if (n && !dst_packed) return EXMY_ERR_NULL;
+  if (n && !aligned16(dst_packed)) return EXMY_ERR_ALIGN;
+  const BlockOp op = scheme == EXMY_MAX_EXP_AFTER_ROUNDING ? BlockOp::kMaxExpRounded : BlockOp::kMaxExp;
+  if (exmy_status_t st = run_blocks(op, src, nullptr, dt, n, block, X, Y, max_exp_dev, stream)) return st;
+  return run_blocks(BlockOp::kEncode, src, dst_packed, dt, n, block, X, Y, max_exp_dev, stream);
 }
 
 exmy_status_t exmy_encode_blocks(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,

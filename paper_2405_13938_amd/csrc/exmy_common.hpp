@@ -73,6 +73,13 @@ struct BlockConsts {
   uint32_t bias_shift;  // Y + L, taken modulo 32 ...
   uint32_t bias_mask;   // ... with the result masked to 0 when Y + L = 32
   uint32_t wide_above;  // metadata above this needs the fp64 rounding path (231 + Y)
+  // "maximum exponent after rounding": the block maximum's fp32 bits a become
+  // a + round_half + ((a >> round_shift) & round_odd) before the exponent is read
+  // (round to nearest even at the mantissa width of the top binade); all zero for
+  // "before rounding".
+  uint32_t round_half;
+  uint32_t round_shift;
+  uint32_t round_odd;
 };
 
 // How a kernel finds the metadata block of a piece of work.  Work is counted in
@@ -125,7 +132,9 @@ exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, bool packe
                           TensorConsts* tc, bool* needs_wide);
 
 // Host: validate (dtype, X, Y) for per-block metadata and fill fc / bc.
-exmy_status_t make_block_format(exmy_dtype_t dt, int X, int Y, bool packed, FormatConsts* fc, BlockConsts* bc);
+// after_rounding selects the scheme of the maximum-exponent kernel.
+exmy_status_t make_block_format(exmy_dtype_t dt, int X, int Y, bool packed, bool after_rounding, FormatConsts* fc,
+                                BlockConsts* bc);
 
 #if defined(__HIPCC__)
 

@@ -168,9 +168,10 @@ __global__ __launch_bounds__(kBlock) void emulate_blocks_kernel(const BlockArgs 
 }
 
 // ---------------------------------------------------------------------------
-// "Maximum exponent before rounding" of every block (Section 2 "Metadata"): the
-// largest biased exponent among the block's finite elements, clamped into the
-// valid range.  Adding 1 to the exponent field turns Inf / NaN patterns negative
+// Maximum exponent of every block, "before rounding" or "after rounding"
+// (Section 2 "Metadata"): the biased exponent of the block's largest finite
+// magnitude, taken as it is or after that value is rounded to the mantissa width
+// of the format's top binade, clamped into the valid range.  Adding 1 to the exponent field turns Inf / NaN patterns negative
 // as signed integers, so a signed maximum skips them.
 
 template <typename T, typename V4>
@@ -200,8 +201,9 @@ __device__ __forceinline__ int32_t element_exp_key(const T* p) {
 }
 
 __device__ __forceinline__ uint8_t key_to_meta(int32_t key, const BlockConsts& bc) {
-  const uint32_t e = key > 0 ? ((uint32_t)key >> 23) - 1u : 0u;  // no finite element: exponent 0
-  return (uint8_t)min(max(e, bc.meta_lo), bc.meta_hi);
+  uint32_t a = key > 0 ? (uint32_t)key - 0x00800000u : 0u;  // bits of the largest finite magnitude (0 if none)
+  a += bc.round_half + ((a >> bc.round_shift) & bc.round_odd);  // "after rounding"; may carry up to exponent 255
+  return (uint8_t)min(max(a >> 23, bc.meta_lo), bc.meta_hi);
 }
 
 // Maximum over the 2^lg lanes (lg <= 6) that share all lane-index bits above the

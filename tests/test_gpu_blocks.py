@@ -176,3 +176,31 @@ def test_uniform_metadata_equals_per_tensor_entry_points():
                            exmy.decode(b, torch.bfloat16, x.numel(), 3, 3, 127).view(torch.int16))
         assert torch.equal(exmy.emulate_blocks(x.clone(), block, 3, 3, meta).view(torch.int16),
                            exmy.emulate(x.clone(), 3, 3, 127).view(torch.int16))
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_max_exp_after_rounding(dtype):
+    # every rounding position, blocks of every launch form, maxima at ties and at carries into the next binade
+    x = synth.shuffled(synth.f32_edge_sweep(seed=11) if dtype == torch.float32 else synth.all_bf16_patterns(), 11).to(DEV)
+    host = synth.bits_numpy(x)
+    P = 23 if dtype == torch.float32 else 7
+    for X in (0, 1, 3, 7):
+        for Y in sorted({0, 1, 2, 3, P - 1, P, P + 1 if X == 0 else P}):
+            for block in (8, 64, 512, 24, 1024, 4096, 40000):
+                got = exmy.block_max_exp_after_rounding(x, block, X, Y)
+                torch.cuda.synchronize()
+                want = O.block_max_exp_after_rounding(host, block, X, Y)
+                assert np.array_equal(got.cpu().numpy(), want), (dtype, X, Y, block)
+
+
+@pytest.mark.parametrize("scheme", [exmy.binding.BEFORE_ROUNDING, exmy.binding.AFTER_ROUNDING])
+def test_encode_blocks_auto(scheme):
+    for dtype in (torch.bfloat16, torch.float32):
+        x = synth.gaussian_bf16(300 * 1024 + 13, seed=21).to(dtype).to(DEV)
+        host = synth.bits_numpy(x)
+        for block, X, Y in ((16, 2, 1), (32, 1, 2), (1024, 3, 2), (4096, 3, 3)):
+            packed, meta = exmy.encode_blocks_auto(x, block, X, Y, scheme)
+            torch.cuda.synchronize()
+            want_meta = (O.block_max_exp_after_rounding(host, block, X, Y) if scheme else O.block_max_exp(host, block, X))
+            assert np.array_equal(meta.cpu().numpy(), want_meta)
+            assert np.array_equal(packed.cpu().numpy(), O.encode_blocks(host, block, X, Y, want_meta, threads=THREADS))

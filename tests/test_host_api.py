@@ -146,3 +146,27 @@ def test_block_entry_points_validate_without_launch():
     for block in (0, 4, 12, 33):
         with pytest.raises(Exception):
             O.block_max_exp(x, block, 3)
+
+
+def test_after_rounding_and_auto_entry_points_validate_without_launch():
+    L = B.lib()
+    ok, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1008)
+    mx = L.exmy_block_max_exp_after_rounding
+    assert mx(ok, B.F32, 0, 8, 3, 3, ok, None) == 0
+    assert mx(None, B.F32, 8, 8, 3, 3, ok, None) == 1
+    assert mx(ok, B.F32, 8, 8, 3, 3, None, None) == 1
+    assert mx(ok, B.F32, 8, 8, 3, 24, ok, None) == 2
+    assert mx(ok, B.F32, 0, 8, 3, 23, ok, None) == 0  # no width limit beyond the container's
+    assert mx(ok, B.BF16, 0, 8, 8, 3, ok, None) == 2
+    assert mx(ok, B.BF16, 8, 12, 3, 3, ok, None) == 7
+    assert mx(odd, B.BF16, 8, 8, 3, 3, ok, None) == 5
+    auto = L.exmy_encode_blocks_auto
+    assert auto(ok, B.BF16, 0, 32, 3, 3, 0, ok, ok, None) == 0
+    assert auto(ok, B.BF16, 0, 32, 3, 3, 1, ok, ok, None) == 0
+    assert auto(ok, B.BF16, 0, 32, 3, 3, 2, ok, ok, None) == 2  # unknown scheme
+    assert auto(ok, B.BF16, 64, 32, 3, 3, 0, ok, None, None) == 1
+    assert auto(ok, B.BF16, 64, 32, 3, 3, 0, None, ok, None) == 1
+    assert auto(None, B.BF16, 64, 32, 3, 3, 0, ok, ok, None) == 1
+    assert auto(ok, B.BF16, 64, 32, 3, 3, 0, ok, odd, None) == 5
+    assert auto(ok, B.F32, 64, 32, 3, 13, 0, ok, ok, None) == 2  # packed form stops at 16 bits
+    assert auto(ok, B.BF16, 64, 20, 3, 3, 0, ok, ok, None) == 7
