@@ -188,6 +188,34 @@ typedef enum { EXMY_MAX_EXP_BEFORE_ROUNDING = 0, EXMY_MAX_EXP_AFTER_ROUNDING = 1
 exmy_status_t exmy_encode_blocks_auto(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
                                       exmy_scheme_t scheme, uint8_t* max_exp_dev, void* dst_packed, void* stream);
 
+/* ---------------------------------------------------------------------------
+ * Float scaling with maximum exponent 127 (Section 2 "Metadata": an additional
+ * float32 scaling factor; Section 2.1: the third scheme of the emulation
+ * example, which reproduces the largest value of a block accurately).
+ *
+ * Every block has one fp32 scale in the DEVICE array scale_dev (4-byte
+ * aligned, exmy_block_count(n, block) entries) instead of a metadata byte; the
+ * codes are those of the format with max_exp = 127, whose top binade is
+ * [1, 2).  The paper prints no formulas; this library computes, in fp32:
+ *   scale   s = max(m / vmax, FLT_MIN), m = largest finite |x| of the block
+ *               (0 if none), vmax = largest value of the format at max_exp = 127;
+ *   encode  the code of |x| * (1 / s) in that format, under the sign of x
+ *           (Inf / NaN: sign + largest magnitude code, as in exmy_encode);
+ *   decode  value * s, one rounding; rounded to nearest even when dt is bf16;
+ *   emulate decode(encode(x)) with Inf / NaN left bit-identical.
+ * Scales given to encode / decode / emulate need not come from
+ * exmy_block_scale but must be finite and >= FLT_MIN (else the result is
+ * unspecified, without any fault).  1 <= X <= 7 or (X = 0, Y >= 1); block,
+ * layout, pointers, n = 0, streams and errors as for the entry points above. */
+exmy_status_t exmy_block_scale(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
+                               float* scale_dev, void* stream);
+exmy_status_t exmy_encode_scaled(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
+                                 const float* scale_dev, void* dst_packed, void* stream);
+exmy_status_t exmy_decode_scaled(const void* src_packed, exmy_dtype_t dt_out, uint64_t n, uint64_t block, int X,
+                                 int Y, const float* scale_dev, void* dst, void* stream);
+exmy_status_t exmy_emulate_scaled(void* data_inout, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
+                                  const float* scale_dev, void* stream);
+
 /* Host helper for Section 3.1's technique (keep the top exponents, let the
  * tail go): the smallest biased exponent e in [0, 254] such that at least
  * `coverage` (0..1) of the finite elements counted in the HOST array

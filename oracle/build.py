@@ -11,7 +11,7 @@ def build(force=True):
     if not force and os.path.exists(LIB) and os.path.getmtime(LIB) >= os.path.getmtime(SRC):
         return LIB
     tmp = LIB + ".tmp.%d" % os.getpid()
-    cmd = ["g++", "-O2", "-std=c++17", "-Wall", "-Wextra", "-fPIC", "-shared", "-pthread", SRC, "-o", tmp]
+    cmd = ["g++", "-O2", "-ffp-contract=off", "-std=c++17", "-Wall", "-Wextra", "-fPIC", "-shared", "-pthread", SRC, "-o", tmp]
     subprocess.run(cmd, check=True)
     os.replace(tmp, LIB)
     return LIB

@@ -48,6 +48,16 @@
 //     mantissa bits as the format's top binade has (Y, or Y - 1 when X = 0), so
 //     that the block maximum is rounded and never cut off by saturation.
 //
+//   - "float scaling with maximum exponent 127" (Section 2 "Metadata", Section
+//     2.1): the paper gives no formulas.  Reading: the block's scale is
+//     s = max|x| / vmax in fp32 (vmax = largest value of the format with
+//     max_exp = 127; s is raised to FLT_MIN if smaller), the code is that of
+//     fl32(|x| * fl32(1 / s)) in the max_exp = 127 format, and the decoded value is
+//     fl32(value * s), rounded to nearest even when the container is bf16.  The
+//     scaled value decides the code, so it is computed in the kernels' precision
+//     (fp32) here too.  Parity unpinned by the paper beyond the property that the
+//     block maximum is reproduced almost exactly.
+//
 // Pinned by tests/test_oracle_pins.py, tests/test_oracle_pack.py and
 // tests/test_oracle_blocks.py against the
 // paper's worked examples, library float8 / bfloat16 / float16 conversions and a
@@ -532,5 +542,110 @@ int exmy_oracle_emulate_blocks(void* data, int dt, uint64_t n, uint64_t block, i
                                int threads) {
   return blocks_op(2, data, data, dt, n, block, X, Y, max_exp, threads);
 }
+
+// ---------------------------------------------------------------------------
+// Float scaling with maximum exponent 127 (Section 2 "Metadata": an additional
+// float32 scaling factor; Section 2.1: this scheme reproduces the largest value
+// of the block accurately).  One fp32 scale per block; the codes are those of
+// the max_exp = 127 format, whose top binade is [1, 2).
+
+static int scaled_format(int dt, int X, int Y, bool packed, Format* f) {
+  if (X < 0 || X > 7) return ORACLE_ERR_FORMAT;
+  if (X == 0 && Y == 0) return ORACLE_ERR_FORMAT;  // the only magnitude is 0: nothing to scale
+  return check_format(dt, X, Y, 127, packed, f);
+}
+
+// fp32 -> bf16, round to nearest, ties to even (the library conversion), as fp32 bits.
+static uint32_t round_to_bf16_bits(float r) {
+  if (std::isnan(r) || std::isinf(r) || r == 0.0f) return float_to_bits(r) & 0xFFFF0000u;
+  int e;
+  (void)std::frexp((double)r, &e);                         // |r| in [2^(e-1), 2^e)
+  const int q = std::max(e - 1, -126) - 7;                 // exponent of the bf16 quantum in this binade
+  const double k = std::nearbyint(std::ldexp((double)r, -q));
+  return float_to_bits((float)std::ldexp(k, q));           // exact in fp32; 2^128 becomes Inf
+}
+
+int exmy_oracle_block_scale(const void* src, int dt, uint64_t n, uint64_t block, int X, int Y, float* scale_out) {
+  if ((!src || !scale_out) && n) return ORACLE_ERR_NULL;
+  if (block == 0 || block % 8) return ORACLE_ERR_FORMAT;
+  Format f;
+  if (int rc = scaled_format(dt, X, Y, false, &f)) return rc;
+  const float vmax = (float)code_magnitude(f, f.cmax);
+  const uint64_t nb = (n + block - 1) / block;
+  for (uint64_t b = 0; b < nb; ++b) {
+    float m = 0.0f;
+    for (uint64_t i = b * block; i < std::min(n, (b + 1) * block); ++i) {
+      const float a = std::fabs(bits_to_float(load_bits(src, dt, i)));
+      if (std::isfinite(a) && a > m) m = a;
+    }
+    float s = m / vmax;
+    if (!(s >= std::ldexp(1.0f, -126))) s = std::ldexp(1.0f, -126);
+    scale_out[b] = s;
+  }
+  return ORACLE_OK;
+}
+
+// what: 0 = encode, 1 = decode, 2 = emulate in place
+static int scaled_op(int what, const void* src, void* dst, int dt, uint64_t n, uint64_t block, int X, int Y,
+                     const float* scale, int threads) {
+  if (n && (!src || !dst || !scale)) return ORACLE_ERR_NULL;
+  if (block == 0 || block % 8) return ORACLE_ERR_FORMAT;
+  Format f;
+  if (int rc = scaled_format(dt, X, Y, what != 2, &f)) return rc;
+  const uint64_t nb = (n + block - 1) / block;
+  const int W = 1 + X + Y;
+  std::vector<uint32_t> codes;
+  if (what != 2) codes.resize(n);
+  if (what == 1) unpack_groups((const uint8_t*)src, n, W, codes.data(), 0, 0, (n + 7) / 8);
+  parallel_ranges(nb, threads, [&](uint64_t b0, uint64_t b1) {
+    for (uint64_t b = b0; b < b1; ++b) {
+      const float s = scale[b];
+      const float inv = 1.0f / s;
+      for (uint64_t i = b * block; i < std::min(n, (b + 1) * block); ++i) {
+        uint32_t code = 0;
+        uint32_t bits = 0;
+        if (what != 1) {
+          bits = load_bits(src, dt, i);
+          const float a = std::fabs(bits_to_float(bits)) * inv;  // fp32 product, one rounding
+          const int64_t c = (std::isnan(a) || std::isinf(a)) ? f.cmax : magnitude_code(f, (double)a);
+          code = (uint32_t)(((bits >> 31) << (X + Y)) | (uint32_t)c);
+        } else {
+          code = codes[i];
+        }
+        if (what == 0) {
+          codes[i] = code;
+          continue;
+        }
+        const float x = bits_to_float(bits);
+        if (what == 2 && (std::isnan(x) || std::isinf(x))) continue;  // preserved
+        const float v = (float)code_magnitude(f, code & (uint32_t)((((int64_t)1) << (X + Y)) - 1));
+        const float r = v * s;  // fp32 product, one rounding
+        uint32_t out = dt == ORACLE_F32 ? float_to_bits(r) : round_to_bf16_bits(r);
+        out |= ((code >> (X + Y)) & 1u) << 31;
+        store_bits(dst, dt, i, out);
+      }
+    }
+  });
+  if (what == 0) pack_groups(codes.data(), 0, n, W, (uint8_t*)dst, 0, (n + 7) / 8);
+  return ORACLE_OK;
+}
+
+int exmy_oracle_encode_scaled(const void* src, int dt, uint64_t n, uint64_t block, int X, int Y, const float* scale,
+                              uint8_t* dst_packed, int threads) {
+  return scaled_op(0, src, dst_packed, dt, n, block, X, Y, scale, threads);
+}
+
+int exmy_oracle_decode_scaled(const uint8_t* src_packed, int dt, uint64_t n, uint64_t block, int X, int Y,
+                              const float* scale, void* dst, int threads) {
+  return scaled_op(1, src_packed, dst, dt, n, block, X, Y, scale, threads);
+}
+
+int exmy_oracle_emulate_scaled(void* data, int dt, uint64_t n, uint64_t block, int X, int Y, const float* scale,
+                               int threads) {
+  return scaled_op(2, data, data, dt, n, block, X, Y, scale, threads);
+}
+
+// fp32 -> bf16 rounding used above, exported so that it can be pinned on its own.
+uint32_t exmy_oracle_round_to_bf16_bits(float r) { return round_to_bf16_bits(r); }
 
 }  // extern "C"

@@ -43,6 +43,12 @@ def lib():
         L.exmy_oracle_encode_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, i32]
         L.exmy_oracle_decode_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, i32]
         L.exmy_oracle_emulate_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, i32]
+        L.exmy_oracle_block_scale.argtypes = [vp, i32, u64, u64, i32, i32, vp]
+        L.exmy_oracle_encode_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, i32]
+        L.exmy_oracle_decode_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, i32]
+        L.exmy_oracle_emulate_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, i32]
+        L.exmy_oracle_round_to_bf16_bits.restype = ctypes.c_uint32
+        L.exmy_oracle_round_to_bf16_bits.argtypes = [ctypes.c_float]
         L.exmy_oracle_max_exp_from_histogram.restype = i32
         L.exmy_oracle_max_exp_from_histogram.argtypes = [vp, dbl]
         _lib = L
@@ -204,3 +210,48 @@ def emulate_blocks(src, block, X, Y, max_exp, threads=1):
     out = a.copy()
     _check(lib().exmy_oracle_emulate_blocks(_ptr(out), dt, out.size, block, X, Y, _ptr(m), threads))
     return out
+
+
+# ------------------------------------------------------------ float scaling, max_exp = 127
+
+
+def _scales(scale, n, block):
+    s = np.ascontiguousarray(scale, dtype=np.float32)
+    assert s.size == (n + block - 1) // block
+    return s
+
+
+def block_scale(src, block, X, Y):
+    a, dt = _src(src)
+    out = np.empty((a.size + block - 1) // block, dtype=np.float32)
+    _check(lib().exmy_oracle_block_scale(_ptr(a), dt, a.size, block, X, Y, _ptr(out)))
+    return out
+
+
+def encode_scaled(src, block, X, Y, scale, threads=1):
+    a, dt = _src(src)
+    s = _scales(scale, a.size, block)
+    out = np.empty(packed_bytes(a.size, X, Y), dtype=np.uint8)
+    _check(lib().exmy_oracle_encode_scaled(_ptr(a), dt, a.size, block, X, Y, _ptr(s), _ptr(out), threads))
+    return out
+
+
+def decode_scaled(packed, dt, n, block, X, Y, scale, threads=1):
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    assert packed.size == packed_bytes(n, X, Y)
+    s = _scales(scale, n, block)
+    out = np.empty(n, dtype=_out_dtype(dt))
+    _check(lib().exmy_oracle_decode_scaled(_ptr(packed), dt, n, block, X, Y, _ptr(s), _ptr(out), threads))
+    return out
+
+
+def emulate_scaled(src, block, X, Y, scale, threads=1):
+    a, dt = _src(src)
+    s = _scales(scale, a.size, block)
+    out = a.copy()
+    _check(lib().exmy_oracle_emulate_scaled(_ptr(out), dt, out.size, block, X, Y, _ptr(s), threads))
+    return out
+
+
+def round_to_bf16_bits(r):
+    return int(lib().exmy_oracle_round_to_bf16_bits(float(r)))

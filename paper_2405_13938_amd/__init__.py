@@ -11,15 +11,19 @@ from .binding import (  # noqa: F401
     block_count,
     block_max_exp,
     block_max_exp_after_rounding,
+    block_scale,
     decode,
     decode_batch,
     decode_blocks,
+    decode_scaled,
     emulate,
     emulate_blocks,
+    emulate_scaled,
     encode,
     encode_batch,
     encode_blocks,
     encode_blocks_auto,
+    encode_scaled,
     encode_with_histogram,
     exponent_histogram,
     max_exp_from_histogram,

@@ -31,6 +31,10 @@ SYMBOLS = [
     "exmy_encode_blocks",
     "exmy_decode_blocks",
     "exmy_emulate_blocks",
+    "exmy_block_scale",
+    "exmy_encode_scaled",
+    "exmy_decode_scaled",
+    "exmy_emulate_scaled",
     "exmy_status_string",
 ]
 
@@ -94,6 +98,14 @@ def lib():
         L.exmy_decode_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, vp]
         L.exmy_emulate_blocks.restype = i32
         L.exmy_emulate_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp]
+        L.exmy_block_scale.restype = i32
+        L.exmy_block_scale.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp]
+        L.exmy_encode_scaled.restype = i32
+        L.exmy_encode_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, vp]
+        L.exmy_decode_scaled.restype = i32
+        L.exmy_decode_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, vp]
+        L.exmy_emulate_scaled.restype = i32
+        L.exmy_emulate_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp]
         L.exmy_status_string.restype = ctypes.c_char_p
         L.exmy_status_string.argtypes = [i32]
         _lib = L
@@ -375,4 +387,70 @@ def emulate_blocks(data, block, X, Y, max_exps):
     _meta_tensor(max_exps, data.numel(), block)
     _check(lib().exmy_emulate_blocks(data.data_ptr(), _dtype_enum(data), data.numel(), block, X, Y,
                                      max_exps.data_ptr(), _stream()))
+    return data
+
+
+# ------------------------------------------------------------ float scaling, max_exp = 127
+
+
+def _scale_tensor(scale, n, block, name="scales"):
+    _device_tensor(scale, name)
+    if scale.dtype != torch.float32 or scale.numel() != block_count(n, block):
+        raise ValueError("exmy: %s must be float32 with %d elements" % (name, block_count(n, block)))
+    return scale
+
+
+def block_scale(src, block, X, Y, out=None):
+    """exmy_block_scale: returns the float32 tensor of one scale per block."""
+    _device_tensor(src, "src")
+    n = src.numel()
+    if out is None:
+        out = torch.empty(block_count(n, block), dtype=torch.float32, device=src.device)
+    else:
+        _scale_tensor(out, n, block, "out")
+    _check(lib().exmy_block_scale(src.data_ptr(), _dtype_enum(src), n, block, X, Y, out.data_ptr(), _stream()))
+    return out
+
+
+def encode_scaled(src, block, X, Y, scales, out=None):
+    """exmy_encode_scaled: returns the packed uint8 tensor (``out`` if given)."""
+    _device_tensor(src, "src")
+    n = src.numel()
+    _scale_tensor(scales, n, block)
+    nbytes = packed_bytes(n, X, Y)
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.uint8, device=src.device)
+    else:
+        _device_tensor(out, "out")
+        if out.dtype != torch.uint8 or out.numel() != nbytes:
+            raise ValueError("exmy: out must be uint8 with %d elements" % nbytes)
+    _check(lib().exmy_encode_scaled(src.data_ptr(), _dtype_enum(src), n, block, X, Y, scales.data_ptr(),
+                                    out.data_ptr(), _stream()))
+    return out
+
+
+def decode_scaled(packed, dtype, n, block, X, Y, scales, out=None):
+    """exmy_decode_scaled: returns a flat tensor of ``n`` values of ``dtype``."""
+    _device_tensor(packed, "packed")
+    _scale_tensor(scales, n, block)
+    tdt = _torch_dtype(dtype)
+    if packed.dtype != torch.uint8 or packed.numel() != packed_bytes(n, X, Y):
+        raise ValueError("exmy: packed must be uint8 with %d elements" % packed_bytes(n, X, Y))
+    if out is None:
+        out = torch.empty(n, dtype=tdt, device=packed.device)
+    else:
+        _device_tensor(out, "out")
+        if out.dtype != tdt or out.numel() != n:
+            raise ValueError("exmy: out must be %s with %d elements" % (tdt, n))
+    _check(lib().exmy_decode_scaled(packed.data_ptr(), _dtype_enum(out), n, block, X, Y, scales.data_ptr(),
+                                    out.data_ptr(), _stream()))
+    return out
+
+
+def emulate_scaled(data, block, X, Y, scales):
+    """exmy_emulate_scaled: in place; returns ``data``."""
+    _device_tensor(data, "data")
+    _scale_tensor(scales, data.numel(), block)
+    _check(lib().exmy_emulate_scaled(data.data_ptr(), _dtype_enum(data), data.numel(), block, X, Y,
+                                     scales.data_ptr(), _stream()))
     return data

@@ -208,50 +208,63 @@ exmy_status_t run_batch(Op op, const exmy_tensor_t* tensors, size_t count, exmy_
   return flush() == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
 }
 
-enum class BlockOp { kMaxExp, kMaxExpRounded, kEncode, kDecode, kEmulate };
+enum class BlockOp { kMaxExp, kMaxExpRounded, kScale, kEncode, kDecode, kEmulate };
 
-// Shared validation and launch of the per-block-metadata entry points.  `elems` is
-// the bf16 / fp32 side, `packed` the plane side (unused by kMaxExp and kEmulate).
-exmy_status_t run_blocks(BlockOp op, const void* elems, const void* packed, exmy_dtype_t dt, uint64_t n,
-                         uint64_t block, int X, int Y, const uint8_t* meta, void* stream) {
+// Shared validation and launch of the per-block entry points.  `elems` is the
+// bf16 / fp32 side, `packed` the plane side (encode and decode only); `side` is
+// the per-block array: metadata bytes, or fp32 scales when `scaled` is set.
+exmy_status_t run_blocks(BlockOp op, bool scaled, const void* elems, const void* packed, exmy_dtype_t dt, uint64_t n,
+                         uint64_t block, int X, int Y, const void* side, void* stream) {
   BlockArgs args;
   const bool is_packed = op == BlockOp::kEncode || op == BlockOp::kDecode;
   if (exmy_status_t st = make_block_format(dt, X, Y, is_packed, op == BlockOp::kMaxExpRounded, &args.fc, &args.bc))
     return st;
+  bool wide_format = Y > 21;
+  args.vmax127 = 0.0f;
+  if (scaled) {
+    // codes of the max_exp = 127 format; a format whose only magnitude is 0 has nothing to scale
+    if (X == 0 && Y == 0) return EXMY_ERR_FORMAT;
+    if (exmy_status_t st = make_format(dt, X, Y, 127, is_packed, nullptr, &args.tc127, &wide_format)) return st;
+    uint32_t sat = args.tc127.sat_bits;
+    memcpy(&args.vmax127, &sat, 4);
+  }
   if (block < 8 || block % 8 || block > EXMY_MAX_BLOCK) return EXMY_ERR_BLOCK;
   if (n > EXMY_MAX_ELEMENTS) return EXMY_ERR_COUNT;
   if (n == 0) return EXMY_OK;
-  if (!elems || !meta || (is_packed && !packed)) return EXMY_ERR_NULL;
+  if (!elems || !side || (is_packed && !packed)) return EXMY_ERR_NULL;
   if (!aligned16(elems) || (is_packed && !aligned16(packed))) return EXMY_ERR_ALIGN;
+  if (scaled && (reinterpret_cast<uintptr_t>(side) & 3u)) return EXMY_ERR_ALIGN;
 
   args.n = n;
   args.n_blocks = (n + block - 1) / block;
   args.block_groups = (uint32_t)(block / 8);
   args.bi = make_block_index(args.block_groups);  // dispatchers rescale it to their kernel's units
-  args.meta = const_cast<uint8_t*>(meta);
+  args.meta = scaled ? nullptr : static_cast<uint8_t*>(const_cast<void*>(side));
+  args.scale = scaled ? static_cast<float*>(const_cast<void*>(side)) : nullptr;
   const hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = hipSuccess;
   switch (op) {
     case BlockOp::kMaxExp:
     case BlockOp::kMaxExpRounded:
+    case BlockOp::kScale:
       args.src = elems;
       args.dst = nullptr;
-      e = block_max_exp_dispatch(dt, args, s);
+      e = block_max_exp_dispatch(dt, args, scaled, s);
       break;
     case BlockOp::kEncode:
       args.src = elems;
       args.dst = const_cast<void*>(packed);
-      e = encode_blocks_dispatch(dt, 1 + X + Y, args, s);
+      e = encode_blocks_dispatch(dt, 1 + X + Y, args, scaled, s);
       break;
     case BlockOp::kDecode:
       args.src = packed;
       args.dst = const_cast<void*>(elems);
-      e = decode_blocks_dispatch(dt, 1 + X + Y, args, s);
+      e = decode_blocks_dispatch(dt, 1 + X + Y, args, scaled, s);
       break;
     case BlockOp::kEmulate:
       args.src = elems;
       args.dst = nullptr;
-      e = emulate_blocks_dispatch(dt, args, Y > 21, s);
+      e = emulate_blocks_dispatch(dt, args, wide_format, scaled, s);
       break;
   }
   return e == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
@@ -324,12 +337,12 @@ size_t exmy_block_count(uint64_t n, uint64_t block) { return block ? (size_t)((n
 
 exmy_status_t exmy_block_max_exp(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X,
                                  uint8_t* max_exp_dev, void* stream) {
-  return run_blocks(BlockOp::kMaxExp, src, nullptr, dt, n, block, X, 0, max_exp_dev, stream);
+  return run_blocks(BlockOp::kMaxExp, false, src, nullptr, dt, n, block, X, 0, max_exp_dev, stream);
 }
 
 exmy_status_t exmy_block_max_exp_after_rounding(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X,
                                                 int Y, uint8_t* max_exp_dev, void* stream) {
-  return run_blocks(BlockOp::kMaxExpRounded, src, nullptr, dt, n, block, X, Y, max_exp_dev, stream);
+  return run_blocks(BlockOp::kMaxExpRounded, false, src, nullptr, dt, n, block, X, Y, max_exp_dev, stream);
 }
 
 exmy_status_t exmy_encode_blocks_auto(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
@@ -340,23 +353,43 @@ exmy_status_t exmy_encode_blocks_auto(const void* src, exmy_dtype_t dt, uint64_t
   if (n && !dst_packed) return EXMY_ERR_NULL;
   if (n && !aligned16(dst_packed)) return EXMY_ERR_ALIGN;
   const BlockOp op = scheme == EXMY_MAX_EXP_AFTER_ROUNDING ? BlockOp::kMaxExpRounded : BlockOp::kMaxExp;
-  if (exmy_status_t st = run_blocks(op, src, nullptr, dt, n, block, X, Y, max_exp_dev, stream)) return st;
-  return run_blocks(BlockOp::kEncode, src, dst_packed, dt, n, block, X, Y, max_exp_dev, stream);
+  if (exmy_status_t st = run_blocks(op, false, src, nullptr, dt, n, block, X, Y, max_exp_dev, stream)) return st;
+  return run_blocks(BlockOp::kEncode, false, src, dst_packed, dt, n, block, X, Y, max_exp_dev, stream);
 }
 
 exmy_status_t exmy_encode_blocks(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
                                  const uint8_t* max_exp_dev, void* dst_packed, void* stream) {
-  return run_blocks(BlockOp::kEncode, src, dst_packed, dt, n, block, X, Y, max_exp_dev, stream);
+  return run_blocks(BlockOp::kEncode, false, src, dst_packed, dt, n, block, X, Y, max_exp_dev, stream);
 }
 
 exmy_status_t exmy_decode_blocks(const void* src_packed, exmy_dtype_t dt_out, uint64_t n, uint64_t block, int X, int Y,
                                  const uint8_t* max_exp_dev, void* dst, void* stream) {
-  return run_blocks(BlockOp::kDecode, dst, src_packed, dt_out, n, block, X, Y, max_exp_dev, stream);
+  return run_blocks(BlockOp::kDecode, false, dst, src_packed, dt_out, n, block, X, Y, max_exp_dev, stream);
 }
 
 exmy_status_t exmy_emulate_blocks(void* data_inout, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
                                   const uint8_t* max_exp_dev, void* stream) {
-  return run_blocks(BlockOp::kEmulate, data_inout, nullptr, dt, n, block, X, Y, max_exp_dev, stream);
+  return run_blocks(BlockOp::kEmulate, false, data_inout, nullptr, dt, n, block, X, Y, max_exp_dev, stream);
+}
+
+exmy_status_t exmy_block_scale(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
+                               float* scale_dev, void* stream) {
+  return run_blocks(BlockOp::kScale, true, src, nullptr, dt, n, block, X, Y, scale_dev, stream);
+}
+
+exmy_status_t exmy_encode_scaled(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
+                                 const float* scale_dev, void* dst_packed, void* stream) {
+  return run_blocks(BlockOp::kEncode, true, src, dst_packed, dt, n, block, X, Y, scale_dev, stream);
+}
+
+exmy_status_t exmy_decode_scaled(const void* src_packed, exmy_dtype_t dt_out, uint64_t n, uint64_t block, int X, int Y,
+                                 const float* scale_dev, void* dst, void* stream) {
+  return run_blocks(BlockOp::kDecode, true, dst, src_packed, dt_out, n, block, X, Y, scale_dev, stream);
+}
+
+exmy_status_t exmy_emulate_scaled(void* data_inout, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
+                                  const float* scale_dev, void* stream) {
+  return run_blocks(BlockOp::kEmulate, true, data_inout, nullptr, dt, n, block, X, Y, scale_dev, stream);
 }
 
 int exmy_max_exp_from_histogram(const uint64_t* hist256_host, double coverage) {

@@ -105,6 +105,12 @@ struct BlockArgs {
   const void* src;      // encode / emulate: elements; decode: packed planes
   void* dst;            // encode: packed planes; decode: elements; emulate: unused
   uint8_t* meta;        // one byte per block (read; written by the max-exponent kernel)
+  // Float scaling (Section 2 "Metadata": an additional float32 scaling factor;
+  // Section 2.1: "float scaling with maximum exponent 127"): one fp32 scale per
+  // block instead of the metadata byte, with the constants of max_exp = 127.
+  float* scale;
+  TensorConsts tc127;
+  float vmax127;        // largest value of the format with max_exp = 127
   uint64_t n;           // elements
   uint64_t n_blocks;    // ceil(n / block)
   uint32_t block_groups;  // block / 8
@@ -275,6 +281,37 @@ __device__ __forceinline__ uint32_t lane_block(uint32_t j, const BlockIndex& bi)
   if (bi.log2 != kNotPow2) return j >> bi.log2;
   if (bi.size >= kTile) return j >= bi.size ? 1u : 0u;  // a tile straddles at most one boundary
   return __umulhi(j, bi.recip32);                       // j < 2 * kTile
+}
+
+// The datum of block number `block` of the array behind `r`: a metadata byte, or
+// the bits of an fp32 scale.
+template <bool kScaled>
+__device__ __forceinline__ uint32_t load_block_datum(rsrc_t r, uint32_t block) {
+  if constexpr (kScaled) return __builtin_amdgcn_raw_buffer_load_b32(r, block * 4u, 0, 0);
+  return __builtin_amdgcn_raw_buffer_load_b8(r, block, 0, 0);
+}
+
+// (mask & a) | (~mask & b) in one instruction.
+__device__ __forceinline__ uint32_t bit_select(uint32_t mask, uint32_t a, uint32_t b) {
+  uint32_t d;
+  asm("v_bfi_b32 %0, %1, %2, %3" : "=v"(d) : "v"(mask), "v"(a), "v"(b));
+  return d;
+}
+
+// Float scaling, encode side: fp32-position bits of x * inv with the sign bit of
+// x itself (a NaN keeps its sign whatever the multiplier does with it).
+__device__ __forceinline__ uint32_t scaled_bits(uint32_t u, float inv) {
+  return bit_select(0x7FFFFFFFu, as_u32(__builtin_fabsf(as_f32(u)) * inv), u);
+}
+
+// Float scaling, decode side: bits of |v| * scale (v finite, scale > 0) under the
+// sign of v.  kBf16: rounded to nearest even at bit 16, the lower half then to be
+// dropped (a carry may run up to the Inf pattern, as in the library conversion).
+template <bool kBf16>
+__device__ __forceinline__ uint32_t rescaled_bits(uint32_t v, float scale) {
+  uint32_t m = as_u32(__builtin_fabsf(as_f32(v)) * scale);
+  if constexpr (kBf16) m += 0x7FFFu + ((m >> 16) & 1u);
+  return bit_select(0x7FFFFFFFu, m, v);
 }
 
 // ---------------------------------------------------------------- planes

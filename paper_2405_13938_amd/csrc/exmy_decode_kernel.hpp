@@ -103,17 +103,21 @@ __device__ __forceinline__ uint32_t element_bits(const UnitWords<W>& uw, int j, 
 }
 
 // Values of one unit, stored to 16-byte vector lane_unit + tile_unit of `out`.
-template <typename T, int W, bool kX8, bool kNT>
+// kScaled (float scaling): every value is multiplied by `scale` on the way out.
+template <typename T, int W, bool kX8, bool kNT, bool kScaled = false>
 __device__ __forceinline__ void decode_unit(const UnitWords<W>& uw, const FormatConsts& fc, const TensorConsts& tc,
-                                            rsrc_t out, uint32_t lane_unit, uint32_t tile_unit) {
+                                            rsrc_t out, uint32_t lane_unit, uint32_t tile_unit, float scale = 1.0f) {
   constexpr int E = 16 / sizeof(T);
   uint32_t b[E];
 #pragma unroll
-  for (int j = 0; j < E; ++j) b[j] = element_bits<W, kX8>(uw, j, fc, tc);
+  for (int j = 0; j < E; ++j) {
+    b[j] = element_bits<W, kX8>(uw, j, fc, tc);
+    if constexpr (kScaled) b[j] = rescaled_bits<sizeof(T) == 2>(b[j], scale);
+  }
   if constexpr (sizeof(T) == 4) {
     store16<kNT>(out, lane_unit * 16, tile_unit * 16, make_uint4(b[0], b[1], b[2], b[3]));
   } else {
-    // every value is exact in bf16: keep the upper halves
+    // every value is exact in bf16 (or has just been rounded to it): keep the upper halves
     uint4 o;
     o.x = __builtin_amdgcn_perm(b[1], b[0], 0x07060302u);
     o.y = __builtin_amdgcn_perm(b[3], b[2], 0x07060302u);
@@ -229,7 +233,9 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(const BatchArgs batch) {
 // Per-block metadata: flat tiles with a per-lane metadata lookup, as in the
 // encoder.  A unit is one lane's 16 bytes of output (E elements).
 
-template <typename T, int W, int kBlock, int kUnroll, bool kNT>
+// kScaled: per-block fp32 scales and the max_exp = 127 format instead of per-block
+// metadata bytes.
+template <typename T, int W, int kBlock, int kUnroll, bool kNT, bool kScaled>
 __global__ __launch_bounds__(kBlock) void decode_blocks_kernel(const BlockArgs args) {
   constexpr uint32_t TU = kBlock * kUnroll;
   constexpr int E = 16 / sizeof(T);
@@ -254,29 +260,36 @@ __global__ __launch_bounds__(kBlock) void decode_blocks_kernel(const BlockArgs a
     PlaneSrc<W> ps;
     make_plane_src<W, E>(src, G, u0, ps);
     const rsrc_t out = make_rsrc(reinterpret_cast<uint4*>(dst) + u0);
-    const rsrc_t mt = make_rsrc(meta + blk0);
+    const rsrc_t mt = kScaled ? make_rsrc(args.scale + blk0) : make_rsrc(meta + blk0);
     TileWords<W, kUnroll> tw;
-    uint32_t me[kUnroll];
+    uint32_t me[kUnroll];  // the block's metadatum, or the bits of its scale
     if (tile < full_tiles) {
       load_tile<W, E, kBlock, kUnroll, false>(ps, 0, 0, tw);
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r)
-        me[r] = __builtin_amdgcn_raw_buffer_load_b8(mt, lane_block<TU>(off + r * kBlock + threadIdx.x, bi), 0, 0);
+        me[r] = load_block_datum<kScaled>(mt, lane_block<TU>(off + r * kBlock + threadIdx.x, bi));
 #pragma unroll
-      for (int r = 0; r < kUnroll; ++r)
-        decode_unit<T, W, false, kNT>(tw.u[r], fc, derive_tc(me[r], bc), out, threadIdx.x, r * kBlock);
+      for (int r = 0; r < kUnroll; ++r) {
+        if constexpr (kScaled)
+          decode_unit<T, W, false, kNT, true>(tw.u[r], fc, args.tc127, out, threadIdx.x, r * kBlock, as_f32(me[r]));
+        else
+          decode_unit<T, W, false, kNT>(tw.u[r], fc, derive_tc(me[r], bc), out, threadIdx.x, r * kBlock);
+      }
     } else {
       load_tile<W, E, kBlock, kUnroll, true>(ps, 0, rem_units, tw);
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r)
         me[r] = (r * kBlock + threadIdx.x < rem_units)
-                    ? (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(
-                          mt, lane_block<TU>(off + r * kBlock + threadIdx.x, bi), 0, 0)
-                    : bc.meta_lo;
+                    ? load_block_datum<kScaled>(mt, lane_block<TU>(off + r * kBlock + threadIdx.x, bi))
+                    : 0u;
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r) {
-        if (r * kBlock + threadIdx.x < rem_units)
-          decode_unit<T, W, false, kNT>(tw.u[r], fc, derive_tc(me[r], bc), out, threadIdx.x, r * kBlock);
+        if (r * kBlock + threadIdx.x < rem_units) {
+          if constexpr (kScaled)
+            decode_unit<T, W, false, kNT, true>(tw.u[r], fc, args.tc127, out, threadIdx.x, r * kBlock, as_f32(me[r]));
+          else
+            decode_unit<T, W, false, kNT>(tw.u[r], fc, derive_tc(me[r], bc), out, threadIdx.x, r * kBlock);
+        }
       }
     }
   }
@@ -285,8 +298,13 @@ __global__ __launch_bounds__(kBlock) void decode_blocks_kernel(const BlockArgs a
   if (blockIdx.x == 0 && threadIdx.x < E) {
     const uint64_t i = Ufull * E + threadIdx.x;
     if (i < n) {
-      const TensorConsts tc = derive_tc(meta[args.n_blocks - 1], bc);
-      const uint32_t b = element_bits_slow<W, false>(src, G, i, fc, tc);
+      uint32_t b;
+      if constexpr (kScaled) {
+        b = element_bits_slow<W, false>(src, G, i, fc, args.tc127);
+        b = rescaled_bits<sizeof(T) == 2>(b, args.scale[args.n_blocks - 1]);
+      } else {
+        b = element_bits_slow<W, false>(src, G, i, fc, derive_tc(meta[args.n_blocks - 1], bc));
+      }
       if constexpr (sizeof(T) == 4)
         reinterpret_cast<uint32_t*>(dst)[i] = b;
       else

@@ -10,28 +10,34 @@
 namespace exmy {
 namespace emu {
 
-// fp32 bits of the emulated value of the element with fp32-position bits u.
+// fp32 bits of the eXmY value nearest to the magnitude with fp32 bits a0 (sign
+// clear); anything above the largest value, Inf and NaN patterns included, gives
+// the largest value.
 //
 // Same rounding as the encoder (magic addend with the ulp of the target
 // quantum), but the rounded magnitude is recovered as a float by subtracting
 // the addend again instead of being re-biased into a code.
 template <bool kWide>
-__device__ __forceinline__ uint32_t emulate_bits(uint32_t u, const FormatConsts& fc, const TensorConsts& tc) {
-  const uint32_t a0 = u & 0x7FFFFFFFu;
+__device__ __forceinline__ uint32_t emulate_magnitude(uint32_t a0, const FormatConsts& fc, const TensorConsts& tc) {
   const uint32_t a = min(a0, tc.sat_bits);
   const uint32_t te = max(a, tc.emin_bits) & 0x7F800000u;
-  uint32_t r;
   if constexpr (!kWide) {
     const float m = as_f32(te) * fc.magic_scale;
     const float s = as_f32(a) + m;
-    r = as_u32(s - m);
+    return as_u32(s - m);
   } else {
     const uint32_t hi = ((te >> 23) + (uint32_t)fc.wide_exp) << 20;
     const double m = __hiloint2double((int)hi, 0);
     const double s = (double)as_f32(a) + m;
-    r = as_u32((float)(s - m));
+    return as_u32((float)(s - m));
   }
-  r |= u & 0x80000000u;
+}
+
+// fp32 bits of the emulated value of the element with fp32-position bits u.
+template <bool kWide>
+__device__ __forceinline__ uint32_t emulate_bits(uint32_t u, const FormatConsts& fc, const TensorConsts& tc) {
+  const uint32_t a0 = u & 0x7FFFFFFFu;
+  const uint32_t r = emulate_magnitude<kWide>(a0, fc, tc) | (u & 0x80000000u);
   return a0 >= 0x7F800000u ? u : r;  // Inf / NaN pass through
 }
 
@@ -109,8 +115,52 @@ __device__ __forceinline__ uint4 emulate_vector_meta(uint4 v, uint32_t me, bool 
   return emulate_vector<T, false>(v, fc, tc);
 }
 
+// Float scaling: the element is multiplied by the reciprocal of its block's scale,
+// rounded in the max_exp = 127 format and multiplied back; the result is rounded
+// to the container (bf16: to nearest even).  Inf / NaN pass through.
+template <bool kWide, bool kBf16>
+__device__ __forceinline__ uint32_t emulate_scaled_bits(uint32_t u, float inv, float scale, const FormatConsts& fc,
+                                                        const TensorConsts& tc127) {
+  const uint32_t a0 = as_u32(__builtin_fabsf(as_f32(u)) * inv);  // an overflow to Inf saturates like any large value
+  const uint32_t r = emulate_magnitude<kWide>(a0, fc, tc127) | (u & 0x80000000u);
+  return (u & 0x7FFFFFFFu) >= 0x7F800000u ? u : rescaled_bits<kBf16>(r, scale);
+}
+
+template <typename T>
+__device__ __forceinline__ uint4 emulate_vector_scaled(uint4 v, uint32_t scale_bits, bool wide_format,
+                                                       const FormatConsts& fc, const TensorConsts& tc127) {
+  const float scale = as_f32(scale_bits);
+  const float inv = 1.0f / scale;
+  uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  if (wide_format) {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if constexpr (sizeof(T) == 4) {
+        w[k] = emulate_scaled_bits<true, false>(w[k], inv, scale, fc, tc127);
+      } else {
+        const uint32_t lo = emulate_scaled_bits<true, true>(w[k] << 16, inv, scale, fc, tc127);
+        const uint32_t hi = emulate_scaled_bits<true, true>(w[k] & 0xFFFF0000u, inv, scale, fc, tc127);
+        w[k] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
+      }
+    }
+  } else {
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      if constexpr (sizeof(T) == 4) {
+        w[k] = emulate_scaled_bits<false, false>(w[k], inv, scale, fc, tc127);
+      } else {
+        const uint32_t lo = emulate_scaled_bits<false, true>(w[k] << 16, inv, scale, fc, tc127);
+        const uint32_t hi = emulate_scaled_bits<false, true>(w[k] & 0xFFFF0000u, inv, scale, fc, tc127);
+        w[k] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
+      }
+    }
+  }
+  return make_uint4(w[0], w[1], w[2], w[3]);
+}
+
 // wide_format: the format itself needs the fp64 path (Y > 21), whatever the metadata.
-template <typename T, int kBlock, int kUnroll, bool kNT>
+// kScaled: per-block fp32 scales instead of per-block metadata bytes.
+template <typename T, int kBlock, int kUnroll, bool kNT, bool kScaled>
 __global__ __launch_bounds__(kBlock) void emulate_blocks_kernel(const BlockArgs args, bool wide_format) {
   constexpr int kPer = 16 / sizeof(T);
   constexpr uint32_t TV = kBlock * kUnroll;
@@ -130,7 +180,7 @@ __global__ __launch_bounds__(kBlock) void emulate_blocks_kernel(const BlockArgs 
     uint32_t off;
     tile_first_block(v0, bi, blk0, off);
     const rsrc_t buf = make_rsrc(reinterpret_cast<uint4*>(data) + v0);
-    const rsrc_t mt = make_rsrc(meta + blk0);
+    const rsrc_t mt = kScaled ? make_rsrc(args.scale + blk0) : make_rsrc(meta + blk0);
     const uint64_t left = V - v0;
     const uint32_t rem = left < TV ? (uint32_t)left : TV;
     uint4 v[kUnroll];
@@ -139,30 +189,46 @@ __global__ __launch_bounds__(kBlock) void emulate_blocks_kernel(const BlockArgs 
     for (int r = 0; r < kUnroll; ++r) {
       if (r * kBlock + threadIdx.x < rem) {
         v[r] = load16<kNT>(buf, lane_off, r * kBlock * 16);
-        me[r] = __builtin_amdgcn_raw_buffer_load_b8(mt, lane_block<TV>(off + r * kBlock + threadIdx.x, bi), 0, 0);
+        me[r] = load_block_datum<kScaled>(mt, lane_block<TV>(off + r * kBlock + threadIdx.x, bi));
       }
     }
 #pragma unroll
-    for (int r = 0; r < kUnroll; ++r)
-      if (r * kBlock + threadIdx.x < rem)
-        store16<kNT>(buf, lane_off, r * kBlock * 16, emulate_vector_meta<T>(v[r], me[r], wide_format, fc, bc));
+    for (int r = 0; r < kUnroll; ++r) {
+      if (r * kBlock + threadIdx.x < rem) {
+        if constexpr (kScaled)
+          store16<kNT>(buf, lane_off, r * kBlock * 16,
+                       emulate_vector_scaled<T>(v[r], me[r], wide_format, fc, args.tc127));
+        else
+          store16<kNT>(buf, lane_off, r * kBlock * 16, emulate_vector_meta<T>(v[r], me[r], wide_format, fc, bc));
+      }
+    }
   }
 
   // Elements past the last whole 16-byte vector belong to the last block.
   if (blockIdx.x == 0 && threadIdx.x < kPer) {
     const uint64_t i = V * kPer + threadIdx.x;
     if (i < n) {
-      const uint32_t me = meta[args.n_blocks - 1];
-      const TensorConsts tc = derive_tc(me, bc);
-      const bool wide = __builtin_amdgcn_ballot_w64(wide_format || me > bc.wide_above) != 0;
-      if constexpr (sizeof(T) == 4) {
-        uint32_t* p = reinterpret_cast<uint32_t*>(data) + i;
-        *p = wide ? emulate_bits<true>(*p, fc, tc) : emulate_bits<false>(*p, fc, tc);
+      uint32_t u;
+      if constexpr (sizeof(T) == 4)
+        u = reinterpret_cast<uint32_t*>(data)[i];
+      else
+        u = (uint32_t) reinterpret_cast<uint16_t*>(data)[i] << 16;
+      uint32_t r;
+      if constexpr (kScaled) {
+        const float scale = args.scale[args.n_blocks - 1];
+        const float inv = 1.0f / scale;
+        r = wide_format ? emulate_scaled_bits<true, sizeof(T) == 2>(u, inv, scale, fc, args.tc127)
+                        : emulate_scaled_bits<false, sizeof(T) == 2>(u, inv, scale, fc, args.tc127);
       } else {
-        uint16_t* p = reinterpret_cast<uint16_t*>(data) + i;
-        const uint32_t u = (uint32_t)*p << 16;
-        *p = (uint16_t)((wide ? emulate_bits<true>(u, fc, tc) : emulate_bits<false>(u, fc, tc)) >> 16);
+        const uint32_t me = meta[args.n_blocks - 1];
+        const TensorConsts tc = derive_tc(me, bc);
+        const bool wide = __builtin_amdgcn_ballot_w64(wide_format || me > bc.wide_above) != 0;
+        r = wide ? emulate_bits<true>(u, fc, tc) : emulate_bits<false>(u, fc, tc);
       }
+      if constexpr (sizeof(T) == 4)
+        reinterpret_cast<uint32_t*>(data)[i] = r;
+      else
+        reinterpret_cast<uint16_t*>(data)[i] = (uint16_t)(r >> 16);
     }
   }
 }
@@ -200,10 +266,19 @@ __device__ __forceinline__ int32_t element_exp_key(const T* p) {
   return (int32_t)((u & 0x7FFFFFFFu) + 0x00800000u);
 }
 
-__device__ __forceinline__ uint8_t key_to_meta(int32_t key, const BlockConsts& bc) {
+// Result of one block from the key of its largest finite magnitude.  kScale:
+// the fp32 scale that maps that magnitude onto the largest value of the
+// max_exp = 127 format (not below the smallest normal float); else the metadatum.
+template <bool kScale>
+__device__ __forceinline__ void store_block_result(const BlockArgs& args, uint64_t block, int32_t key) {
   uint32_t a = key > 0 ? (uint32_t)key - 0x00800000u : 0u;  // bits of the largest finite magnitude (0 if none)
-  a += bc.round_half + ((a >> bc.round_shift) & bc.round_odd);  // "after rounding"; may carry up to exponent 255
-  return (uint8_t)min(max(a >> 23, bc.meta_lo), bc.meta_hi);
+  if constexpr (kScale) {
+    args.scale[block] = fmaxf(as_f32(a) / args.vmax127, as_f32(0x00800000u));
+  } else {
+    const BlockConsts& bc = args.bc;
+    a += bc.round_half + ((a >> bc.round_shift) & bc.round_odd);  // "after rounding"; may carry up to exponent 255
+    args.meta[block] = (uint8_t)min(max(a >> 23, bc.meta_lo), bc.meta_hi);
+  }
 }
 
 // Maximum over the 2^lg lanes (lg <= 6) that share all lane-index bits above the
@@ -223,15 +298,13 @@ __device__ __forceinline__ int32_t max_over_lanes(int32_t m, uint32_t lg) {
 
 // Blocks of 2^lg vectors, lg <= 6: flat tiles of kBlock * kUnroll vectors, one
 // vector per lane and step; the lanes of a block combine with a butterfly.
-template <typename T, int kBlock, int kUnroll>
+template <typename T, int kBlock, int kUnroll, bool kScale>
 __global__ __launch_bounds__(kBlock) void block_max_exp_small_kernel(const BlockArgs args) {
   constexpr int kPer = 16 / sizeof(T);
   constexpr uint32_t TV = kBlock * kUnroll;
   const T* __restrict__ src = static_cast<const T*>(args.src);
   const uint4* __restrict__ src4 = static_cast<const uint4*>(args.src);
-  uint8_t* __restrict__ meta = args.meta;
   const uint64_t n = args.n;
-  const BlockConsts bc = args.bc;
   const uint32_t lg = args.bi.log2;  // of vectors per block
   const uint64_t V = n / kPer;                  // whole vectors
   const uint64_t Vall = (n + kPer - 1) / kPer;  // the last one may be partial
@@ -255,14 +328,14 @@ __global__ __launch_bounds__(kBlock) void block_max_exp_small_kernel(const Block
     for (int r = 0; r < kUnroll; ++r) {
       const uint64_t i = v0 + r * kBlock + threadIdx.x;
       const int32_t mm = max_over_lanes(m[r], lg);
-      if (i < Vall && (threadIdx.x & ((1u << lg) - 1u)) == 0) meta[i >> lg] = key_to_meta(mm, bc);
+      if (i < Vall && (threadIdx.x & ((1u << lg) - 1u)) == 0) store_block_result<kScale>(args, i >> lg, mm);
     }
   }
 }
 
 // Any other block size: a team of kTeam lanes per block, kTeam = 64 (a wavefront;
 // blocks of up to about a thousand vectors) or kTeam = kBlock (the workgroup).
-template <typename T, int kBlock, int kTeam>
+template <typename T, int kBlock, int kTeam, bool kScale>
 __global__ __launch_bounds__(kBlock) void block_max_exp_team_kernel(const BlockArgs args) {
   static_assert(kTeam == 64 || kTeam == kBlock, "a team is a wavefront or the workgroup");
   constexpr int kPer = 16 / sizeof(T);
@@ -270,9 +343,7 @@ __global__ __launch_bounds__(kBlock) void block_max_exp_team_kernel(const BlockA
   __shared__ int32_t part[kBlock / 64];
   const T* __restrict__ src = static_cast<const T*>(args.src);
   const uint4* __restrict__ src4 = static_cast<const uint4*>(args.src);
-  uint8_t* __restrict__ meta = args.meta;
   const uint64_t n = args.n;
-  const BlockConsts bc = args.bc;
   const uint64_t V = n / kPer;  // whole vectors
   const uint32_t block_vecs = args.bi.size;
   const uint32_t team = kTeams > 1 ? __builtin_amdgcn_readfirstlane(threadIdx.x >> 6) : 0;
@@ -303,14 +374,14 @@ __global__ __launch_bounds__(kBlock) void block_max_exp_team_kernel(const BlockA
     }
     m = max_over_lanes(m, 6);
     if constexpr (kTeam == 64) {
-      if (lane == 0 && row < args.n_blocks) meta[row] = key_to_meta(m, bc);
+      if (lane == 0 && row < args.n_blocks) store_block_result<kScale>(args, row, m);
     } else {
       if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = m;
       __syncthreads();
       if (threadIdx.x == 0) {
 #pragma unroll
         for (int w = 1; w < kBlock / 64; ++w) m = max(m, part[w]);
-        meta[row] = key_to_meta(m, bc);
+        store_block_result<kScale>(args, row, m);
       }
       __syncthreads();  // part is reused by the next block
     }

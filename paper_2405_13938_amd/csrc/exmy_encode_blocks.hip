@@ -20,23 +20,23 @@ struct Shape<float> {
   static constexpr int kUnroll = 1;
 };
 
-template <typename T, int W>
+template <typename T, int W, bool kScaled>
 hipError_t launch(BlockArgs args, hipStream_t stream) {
   using S = Shape<T>;
   const uint64_t tile_groups = (uint64_t)S::kBlock * S::kUnroll;
   const uint64_t tiles = (args.n / 8 + tile_groups - 1) / tile_groups;
   args.bi = make_block_index(args.block_groups);
-  hipLaunchKernelGGL((enc::encode_blocks_kernel<T, W, S::kBlock, S::kUnroll, true>),
+  hipLaunchKernelGGL((enc::encode_blocks_kernel<T, W, S::kBlock, S::kUnroll, true, kScaled>),
                      dim3(grid_for_chunks(tiles, 1, S::kBlock)), dim3(S::kBlock), 0, stream, args);
   return hipGetLastError();
 }
 
-template <typename T>
+template <typename T, bool kScaled>
 hipError_t dispatch_w(int W, const BlockArgs& args, hipStream_t stream) {
   switch (W) {
 #define EXMY_CASE(w) \
   case w:            \
-    return launch<T, w>(args, stream);
+    return launch<T, w, kScaled>(args, stream);
     EXMY_CASE(1) EXMY_CASE(2) EXMY_CASE(3) EXMY_CASE(4) EXMY_CASE(5) EXMY_CASE(6) EXMY_CASE(7) EXMY_CASE(8)
     EXMY_CASE(9) EXMY_CASE(10) EXMY_CASE(11) EXMY_CASE(12) EXMY_CASE(13) EXMY_CASE(14) EXMY_CASE(15) EXMY_CASE(16)
 #undef EXMY_CASE
@@ -46,8 +46,10 @@ hipError_t dispatch_w(int W, const BlockArgs& args, hipStream_t stream) {
 
 }  // namespace
 
-hipError_t encode_blocks_dispatch(exmy_dtype_t dt, int W, const BlockArgs& args, hipStream_t stream) {
-  return dt == EXMY_F32 ? dispatch_w<float>(W, args, stream) : dispatch_w<uint16_t>(W, args, stream);
+hipError_t encode_blocks_dispatch(exmy_dtype_t dt, int W, const BlockArgs& args, bool scaled, hipStream_t stream) {
+  if (scaled)
+    return dt == EXMY_F32 ? dispatch_w<float, true>(W, args, stream) : dispatch_w<uint16_t, true>(W, args, stream);
+  return dt == EXMY_F32 ? dispatch_w<float, false>(W, args, stream) : dispatch_w<uint16_t, false>(W, args, stream);
 }
 
 }  // namespace exmy

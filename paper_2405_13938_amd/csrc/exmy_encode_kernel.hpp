@@ -304,7 +304,20 @@ __device__ __forceinline__ void encode_group_meta(const uint32_t u[8], uint32_t 
     encode_group<W, false>(u, fc, tc, pd, lane_group, tile_group);
 }
 
-template <typename T, int W, int kBlock, int kUnroll, bool kNT>
+// Float scaling: the group's elements are multiplied by the reciprocal of their
+// block's scale and take the codes of the max_exp = 127 format.
+template <int W>
+__device__ __forceinline__ void encode_group_scaled(uint32_t u[8], uint32_t scale_bits, const FormatConsts& fc,
+                                                    const TensorConsts& tc127, const PlaneDst<W>& pd,
+                                                    uint32_t lane_group, uint32_t tile_group) {
+  const float inv = 1.0f / as_f32(scale_bits);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) u[j] = scaled_bits(u[j], inv);
+  encode_group<W, false>(u, fc, tc127, pd, lane_group, tile_group);
+}
+
+// kScaled: per-block fp32 scales instead of per-block metadata bytes.
+template <typename T, int W, int kBlock, int kUnroll, bool kNT, bool kScaled>
 __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs args) {
   constexpr uint32_t TG = kBlock * kUnroll;
   constexpr int kLoads = TileRegs<T, kUnroll>::kLoads;
@@ -327,36 +340,40 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
     uint32_t off;
     tile_first_block(g0, bi, blk0, off);
     const rsrc_t src = make_rsrc(src4 + g0 * kLoads);
-    const rsrc_t mt = make_rsrc(meta + blk0);
+    const rsrc_t mt = kScaled ? make_rsrc(args.scale + blk0) : make_rsrc(meta + blk0);
     PlaneDst<W> pd;
     make_plane_dst<W>(dst, G, g0, pd);
     TileRegs<T, kUnroll> regs;
-    uint32_t me[kUnroll];
+    uint32_t me[kUnroll];  // the block's metadatum, or the bits of its scale
     if (tile < full_tiles) {
       load_tile<T, kBlock, kUnroll, kNT, false>(src, 0, 0, regs);
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r)
-        me[r] = __builtin_amdgcn_raw_buffer_load_b8(mt, lane_block<TG>(off + r * kBlock + threadIdx.x, bi), 0, 0);
+        me[r] = load_block_datum<kScaled>(mt, lane_block<TG>(off + r * kBlock + threadIdx.x, bi));
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r) {
         uint32_t u[8];
         group_bits<T>(regs.v[r], u);
-        encode_group_meta<W>(u, me[r], fc, bc, pd, threadIdx.x, r * kBlock);
+        if constexpr (kScaled)
+          encode_group_scaled<W>(u, me[r], fc, args.tc127, pd, threadIdx.x, r * kBlock);
+        else
+          encode_group_meta<W>(u, me[r], fc, bc, pd, threadIdx.x, r * kBlock);
       }
     } else {
       load_tile<T, kBlock, kUnroll, kNT, true>(src, 0, rem_groups, regs);
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r)
-        me[r] = (r * kBlock + threadIdx.x < rem_groups)
-                    ? (uint32_t)__builtin_amdgcn_raw_buffer_load_b8(
-                          mt, lane_block<TG>(off + r * kBlock + threadIdx.x, bi), 0, 0)
-                    : bc.meta_lo;
+        if (r * kBlock + threadIdx.x < rem_groups)
+          me[r] = load_block_datum<kScaled>(mt, lane_block<TG>(off + r * kBlock + threadIdx.x, bi));
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r) {
         if (r * kBlock + threadIdx.x < rem_groups) {  // the rounding-variant vote is among the lanes that get here
           uint32_t u[8];
           group_bits<T>(regs.v[r], u);
-          encode_group_meta<W>(u, me[r], fc, bc, pd, threadIdx.x, r * kBlock);
+          if constexpr (kScaled)
+            encode_group_scaled<W>(u, me[r], fc, args.tc127, pd, threadIdx.x, r * kBlock);
+          else
+            encode_group_meta<W>(u, me[r], fc, bc, pd, threadIdx.x, r * kBlock);
         }
       }
     }
@@ -379,7 +396,10 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
     }
     PlaneDst<W> pd;
     make_plane_dst<W>(dst, G, Gfull, pd);
-    encode_group_meta<W>(u, meta[args.n_blocks - 1], fc, bc, pd, 0, 0);
+    if constexpr (kScaled)
+      encode_group_scaled<W>(u, as_u32(args.scale[args.n_blocks - 1]), fc, args.tc127, pd, 0, 0);
+    else
+      encode_group_meta<W>(u, meta[args.n_blocks - 1], fc, bc, pd, 0, 0);
   }
 }
 

@@ -37,10 +37,13 @@ hipError_t decode_dispatch(exmy_dtype_t dt, int W, bool x8, const BatchArgs& arg
 hipError_t emulate_dispatch(exmy_dtype_t dt, bool wide, void* data, uint64_t n, const FormatConsts& fc,
                             const TensorConsts& tc, hipStream_t stream);
 // Per-block metadata (args.bi is filled in by the dispatcher from args.block_groups).
-hipError_t encode_blocks_dispatch(exmy_dtype_t dt, int W, const BlockArgs& args, hipStream_t stream);
-hipError_t decode_blocks_dispatch(exmy_dtype_t dt, int W, const BlockArgs& args, hipStream_t stream);
-hipError_t emulate_blocks_dispatch(exmy_dtype_t dt, const BlockArgs& args, bool wide_format, hipStream_t stream);
-hipError_t block_max_exp_dispatch(exmy_dtype_t dt, const BlockArgs& args, hipStream_t stream);
+// `scaled` / `scale`: the float-scaling variants, which read or write args.scale
+// instead of args.meta.
+hipError_t encode_blocks_dispatch(exmy_dtype_t dt, int W, const BlockArgs& args, bool scaled, hipStream_t stream);
+hipError_t decode_blocks_dispatch(exmy_dtype_t dt, int W, const BlockArgs& args, bool scaled, hipStream_t stream);
+hipError_t emulate_blocks_dispatch(exmy_dtype_t dt, const BlockArgs& args, bool wide_format, bool scaled,
+                                   hipStream_t stream);
+hipError_t block_max_exp_dispatch(exmy_dtype_t dt, const BlockArgs& args, bool scale, hipStream_t stream);
 hipError_t histogram_dispatch(exmy_dtype_t dt, const void* src, uint64_t n, uint64_t* hist, hipStream_t stream);
 
 }  // namespace exmy

@@ -1,0 +1,155 @@
+"""Parity of the float-scaling entry points (through the C ABI) with the CPU oracle,
+tolerance 0: scales (fp32 bit patterns), packed bytes, decoded and emulated bits."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2405_13938_amd as exmy
+from oracle import exmy_oracle as O
+from paper_2405_13938_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+THREADS = min(O.default_threads(), 16)
+
+
+def odt(t):
+    return O.F32 if t.dtype == torch.float32 else O.BF16
+
+
+def ubits(a):
+    return a.view(np.uint32) if a.dtype == np.float32 else a
+
+
+def tbits(t):
+    return ubits(synth.bits_numpy(t))
+
+
+def formats_of_width(W, dtype):
+    P = 23 if dtype == torch.float32 else 7
+    return [(X, W - 1 - X) for X in range(0, min(W - 1, 7) + 1)
+            if W - 1 - X <= (P if X >= 1 else P + 1) and (X, W - 1 - X) != (0, 0)]
+
+
+def scales_for(kind, host, block, X, Y, seed=0):
+    s = O.block_scale(host, block, X, Y)
+    if kind == "block_scale":
+        return s
+    rng = np.random.default_rng(seed + block)
+    if kind == "perturbed":  # any finite scale >= FLT_MIN is valid input: up to 4x off either way, and extremes
+        f = np.exp2(rng.uniform(-2.0, 2.0, s.size)).astype(np.float32)
+        out = np.clip(s.astype(np.float64) * f, 2.0 ** -126, 3.0e38).astype(np.float32)
+        out[rng.random(s.size) < 0.02] = np.float32(2.0 ** -126)
+        out[rng.random(s.size) < 0.02] = np.float32(3.0e38)
+        out[rng.random(s.size) < 0.02] = np.float32(1.0)
+        return out
+    raise ValueError(kind)
+
+
+def check_scaled(x_dev, block, X, Y, kind, host=None, what=("scale", "encode", "decode", "emulate"), seed=0):
+    x_dev = x_dev.reshape(-1)
+    n = x_dev.numel()
+    if host is None:
+        host = synth.bits_numpy(x_dev)
+    dt = odt(x_dev)
+    label = "e%dm%d block=%d n=%d %s %s" % (X, Y, block, n, x_dev.dtype, kind)
+    if "scale" in what:
+        got = exmy.block_scale(x_dev, block, X, Y)
+        torch.cuda.synchronize()
+        want = O.block_scale(host, block, X, Y)
+        assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32)), "block_scale " + label
+    scale = scales_for(kind, host, block, X, Y, seed)
+    scale_dev = torch.from_numpy(scale).to(DEV)
+    if 1 + X + Y <= 16 and ("encode" in what or "decode" in what):
+        want_packed = O.encode_scaled(host, block, X, Y, scale, threads=THREADS)
+        if "encode" in what:
+            got = exmy.encode_scaled(x_dev, block, X, Y, scale_dev)
+            torch.cuda.synchronize()
+            assert np.array_equal(got.cpu().numpy(), want_packed), "encode_scaled " + label
+        if "decode" in what:
+            pd = torch.from_numpy(want_packed).to(DEV)
+            got = exmy.decode_scaled(pd, x_dev.dtype, n, block, X, Y, scale_dev)
+            torch.cuda.synchronize()
+            want = O.decode_scaled(want_packed, dt, n, block, X, Y, scale, threads=THREADS)
+            assert np.array_equal(tbits(got), ubits(want)), "decode_scaled " + label
+    if "emulate" in what:
+        got = exmy.emulate_scaled(x_dev.clone(), block, X, Y, scale_dev)
+        torch.cuda.synchronize()
+        want = O.emulate_scaled(host, block, X, Y, scale, threads=THREADS)
+        assert np.array_equal(tbits(got), ubits(want)), "emulate_scaled " + label
+
+
+BLOCKS = [8, 16, 32, 64, 128, 256, 512, 24, 520, 1024, 4096, 11008]
+
+
+@pytest.mark.parametrize("W", range(2, 17))
+def test_every_bf16_pattern_every_width(W):
+    x = synth.shuffled(synth.all_bf16_patterns(), 100 + W).to(DEV)
+    host = synth.bits_numpy(x)
+    for i, (X, Y) in enumerate(formats_of_width(W, torch.bfloat16)):
+        b1 = BLOCKS[(W + i) % len(BLOCKS)]
+        b2 = BLOCKS[(W + i + 5) % len(BLOCKS)]
+        check_scaled(x, b1, X, Y, "block_scale", host)
+        check_scaled(x, b2, X, Y, "perturbed", host, what=("encode", "decode", "emulate"), seed=i)
+
+
+@pytest.mark.parametrize("W", range(2, 17))
+def test_fp32_sweep_every_width(W):
+    x = synth.shuffled(synth.f32_edge_sweep(seed=W), 200 + W).to(DEV)
+    host = synth.bits_numpy(x)
+    for i, (X, Y) in enumerate(formats_of_width(W, torch.float32)):
+        b1 = BLOCKS[(W + i + 2) % len(BLOCKS)]
+        b2 = BLOCKS[(W + i + 7) % len(BLOCKS)]
+        check_scaled(x, b1, X, Y, "block_scale", host)
+        check_scaled(x, b2, X, Y, "perturbed", host, what=("encode", "decode", "emulate"), seed=i)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_emulate_only_formats(dtype):
+    x = synth.shuffled(synth.f32_edge_sweep(seed=5) if dtype == torch.float32 else synth.all_bf16_patterns(), 5).to(DEV)
+    host = synth.bits_numpy(x)
+    fmts = [(7, 7), (5, 7), (0, 8)] if dtype == torch.bfloat16 else [(7, 23), (2, 22), (4, 21), (0, 24), (7, 12), (3, 20)]
+    for X, Y in fmts:
+        for block in (32, 1000, 4096):
+            for kind in ("block_scale", "perturbed"):
+                check_scaled(x, block, X, Y, kind, host, what=("scale", "emulate"))
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("block", [8, 32, 512, 24, 4096])
+def test_ragged_lengths(dtype, block):
+    g = torch.Generator().manual_seed(block + 1)
+    lengths = sorted({1, 3, 7, 8, 9, 17, block - 1, block, block + 1, 2 * block + 5, 1023, 2048 + 4, 4096 + 12,
+                      5 * 4096 + 8 * 7 + 3, 33 * 1024 + 1})
+    for n in lengths:
+        x = (torch.randn(n, generator=g) * torch.exp2(torch.randint(-10, 10, (n,), generator=g).float())).to(dtype).to(DEV)
+        for X, Y in ((3, 3), (2, 1), (0, 4)):
+            check_scaled(x, block, X, Y, "block_scale")
+
+
+def test_special_blocks_and_empty_input():
+    x = torch.randn(4096)
+    x[64:128] = float("nan")
+    x[128:192] = float("inf")
+    x[192:256] = 0.0
+    x[256:320] = 1e-40
+    x[320:384] = 3.0e38
+    for dtype in (torch.bfloat16, torch.float32):
+        xd = x.to(dtype).to(DEV)
+        for block in (64, 1024):
+            check_scaled(xd, block, 3, 2, "block_scale")
+        empty = torch.empty(0, dtype=dtype, device=DEV)
+        sc = torch.empty(0, dtype=torch.float32, device=DEV)
+        assert exmy.block_scale(empty, 32, 3, 3).numel() == 0
+        assert exmy.encode_scaled(empty, 32, 3, 3, sc).numel() == 0
+        assert exmy.decode_scaled(torch.empty(0, dtype=torch.uint8, device=DEV), dtype, 0, 32, 3, 3, sc).numel() == 0
+        assert exmy.emulate_scaled(empty, 32, 3, 3, sc).numel() == 0
+
+
+@pytest.mark.parametrize("block", [16, 4096])
+def test_weight_matrix(block):
+    x = synth.gaussian_bf16(4096 * 4096, seed=block + 3).to(DEV)
+    host = synth.bits_numpy(x)
+    for X, Y in ((2, 1), (3, 2)):
+        check_scaled(x, block, X, Y, "block_scale", host)

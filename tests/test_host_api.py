@@ -170,3 +170,30 @@ def test_after_rounding_and_auto_entry_points_validate_without_launch():
     assert auto(ok, B.BF16, 64, 32, 3, 3, 0, ok, odd, None) == 5
     assert auto(ok, B.F32, 64, 32, 3, 13, 0, ok, ok, None) == 2  # packed form stops at 16 bits
     assert auto(ok, B.BF16, 64, 20, 3, 3, 0, ok, ok, None) == 7
+
+
+def test_float_scaling_entry_points_validate_without_launch():
+    L = B.lib()
+    ok, odd16, odd4 = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1008), ctypes.c_void_p(0x1002)
+    sc, enc, dec, emu = L.exmy_block_scale, L.exmy_encode_scaled, L.exmy_decode_scaled, L.exmy_emulate_scaled
+    assert sc(ok, B.F32, 0, 8, 3, 3, ok, None) == 0
+    assert sc(None, B.F32, 8, 8, 3, 3, ok, None) == 1
+    assert sc(ok, B.F32, 8, 8, 3, 3, None, None) == 1
+    assert sc(ok, B.F32, 8, 8, 3, 3, odd4, None) == 5  # scales are 4-byte aligned
+    assert sc(odd16, B.F32, 8, 8, 3, 3, ok, None) == 5
+    for X, Y in ((8, 3), (0, 0), (9, 1), (-1, 2)):
+        assert sc(ok, B.F32, 0, 8, X, Y, ok, None) == 2
+        assert enc(ok, B.F32, 0, 8, X, Y, ok, ok, None) == 2
+        assert dec(ok, B.F32, 0, 8, X, Y, ok, ok, None) == 2
+        assert emu(ok, B.F32, 0, 8, X, Y, ok, None) == 2
+    assert enc(ok, B.F32, 0, 8, 3, 13, ok, ok, None) == 2   # packed form stops at 16 bits
+    assert emu(ok, B.F32, 0, 8, 3, 13, ok, None) == 0       # emulation does not
+    assert sc(ok, B.F32, 0, 8, 3, 23, ok, None) == 0
+    assert sc(ok, B.BF16, 0, 8, 3, 8, ok, None) == 2
+    assert enc(ok, B.BF16, 64, 12, 3, 3, ok, ok, None) == 7
+    assert enc(ok, B.BF16, 64, 16, 3, 3, None, ok, None) == 1
+    assert enc(ok, B.BF16, 64, 16, 3, 3, ok, None, None) == 1
+    assert dec(ok, B.BF16, 64, 16, 3, 3, ok, None, None) == 1
+    assert dec(odd16, B.BF16, 64, 16, 3, 3, ok, ok, None) == 5
+    assert emu(ok, B.BF16, 64, 16, 3, 3, odd4, None) == 5
+    assert emu(ok, B.BF16, (1 << 40) + 8, 16, 3, 3, ok, None) == 4
