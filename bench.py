@@ -30,8 +30,8 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E datasheet peak
 # runs scaled by a copy kernel of known size (profiles/*hbm_traffic*.txt).  None = not measured.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
     # profiles/cfg5_bf16_e3m3_encode_decode_hbm_traffic.txt: mean over the 5 launches of a batched call
-    ("cfg5", "batch", "encode"): 3723911859,
-    ("cfg5", "batch", "decode"): 3723935679,
+    ("cfg5", "batch", "encode"): 3723933734,
+    ("cfg5", "batch", "decode"): 3723937372,
 }
 
 
@@ -188,6 +188,58 @@ def time_phases(wl, exmy, steps, warmup):
     return wall, enc_ms, dec_ms
 
 
+def block_scheme_rates(exmy, synth, dev):
+    """Per-block metadata and float scaling on a 4096 x 11008 x 8 bf16 weight slab (0.72 GiB):
+    algorithmic bytes (elements + packed codes + per-block side array, read and written once)
+    per second of each kernel, timed with HIP events over 4 rotating buffers."""
+    import torch
+
+    n = 8 * 4096 * 11008
+    xs = [synth.gaussian_bf16(n, seed=40 + k, device=dev) for k in range(4)]
+    outs = [None] * 4
+    dst = torch.empty_like(xs[0])
+    turn = [0]
+
+    def timed(fn, iters=8, warm=2):
+        for _ in range(warm):
+            fn()
+        a, b = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        a.record()
+        for _ in range(iters):
+            fn()
+        b.record()
+        torch.cuda.synchronize()
+        return a.elapsed_time(b) / iters * 1e-3
+
+    res = {}
+    for label, block, X, Y in (("block32_e2m1", 32, 2, 1), ("row11008_e3m2", 11008, 3, 2)):
+        W = 1 + X + Y
+        nb = exmy.block_count(n, block)
+        for k in range(4):
+            outs[k] = torch.empty(exmy.packed_bytes(n, X, Y), dtype=torch.uint8, device=dev)
+        meta = exmy.block_max_exp(xs[0], block, X)
+        scale = exmy.block_scale(xs[0], block, X, Y)
+
+        def rot(f):
+            def g():
+                k = turn[0] = (turn[0] + 1) % 4
+                f(k)
+            return g
+
+        codec = n * (2 + W / 8)
+        rates = {
+            "block_max_exp": (n * 2 + nb, rot(lambda k: exmy.block_max_exp(xs[k], block, X, out=meta))),
+            "encode_blocks": (codec + nb, rot(lambda k: exmy.encode_blocks(xs[k], block, X, Y, meta, out=outs[k]))),
+            "decode_blocks": (codec + nb, rot(lambda k: exmy.decode_blocks(outs[k], torch.bfloat16, n, block, X, Y, meta, out=dst))),
+            "block_scale": (n * 2 + 4 * nb, rot(lambda k: exmy.block_scale(xs[k], block, X, Y, out=scale))),
+            "encode_scaled": (codec + 4 * nb, rot(lambda k: exmy.encode_scaled(xs[k], block, X, Y, scale, out=outs[k]))),
+            "decode_scaled": (codec + 4 * nb, rot(lambda k: exmy.decode_scaled(outs[k], torch.bfloat16, n, block, X, Y, scale, out=dst))),
+        }
+        res[label] = {name: round(nbytes / timed(fn) / 1e9, 1) for name, (nbytes, fn) in rates.items()}
+        res[label]["unit"] = "GB/s"
+    return res
+
+
 def count_launches(wl):
     """Launches that one batched call makes: tensors are walked by size, a launch holds at
     most 64 of them and is cut when a tensor is more than a quarter smaller than its largest."""
@@ -202,7 +254,7 @@ def count_launches(wl):
     return launches + (1 if count else 0)
 
 
-def cpu_baseline(wl, synth, budget_elems=1 << 27):
+def cpu_baseline(wl, synth, budget_elems=1 << 29):
     """The oracle, as it stands, on the host cores over a bounded prefix of the workload."""
     from oracle import exmy_oracle as O
 
@@ -337,6 +389,8 @@ def main():
                              "decode_GBps": round(b / d_ms / 1e6, 1)}
             del w2
             torch.cuda.empty_cache()
+        extras["per_block_schemes_bf16"] = block_scheme_rates(exmy, synth, dev)
+        torch.cuda.empty_cache()
         line["other_workloads"] = extras
         wl = build_workload(args.workload, exmy, synth, dev, min(args.layers, 1)) if not args.no_cpu_baseline else None
 
