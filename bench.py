@@ -289,8 +289,8 @@ def main():
     args = parse_args()
     world = int(os.environ.get("WORLD_SIZE", "1"))
     if args.gpus != 1 or world != 1:
-        print("bench.py: this build measures one GPU only (the codec shards with no communication; "
-              "see DESIGN.md). Run with --gpus 1.", file=sys.stderr)
+        print("bench.py: this build measures one GPU only (every group of 8 elements is independent, so the "
+              "codec shards with no communication). Run with --gpus 1.", file=sys.stderr)
         sys.exit(2)
 
     import torch

@@ -48,6 +48,10 @@
 //     mantissa bits as the format's top binade has (Y, or Y - 1 when X = 0), so
 //     that the block maximum is rounded and never cut off by saturation.
 //
+//   - packing along rows (Section 2.2.2: (8R, C) -> arrays of shape (R, C)): the
+//     group of output position (r, c) is elements (8r + j, c), j = 0..7, of the
+//     row-major matrix; rows beyond the last are zero codes; each plane is a
+//     row-major (R, C) array of words, planes back to back, widest first;
 //   - "float scaling with maximum exponent 127" (Section 2 "Metadata", Section
 //     2.1): the paper gives no formulas.  Reading: the block's scale is
 //     s = max|x| / vmax in fp32 (vmax = largest value of the format with
@@ -643,6 +647,87 @@ int exmy_oracle_decode_scaled(const uint8_t* src_packed, int dt, uint64_t n, uin
 int exmy_oracle_emulate_scaled(void* data, int dt, uint64_t n, uint64_t block, int X, int Y, const float* scale,
                                int threads) {
   return scaled_op(2, data, data, dt, n, block, X, Y, scale, threads);
+}
+
+// ---------------------------------------------------------------------------
+// Packing along rows (Section 2.2.2, Fig. 2: an array of shape (8R, C) becomes
+// arrays of shape (R, C), one per power-of-2 segment).  The matrix is row-major
+// with `rows` rows of `cols` elements; R = ceil(rows / 8).  max_exp_rows: one
+// metadatum per row of the matrix (Section 2.2.1: the (R, 1) metadata tensor of an
+// (R, C) tensor), read with the block-mode range; or null, then `max_exp` holds for
+// the whole tensor.
+
+uint64_t exmy_oracle_packed_bytes_rows(uint64_t rows, uint64_t cols, int X, int Y) {
+  return ((rows + 7) / 8) * cols * (uint64_t)(1 + X + Y);
+}
+
+// what: 0 = encode, 1 = decode
+static int rows_op(int what, const void* src, void* dst, int dt, uint64_t rows, uint64_t cols, int X, int Y,
+                   int max_exp, const uint8_t* max_exp_rows) {
+  const uint64_t n = rows * cols;
+  if (n && (!src || !dst)) return ORACLE_ERR_NULL;
+  Format f0;
+  int lo = 0, hi = 0;
+  if (max_exp_rows) {
+    if (int rc = block_meta_range(X, &lo, &hi)) return rc;
+    if (int rc = check_format(dt, X, Y, hi, true, &f0)) return rc;
+  } else {
+    if (int rc = check_format(dt, X, Y, max_exp, true, &f0)) return rc;
+  }
+  const int W = 1 + X + Y;
+  const uint64_t R = (rows + 7) / 8;
+  int seg[8];
+  const int np = plane_list(W, seg);
+  uint8_t* packed = (uint8_t*)(what == 0 ? dst : const_cast<void*>(src));
+  for (uint64_t r = 0; r < R; ++r) {
+    Format f[8];
+    for (int j = 0; j < 8; ++j) {
+      f[j] = f0;
+      const uint64_t row = 8 * r + j;
+      if (max_exp_rows && row < rows) check_format(dt, X, Y, clamp_meta(max_exp_rows[row], lo, hi), true, &f[j]);
+    }
+    for (uint64_t c = 0; c < cols; ++c) {
+      uint32_t code[8] = {0, 0, 0, 0, 0, 0, 0, 0};
+      if (what == 0)
+        for (int j = 0; j < 8; ++j)
+          if (8 * r + j < rows) code[j] = encode_one(f[j], load_bits(src, dt, (8 * r + j) * cols + c));
+      // the word of plane p at (r, c): element j at bits [s*j, s*j + s), little-endian bytes
+      uint64_t plane_off = 0;
+      int lob = 0;
+      for (int p = 0; p < np; ++p) {
+        const int sb = seg[p];
+        uint8_t* word = packed + plane_off + (r * cols + c) * (uint64_t)sb;
+        if (what == 0)
+          for (int b = 0; b < sb; ++b) word[b] = 0;
+        for (int j = 0; j < 8; ++j) {
+          for (int b = 0; b < sb; ++b) {
+            const int bit = sb * j + b;
+            if (what == 0) {
+              if ((code[j] >> (lob + b)) & 1u) word[bit / 8] |= (uint8_t)(1u << (bit % 8));
+            } else {
+              if ((word[bit / 8] >> (bit % 8)) & 1u) code[j] |= 1u << (lob + b);
+            }
+          }
+        }
+        plane_off += R * cols * (uint64_t)sb;
+        lob += sb;
+      }
+      if (what == 1)
+        for (int j = 0; j < 8; ++j)
+          if (8 * r + j < rows) store_bits(dst, dt, (8 * r + j) * cols + c, decode_one(f[j], code[j]));
+    }
+  }
+  return ORACLE_OK;
+}
+
+int exmy_oracle_encode_rows(const void* src, int dt, uint64_t rows, uint64_t cols, int X, int Y, int max_exp,
+                            const uint8_t* max_exp_rows, uint8_t* dst_packed) {
+  return rows_op(0, src, dst_packed, dt, rows, cols, X, Y, max_exp, max_exp_rows);
+}
+
+int exmy_oracle_decode_rows(const uint8_t* src_packed, int dt, uint64_t rows, uint64_t cols, int X, int Y,
+                            int max_exp, const uint8_t* max_exp_rows, void* dst) {
+  return rows_op(1, src_packed, dst, dt, rows, cols, X, Y, max_exp, max_exp_rows);
 }
 
 // fp32 -> bf16 rounding used above, exported so that it can be pinned on its own.

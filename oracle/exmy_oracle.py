@@ -49,6 +49,10 @@ def lib():
         L.exmy_oracle_emulate_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, i32]
         L.exmy_oracle_round_to_bf16_bits.restype = ctypes.c_uint32
         L.exmy_oracle_round_to_bf16_bits.argtypes = [ctypes.c_float]
+        L.exmy_oracle_packed_bytes_rows.restype = u64
+        L.exmy_oracle_packed_bytes_rows.argtypes = [u64, u64, i32, i32]
+        L.exmy_oracle_encode_rows.argtypes = [vp, i32, u64, u64, i32, i32, i32, vp, vp]
+        L.exmy_oracle_decode_rows.argtypes = [vp, i32, u64, u64, i32, i32, i32, vp, vp]
         L.exmy_oracle_max_exp_from_histogram.restype = i32
         L.exmy_oracle_max_exp_from_histogram.argtypes = [vp, dbl]
         _lib = L
@@ -255,3 +259,38 @@ def emulate_scaled(src, block, X, Y, scale, threads=1):
 
 def round_to_bf16_bits(r):
     return int(lib().exmy_oracle_round_to_bf16_bits(float(r)))
+
+
+# ------------------------------------------------------------ packing along rows
+
+
+def packed_bytes_rows(rows, cols, X, Y):
+    return int(lib().exmy_oracle_packed_bytes_rows(rows, cols, X, Y))
+
+
+def _row_meta(max_exp_rows, rows):
+    if max_exp_rows is None:
+        return None
+    m = np.ascontiguousarray(max_exp_rows, dtype=np.uint8)
+    assert m.size == rows
+    return m
+
+
+def encode_rows(src, rows, cols, X, Y, max_exp=0, max_exp_rows=None):
+    a, dt = _src(src)
+    assert a.size == rows * cols
+    m = _row_meta(max_exp_rows, rows)
+    out = np.empty(packed_bytes_rows(rows, cols, X, Y), dtype=np.uint8)
+    _check(lib().exmy_oracle_encode_rows(_ptr(a), dt, rows, cols, X, Y, max_exp, _ptr(m) if m is not None else None,
+                                         _ptr(out)))
+    return out
+
+
+def decode_rows(packed, dt, rows, cols, X, Y, max_exp=0, max_exp_rows=None):
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    assert packed.size == packed_bytes_rows(rows, cols, X, Y)
+    m = _row_meta(max_exp_rows, rows)
+    out = np.empty(rows * cols, dtype=_out_dtype(dt))
+    _check(lib().exmy_oracle_decode_rows(_ptr(packed), dt, rows, cols, X, Y, max_exp,
+                                         _ptr(m) if m is not None else None, _ptr(out)))
+    return out
