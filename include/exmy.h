@@ -64,11 +64,13 @@ typedef enum {
   EXMY_ERR_COUNT = 4,   /* n above EXMY_MAX_ELEMENTS */
   EXMY_ERR_ALIGN = 5,   /* a pointer is not 16-byte aligned */
   EXMY_ERR_DEVICE = 6,  /* the HIP runtime reported an error at launch */
-  EXMY_ERR_BLOCK = 7    /* metadata block size not a multiple of 8 in [8, EXMY_MAX_BLOCK] */
+  EXMY_ERR_BLOCK = 7,   /* metadata block size not a multiple of 8 in [8, EXMY_MAX_BLOCK] */
+  EXMY_ERR_SHAPE = 8    /* packing along rows: cols not a multiple of 8, or above EXMY_MAX_COLS */
 } exmy_status_t;
 
 #define EXMY_MAX_ELEMENTS ((uint64_t)1 << 40)
 #define EXMY_MAX_BLOCK ((uint64_t)1 << 31)
+#define EXMY_MAX_COLS ((uint64_t)1 << 26)
 
 /* Bytes of the packed form of n elements: ceil(n / 8) * (1 + X + Y)
  * (perfect compression, Section 2.2.2).  Host only; no validation. */
@@ -215,6 +217,34 @@ exmy_status_t exmy_decode_scaled(const void* src_packed, exmy_dtype_t dt_out, ui
                                  int Y, const float* scale_dev, void* dst, void* stream);
 exmy_status_t exmy_emulate_scaled(void* data_inout, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
                                   const float* scale_dev, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Packing along rows (Section 2.2.2 and Fig. 2: an array of shape (8R, C) is
+ * packed into one array of shape (R, C) per power-of-2 segment).
+ *
+ * src is a row-major matrix of `rows` rows of `cols` elements.  The group of
+ * output position (r, c) is the 8 elements (8r + j, c), j = 0..7; element j
+ * sits at bits [s*j, s*j + s) of the plane word as in the layout above.
+ * R = ceil(rows / 8); rows past the end count as zero codes.  Each plane is a
+ * row-major (R, C) array of little-endian words of s bytes; the planes lie
+ * back to back, widest first: exmy_packed_bytes_rows = R * cols * W bytes.
+ * Rows [8a, 8b) of the matrix are rows [a, b) of every plane, columns
+ * [a, b) are columns [a, b) of every plane: the matrix can be sharded either
+ * way before or after packing.
+ * Metadata: max_exp_rows_dev == NULL: `max_exp` holds for the whole tensor
+ * (range as for exmy_encode, X = 8 included).  Else it is a DEVICE array of
+ * one byte per row of the matrix (Section 2.2.1: the (R, 1) metadata tensor of
+ * an (R, C) tensor), read as for exmy_encode_blocks (exmy_block_max_exp with
+ * block = cols computes it), and `max_exp` is ignored.
+ * cols must be a multiple of 8 and at most EXMY_MAX_COLS (EXMY_ERR_SHAPE);
+ * rows * cols <= EXMY_MAX_ELEMENTS.  Values and codes equal those of the
+ * entry points above; only the grouping differs.  Pointers, alignment, empty
+ * input, streams and errors as for exmy_encode. */
+size_t exmy_packed_bytes_rows(uint64_t rows, uint64_t cols, int X, int Y);
+exmy_status_t exmy_encode_rows(const void* src, exmy_dtype_t dt, uint64_t rows, uint64_t cols, int X, int Y,
+                               int max_exp, const uint8_t* max_exp_rows_dev, void* dst_packed, void* stream);
+exmy_status_t exmy_decode_rows(const void* src_packed, exmy_dtype_t dt_out, uint64_t rows, uint64_t cols, int X,
+                               int Y, int max_exp, const uint8_t* max_exp_rows_dev, void* dst, void* stream);
 
 /* Host helper for Section 3.1's technique (keep the top exponents, let the
  * tail go): the smallest biased exponent e in [0, 254] such that at least

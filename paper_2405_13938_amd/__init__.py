@@ -15,6 +15,7 @@ from .binding import (  # noqa: F401
     decode,
     decode_batch,
     decode_blocks,
+    decode_rows,
     decode_scaled,
     emulate,
     emulate_blocks,
@@ -23,9 +24,11 @@ from .binding import (  # noqa: F401
     encode_batch,
     encode_blocks,
     encode_blocks_auto,
+    encode_rows,
     encode_scaled,
     encode_with_histogram,
     exponent_histogram,
     max_exp_from_histogram,
     packed_bytes,
+    packed_bytes_rows,
 )

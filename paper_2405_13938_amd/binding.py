@@ -35,6 +35,9 @@ SYMBOLS = [
     "exmy_encode_scaled",
     "exmy_decode_scaled",
     "exmy_emulate_scaled",
+    "exmy_packed_bytes_rows",
+    "exmy_encode_rows",
+    "exmy_decode_rows",
     "exmy_status_string",
 ]
 
@@ -106,6 +109,12 @@ def lib():
         L.exmy_decode_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, vp]
         L.exmy_emulate_scaled.restype = i32
         L.exmy_emulate_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp]
+        L.exmy_packed_bytes_rows.restype = ctypes.c_size_t
+        L.exmy_packed_bytes_rows.argtypes = [u64, u64, i32, i32]
+        L.exmy_encode_rows.restype = i32
+        L.exmy_encode_rows.argtypes = [vp, i32, u64, u64, i32, i32, i32, vp, vp, vp]
+        L.exmy_decode_rows.restype = i32
+        L.exmy_decode_rows.argtypes = [vp, i32, u64, u64, i32, i32, i32, vp, vp, vp]
         L.exmy_status_string.restype = ctypes.c_char_p
         L.exmy_status_string.argtypes = [i32]
         _lib = L
@@ -454,3 +463,54 @@ def emulate_scaled(data, block, X, Y, scales):
     _check(lib().exmy_emulate_scaled(data.data_ptr(), _dtype_enum(data), data.numel(), block, X, Y,
                                      scales.data_ptr(), _stream()))
     return data
+
+
+# ------------------------------------------------------------ packing along rows
+
+
+def packed_bytes_rows(rows, cols, X, Y):
+    return int(lib().exmy_packed_bytes_rows(rows, cols, X, Y))
+
+
+def _row_meta_ptr(max_exp_rows, rows):
+    if max_exp_rows is None:
+        return None
+    _device_tensor(max_exp_rows, "max_exp_rows")
+    if max_exp_rows.dtype != torch.uint8 or max_exp_rows.numel() != rows:
+        raise ValueError("exmy: max_exp_rows must be uint8 with %d elements" % rows)
+    return max_exp_rows.data_ptr()
+
+
+def encode_rows(src, X, Y, max_exp=0, max_exp_rows=None, out=None):
+    """exmy_encode_rows on a 2-D tensor (rows, cols); returns the packed uint8 tensor."""
+    _device_tensor(src, "src")
+    if src.dim() != 2:
+        raise ValueError("exmy: src must be a matrix")
+    rows, cols = src.shape
+    nbytes = packed_bytes_rows(rows, cols, X, Y)
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.uint8, device=src.device)
+    else:
+        _device_tensor(out, "out")
+        if out.dtype != torch.uint8 or out.numel() != nbytes:
+            raise ValueError("exmy: out must be uint8 with %d elements" % nbytes)
+    _check(lib().exmy_encode_rows(src.data_ptr(), _dtype_enum(src), rows, cols, X, Y, max_exp,
+                                  _row_meta_ptr(max_exp_rows, rows), out.data_ptr(), _stream()))
+    return out
+
+
+def decode_rows(packed, dtype, rows, cols, X, Y, max_exp=0, max_exp_rows=None, out=None):
+    """exmy_decode_rows: returns a (rows, cols) tensor of ``dtype``."""
+    _device_tensor(packed, "packed")
+    tdt = _torch_dtype(dtype)
+    if packed.dtype != torch.uint8 or packed.numel() != packed_bytes_rows(rows, cols, X, Y):
+        raise ValueError("exmy: packed must be uint8 with %d elements" % packed_bytes_rows(rows, cols, X, Y))
+    if out is None:
+        out = torch.empty((rows, cols), dtype=tdt, device=packed.device)
+    else:
+        _device_tensor(out, "out")
+        if out.dtype != tdt or tuple(out.shape) != (rows, cols):
+            raise ValueError("exmy: out must be %s of shape (%d, %d)" % (tdt, rows, cols))
+    _check(lib().exmy_decode_rows(packed.data_ptr(), _dtype_enum(out), rows, cols, X, Y, max_exp,
+                                  _row_meta_ptr(max_exp_rows, rows), out.data_ptr(), _stream()))
+    return out

@@ -270,6 +270,43 @@ exmy_status_t run_blocks(BlockOp op, bool scaled, const void* elems, const void*
   return e == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
 }
 
+enum class RowsOp { kEncode, kDecode };
+
+// Shared validation and launch of the entry points that pack along rows.
+exmy_status_t run_rows(RowsOp op, const void* matrix, const void* packed, exmy_dtype_t dt, uint64_t rows, uint64_t cols,
+                       int X, int Y, int max_exp, const uint8_t* max_exp_rows, void* stream) {
+  RowsArgs args;
+  bool wide = false;
+  if (max_exp_rows) {
+    if (exmy_status_t st = make_block_format(dt, X, Y, true, false, &args.fc, &args.bc)) return st;
+    memset(&args.tc, 0, sizeof(args.tc));
+  } else {
+    if (exmy_status_t st = make_format(dt, X, Y, max_exp, true, &args.fc, &args.tc, &wide)) return st;
+    memset(&args.bc, 0, sizeof(args.bc));
+  }
+  if (cols % 8 || cols > EXMY_MAX_COLS) return EXMY_ERR_SHAPE;
+  if (cols && rows > EXMY_MAX_ELEMENTS / cols) return EXMY_ERR_COUNT;
+  if (rows == 0 || cols == 0) return EXMY_OK;
+  if (!matrix || !packed) return EXMY_ERR_NULL;
+  if (!aligned16(matrix) || !aligned16(packed)) return EXMY_ERR_ALIGN;
+  args.meta = max_exp_rows;
+  args.rows = rows;
+  args.cols = (uint32_t)cols;
+  args.tiles = make_block_index(1);
+  const hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e;
+  if (op == RowsOp::kEncode) {
+    args.src = matrix;
+    args.dst = const_cast<void*>(packed);
+    e = encode_rows_dispatch(dt, 1 + X + Y, args, max_exp_rows != nullptr, wide, s);
+  } else {
+    args.src = packed;
+    args.dst = const_cast<void*>(matrix);
+    e = decode_rows_dispatch(dt, 1 + X + Y, args, max_exp_rows != nullptr, X == 8, s);
+  }
+  return e == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
+}
+
 }  // namespace
 
 extern "C" {
@@ -392,6 +429,20 @@ exmy_status_t exmy_emulate_scaled(void* data_inout, exmy_dtype_t dt, uint64_t n,
   return run_blocks(BlockOp::kEmulate, true, data_inout, nullptr, dt, n, block, X, Y, scale_dev, stream);
 }
 
+size_t exmy_packed_bytes_rows(uint64_t rows, uint64_t cols, int X, int Y) {
+  return (size_t)(((rows + 7) / 8) * cols * (uint64_t)(1 + X + Y));
+}
+
+exmy_status_t exmy_encode_rows(const void* src, exmy_dtype_t dt, uint64_t rows, uint64_t cols, int X, int Y,
+                               int max_exp, const uint8_t* max_exp_rows_dev, void* dst_packed, void* stream) {
+  return run_rows(RowsOp::kEncode, src, dst_packed, dt, rows, cols, X, Y, max_exp, max_exp_rows_dev, stream);
+}
+
+exmy_status_t exmy_decode_rows(const void* src_packed, exmy_dtype_t dt_out, uint64_t rows, uint64_t cols, int X, int Y,
+                               int max_exp, const uint8_t* max_exp_rows_dev, void* dst, void* stream) {
+  return run_rows(RowsOp::kDecode, dst, src_packed, dt_out, rows, cols, X, Y, max_exp, max_exp_rows_dev, stream);
+}
+
 int exmy_max_exp_from_histogram(const uint64_t* hist256_host, double coverage) {
   if (!hist256_host) return -1;
   uint64_t finite = 0;
@@ -415,6 +466,7 @@ const char* exmy_status_string(exmy_status_t status) {
     case EXMY_ERR_COUNT: return "element count too large";
     case EXMY_ERR_ALIGN: return "pointer not 16-byte aligned";
     case EXMY_ERR_DEVICE: return "HIP launch error";
+    case EXMY_ERR_SHAPE: return "column count not a multiple of 8, or above 2^26";
     case EXMY_ERR_BLOCK: return "block size not a multiple of 8 in [8, 2^31]";
   }
   return "unknown status";

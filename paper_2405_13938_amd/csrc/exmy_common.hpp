@@ -116,6 +116,20 @@ struct BlockArgs {
   uint32_t block_groups;  // block / 8
 };
 
+// Kernel arguments of the kernels that pack along rows (Section 2.2.2: groups are
+// the 8 rows of a row block at one column of a row-major matrix).
+struct RowsArgs {
+  FormatConsts fc;
+  TensorConsts tc;      // per-tensor metadata (meta == null)
+  BlockConsts bc;       // per-row metadata: derivation constants
+  BlockIndex tiles;     // tiles per row block, for the tile -> (row block, column tile) split
+  const void* src;      // encode: matrix; decode: packed planes
+  void* dst;            // encode: packed planes; decode: matrix
+  const uint8_t* meta;  // one byte per row, or null
+  uint64_t rows;
+  uint32_t cols;        // a multiple of 8
+};
+
 inline BlockIndex make_block_index(uint64_t size) {
   BlockIndex bi;
   bi.size = (uint32_t)size;

@@ -44,6 +44,11 @@ hipError_t decode_blocks_dispatch(exmy_dtype_t dt, int W, const BlockArgs& args,
 hipError_t emulate_blocks_dispatch(exmy_dtype_t dt, const BlockArgs& args, bool wide_format, bool scaled,
                                    hipStream_t stream);
 hipError_t block_max_exp_dispatch(exmy_dtype_t dt, const BlockArgs& args, bool scale, hipStream_t stream);
+// Packing along rows (args.tiles is filled in by the dispatcher).
+hipError_t encode_rows_dispatch(exmy_dtype_t dt, int W, const RowsArgs& args, bool per_row, bool wide,
+                                hipStream_t stream);
+hipError_t decode_rows_dispatch(exmy_dtype_t dt, int W, const RowsArgs& args, bool per_row, bool x8,
+                                hipStream_t stream);
 hipError_t histogram_dispatch(exmy_dtype_t dt, const void* src, uint64_t n, uint64_t* hist, hipStream_t stream);
 
 }  // namespace exmy

@@ -1,0 +1,303 @@
+// Codec with packing along rows (Section 2.2.2, Fig. 2: an array of shape (8R, C)
+// becomes, per power-of-2 segment, an array of shape (R, C)): the 8 elements of a
+// group are the 8 rows of one row block at one column of a row-major matrix.
+//
+// One lane owns kCols adjacent columns (16 bytes of every row: 8 bf16 or 4 fp32
+// values) of one row block: eight 16-byte loads, one per row, each contiguous
+// over the wavefront; kCols adjacent words of every plane, written (or read) as
+// one contiguous piece of kCols * S bytes.  A tile is kBlock * kCols columns of
+// one row block; tiles are numbered row-block-major, so a launch walks the plane
+// arrays in address order and the source as 8 parallel streams.
+//
+// Metadata: one max_exp for the tensor, or one per row of the matrix (Section
+// 2.2.1: the (R, 1) metadata tensor).  Either way a tile sees at most 8 metadata,
+// all wave-uniform, so the constants of the 8 rows stay in SGPRs.
+#pragma once
+
+#include "exmy_decode_kernel.hpp"
+#include "exmy_encode_kernel.hpp"
+
+namespace exmy {
+
+namespace rows {
+
+// The S * 8 bits of one plane word from the fields that sit at the TOP of
+// t[0..7], element j at bits [S*j, S*j + S): out[0 .. S/4) for S >= 4, else the
+// low 2 or 1 bytes of out[0].
+template <int S>
+__device__ __forceinline__ void plane_word_from_top(const uint32_t t[8], uint32_t out[4]) {
+  using enc::append_top;
+  if constexpr (S == 16) {
+    out[0] = append_top(t[1] >> 16, t[0], 16);
+    out[1] = append_top(t[3] >> 16, t[2], 16);
+    out[2] = append_top(t[5] >> 16, t[4], 16);
+    out[3] = append_top(t[7] >> 16, t[6], 16);
+  } else if constexpr (S == 8) {
+    out[0] = append_top(append_top(append_top(t[3] >> 24, t[2], 8), t[1], 8), t[0], 8);
+    out[1] = append_top(append_top(append_top(t[7] >> 24, t[6], 8), t[5], 8), t[4], 8);
+  } else {
+    uint32_t word = t[7] >> (32 - S);
+#pragma unroll
+    for (int j = 6; j >= 0; --j) word = append_top(word, t[j], S);
+    out[0] = word;
+  }
+}
+
+// fp32-position bits of column c of a 16-byte row piece.
+template <typename T>
+__device__ __forceinline__ uint32_t column_bits(const uint4& v, int c) {
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  if constexpr (sizeof(T) == 4) return w[c];
+  return (c & 1) ? (w[c / 2] & 0xFFFF0000u) : (w[c / 2] << 16);
+}
+
+// Plane words of a lane: plane P holds kCols words of S bytes, packed into
+// dwords in column order.
+template <int W, int kCols>
+struct LaneWords {
+  uint32_t w[Planes<W>::count][kCols * 4];  // plane P uses the first kCols * S / 4 (at least 1)
+};
+
+// Place the word of column c (from plane_word_from_top) into the lane's piece of plane P.
+template <int W, int kCols, int P>
+__device__ __forceinline__ void put_word(LaneWords<W, kCols>& lw, int c, const uint32_t word[4]) {
+  constexpr int S = Planes<W>::seg(P);
+  if constexpr (S >= 4) {
+#pragma unroll
+    for (int k = 0; k < S / 4; ++k) lw.w[P][c * (S / 4) + k] = word[k];
+  } else if constexpr (S == 2) {
+    if (c & 1)
+      lw.w[P][c / 2] |= word[0] << 16;
+    else
+      lw.w[P][c / 2] = word[0] & 0xFFFFu;
+  } else {
+    if (c & 3)
+      lw.w[P][c / 4] |= (word[0] & 0xFFu) << (8 * (c & 3));
+    else
+      lw.w[P][c / 4] = word[0] & 0xFFu;
+  }
+}
+
+// Peel the planes of column c off the left-aligned codes f (sign plane of an odd W from u).
+template <int W, int kCols, int P>
+__device__ __forceinline__ void peel_column(uint32_t f[8], const uint32_t u[8], int c, LaneWords<W, kCols>& lw) {
+  constexpr int S = Planes<W>::seg(P);
+  constexpr bool sign_plane = (W & 1) && P == Planes<W>::count - 1;
+  uint32_t word[4];
+  if constexpr (sign_plane) {
+    plane_word_from_top<S>(u, word);
+  } else {
+    plane_word_from_top<S>(f, word);
+    if constexpr (P > 0) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) f[j] <<= S;
+    }
+  }
+  put_word<W, kCols, P>(lw, c, word);
+  if constexpr (P > 0) peel_column<W, kCols, P - 1>(f, u, c, lw);
+}
+
+// Store (kStore) or load the lane's piece of every plane: kCols * S bytes at byte
+// offset lane * kCols * S of the plane descriptor.
+template <int W, int kCols, bool kStore, int P = 0>
+__device__ __forceinline__ void move_words(LaneWords<W, kCols>& lw, const rsrc_t* plane, uint32_t lane) {
+  if constexpr (P < Planes<W>::count) {
+    constexpr int S = Planes<W>::seg(P);
+    constexpr int kBytes = kCols * S;  // 4 ... 128
+    const uint32_t off = lane * kBytes;
+    const rsrc_t r = plane[P];
+    if constexpr (kBytes >= 16) {
+#pragma unroll
+      for (int k = 0; k < kBytes / 16; ++k) {
+        if constexpr (kStore) {
+          store16<false>(r, off, k * 16, make_uint4(lw.w[P][4 * k], lw.w[P][4 * k + 1], lw.w[P][4 * k + 2], lw.w[P][4 * k + 3]));
+        } else {
+          const uint4 v = load16<false>(r, off, k * 16);
+          lw.w[P][4 * k] = v.x; lw.w[P][4 * k + 1] = v.y; lw.w[P][4 * k + 2] = v.z; lw.w[P][4 * k + 3] = v.w;
+        }
+      }
+    } else if constexpr (kBytes == 8) {
+      if constexpr (kStore) {
+        const u32x2_t o = {lw.w[P][0], lw.w[P][1]};
+        __builtin_amdgcn_raw_buffer_store_b64(o, r, off, 0, 0);
+      } else {
+        const u32x2_t v = __builtin_amdgcn_raw_buffer_load_b64(r, off, 0, 0);
+        lw.w[P][0] = v.x; lw.w[P][1] = v.y;
+      }
+    } else {
+      static_assert(kBytes == 4, "a lane's piece of a plane is at least one dword");
+      if constexpr (kStore)
+        __builtin_amdgcn_raw_buffer_store_b32(lw.w[P][0], r, off, 0, 0);
+      else
+        lw.w[P][0] = __builtin_amdgcn_raw_buffer_load_b32(r, off, 0, 0);
+    }
+    move_words<W, kCols, kStore, P + 1>(lw, plane, lane);
+  }
+}
+
+// Plane descriptors based at the plane words of (row block rb, column col0).
+template <int W, int P = 0>
+__device__ __forceinline__ void make_plane_rsrc(uint8_t* packed, uint64_t R, uint32_t cols, uint64_t rb, uint32_t col0,
+                                                rsrc_t* plane) {
+  if constexpr (P < Planes<W>::count) {
+    constexpr uint64_t S = Planes<W>::seg(P);
+    constexpr uint64_t LO = Planes<W>::lo(P);
+    plane[P] = make_rsrc(packed + (R * cols * LO + (rb * cols + col0) * S));
+    make_plane_rsrc<W, P + 1>(packed, R, cols, rb, col0, plane);
+  }
+}
+
+// Constants of the 8 rows of row block rb.
+template <bool kPerRow>
+__device__ __forceinline__ void row_constants(const RowsArgs& a, uint64_t rb, TensorConsts tc[8], bool& any_wide) {
+  any_wide = false;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    if constexpr (kPerRow) {
+      const uint64_t row = 8 * rb + j;
+      const uint32_t me = row < a.rows ? __builtin_amdgcn_readfirstlane((uint32_t)a.meta[row]) : a.bc.meta_lo;
+      tc[j] = derive_tc(me, a.bc);
+      any_wide = any_wide || min(max(me, a.bc.meta_lo), a.bc.meta_hi) > a.bc.wide_above;
+    } else {
+      tc[j] = a.tc;
+    }
+  }
+}
+
+template <typename T, int W, int kCols, bool kWide>
+__device__ __forceinline__ void encode_columns(const uint4 v[8], const FormatConsts& fc, const TensorConsts tc[8],
+                                               LaneWords<W, kCols>& lw) {
+#pragma unroll
+  for (int c = 0; c < kCols; ++c) {
+    uint32_t u[8], f[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      u[j] = column_bits<T>(v[j], c);
+      const uint32_t m = magnitude_code_left<kWide>(u[j], fc, tc[j]);
+      f[j] = (W & 1) ? m : ((u[j] & 0x80000000u) | m);
+    }
+    peel_column<W, kCols, Planes<W>::count - 1>(f, u, c, lw);
+  }
+}
+
+// kWide: per-tensor metadata only (with per-row metadata the variant is chosen per tile).
+template <typename T, int W, int kBlock, bool kPerRow, bool kWide>
+__global__ __launch_bounds__(kBlock) void encode_rows_kernel(const RowsArgs args) {
+  constexpr int kCols = 16 / sizeof(T);
+  constexpr uint32_t kTileCols = kBlock * kCols;
+  const uint8_t* __restrict__ src = static_cast<const uint8_t*>(args.src);
+  uint8_t* __restrict__ dst = static_cast<uint8_t*>(args.dst);
+  const FormatConsts fc = args.fc;
+  const uint32_t cols = args.cols;
+  const uint64_t R = (args.rows + 7) / 8;
+  const uint32_t row_bytes = cols * (uint32_t)sizeof(T);
+  const uint64_t total = R * args.tiles.size;
+
+  for (uint64_t t = blockIdx.x; t < total; t += gridDim.x) {
+    uint64_t rb;
+    uint32_t ct;
+    tile_first_block(t, args.tiles, rb, ct);
+    const uint32_t col0 = ct * kTileCols;
+    if (col0 + threadIdx.x * kCols >= cols) continue;
+    const uint64_t left = args.rows - 8 * rb;
+    const uint32_t nrows = left < 8 ? (uint32_t)left : 8u;
+    const rsrc_t in = make_rsrc(src + ((8 * rb) * cols + col0) * sizeof(T));
+    uint4 v[8];
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      if (j < (int)nrows)
+        v[j] = load16<true>(in, threadIdx.x * 16, j * row_bytes);
+      else
+        v[j] = make_uint4(0, 0, 0, 0);  // rows past the end hold zero codes
+    }
+    TensorConsts tc[8];
+    bool any_wide;
+    row_constants<kPerRow>(args, rb, tc, any_wide);
+    LaneWords<W, kCols> lw;
+    if constexpr (kPerRow) {
+      if (any_wide)
+        encode_columns<T, W, kCols, true>(v, fc, tc, lw);
+      else
+        encode_columns<T, W, kCols, false>(v, fc, tc, lw);
+    } else {
+      encode_columns<T, W, kCols, kWide>(v, fc, tc, lw);
+    }
+    rsrc_t plane[Planes<W>::count];
+    make_plane_rsrc<W>(dst, R, cols, rb, col0, plane);
+    move_words<W, kCols, true>(lw, plane, threadIdx.x);
+  }
+}
+
+// The plane bits of column c of the lane, in the form element_bits reads (a unit of 8 elements).
+template <int W, int kCols, int P = 0>
+__device__ __forceinline__ void column_unit(const LaneWords<W, kCols>& lw, int c, dec::UnitWords<W>& uw) {
+  if constexpr (P < Planes<W>::count) {
+    constexpr int S = Planes<W>::seg(P);
+    if constexpr (S >= 4) {
+#pragma unroll
+      for (int k = 0; k < S / 4; ++k) uw.w[P][k] = lw.w[P][c * (S / 4) + k];
+    } else if constexpr (S == 2) {
+      uw.w[P][0] = lw.w[P][c / 2] >> (16 * (c & 1));
+    } else {
+      uw.w[P][0] = lw.w[P][c / 4] >> (8 * (c & 3));
+    }
+    column_unit<W, kCols, P + 1>(lw, c, uw);
+  }
+}
+
+template <typename T, int W, int kBlock, bool kPerRow, bool kX8>
+__global__ __launch_bounds__(kBlock) void decode_rows_kernel(const RowsArgs args) {
+  constexpr int kCols = 16 / sizeof(T);
+  constexpr uint32_t kTileCols = kBlock * kCols;
+  uint8_t* __restrict__ src = static_cast<uint8_t*>(const_cast<void*>(args.src));
+  uint8_t* __restrict__ dst = static_cast<uint8_t*>(args.dst);
+  const FormatConsts fc = args.fc;
+  const uint32_t cols = args.cols;
+  const uint64_t R = (args.rows + 7) / 8;
+  const uint32_t row_bytes = cols * (uint32_t)sizeof(T);
+  const uint64_t total = R * args.tiles.size;
+
+  for (uint64_t t = blockIdx.x; t < total; t += gridDim.x) {
+    uint64_t rb;
+    uint32_t ct;
+    tile_first_block(t, args.tiles, rb, ct);
+    const uint32_t col0 = ct * kTileCols;
+    if (col0 + threadIdx.x * kCols >= cols) continue;
+    const uint64_t left = args.rows - 8 * rb;
+    const uint32_t nrows = left < 8 ? (uint32_t)left : 8u;
+    rsrc_t plane[Planes<W>::count];
+    make_plane_rsrc<W>(src, R, cols, rb, col0, plane);
+    LaneWords<W, kCols> lw;
+    move_words<W, kCols, false>(lw, plane, threadIdx.x);
+    TensorConsts tc[8];
+    bool any_wide;
+    row_constants<kPerRow>(args, rb, tc, any_wide);
+
+    uint32_t o[8][4];  // the lane's 16 bytes of every row
+#pragma unroll
+    for (int c = 0; c < kCols; ++c) {
+      dec::UnitWords<W> uw;
+      column_unit<W, kCols>(lw, c, uw);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const uint32_t b = dec::element_bits<W, kX8>(uw, j, fc, tc[j]);
+        if constexpr (sizeof(T) == 4) {
+          o[j][c] = b;
+        } else {  // every value is exact in bf16: keep the upper half
+          if (c & 1)
+            o[j][c / 2] = __builtin_amdgcn_perm(b, o[j][c / 2], 0x07060302u);
+          else
+            o[j][c / 2] = b;
+        }
+      }
+    }
+    const rsrc_t out = make_rsrc(dst + ((8 * rb) * cols + col0) * sizeof(T));
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (j < (int)nrows)
+        store16<true>(out, threadIdx.x * 16, j * row_bytes, make_uint4(o[j][0], o[j][1], o[j][2], o[j][3]));
+  }
+}
+
+}  // namespace rows
+}  // namespace exmy

@@ -1,0 +1,120 @@
+"""Parity of the entry points that pack along rows (through the C ABI) with the CPU
+oracle, tolerance 0: packed bytes and decoded bit patterns."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2405_13938_amd as exmy
+from oracle import exmy_oracle as O
+from paper_2405_13938_amd import synth
+
+pytestmark = pytest.mark.gpu
+
+DEV = "cuda:0"
+
+
+def odt(dtype):
+    return O.F32 if dtype == torch.float32 else O.BF16
+
+
+def ubits(a):
+    return a.view(np.uint32) if a.dtype == np.float32 else a
+
+
+def tbits(t):
+    return ubits(synth.bits_numpy(t))
+
+
+def formats_of_width(W, dtype):
+    P = 23 if dtype == torch.float32 else 7
+    return [(X, W - 1 - X) for X in range(0, min(W - 1, 8) + 1) if W - 1 - X <= (P if X >= 1 else P + 1)]
+
+
+def tensor_max_exp(X):
+    return 255 if X == 8 else (120 if X == 0 else max(130, (1 << X) - 1))
+
+
+def check_rows(x_dev, X, Y, max_exp=0, meta=None):
+    rows, cols = x_dev.shape
+    host = synth.bits_numpy(x_dev)
+    dt = odt(x_dev.dtype)
+    label = "e%dm%d %dx%d %s %s" % (X, Y, rows, cols, x_dev.dtype, "per-row" if meta is not None else "max_exp=%d" % max_exp)
+    meta_dev = None if meta is None else torch.from_numpy(meta).to(DEV)
+    want = O.encode_rows(host, rows, cols, X, Y, max_exp, meta)
+    got = exmy.encode_rows(x_dev, X, Y, max_exp, meta_dev)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), want), "encode_rows " + label
+    dec = exmy.decode_rows(torch.from_numpy(want).to(DEV), x_dev.dtype, rows, cols, X, Y, max_exp, meta_dev)
+    torch.cuda.synchronize()
+    want_dec = O.decode_rows(want, dt, rows, cols, X, Y, max_exp, meta)
+    assert np.array_equal(tbits(dec), ubits(want_dec)), "decode_rows " + label
+
+
+def per_row_meta(x_dev, X, kind, seed=0):
+    rows, cols = x_dev.shape
+    host = synth.bits_numpy(x_dev)
+    if kind == "before_rounding":
+        return O.block_max_exp(host, cols, X)
+    return np.random.default_rng(seed).integers(0, 256, rows).astype(np.uint8)  # any byte, out-of-range ones included
+
+
+@pytest.mark.parametrize("W", range(1, 17))
+def test_every_bf16_pattern_every_width(W):
+    # 65536 patterns as 128 x 512 and as 89 rows (ragged last row block) of 736 columns (partial column tile)
+    x = synth.shuffled(synth.all_bf16_patterns(), 300 + W).to(DEV)
+    shapes = [x.reshape(128, 512), x[: 89 * 736].reshape(89, 736).contiguous()]
+    for i, (X, Y) in enumerate(formats_of_width(W, torch.bfloat16)):
+        m = shapes[i % 2]
+        check_rows(m, X, Y, tensor_max_exp(X))
+        if X != 8:
+            check_rows(shapes[(i + 1) % 2], X, Y, meta=per_row_meta(shapes[(i + 1) % 2], X, "any_byte", seed=i))
+
+
+@pytest.mark.parametrize("W", range(1, 17))
+def test_fp32_sweep_every_width(W):
+    x = synth.shuffled(synth.f32_edge_sweep(seed=W), 400 + W).to(DEV)
+    shapes = [x[: 256 * 512].reshape(256, 512).contiguous(), x[: 203 * 328].reshape(203, 328).contiguous()]
+    for i, (X, Y) in enumerate(formats_of_width(W, torch.float32)):
+        m = shapes[i % 2]
+        check_rows(m, X, Y, tensor_max_exp(X))
+        if X != 8:
+            check_rows(shapes[(i + 1) % 2], X, Y, meta=per_row_meta(shapes[(i + 1) % 2], X, "any_byte", seed=i))
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_shapes(dtype):
+    g = torch.Generator().manual_seed(12)
+    for rows, cols in [(1, 8), (7, 8), (8, 8), (9, 16), (16, 504), (17, 512), (23, 520), (64, 1032), (5, 4096), (40, 11008)]:
+        x = (torch.randn(rows, cols, generator=g) * torch.exp2(torch.randint(-6, 6, (rows, 1), generator=g).float())).to(dtype).to(DEV)
+        for X, Y in ((3, 3), (2, 1), (0, 4)):
+            check_rows(x, X, Y, tensor_max_exp(X))
+            check_rows(x, X, Y, meta=per_row_meta(x, X, "before_rounding"))
+
+
+def test_wide_rounding_paths():
+    # metadata so large that the fp32 magic addend would overflow: the fp64 variant, per tensor and per tile
+    x = synth.shuffled(synth.f32_edge_sweep(seed=2), 2)[: 64 * 512].reshape(64, 512).contiguous().to(DEV)
+    check_rows(x, 3, 2, 254)
+    check_rows(x, 8, 7, 255)
+    meta = np.full(64, 200, dtype=np.uint8)
+    meta[8:16] = 254
+    meta[40] = 250
+    check_rows(x, 3, 2, meta=meta)
+
+
+def test_weight_matrix_per_row_metadata():
+    # Section 4.1: the block is the row of the weight matrix
+    x = synth.gaussian_bf16(1000 * 11008, seed=31).reshape(1000, 11008).to(DEV)
+    for X, Y in ((3, 2), (2, 1)):
+        meta = exmy.block_max_exp(x.reshape(-1), 11008, X)
+        torch.cuda.synchronize()
+        check_rows(x, X, Y, meta=meta.cpu().numpy())
+
+
+def test_empty_and_rejected_shapes():
+    e = torch.empty((0, 64), dtype=torch.bfloat16, device=DEV)
+    assert exmy.encode_rows(e, 3, 3, 130).numel() == 0
+    x = torch.zeros((8, 12), dtype=torch.bfloat16, device=DEV)
+    with pytest.raises(exmy.ExmyError) as err:
+        exmy.encode_rows(x, 3, 3, 130)
+    assert err.value.status == 8

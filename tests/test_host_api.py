@@ -197,3 +197,28 @@ def test_float_scaling_entry_points_validate_without_launch():
     assert dec(odd16, B.BF16, 64, 16, 3, 3, ok, ok, None) == 5
     assert emu(ok, B.BF16, 64, 16, 3, 3, odd4, None) == 5
     assert emu(ok, B.BF16, (1 << 40) + 8, 16, 3, 3, ok, None) == 4
+
+
+def test_row_packing_entry_points_validate_without_launch():
+    L = B.lib()
+    ok, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1008)
+    for rows, cols in ((0, 8), (1, 8), (8, 8), (9, 16), (4096, 11008)):
+        assert B.packed_bytes_rows(rows, cols, 3, 3) == ((rows + 7) // 8) * cols * 7 == O.packed_bytes_rows(rows, cols, 3, 3)
+    enc, dec = L.exmy_encode_rows, L.exmy_decode_rows
+    assert enc(ok, B.BF16, 0, 64, 3, 3, 130, None, ok, None) == 0
+    assert enc(ok, B.BF16, 64, 0, 3, 3, 130, None, ok, None) == 0
+    assert enc(None, B.BF16, 8, 8, 3, 3, 130, None, ok, None) == 1
+    assert enc(ok, B.BF16, 8, 8, 3, 3, 130, None, None, None) == 1
+    assert dec(ok, B.BF16, 8, 8, 3, 3, 130, None, None, None) == 1
+    assert enc(odd, B.BF16, 8, 8, 3, 3, 130, None, ok, None) == 5
+    assert dec(ok, B.BF16, 8, 8, 3, 3, 130, None, odd, None) == 5
+    assert enc(ok, B.BF16, 8, 8, 3, 3, 5, None, ok, None) == 3       # max_exp below 2^X - 1
+    assert enc(ok, B.BF16, 0, 8, 8, 7, 255, None, ok, None) == 0     # X = 8 with its fixed metadatum
+    assert enc(ok, B.BF16, 0, 8, 8, 7, 255, ok, ok, None) == 2       # but not with per-row metadata
+    assert enc(ok, B.BF16, 0, 8, 3, 3, 5, ok, ok, None) == 0         # max_exp is ignored with per-row metadata
+    assert enc(ok, B.F32, 8, 8, 3, 13, 130, None, ok, None) == 2
+    for cols in (1, 4, 12, 8 * 11 + 4, (1 << 26) + 8):
+        assert enc(ok, B.BF16, 8, cols, 3, 3, 130, None, ok, None) == 8
+        assert dec(ok, B.BF16, 8, cols, 3, 3, 130, None, ok, None) == 8
+    assert enc(ok, B.BF16, 1 << 30, 1 << 20, 3, 3, 130, None, ok, None) == 4
+    assert B.status_string(8).startswith("column count")
