@@ -235,6 +235,12 @@ def block_scheme_rates(exmy, synth, dev):
             "encode_scaled": (codec + 4 * nb, rot(lambda k: exmy.encode_scaled(xs[k], block, X, Y, scale, out=outs[k]))),
             "decode_scaled": (codec + 4 * nb, rot(lambda k: exmy.decode_scaled(outs[k], torch.bfloat16, n, block, X, Y, scale, out=dst))),
         }
+        if block == 11008:  # the same slab as a (32768, 11008) matrix packed along rows, one metadatum per row
+            rows, cols = n // block, block
+            ms = [x.view(rows, cols) for x in xs]
+            dm = dst.view(rows, cols)
+            rates["encode_rows_per_row_metadata"] = (codec + nb, rot(lambda k: exmy.encode_rows(ms[k], X, Y, 0, meta, out=outs[k])))
+            rates["decode_rows_per_row_metadata"] = (codec + nb, rot(lambda k: exmy.decode_rows(outs[k], torch.bfloat16, rows, cols, X, Y, 0, meta, out=dm)))
         res[label] = {name: round(nbytes / timed(fn) / 1e9, 1) for name, (nbytes, fn) in rates.items()}
         res[label]["unit"] = "GB/s"
     return res

@@ -147,40 +147,65 @@ __device__ __forceinline__ void make_plane_rsrc(uint8_t* packed, uint64_t R, uin
   }
 }
 
-// Constants of the 8 rows of row block rb.
+// Metadata of the 8 rows of row block rb: lane l fetches the byte of row 8 rb + (l & 7),
+// one load for the whole block.  Every lane of the wavefront must call it.
 template <bool kPerRow>
-__device__ __forceinline__ void row_constants(const RowsArgs& a, uint64_t rb, TensorConsts tc[8], bool& any_wide) {
-  any_wide = false;
+__device__ __forceinline__ uint32_t load_row_metadata(const RowsArgs& a, uint64_t rb) {
+  uint32_t mv = a.bc.meta_lo;
+  if constexpr (kPerRow) {
+    const uint64_t row = 8 * rb + (threadIdx.x & 7u);
+    if (row < a.rows) mv = a.meta[row];
+  }
+  return mv;
+}
+
+// Constants of the 8 rows from the bytes that lanes 0-7 hold (wave-uniform results).
+//
+// A metadatum so large that the fp32 rounding addend 2^(ec-127+23-Y) would overflow
+// (max_exp > 231 + Y; values beyond 2^104) is handled without the fp64 variant: the
+// row's values are multiplied by 2^-64 and its metadatum lowered by 64.  That is
+// exact for every value that does not flush to zero anyway: in such a row the
+// subnormal quantum is above 2^-46, while only values under 2^-62 underflow.
+template <bool kPerRow>
+__device__ __forceinline__ void row_constants(const RowsArgs& a, uint32_t mv, TensorConsts tc[8], float pre[8],
+                                              bool& any_pre) {
+  any_pre = false;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
+    pre[j] = 1.0f;
     if constexpr (kPerRow) {
-      const uint64_t row = 8 * rb + j;
-      const uint32_t me = row < a.rows ? __builtin_amdgcn_readfirstlane((uint32_t)a.meta[row]) : a.bc.meta_lo;
+      uint32_t me = min(max((uint32_t)__builtin_amdgcn_readlane(mv, j), a.bc.meta_lo), a.bc.meta_hi);
+      if (me > a.bc.wide_above) {
+        me -= 64u;
+        pre[j] = as_f32((127u - 64u) << 23);
+        any_pre = true;
+      }
       tc[j] = derive_tc(me, a.bc);
-      any_wide = any_wide || min(max(me, a.bc.meta_lo), a.bc.meta_hi) > a.bc.wide_above;
     } else {
       tc[j] = a.tc;
     }
   }
 }
 
-template <typename T, int W, int kCols, bool kWide>
+// kPre: multiply row j by pre[j] first (see row_constants).
+template <typename T, int W, int kCols, bool kWide, bool kPre>
 __device__ __forceinline__ void encode_columns(const uint4 v[8], const FormatConsts& fc, const TensorConsts tc[8],
-                                               LaneWords<W, kCols>& lw) {
+                                               const float pre[8], LaneWords<W, kCols>& lw) {
 #pragma unroll
   for (int c = 0; c < kCols; ++c) {
     uint32_t u[8], f[8];
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       u[j] = column_bits<T>(v[j], c);
-      const uint32_t m = magnitude_code_left<kWide>(u[j], fc, tc[j]);
+      const uint32_t a = kPre ? as_u32(as_f32(u[j]) * pre[j]) : u[j];
+      const uint32_t m = magnitude_code_left<kWide>(a, fc, tc[j]);
       f[j] = (W & 1) ? m : ((u[j] & 0x80000000u) | m);
     }
     peel_column<W, kCols, Planes<W>::count - 1>(f, u, c, lw);
   }
 }
 
-// kWide: per-tensor metadata only (with per-row metadata the variant is chosen per tile).
+// kWide: per-tensor metadata only (per-row metadata never needs the fp64 variant, see row_constants).
 template <typename T, int W, int kBlock, bool kPerRow, bool kWide>
 __global__ __launch_bounds__(kBlock) void encode_rows_kernel(const RowsArgs args) {
   constexpr int kCols = 16 / sizeof(T);
@@ -198,6 +223,7 @@ __global__ __launch_bounds__(kBlock) void encode_rows_kernel(const RowsArgs args
     uint32_t ct;
     tile_first_block(t, args.tiles, rb, ct);
     const uint32_t col0 = ct * kTileCols;
+    const uint32_t mv = load_row_metadata<kPerRow>(args, rb);
     if (col0 + threadIdx.x * kCols >= cols) continue;
     const uint64_t left = args.rows - 8 * rb;
     const uint32_t nrows = left < 8 ? (uint32_t)left : 8u;
@@ -211,16 +237,17 @@ __global__ __launch_bounds__(kBlock) void encode_rows_kernel(const RowsArgs args
         v[j] = make_uint4(0, 0, 0, 0);  // rows past the end hold zero codes
     }
     TensorConsts tc[8];
-    bool any_wide;
-    row_constants<kPerRow>(args, rb, tc, any_wide);
+    float pre[8];
+    bool any_pre;
+    row_constants<kPerRow>(args, mv, tc, pre, any_pre);
     LaneWords<W, kCols> lw;
     if constexpr (kPerRow) {
-      if (any_wide)
-        encode_columns<T, W, kCols, true>(v, fc, tc, lw);
+      if (any_pre)
+        encode_columns<T, W, kCols, false, true>(v, fc, tc, pre, lw);
       else
-        encode_columns<T, W, kCols, false>(v, fc, tc, lw);
+        encode_columns<T, W, kCols, false, false>(v, fc, tc, pre, lw);
     } else {
-      encode_columns<T, W, kCols, kWide>(v, fc, tc, lw);
+      encode_columns<T, W, kCols, kWide, false>(v, fc, tc, pre, lw);
     }
     rsrc_t plane[Planes<W>::count];
     make_plane_rsrc<W>(dst, R, cols, rb, col0, plane);
@@ -262,6 +289,7 @@ __global__ __launch_bounds__(kBlock) void decode_rows_kernel(const RowsArgs args
     uint32_t ct;
     tile_first_block(t, args.tiles, rb, ct);
     const uint32_t col0 = ct * kTileCols;
+    const uint32_t mv = load_row_metadata<kPerRow>(args, rb);
     if (col0 + threadIdx.x * kCols >= cols) continue;
     const uint64_t left = args.rows - 8 * rb;
     const uint32_t nrows = left < 8 ? (uint32_t)left : 8u;
@@ -270,8 +298,13 @@ __global__ __launch_bounds__(kBlock) void decode_rows_kernel(const RowsArgs args
     LaneWords<W, kCols> lw;
     move_words<W, kCols, false>(lw, plane, threadIdx.x);
     TensorConsts tc[8];
-    bool any_wide;
-    row_constants<kPerRow>(args, rb, tc, any_wide);
+    if constexpr (kPerRow) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) tc[j] = derive_tc(__builtin_amdgcn_readlane(mv, j), args.bc);
+    } else {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) tc[j] = args.tc;
+    }
 
     uint32_t o[8][4];  // the lane's 16 bytes of every row
 #pragma unroll
