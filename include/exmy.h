@@ -23,7 +23,11 @@
  *    max_exp = 255 exactly for X = 8 (identity exponent map).
  *  - A format fits a container when X <= 8 and Y <= 7 (bf16) / 23 (fp32)
  *    (Section 2.1); with X = 0 one more mantissa bit is allowed.  Packed codes
- *    are limited to W <= 16.
+ *    are limited to W <= 31 (segments of 16, 8, 4, 2 and 1 bits; widths above
+ *    16 need the fp32 container) in exmy_encode / exmy_decode and their batch
+ *    and histogram forms, and to W <= 16 in the per-block, float-scaling and
+ *    row-packing entry points.  e0m24 has no packed form (use e1m23, which it
+ *    equals bit for bit).
  *  - Rounding is round-to-nearest-even to Y mantissa bits (Section 2
  *    "Rounding"); a tie goes to the even multiple of the quantum of the value's
  *    binade.  Values under the smallest normal are rounded on the subnormal
@@ -77,7 +81,7 @@ typedef enum {
 size_t exmy_packed_bytes(uint64_t n, int X, int Y);
 
 /* Host-side validation of (dtype, X, Y, max_exp) as described above.  `packed`
- * non-zero also applies the W <= 16 limit of the packed form. */
+ * non-zero also applies the W <= 31 limit of the packed form. */
 exmy_status_t exmy_check_format(exmy_dtype_t dt, int X, int Y, int max_exp, int packed);
 
 /* Encode (Sections 2.2.1 + 2.2.2 fused): round n elements of type dt at `src`

@@ -108,7 +108,8 @@ int check_format(int dt, int X, int Y, int max_exp, bool packed, Format* f) {
   if (X < 0 || X > 8 || Y < 0) return ORACLE_ERR_FORMAT;
   const int P = container_mantissa(dt);
   if (X >= 1 ? (Y > P) : (Y > P + 1)) return ORACLE_ERR_FORMAT;
-  if (packed && 1 + X + Y > 16) return ORACLE_ERR_FORMAT;
+  if (packed && 1 + X + Y > 31) return ORACLE_ERR_FORMAT;  // segments of 16, 8, 4, 2 and 1 bits reach 31
+  if (packed && Y > 23) return ORACLE_ERR_FORMAT;          // e0m24 packs as e1m23, which it equals bit for bit
   if (X == 8) {
     if (max_exp != 255) return ORACLE_ERR_MAX_EXP;
   } else if (X == 0) {
@@ -337,14 +338,14 @@ int exmy_oracle_from_codes(const uint32_t* codes, int dt, uint64_t n, int X, int
 // Step 2 of the codec (Section 2.2.2): W-bit codes -> planes.
 int exmy_oracle_pack(const uint32_t* codes, uint64_t n, int W, uint8_t* out, int threads) {
   if ((!codes || !out) && n) return ORACLE_ERR_NULL;
-  if (W < 1 || W > 16) return ORACLE_ERR_FORMAT;
+  if (W < 1 || W > 31) return ORACLE_ERR_FORMAT;
   parallel_ranges((n + 7) / 8, threads, [&](uint64_t a, uint64_t b) { pack_groups(codes, 0, n, W, out, a, b); });
   return ORACLE_OK;
 }
 
 int exmy_oracle_unpack(const uint8_t* in, uint64_t n, int W, uint32_t* codes, int threads) {
   if ((!codes || !in) && n) return ORACLE_ERR_NULL;
-  if (W < 1 || W > 16) return ORACLE_ERR_FORMAT;
+  if (W < 1 || W > 31) return ORACLE_ERR_FORMAT;
   parallel_ranges((n + 7) / 8, threads, [&](uint64_t a, uint64_t b) { unpack_groups(in, n, W, codes, 0, a, b); });
   return ORACLE_OK;
 }
@@ -433,6 +434,9 @@ int exmy_oracle_max_exp_from_histogram(const uint64_t* hist256, double coverage)
 // container); values outside are clamped into that range.  X = 8 has no
 // per-block metadata.
 
+// The per-block, float-scaling and row-packing forms stop at 16-bit codes.
+static const int kBlockWidth = 16;
+
 static int block_meta_range(int X, int* lo, int* hi) {
   if (X < 0 || X > 7) return ORACLE_ERR_FORMAT;
   *lo = X == 0 ? 1 : (1 << X);
@@ -504,6 +508,7 @@ static int blocks_op(int what, const void* src, void* dst, int dt, uint64_t n, u
   if (int rc = block_meta_range(X, &lo, &hi)) return rc;
   Format f0;
   if (int rc = check_format(dt, X, Y, hi, what != 2, &f0)) return rc;
+  if (what != 2 && 1 + X + Y > kBlockWidth) return ORACLE_ERR_FORMAT;
   const uint64_t nb = (n + block - 1) / block;
   const int W = 1 + X + Y;
   std::vector<uint32_t> codes;
@@ -596,6 +601,7 @@ static int scaled_op(int what, const void* src, void* dst, int dt, uint64_t n, u
   if (block == 0 || block % 8) return ORACLE_ERR_FORMAT;
   Format f;
   if (int rc = scaled_format(dt, X, Y, what != 2, &f)) return rc;
+  if (what != 2 && 1 + X + Y > kBlockWidth) return ORACLE_ERR_FORMAT;
   const uint64_t nb = (n + block - 1) / block;
   const int W = 1 + X + Y;
   std::vector<uint32_t> codes;
@@ -675,6 +681,7 @@ static int rows_op(int what, const void* src, void* dst, int dt, uint64_t rows, 
     if (int rc = check_format(dt, X, Y, max_exp, true, &f0)) return rc;
   }
   const int W = 1 + X + Y;
+  if (W > kBlockWidth) return ORACLE_ERR_FORMAT;
   const uint64_t R = (rows + 7) / 8;
   int seg[8];
   const int np = plane_list(W, seg);

@@ -38,7 +38,7 @@ int compute_units() {
   return cu;
 }
 
-exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, bool packed, FormatConsts* fc,
+exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, int max_width, FormatConsts* fc,
                           TensorConsts* tc, bool* needs_wide) {
   if (dt != EXMY_F32 && dt != EXMY_BF16) return EXMY_ERR_FORMAT;
   if (X < 0 || X > 8 || Y < 0) return EXMY_ERR_FORMAT;
@@ -46,7 +46,8 @@ exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, bool packe
   // no leading one, so its Y bits need only Y significant bits of the container.
   const int P = dt == EXMY_F32 ? 23 : 7;
   if (Y > (X >= 1 ? P : P + 1)) return EXMY_ERR_FORMAT;
-  if (packed && 1 + X + Y > 16) return EXMY_ERR_FORMAT;
+  if (1 + X + Y > max_width) return EXMY_ERR_FORMAT;
+  if (max_width != kAnyWidth && Y > 23) return EXMY_ERR_FORMAT;  // e0m24 packs as e1m23, which it equals bit for bit
   if (X == 8) {
     if (max_exp != 255) return EXMY_ERR_MAX_EXP;
   } else if (X == 0) {
@@ -98,15 +99,18 @@ exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, bool packe
   // The fp32 magic addend 2^(ec-127+23-Y) must be finite for the largest clamped
   // exponent ec, and the sum must stay in the addend's binade (Y <= 21).
   const int ec_max = X == 0 ? emin8 : (X == 8 ? 254 : max_exp);
-  if (needs_wide) *needs_wide = (ec_max + 23 - Y > 254) || (Y > 21);
+  // Codes of more than 23 bits (24 with the sign riding along) would also pick up exponent
+  // bits of the fp32 sum when it is shifted left; the fp64 sum has zeros there.
+  const int kept = X + Y + ((W & 1) ? 0 : 1);
+  if (needs_wide) *needs_wide = (ec_max + 23 - Y > 254) || (Y > 21) || (kept > 23);
   return EXMY_OK;
 }
 
-exmy_status_t make_block_format(exmy_dtype_t dt, int X, int Y, bool packed, bool after_rounding, FormatConsts* fc,
+exmy_status_t make_block_format(exmy_dtype_t dt, int X, int Y, int max_width, bool after_rounding, FormatConsts* fc,
                                 BlockConsts* bc) {
   if (X == 8) return EXMY_ERR_FORMAT;  // identity exponent map: nothing for a block to choose
   const int hi = X == 0 ? 253 : 254;
-  if (exmy_status_t st = make_format(dt, X, Y, hi, packed, fc, nullptr, nullptr)) return st;
+  if (exmy_status_t st = make_format(dt, X, Y, hi, max_width, fc, nullptr, nullptr)) return st;
   if (bc) {
     const int W = 1 + X + Y;
     const int L = ((W & 1) ? 32 : 31) - (X + Y);
@@ -158,7 +162,7 @@ exmy_status_t run_batch(Op op, const exmy_tensor_t* tensors, size_t count, exmy_
   for (size_t i = 0; i < count; ++i) {
     const exmy_tensor_t& t = tensors[i];
     bool wide = false;
-    if (exmy_status_t st = make_format(dt, X, Y, t.max_exp, true, &fc, nullptr, &wide)) return st;
+    if (exmy_status_t st = make_format(dt, X, Y, t.max_exp, kFlatWidth, &fc, nullptr, &wide)) return st;
     any_wide = any_wide || wide;
     if (t.n > EXMY_MAX_ELEMENTS) return EXMY_ERR_COUNT;
     if (t.n == 0) continue;
@@ -203,7 +207,7 @@ exmy_status_t run_batch(Op op, const exmy_tensor_t* tensors, size_t count, exmy_
     ta.src = t.src;
     ta.dst = t.dst;
     ta.n = t.n;
-    make_format(dt, X, Y, t.max_exp, true, nullptr, &ta.tc, nullptr);
+    make_format(dt, X, Y, t.max_exp, kFlatWidth, nullptr, &ta.tc, nullptr);
   }
   return flush() == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
 }
@@ -217,14 +221,16 @@ exmy_status_t run_blocks(BlockOp op, bool scaled, const void* elems, const void*
                          uint64_t block, int X, int Y, const void* side, void* stream) {
   BlockArgs args;
   const bool is_packed = op == BlockOp::kEncode || op == BlockOp::kDecode;
-  if (exmy_status_t st = make_block_format(dt, X, Y, is_packed, op == BlockOp::kMaxExpRounded, &args.fc, &args.bc))
+  if (exmy_status_t st = make_block_format(dt, X, Y, is_packed ? kBlockWidth : kAnyWidth, op == BlockOp::kMaxExpRounded, &args.fc,
+                                            &args.bc))
     return st;
   bool wide_format = Y > 21;
   args.vmax127 = 0.0f;
   if (scaled) {
     // codes of the max_exp = 127 format; a format whose only magnitude is 0 has nothing to scale
     if (X == 0 && Y == 0) return EXMY_ERR_FORMAT;
-    if (exmy_status_t st = make_format(dt, X, Y, 127, is_packed, nullptr, &args.tc127, &wide_format)) return st;
+    if (exmy_status_t st = make_format(dt, X, Y, 127, is_packed ? kBlockWidth : kAnyWidth, nullptr, &args.tc127,
+                                       &wide_format)) return st;
     uint32_t sat = args.tc127.sat_bits;
     memcpy(&args.vmax127, &sat, 4);
   }
@@ -278,10 +284,10 @@ exmy_status_t run_rows(RowsOp op, const void* matrix, const void* packed, exmy_d
   RowsArgs args;
   bool wide = false;
   if (max_exp_rows) {
-    if (exmy_status_t st = make_block_format(dt, X, Y, true, false, &args.fc, &args.bc)) return st;
+    if (exmy_status_t st = make_block_format(dt, X, Y, kBlockWidth, false, &args.fc, &args.bc)) return st;
     memset(&args.tc, 0, sizeof(args.tc));
   } else {
-    if (exmy_status_t st = make_format(dt, X, Y, max_exp, true, &args.fc, &args.tc, &wide)) return st;
+    if (exmy_status_t st = make_format(dt, X, Y, max_exp, kBlockWidth, &args.fc, &args.tc, &wide)) return st;
     memset(&args.bc, 0, sizeof(args.bc));
   }
   if (cols % 8 || cols > EXMY_MAX_COLS) return EXMY_ERR_SHAPE;
@@ -314,7 +320,7 @@ extern "C" {
 size_t exmy_packed_bytes(uint64_t n, int X, int Y) { return (size_t)(((n + 7) / 8) * (uint64_t)(1 + X + Y)); }
 
 exmy_status_t exmy_check_format(exmy_dtype_t dt, int X, int Y, int max_exp, int packed) {
-  return make_format(dt, X, Y, max_exp, packed != 0, nullptr, nullptr, nullptr);
+  return make_format(dt, X, Y, max_exp, packed ? kFlatWidth : kAnyWidth, nullptr, nullptr, nullptr);
 }
 
 exmy_status_t exmy_encode(const void* src, exmy_dtype_t dt, uint64_t n, int X, int Y, int max_exp,
@@ -349,7 +355,7 @@ exmy_status_t exmy_emulate(void* data_inout, exmy_dtype_t dt, uint64_t n, int X,
   FormatConsts fc;
   TensorConsts tc;
   bool wide = false;
-  if (exmy_status_t st = make_format(dt, X, Y, max_exp, false, &fc, &tc, &wide)) return st;
+  if (exmy_status_t st = make_format(dt, X, Y, max_exp, kAnyWidth, &fc, &tc, &wide)) return st;
   if (n > EXMY_MAX_ELEMENTS) return EXMY_ERR_COUNT;
   if (n == 0) return EXMY_OK;
   if (!data_inout) return EXMY_ERR_NULL;
@@ -386,7 +392,7 @@ exmy_status_t exmy_encode_blocks_auto(const void* src, exmy_dtype_t dt, uint64_t
                                       exmy_scheme_t scheme, uint8_t* max_exp_dev, void* dst_packed, void* stream) {
   if (scheme != EXMY_MAX_EXP_BEFORE_ROUNDING && scheme != EXMY_MAX_EXP_AFTER_ROUNDING) return EXMY_ERR_FORMAT;
   // validate the second launch before the first, so that an error leaves both outputs untouched
-  if (exmy_status_t st = make_block_format(dt, X, Y, true, false, nullptr, nullptr)) return st;
+  if (exmy_status_t st = make_block_format(dt, X, Y, kBlockWidth, false, nullptr, nullptr)) return st;
   if (n && !dst_packed) return EXMY_ERR_NULL;
   if (n && !aligned16(dst_packed)) return EXMY_ERR_ALIGN;
   const BlockOp op = scheme == EXMY_MAX_EXP_AFTER_ROUNDING ? BlockOp::kMaxExpRounded : BlockOp::kMaxExp;

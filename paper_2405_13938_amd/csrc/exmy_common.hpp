@@ -146,14 +146,20 @@ inline BlockIndex make_block_index(uint64_t size) {
   return bi;
 }
 
+constexpr int kFlatWidth = 31;   // segments of 16, 8, 4, 2 and 1 bits
+constexpr int kBlockWidth = 16;
+constexpr int kAnyWidth = 64;
+
 // Host: validate (dtype, X, Y, max_exp) and fill the constants (either may be
-// null).  `packed` applies the W <= 16 limit of the packed form.
-exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, bool packed, FormatConsts* fc,
+// null).  max_width: largest W the caller's kernels handle (kFlatWidth for the
+// per-tensor packed form, kBlockWidth for the per-block, scaled and row-packed
+// forms, kAnyWidth for emulation, which has no packed form).
+exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, int max_width, FormatConsts* fc,
                           TensorConsts* tc, bool* needs_wide);
 
 // Host: validate (dtype, X, Y) for per-block metadata and fill fc / bc.
 // after_rounding selects the scheme of the maximum-exponent kernel.
-exmy_status_t make_block_format(exmy_dtype_t dt, int X, int Y, bool packed, bool after_rounding, FormatConsts* fc,
+exmy_status_t make_block_format(exmy_dtype_t dt, int X, int Y, int max_width, bool after_rounding, FormatConsts* fc,
                                 BlockConsts* bc);
 
 #if defined(__HIPCC__)

@@ -48,8 +48,14 @@ hipError_t dispatch_w(int W, const BatchArgs& args, uint64_t n_max, hipStream_t 
     return launch_encode<T, w, kWide, kHist>(args, n_max, stream);
     EXMY_CASE(1) EXMY_CASE(2) EXMY_CASE(3) EXMY_CASE(4) EXMY_CASE(5) EXMY_CASE(6) EXMY_CASE(7) EXMY_CASE(8)
     EXMY_CASE(9) EXMY_CASE(10) EXMY_CASE(11) EXMY_CASE(12) EXMY_CASE(13) EXMY_CASE(14) EXMY_CASE(15) EXMY_CASE(16)
-#undef EXMY_CASE
   }
+  if constexpr (sizeof(T) == 4) {  // only fp32 holds formats wider than 16 bits
+    switch (W) {
+      EXMY_CASE(17) EXMY_CASE(18) EXMY_CASE(19) EXMY_CASE(20) EXMY_CASE(21) EXMY_CASE(22) EXMY_CASE(23) EXMY_CASE(24)
+      EXMY_CASE(25) EXMY_CASE(26) EXMY_CASE(27) EXMY_CASE(28) EXMY_CASE(29) EXMY_CASE(30) EXMY_CASE(31)
+    }
+  }
+#undef EXMY_CASE
   return hipErrorInvalidValue;
 }
 

@@ -49,7 +49,7 @@ def check_all(x_dev, X, Y, max_exp, host=None, what=("encode", "decode", "emulat
         host = synth.bits_numpy(x_dev)
     dt = odt(x_dev)
     label = "e%dm%d max_exp=%d n=%d %s" % (X, Y, max_exp, n, x_dev.dtype)
-    if 1 + X + Y <= 16 and ("encode" in what or "decode" in what):
+    if 1 + X + Y <= 31 and Y <= 23 and ("encode" in what or "decode" in what):
         want_packed = O.encode(host, X, Y, max_exp, threads=THREADS)
         if "encode" in what:
             got = exmy.encode(x_dev.reshape(-1), X, Y, max_exp)
@@ -100,7 +100,7 @@ def test_every_bf16_pattern_every_format(W):
             check_all(x, X, Y, max_exp, host)
 
 
-@pytest.mark.parametrize("W", range(1, 17))
+@pytest.mark.parametrize("W", range(1, 32))
 def test_fp32_edge_sweep_every_format(W):
     """fp32 patterns at and around every rounding tie of every exponent, plus random bits."""
     x = synth.f32_edge_sweep()
@@ -109,6 +109,42 @@ def test_fp32_edge_sweep_every_format(W):
     for X, Y in formats_of_width(W, torch.float32):
         for max_exp in some_max_exps(X):
             check_all(x, X, Y, max_exp, host)
+
+
+@pytest.mark.parametrize("W", range(17, 32))
+def test_sampled_code_points_of_wide_formats_decode(W):
+    """Formats wider than 16 bits: sampled codes (both ends of the code space included) through the packed form."""
+    rng = np.random.default_rng(W)
+    mags = np.unique(np.concatenate([rng.integers(0, 1 << (W - 1), 100000), np.arange(0, 2000),
+                                     (1 << (W - 1)) - 1 - np.arange(0, 2000)])).astype(np.uint32)
+    codes = np.concatenate([mags, mags | np.uint32(1 << (W - 1))])[:-3]  # ragged
+    n = codes.size
+    pd = torch.from_numpy(O.pack(codes, W)).to(DEV)
+    for X, Y in formats_of_width(W, torch.float32):
+        if Y > 23:
+            continue  # e0m24 has no packed form
+        for max_exp in some_max_exps(X):
+            got = exmy.decode(pd, torch.float32, n, X, Y, max_exp)
+            torch.cuda.synchronize()
+            assert np.array_equal(tbits(got), ubits(O.from_codes(codes, O.F32, X, Y, max_exp))), (W, X, Y, max_exp)
+
+
+def test_wide_formats_batch_and_histogram():
+    xs = [synth.cfg1(n=(1 << 18) + 8 * k + k, seed=k)[0].to(DEV) for k in range(5)]
+    for X, Y in ((8, 10), (5, 14), (4, 23), (8, 22)):
+        me = 255 if X == 8 else 131
+        outs = exmy.encode_batch(xs, X, Y, [me] * 5)
+        torch.cuda.synchronize()
+        for x, o in zip(xs, outs):
+            assert np.array_equal(o.cpu().numpy(), O.encode(synth.bits_numpy(x), X, Y, me, threads=THREADS))
+        decs = exmy.decode_batch(outs, torch.float32, [x.numel() for x in xs], X, Y, [me] * 5)
+        torch.cuda.synchronize()
+        for x, o, d in zip(xs, outs, decs):
+            assert np.array_equal(tbits(d), ubits(O.decode(o.cpu().numpy(), O.F32, x.numel(), X, Y, me, threads=THREADS)))
+        p, h = exmy.encode_with_histogram(xs[0], X, Y, me)
+        torch.cuda.synchronize()
+        assert torch.equal(p, outs[0])
+        assert np.array_equal(h.cpu().numpy().astype(np.uint64), O.exponent_histogram(synth.bits_numpy(xs[0])))
 
 
 def test_emulate_wider_than_packable():

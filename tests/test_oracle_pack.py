@@ -22,7 +22,7 @@ def test_paper_plane_sizes(golden):
         assert O.pack(codes, W).size == W
 
 
-@pytest.mark.parametrize("W", range(1, 17))
+@pytest.mark.parametrize("W", range(1, 32))
 def test_roundtrip_and_size(W):
     rng = np.random.default_rng(W)
     for n in (0, 1, 7, 8, 9, 64, 1000, 4099):
@@ -33,7 +33,7 @@ def test_roundtrip_and_size(W):
         assert np.array_equal(O.pack(codes, W, threads=3), p)
 
 
-@pytest.mark.parametrize("W", [3, 5, 6, 7, 9, 12, 16])
+@pytest.mark.parametrize("W", [3, 5, 6, 7, 9, 12, 16, 17, 23, 31])
 def test_walking_one_bit_positions(W):
     """Code bit b of element j lands in exactly one bit of the blob: plane of the segment
     that owns b (widest plane owns the lowest bits), group word g, bit s*j + (b - lo)."""

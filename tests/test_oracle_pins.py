@@ -269,7 +269,8 @@ def test_nearest_value_bruteforce_all_bf16(X, Y):
         assert np.array_equal(got[nf] >> (X + Y), (bits[nf] >> 15).astype(np.uint32))
 
 
-@pytest.mark.parametrize("X,Y", [(3, 3), (4, 2), (2, 3), (5, 0), (0, 6), (1, 5), (8, 0), (8, 7), (4, 11), (2, 13), (0, 15)])
+@pytest.mark.parametrize("X,Y", [(3, 3), (4, 2), (2, 3), (5, 0), (0, 6), (1, 5), (8, 0), (8, 7), (4, 11), (2, 13), (0, 15),
+                                 (4, 14), (8, 10), (2, 19), (5, 16), (1, 21)])  # the last five: packed widths above 16
 def test_nearest_value_bruteforce_fp32_sweep(X, Y):
     x = synth.f32_edge_sweep()
     xs = x.numpy()
@@ -305,6 +306,31 @@ def test_every_code_point(X, Y):
             assert np.array_equal((dec16.astype(np.uint32) << 16), dec.view(np.uint32))
 
 
+@pytest.mark.parametrize("X,Y", [(8, 10), (5, 11), (4, 14), (7, 16), (3, 20), (8, 22), (6, 23), (0, 23), (1, 23)])
+def test_sampled_code_points_of_wide_formats(X, Y):
+    """Formats wider than 16 bits (fp32 container only): decode is the textbook formula on sampled codes,
+    encode(decode(c)) == c, and codes survive the packed form."""
+    W = 1 + X + Y
+    rng = np.random.default_rng(W)
+    mags = np.unique(np.concatenate([rng.integers(0, 1 << (X + Y), 20000), np.arange(0, 300),
+                                     (1 << (X + Y)) - 1 - np.arange(0, 300)])).astype(np.uint32)
+    codes = np.concatenate([mags, mags | np.uint32(1 << (X + Y))])
+    for max_exp in _max_exps(X):
+        b = (1 << X) - 1 + 127 - max_exp
+        E, M = (mags >> Y).astype(np.int64), (mags & ((1 << Y) - 1)).astype(np.int64)
+        vals = np.where(E == 0, np.ldexp(M.astype(np.float64), 1 - b - Y),
+                        np.ldexp(((1 << Y) + M).astype(np.float64), (E - b - Y).astype(np.int64)))
+        if X == 8:
+            vals = np.minimum(vals, np.ldexp(2.0 - 2.0 ** -Y, 127))
+        dec = O.from_codes(codes, F32, X, Y, max_exp)
+        assert np.array_equal(dec.astype(np.float64), np.concatenate([vals, -vals]))
+        back = O.to_codes(dec, X, Y, max_exp)
+        keep = np.concatenate([E, E]) < 255 if X == 8 else np.ones(codes.size, dtype=bool)
+        assert np.array_equal(back[keep], codes[keep])
+        if W <= 31:
+            assert np.array_equal(O.unpack(O.pack(codes, W), codes.size, W), codes)
+
+
 def test_sum_of_code_points():
     assert sum(W * (1 << W) for W in range(3, 10)) == 8184
     assert len(FORMATS_3_TO_9) == 42
@@ -324,7 +350,7 @@ def test_emulate_properties():
         # idempotent, sign kept (also for values flushed to zero)
         assert np.array_equal(O.emulate(e, X, Y, max_exp).view(np.uint32), e.view(np.uint32))
         assert np.array_equal(np.signbit(e), np.signbit(xs))
-        if 1 + X + Y <= 16:
+        if 1 + X + Y <= 31:
             fin = ~nonfinite
             d = O.from_codes(O.to_codes(xs, X, Y, max_exp), F32, X, Y, max_exp)
             assert np.array_equal(d.view(np.uint32)[fin], e.view(np.uint32)[fin])
@@ -336,8 +362,10 @@ def test_format_validation():
     assert O.check_format(BF16, 1, 8, 130) != 0
     assert O.check_format(BF16, 0, 9, 130) != 0
     assert O.check_format(F32, 9, 0, 130) != 0
-    assert O.check_format(F32, 4, 12, 130) != 0  # W = 17 cannot be packed here
-    assert O.check_format(F32, 4, 12, 130, packed=False) == 0
+    assert O.check_format(F32, 4, 12, 130) == 0  # W = 17 = 16 + 1 packs
+    assert O.check_format(F32, 8, 22, 255) == 0  # W = 31 = 16 + 8 + 4 + 2 + 1, the widest packed form
+    assert O.check_format(F32, 8, 23, 255) != 0  # W = 32 would need a 32-bit segment
+    assert O.check_format(F32, 8, 23, 255, packed=False) == 0
     assert O.check_format(F32, 8, 3, 254) != 0 and O.check_format(F32, 8, 3, 255) == 0
     assert O.check_format(F32, 3, 3, 6) != 0 and O.check_format(F32, 3, 3, 7) == 0
     assert O.check_format(F32, 3, 3, 255) != 0
