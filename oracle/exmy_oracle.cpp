@@ -52,6 +52,11 @@
 //     group of output position (r, c) is elements (8r + j, c), j = 0..7, of the
 //     row-major matrix; rows beyond the last are zero codes; each plane is a
 //     row-major (R, C) array of words, planes back to back, widest first;
+//   - two's complement reading of X = 0 (Section 2 "Format": e0m3 used as int4
+//     represents [-8, 7]): the W = 1 + Y bits are a two's complement integer k in
+//     [-2^Y, 2^Y - 1] and the value is k quanta; k = round-half-even(x / quantum),
+//     clamped; Inf / NaN go to the end of the range on the side of their sign bit;
+//     -0 and negative values that round to 0 give k = 0, which decodes to +0;
 //   - "float scaling with maximum exponent 127" (Section 2 "Metadata", Section
 //     2.1): the paper gives no formulas.  Reading: the block's scale is
 //     s = max|x| / vmax in fp32 (vmax = largest value of the format with
@@ -735,6 +740,83 @@ int exmy_oracle_encode_rows(const void* src, int dt, uint64_t rows, uint64_t col
 int exmy_oracle_decode_rows(const uint8_t* src_packed, int dt, uint64_t rows, uint64_t cols, int X, int Y,
                             int max_exp, const uint8_t* max_exp_rows, void* dst) {
   return rows_op(1, src_packed, dst, dt, rows, cols, X, Y, max_exp, max_exp_rows);
+}
+
+// ---------------------------------------------------------------------------
+// Two's complement reading of the X = 0 formats (Section 2 "Format": instead of
+// (sign, magnitude) with its double zero, the 1 + Y bits are a two's complement
+// number, which gains one encoding: e0m3 as int4 covers [-8, 7]).  The quantum
+// is that of e0mY with the same max_exp: 2^(max_exp + 1 - 127 - Y).
+
+static int int_format(int dt, int Y, int max_exp, bool packed, Format* f) {
+  if (int rc = check_format(dt, 0, Y, max_exp, packed, f)) return rc;
+  if (packed && 1 + Y > kBlockWidth) return ORACLE_ERR_FORMAT;
+  // -2^Y quanta = -2^(max_exp + 1 - 127) must be a value of the container (it always is), and Y >= 1
+  // keeps at least one magnitude bit (with Y = 0 the range would be [-1, 0])
+  if (Y < 1) return ORACLE_ERR_FORMAT;
+  return ORACLE_OK;
+}
+
+static int64_t int_code(const Format& f, uint32_t bits) {
+  const float x = bits_to_float(bits);
+  const int64_t lo = -((int64_t)1 << f.Y), hi = ((int64_t)1 << f.Y) - 1;
+  const bool neg = (bits >> 31) != 0;
+  if (std::isnan(x) || std::isinf(x)) return neg ? lo : hi;
+  const double k = std::nearbyint(std::ldexp((double)x, -(f.emin8 - 127 - f.Y)));  // x / quantum is exact
+  return k < (double)lo ? lo : (k > (double)hi ? hi : (int64_t)k);
+}
+
+static float int_value(const Format& f, int64_t k) { return (float)std::ldexp((double)k, f.emin8 - 127 - f.Y); }
+
+int exmy_oracle_to_codes_int(const void* src, int dt, uint64_t n, int Y, int max_exp, uint32_t* codes) {
+  if ((!src || !codes) && n) return ORACLE_ERR_NULL;
+  Format f;
+  if (int rc = int_format(dt, Y, max_exp, true, &f)) return rc;
+  for (uint64_t i = 0; i < n; ++i) codes[i] = (uint32_t)int_code(f, load_bits(src, dt, i)) & ((2u << Y) - 1u);
+  return ORACLE_OK;
+}
+
+int exmy_oracle_from_codes_int(const uint32_t* codes, int dt, uint64_t n, int Y, int max_exp, void* dst) {
+  if ((!dst || !codes) && n) return ORACLE_ERR_NULL;
+  Format f;
+  if (int rc = int_format(dt, Y, max_exp, true, &f)) return rc;
+  for (uint64_t i = 0; i < n; ++i) {
+    int64_t k = codes[i] & ((2u << Y) - 1u);
+    if (k >> Y) k -= (int64_t)2 << Y;  // sign extension of the (1 + Y)-bit number
+    store_bits(dst, dt, i, float_to_bits(int_value(f, k)));
+  }
+  return ORACLE_OK;
+}
+
+int exmy_oracle_encode_int(const void* src, int dt, uint64_t n, int Y, int max_exp, uint8_t* dst_packed) {
+  if ((!src || !dst_packed) && n) return ORACLE_ERR_NULL;
+  std::vector<uint32_t> codes(n);
+  if (int rc = exmy_oracle_to_codes_int(src, dt, n, Y, max_exp, codes.data())) return rc;
+  pack_groups(codes.data(), 0, n, 1 + Y, dst_packed, 0, (n + 7) / 8);
+  return ORACLE_OK;
+}
+
+int exmy_oracle_decode_int(const uint8_t* src_packed, int dt, uint64_t n, int Y, int max_exp, void* dst) {
+  if ((!src_packed || !dst) && n) return ORACLE_ERR_NULL;
+  Format f;
+  if (int rc = int_format(dt, Y, max_exp, true, &f)) return rc;
+  std::vector<uint32_t> codes(n);
+  unpack_groups(src_packed, n, 1 + Y, codes.data(), 0, 0, (n + 7) / 8);
+  return exmy_oracle_from_codes_int(codes.data(), dt, n, Y, max_exp, dst);
+}
+
+// In place; Inf / NaN are left bit-identical (Section 2.1).
+int exmy_oracle_emulate_int(void* data, int dt, uint64_t n, int Y, int max_exp) {
+  if (!data && n) return ORACLE_ERR_NULL;
+  Format f;
+  if (int rc = int_format(dt, Y, max_exp, false, &f)) return rc;
+  for (uint64_t i = 0; i < n; ++i) {
+    const uint32_t bits = load_bits(data, dt, i);
+    const float x = bits_to_float(bits);
+    if (std::isnan(x) || std::isinf(x)) continue;
+    store_bits(data, dt, i, float_to_bits(int_value(f, int_code(f, bits))));
+  }
+  return ORACLE_OK;
 }
 
 // fp32 -> bf16 rounding used above, exported so that it can be pinned on its own.

@@ -53,6 +53,11 @@ def lib():
         L.exmy_oracle_packed_bytes_rows.argtypes = [u64, u64, i32, i32]
         L.exmy_oracle_encode_rows.argtypes = [vp, i32, u64, u64, i32, i32, i32, vp, vp]
         L.exmy_oracle_decode_rows.argtypes = [vp, i32, u64, u64, i32, i32, i32, vp, vp]
+        L.exmy_oracle_to_codes_int.argtypes = [vp, i32, u64, i32, i32, vp]
+        L.exmy_oracle_from_codes_int.argtypes = [vp, i32, u64, i32, i32, vp]
+        L.exmy_oracle_encode_int.argtypes = [vp, i32, u64, i32, i32, vp]
+        L.exmy_oracle_decode_int.argtypes = [vp, i32, u64, i32, i32, vp]
+        L.exmy_oracle_emulate_int.argtypes = [vp, i32, u64, i32, i32]
         L.exmy_oracle_max_exp_from_histogram.restype = i32
         L.exmy_oracle_max_exp_from_histogram.argtypes = [vp, dbl]
         _lib = L
@@ -293,4 +298,43 @@ def decode_rows(packed, dt, rows, cols, X, Y, max_exp=0, max_exp_rows=None):
     out = np.empty(rows * cols, dtype=_out_dtype(dt))
     _check(lib().exmy_oracle_decode_rows(_ptr(packed), dt, rows, cols, X, Y, max_exp,
                                          _ptr(m) if m is not None else None, _ptr(out)))
+    return out
+
+
+# ------------------------------------------------------------ two's complement reading of X = 0
+
+
+def to_codes_int(src, Y, max_exp):
+    a, dt = _src(src)
+    out = np.empty(a.size, dtype=np.uint32)
+    _check(lib().exmy_oracle_to_codes_int(_ptr(a), dt, a.size, Y, max_exp, _ptr(out)))
+    return out
+
+
+def from_codes_int(codes, dt, Y, max_exp):
+    codes = np.ascontiguousarray(codes, dtype=np.uint32)
+    out = np.empty(codes.size, dtype=_out_dtype(dt))
+    _check(lib().exmy_oracle_from_codes_int(_ptr(codes), dt, codes.size, Y, max_exp, _ptr(out)))
+    return out
+
+
+def encode_int(src, Y, max_exp):
+    a, dt = _src(src)
+    out = np.empty(packed_bytes(a.size, 0, Y), dtype=np.uint8)
+    _check(lib().exmy_oracle_encode_int(_ptr(a), dt, a.size, Y, max_exp, _ptr(out)))
+    return out
+
+
+def decode_int(packed, dt, n, Y, max_exp):
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    assert packed.size == packed_bytes(n, 0, Y)
+    out = np.empty(n, dtype=_out_dtype(dt))
+    _check(lib().exmy_oracle_decode_int(_ptr(packed), dt, n, Y, max_exp, _ptr(out)))
+    return out
+
+
+def emulate_int(src, Y, max_exp):
+    a, dt = _src(src)
+    out = a.copy()
+    _check(lib().exmy_oracle_emulate_int(_ptr(out), dt, out.size, Y, max_exp))
     return out
