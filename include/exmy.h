@@ -250,6 +250,28 @@ exmy_status_t exmy_encode_rows(const void* src, exmy_dtype_t dt, uint64_t rows, 
 exmy_status_t exmy_decode_rows(const void* src_packed, exmy_dtype_t dt_out, uint64_t rows, uint64_t cols, int X,
                                int Y, int max_exp, const uint8_t* max_exp_rows_dev, void* dst, void* stream);
 
+/* ---------------------------------------------------------------------------
+ * Two's complement reading of the X = 0 formats (Section 2 "Format": e0m3 read
+ * as a two's complement number is int4 and represents [-8, 7], one encoding
+ * more than the (sign, magnitude) form with its double zero).
+ *
+ * The W = 1 + Y bits of a code are a two's complement integer k in
+ * [-2^Y, 2^Y - 1]; the value is k quanta, the quantum being that of e0mY with
+ * the same max_exp: 2^(max_exp + 1 - 127 - Y) (max_exp = 126 + Y makes it 1).
+ * encode: k = round-half-even(x / quantum), clamped to the range; +-Inf and NaN
+ * go to the end of the range on the side of their sign bit; -0 and negative
+ * values that round to 0 give k = 0.  decode: k * quantum (k = 0 is +0).
+ * emulate: decode(encode(x)), Inf / NaN left bit-identical.  Packed layout as
+ * for exmy_encode with W = 1 + Y.
+ * 1 <= Y <= 8 (bf16) / 21 (fp32), 1 + Y <= 16 for the packed form;
+ * 0 <= max_exp <= min(253, 230 + Y) (EXMY_ERR_MAX_EXP).  Pointers, alignment,
+ * n = 0, streams and errors as for exmy_encode. */
+exmy_status_t exmy_encode_int(const void* src, exmy_dtype_t dt, uint64_t n, int Y, int max_exp, void* dst_packed,
+                              void* stream);
+exmy_status_t exmy_decode_int(const void* src_packed, exmy_dtype_t dt_out, uint64_t n, int Y, int max_exp, void* dst,
+                              void* stream);
+exmy_status_t exmy_emulate_int(void* data_inout, exmy_dtype_t dt, uint64_t n, int Y, int max_exp, void* stream);
+
 /* Host helper for Section 3.1's technique (keep the top exponents, let the
  * tail go): the smallest biased exponent e in [0, 254] such that at least
  * `coverage` (0..1) of the finite elements counted in the HOST array

@@ -15,15 +15,18 @@ from .binding import (  # noqa: F401
     decode,
     decode_batch,
     decode_blocks,
+    decode_int,
     decode_rows,
     decode_scaled,
     emulate,
     emulate_blocks,
+    emulate_int,
     emulate_scaled,
     encode,
     encode_batch,
     encode_blocks,
     encode_blocks_auto,
+    encode_int,
     encode_rows,
     encode_scaled,
     encode_with_histogram,

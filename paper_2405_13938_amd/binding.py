@@ -38,6 +38,9 @@ SYMBOLS = [
     "exmy_packed_bytes_rows",
     "exmy_encode_rows",
     "exmy_decode_rows",
+    "exmy_encode_int",
+    "exmy_decode_int",
+    "exmy_emulate_int",
     "exmy_status_string",
 ]
 
@@ -115,6 +118,12 @@ def lib():
         L.exmy_encode_rows.argtypes = [vp, i32, u64, u64, i32, i32, i32, vp, vp, vp]
         L.exmy_decode_rows.restype = i32
         L.exmy_decode_rows.argtypes = [vp, i32, u64, u64, i32, i32, i32, vp, vp, vp]
+        L.exmy_encode_int.restype = i32
+        L.exmy_encode_int.argtypes = [vp, i32, u64, i32, i32, vp, vp]
+        L.exmy_decode_int.restype = i32
+        L.exmy_decode_int.argtypes = [vp, i32, u64, i32, i32, vp, vp]
+        L.exmy_emulate_int.restype = i32
+        L.exmy_emulate_int.argtypes = [vp, i32, u64, i32, i32, vp]
         L.exmy_status_string.restype = ctypes.c_char_p
         L.exmy_status_string.argtypes = [i32]
         _lib = L
@@ -514,3 +523,44 @@ def decode_rows(packed, dtype, rows, cols, X, Y, max_exp=0, max_exp_rows=None, o
     _check(lib().exmy_decode_rows(packed.data_ptr(), _dtype_enum(out), rows, cols, X, Y, max_exp,
                                   _row_meta_ptr(max_exp_rows, rows), out.data_ptr(), _stream()))
     return out
+
+
+# ------------------------------------------------------------ two's complement reading of X = 0
+
+
+def encode_int(src, Y, max_exp, out=None):
+    """exmy_encode_int: returns the packed uint8 tensor of (1 + Y)-bit two's complement codes."""
+    _device_tensor(src, "src")
+    n = src.numel()
+    nbytes = packed_bytes(n, 0, Y)
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.uint8, device=src.device)
+    else:
+        _device_tensor(out, "out")
+        if out.dtype != torch.uint8 or out.numel() != nbytes:
+            raise ValueError("exmy: out must be uint8 with %d elements" % nbytes)
+    _check(lib().exmy_encode_int(src.data_ptr(), _dtype_enum(src), n, Y, max_exp, out.data_ptr(), _stream()))
+    return out
+
+
+def decode_int(packed, dtype, n, Y, max_exp, out=None):
+    """exmy_decode_int: returns a flat tensor of ``n`` values of ``dtype``."""
+    _device_tensor(packed, "packed")
+    tdt = _torch_dtype(dtype)
+    if packed.dtype != torch.uint8 or packed.numel() != packed_bytes(n, 0, Y):
+        raise ValueError("exmy: packed must be uint8 with %d elements" % packed_bytes(n, 0, Y))
+    if out is None:
+        out = torch.empty(n, dtype=tdt, device=packed.device)
+    else:
+        _device_tensor(out, "out")
+        if out.dtype != tdt or out.numel() != n:
+            raise ValueError("exmy: out must be %s with %d elements" % (tdt, n))
+    _check(lib().exmy_decode_int(packed.data_ptr(), _dtype_enum(out), n, Y, max_exp, out.data_ptr(), _stream()))
+    return out
+
+
+def emulate_int(data, Y, max_exp):
+    """exmy_emulate_int: in place; returns ``data``."""
+    _device_tensor(data, "data")
+    _check(lib().exmy_emulate_int(data.data_ptr(), _dtype_enum(data), data.numel(), Y, max_exp, _stream()))
+    return data

@@ -141,6 +141,26 @@ exmy_status_t make_block_format(exmy_dtype_t dt, int X, int Y, int max_width, bo
   return EXMY_OK;
 }
 
+exmy_status_t make_int_format(exmy_dtype_t dt, int Y, int max_exp, bool packed, IntConsts* ic) {
+  if (dt != EXMY_F32 && dt != EXMY_BF16) return EXMY_ERR_FORMAT;
+  const int P = dt == EXMY_F32 ? 23 : 7;
+  // at least one magnitude bit; the container's significand holds Y + 1 bits (as for e0mY); the packed
+  // form stops at 16 bits; the single fp32 rounding addend needs Y <= 21
+  if (Y < 1 || Y > P + 1 || Y > 21 || (packed && 1 + Y > kBlockWidth)) return EXMY_ERR_FORMAT;
+  if (max_exp < 0 || max_exp > 253) return EXMY_ERR_MAX_EXP;
+  if (Y == P + 1 && max_exp < 1) return EXMY_ERR_MAX_EXP;  // the quantum must be a value of the container
+  const int emin8 = max_exp + 1;
+  if (emin8 + 23 - Y > 254) return EXMY_ERR_MAX_EXP;  // the rounding addend must be a finite float
+  if (ic) {
+    ic->sat_pos_bits = float_bits(ldexpf((float)((1u << Y) - 1u), emin8 - 127 - Y));
+    ic->neg_extra = float_bits(ldexpf(1.0f, emin8 - 127)) - ic->sat_pos_bits;
+    ic->left_shift = (uint32_t)(31 - Y);
+    ic->magic = ldexpf(1.0f, emin8 - 127 + 23 - Y);
+    ic->quantum = ldexpf(1.0f, emin8 - 127 - Y);
+  }
+  return EXMY_OK;
+}
+
 }  // namespace exmy
 
 using namespace exmy;
@@ -447,6 +467,41 @@ exmy_status_t exmy_encode_rows(const void* src, exmy_dtype_t dt, uint64_t rows, 
 exmy_status_t exmy_decode_rows(const void* src_packed, exmy_dtype_t dt_out, uint64_t rows, uint64_t cols, int X, int Y,
                                int max_exp, const uint8_t* max_exp_rows_dev, void* dst, void* stream) {
   return run_rows(RowsOp::kDecode, dst, src_packed, dt_out, rows, cols, X, Y, max_exp, max_exp_rows_dev, stream);
+}
+
+exmy_status_t exmy_encode_int(const void* src, exmy_dtype_t dt, uint64_t n, int Y, int max_exp, void* dst_packed,
+                              void* stream) {
+  IntConsts ic;
+  if (exmy_status_t st = make_int_format(dt, Y, max_exp, true, &ic)) return st;
+  if (n > EXMY_MAX_ELEMENTS) return EXMY_ERR_COUNT;
+  if (n == 0) return EXMY_OK;
+  if (!src || !dst_packed) return EXMY_ERR_NULL;
+  if (!aligned16(src) || !aligned16(dst_packed)) return EXMY_ERR_ALIGN;
+  const hipError_t e = encode_int_dispatch(dt, 1 + Y, src, dst_packed, n, ic, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
+}
+
+exmy_status_t exmy_decode_int(const void* src_packed, exmy_dtype_t dt_out, uint64_t n, int Y, int max_exp, void* dst,
+                              void* stream) {
+  IntConsts ic;
+  if (exmy_status_t st = make_int_format(dt_out, Y, max_exp, true, &ic)) return st;
+  if (n > EXMY_MAX_ELEMENTS) return EXMY_ERR_COUNT;
+  if (n == 0) return EXMY_OK;
+  if (!src_packed || !dst) return EXMY_ERR_NULL;
+  if (!aligned16(src_packed) || !aligned16(dst)) return EXMY_ERR_ALIGN;
+  const hipError_t e = decode_int_dispatch(dt_out, 1 + Y, src_packed, dst, n, ic, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
+}
+
+exmy_status_t exmy_emulate_int(void* data_inout, exmy_dtype_t dt, uint64_t n, int Y, int max_exp, void* stream) {
+  IntConsts ic;
+  if (exmy_status_t st = make_int_format(dt, Y, max_exp, false, &ic)) return st;
+  if (n > EXMY_MAX_ELEMENTS) return EXMY_ERR_COUNT;
+  if (n == 0) return EXMY_OK;
+  if (!data_inout) return EXMY_ERR_NULL;
+  if (!aligned16(data_inout)) return EXMY_ERR_ALIGN;
+  const hipError_t e = emulate_int_dispatch(dt, data_inout, n, ic, static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
 }
 
 int exmy_max_exp_from_histogram(const uint64_t* hist256_host, double coverage) {

@@ -82,6 +82,16 @@ struct BlockConsts {
   uint32_t round_odd;
 };
 
+// Constants of the two's complement reading of e0mY (Section 2 "Format"): the
+// code is a (1 + Y)-bit two's complement integer k, the value k quanta.
+struct IntConsts {
+  uint32_t sat_pos_bits;     // fp32 bits of (2^Y - 1) quanta, the largest positive value
+  uint32_t neg_extra;        // fp32 bits of 2^Y quanta (the most negative magnitude) minus sat_pos_bits
+  uint32_t left_shift;       // 31 - Y: moves the low 1 + Y bits of a register to its top
+  float magic;               // 2^(emin8 - 127 + 23 - Y): adding it leaves round(|x| / quantum) in the low bits
+  float quantum;             // 2^(emin8 - 127 - Y), emin8 = max_exp + 1
+};
+
 // How a kernel finds the metadata block of a piece of work.  Work is counted in
 // the kernel's own units (groups of 8 elements, or 16-byte vectors); a block is
 // `size` of them.  Tiles run flat over the tensor and may straddle blocks: the
@@ -156,6 +166,9 @@ constexpr int kAnyWidth = 64;
 // forms, kAnyWidth for emulation, which has no packed form).
 exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, int max_width, FormatConsts* fc,
                           TensorConsts* tc, bool* needs_wide);
+
+// Host: validate (dtype, Y, max_exp) for the two's complement reading and fill ic.
+exmy_status_t make_int_format(exmy_dtype_t dt, int Y, int max_exp, bool packed, IntConsts* ic);
 
 // Host: validate (dtype, X, Y) for per-block metadata and fill fc / bc.
 // after_rounding selects the scheme of the maximum-exponent kernel.

@@ -49,6 +49,12 @@ hipError_t encode_rows_dispatch(exmy_dtype_t dt, int W, const RowsArgs& args, bo
                                 hipStream_t stream);
 hipError_t decode_rows_dispatch(exmy_dtype_t dt, int W, const RowsArgs& args, bool per_row, bool x8,
                                 hipStream_t stream);
+// Two's complement reading of e0mY (W = 1 + Y).
+hipError_t encode_int_dispatch(exmy_dtype_t dt, int W, const void* src, void* dst, uint64_t n, const IntConsts& ic,
+                               hipStream_t stream);
+hipError_t decode_int_dispatch(exmy_dtype_t dt, int W, const void* src, void* dst, uint64_t n, const IntConsts& ic,
+                               hipStream_t stream);
+hipError_t emulate_int_dispatch(exmy_dtype_t dt, void* data, uint64_t n, const IntConsts& ic, hipStream_t stream);
 hipError_t histogram_dispatch(exmy_dtype_t dt, const void* src, uint64_t n, uint64_t* hist, hipStream_t stream);
 
 }  // namespace exmy

@@ -224,3 +224,27 @@ def test_row_packing_entry_points_validate_without_launch():
         assert dec(ok, B.BF16, 8, cols, 3, 3, 130, None, ok, None) == 8
     assert enc(ok, B.BF16, 1 << 30, 1 << 20, 3, 3, 130, None, ok, None) == 4
     assert B.status_string(8).startswith("column count")
+
+
+def test_twos_complement_entry_points_validate_without_launch():
+    L = B.lib()
+    ok, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1008)
+    enc, dec, emu = L.exmy_encode_int, L.exmy_decode_int, L.exmy_emulate_int
+    assert enc(ok, B.F32, 0, 7, 133, ok, None) == 0
+    assert enc(None, B.F32, 8, 7, 133, ok, None) == 1
+    assert dec(ok, B.F32, 8, 7, 133, None, None) == 1
+    assert emu(None, B.F32, 8, 7, 133, None) == 1
+    assert enc(odd, B.F32, 8, 7, 133, ok, None) == 5
+    assert dec(ok, B.F32, 8, 7, 133, odd, None) == 5
+    assert emu(odd, B.BF16, 8, 7, 133, None) == 5
+    for Y in (0, -1, 16, 25):
+        assert enc(ok, B.F32, 0, Y, 133, ok, None) == 2
+    assert enc(ok, B.BF16, 0, 9, 133, ok, None) == 2    # bf16 holds 8 significant bits
+    assert enc(ok, B.BF16, 0, 8, 133, ok, None) == 0
+    assert emu(ok, B.F32, 0, 21, 133, None) == 0         # emulation goes beyond the packed widths ...
+    assert emu(ok, B.F32, 0, 22, 133, None) == 2         # ... up to what one fp32 rounding addend covers
+    assert enc(ok, B.F32, 0, 7, 254, ok, None) == 3
+    assert enc(ok, B.F32, 0, 7, -1, ok, None) == 3
+    assert enc(ok, B.F32, 0, 7, 238, ok, None) == 3      # above 230 + Y the rounding addend would overflow
+    assert enc(ok, B.F32, 0, 7, 237, ok, None) == 0
+    assert enc(ok, B.F32, (1 << 40) + 1, 7, 133, ok, None) == 4
