@@ -48,6 +48,12 @@
 //     mantissa bits as the format's top binade has (Y, or Y - 1 when X = 0), so
 //     that the block maximum is rounded and never cut off by saturation.
 //
+//   - fp16 container (Section 2.1: fp16 emulates X <= 5, Y <= 10): every half is
+//     converted exactly to fp32 first; a format is valid with a max_exp only if its
+//     top binade and its quantum are fp16 values (max_exp <= 142 and
+//     max_exp - 2^X + 2 - 127 - Y >= -24), so that every decoded value is exact;
+//     the histogram bins by the exponent of the value as an fp32 (an fp16
+//     denormal therefore does not fall in bin 0);
 //   - packing along rows (Section 2.2.2: (8R, C) -> arrays of shape (R, C)): the
 //     group of output position (r, c) is elements (8r + j, c), j = 0..7, of the
 //     row-major matrix; rows beyond the last are zero codes; each plane is a
@@ -82,7 +88,7 @@
 
 extern "C" {
 
-enum { ORACLE_F32 = 0, ORACLE_BF16 = 1 };
+enum { ORACLE_F32 = 0, ORACLE_BF16 = 1, ORACLE_F16 = 2 };
 enum {
   ORACLE_OK = 0,
   ORACLE_ERR_NULL = 1,
@@ -102,15 +108,16 @@ struct Format {
 };
 
 // Mantissa bits the float container itself stores.
-int container_mantissa(int dt) { return dt == ORACLE_F32 ? 23 : 7; }
+int container_mantissa(int dt) { return dt == ORACLE_F32 ? 23 : (dt == ORACLE_F16 ? 10 : 7); }
 
 // Section 2.1: a format can be emulated in (and therefore converted from / to)
 // a float container when its exponent and mantissa fit.  With X = 0 a code has
 // only Y significant bits, one fewer than a normal with Y mantissa bits, so one
 // more is allowed.
 int check_format(int dt, int X, int Y, int max_exp, bool packed, Format* f) {
-  if (dt != ORACLE_F32 && dt != ORACLE_BF16) return ORACLE_ERR_FORMAT;
+  if (dt != ORACLE_F32 && dt != ORACLE_BF16 && dt != ORACLE_F16) return ORACLE_ERR_FORMAT;
   if (X < 0 || X > 8 || Y < 0) return ORACLE_ERR_FORMAT;
+  if (dt == ORACLE_F16 && X > 5) return ORACLE_ERR_FORMAT;  // Section 2.1: fp16 emulates X <= 5, Y <= 10
   const int P = container_mantissa(dt);
   if (X >= 1 ? (Y > P) : (Y > P + 1)) return ORACLE_ERR_FORMAT;
   if (packed && 1 + X + Y > 31) return ORACLE_ERR_FORMAT;  // segments of 16, 8, 4, 2 and 1 bits reach 31
@@ -123,6 +130,12 @@ int check_format(int dt, int X, int Y, int max_exp, bool packed, Format* f) {
     if (Y == P + 1 && max_exp < 1) return ORACLE_ERR_MAX_EXP;
   } else {
     if (max_exp < (1 << X) - 1 || max_exp > 254) return ORACLE_ERR_MAX_EXP;
+  }
+  if (dt == ORACLE_F16) {
+    // fp16 holds binades 2^-14 .. 2^15 and multiples of 2^-24 below: the top binade of the format and
+    // its quantum must lie inside
+    if (max_exp > 142) return ORACLE_ERR_MAX_EXP;
+    if (max_exp - (1 << X) + 2 - 127 - Y < -24) return ORACLE_ERR_MAX_EXP;
   }
   f->X = X;
   f->Y = Y;
@@ -168,14 +181,48 @@ int64_t magnitude_code(const Format& f, double a) {
   return std::min(c, f.cmax);  // saturate to the largest normal
 }
 
+inline float bits_to_float(uint32_t b);
+inline uint32_t float_to_bits(float f);
+
+// fp32 bits of an IEEE half: 1 sign, 5 exponent (bias 15), 10 mantissa bits; every half is an fp32 value.
+inline uint32_t half_to_float_bits(uint16_t h) {
+  const uint32_t sign = (uint32_t)(h >> 15) << 31;
+  const int e = (h >> 10) & 0x1F;
+  const int m = h & 0x3FF;
+  if (e == 31) return sign | 0x7F800000u | ((uint32_t)m << 13);      // Inf, or NaN with its payload
+  const float v = e == 0 ? std::ldexp((float)m, -24) : std::ldexp((float)(1024 + m), e - 25);
+  return sign | float_to_bits(v);
+}
+
+// The half with exactly the value of these fp32 bits; aborts if there is none (the callers only store
+// values that the format's validation has shown to be fp16 values).
+inline uint16_t float_bits_to_half_exact(uint32_t bits) {
+  const uint16_t sign = (uint16_t)((bits >> 31) << 15);
+  const float a = std::fabs(bits_to_float(bits));
+  if (a == 0.0f) return sign;
+  int e;
+  const float frac = std::frexp(a, &e);  // a = frac * 2^e, frac in [0.5, 1)
+  if (e - 1 >= -14) {                    // normal half: 11 significant bits
+    const float k = std::ldexp(frac, 11);
+    if (e - 1 > 15 || k != std::floor(k)) std::abort();
+    return (uint16_t)(sign | ((e - 1 + 15) << 10) | ((int)k - 1024));
+  }
+  const float k = std::ldexp(a, 24);     // subnormal half: a multiple of 2^-24
+  if (k != std::floor(k) || k >= 1024.0f) std::abort();
+  return (uint16_t)(sign | (int)k);
+}
+
 inline uint32_t load_bits(const void* src, int dt, uint64_t i) {
   if (dt == ORACLE_F32) return ((const uint32_t*)src)[i];
+  if (dt == ORACLE_F16) return half_to_float_bits(((const uint16_t*)src)[i]);
   return (uint32_t)((const uint16_t*)src)[i] << 16;  // bf16 = upper half of fp32
 }
 
 inline void store_bits(void* dst, int dt, uint64_t i, uint32_t bits) {
   if (dt == ORACLE_F32)
     ((uint32_t*)dst)[i] = bits;
+  else if (dt == ORACLE_F16)
+    ((uint16_t*)dst)[i] = float_bits_to_half_exact(bits);
   else {
     if (bits & 0xFFFFu) std::abort();  // every decoded value must be exact in bf16
     ((uint16_t*)dst)[i] = (uint16_t)(bits >> 16);
@@ -408,7 +455,7 @@ int exmy_oracle_emulate(void* data, int dt, uint64_t n, int X, int Y, int max_ex
 // denormals fall in bin 0, Inf / NaN in bin 255.  Accumulates into hist.
 int exmy_oracle_exponent_histogram(const void* src, int dt, uint64_t n, uint64_t* hist256) {
   if ((!src && n) || !hist256) return ORACLE_ERR_NULL;
-  if (dt != ORACLE_F32 && dt != ORACLE_BF16) return ORACLE_ERR_FORMAT;
+  if (dt != ORACLE_F32 && dt != ORACLE_BF16 && dt != ORACLE_F16) return ORACLE_ERR_FORMAT;
   for (uint64_t i = 0; i < n; ++i) hist256[(load_bits(src, dt, i) >> 23) & 0xFFu] += 1;
   return ORACLE_OK;
 }
@@ -478,6 +525,7 @@ int exmy_oracle_block_max_exp(const void* src, int dt, uint64_t n, uint64_t bloc
 int exmy_oracle_block_max_exp_after_rounding(const void* src, int dt, uint64_t n, uint64_t block, int X, int Y,
                                              uint8_t* max_exp_out) {
   if ((!src || !max_exp_out) && n) return ORACLE_ERR_NULL;
+  if (dt == ORACLE_F16) return ORACLE_ERR_FORMAT;
   if (block == 0 || block % 8) return ORACLE_ERR_FORMAT;
   int lo, hi;
   if (int rc = block_meta_range(X, &lo, &hi)) return rc;
@@ -508,6 +556,7 @@ int exmy_oracle_block_max_exp_after_rounding(const void* src, int dt, uint64_t n
 static int blocks_op(int what, const void* src, void* dst, int dt, uint64_t n, uint64_t block, int X, int Y,
                      const uint8_t* max_exp, int threads) {
   if (n && (!src || !dst || !max_exp)) return ORACLE_ERR_NULL;
+  if (dt == ORACLE_F16) return ORACLE_ERR_FORMAT;  // per-block forms: fp32 and bf16 containers only
   if (block == 0 || block % 8) return ORACLE_ERR_FORMAT;
   int lo, hi;
   if (int rc = block_meta_range(X, &lo, &hi)) return rc;
@@ -564,7 +613,7 @@ int exmy_oracle_emulate_blocks(void* data, int dt, uint64_t n, uint64_t block, i
 // the max_exp = 127 format, whose top binade is [1, 2).
 
 static int scaled_format(int dt, int X, int Y, bool packed, Format* f) {
-  if (X < 0 || X > 7) return ORACLE_ERR_FORMAT;
+  if (X < 0 || X > 7 || dt == ORACLE_F16) return ORACLE_ERR_FORMAT;
   if (X == 0 && Y == 0) return ORACLE_ERR_FORMAT;  // the only magnitude is 0: nothing to scale
   return check_format(dt, X, Y, 127, packed, f);
 }
@@ -677,6 +726,7 @@ static int rows_op(int what, const void* src, void* dst, int dt, uint64_t rows, 
                    int max_exp, const uint8_t* max_exp_rows) {
   const uint64_t n = rows * cols;
   if (n && (!src || !dst)) return ORACLE_ERR_NULL;
+  if (dt == ORACLE_F16) return ORACLE_ERR_FORMAT;
   Format f0;
   int lo = 0, hi = 0;
   if (max_exp_rows) {
@@ -749,6 +799,7 @@ int exmy_oracle_decode_rows(const uint8_t* src_packed, int dt, uint64_t rows, ui
 // is that of e0mY with the same max_exp: 2^(max_exp + 1 - 127 - Y).
 
 static int int_format(int dt, int Y, int max_exp, bool packed, Format* f) {
+  if (dt == ORACLE_F16) return ORACLE_ERR_FORMAT;
   if (int rc = check_format(dt, 0, Y, max_exp, packed, f)) return rc;
   if (packed && 1 + Y > kBlockWidth) return ORACLE_ERR_FORMAT;
   // -2^Y quanta = -2^(max_exp + 1 - 127) must be a value of the container (it always is), and Y >= 1

@@ -10,7 +10,7 @@ import numpy as np
 
 from . import build as _build
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 _STATUS = {0: "ok", 1: "null pointer", 2: "bad format", 3: "bad max_exp"}
 
 _lib = None
@@ -84,7 +84,9 @@ def _src(a):
         return a, F32
     if a.dtype == np.uint16:
         return a, BF16
-    raise TypeError("expected float32/uint32 (fp32) or uint16 (bf16 bits), got %s" % a.dtype)
+    if a.dtype == np.float16:
+        return a, F16
+    raise TypeError("expected float32/uint32 (fp32), uint16 (bf16 bits) or float16, got %s" % a.dtype)
 
 
 def _ptr(a):
@@ -92,7 +94,7 @@ def _ptr(a):
 
 
 def _out_dtype(dt):
-    return np.float32 if dt == F32 else np.uint16
+    return np.float32 if dt == F32 else (np.float16 if dt == F16 else np.uint16)
 
 
 def packed_bytes(n, X, Y):

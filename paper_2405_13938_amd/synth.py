@@ -154,6 +154,11 @@ def all_bf16_patterns(device="cpu"):
     return torch.arange(0, 65536, dtype=torch.int32, device=device).to(torch.int16).view(torch.bfloat16)
 
 
+def all_f16_patterns(device="cpu"):
+    """Every one of the 65536 fp16 bit patterns, in order."""
+    return torch.arange(0, 65536, dtype=torch.int32, device=device).to(torch.int16).view(torch.float16)
+
+
 def f32_edge_sweep(device="cpu", seed=7, n_random=1 << 16):
     """fp32 bit patterns that stress rounding: every exponent with mantissas at
     and around each tie position, plus random bit patterns."""
@@ -185,10 +190,12 @@ def shuffled(t, seed):
 
 def bits_numpy(t):
     """Host numpy view of a tensor's bits in the form the oracle takes:
-    float32 for fp32 tensors, uint16 bit patterns for bf16 tensors."""
+    float32 for fp32 tensors, uint16 bit patterns for bf16 tensors, float16 for fp16 tensors."""
     t = t.detach().reshape(-1).cpu().contiguous()
     if t.dtype == torch.float32:
         return t.numpy()
     if t.dtype == torch.bfloat16:
         return t.view(torch.int16).numpy().view("uint16")
+    if t.dtype == torch.float16:
+        return t.numpy()
     raise TypeError(t.dtype)
