@@ -21,8 +21,15 @@
  *    Valid: 2^X - 1 <= max_exp <= 254 for 1 <= X <= 7; 0 <= max_exp <= 253 for
  *    X = 0 (and >= 1 when Y is one more than the container's mantissa);
  *    max_exp = 255 exactly for X = 8 (identity exponent map).
- *  - A format fits a container when X <= 8 and Y <= 7 (bf16) / 23 (fp32)
- *    (Section 2.1); with X = 0 one more mantissa bit is allowed.  Packed codes
+ *  - A format fits a container when X <= 8 and Y <= 7 (bf16) / 23 (fp32), or
+ *    X <= 5 and Y <= 10 (fp16) (Section 2.1); with X = 0 one more mantissa bit
+ *    is allowed.  With the fp16 container (EXMY_F16: exmy_encode / exmy_decode,
+ *    their batch and histogram forms, exmy_emulate and
+ *    exmy_exponent_histogram only; EXMY_ERR_FORMAT elsewhere) max_exp must also
+ *    keep the format's top binade and its quantum inside fp16:
+ *    max_exp <= 142 and max_exp - 2^X + 2 - 127 - Y >= -24 (EXMY_ERR_MAX_EXP),
+ *    so that every decoded value is an fp16 value; the exponent histogram of
+ *    fp16 data bins the exponent of the value as an fp32.  Packed codes
  *    are limited to W <= 31 (segments of 16, 8, 4, 2 and 1 bits; widths above
  *    16 need the fp32 container) in exmy_encode / exmy_decode and their batch
  *    and histogram forms, and to W <= 16 in the per-block, float-scaling and
@@ -58,7 +65,7 @@
 extern "C" {
 #endif
 
-typedef enum { EXMY_F32 = 0, EXMY_BF16 = 1 } exmy_dtype_t;
+typedef enum { EXMY_F32 = 0, EXMY_BF16 = 1, EXMY_F16 = 2 } exmy_dtype_t;
 
 typedef enum {
   EXMY_OK = 0,

@@ -5,6 +5,7 @@
 from . import binding  # noqa: F401
 from .binding import (  # noqa: F401
     BF16,
+    F16,
     F32,
     Batch,
     ExmyError,

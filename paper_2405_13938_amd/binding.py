@@ -12,7 +12,7 @@ import torch
 HERE = os.path.dirname(os.path.abspath(__file__))
 LIB_PATH = os.path.join(HERE, "libexmy.so")
 
-F32, BF16 = 0, 1
+F32, BF16, F16 = 0, 1, 2
 SYMBOLS = [
     "exmy_packed_bytes",
     "exmy_check_format",
@@ -140,10 +140,14 @@ def _dtype_enum(t):
         return F32
     if t.dtype == torch.bfloat16:
         return BF16
-    raise TypeError("exmy: tensors must be float32 or bfloat16, got %s" % t.dtype)
+    if t.dtype == torch.float16:
+        return F16
+    raise TypeError("exmy: tensors must be float32, bfloat16 or float16, got %s" % t.dtype)
 
 
 def _torch_dtype(dt):
+    if dt in (F16, torch.float16):
+        return torch.float16
     return torch.float32 if dt in (F32, torch.float32) else torch.bfloat16
 
 
@@ -230,7 +234,7 @@ class Batch:
     def run(self):
         L = lib()
         fn = L.exmy_decode_batch if self.decode else L.exmy_encode_batch
-        dt = F32 if self.dtype == torch.float32 else BF16
+        dt = _dtype_enum(self._keep[0][0]) if self.count else BF16
         _check(fn(ctypes.cast(self.array, ctypes.c_void_p), self.count, dt, self.X, self.Y, _stream()))
 
 

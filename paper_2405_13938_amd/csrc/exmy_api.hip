@@ -40,11 +40,12 @@ int compute_units() {
 
 exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, int max_width, FormatConsts* fc,
                           TensorConsts* tc, bool* needs_wide) {
-  if (dt != EXMY_F32 && dt != EXMY_BF16) return EXMY_ERR_FORMAT;
+  if (dt != EXMY_F32 && dt != EXMY_BF16 && dt != EXMY_F16) return EXMY_ERR_FORMAT;
   if (X < 0 || X > 8 || Y < 0) return EXMY_ERR_FORMAT;
-  // Section 2.1: bf16 holds Y <= 7, fp32 Y <= 23; a sign-magnitude format (X = 0) has
-  // no leading one, so its Y bits need only Y significant bits of the container.
-  const int P = dt == EXMY_F32 ? 23 : 7;
+  if (dt == EXMY_F16 && X > 5) return EXMY_ERR_FORMAT;
+  // Section 2.1: bf16 holds Y <= 7, fp16 Y <= 10 (and X <= 5), fp32 Y <= 23; a sign-magnitude
+  // format (X = 0) has no leading one, so its Y bits need only Y significant bits of the container.
+  const int P = dt == EXMY_F32 ? 23 : (dt == EXMY_F16 ? 10 : 7);
   if (Y > (X >= 1 ? P : P + 1)) return EXMY_ERR_FORMAT;
   if (1 + X + Y > max_width) return EXMY_ERR_FORMAT;
   if (max_width != kAnyWidth && Y > 23) return EXMY_ERR_FORMAT;  // e0m24 packs as e1m23, which it equals bit for bit
@@ -58,6 +59,9 @@ exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, int max_wi
   }
 
   const int emin8 = max_exp - (1 << X) + 2;
+  // fp16 holds binades 2^-14 .. 2^15 and multiples of 2^-24 below them: the format's top binade and its
+  // quantum must lie inside, so that every decoded value is an fp16 value
+  if (dt == EXMY_F16 && (max_exp > 142 || emin8 - 127 - Y < -24)) return EXMY_ERR_MAX_EXP;
   const uint32_t ones_y = (uint32_t)((1ull << Y) - 1ull);
   // Odd widths end in a 1-bit plane that holds exactly the sign: the encoder takes
   // it from the source bits and left-aligns the magnitude alone.
@@ -109,6 +113,7 @@ exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, int max_wi
 exmy_status_t make_block_format(exmy_dtype_t dt, int X, int Y, int max_width, bool after_rounding, FormatConsts* fc,
                                 BlockConsts* bc) {
   if (X == 8) return EXMY_ERR_FORMAT;  // identity exponent map: nothing for a block to choose
+  if (dt == EXMY_F16) return EXMY_ERR_FORMAT;  // the per-block forms take fp32 and bf16 only
   const int hi = X == 0 ? 253 : 254;
   if (exmy_status_t st = make_format(dt, X, Y, hi, max_width, fc, nullptr, nullptr)) return st;
   if (bc) {
@@ -303,6 +308,7 @@ exmy_status_t run_rows(RowsOp op, const void* matrix, const void* packed, exmy_d
                        int X, int Y, int max_exp, const uint8_t* max_exp_rows, void* stream) {
   RowsArgs args;
   bool wide = false;
+  if (dt == EXMY_F16) return EXMY_ERR_FORMAT;  // fp32 and bf16 only
   if (max_exp_rows) {
     if (exmy_status_t st = make_block_format(dt, X, Y, kBlockWidth, false, &args.fc, &args.bc)) return st;
     memset(&args.tc, 0, sizeof(args.tc));
@@ -386,7 +392,7 @@ exmy_status_t exmy_emulate(void* data_inout, exmy_dtype_t dt, uint64_t n, int X,
 
 exmy_status_t exmy_exponent_histogram(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t* hist256_dev,
                                       void* stream) {
-  if (dt != EXMY_F32 && dt != EXMY_BF16) return EXMY_ERR_FORMAT;
+  if (dt != EXMY_F32 && dt != EXMY_BF16 && dt != EXMY_F16) return EXMY_ERR_FORMAT;
   if (n > EXMY_MAX_ELEMENTS) return EXMY_ERR_COUNT;
   if (!hist256_dev) return EXMY_ERR_NULL;
   if (n == 0) return EXMY_OK;

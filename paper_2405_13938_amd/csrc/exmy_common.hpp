@@ -324,6 +324,47 @@ __device__ __forceinline__ uint32_t load_block_datum(rsrc_t r, uint32_t block) {
   return __builtin_amdgcn_raw_buffer_load_b8(r, block, 0, 0);
 }
 
+// Element types: float (fp32), uint16_t (bf16: the upper half of an fp32) and
+// f16_t (IEEE half: converted exactly to fp32 on the way in; the formats admitted
+// for it decode to fp16 values only, so the way out is exact too).  Elements of
+// the 16-bit types travel in pairs inside dwords.
+struct f16_t {
+  uint16_t bits;
+};
+template <typename T>
+inline constexpr bool kIsF16 = false;
+template <>
+inline constexpr bool kIsF16<f16_t> = true;
+
+// fp32-position bits of a 16-bit element.
+template <typename T>
+__device__ __forceinline__ uint32_t elem_bits(uint16_t raw) {
+  if constexpr (kIsF16<T>) return as_u32((float)__builtin_bit_cast(_Float16, raw));
+  return (uint32_t)raw << 16;
+}
+template <typename T>
+__device__ __forceinline__ uint32_t lo_elem_bits(uint32_t w) {
+  if constexpr (kIsF16<T>) return elem_bits<T>((uint16_t)w);
+  return w << 16;
+}
+template <typename T>
+__device__ __forceinline__ uint32_t hi_elem_bits(uint32_t w) {
+  if constexpr (kIsF16<T>) return elem_bits<T>((uint16_t)(w >> 16));
+  return w & 0xFFFF0000u;
+}
+// The 16-bit element with exactly the value of these fp32 bits, and a pair of them in a dword.
+template <typename T>
+__device__ __forceinline__ uint16_t to_elem(uint32_t bits) {
+  if constexpr (kIsF16<T>) return __builtin_bit_cast(uint16_t, (_Float16)as_f32(bits));
+  return (uint16_t)(bits >> 16);
+}
+template <typename T>
+__device__ __forceinline__ uint32_t pack_elems(uint32_t lo_bits, uint32_t hi_bits) {
+  if constexpr (kIsF16<T>)  // the values are fp16 values: any rounding mode converts them exactly
+    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(as_f32(lo_bits), as_f32(hi_bits)));
+  return __builtin_amdgcn_perm(hi_bits, lo_bits, 0x07060302u);
+}
+
 // (mask & a) | (~mask & b) in one instruction.
 __device__ __forceinline__ uint32_t bit_select(uint32_t mask, uint32_t a, uint32_t b) {
   uint32_t d;

@@ -18,6 +18,8 @@ struct Shape<uint16_t> {
   static constexpr bool kNT = true;
 };
 template <>
+struct Shape<f16_t> : Shape<uint16_t> {};
+template <>
 struct Shape<float> {
   static constexpr int kBlock = 256;
   static constexpr int kUnroll = 2;
@@ -68,6 +70,7 @@ hipError_t dispatch_w(int W, bool x8, const BatchArgs& args, uint64_t n_max, hip
 hipError_t decode_dispatch(exmy_dtype_t dt, int W, bool x8, const BatchArgs& args, uint64_t n_max,
                            hipStream_t stream) {
   if (dt == EXMY_F32) return dispatch_w<float>(W, x8, args, n_max, stream);
+  if (dt == EXMY_F16) return dispatch_w<f16_t>(W, x8, args, n_max, stream);
   return dispatch_w<uint16_t>(W, x8, args, n_max, stream);
 }
 

@@ -119,10 +119,10 @@ __device__ __forceinline__ void decode_unit(const UnitWords<W>& uw, const Format
   } else {
     // every value is exact in bf16 (or has just been rounded to it): keep the upper halves
     uint4 o;
-    o.x = __builtin_amdgcn_perm(b[1], b[0], 0x07060302u);
-    o.y = __builtin_amdgcn_perm(b[3], b[2], 0x07060302u);
-    o.z = __builtin_amdgcn_perm(b[5], b[4], 0x07060302u);
-    o.w = __builtin_amdgcn_perm(b[7], b[6], 0x07060302u);
+    o.x = pack_elems<T>(b[0], b[1]);
+    o.y = pack_elems<T>(b[2], b[3]);
+    o.z = pack_elems<T>(b[4], b[5]);
+    o.w = pack_elems<T>(b[6], b[7]);
     store16<kNT>(out, lane_unit * 16, tile_unit * 16, o);
   }
 }
@@ -224,7 +224,7 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(const BatchArgs batch) {
       if constexpr (sizeof(T) == 4)
         reinterpret_cast<uint32_t*>(dst)[i] = b;
       else
-        reinterpret_cast<uint16_t*>(dst)[i] = (uint16_t)(b >> 16);
+        reinterpret_cast<uint16_t*>(dst)[i] = to_elem<T>(b);
     }
   }
 }

@@ -30,6 +30,9 @@ hipError_t emulate_dispatch(exmy_dtype_t dt, bool wide, void* data, uint64_t n, 
   if (dt == EXMY_F32)
     return wide ? launch_emulate<float, true>(data, n, fc, tc, stream)
                 : launch_emulate<float, false>(data, n, fc, tc, stream);
+  if (dt == EXMY_F16)
+    return wide ? launch_emulate<f16_t, true>(data, n, fc, tc, stream)
+                : launch_emulate<f16_t, false>(data, n, fc, tc, stream);
   return wide ? launch_emulate<uint16_t, true>(data, n, fc, tc, stream)
               : launch_emulate<uint16_t, false>(data, n, fc, tc, stream);
 }

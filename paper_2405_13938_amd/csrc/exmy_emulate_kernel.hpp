@@ -41,6 +41,14 @@ __device__ __forceinline__ uint32_t emulate_bits(uint32_t u, const FormatConsts&
   return a0 >= 0x7F800000u ? u : r;  // Inf / NaN pass through
 }
 
+// Where an element of the pair in w is Inf / NaN, the original 16 bits (a half's NaN payload would not
+// survive the round trip through fp32 unchanged); elsewhere the emulated pair.
+__device__ __forceinline__ uint32_t keep_nonfinite_halves(uint32_t w, uint32_t emulated) {
+  const uint32_t lo = (w & 0x00007C00u) == 0x00007C00u ? 0x0000FFFFu : 0u;
+  const uint32_t hi = (w & 0x7C000000u) == 0x7C000000u ? 0xFFFF0000u : 0u;
+  return bit_select(lo | hi, w, emulated);
+}
+
 template <typename T, bool kWide>
 __device__ __forceinline__ uint4 emulate_vector(uint4 v, const FormatConsts& fc, const TensorConsts& tc) {
   uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -49,9 +57,10 @@ __device__ __forceinline__ uint4 emulate_vector(uint4 v, const FormatConsts& fc,
     if constexpr (sizeof(T) == 4) {
       w[k] = emulate_bits<kWide>(w[k], fc, tc);
     } else {
-      const uint32_t lo = emulate_bits<kWide>(w[k] << 16, fc, tc);
-      const uint32_t hi = emulate_bits<kWide>(w[k] & 0xFFFF0000u, fc, tc);
-      w[k] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
+      const uint32_t lo = emulate_bits<kWide>(lo_elem_bits<T>(w[k]), fc, tc);
+      const uint32_t hi = emulate_bits<kWide>(hi_elem_bits<T>(w[k]), fc, tc);
+      const uint32_t pair = pack_elems<T>(lo, hi);
+      w[k] = kIsF16<T> ? keep_nonfinite_halves(w[k], pair) : pair;
     }
   }
   return make_uint4(w[0], w[1], w[2], w[3]);
@@ -97,7 +106,8 @@ __global__ __launch_bounds__(kBlock) void emulate_kernel(T* __restrict__ data, u
         *p = emulate_bits<kWide>(*p, fc, tc);
       } else {
         uint16_t* p = reinterpret_cast<uint16_t*>(data) + i;
-        *p = (uint16_t)(emulate_bits<kWide>((uint32_t)*p << 16, fc, tc) >> 16);
+        const uint32_t u = elem_bits<T>(*p);
+        if ((u & 0x7FFFFFFFu) < 0x7F800000u) *p = to_elem<T>(emulate_bits<kWide>(u, fc, tc));  // Inf / NaN stay as they are
       }
     }
   }

@@ -22,6 +22,8 @@ struct Shape<uint16_t, kHist> {
   static constexpr bool kNT = true;
 };
 template <bool kHist>
+struct Shape<f16_t, kHist> : Shape<uint16_t, kHist> {};
+template <bool kHist>
 struct Shape<float, kHist> {
   static constexpr int kBlock = kHist ? 512 : 128;
   static constexpr int kUnroll = kHist ? 2 : 1;
@@ -68,6 +70,12 @@ hipError_t encode_dispatch(exmy_dtype_t dt, int W, bool wide, bool with_hist, co
                                : dispatch_w<float, false, true>(W, args, n_max, stream);
     return wide ? dispatch_w<float, true, false>(W, args, n_max, stream)
                 : dispatch_w<float, false, false>(W, args, n_max, stream);
+  }
+  if (dt == EXMY_F16) {
+    if (with_hist) return wide ? dispatch_w<f16_t, true, true>(W, args, n_max, stream)
+                               : dispatch_w<f16_t, false, true>(W, args, n_max, stream);
+    return wide ? dispatch_w<f16_t, true, false>(W, args, n_max, stream)
+                : dispatch_w<f16_t, false, false>(W, args, n_max, stream);
   }
   if (with_hist) return wide ? dispatch_w<uint16_t, true, true>(W, args, n_max, stream)
                              : dispatch_w<uint16_t, false, true>(W, args, n_max, stream);

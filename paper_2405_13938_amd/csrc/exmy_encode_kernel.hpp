@@ -55,8 +55,8 @@ __device__ __forceinline__ void group_bits(const uint4* v, uint32_t u[8]) {
     const uint32_t w[4] = {v[0].x, v[0].y, v[0].z, v[0].w};
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      u[2 * i] = w[i] << 16;
-      u[2 * i + 1] = w[i] & 0xFFFF0000u;
+      u[2 * i] = lo_elem_bits<T>(w[i]);
+      u[2 * i + 1] = hi_elem_bits<T>(w[i]);
     }
   }
 }
@@ -271,7 +271,7 @@ __global__ __launch_bounds__(kBlock) void encode_kernel(const BatchArgs batch) {
         if constexpr (sizeof(T) == 4)
           u[j] = reinterpret_cast<const uint32_t*>(src)[i];
         else
-          u[j] = (uint32_t) reinterpret_cast<const uint16_t*>(src)[i] << 16;
+          u[j] = elem_bits<T>(reinterpret_cast<const uint16_t*>(src)[i]);
         if constexpr (kHist) atomicAdd(&lds_hist[((u[j] >> 23) & 0xFFu) * kHistCopies], 1u);
       }
     }

@@ -28,6 +28,7 @@ hipError_t launch_histogram(const void* src, uint64_t n, uint64_t* hist, hipStre
 
 hipError_t histogram_dispatch(exmy_dtype_t dt, const void* src, uint64_t n, uint64_t* hist, hipStream_t stream) {
   if (dt == EXMY_F32) return launch_histogram<float>(src, n, hist, stream);
+  if (dt == EXMY_F16) return launch_histogram<f16_t>(src, n, hist, stream);
   return launch_histogram<uint16_t>(src, n, hist, stream);
 }
 

@@ -43,6 +43,9 @@ __device__ __forceinline__ void count_vector(uint4 v, uint32_t* bins, uint32_t c
   for (int k = 0; k < 4; ++k) {
     if constexpr (sizeof(T) == 4) {
       atomicAdd(&bins[__builtin_amdgcn_ubfe(w[k], 23, 8) * kCopies + copy], 1u);
+    } else if constexpr (kIsF16<T>) {  // the exponent of the value as an fp32
+      atomicAdd(&bins[__builtin_amdgcn_ubfe(lo_elem_bits<T>(w[k]), 23, 8) * kCopies + copy], 1u);
+      atomicAdd(&bins[__builtin_amdgcn_ubfe(hi_elem_bits<T>(w[k]), 23, 8) * kCopies + copy], 1u);
     } else {
       atomicAdd(&bins[__builtin_amdgcn_ubfe(w[k], 7, 8) * kCopies + copy], 1u);
       atomicAdd(&bins[__builtin_amdgcn_ubfe(w[k], 23, 8) * kCopies + copy], 1u);
@@ -98,7 +101,7 @@ __global__ __launch_bounds__(kBlock) void histogram_kernel(const T* __restrict__
       if constexpr (sizeof(T) == 4)
         e = (reinterpret_cast<const uint32_t*>(src)[i] >> 23) & 0xFFu;
       else
-        e = (reinterpret_cast<const uint16_t*>(src)[i] >> 7) & 0xFFu;
+        e = (elem_bits<T>(reinterpret_cast<const uint16_t*>(src)[i]) >> 23) & 0xFFu;
       atomicAdd(&bins[e * kCopies + copy], 1u);
     }
   }

@@ -36,10 +36,11 @@ def test_packed_bytes():
 
 
 def test_format_validation_matches_oracle_over_the_whole_domain():
-    for dt in (B.F32, B.BF16):
+    for dt in (B.F32, B.BF16, B.F16):
         for X in range(-1, 10):
             for Y in range(-1, 26):
-                for max_exp in (-1, 0, 1, (1 << max(X, 0)) - 2, (1 << max(X, 0)) - 1, 127, 253, 254, 255, 256):
+                for max_exp in (-1, 0, 1, (1 << max(X, 0)) - 2, (1 << max(X, 0)) - 1, 100 + Y + (1 << max(X, 0)),
+                                101 + Y + (1 << max(X, 0)), 102 + Y, 127, 142, 143, 253, 254, 255, 256):
                     for packed in (False, True):
                         got = B.check_format(dt, X, Y, max_exp, packed)
                         want = O.check_format(dt, X, Y, max_exp, packed)
@@ -113,7 +114,7 @@ def test_cpu_tensors_are_rejected():
     with pytest.raises(ValueError):
         B.encode(torch.zeros(8), 3, 3, 130)
     with pytest.raises(TypeError):
-        B._dtype_enum(torch.zeros(8, dtype=torch.float16))
+        B._dtype_enum(torch.zeros(8, dtype=torch.float64))
 
 
 def test_block_entry_points_validate_without_launch():
@@ -248,3 +249,22 @@ def test_twos_complement_entry_points_validate_without_launch():
     assert enc(ok, B.F32, 0, 7, 238, ok, None) == 3      # above 230 + Y the rounding addend would overflow
     assert enc(ok, B.F32, 0, 7, 237, ok, None) == 0
     assert enc(ok, B.F32, (1 << 40) + 1, 7, 133, ok, None) == 4
+
+
+def test_fp16_container_is_limited_to_the_per_tensor_entry_points():
+    L = B.lib()
+    ok = ctypes.c_void_p(0x1000)
+    assert L.exmy_encode(ok, B.F16, 0, 3, 3, 130, ok, None) == 0
+    assert L.exmy_decode(ok, B.F16, 0, 3, 3, 130, ok, None) == 0
+    assert L.exmy_emulate(ok, B.F16, 0, 4, 10, 130, None) == 0
+    assert L.exmy_exponent_histogram(ok, B.F16, 0, ok, None) == 0
+    assert L.exmy_encode(ok, B.F16, 0, 6, 3, 130, ok, None) == 2       # X <= 5
+    assert L.exmy_encode(ok, B.F16, 0, 3, 11, 130, ok, None) == 2      # Y <= 10
+    assert L.exmy_encode(ok, B.F16, 0, 3, 3, 143, ok, None) == 3       # top binade above 2^15
+    assert L.exmy_encode(ok, B.F16, 0, 3, 3, 111, ok, None) == 3       # quantum below 2^-24
+    assert L.exmy_encode(ok, B.F16, 0, 3, 3, 112, ok, None) == 0
+    assert L.exmy_block_max_exp(ok, B.F16, 0, 8, 3, ok, None) == 2
+    assert L.exmy_encode_blocks(ok, B.F16, 0, 8, 3, 3, ok, ok, None) == 2
+    assert L.exmy_block_scale(ok, B.F16, 0, 8, 3, 3, ok, None) == 2
+    assert L.exmy_encode_rows(ok, B.F16, 0, 8, 3, 3, 130, None, ok, None) == 2
+    assert L.exmy_encode_int(ok, B.F16, 0, 7, 133, ok, None) == 2
