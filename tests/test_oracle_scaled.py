@@ -135,6 +135,22 @@ def test_scaled_codes_are_the_nearest_grid_points(X, Y):
     assert np.array_equal(dec.view(np.uint32), want.view(np.uint32))
 
 
+def test_bf16_results_are_the_fp32_results_rounded_by_the_library():
+    g = torch.Generator().manual_seed(11)
+    n, block = 1 << 14, 32
+    x = (torch.randn(n, generator=g) * torch.exp2(torch.randint(-20, 20, (n,), generator=g).float())).bfloat16()
+    xn = as_np(x)
+    for X, Y in ((2, 1), (3, 3), (0, 4), (4, 3)):
+        s = O.block_scale(xn, block, X, Y)
+        s = (s * np.float32(1.2345)).astype(np.float32)  # not a power of two: products need rounding
+        packed = O.encode_scaled(xn, block, X, Y, s)
+        d32 = O.decode_scaled(packed, F32, n, block, X, Y, s)
+        d16 = O.decode_scaled(packed, BF16, n, block, X, Y, s)
+        want = torch.from_numpy(d32).bfloat16()
+        assert np.array_equal(d16, want.view(torch.int16).numpy().view(np.uint16))
+        assert (torch.from_numpy(d32) != want.float()).any()  # the rounding really happens
+
+
 def test_scaled_validation():
     x = np.zeros(64, dtype=np.float32)
     s = np.ones(8, dtype=np.float32)
