@@ -230,6 +230,7 @@ def block_scheme_rates(exmy, synth, dev):
         rates = {
             "block_max_exp": (n * 2 + nb, rot(lambda k: exmy.block_max_exp(xs[k], block, X, out=meta))),
             "encode_blocks": (codec + nb, rot(lambda k: exmy.encode_blocks(xs[k], block, X, Y, meta, out=outs[k]))),
+            "encode_blocks_auto": (codec + nb, rot(lambda k: exmy.encode_blocks_auto(xs[k], block, X, Y, 0, meta, out=outs[k]))),
             "decode_blocks": (codec + nb, rot(lambda k: exmy.decode_blocks(outs[k], torch.bfloat16, n, block, X, Y, meta, out=dst))),
             "block_scale": (n * 2 + 4 * nb, rot(lambda k: exmy.block_scale(xs[k], block, X, Y, out=scale))),
             "encode_scaled": (codec + 4 * nb, rot(lambda k: exmy.encode_scaled(xs[k], block, X, Y, scale, out=outs[k]))),

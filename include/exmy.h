@@ -195,8 +195,11 @@ exmy_status_t exmy_emulate_blocks(void* data_inout, exmy_dtype_t dt, uint64_t n,
                                   const uint8_t* max_exp_dev, void* stream);
 
 /* The pipeline of Section 2.2.1 in one call: the metadata of `scheme` is
- * computed from src into max_exp_dev (an OUTPUT here, one byte per block), then
- * src is encoded with it; two launches on `stream`, src is read twice. */
+ * computed from src into max_exp_dev (an OUTPUT here, one byte per block) and
+ * src is encoded with it.  Blocks of 8, 16, ..., 512 elements and blocks of 520
+ * to 32768 (bf16) / 16384 (fp32) elements take one launch that reads src once
+ * (the block stays in registers between the two steps); other sizes take two
+ * launches on `stream` and read src twice.  Same results either way. */
 typedef enum { EXMY_MAX_EXP_BEFORE_ROUNDING = 0, EXMY_MAX_EXP_AFTER_ROUNDING = 1 } exmy_scheme_t;
 exmy_status_t exmy_encode_blocks_auto(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
                                       exmy_scheme_t scheme, uint8_t* max_exp_dev, void* dst_packed, void* stream);

@@ -11,7 +11,7 @@ LIB = os.path.join(HERE, "libexmy.so")
 OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["exmy_api.hip", "exmy_encode.hip", "exmy_decode.hip", "exmy_emulate.hip", "exmy_histogram.hip",
            "exmy_encode_blocks.hip", "exmy_decode_blocks.hip", "exmy_emulate_blocks.hip",
-           "exmy_encode_rows.hip", "exmy_decode_rows.hip", "exmy_int.hip"]
+           "exmy_encode_rows.hip", "exmy_decode_rows.hip", "exmy_int.hip", "exmy_encode_auto.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3",

@@ -237,7 +237,7 @@ exmy_status_t run_batch(Op op, const exmy_tensor_t* tensors, size_t count, exmy_
   return flush() == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
 }
 
-enum class BlockOp { kMaxExp, kMaxExpRounded, kScale, kEncode, kDecode, kEmulate };
+enum class BlockOp { kMaxExp, kMaxExpRounded, kScale, kEncode, kDecode, kEmulate, kAutoEncode, kAutoEncodeRounded };
 
 // Shared validation and launch of the per-block entry points.  `elems` is the
 // bf16 / fp32 side, `packed` the plane side (encode and decode only); `side` is
@@ -245,9 +245,10 @@ enum class BlockOp { kMaxExp, kMaxExpRounded, kScale, kEncode, kDecode, kEmulate
 exmy_status_t run_blocks(BlockOp op, bool scaled, const void* elems, const void* packed, exmy_dtype_t dt, uint64_t n,
                          uint64_t block, int X, int Y, const void* side, void* stream) {
   BlockArgs args;
-  const bool is_packed = op == BlockOp::kEncode || op == BlockOp::kDecode;
-  if (exmy_status_t st = make_block_format(dt, X, Y, is_packed ? kBlockWidth : kAnyWidth, op == BlockOp::kMaxExpRounded, &args.fc,
-                                            &args.bc))
+  const bool is_auto = op == BlockOp::kAutoEncode || op == BlockOp::kAutoEncodeRounded;
+  const bool is_packed = op == BlockOp::kEncode || op == BlockOp::kDecode || is_auto;
+  const bool rounded = op == BlockOp::kMaxExpRounded || op == BlockOp::kAutoEncodeRounded;
+  if (exmy_status_t st = make_block_format(dt, X, Y, is_packed ? kBlockWidth : kAnyWidth, rounded, &args.fc, &args.bc))
     return st;
   bool wide_format = Y > 21;
   args.vmax127 = 0.0f;
@@ -286,6 +287,12 @@ exmy_status_t run_blocks(BlockOp op, bool scaled, const void* elems, const void*
       args.src = elems;
       args.dst = const_cast<void*>(packed);
       e = encode_blocks_dispatch(dt, 1 + X + Y, args, scaled, s);
+      break;
+    case BlockOp::kAutoEncode:
+    case BlockOp::kAutoEncodeRounded:
+      args.src = elems;
+      args.dst = const_cast<void*>(packed);
+      e = encode_blocks_auto_dispatch(dt, 1 + X + Y, args, s);
       break;
     case BlockOp::kDecode:
       args.src = packed;
@@ -421,7 +428,11 @@ exmy_status_t exmy_encode_blocks_auto(const void* src, exmy_dtype_t dt, uint64_t
   if (exmy_status_t st = make_block_format(dt, X, Y, kBlockWidth, false, nullptr, nullptr)) return st;
   if (n && !dst_packed) return EXMY_ERR_NULL;
   if (n && !aligned16(dst_packed)) return EXMY_ERR_ALIGN;
-  const BlockOp op = scheme == EXMY_MAX_EXP_AFTER_ROUNDING ? BlockOp::kMaxExpRounded : BlockOp::kMaxExp;
+  const bool rounded = scheme == EXMY_MAX_EXP_AFTER_ROUNDING;
+  if (block >= 8 && block % 8 == 0 && block <= EXMY_MAX_BLOCK && encode_blocks_auto_fits(dt, (uint32_t)(block / 8)))
+    return run_blocks(rounded ? BlockOp::kAutoEncodeRounded : BlockOp::kAutoEncode, false, src, dst_packed, dt, n, block, X,
+                      Y, max_exp_dev, stream);  // one pass: the block stays in registers
+  const BlockOp op = rounded ? BlockOp::kMaxExpRounded : BlockOp::kMaxExp;
   if (exmy_status_t st = run_blocks(op, false, src, nullptr, dt, n, block, X, Y, max_exp_dev, stream)) return st;
   return run_blocks(BlockOp::kEncode, false, src, dst_packed, dt, n, block, X, Y, max_exp_dev, stream);
 }

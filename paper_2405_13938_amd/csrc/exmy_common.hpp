@@ -296,6 +296,37 @@ __device__ __forceinline__ TensorConsts derive_tc(uint32_t max_exp, const BlockC
   return tc;
 }
 
+// Key of an element for the block maximum: its magnitude bits plus one in the
+// exponent field, as a signed integer.  Inf / NaN patterns come out negative, so
+// a signed maximum over keys skips them; no finite element gives a key <= 0.
+__device__ __forceinline__ int32_t exp_key(uint32_t u) { return (int32_t)((u & 0x7FFFFFFFu) + 0x00800000u); }
+constexpr int32_t kNoKey = (int32_t)0x80000000;
+
+// Metadatum of a block from the largest key of its elements: the biased exponent
+// of the largest finite magnitude, "before rounding" or, with the round_* fields
+// set, after that magnitude is rounded to the mantissa width of the top binade
+// (Section 2 "Metadata"), clamped into the valid range.
+__device__ __forceinline__ uint32_t meta_from_key(int32_t key, const BlockConsts& bc) {
+  uint32_t a = key > 0 ? (uint32_t)key - 0x00800000u : 0u;  // bits of the largest finite magnitude (0 if none)
+  a += bc.round_half + ((a >> bc.round_shift) & bc.round_odd);  // may carry up to exponent 255
+  return min(max(a >> 23, bc.meta_lo), bc.meta_hi);
+}
+
+// Maximum over the 2^lg lanes (lg <= 6) that share all lane-index bits above the
+// low lg; every lane of the wavefront must call it.  Steps inside a row of 16
+// lanes are data-parallel-primitive moves: after the two quad permutes every
+// lane of a quad holds the quad's maximum, so mirroring 8 and then 16 lanes
+// brings in exactly the other half each time.
+__device__ __forceinline__ int32_t max_over_lanes(int32_t m, uint32_t lg) {
+  if (lg >= 1) m = max(m, __builtin_amdgcn_update_dpp(m, m, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
+  if (lg >= 2) m = max(m, __builtin_amdgcn_update_dpp(m, m, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
+  if (lg >= 3) m = max(m, __builtin_amdgcn_update_dpp(m, m, 0x141, 0xF, 0xF, false));  // row_half_mirror
+  if (lg >= 4) m = max(m, __builtin_amdgcn_update_dpp(m, m, 0x140, 0xF, 0xF, false));  // row_mirror
+  if (lg >= 5) m = max(m, __shfl_xor(m, 16, 64));
+  if (lg >= 6) m = max(m, __shfl_xor(m, 32, 64));
+  return m;
+}
+
 // First block touched by the tile whose first unit is w0, and w0's offset inside it.
 __device__ __forceinline__ void tile_first_block(uint64_t w0, const BlockIndex& bi, uint64_t& blk0, uint32_t& off) {
   if (bi.log2 != kNotPow2) {

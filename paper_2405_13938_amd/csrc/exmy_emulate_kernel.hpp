@@ -247,8 +247,8 @@ __global__ __launch_bounds__(kBlock) void emulate_blocks_kernel(const BlockArgs 
 // Maximum exponent of every block, "before rounding" or "after rounding"
 // (Section 2 "Metadata"): the biased exponent of the block's largest finite
 // magnitude, taken as it is or after that value is rounded to the mantissa width
-// of the format's top binade, clamped into the valid range.  Adding 1 to the exponent field turns Inf / NaN patterns negative
-// as signed integers, so a signed maximum skips them.
+// of the format's top binade, clamped into the valid range (see exp_key and
+// meta_from_key).
 
 template <typename T, typename V4>
 __device__ __forceinline__ int32_t vector_exp_key(V4 v) {
@@ -257,10 +257,10 @@ __device__ __forceinline__ int32_t vector_exp_key(V4 v) {
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     if constexpr (sizeof(T) == 4) {
-      m = max(m, (int32_t)((w[k] & 0x7FFFFFFFu) + 0x00800000u));
+      m = max(m, exp_key(w[k]));
     } else {
-      m = max(m, (int32_t)(((w[k] << 16) & 0x7FFFFFFFu) + 0x00800000u));
-      m = max(m, (int32_t)((w[k] & 0x7FFF0000u) + 0x00800000u));
+      m = max(m, exp_key(w[k] << 16));
+      m = max(m, exp_key(w[k] & 0xFFFF0000u));
     }
   }
   return m;
@@ -273,7 +273,7 @@ __device__ __forceinline__ int32_t element_exp_key(const T* p) {
     u = *reinterpret_cast<const uint32_t*>(p);
   else
     u = (uint32_t)*reinterpret_cast<const uint16_t*>(p) << 16;
-  return (int32_t)((u & 0x7FFFFFFFu) + 0x00800000u);
+  return exp_key(u);
 }
 
 // Result of one block from the key of its largest finite magnitude.  kScale:
@@ -285,25 +285,8 @@ __device__ __forceinline__ void store_block_result(const BlockArgs& args, uint64
   if constexpr (kScale) {
     args.scale[block] = fmaxf(as_f32(a) / args.vmax127, as_f32(0x00800000u));
   } else {
-    const BlockConsts& bc = args.bc;
-    a += bc.round_half + ((a >> bc.round_shift) & bc.round_odd);  // "after rounding"; may carry up to exponent 255
-    args.meta[block] = (uint8_t)min(max(a >> 23, bc.meta_lo), bc.meta_hi);
+    args.meta[block] = (uint8_t)meta_from_key(key, args.bc);
   }
-}
-
-// Maximum over the 2^lg lanes (lg <= 6) that share all lane-index bits above the
-// low lg; every lane of the wavefront must call it.  Steps inside a row of 16
-// lanes are data-parallel-primitive moves: after the two quad permutes every
-// lane of a quad holds the quad's maximum, so mirroring 8 and then 16 lanes
-// brings in exactly the other half each time.
-__device__ __forceinline__ int32_t max_over_lanes(int32_t m, uint32_t lg) {
-  if (lg >= 1) m = max(m, __builtin_amdgcn_update_dpp(m, m, 0xB1, 0xF, 0xF, false));   // quad_perm [1,0,3,2]
-  if (lg >= 2) m = max(m, __builtin_amdgcn_update_dpp(m, m, 0x4E, 0xF, 0xF, false));   // quad_perm [2,3,0,1]
-  if (lg >= 3) m = max(m, __builtin_amdgcn_update_dpp(m, m, 0x141, 0xF, 0xF, false));  // row_half_mirror
-  if (lg >= 4) m = max(m, __builtin_amdgcn_update_dpp(m, m, 0x140, 0xF, 0xF, false));  // row_mirror
-  if (lg >= 5) m = max(m, __shfl_xor(m, 16, 64));
-  if (lg >= 6) m = max(m, __shfl_xor(m, 32, 64));
-  return m;
 }
 
 // Blocks of 2^lg vectors, lg <= 6: flat tiles of kBlock * kUnroll vectors, one

@@ -403,5 +403,223 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
   }
 }
 
+// ---------------------------------------------------------------------------
+// Metadata and codes in one pass over the source (Section 2.2.1: the encoded
+// tensor is the codes plus the per-block maximum exponents): the elements stay in
+// registers between the block maximum and the conversion.
+
+// The group's 8 elements in fp32 position: a 16-byte group from registers, or, for
+// the ragged last group of the tensor, its elements one by one (zeros beyond n).
+template <typename T>
+__device__ __forceinline__ void ragged_group_bits(const void* src_v, uint64_t first, uint64_t n, uint32_t u[8]) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const uint64_t i = first + j;
+    u[j] = 0;
+    if (i < n) {
+      if constexpr (sizeof(T) == 4)
+        u[j] = static_cast<const uint32_t*>(src_v)[i];
+      else
+        u[j] = elem_bits<T>(static_cast<const uint16_t*>(src_v)[i]);
+    }
+  }
+}
+
+__device__ __forceinline__ int32_t group_key(const uint32_t u[8]) {
+  int32_t k = kNoKey;
+#pragma unroll
+  for (int j = 0; j < 8; ++j) k = max(k, exp_key(u[j]));
+  return k;
+}
+
+// Blocks of 2^lg groups, lg <= 6: flat tiles; the lanes of a block combine their
+// keys with a butterfly, one of them writes the metadatum, all of them encode.
+template <typename T, int W, int kBlock, int kUnroll, bool kNT>
+__global__ __launch_bounds__(kBlock) void encode_blocks_auto_small_kernel(const BlockArgs args) {
+  constexpr uint32_t TG = kBlock * kUnroll;
+  constexpr int kLoads = TileRegs<T, kUnroll>::kLoads;
+  const uint4* __restrict__ src4 = static_cast<const uint4*>(args.src);
+  uint8_t* __restrict__ dst = static_cast<uint8_t*>(args.dst);
+  const uint64_t n = args.n;
+  const FormatConsts fc = args.fc;
+  const BlockConsts bc = args.bc;
+  const uint32_t lg = args.bi.log2;
+  const uint64_t G = (n + 7) / 8;
+  const uint64_t Gfull = n / 8;
+  const uint32_t tiles = (uint32_t)((G + TG - 1) / TG);
+
+  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+    const uint64_t g0 = (uint64_t)tile * TG;
+    const rsrc_t src = make_rsrc(src4 + g0 * kLoads);
+    PlaneDst<W> pd;
+    make_plane_dst<W>(dst, G, g0, pd);
+    const uint64_t whole_left = Gfull > g0 ? Gfull - g0 : 0;
+    const uint32_t whole = whole_left < TG ? (uint32_t)whole_left : TG;  // groups of this tile with all 8 elements
+    TileRegs<T, kUnroll> regs;
+    load_tile<T, kBlock, kUnroll, kNT, true>(src, 0, whole, regs);
+#pragma unroll
+    for (int r = 0; r < kUnroll; ++r) {
+      const uint32_t idx = r * kBlock + threadIdx.x;
+      const uint64_t g = g0 + idx;
+      uint32_t u[8];
+      int32_t key = kNoKey;
+      if (idx < whole) {
+        group_bits<T>(regs.v[r], u);
+        key = group_key(u);
+      } else if (g < G) {  // the ragged last group of the tensor
+        ragged_group_bits<T>(args.src, g * 8, n, u);
+        key = group_key(u);
+      }
+      key = max_over_lanes(key, lg);  // every lane takes part
+      if (g < G) {
+        const uint32_t me = meta_from_key(key, bc);
+        if ((threadIdx.x & ((1u << lg) - 1u)) == 0) args.meta[g >> lg] = (uint8_t)me;
+        encode_group_meta<W>(u, me, fc, bc, pd, threadIdx.x, r * kBlock);
+      }
+    }
+  }
+}
+
+// Longer blocks: one workgroup per block, every lane holding up to kUnroll of the
+// block's groups (the block must not exceed kBlock * kUnroll groups).
+template <typename T, int W, int kBlock, int kUnroll, bool kNT>
+__global__ __launch_bounds__(kBlock) void encode_blocks_auto_team_kernel(const BlockArgs args) {
+  constexpr int kLoads = TileRegs<T, kUnroll>::kLoads;
+  __shared__ int32_t part[kBlock / 64];
+  const uint4* __restrict__ src4 = static_cast<const uint4*>(args.src);
+  uint8_t* __restrict__ dst = static_cast<uint8_t*>(args.dst);
+  const uint64_t n = args.n;
+  const FormatConsts fc = args.fc;
+  const BlockConsts bc = args.bc;
+  const uint64_t G = (n + 7) / 8;
+  const uint64_t Gfull = n / 8;
+  const uint32_t bg = args.block_groups;
+
+  for (uint64_t b = blockIdx.x; b < args.n_blocks; b += gridDim.x) {
+    const uint64_t g0 = b * bg;
+    const uint64_t left = G - g0;
+    const uint32_t count = left < bg ? (uint32_t)left : bg;  // groups of this block, a ragged last one included
+    const uint64_t whole_left = Gfull > g0 ? Gfull - g0 : 0;
+    const uint32_t whole = whole_left < count ? (uint32_t)whole_left : count;
+    const rsrc_t src = make_rsrc(src4 + g0 * kLoads);
+    TileRegs<T, kUnroll> regs;
+    load_tile<T, kBlock, kUnroll, kNT, true>(src, 0, whole, regs);
+    uint32_t ragged[8];
+    const bool has_ragged = whole < count && threadIdx.x == whole % kBlock;  // the lane that owns group `whole`
+    if (has_ragged) ragged_group_bits<T>(args.src, (g0 + whole) * 8, n, ragged);
+    int32_t key = kNoKey;
+#pragma unroll
+    for (int r = 0; r < kUnroll; ++r) {
+      if (r * kBlock + threadIdx.x < whole) {
+        uint32_t u[8];
+        group_bits<T>(regs.v[r], u);
+        key = max(key, group_key(u));
+      }
+    }
+    if (has_ragged) key = max(key, group_key(ragged));
+    key = max_over_lanes(key, 6);
+    if constexpr (kBlock > 64) {
+      if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = key;
+      __syncthreads();
+#pragma unroll
+      for (int w = 0; w < kBlock / 64; ++w) key = max(key, part[w]);
+      __syncthreads();  // part is reused by the next block
+    }
+    const uint32_t me = __builtin_amdgcn_readfirstlane(meta_from_key(key, bc));
+    if (threadIdx.x == 0) args.meta[b] = (uint8_t)me;
+    PlaneDst<W> pd;
+    make_plane_dst<W>(dst, G, g0, pd);
+#pragma unroll
+    for (int r = 0; r < kUnroll; ++r) {
+      const uint32_t idx = r * kBlock + threadIdx.x;
+      if (idx < whole) {
+        uint32_t u[8];
+        group_bits<T>(regs.v[r], u);
+        encode_group_meta<W>(u, me, fc, bc, pd, threadIdx.x, r * kBlock);
+      } else if (idx == whole && whole < count) {
+        encode_group_meta<W>(ragged, me, fc, bc, pd, threadIdx.x, r * kBlock);
+      }
+    }
+  }
+}
+
+// Blocks too long for the registers of one workgroup: the workgroup first walks its
+// block for the maximum, then walks it again to encode; the second walk finds the
+// block (tens of KB) in the L2 cache, so HBM is still read once.
+template <typename T, int W, int kBlock, int kUnroll, bool kNT>
+__global__ __launch_bounds__(kBlock) void encode_blocks_auto_twopass_kernel(const BlockArgs args) {
+  constexpr uint32_t TG = kBlock * kUnroll;
+  constexpr int kLoads = TileRegs<T, kUnroll>::kLoads;
+  __shared__ int32_t part[kBlock / 64];
+  const uint4* __restrict__ src4 = static_cast<const uint4*>(args.src);
+  uint8_t* __restrict__ dst = static_cast<uint8_t*>(args.dst);
+  const uint64_t n = args.n;
+  const FormatConsts fc = args.fc;
+  const BlockConsts bc = args.bc;
+  const uint64_t G = (n + 7) / 8;
+  const uint64_t Gfull = n / 8;
+  const uint32_t bg = args.block_groups;
+
+  for (uint64_t b = blockIdx.x; b < args.n_blocks; b += gridDim.x) {
+    const uint64_t g0 = b * bg;
+    const uint64_t left = G - g0;
+    const uint32_t count = left < bg ? (uint32_t)left : bg;  // groups of this block, a ragged last one included
+    const uint64_t whole_left = Gfull > g0 ? Gfull - g0 : 0;
+    const uint32_t whole = whole_left < count ? (uint32_t)whole_left : count;
+    const rsrc_t src = make_rsrc(src4 + g0 * kLoads);
+    const uint32_t tiles = (whole + TG - 1) / TG;
+
+    // first walk (plain loads: the lines should stay cached for the second)
+    int32_t key = kNoKey;
+    for (uint32_t t = 0; t < tiles; ++t) {
+      TileRegs<T, kUnroll> regs;
+      load_tile<T, kBlock, kUnroll, false, true>(src, t * TG, whole - t * TG, regs);
+#pragma unroll
+      for (int r = 0; r < kUnroll; ++r) {
+        if (r * kBlock + threadIdx.x < whole - t * TG) {
+          uint32_t u[8];
+          group_bits<T>(regs.v[r], u);
+          key = max(key, group_key(u));
+        }
+      }
+    }
+    uint32_t ragged[8];
+    const bool has_ragged = whole < count && threadIdx.x == 0;
+    if (has_ragged) {
+      ragged_group_bits<T>(args.src, (g0 + whole) * 8, n, ragged);
+      key = max(key, group_key(ragged));
+    }
+    key = max_over_lanes(key, 6);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = key;
+    __syncthreads();
+#pragma unroll
+    for (int w = 0; w < kBlock / 64; ++w) key = max(key, part[w]);
+    __syncthreads();  // part is reused by the next block
+    const uint32_t me = __builtin_amdgcn_readfirstlane(meta_from_key(key, bc));
+    if (threadIdx.x == 0) args.meta[b] = (uint8_t)me;
+
+    // second walk
+    PlaneDst<W> pd;
+    make_plane_dst<W>(dst, G, g0, pd);
+    for (uint32_t t = 0; t < tiles; ++t) {
+      TileRegs<T, kUnroll> regs;
+      load_tile<T, kBlock, kUnroll, kNT, true>(src, t * TG, whole - t * TG, regs);
+#pragma unroll
+      for (int r = 0; r < kUnroll; ++r) {
+        if (r * kBlock + threadIdx.x < whole - t * TG) {
+          uint32_t u[8];
+          group_bits<T>(regs.v[r], u);
+          encode_group_meta<W>(u, me, fc, bc, pd, threadIdx.x, t * TG + r * kBlock);
+        }
+      }
+    }
+    if (has_ragged) {
+      PlaneDst<W> pr;
+      make_plane_dst<W>(dst, G, g0 + whole, pr);
+      encode_group_meta<W>(ragged, me, fc, bc, pr, 0, 0);
+    }
+  }
+}
+
 }  // namespace enc
 }  // namespace exmy

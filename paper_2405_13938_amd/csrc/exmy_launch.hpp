@@ -43,6 +43,9 @@ hipError_t encode_blocks_dispatch(exmy_dtype_t dt, int W, const BlockArgs& args,
 hipError_t decode_blocks_dispatch(exmy_dtype_t dt, int W, const BlockArgs& args, bool scaled, hipStream_t stream);
 hipError_t emulate_blocks_dispatch(exmy_dtype_t dt, const BlockArgs& args, bool wide_format, bool scaled,
                                    hipStream_t stream);
+// Metadata + codes in one pass; only for block sizes that encode_blocks_auto_fits accepts (args.meta is written).
+bool encode_blocks_auto_fits(exmy_dtype_t dt, uint32_t block_groups);
+hipError_t encode_blocks_auto_dispatch(exmy_dtype_t dt, int W, const BlockArgs& args, hipStream_t stream);
 hipError_t block_max_exp_dispatch(exmy_dtype_t dt, const BlockArgs& args, bool scale, hipStream_t stream);
 // Packing along rows (args.tiles is filled in by the dispatcher).
 hipError_t encode_rows_dispatch(exmy_dtype_t dt, int W, const RowsArgs& args, bool per_row, bool wide,

@@ -194,13 +194,51 @@ def test_max_exp_after_rounding(dtype):
 
 
 @pytest.mark.parametrize("scheme", [exmy.binding.BEFORE_ROUNDING, exmy.binding.AFTER_ROUNDING])
-def test_encode_blocks_auto(scheme):
-    for dtype in (torch.bfloat16, torch.float32):
-        x = synth.gaussian_bf16(300 * 1024 + 13, seed=21).to(dtype).to(DEV)
-        host = synth.bits_numpy(x)
-        for block, X, Y in ((16, 2, 1), (32, 1, 2), (1024, 3, 2), (4096, 3, 3)):
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+def test_encode_blocks_auto(scheme, dtype):
+    # every launch form: blocks inside flat tiles, a wavefront-sized or a full workgroup per block with few or
+    # many groups per lane, and the two-launch fallback (odd small blocks, very long blocks); ragged ends
+    g = torch.Generator().manual_seed(21 + scheme)
+    n = 300 * 1024 + 13
+    x = (torch.randn(n, generator=g) * torch.exp2(torch.randint(-10, 10, (n,), generator=g).float()))
+    x[::1001] = float("inf")
+    x[5::1003] = float("nan")
+    x[4096:8192] = 0.0
+    x = x.to(dtype).to(DEV)
+    host = synth.bits_numpy(x)
+    fmts = [(2, 1), (3, 3), (1, 2), (0, 4), (4, 3), (5, 2), (7, 0), (4, 7)]
+    blocks = [8, 16, 32, 64, 128, 256, 512, 24, 520, 1024, 2048, 2056, 4096, 8192, 11008, 16384, 32768, 40000, 1 << 18]
+    for i, block in enumerate(blocks):
+        X, Y = fmts[i % len(fmts)]
+        for nn in (n, n - n % block if n >= block else n, 7, block + 3):
+            xd, hd = x[:nn], host[:nn]
+            packed, meta = exmy.encode_blocks_auto(xd, block, X, Y, scheme)
+            torch.cuda.synchronize()
+            want_meta = (O.block_max_exp_after_rounding(hd, block, X, Y) if scheme else O.block_max_exp(hd, block, X))
+            assert np.array_equal(meta.cpu().numpy(), want_meta), (block, X, Y, nn)
+            want = O.encode_blocks(hd, block, X, Y, want_meta, threads=THREADS)
+            assert np.array_equal(packed.cpu().numpy(), want), (block, X, Y, nn)
+
+
+@pytest.mark.parametrize("W", range(1, 17))
+def test_encode_blocks_auto_every_width(W):
+    x = synth.shuffled(synth.all_bf16_patterns(), 500 + W).to(DEV)
+    host = synth.bits_numpy(x)
+    x32 = synth.shuffled(synth.f32_edge_sweep(seed=W), 600 + W).to(DEV)
+    host32 = synth.bits_numpy(x32)
+    for i, (X, Y) in enumerate(formats_of_width(W, torch.bfloat16)):
+        for block in ([16, 1024, 4096, 11008][(W + i) % 4], [512, 520, 8192, 32768][(W + i) % 4]):
+            scheme = (W + i) % 2
             packed, meta = exmy.encode_blocks_auto(x, block, X, Y, scheme)
             torch.cuda.synchronize()
             want_meta = (O.block_max_exp_after_rounding(host, block, X, Y) if scheme else O.block_max_exp(host, block, X))
-            assert np.array_equal(meta.cpu().numpy(), want_meta)
+            assert np.array_equal(meta.cpu().numpy(), want_meta), (block, X, Y)
             assert np.array_equal(packed.cpu().numpy(), O.encode_blocks(host, block, X, Y, want_meta, threads=THREADS))
+    for i, (X, Y) in enumerate(formats_of_width(W, torch.float32)):
+        block = [32, 1024, 4096, 16384][(W + i) % 4]
+        scheme = (W + i + 1) % 2
+        packed, meta = exmy.encode_blocks_auto(x32, block, X, Y, scheme)
+        torch.cuda.synchronize()
+        want_meta = (O.block_max_exp_after_rounding(host32, block, X, Y) if scheme else O.block_max_exp(host32, block, X))
+        assert np.array_equal(meta.cpu().numpy(), want_meta), (block, X, Y)
+        assert np.array_equal(packed.cpu().numpy(), O.encode_blocks(host32, block, X, Y, want_meta, threads=THREADS))
