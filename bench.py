@@ -358,6 +358,23 @@ def main():
         "decode_frac": round(dec_gbps / HBM_PEAK_GBPS, 4),
     }
 
+    # a plain device copy on the same box, for scale: 1 GiB read + 1 GiB written per launch
+    ca = torch.empty(1 << 28, dtype=torch.float32, device=dev).normal_()
+    cb = torch.empty_like(ca)
+    for _ in range(3):
+        cb.copy_(ca)
+    c0, c1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    c0.record()
+    for _ in range(10):
+        cb.copy_(ca)
+    c1.record()
+    torch.cuda.synchronize()
+    copy_gbps = 10 * 2 * ca.numel() * 4 / (c0.elapsed_time(c1) * 1e-3) / 1e9
+    del ca, cb
+    torch.cuda.empty_cache()
+    roofline["device_copy_GBps"] = round(copy_gbps, 1)
+    roofline["frac_of_device_copy"] = round(achieved / copy_gbps, 4)
+
     line = {
         "metric": "encode / decode GB/s (bytes in+out) and % of MI355X HBM peak, e3m3 7-bit",
         "value": round(value, 1),
