@@ -152,10 +152,8 @@ exmy_status_t exmy_encode_with_histogram(const void* src, exmy_dtype_t dt, uint6
  * block may be short; there are exmy_block_count(n, block) of them.  With a
  * row-major matrix, block = the row length gives per-row (per-channel)
  * metadata, a divisor of it gives sub-row blocks (e.g. 32 or 64 elements).
- * `block` is a multiple of 8 in [8, EXMY_MAX_BLOCK], else EXMY_ERR_BLOCK.
- * Blocks of 8, 16, ..., 512 elements are handled inside flat tiles; any other
- * block size gets workgroups of its own (fastest when a block is a few thousand
- * elements or more).
+ * `block` is a multiple of 8 in [8, EXMY_MAX_BLOCK], else EXMY_ERR_BLOCK;
+ * every such size runs at the same rate (a block need not be a power of two).
  *
  * max_exp_dev is a DEVICE array of one byte per block.  Valid metadata here is
  * 2^X <= max_exp <= 254 for 1 <= X <= 7 and 1 <= max_exp <= 253 for X = 0 (the
