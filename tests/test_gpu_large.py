@@ -74,3 +74,87 @@ def test_beyond_4g(dtype, n):
     assert np.array_equal(hist2.cpu().numpy(), want)
     host = synth.bits_numpy(x[: 1 << 22])
     assert np.array_equal(O.exponent_histogram(host), np.bincount((host.view(np.uint32 if dtype == torch.float32 else np.uint16) >> shift) & 0xFF, minlength=256).astype(np.uint64))
+
+
+def block_shards(n, block, span=1 << 20):
+    """Shards that start on a block boundary: at the start, across element 2^32 and at the ragged end."""
+    per = max(1, span // block)
+    mid = ((1 << 32) // block - per // 2) * block
+    last = max(0, ((n - 1) // block - per + 1)) * block
+    out = [(0, per * block), (mid, mid + per * block), (last, n)]
+    return [(a, min(b, n)) for a, b in out if 0 <= a < n]
+
+
+@pytest.mark.parametrize("block", [64, 11008])
+def test_block_forms_beyond_4g(block):
+    X, Y, W = 3, 3, 7
+    n = (1 << 32) + 11008 * 40 + 8 * 5 + 3
+    x = synth.gaussian_bf16(n, std=0.05, seed=23, device=DEV)
+    x[::4099] *= 37.0  # spread the block maxima over several binades
+    G = (n + 7) // 8
+    meta = exmy.block_max_exp(x, block, X)
+    packed, meta2 = exmy.encode_blocks_auto(x, block, X, Y, 0)
+    packed2 = exmy.encode_blocks(x, block, X, Y, meta)
+    back = exmy.decode_blocks(packed, torch.bfloat16, n, block, X, Y, meta)
+    scale = exmy.block_scale(x, block, X, Y)
+    spacked = exmy.encode_scaled(x, block, X, Y, scale)
+    sback = exmy.decode_scaled(spacked, torch.bfloat16, n, block, X, Y, scale)
+    torch.cuda.synchronize()
+    assert torch.equal(meta, meta2) and torch.equal(packed, packed2)
+    del packed2, meta2
+
+    def plane_slices(p, g0, g1):
+        out, po = [], 0
+        for s in plane_sizes(W):
+            out.append(p[po + g0 * s : po + g1 * s].cpu().numpy())
+            po += G * s
+        return np.concatenate(out)
+
+    for a, b in block_shards(n, block):
+        host = synth.bits_numpy(x[a:b])
+        b0, b1 = a // block, (b + block - 1) // block
+        want_meta = O.block_max_exp(host, block, X)
+        assert np.array_equal(meta[b0:b1].cpu().numpy(), want_meta), (block, a, b)
+        want = O.encode_blocks(host, block, X, Y, want_meta, threads=THREADS)
+        assert np.array_equal(plane_slices(packed, a // 8, (b + 7) // 8), want), (block, a, b)
+        want_dec = O.decode_blocks(want, O.BF16, b - a, block, X, Y, want_meta, threads=THREADS)
+        assert np.array_equal(synth.bits_numpy(back[a:b]), want_dec), (block, a, b)
+        want_scale = O.block_scale(host, block, X, Y)
+        assert np.array_equal(scale[b0:b1].cpu().numpy().view(np.uint32), want_scale.view(np.uint32)), (block, a, b)
+        want_s = O.encode_scaled(host, block, X, Y, want_scale, threads=THREADS)
+        assert np.array_equal(plane_slices(spacked, a // 8, (b + 7) // 8), want_s), (block, a, b)
+        want_sdec = O.decode_scaled(want_s, O.BF16, b - a, block, X, Y, want_scale, threads=THREADS)
+        assert np.array_equal(synth.bits_numpy(sback[a:b]), want_sdec), (block, a, b)
+    # everywhere: emulate == decode(encode) for these finite inputs
+    emu = exmy.emulate_blocks(x.clone(), block, X, Y, meta)
+    torch.cuda.synchronize()
+    assert torch.equal(emu.view(torch.int16), back.view(torch.int16))
+
+
+def test_row_packing_beyond_4g():
+    X, Y, W = 3, 3, 7
+    cols = 4096
+    rows = (1 << 20) + 8 * 3 + 5  # rows * cols > 2^32, ragged last row block
+    x = synth.gaussian_bf16(rows * cols, std=0.05, seed=24, device=DEV).view(rows, cols)
+    meta = exmy.block_max_exp(x.view(-1), cols, X)
+    packed = exmy.encode_rows(x, X, Y, 0, meta)
+    back = exmy.decode_rows(packed, torch.bfloat16, rows, cols, X, Y, 0, meta)
+    torch.cuda.synchronize()
+    R = (rows + 7) // 8
+    # row blocks: the middle shard straddles byte offset 2^32 of the source, the last one element 2^32 and the ragged end
+    for r0, r1 in ((0, 16), ((1 << 16) - 8, (1 << 16) + 8), (R - 16, R)):
+        a, b = 8 * r0, min(rows, 8 * r1)
+        host = synth.bits_numpy(x[a:b])
+        m = meta[a:b].cpu().numpy()
+        want = O.encode_rows(host, b - a, cols, X, Y, 0, m)
+        got, po, wo = [], 0, 0
+        for s in plane_sizes(W):
+            got.append(packed[po + r0 * cols * s : po + r1 * cols * s].cpu().numpy())
+            po += R * cols * s
+        assert np.array_equal(np.concatenate(got), want), (r0, r1)
+        want_dec = O.decode_rows(want, O.BF16, b - a, cols, X, Y, 0, m)
+        assert np.array_equal(synth.bits_numpy(back[a:b]), want_dec), (r0, r1)
+    # everywhere: values equal those of the flat per-block codec with block = one row
+    flat = exmy.decode_blocks(exmy.encode_blocks(x.view(-1), cols, X, Y, meta), torch.bfloat16, rows * cols, cols, X, Y, meta)
+    torch.cuda.synchronize()
+    assert torch.equal(flat.view(torch.int16), back.view(-1).view(torch.int16))
