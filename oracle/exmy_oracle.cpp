@@ -200,6 +200,7 @@ inline uint16_t float_bits_to_half_exact(uint32_t bits) {
   const uint16_t sign = (uint16_t)((bits >> 31) << 15);
   const float a = std::fabs(bits_to_float(bits));
   if (a == 0.0f) return sign;
+  if (std::isinf(a)) return (uint16_t)(sign | 0x7C00);
   int e;
   const float frac = std::frexp(a, &e);  // a = frac * 2^e, frac in [0.5, 1)
   if (e - 1 >= -14) {                    // normal half: 11 significant bits
@@ -489,10 +490,18 @@ int exmy_oracle_max_exp_from_histogram(const uint64_t* hist256, double coverage)
 // The per-block, float-scaling and row-packing forms stop at 16-bit codes.
 static const int kBlockWidth = 16;
 
-static int block_meta_range(int X, int* lo, int* hi) {
+// Y < 0: the caller has no Y (the "before rounding" maximum); the fp16 container then applies
+// only the limits that do not depend on it.
+static int block_meta_range(int dt, int X, int Y, int* lo, int* hi) {
   if (X < 0 || X > 7) return ORACLE_ERR_FORMAT;
   *lo = X == 0 ? 1 : (1 << X);
   *hi = X == 0 ? 253 : 254;
+  if (dt == ORACLE_F16) {  // top binade at most 2^15, quantum at least 2^-24 (see check_format)
+    if (X > 5) return ORACLE_ERR_FORMAT;
+    *hi = 142;
+    if (Y >= 0) *lo = std::max(*lo, X == 0 ? 102 + Y : 101 + Y + (1 << X));
+    if (*lo > *hi) return ORACLE_ERR_FORMAT;
+  }
   return ORACLE_OK;
 }
 
@@ -502,10 +511,10 @@ static int clamp_meta(int m, int lo, int hi) { return m < lo ? lo : (m > hi ? hi
 // finite elements of each block, clamped into the valid range.
 int exmy_oracle_block_max_exp(const void* src, int dt, uint64_t n, uint64_t block, int X, uint8_t* max_exp_out) {
   if ((!src || !max_exp_out) && n) return ORACLE_ERR_NULL;
-  if (dt != ORACLE_F32 && dt != ORACLE_BF16) return ORACLE_ERR_FORMAT;
+  if (dt != ORACLE_F32 && dt != ORACLE_BF16 && dt != ORACLE_F16) return ORACLE_ERR_FORMAT;
   if (block == 0 || block % 8) return ORACLE_ERR_FORMAT;
   int lo, hi;
-  if (int rc = block_meta_range(X, &lo, &hi)) return rc;
+  if (int rc = block_meta_range(dt, X, -1, &lo, &hi)) return rc;
   const uint64_t nb = (n + block - 1) / block;
   for (uint64_t b = 0; b < nb; ++b) {
     int m = 0;
@@ -525,10 +534,9 @@ int exmy_oracle_block_max_exp(const void* src, int dt, uint64_t n, uint64_t bloc
 int exmy_oracle_block_max_exp_after_rounding(const void* src, int dt, uint64_t n, uint64_t block, int X, int Y,
                                              uint8_t* max_exp_out) {
   if ((!src || !max_exp_out) && n) return ORACLE_ERR_NULL;
-  if (dt == ORACLE_F16) return ORACLE_ERR_FORMAT;
   if (block == 0 || block % 8) return ORACLE_ERR_FORMAT;
   int lo, hi;
-  if (int rc = block_meta_range(X, &lo, &hi)) return rc;
+  if (int rc = block_meta_range(dt, X, Y, &lo, &hi)) return rc;
   Format f0;
   if (int rc = check_format(dt, X, Y, hi, false, &f0)) return rc;
   const int bits = X == 0 ? (Y > 0 ? Y - 1 : 0) : Y;  // mantissa bits of the top binade
@@ -556,10 +564,9 @@ int exmy_oracle_block_max_exp_after_rounding(const void* src, int dt, uint64_t n
 static int blocks_op(int what, const void* src, void* dst, int dt, uint64_t n, uint64_t block, int X, int Y,
                      const uint8_t* max_exp, int threads) {
   if (n && (!src || !dst || !max_exp)) return ORACLE_ERR_NULL;
-  if (dt == ORACLE_F16) return ORACLE_ERR_FORMAT;  // per-block forms: fp32 and bf16 containers only
   if (block == 0 || block % 8) return ORACLE_ERR_FORMAT;
   int lo, hi;
-  if (int rc = block_meta_range(X, &lo, &hi)) return rc;
+  if (int rc = block_meta_range(dt, X, Y, &lo, &hi)) return rc;
   Format f0;
   if (int rc = check_format(dt, X, Y, hi, what != 2, &f0)) return rc;
   if (what != 2 && 1 + X + Y > kBlockWidth) return ORACLE_ERR_FORMAT;
@@ -613,7 +620,7 @@ int exmy_oracle_emulate_blocks(void* data, int dt, uint64_t n, uint64_t block, i
 // the max_exp = 127 format, whose top binade is [1, 2).
 
 static int scaled_format(int dt, int X, int Y, bool packed, Format* f) {
-  if (X < 0 || X > 7 || dt == ORACLE_F16) return ORACLE_ERR_FORMAT;
+  if (X < 0 || X > 7) return ORACLE_ERR_FORMAT;
   if (X == 0 && Y == 0) return ORACLE_ERR_FORMAT;  // the only magnitude is 0: nothing to scale
   return check_format(dt, X, Y, 127, packed, f);
 }
@@ -626,6 +633,17 @@ static uint32_t round_to_bf16_bits(float r) {
   const int q = std::max(e - 1, -126) - 7;                 // exponent of the bf16 quantum in this binade
   const double k = std::nearbyint(std::ldexp((double)r, -q));
   return float_to_bits((float)std::ldexp(k, q));           // exact in fp32; 2^128 becomes Inf
+}
+
+// fp32 -> fp16, round to nearest, ties to even (the library conversion), as the fp32 bits of the half's value.
+static uint32_t round_to_half_float_bits(float r) {
+  if (std::isnan(r) || std::isinf(r) || r == 0.0f) return float_to_bits(r);
+  int e;
+  (void)std::frexp((double)r, &e);                         // |r| in [2^(e-1), 2^e)
+  const int q = std::max(e - 1, -14) - 10;                 // exponent of the fp16 quantum in this binade
+  const double v = std::ldexp(std::nearbyint(std::ldexp((double)r, -q)), q);
+  if (std::fabs(v) >= 65536.0) return float_to_bits(std::copysign(INFINITY, r));  // past the largest half (65504)
+  return float_to_bits((float)v);
 }
 
 int exmy_oracle_block_scale(const void* src, int dt, uint64_t n, uint64_t block, int X, int Y, float* scale_out) {
@@ -684,7 +702,7 @@ static int scaled_op(int what, const void* src, void* dst, int dt, uint64_t n, u
         if (what == 2 && (std::isnan(x) || std::isinf(x))) continue;  // preserved
         const float v = (float)code_magnitude(f, code & (uint32_t)((((int64_t)1) << (X + Y)) - 1));
         const float r = v * s;  // fp32 product, one rounding
-        uint32_t out = dt == ORACLE_F32 ? float_to_bits(r) : round_to_bf16_bits(r);
+        uint32_t out = dt == ORACLE_F32 ? float_to_bits(r) : (dt == ORACLE_F16 ? round_to_half_float_bits(r) : round_to_bf16_bits(r));
         out |= ((code >> (X + Y)) & 1u) << 31;
         store_bits(dst, dt, i, out);
       }
@@ -726,11 +744,10 @@ static int rows_op(int what, const void* src, void* dst, int dt, uint64_t rows, 
                    int max_exp, const uint8_t* max_exp_rows) {
   const uint64_t n = rows * cols;
   if (n && (!src || !dst)) return ORACLE_ERR_NULL;
-  if (dt == ORACLE_F16) return ORACLE_ERR_FORMAT;
   Format f0;
   int lo = 0, hi = 0;
   if (max_exp_rows) {
-    if (int rc = block_meta_range(X, &lo, &hi)) return rc;
+    if (int rc = block_meta_range(dt, X, Y, &lo, &hi)) return rc;
     if (int rc = check_format(dt, X, Y, hi, true, &f0)) return rc;
   } else {
     if (int rc = check_format(dt, X, Y, max_exp, true, &f0)) return rc;
@@ -799,8 +816,8 @@ int exmy_oracle_decode_rows(const uint8_t* src_packed, int dt, uint64_t rows, ui
 // is that of e0mY with the same max_exp: 2^(max_exp + 1 - 127 - Y).
 
 static int int_format(int dt, int Y, int max_exp, bool packed, Format* f) {
-  if (dt == ORACLE_F16) return ORACLE_ERR_FORMAT;
   if (int rc = check_format(dt, 0, Y, max_exp, packed, f)) return rc;
+  if (dt == ORACLE_F16 && max_exp > 141) return ORACLE_ERR_MAX_EXP;  // -2^Y quanta = -2^(max_exp - 126) must be a half
   if (packed && 1 + Y > kBlockWidth) return ORACLE_ERR_FORMAT;
   // -2^Y quanta = -2^(max_exp + 1 - 127) must be a value of the container (it always is), and Y >= 1
   // keeps at least one magnitude bit (with Y = 0 the range would be [-1, 0])
@@ -870,7 +887,8 @@ int exmy_oracle_emulate_int(void* data, int dt, uint64_t n, int Y, int max_exp) 
   return ORACLE_OK;
 }
 
-// fp32 -> bf16 rounding used above, exported so that it can be pinned on its own.
+// fp32 -> bf16 / fp16 roundings used above, exported so that they can be pinned on their own.
 uint32_t exmy_oracle_round_to_bf16_bits(float r) { return round_to_bf16_bits(r); }
+uint32_t exmy_oracle_round_to_half_float_bits(float r) { return round_to_half_float_bits(r); }
 
 }  // extern "C"

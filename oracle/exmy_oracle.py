@@ -49,6 +49,8 @@ def lib():
         L.exmy_oracle_emulate_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, i32]
         L.exmy_oracle_round_to_bf16_bits.restype = ctypes.c_uint32
         L.exmy_oracle_round_to_bf16_bits.argtypes = [ctypes.c_float]
+        L.exmy_oracle_round_to_half_float_bits.restype = ctypes.c_uint32
+        L.exmy_oracle_round_to_half_float_bits.argtypes = [ctypes.c_float]
         L.exmy_oracle_packed_bytes_rows.restype = u64
         L.exmy_oracle_packed_bytes_rows.argtypes = [u64, u64, i32, i32]
         L.exmy_oracle_encode_rows.argtypes = [vp, i32, u64, u64, i32, i32, i32, vp, vp]
@@ -262,6 +264,10 @@ def emulate_scaled(src, block, X, Y, scale, threads=1):
     out = a.copy()
     _check(lib().exmy_oracle_emulate_scaled(_ptr(out), dt, out.size, block, X, Y, _ptr(s), threads))
     return out
+
+
+def round_to_half_float_bits(r):
+    return int(lib().exmy_oracle_round_to_half_float_bits(float(r)))
 
 
 def round_to_bf16_bits(r):

@@ -87,10 +87,118 @@ def test_f16_histogram_bins_by_value_exponent():
     assert h[0] == 2 and h[255] == 2 * 1024 and h.sum() == 65536
 
 
-def test_f16_is_rejected_by_the_other_forms():
+def test_half_rounding_is_the_library_conversion():
+    g = torch.Generator().manual_seed(2)
+    bits = torch.randint(0, 2 ** 32, (200000,), generator=g, dtype=torch.int64)
+    extra = [0x477FE000, 0x477FEFFF, 0x477FF000, 0x47800000, 0x33000000, 0x33000001, 0x32FFFFFF, 0x38800000, 0x387FC000,
+             0x387FE000, 0x3F801000, 0x3F803000, 0x3F802FFF, 0x0, 0x80000000, 0x00000001]
+    bits = torch.cat([bits, torch.tensor(extra, dtype=torch.int64)])
+    bits = torch.where(bits >= 2 ** 31, bits - 2 ** 32, bits).to(torch.int32)
+    x = bits.view(torch.float32)
+    x = x[torch.isfinite(x)]
+    want = x.half().float().view(torch.int32)
+    got = torch.tensor([O.round_to_half_float_bits(v) for v in x.tolist()], dtype=torch.int64)
+    got = torch.where(got >= 2 ** 31, got - 2 ** 32, got).to(torch.int32)
+    assert torch.equal(got, want)
+
+
+def block_range(X, Y):
+    lo, hi = f16_range(X, Y)
+    return max(lo, 1 if X == 0 else (1 << X)), hi
+
+
+@pytest.mark.parametrize("X,Y", [(3, 3), (2, 1), (4, 3), (5, 2), (1, 7), (0, 4), (4, 10), (0, 11)])
+def test_block_forms_match_the_fp32_container_on_the_same_values(X, Y):
+    # with metadata inside the fp16 range, codes and values are those of the fp32 container (pinned
+    # elsewhere); metadata outside is read as the nearest value of the (narrower) fp16 range
+    x = synth.shuffled(synth.all_f16_patterns(), 40 + X)
+    x = x[: (x.numel() // 64) * 64]
+    xn = synth.bits_numpy(x)
+    x32 = x.float().numpy()
+    fin = np.isfinite(x32)
+    lo, hi = block_range(X, Y)
+    for block in (32, 64):
+        nb = x.numel() // block
+        before = O.block_max_exp(xn, block, X)
+        assert np.array_equal(before, np.minimum(O.block_max_exp(x32, block, X), 142))
+        after = O.block_max_exp_after_rounding(xn, block, X, Y)
+        assert np.array_equal(after, np.clip(O.block_max_exp_after_rounding(x32, block, X, Y), lo, hi))
+        for meta in (before, after, np.random.default_rng(X + Y).integers(0, 256, nb).astype(np.uint8)):
+            eff = np.clip(meta, lo, hi).astype(np.uint8)
+            p16 = O.encode_blocks(xn, block, X, Y, meta)
+            assert np.array_equal(p16, O.encode_blocks(x32, block, X, Y, eff))
+            d16 = O.decode_blocks(p16, F16, x.numel(), block, X, Y, meta)
+            d32 = O.decode_blocks(p16, F32, x.numel(), block, X, Y, eff)
+            assert np.array_equal(d16.astype(np.float32), d32)
+            e16 = O.emulate_blocks(xn, block, X, Y, meta)
+            assert np.array_equal(e16.view(np.uint16)[fin], d16.view(np.uint16)[fin])
+            assert np.array_equal(e16.view(np.uint16)[~fin], xn.view(np.uint16)[~fin])
+    # packing along rows with per-row metadata: the flat block codec's codes, permuted
+    rows, cols = 40, 64
+    m = O.block_max_exp(xn[: rows * cols], cols, X)
+    pr = O.encode_rows(xn[: rows * cols], rows, cols, X, Y, max_exp_rows=m)
+    assert np.array_equal(pr, O.encode_rows(x32[: rows * cols], rows, cols, X, Y, max_exp_rows=np.clip(m, lo, hi).astype(np.uint8)))
+    dr = O.decode_rows(pr, F16, rows, cols, X, Y, max_exp_rows=m)
+    assert np.array_equal(dr.astype(np.float32), O.decode_rows(pr, F32, rows, cols, X, Y, max_exp_rows=np.clip(m, lo, hi).astype(np.uint8)))
+
+
+@pytest.mark.parametrize("X,Y", [(3, 3), (2, 1), (4, 3), (1, 7), (0, 4), (4, 10)])
+def test_float_scaling_in_fp16_is_the_fp32_result_rounded_by_the_library(X, Y):
+    g = torch.Generator().manual_seed(X * 7 + Y)
+    n, block = 1 << 14, 32
+    x = (torch.randn(n, generator=g) * torch.exp2(torch.randint(-12, 10, (n,), generator=g).float())).half()
+    x[::101] = float("inf")
+    x[5::103] = float("nan")
+    x[64:96] = 65504.0
+    xn = synth.bits_numpy(x)
+    x32 = x.float().numpy()
+    s = O.block_scale(xn, block, X, Y)
+    assert np.array_equal(s.view(np.uint32), O.block_scale(x32, block, X, Y).view(np.uint32))
+    p = O.encode_scaled(xn, block, X, Y, s)
+    assert np.array_equal(p, O.encode_scaled(x32, block, X, Y, s))
+    d32 = torch.from_numpy(O.decode_scaled(p, F32, n, block, X, Y, s))
+    d16 = O.decode_scaled(p, F16, n, block, X, Y, s)
+    assert np.array_equal(d16.view(np.uint16), d32.half().numpy().view(np.uint16))
+    e16 = O.emulate_scaled(xn, block, X, Y, s)
+    fin = np.isfinite(x32)
+    assert np.array_equal(e16.view(np.uint16)[fin], d16.view(np.uint16)[fin])
+    assert np.array_equal(e16.view(np.uint16)[~fin], xn.view(np.uint16)[~fin])
+    # the block maximum is kept (Section 2.1), to an ulp of the container
+    m = torch.where(torch.isfinite(x.float()), x.float().abs(), torch.zeros(())).reshape(-1, block).max(dim=1).values
+    em = torch.where(torch.isfinite(torch.from_numpy(e16.astype(np.float32))), torch.from_numpy(e16.astype(np.float32)).abs(),
+                     torch.zeros(())).reshape(-1, block).max(dim=1).values
+    assert ((em - m).abs() <= m * 2.0 ** -10).all()
+
+
+@pytest.mark.parametrize("Y,max_exp", [(3, 129), (7, 133), (8, 127), (10, 141), (4, 110)])
+def test_twos_complement_in_fp16(Y, max_exp):
+    x = synth.all_f16_patterns()
+    xn = synth.bits_numpy(x)
+    x32 = x.float().numpy()
+    fin = np.isfinite(x32)
+    c16 = O.to_codes_int(xn, Y, max_exp)
+    assert np.array_equal(c16, O.to_codes_int(x32, Y, max_exp))
+    d16 = O.from_codes_int(c16, F16, Y, max_exp)
+    assert np.array_equal(d16.astype(np.float32), O.from_codes_int(c16, F32, Y, max_exp))
+    e16 = O.emulate_int(xn, Y, max_exp)
+    assert np.array_equal(e16.view(np.uint16)[fin], d16.view(np.uint16)[fin])
+    assert np.array_equal(e16.view(np.uint16)[~fin], xn.view(np.uint16)[~fin])
+    assert np.array_equal(O.decode_int(O.encode_int(xn, Y, max_exp), F16, xn.size, Y, max_exp).view(np.uint16), d16.view(np.uint16))
+
+
+def test_fp16_limits_of_the_other_forms():
     x = np.zeros(64, dtype=np.float16)
     m = np.full(8, 130, dtype=np.uint8)
-    for fn in (lambda: O.block_max_exp_after_rounding(x, 8, 3, 3), lambda: O.encode_blocks(x, 8, 3, 3, m),
-               lambda: O.block_scale(x, 8, 3, 3), lambda: O.encode_rows(x, 8, 8, 3, 3, 130), lambda: O.encode_int(x, 3, 130)):
-        with pytest.raises(Exception):
-            fn()
+    with pytest.raises(Exception):
+        O.encode_blocks(x, 8, 5, 10, m)   # no max_exp keeps e5m10 inside fp16
+    with pytest.raises(Exception):
+        O.encode_blocks(x, 8, 6, 2, m)    # X <= 5
+    with pytest.raises(Exception):
+        O.block_scale(x, 8, 5, 2)         # max_exp = 127 is below e5m2's fp16 range
+    O.block_scale(x, 8, 4, 10)
+    with pytest.raises(Exception):
+        O.encode_int(x, 7, 142)           # -2^16 is not a half
+    O.encode_int(x, 7, 141)
+    with pytest.raises(Exception):
+        O.encode_int(x, 7, 108)           # quantum 2^-25
+    O.encode_int(x, 7, 109)
