@@ -23,13 +23,14 @@
  *    max_exp = 255 exactly for X = 8 (identity exponent map).
  *  - A format fits a container when X <= 8 and Y <= 7 (bf16) / 23 (fp32), or
  *    X <= 5 and Y <= 10 (fp16) (Section 2.1); with X = 0 one more mantissa bit
- *    is allowed.  With the fp16 container (EXMY_F16: exmy_encode / exmy_decode,
- *    their batch and histogram forms, exmy_emulate and
- *    exmy_exponent_histogram only; EXMY_ERR_FORMAT elsewhere) max_exp must also
- *    keep the format's top binade and its quantum inside fp16:
- *    max_exp <= 142 and max_exp - 2^X + 2 - 127 - Y >= -24 (EXMY_ERR_MAX_EXP),
- *    so that every decoded value is an fp16 value; the exponent histogram of
- *    fp16 data bins the exponent of the value as an fp32.  Packed codes
+ *    is allowed.  With the fp16 container (EXMY_F16) max_exp must also keep the
+ *    format's top binade and its quantum inside fp16: max_exp <= 142 and
+ *    max_exp - 2^X + 2 - 127 - Y >= -24 (EXMY_ERR_MAX_EXP), so that every
+ *    decoded value is an fp16 value (e5m10 therefore has no valid max_exp, and
+ *    float scaling, whose formats sit at max_exp = 127, needs Y + 2^X <= 26);
+ *    per-block metadata bytes are read as the nearest value of that narrower
+ *    range; the exponent histogram of fp16 data bins the exponent of the value
+ *    as an fp32.  Packed codes
  *    are limited to W <= 31 (segments of 16, 8, 4, 2 and 1 bits; widths above
  *    16 need the fp32 container) in exmy_encode / exmy_decode and their batch
  *    and histogram forms, and to W <= 16 in the per-block, float-scaling and
@@ -193,7 +194,8 @@ exmy_status_t exmy_emulate_blocks(void* data_inout, exmy_dtype_t dt, uint64_t n,
                                   const uint8_t* max_exp_dev, void* stream);
 
 /* The pipeline of Section 2.2.1 in one call: the metadata of `scheme` is
- * computed from src into max_exp_dev (an OUTPUT here, one byte per block) and
+ * computed from src into max_exp_dev (an OUTPUT here, one byte per block; the
+ * bytes are already inside the range valid for (X, Y) and the container) and
  * src is encoded with it.  Blocks of 8, 16, ..., 512 elements and blocks of 520
  * to 32768 (bf16) / 16384 (fp32) elements take one launch that reads src once
  * (the block stays in registers between the two steps); other sizes take two
@@ -271,8 +273,9 @@ exmy_status_t exmy_decode_rows(const void* src_packed, exmy_dtype_t dt_out, uint
  * values that round to 0 give k = 0.  decode: k * quantum (k = 0 is +0).
  * emulate: decode(encode(x)), Inf / NaN left bit-identical.  Packed layout as
  * for exmy_encode with W = 1 + Y.
- * 1 <= Y <= 8 (bf16) / 21 (fp32), 1 + Y <= 16 for the packed form;
- * 0 <= max_exp <= min(253, 230 + Y) (EXMY_ERR_MAX_EXP).  Pointers, alignment,
+ * 1 <= Y <= 8 (bf16) / 11 (fp16) / 21 (fp32), 1 + Y <= 16 for the packed form;
+ * 0 <= max_exp <= min(253, 230 + Y), and 102 + Y <= max_exp <= 141 inside fp16
+ * (EXMY_ERR_MAX_EXP).  Pointers, alignment,
  * n = 0, streams and errors as for exmy_encode. */
 exmy_status_t exmy_encode_int(const void* src, exmy_dtype_t dt, uint64_t n, int Y, int max_exp, void* dst_packed,
                               void* stream);

@@ -110,16 +110,23 @@ exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, int max_wi
   return EXMY_OK;
 }
 
-exmy_status_t make_block_format(exmy_dtype_t dt, int X, int Y, int max_width, bool after_rounding, FormatConsts* fc,
-                                BlockConsts* bc) {
+exmy_status_t make_block_format(exmy_dtype_t dt, int X, int Y, int max_width, bool after_rounding, bool y_known,
+                                FormatConsts* fc, BlockConsts* bc) {
   if (X == 8) return EXMY_ERR_FORMAT;  // identity exponent map: nothing for a block to choose
-  if (dt == EXMY_F16) return EXMY_ERR_FORMAT;  // the per-block forms take fp32 and bf16 only
-  const int hi = X == 0 ? 253 : 254;
+  // valid metadata: [2^X, 254] ([1, 253] for X = 0); inside fp16 also the container's limits on the top binade
+  // (at most 2^15) and, where the caller knows Y, on the quantum (at least 2^-24)
+  int lo = X == 0 ? 1 : (1 << X);
+  int hi = X == 0 ? 253 : 254;
+  if (dt == EXMY_F16) {
+    hi = 142;
+    if (y_known) lo = std::max(lo, X == 0 ? 102 + Y : 101 + Y + (1 << X));
+    if (X <= 5 && lo > hi) return EXMY_ERR_FORMAT;  // no metadatum keeps this format inside fp16
+  }
   if (exmy_status_t st = make_format(dt, X, Y, hi, max_width, fc, nullptr, nullptr)) return st;
   if (bc) {
     const int W = 1 + X + Y;
     const int L = ((W & 1) ? 32 : 31) - (X + Y);
-    bc->meta_lo = X == 0 ? 1u : (1u << X);
+    bc->meta_lo = (uint32_t)lo;
     bc->meta_hi = (uint32_t)hi;
     bc->emin_off = (1u << X) - 2u;  // X = 0: 2^0 - 2 = -1, i.e. emin8 = max_exp + 1 (wraps as intended)
     // largest value: exponent field max_exp; mantissa all ones with X >= 1; with X = 0 it is
@@ -147,8 +154,8 @@ exmy_status_t make_block_format(exmy_dtype_t dt, int X, int Y, int max_width, bo
 }
 
 exmy_status_t make_int_format(exmy_dtype_t dt, int Y, int max_exp, bool packed, IntConsts* ic) {
-  if (dt != EXMY_F32 && dt != EXMY_BF16) return EXMY_ERR_FORMAT;
-  const int P = dt == EXMY_F32 ? 23 : 7;
+  if (dt != EXMY_F32 && dt != EXMY_BF16 && dt != EXMY_F16) return EXMY_ERR_FORMAT;
+  const int P = dt == EXMY_F32 ? 23 : (dt == EXMY_F16 ? 10 : 7);
   // at least one magnitude bit; the container's significand holds Y + 1 bits (as for e0mY); the packed
   // form stops at 16 bits; the single fp32 rounding addend needs Y <= 21
   if (Y < 1 || Y > P + 1 || Y > 21 || (packed && 1 + Y > kBlockWidth)) return EXMY_ERR_FORMAT;
@@ -156,6 +163,8 @@ exmy_status_t make_int_format(exmy_dtype_t dt, int Y, int max_exp, bool packed, 
   if (Y == P + 1 && max_exp < 1) return EXMY_ERR_MAX_EXP;  // the quantum must be a value of the container
   const int emin8 = max_exp + 1;
   if (emin8 + 23 - Y > 254) return EXMY_ERR_MAX_EXP;  // the rounding addend must be a finite float
+  // inside fp16 the quantum must be at least 2^-24 and -2^Y quanta = -2^(max_exp - 126) at most 2^15 in magnitude
+  if (dt == EXMY_F16 && (max_exp > 141 || emin8 - 127 - Y < -24)) return EXMY_ERR_MAX_EXP;
   if (ic) {
     ic->sat_pos_bits = float_bits(ldexpf((float)((1u << Y) - 1u), emin8 - 127 - Y));
     ic->neg_extra = float_bits(ldexpf(1.0f, emin8 - 127)) - ic->sat_pos_bits;
@@ -237,7 +246,8 @@ exmy_status_t run_batch(Op op, const exmy_tensor_t* tensors, size_t count, exmy_
   return flush() == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
 }
 
-enum class BlockOp { kMaxExp, kMaxExpRounded, kScale, kEncode, kDecode, kEmulate, kAutoEncode, kAutoEncodeRounded };
+// kMaxExpOfFormat: the "before rounding" maximum brought into the range valid for (X, Y), not only for X
+enum class BlockOp { kMaxExp, kMaxExpOfFormat, kMaxExpRounded, kScale, kEncode, kDecode, kEmulate, kAutoEncode, kAutoEncodeRounded };
 
 // Shared validation and launch of the per-block entry points.  `elems` is the
 // bf16 / fp32 side, `packed` the plane side (encode and decode only); `side` is
@@ -248,7 +258,8 @@ exmy_status_t run_blocks(BlockOp op, bool scaled, const void* elems, const void*
   const bool is_auto = op == BlockOp::kAutoEncode || op == BlockOp::kAutoEncodeRounded;
   const bool is_packed = op == BlockOp::kEncode || op == BlockOp::kDecode || is_auto;
   const bool rounded = op == BlockOp::kMaxExpRounded || op == BlockOp::kAutoEncodeRounded;
-  if (exmy_status_t st = make_block_format(dt, X, Y, is_packed ? kBlockWidth : kAnyWidth, rounded, &args.fc, &args.bc))
+  if (exmy_status_t st = make_block_format(dt, X, Y, is_packed ? kBlockWidth : kAnyWidth, rounded,
+                                           op != BlockOp::kMaxExp, &args.fc, &args.bc))
     return st;
   bool wide_format = Y > 21;
   args.vmax127 = 0.0f;
@@ -277,6 +288,7 @@ exmy_status_t run_blocks(BlockOp op, bool scaled, const void* elems, const void*
   hipError_t e = hipSuccess;
   switch (op) {
     case BlockOp::kMaxExp:
+    case BlockOp::kMaxExpOfFormat:
     case BlockOp::kMaxExpRounded:
     case BlockOp::kScale:
       args.src = elems;
@@ -315,9 +327,8 @@ exmy_status_t run_rows(RowsOp op, const void* matrix, const void* packed, exmy_d
                        int X, int Y, int max_exp, const uint8_t* max_exp_rows, void* stream) {
   RowsArgs args;
   bool wide = false;
-  if (dt == EXMY_F16) return EXMY_ERR_FORMAT;  // fp32 and bf16 only
   if (max_exp_rows) {
-    if (exmy_status_t st = make_block_format(dt, X, Y, kBlockWidth, false, &args.fc, &args.bc)) return st;
+    if (exmy_status_t st = make_block_format(dt, X, Y, kBlockWidth, false, true, &args.fc, &args.bc)) return st;
     memset(&args.tc, 0, sizeof(args.tc));
   } else {
     if (exmy_status_t st = make_format(dt, X, Y, max_exp, kBlockWidth, &args.fc, &args.tc, &wide)) return st;
@@ -425,14 +436,14 @@ exmy_status_t exmy_encode_blocks_auto(const void* src, exmy_dtype_t dt, uint64_t
                                       exmy_scheme_t scheme, uint8_t* max_exp_dev, void* dst_packed, void* stream) {
   if (scheme != EXMY_MAX_EXP_BEFORE_ROUNDING && scheme != EXMY_MAX_EXP_AFTER_ROUNDING) return EXMY_ERR_FORMAT;
   // validate the second launch before the first, so that an error leaves both outputs untouched
-  if (exmy_status_t st = make_block_format(dt, X, Y, kBlockWidth, false, nullptr, nullptr)) return st;
+  if (exmy_status_t st = make_block_format(dt, X, Y, kBlockWidth, false, true, nullptr, nullptr)) return st;
   if (n && !dst_packed) return EXMY_ERR_NULL;
   if (n && !aligned16(dst_packed)) return EXMY_ERR_ALIGN;
   const bool rounded = scheme == EXMY_MAX_EXP_AFTER_ROUNDING;
   if (block >= 8 && block % 8 == 0 && block <= EXMY_MAX_BLOCK && encode_blocks_auto_fits(dt, (uint32_t)(block / 8)))
     return run_blocks(rounded ? BlockOp::kAutoEncodeRounded : BlockOp::kAutoEncode, false, src, dst_packed, dt, n, block, X,
                       Y, max_exp_dev, stream);  // one pass: the block stays in registers
-  const BlockOp op = rounded ? BlockOp::kMaxExpRounded : BlockOp::kMaxExp;
+  const BlockOp op = rounded ? BlockOp::kMaxExpRounded : BlockOp::kMaxExpOfFormat;
   if (exmy_status_t st = run_blocks(op, false, src, nullptr, dt, n, block, X, Y, max_exp_dev, stream)) return st;
   return run_blocks(BlockOp::kEncode, false, src, dst_packed, dt, n, block, X, Y, max_exp_dev, stream);
 }

@@ -171,9 +171,10 @@ exmy_status_t make_format(exmy_dtype_t dt, int X, int Y, int max_exp, int max_wi
 exmy_status_t make_int_format(exmy_dtype_t dt, int Y, int max_exp, bool packed, IntConsts* ic);
 
 // Host: validate (dtype, X, Y) for per-block metadata and fill fc / bc.
-// after_rounding selects the scheme of the maximum-exponent kernel.
-exmy_status_t make_block_format(exmy_dtype_t dt, int X, int Y, int max_width, bool after_rounding, FormatConsts* fc,
-                                BlockConsts* bc);
+// after_rounding selects the scheme of the maximum-exponent kernel; y_known is false for the "before
+// rounding" maximum, whose entry point has no Y (matters for the fp16 container's metadata range only).
+exmy_status_t make_block_format(exmy_dtype_t dt, int X, int Y, int max_width, bool after_rounding, bool y_known,
+                                FormatConsts* fc, BlockConsts* bc);
 
 #if defined(__HIPCC__)
 
@@ -389,12 +390,20 @@ __device__ __forceinline__ uint16_t to_elem(uint32_t bits) {
   if constexpr (kIsF16<T>) return __builtin_bit_cast(uint16_t, (_Float16)as_f32(bits));
   return (uint16_t)(bits >> 16);
 }
-template <typename T>
+// kExact: the values are known to be values of T (any rounding mode converts them exactly); otherwise an
+// fp16 pair is rounded to nearest even here, and a bf16 pair must have been rounded by the caller.
+template <typename T, bool kExact = true>
 __device__ __forceinline__ uint32_t pack_elems(uint32_t lo_bits, uint32_t hi_bits) {
-  if constexpr (kIsF16<T>)  // the values are fp16 values: any rounding mode converts them exactly
-    return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(as_f32(lo_bits), as_f32(hi_bits)));
+  if constexpr (kIsF16<T>) {
+    if constexpr (kExact) return __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(as_f32(lo_bits), as_f32(hi_bits)));
+    return (uint32_t)to_elem<T>(lo_bits) | ((uint32_t)to_elem<T>(hi_bits) << 16);
+  }
   return __builtin_amdgcn_perm(hi_bits, lo_bits, 0x07060302u);
 }
+
+// Of a pair of halves w, the original 16 bits where the half is Inf / NaN (a half's NaN payload would
+// not survive the round trip through fp32 unchanged); elsewhere the pair `emulated`.
+__device__ __forceinline__ uint32_t keep_nonfinite_halves(uint32_t w, uint32_t emulated);
 
 // (mask & a) | (~mask & b) in one instruction.
 __device__ __forceinline__ uint32_t bit_select(uint32_t mask, uint32_t a, uint32_t b) {
@@ -410,13 +419,20 @@ __device__ __forceinline__ uint32_t scaled_bits(uint32_t u, float inv) {
 }
 
 // Float scaling, decode side: bits of |v| * scale (v finite, scale > 0) under the
-// sign of v.  kBf16: rounded to nearest even at bit 16, the lower half then to be
-// dropped (a carry may run up to the Inf pattern, as in the library conversion).
-template <bool kBf16>
+// sign of v.  For bf16 the result is rounded to nearest even at bit 16 here, the
+// lower half then to be dropped (a carry may run up to the Inf pattern, as in the
+// library conversion); fp16 results are rounded when they are converted.
+template <typename T>
 __device__ __forceinline__ uint32_t rescaled_bits(uint32_t v, float scale) {
   uint32_t m = as_u32(__builtin_fabsf(as_f32(v)) * scale);
-  if constexpr (kBf16) m += 0x7FFFu + ((m >> 16) & 1u);
+  if constexpr (sizeof(T) == 2 && !kIsF16<T>) m += 0x7FFFu + ((m >> 16) & 1u);
   return bit_select(0x7FFFFFFFu, m, v);
+}
+
+__device__ __forceinline__ uint32_t keep_nonfinite_halves(uint32_t w, uint32_t emulated) {
+  const uint32_t lo = (w & 0x00007C00u) == 0x00007C00u ? 0x0000FFFFu : 0u;
+  const uint32_t hi = (w & 0x7C000000u) == 0x7C000000u ? 0xFFFF0000u : 0u;
+  return bit_select(lo | hi, w, emulated);
 }
 
 // ---------------------------------------------------------------- planes

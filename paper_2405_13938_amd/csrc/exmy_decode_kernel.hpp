@@ -112,17 +112,17 @@ __device__ __forceinline__ void decode_unit(const UnitWords<W>& uw, const Format
 #pragma unroll
   for (int j = 0; j < E; ++j) {
     b[j] = element_bits<W, kX8>(uw, j, fc, tc);
-    if constexpr (kScaled) b[j] = rescaled_bits<sizeof(T) == 2>(b[j], scale);
+    if constexpr (kScaled) b[j] = rescaled_bits<T>(b[j], scale);
   }
   if constexpr (sizeof(T) == 4) {
     store16<kNT>(out, lane_unit * 16, tile_unit * 16, make_uint4(b[0], b[1], b[2], b[3]));
   } else {
     // every value is exact in bf16 (or has just been rounded to it): keep the upper halves
     uint4 o;
-    o.x = pack_elems<T>(b[0], b[1]);
-    o.y = pack_elems<T>(b[2], b[3]);
-    o.z = pack_elems<T>(b[4], b[5]);
-    o.w = pack_elems<T>(b[6], b[7]);
+    o.x = pack_elems<T, !kScaled>(b[0], b[1]);
+    o.y = pack_elems<T, !kScaled>(b[2], b[3]);
+    o.z = pack_elems<T, !kScaled>(b[4], b[5]);
+    o.w = pack_elems<T, !kScaled>(b[6], b[7]);
     store16<kNT>(out, lane_unit * 16, tile_unit * 16, o);
   }
 }
@@ -301,14 +301,14 @@ __global__ __launch_bounds__(kBlock) void decode_blocks_kernel(const BlockArgs a
       uint32_t b;
       if constexpr (kScaled) {
         b = element_bits_slow<W, false>(src, G, i, fc, args.tc127);
-        b = rescaled_bits<sizeof(T) == 2>(b, args.scale[args.n_blocks - 1]);
+        b = rescaled_bits<T>(b, args.scale[args.n_blocks - 1]);
       } else {
         b = element_bits_slow<W, false>(src, G, i, fc, derive_tc(meta[args.n_blocks - 1], bc));
       }
       if constexpr (sizeof(T) == 4)
         reinterpret_cast<uint32_t*>(dst)[i] = b;
       else
-        reinterpret_cast<uint16_t*>(dst)[i] = (uint16_t)(b >> 16);
+        reinterpret_cast<uint16_t*>(dst)[i] = to_elem<T>(b);
     }
   }
 }

@@ -40,6 +40,7 @@ hipError_t dispatch_w(int W, const RowsArgs& args, bool per_row, bool x8, hipStr
 
 hipError_t decode_rows_dispatch(exmy_dtype_t dt, int W, const RowsArgs& args, bool per_row, bool x8,
                                 hipStream_t stream) {
+  if (dt == EXMY_F16) return dispatch_w<f16_t>(W, args, per_row, x8, stream);
   return dt == EXMY_F32 ? dispatch_w<float>(W, args, per_row, x8, stream)
                         : dispatch_w<uint16_t>(W, args, per_row, x8, stream);
 }

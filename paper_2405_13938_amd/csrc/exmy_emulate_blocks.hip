@@ -54,6 +54,9 @@ hipError_t launch_max_exp(BlockArgs args, hipStream_t stream) {
 
 hipError_t emulate_blocks_dispatch(exmy_dtype_t dt, const BlockArgs& args, bool wide_format, bool scaled,
                                    hipStream_t stream) {
+  if (dt == EXMY_F16)
+    return scaled ? launch_emulate<f16_t, true>(args, wide_format, stream)
+                  : launch_emulate<f16_t, false>(args, wide_format, stream);
   if (scaled)
     return dt == EXMY_F32 ? launch_emulate<float, true>(args, wide_format, stream)
                           : launch_emulate<uint16_t, true>(args, wide_format, stream);
@@ -62,6 +65,7 @@ hipError_t emulate_blocks_dispatch(exmy_dtype_t dt, const BlockArgs& args, bool 
 }
 
 hipError_t block_max_exp_dispatch(exmy_dtype_t dt, const BlockArgs& args, bool scale, hipStream_t stream) {
+  if (dt == EXMY_F16) return scale ? launch_max_exp<f16_t, true>(args, stream) : launch_max_exp<f16_t, false>(args, stream);
   if (scale)
     return dt == EXMY_F32 ? launch_max_exp<float, true>(args, stream) : launch_max_exp<uint16_t, true>(args, stream);
   return dt == EXMY_F32 ? launch_max_exp<float, false>(args, stream) : launch_max_exp<uint16_t, false>(args, stream);

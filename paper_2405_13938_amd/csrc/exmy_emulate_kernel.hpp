@@ -41,14 +41,6 @@ __device__ __forceinline__ uint32_t emulate_bits(uint32_t u, const FormatConsts&
   return a0 >= 0x7F800000u ? u : r;  // Inf / NaN pass through
 }
 
-// Where an element of the pair in w is Inf / NaN, the original 16 bits (a half's NaN payload would not
-// survive the round trip through fp32 unchanged); elsewhere the emulated pair.
-__device__ __forceinline__ uint32_t keep_nonfinite_halves(uint32_t w, uint32_t emulated) {
-  const uint32_t lo = (w & 0x00007C00u) == 0x00007C00u ? 0x0000FFFFu : 0u;
-  const uint32_t hi = (w & 0x7C000000u) == 0x7C000000u ? 0xFFFF0000u : 0u;
-  return bit_select(lo | hi, w, emulated);
-}
-
 template <typename T, bool kWide>
 __device__ __forceinline__ uint4 emulate_vector(uint4 v, const FormatConsts& fc, const TensorConsts& tc) {
   uint32_t w[4] = {v.x, v.y, v.z, v.w};
@@ -128,12 +120,30 @@ __device__ __forceinline__ uint4 emulate_vector_meta(uint4 v, uint32_t me, bool 
 // Float scaling: the element is multiplied by the reciprocal of its block's scale,
 // rounded in the max_exp = 127 format and multiplied back; the result is rounded
 // to the container (bf16: to nearest even).  Inf / NaN pass through.
-template <bool kWide, bool kBf16>
+template <bool kWide, typename T>
 __device__ __forceinline__ uint32_t emulate_scaled_bits(uint32_t u, float inv, float scale, const FormatConsts& fc,
                                                         const TensorConsts& tc127) {
   const uint32_t a0 = as_u32(__builtin_fabsf(as_f32(u)) * inv);  // an overflow to Inf saturates like any large value
   const uint32_t r = emulate_magnitude<kWide>(a0, fc, tc127) | (u & 0x80000000u);
-  return (u & 0x7FFFFFFFu) >= 0x7F800000u ? u : rescaled_bits<kBf16>(r, scale);
+  return (u & 0x7FFFFFFFu) >= 0x7F800000u ? u : rescaled_bits<T>(r, scale);
+}
+
+template <typename T, bool kWide>
+__device__ __forceinline__ uint4 emulate_vector_scaled_as(uint4 v, float scale, float inv, const FormatConsts& fc,
+                                                          const TensorConsts& tc127) {
+  uint32_t w[4] = {v.x, v.y, v.z, v.w};
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    if constexpr (sizeof(T) == 4) {
+      w[k] = emulate_scaled_bits<kWide, T>(w[k], inv, scale, fc, tc127);
+    } else {
+      const uint32_t lo = emulate_scaled_bits<kWide, T>(lo_elem_bits<T>(w[k]), inv, scale, fc, tc127);
+      const uint32_t hi = emulate_scaled_bits<kWide, T>(hi_elem_bits<T>(w[k]), inv, scale, fc, tc127);
+      const uint32_t pair = pack_elems<T, false>(lo, hi);
+      w[k] = kIsF16<T> ? keep_nonfinite_halves(w[k], pair) : pair;
+    }
+  }
+  return make_uint4(w[0], w[1], w[2], w[3]);
 }
 
 template <typename T>
@@ -141,31 +151,8 @@ __device__ __forceinline__ uint4 emulate_vector_scaled(uint4 v, uint32_t scale_b
                                                        const FormatConsts& fc, const TensorConsts& tc127) {
   const float scale = as_f32(scale_bits);
   const float inv = 1.0f / scale;
-  uint32_t w[4] = {v.x, v.y, v.z, v.w};
-  if (wide_format) {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      if constexpr (sizeof(T) == 4) {
-        w[k] = emulate_scaled_bits<true, false>(w[k], inv, scale, fc, tc127);
-      } else {
-        const uint32_t lo = emulate_scaled_bits<true, true>(w[k] << 16, inv, scale, fc, tc127);
-        const uint32_t hi = emulate_scaled_bits<true, true>(w[k] & 0xFFFF0000u, inv, scale, fc, tc127);
-        w[k] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
-      }
-    }
-  } else {
-#pragma unroll
-    for (int k = 0; k < 4; ++k) {
-      if constexpr (sizeof(T) == 4) {
-        w[k] = emulate_scaled_bits<false, false>(w[k], inv, scale, fc, tc127);
-      } else {
-        const uint32_t lo = emulate_scaled_bits<false, true>(w[k] << 16, inv, scale, fc, tc127);
-        const uint32_t hi = emulate_scaled_bits<false, true>(w[k] & 0xFFFF0000u, inv, scale, fc, tc127);
-        w[k] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
-      }
-    }
-  }
-  return make_uint4(w[0], w[1], w[2], w[3]);
+  if (wide_format) return emulate_vector_scaled_as<T, true>(v, scale, inv, fc, tc127);
+  return emulate_vector_scaled_as<T, false>(v, scale, inv, fc, tc127);
 }
 
 // wide_format: the format itself needs the fp64 path (Y > 21), whatever the metadata.
@@ -222,23 +209,25 @@ __global__ __launch_bounds__(kBlock) void emulate_blocks_kernel(const BlockArgs 
       if constexpr (sizeof(T) == 4)
         u = reinterpret_cast<uint32_t*>(data)[i];
       else
-        u = (uint32_t) reinterpret_cast<uint16_t*>(data)[i] << 16;
+        u = elem_bits<T>(reinterpret_cast<uint16_t*>(data)[i]);
       uint32_t r;
       if constexpr (kScaled) {
         const float scale = args.scale[args.n_blocks - 1];
         const float inv = 1.0f / scale;
-        r = wide_format ? emulate_scaled_bits<true, sizeof(T) == 2>(u, inv, scale, fc, args.tc127)
-                        : emulate_scaled_bits<false, sizeof(T) == 2>(u, inv, scale, fc, args.tc127);
+        r = wide_format ? emulate_scaled_bits<true, T>(u, inv, scale, fc, args.tc127)
+                        : emulate_scaled_bits<false, T>(u, inv, scale, fc, args.tc127);
       } else {
         const uint32_t me = meta[args.n_blocks - 1];
         const TensorConsts tc = derive_tc(me, bc);
         const bool wide = __builtin_amdgcn_ballot_w64(wide_format || me > bc.wide_above) != 0;
         r = wide ? emulate_bits<true>(u, fc, tc) : emulate_bits<false>(u, fc, tc);
       }
-      if constexpr (sizeof(T) == 4)
-        reinterpret_cast<uint32_t*>(data)[i] = r;
-      else
-        reinterpret_cast<uint16_t*>(data)[i] = (uint16_t)(r >> 16);
+      if ((u & 0x7FFFFFFFu) < 0x7F800000u) {  // Inf / NaN stay as they are
+        if constexpr (sizeof(T) == 4)
+          reinterpret_cast<uint32_t*>(data)[i] = r;
+        else
+          reinterpret_cast<uint16_t*>(data)[i] = to_elem<T>(r);
+      }
     }
   }
 }
@@ -259,8 +248,8 @@ __device__ __forceinline__ int32_t vector_exp_key(V4 v) {
     if constexpr (sizeof(T) == 4) {
       m = max(m, exp_key(w[k]));
     } else {
-      m = max(m, exp_key(w[k] << 16));
-      m = max(m, exp_key(w[k] & 0xFFFF0000u));
+      m = max(m, exp_key(lo_elem_bits<T>(w[k])));
+      m = max(m, exp_key(hi_elem_bits<T>(w[k])));
     }
   }
   return m;
@@ -272,7 +261,7 @@ __device__ __forceinline__ int32_t element_exp_key(const T* p) {
   if constexpr (sizeof(T) == 4)
     u = *reinterpret_cast<const uint32_t*>(p);
   else
-    u = (uint32_t)*reinterpret_cast<const uint16_t*>(p) << 16;
+    u = elem_bits<T>(*reinterpret_cast<const uint16_t*>(p));
   return exp_key(u);
 }
 

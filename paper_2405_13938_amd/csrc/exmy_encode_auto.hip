@@ -14,6 +14,8 @@ struct Small<uint16_t> {
   static constexpr int kBlock = 64, kUnroll = 2;
 };
 template <>
+struct Small<f16_t> : Small<uint16_t> {};
+template <>
 struct Small<float> {
   static constexpr int kBlock = 128, kUnroll = 1;
 };
@@ -81,6 +83,7 @@ bool encode_blocks_auto_fits(exmy_dtype_t dt, uint32_t block_groups) {
 }
 
 hipError_t encode_blocks_auto_dispatch(exmy_dtype_t dt, int W, const BlockArgs& args, hipStream_t stream) {
+  if (dt == EXMY_F16) return dispatch_w<f16_t>(W, args, stream);
   return dt == EXMY_F32 ? dispatch_w<float>(W, args, stream) : dispatch_w<uint16_t>(W, args, stream);
 }
 

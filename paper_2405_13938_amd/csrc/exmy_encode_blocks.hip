@@ -15,6 +15,8 @@ struct Shape<uint16_t> {
   static constexpr int kUnroll = 2;
 };
 template <>
+struct Shape<f16_t> : Shape<uint16_t> {};
+template <>
 struct Shape<float> {
   static constexpr int kBlock = 128;
   static constexpr int kUnroll = 1;
@@ -47,6 +49,7 @@ hipError_t dispatch_w(int W, const BlockArgs& args, hipStream_t stream) {
 }  // namespace
 
 hipError_t encode_blocks_dispatch(exmy_dtype_t dt, int W, const BlockArgs& args, bool scaled, hipStream_t stream) {
+  if (dt == EXMY_F16) return scaled ? dispatch_w<f16_t, true>(W, args, stream) : dispatch_w<f16_t, false>(W, args, stream);
   if (scaled)
     return dt == EXMY_F32 ? dispatch_w<float, true>(W, args, stream) : dispatch_w<uint16_t, true>(W, args, stream);
   return dt == EXMY_F32 ? dispatch_w<float, false>(W, args, stream) : dispatch_w<uint16_t, false>(W, args, stream);

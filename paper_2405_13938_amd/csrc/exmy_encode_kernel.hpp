@@ -391,7 +391,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
         if constexpr (sizeof(T) == 4)
           u[j] = reinterpret_cast<const uint32_t*>(src)[i];
         else
-          u[j] = (uint32_t) reinterpret_cast<const uint16_t*>(src)[i] << 16;
+          u[j] = elem_bits<T>(reinterpret_cast<const uint16_t*>(src)[i]);
       }
     }
     PlaneDst<W> pd;

@@ -40,6 +40,7 @@ hipError_t dispatch_w(int W, const RowsArgs& args, bool per_row, bool wide, hipS
 
 hipError_t encode_rows_dispatch(exmy_dtype_t dt, int W, const RowsArgs& args, bool per_row, bool wide,
                                 hipStream_t stream) {
+  if (dt == EXMY_F16) return dispatch_w<f16_t>(W, args, per_row, wide, stream);
   return dt == EXMY_F32 ? dispatch_w<float>(W, args, per_row, wide, stream)
                         : dispatch_w<uint16_t>(W, args, per_row, wide, stream);
 }

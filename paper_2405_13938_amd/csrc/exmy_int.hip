@@ -14,6 +14,8 @@ struct Shape<uint16_t> {
   static constexpr int kEncBlock = 64, kEncUnroll = 2, kDecBlock = 128, kDecUnroll = 2;
 };
 template <>
+struct Shape<f16_t> : Shape<uint16_t> {};
+template <>
 struct Shape<float> {
   static constexpr int kEncBlock = 128, kEncUnroll = 1, kDecBlock = 256, kDecUnroll = 2;
 };
@@ -64,17 +66,20 @@ hipError_t launch_emulate(void* data, uint64_t n, const IntConsts& ic, hipStream
 
 hipError_t encode_int_dispatch(exmy_dtype_t dt, int W, const void* src, void* dst, uint64_t n, const IntConsts& ic,
                                hipStream_t stream) {
+  if (dt == EXMY_F16) return dispatch_w<f16_t, true>(W, src, dst, n, ic, stream);
   return dt == EXMY_F32 ? dispatch_w<float, true>(W, src, dst, n, ic, stream)
                         : dispatch_w<uint16_t, true>(W, src, dst, n, ic, stream);
 }
 
 hipError_t decode_int_dispatch(exmy_dtype_t dt, int W, const void* src, void* dst, uint64_t n, const IntConsts& ic,
                                hipStream_t stream) {
+  if (dt == EXMY_F16) return dispatch_w<f16_t, false>(W, src, dst, n, ic, stream);
   return dt == EXMY_F32 ? dispatch_w<float, false>(W, src, dst, n, ic, stream)
                         : dispatch_w<uint16_t, false>(W, src, dst, n, ic, stream);
 }
 
 hipError_t emulate_int_dispatch(exmy_dtype_t dt, void* data, uint64_t n, const IntConsts& ic, hipStream_t stream) {
+  if (dt == EXMY_F16) return launch_emulate<f16_t>(data, n, ic, stream);
   return dt == EXMY_F32 ? launch_emulate<float>(data, n, ic, stream) : launch_emulate<uint16_t>(data, n, ic, stream);
 }
 

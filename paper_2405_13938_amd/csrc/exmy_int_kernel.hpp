@@ -97,7 +97,7 @@ __global__ __launch_bounds__(kBlock) void encode_int_kernel(const void* src_v, v
         if constexpr (sizeof(T) == 4)
           u[j] = reinterpret_cast<const uint32_t*>(src)[i];
         else
-          u[j] = (uint32_t) reinterpret_cast<const uint16_t*>(src)[i] << 16;
+          u[j] = elem_bits<T>(reinterpret_cast<const uint16_t*>(src)[i]);
       }
     }
     enc::PlaneDst<W> pd;
@@ -130,10 +130,10 @@ __device__ __forceinline__ void decode_unit(const dec::UnitWords<W>& uw, const F
     store16<true>(out, lane_unit * 16, tile_unit * 16, make_uint4(b[0], b[1], b[2], b[3]));
   } else {
     uint4 o;
-    o.x = __builtin_amdgcn_perm(b[1], b[0], 0x07060302u);
-    o.y = __builtin_amdgcn_perm(b[3], b[2], 0x07060302u);
-    o.z = __builtin_amdgcn_perm(b[5], b[4], 0x07060302u);
-    o.w = __builtin_amdgcn_perm(b[7], b[6], 0x07060302u);
+    o.x = pack_elems<T>(b[0], b[1]);
+    o.y = pack_elems<T>(b[2], b[3]);
+    o.z = pack_elems<T>(b[4], b[5]);
+    o.w = pack_elems<T>(b[6], b[7]);
     store16<true>(out, lane_unit * 16, tile_unit * 16, o);
   }
 }
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kBlock) void decode_int_kernel(const void* src_v, v
       if constexpr (sizeof(T) == 4)
         reinterpret_cast<uint32_t*>(dst)[i] = b;
       else
-        reinterpret_cast<uint16_t*>(dst)[i] = (uint16_t)(b >> 16);
+        reinterpret_cast<uint16_t*>(dst)[i] = to_elem<T>(b);
     }
   }
 }
@@ -213,9 +213,10 @@ __global__ __launch_bounds__(kBlock) void emulate_int_kernel(void* data_v, uint6
       if constexpr (sizeof(T) == 4) {
         w[k] = emulate_bits(w[k], ic);
       } else {
-        const uint32_t lo = emulate_bits(w[k] << 16, ic);
-        const uint32_t hi = emulate_bits(w[k] & 0xFFFF0000u, ic);
-        w[k] = __builtin_amdgcn_perm(hi, lo, 0x07060302u);
+        const uint32_t lo = emulate_bits(lo_elem_bits<T>(w[k]), ic);
+        const uint32_t hi = emulate_bits(hi_elem_bits<T>(w[k]), ic);
+        const uint32_t pair = pack_elems<T>(lo, hi);
+        w[k] = kIsF16<T> ? keep_nonfinite_halves(w[k], pair) : pair;
       }
     }
     store16<true>(buf, threadIdx.x * 16, 0, make_uint4(w[0], w[1], w[2], w[3]));
@@ -228,7 +229,8 @@ __global__ __launch_bounds__(kBlock) void emulate_int_kernel(void* data_v, uint6
         *p = emulate_bits(*p, ic);
       } else {
         uint16_t* p = reinterpret_cast<uint16_t*>(data) + i;
-        *p = (uint16_t)(emulate_bits((uint32_t)*p << 16, ic) >> 16);
+        const uint32_t u = elem_bits<T>(*p);
+        if ((u & 0x7FFFFFFFu) < 0x7F800000u) *p = to_elem<T>(emulate_bits(u, ic));  // Inf / NaN stay as they are
       }
     }
   }

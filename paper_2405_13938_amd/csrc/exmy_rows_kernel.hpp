@@ -48,7 +48,7 @@ template <typename T>
 __device__ __forceinline__ uint32_t column_bits(const uint4& v, int c) {
   const uint32_t w[4] = {v.x, v.y, v.z, v.w};
   if constexpr (sizeof(T) == 4) return w[c];
-  return (c & 1) ? (w[c / 2] & 0xFFFF0000u) : (w[c / 2] << 16);
+  return (c & 1) ? hi_elem_bits<T>(w[c / 2]) : lo_elem_bits<T>(w[c / 2]);
 }
 
 // Plane words of a lane: plane P holds kCols words of S bytes, packed into
@@ -316,9 +316,9 @@ __global__ __launch_bounds__(kBlock) void decode_rows_kernel(const RowsArgs args
         const uint32_t b = dec::element_bits<W, kX8>(uw, j, fc, tc[j]);
         if constexpr (sizeof(T) == 4) {
           o[j][c] = b;
-        } else {  // every value is exact in bf16: keep the upper half
+        } else {  // every value is exact in the 16-bit type: pair it with its neighbour
           if (c & 1)
-            o[j][c / 2] = __builtin_amdgcn_perm(b, o[j][c / 2], 0x07060302u);
+            o[j][c / 2] = pack_elems<T>(o[j][c / 2], b);
           else
             o[j][c / 2] = b;
         }

@@ -90,3 +90,109 @@ def test_histogram_batch_and_ragged_lengths():
     torch.cuda.synchronize()
     for x, o, d in zip(xs, outs, decs):
         assert np.array_equal(hbits(d), O.decode(o.cpu().numpy(), O.F16, x.numel(), 3, 3, 130).view(np.uint16))
+
+
+# ------------------------------------------------------------ the other forms
+
+
+def f16_block_formats(W):
+    out = []
+    for X, Y in f16_formats(W):
+        if X <= 5 and f16_max_exps(X, Y):
+            out.append((X, Y))
+    return out
+
+
+@pytest.mark.parametrize("W", range(1, 17))
+def test_block_forms_every_width(W):
+    x = synth.shuffled(synth.all_f16_patterns(), 700 + W).to(DEV)
+    host = synth.bits_numpy(x)
+    n = x.numel()
+    for i, (X, Y) in enumerate(f16_block_formats(W)):
+        block = [8, 32, 64, 512, 24, 1024, 4096, 11008][(W + i) % 8]
+        nb = (n + block - 1) // block
+        got_before = exmy.block_max_exp(x, block, X)
+        got_after = exmy.block_max_exp_after_rounding(x, block, X, Y)
+        torch.cuda.synchronize()
+        assert np.array_equal(got_before.cpu().numpy(), O.block_max_exp(host, block, X)), (X, Y, block)
+        assert np.array_equal(got_after.cpu().numpy(), O.block_max_exp_after_rounding(host, block, X, Y)), (X, Y, block)
+        for meta in (O.block_max_exp(host, block, X), np.random.default_rng(W + i).integers(0, 256, nb).astype(np.uint8)):
+            md = torch.from_numpy(meta).to(DEV)
+            want = O.encode_blocks(host, block, X, Y, meta, threads=THREADS)
+            got = exmy.encode_blocks(x, block, X, Y, md)
+            torch.cuda.synchronize()
+            assert np.array_equal(got.cpu().numpy(), want), ("encode_blocks", X, Y, block)
+            dec = exmy.decode_blocks(torch.from_numpy(want).to(DEV), torch.float16, n, block, X, Y, md)
+            emu = exmy.emulate_blocks(x.clone(), block, X, Y, md)
+            torch.cuda.synchronize()
+            assert np.array_equal(hbits(dec), O.decode_blocks(want, O.F16, n, block, X, Y, meta, threads=THREADS).view(np.uint16))
+            assert np.array_equal(hbits(emu), O.emulate_blocks(host, block, X, Y, meta, threads=THREADS).view(np.uint16))
+        for scheme in (0, 1):
+            packed, meta = exmy.encode_blocks_auto(x, block, X, Y, scheme)
+            torch.cuda.synchronize()
+            want_meta = O.block_max_exp_after_rounding(host, block, X, Y) if scheme else O.block_max_exp(host, block, X)
+            want_meta = np.clip(want_meta, f16_max_exps(X, Y)[0], 142)  # the one-call form writes bytes valid for (X, Y)
+            assert np.array_equal(meta.cpu().numpy(), want_meta), ("auto", X, Y, block, scheme)
+            assert np.array_equal(packed.cpu().numpy(), O.encode_blocks(host, block, X, Y, want_meta, threads=THREADS))
+
+
+@pytest.mark.parametrize("W", range(2, 17))
+def test_float_scaling_every_width(W):
+    x = synth.shuffled(synth.all_f16_patterns(), 800 + W).to(DEV)
+    host = synth.bits_numpy(x)
+    n = x.numel()
+    for i, (X, Y) in enumerate(f16_formats(W)):
+        if (X, Y) == (0, 0) or O.check_format(O.F16, X, Y, 127, False) != 0:
+            continue
+        block = [16, 64, 512, 40, 2048, 11008][(W + i) % 6]
+        got = exmy.block_scale(x, block, X, Y)
+        torch.cuda.synchronize()
+        scale = O.block_scale(host, block, X, Y)
+        assert np.array_equal(got.cpu().numpy().view(np.uint32), scale.view(np.uint32)), (X, Y, block)
+        rng = np.random.default_rng(W * 31 + i)
+        for sc in (scale, np.clip(scale.astype(np.float64) * np.exp2(rng.uniform(-2, 2, scale.size)), 2.0 ** -126, 3.0e38).astype(np.float32)):
+            sd = torch.from_numpy(sc).to(DEV)
+            want = O.encode_scaled(host, block, X, Y, sc, threads=THREADS)
+            enc = exmy.encode_scaled(x, block, X, Y, sd)
+            dec = exmy.decode_scaled(torch.from_numpy(want).to(DEV), torch.float16, n, block, X, Y, sd)
+            emu = exmy.emulate_scaled(x.clone(), block, X, Y, sd)
+            torch.cuda.synchronize()
+            assert np.array_equal(enc.cpu().numpy(), want), ("encode_scaled", X, Y, block)
+            assert np.array_equal(hbits(dec), O.decode_scaled(want, O.F16, n, block, X, Y, sc, threads=THREADS).view(np.uint16)), ("decode_scaled", X, Y, block)
+            assert np.array_equal(hbits(emu), O.emulate_scaled(host, block, X, Y, sc, threads=THREADS).view(np.uint16)), ("emulate_scaled", X, Y, block)
+
+
+@pytest.mark.parametrize("W", range(1, 17))
+def test_row_packing_every_width(W):
+    x = synth.shuffled(synth.all_f16_patterns(), 900 + W).to(DEV)
+    shapes = [x.reshape(128, 512), x[: 89 * 736].reshape(89, 736).contiguous()]
+    for i, (X, Y) in enumerate(f16_block_formats(W)):
+        m = shapes[i % 2]
+        rows, cols = m.shape
+        host = synth.bits_numpy(m)
+        me = f16_max_exps(X, Y)[-1]
+        meta = np.random.default_rng(W + i).integers(0, 256, rows).astype(np.uint8)
+        for max_exp, mrows in ((me, None), (0, meta)):
+            md = None if mrows is None else torch.from_numpy(mrows).to(DEV)
+            want = O.encode_rows(host, rows, cols, X, Y, max_exp, mrows)
+            got = exmy.encode_rows(m, X, Y, max_exp, md)
+            dec = exmy.decode_rows(torch.from_numpy(want).to(DEV), torch.float16, rows, cols, X, Y, max_exp, md)
+            torch.cuda.synchronize()
+            assert np.array_equal(got.cpu().numpy(), want), ("encode_rows", X, Y, rows, cols)
+            assert np.array_equal(hbits(dec), O.decode_rows(want, O.F16, rows, cols, X, Y, max_exp, mrows).view(np.uint16))
+
+
+@pytest.mark.parametrize("Y", range(1, 12))
+def test_twos_complement(Y):
+    x = torch.cat([synth.all_f16_patterns(), synth.all_f16_patterns()[777:782]]).to(DEV)
+    host = synth.bits_numpy(x)
+    n = x.numel()
+    for me in sorted({102 + Y, 126 + Y if 126 + Y <= 141 else 141, 141}):
+        want = O.encode_int(host, Y, me)
+        got = exmy.encode_int(x, Y, me)
+        dec = exmy.decode_int(torch.from_numpy(want).to(DEV), torch.float16, n, Y, me)
+        emu = exmy.emulate_int(x.clone(), Y, me)
+        torch.cuda.synchronize()
+        assert np.array_equal(got.cpu().numpy(), want), (Y, me)
+        assert np.array_equal(hbits(dec), O.decode_int(want, O.F16, n, Y, me).view(np.uint16)), (Y, me)
+        assert np.array_equal(hbits(emu), O.emulate_int(host, Y, me).view(np.uint16)), (Y, me)

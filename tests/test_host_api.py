@@ -251,7 +251,7 @@ def test_twos_complement_entry_points_validate_without_launch():
     assert enc(ok, B.F32, (1 << 40) + 1, 7, 133, ok, None) == 4
 
 
-def test_fp16_container_is_limited_to_the_per_tensor_entry_points():
+def test_fp16_container_limits():
     L = B.lib()
     ok = ctypes.c_void_p(0x1000)
     assert L.exmy_encode(ok, B.F16, 0, 3, 3, 130, ok, None) == 0
@@ -263,8 +263,21 @@ def test_fp16_container_is_limited_to_the_per_tensor_entry_points():
     assert L.exmy_encode(ok, B.F16, 0, 3, 3, 143, ok, None) == 3       # top binade above 2^15
     assert L.exmy_encode(ok, B.F16, 0, 3, 3, 111, ok, None) == 3       # quantum below 2^-24
     assert L.exmy_encode(ok, B.F16, 0, 3, 3, 112, ok, None) == 0
-    assert L.exmy_block_max_exp(ok, B.F16, 0, 8, 3, ok, None) == 2
-    assert L.exmy_encode_blocks(ok, B.F16, 0, 8, 3, 3, ok, ok, None) == 2
-    assert L.exmy_block_scale(ok, B.F16, 0, 8, 3, 3, ok, None) == 2
-    assert L.exmy_encode_rows(ok, B.F16, 0, 8, 3, 3, 130, None, ok, None) == 2
-    assert L.exmy_encode_int(ok, B.F16, 0, 7, 133, ok, None) == 2
+    # per-block forms: the same formats, unless no metadatum keeps them inside fp16
+    assert L.exmy_block_max_exp(ok, B.F16, 0, 8, 3, ok, None) == 0
+    assert L.exmy_block_max_exp(ok, B.F16, 0, 8, 6, ok, None) == 2
+    assert L.exmy_block_max_exp_after_rounding(ok, B.F16, 0, 8, 3, 3, ok, None) == 0
+    assert L.exmy_encode_blocks(ok, B.F16, 0, 8, 3, 3, ok, ok, None) == 0
+    assert L.exmy_encode_blocks(ok, B.F16, 0, 8, 5, 9, ok, ok, None) == 0
+    assert L.exmy_encode_blocks(ok, B.F16, 0, 8, 5, 10, ok, ok, None) != 0
+    assert L.exmy_encode_blocks_auto(ok, B.F16, 0, 8, 3, 3, 0, ok, ok, None) == 0
+    assert L.exmy_block_scale(ok, B.F16, 0, 8, 3, 3, ok, None) == 0
+    assert L.exmy_block_scale(ok, B.F16, 0, 8, 4, 10, ok, None) == 0
+    assert L.exmy_block_scale(ok, B.F16, 0, 8, 5, 2, ok, None) != 0    # max_exp = 127 lies under e5m2's fp16 range
+    assert L.exmy_encode_rows(ok, B.F16, 0, 8, 3, 3, 130, None, ok, None) == 0
+    assert L.exmy_encode_rows(ok, B.F16, 0, 8, 3, 3, 143, None, ok, None) == 3
+    assert L.exmy_encode_rows(ok, B.F16, 0, 8, 3, 3, 0, ok, ok, None) == 0
+    assert L.exmy_encode_int(ok, B.F16, 0, 7, 133, ok, None) == 0
+    assert L.exmy_encode_int(ok, B.F16, 0, 7, 142, ok, None) == 3      # -2^16 is not a half
+    assert L.exmy_encode_int(ok, B.F16, 0, 7, 108, ok, None) == 3      # quantum 2^-25
+    assert L.exmy_encode_int(ok, B.F16, 0, 12, 133, ok, None) == 2
