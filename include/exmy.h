@@ -206,31 +206,37 @@ exmy_status_t exmy_encode_blocks_auto(const void* src, exmy_dtype_t dt, uint64_t
 
 /* ---------------------------------------------------------------------------
  * Float scaling with maximum exponent 127 (Section 2 "Metadata": an additional
- * float32 scaling factor; Section 2.1: the third scheme of the emulation
- * example, which reproduces the largest value of a block accurately).
+ * bfloat16 or float32 scaling factor; Section 2.1: the third scheme of the
+ * emulation example, which reproduces the largest value of a block accurately).
  *
- * Every block has one fp32 scale in the DEVICE array scale_dev (4-byte
- * aligned, exmy_block_count(n, block) entries) instead of a metadata byte; the
- * codes are those of the format with max_exp = 127, whose top binade is
- * [1, 2).  The paper prints no formulas; this library computes, in fp32:
+ * Every block has one scale in the DEVICE array scale_dev
+ * (exmy_block_count(n, block) entries of type scale_dt: EXMY_F32, 4-byte
+ * aligned, or EXMY_BF16, 2-byte aligned; EXMY_F16 gives EXMY_ERR_FORMAT)
+ * instead of a metadata byte; the codes are those of the format with
+ * max_exp = 127, whose top binade is [1, 2).  The paper prints no formulas;
+ * this library computes, in fp32:
  *   scale   s = max(m / vmax, FLT_MIN), m = largest finite |x| of the block
  *               (0 if none), vmax = largest value of the format at max_exp = 127;
+ *               a bf16 scale is the smallest bf16 value >= s (so the block
+ *               maximum still lands on the largest code), at most the largest
+ *               finite bf16;
  *   encode  the code of |x| * (1 / s) in that format, under the sign of x
  *           (Inf / NaN: sign + largest magnitude code, as in exmy_encode);
  *   decode  value * s, one rounding; rounded to nearest even when dt is bf16;
  *   emulate decode(encode(x)) with Inf / NaN left bit-identical.
- * Scales given to encode / decode / emulate need not come from
- * exmy_block_scale but must be finite and >= FLT_MIN (else the result is
- * unspecified, without any fault).  1 <= X <= 7 or (X = 0, Y >= 1); block,
- * layout, pointers, n = 0, streams and errors as for the entry points above. */
+ * A bf16 scale enters this arithmetic widened exactly to fp32.  Scales given to
+ * encode / decode / emulate need not come from exmy_block_scale but must be
+ * finite and >= FLT_MIN (else the result is unspecified, without any fault).
+ * 1 <= X <= 7 or (X = 0, Y >= 1); block, layout, pointers, n = 0, streams and
+ * errors as for the entry points above. */
 exmy_status_t exmy_block_scale(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
-                               float* scale_dev, void* stream);
+                               void* scale_dev, exmy_dtype_t scale_dt, void* stream);
 exmy_status_t exmy_encode_scaled(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
-                                 const float* scale_dev, void* dst_packed, void* stream);
+                                 const void* scale_dev, exmy_dtype_t scale_dt, void* dst_packed, void* stream);
 exmy_status_t exmy_decode_scaled(const void* src_packed, exmy_dtype_t dt_out, uint64_t n, uint64_t block, int X,
-                                 int Y, const float* scale_dev, void* dst, void* stream);
+                                 int Y, const void* scale_dev, exmy_dtype_t scale_dt, void* dst, void* stream);
 exmy_status_t exmy_emulate_scaled(void* data_inout, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
-                                  const float* scale_dev, void* stream);
+                                  const void* scale_dev, exmy_dtype_t scale_dt, void* stream);
 
 /* ---------------------------------------------------------------------------
  * Packing along rows (Section 2.2.2 and Fig. 2: an array of shape (8R, C) is

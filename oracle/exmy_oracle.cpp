@@ -71,7 +71,11 @@
 //     fl32(value * s), rounded to nearest even when the container is bf16.  The
 //     scaled value decides the code, so it is computed in the kernels' precision
 //     (fp32) here too.  Parity unpinned by the paper beyond the property that the
-//     block maximum is reproduced almost exactly.
+//     block maximum is reproduced almost exactly.  The "bfloat16 scaling factor"
+//     of the same passage: the smallest bf16 value not below that fp32 scale
+//     (never below, so that the block maximum divided by it still lies within
+//     the format's range), at most the largest finite bf16; it enters encode and
+//     decode widened exactly to fp32.
 //
 // Pinned by tests/test_oracle_pins.py, tests/test_oracle_pack.py and
 // tests/test_oracle_blocks.py against the
@@ -662,6 +666,27 @@ int exmy_oracle_block_scale(const void* src, int dt, uint64_t n, uint64_t block,
     float s = m / vmax;
     if (!(s >= std::ldexp(1.0f, -126))) s = std::ldexp(1.0f, -126);
     scale_out[b] = s;
+  }
+  return ORACLE_OK;
+}
+
+// The bf16 form of the scales: for each block the smallest bf16 value >= the fp32
+// scale above, capped at the largest finite bf16; written as bf16 bit patterns.
+int exmy_oracle_block_scale_bf16(const void* src, int dt, uint64_t n, uint64_t block, int X, int Y,
+                                 uint16_t* scale_out) {
+  if ((!src || !scale_out) && n) return ORACLE_ERR_NULL;
+  if (block == 0 || block % 8) return ORACLE_ERR_FORMAT;
+  const uint64_t nb = (n + block - 1) / block;
+  std::vector<float> s32(nb);
+  if (int rc = exmy_oracle_block_scale(src, dt, n, block, X, Y, s32.data())) return rc;
+  const double bf16_max = std::ldexp(255.0, 127 - 7);  // (2 - 2^-7) * 2^127
+  for (uint64_t b = 0; b < nb; ++b) {
+    int e;
+    (void)std::frexp((double)s32[b], &e);                   // s in [2^(e-1), 2^e), a normal float
+    const int q = e - 1 - 7;                                // exponent of the bf16 quantum in this binade
+    double up = std::ldexp(std::ceil(std::ldexp((double)s32[b], -q)), q);
+    if (up > bf16_max) up = bf16_max;
+    scale_out[b] = (uint16_t)(float_to_bits((float)up) >> 16);  // exact: `up` is a bf16 value
   }
   return ORACLE_OK;
 }

@@ -44,6 +44,7 @@ def lib():
         L.exmy_oracle_decode_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, i32]
         L.exmy_oracle_emulate_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, i32]
         L.exmy_oracle_block_scale.argtypes = [vp, i32, u64, u64, i32, i32, vp]
+        L.exmy_oracle_block_scale_bf16.argtypes = [vp, i32, u64, u64, i32, i32, vp]
         L.exmy_oracle_encode_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, i32]
         L.exmy_oracle_decode_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, i32]
         L.exmy_oracle_emulate_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, i32]
@@ -229,14 +230,25 @@ def emulate_blocks(src, block, X, Y, max_exp, threads=1):
 
 
 def _scales(scale, n, block):
-    s = np.ascontiguousarray(scale, dtype=np.float32)
+    """fp32 scales as they are; bf16 scales (uint16 bit patterns) widened exactly to fp32."""
+    scale = np.asarray(scale)
+    if scale.dtype == np.uint16:
+        s = (scale.astype(np.uint32) << 16).view(np.float32)
+    else:
+        s = np.ascontiguousarray(scale, dtype=np.float32)
     assert s.size == (n + block - 1) // block
-    return s
+    return np.ascontiguousarray(s)
 
 
-def block_scale(src, block, X, Y):
+def block_scale(src, block, X, Y, bf16=False):
+    """One scale per block: float32 values, or with ``bf16`` the uint16 bit patterns of bf16 scales."""
     a, dt = _src(src)
-    out = np.empty((a.size + block - 1) // block, dtype=np.float32)
+    nb = (a.size + block - 1) // block
+    if bf16:
+        out = np.empty(nb, dtype=np.uint16)
+        _check(lib().exmy_oracle_block_scale_bf16(_ptr(a), dt, a.size, block, X, Y, _ptr(out)))
+        return out
+    out = np.empty(nb, dtype=np.float32)
     _check(lib().exmy_oracle_block_scale(_ptr(a), dt, a.size, block, X, Y, _ptr(out)))
     return out
 

@@ -105,13 +105,13 @@ def lib():
         L.exmy_emulate_blocks.restype = i32
         L.exmy_emulate_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp]
         L.exmy_block_scale.restype = i32
-        L.exmy_block_scale.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp]
+        L.exmy_block_scale.argtypes = [vp, i32, u64, u64, i32, i32, vp, i32, vp]
         L.exmy_encode_scaled.restype = i32
-        L.exmy_encode_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, vp]
+        L.exmy_encode_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, i32, vp, vp]
         L.exmy_decode_scaled.restype = i32
-        L.exmy_decode_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, vp]
+        L.exmy_decode_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, i32, vp, vp]
         L.exmy_emulate_scaled.restype = i32
-        L.exmy_emulate_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp]
+        L.exmy_emulate_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, i32, vp]
         L.exmy_packed_bytes_rows.restype = ctypes.c_size_t
         L.exmy_packed_bytes_rows.argtypes = [u64, u64, i32, i32]
         L.exmy_encode_rows.restype = i32
@@ -417,20 +417,20 @@ def emulate_blocks(data, block, X, Y, max_exps):
 
 def _scale_tensor(scale, n, block, name="scales"):
     _device_tensor(scale, name)
-    if scale.dtype != torch.float32 or scale.numel() != block_count(n, block):
-        raise ValueError("exmy: %s must be float32 with %d elements" % (name, block_count(n, block)))
+    if scale.dtype not in (torch.float32, torch.bfloat16) or scale.numel() != block_count(n, block):
+        raise ValueError("exmy: %s must be float32 or bfloat16 with %d elements" % (name, block_count(n, block)))
     return scale
 
 
-def block_scale(src, block, X, Y, out=None):
-    """exmy_block_scale: returns the float32 tensor of one scale per block."""
+def block_scale(src, block, X, Y, out=None, scale_dtype=torch.float32):
+    """exmy_block_scale: returns the tensor of one scale per block (``scale_dtype``: float32 or bfloat16)."""
     _device_tensor(src, "src")
     n = src.numel()
     if out is None:
-        out = torch.empty(block_count(n, block), dtype=torch.float32, device=src.device)
-    else:
-        _scale_tensor(out, n, block, "out")
-    _check(lib().exmy_block_scale(src.data_ptr(), _dtype_enum(src), n, block, X, Y, out.data_ptr(), _stream()))
+        out = torch.empty(block_count(n, block), dtype=scale_dtype, device=src.device)
+    _scale_tensor(out, n, block, "out")
+    _check(lib().exmy_block_scale(src.data_ptr(), _dtype_enum(src), n, block, X, Y, out.data_ptr(), _dtype_enum(out),
+                                  _stream()))
     return out
 
 
@@ -447,7 +447,7 @@ def encode_scaled(src, block, X, Y, scales, out=None):
         if out.dtype != torch.uint8 or out.numel() != nbytes:
             raise ValueError("exmy: out must be uint8 with %d elements" % nbytes)
     _check(lib().exmy_encode_scaled(src.data_ptr(), _dtype_enum(src), n, block, X, Y, scales.data_ptr(),
-                                    out.data_ptr(), _stream()))
+                                    _dtype_enum(scales), out.data_ptr(), _stream()))
     return out
 
 
@@ -465,7 +465,7 @@ def decode_scaled(packed, dtype, n, block, X, Y, scales, out=None):
         if out.dtype != tdt or out.numel() != n:
             raise ValueError("exmy: out must be %s with %d elements" % (tdt, n))
     _check(lib().exmy_decode_scaled(packed.data_ptr(), _dtype_enum(out), n, block, X, Y, scales.data_ptr(),
-                                    out.data_ptr(), _stream()))
+                                    _dtype_enum(scales), out.data_ptr(), _stream()))
     return out
 
 
@@ -474,7 +474,7 @@ def emulate_scaled(data, block, X, Y, scales):
     _device_tensor(data, "data")
     _scale_tensor(scales, data.numel(), block)
     _check(lib().exmy_emulate_scaled(data.data_ptr(), _dtype_enum(data), data.numel(), block, X, Y,
-                                     scales.data_ptr(), _stream()))
+                                     scales.data_ptr(), _dtype_enum(scales), _stream()))
     return data
 
 

@@ -251,10 +251,12 @@ enum class BlockOp { kMaxExp, kMaxExpOfFormat, kMaxExpRounded, kScale, kEncode, 
 
 // Shared validation and launch of the per-block entry points.  `elems` is the
 // bf16 / fp32 side, `packed` the plane side (encode and decode only); `side` is
-// the per-block array: metadata bytes, or fp32 scales when `scaled` is set.
+// the per-block array: metadata bytes, or scales of type `scale_dt` when `scaled` is set.
 exmy_status_t run_blocks(BlockOp op, bool scaled, const void* elems, const void* packed, exmy_dtype_t dt, uint64_t n,
-                         uint64_t block, int X, int Y, const void* side, void* stream) {
+                         uint64_t block, int X, int Y, const void* side, void* stream,
+                         exmy_dtype_t scale_dt = EXMY_F32) {
   BlockArgs args;
+  if (scaled && scale_dt != EXMY_F32 && scale_dt != EXMY_BF16) return EXMY_ERR_FORMAT;
   const bool is_auto = op == BlockOp::kAutoEncode || op == BlockOp::kAutoEncodeRounded;
   const bool is_packed = op == BlockOp::kEncode || op == BlockOp::kDecode || is_auto;
   const bool rounded = op == BlockOp::kMaxExpRounded || op == BlockOp::kAutoEncodeRounded;
@@ -276,14 +278,15 @@ exmy_status_t run_blocks(BlockOp op, bool scaled, const void* elems, const void*
   if (n == 0) return EXMY_OK;
   if (!elems || !side || (is_packed && !packed)) return EXMY_ERR_NULL;
   if (!aligned16(elems) || (is_packed && !aligned16(packed))) return EXMY_ERR_ALIGN;
-  if (scaled && (reinterpret_cast<uintptr_t>(side) & 3u)) return EXMY_ERR_ALIGN;
+  if (scaled && (reinterpret_cast<uintptr_t>(side) & (scale_dt == EXMY_F32 ? 3u : 1u))) return EXMY_ERR_ALIGN;
 
   args.n = n;
   args.n_blocks = (n + block - 1) / block;
   args.block_groups = (uint32_t)(block / 8);
   args.bi = make_block_index(args.block_groups);  // dispatchers rescale it to their kernel's units
   args.meta = scaled ? nullptr : static_cast<uint8_t*>(const_cast<void*>(side));
-  args.scale = scaled ? static_cast<float*>(const_cast<void*>(side)) : nullptr;
+  args.scale = scaled ? const_cast<void*>(side) : nullptr;
+  args.scale_log2_bytes = scale_dt == EXMY_F32 ? 2u : 1u;
   const hipStream_t s = static_cast<hipStream_t>(stream);
   hipError_t e = hipSuccess;
   switch (op) {
@@ -464,23 +467,23 @@ exmy_status_t exmy_emulate_blocks(void* data_inout, exmy_dtype_t dt, uint64_t n,
 }
 
 exmy_status_t exmy_block_scale(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
-                               float* scale_dev, void* stream) {
-  return run_blocks(BlockOp::kScale, true, src, nullptr, dt, n, block, X, Y, scale_dev, stream);
+                               void* scale_dev, exmy_dtype_t scale_dt, void* stream) {
+  return run_blocks(BlockOp::kScale, true, src, nullptr, dt, n, block, X, Y, scale_dev, stream, scale_dt);
 }
 
 exmy_status_t exmy_encode_scaled(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
-                                 const float* scale_dev, void* dst_packed, void* stream) {
-  return run_blocks(BlockOp::kEncode, true, src, dst_packed, dt, n, block, X, Y, scale_dev, stream);
+                                 const void* scale_dev, exmy_dtype_t scale_dt, void* dst_packed, void* stream) {
+  return run_blocks(BlockOp::kEncode, true, src, dst_packed, dt, n, block, X, Y, scale_dev, stream, scale_dt);
 }
 
 exmy_status_t exmy_decode_scaled(const void* src_packed, exmy_dtype_t dt_out, uint64_t n, uint64_t block, int X, int Y,
-                                 const float* scale_dev, void* dst, void* stream) {
-  return run_blocks(BlockOp::kDecode, true, dst, src_packed, dt_out, n, block, X, Y, scale_dev, stream);
+                                 const void* scale_dev, exmy_dtype_t scale_dt, void* dst, void* stream) {
+  return run_blocks(BlockOp::kDecode, true, dst, src_packed, dt_out, n, block, X, Y, scale_dev, stream, scale_dt);
 }
 
 exmy_status_t exmy_emulate_scaled(void* data_inout, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
-                                  const float* scale_dev, void* stream) {
-  return run_blocks(BlockOp::kEmulate, true, data_inout, nullptr, dt, n, block, X, Y, scale_dev, stream);
+                                  const void* scale_dev, exmy_dtype_t scale_dt, void* stream) {
+  return run_blocks(BlockOp::kEmulate, true, data_inout, nullptr, dt, n, block, X, Y, scale_dev, stream, scale_dt);
 }
 
 size_t exmy_packed_bytes_rows(uint64_t rows, uint64_t cols, int X, int Y) {

@@ -115,10 +115,12 @@ struct BlockArgs {
   const void* src;      // encode / emulate: elements; decode: packed planes
   void* dst;            // encode: packed planes; decode: elements; emulate: unused
   uint8_t* meta;        // one byte per block (read; written by the max-exponent kernel)
-  // Float scaling (Section 2 "Metadata": an additional float32 scaling factor;
-  // Section 2.1: "float scaling with maximum exponent 127"): one fp32 scale per
-  // block instead of the metadata byte, with the constants of max_exp = 127.
-  float* scale;
+  // Float scaling (Section 2 "Metadata": an additional bfloat16 or float32
+  // scaling factor; Section 2.1: "float scaling with maximum exponent 127"): one
+  // scale per block instead of the metadata byte, with the constants of
+  // max_exp = 127.  A bf16 scale is used widened to fp32.
+  void* scale;
+  uint32_t scale_log2_bytes;  // 2: fp32 scales, 1: bf16 scales
   TensorConsts tc127;
   float vmax127;        // largest value of the format with max_exp = 127
   uint64_t n;           // elements
@@ -349,11 +351,24 @@ __device__ __forceinline__ uint32_t lane_block(uint32_t j, const BlockIndex& bi)
 }
 
 // The datum of block number `block` of the array behind `r`: a metadata byte, or
-// the bits of an fp32 scale.
+// the fp32 bits of a scale stored as fp32 or bf16 (`scale_log2_bytes`, uniform).
 template <bool kScaled>
-__device__ __forceinline__ uint32_t load_block_datum(rsrc_t r, uint32_t block) {
-  if constexpr (kScaled) return __builtin_amdgcn_raw_buffer_load_b32(r, block * 4u, 0, 0);
+__device__ __forceinline__ uint32_t load_block_datum(rsrc_t r, uint32_t block, uint32_t scale_log2_bytes) {
+  if constexpr (kScaled) {
+    if (scale_log2_bytes == 2) return __builtin_amdgcn_raw_buffer_load_b32(r, block * 4u, 0, 0);
+    return (uint32_t)__builtin_amdgcn_raw_buffer_load_b16(r, block * 2u, 0, 0) << 16;
+  }
   return __builtin_amdgcn_raw_buffer_load_b8(r, block, 0, 0);
+}
+
+// Address of the scale of block `block`, and its fp32 bits.
+__device__ __forceinline__ char* scale_address(const BlockArgs& args, uint64_t block) {
+  return static_cast<char*>(args.scale) + (block << args.scale_log2_bytes);
+}
+__device__ __forceinline__ uint32_t load_scale_bits(const BlockArgs& args, uint64_t block) {
+  const char* p = scale_address(args, block);
+  if (args.scale_log2_bytes == 2) return *reinterpret_cast<const uint32_t*>(p);
+  return (uint32_t)*reinterpret_cast<const uint16_t*>(p) << 16;
 }
 
 // Element types: float (fp32), uint16_t (bf16: the upper half of an fp32) and

@@ -260,14 +260,14 @@ __global__ __launch_bounds__(kBlock) void decode_blocks_kernel(const BlockArgs a
     PlaneSrc<W> ps;
     make_plane_src<W, E>(src, G, u0, ps);
     const rsrc_t out = make_rsrc(reinterpret_cast<uint4*>(dst) + u0);
-    const rsrc_t mt = kScaled ? make_rsrc(args.scale + blk0) : make_rsrc(meta + blk0);
+    const rsrc_t mt = kScaled ? make_rsrc(scale_address(args, blk0)) : make_rsrc(meta + blk0);
     TileWords<W, kUnroll> tw;
     uint32_t me[kUnroll];  // the block's metadatum, or the bits of its scale
     if (tile < full_tiles) {
       load_tile<W, E, kBlock, kUnroll, false>(ps, 0, 0, tw);
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r)
-        me[r] = load_block_datum<kScaled>(mt, lane_block<TU>(off + r * kBlock + threadIdx.x, bi));
+        me[r] = load_block_datum<kScaled>(mt, lane_block<TU>(off + r * kBlock + threadIdx.x, bi), args.scale_log2_bytes);
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r) {
         if constexpr (kScaled)
@@ -280,7 +280,7 @@ __global__ __launch_bounds__(kBlock) void decode_blocks_kernel(const BlockArgs a
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r)
         me[r] = (r * kBlock + threadIdx.x < rem_units)
-                    ? load_block_datum<kScaled>(mt, lane_block<TU>(off + r * kBlock + threadIdx.x, bi))
+                    ? load_block_datum<kScaled>(mt, lane_block<TU>(off + r * kBlock + threadIdx.x, bi), args.scale_log2_bytes)
                     : 0u;
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r) {
@@ -301,7 +301,7 @@ __global__ __launch_bounds__(kBlock) void decode_blocks_kernel(const BlockArgs a
       uint32_t b;
       if constexpr (kScaled) {
         b = element_bits_slow<W, false>(src, G, i, fc, args.tc127);
-        b = rescaled_bits<T>(b, args.scale[args.n_blocks - 1]);
+        b = rescaled_bits<T>(b, as_f32(load_scale_bits(args, args.n_blocks - 1)));
       } else {
         b = element_bits_slow<W, false>(src, G, i, fc, derive_tc(meta[args.n_blocks - 1], bc));
       }

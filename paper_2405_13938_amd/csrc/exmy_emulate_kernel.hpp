@@ -177,7 +177,7 @@ __global__ __launch_bounds__(kBlock) void emulate_blocks_kernel(const BlockArgs 
     uint32_t off;
     tile_first_block(v0, bi, blk0, off);
     const rsrc_t buf = make_rsrc(reinterpret_cast<uint4*>(data) + v0);
-    const rsrc_t mt = kScaled ? make_rsrc(args.scale + blk0) : make_rsrc(meta + blk0);
+    const rsrc_t mt = kScaled ? make_rsrc(scale_address(args, blk0)) : make_rsrc(meta + blk0);
     const uint64_t left = V - v0;
     const uint32_t rem = left < TV ? (uint32_t)left : TV;
     uint4 v[kUnroll];
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(kBlock) void emulate_blocks_kernel(const BlockArgs 
     for (int r = 0; r < kUnroll; ++r) {
       if (r * kBlock + threadIdx.x < rem) {
         v[r] = load16<kNT>(buf, lane_off, r * kBlock * 16);
-        me[r] = load_block_datum<kScaled>(mt, lane_block<TV>(off + r * kBlock + threadIdx.x, bi));
+        me[r] = load_block_datum<kScaled>(mt, lane_block<TV>(off + r * kBlock + threadIdx.x, bi), args.scale_log2_bytes);
       }
     }
 #pragma unroll
@@ -212,7 +212,7 @@ __global__ __launch_bounds__(kBlock) void emulate_blocks_kernel(const BlockArgs 
         u = elem_bits<T>(reinterpret_cast<uint16_t*>(data)[i]);
       uint32_t r;
       if constexpr (kScaled) {
-        const float scale = args.scale[args.n_blocks - 1];
+        const float scale = as_f32(load_scale_bits(args, args.n_blocks - 1));
         const float inv = 1.0f / scale;
         r = wide_format ? emulate_scaled_bits<true, T>(u, inv, scale, fc, args.tc127)
                         : emulate_scaled_bits<false, T>(u, inv, scale, fc, args.tc127);
@@ -266,13 +266,20 @@ __device__ __forceinline__ int32_t element_exp_key(const T* p) {
 }
 
 // Result of one block from the key of its largest finite magnitude.  kScale:
-// the fp32 scale that maps that magnitude onto the largest value of the
-// max_exp = 127 format (not below the smallest normal float); else the metadatum.
+// the scale that maps that magnitude onto the largest value of the
+// max_exp = 127 format (not below the smallest normal float), as fp32 or as the
+// smallest bf16 not below it (capped at the largest finite bf16); else the
+// metadatum.
 template <bool kScale>
 __device__ __forceinline__ void store_block_result(const BlockArgs& args, uint64_t block, int32_t key) {
   uint32_t a = key > 0 ? (uint32_t)key - 0x00800000u : 0u;  // bits of the largest finite magnitude (0 if none)
   if constexpr (kScale) {
-    args.scale[block] = fmaxf(as_f32(a) / args.vmax127, as_f32(0x00800000u));
+    const uint32_t s = as_u32(fmaxf(as_f32(a) / args.vmax127, as_f32(0x00800000u)));
+    char* p = scale_address(args, block);
+    if (args.scale_log2_bytes == 2)
+      *reinterpret_cast<uint32_t*>(p) = s;
+    else
+      *reinterpret_cast<uint16_t*>(p) = (uint16_t)min((s + 0xFFFFu) >> 16, 0x7F7Fu);
   } else {
     args.meta[block] = (uint8_t)meta_from_key(key, args.bc);
   }

@@ -340,7 +340,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
     uint32_t off;
     tile_first_block(g0, bi, blk0, off);
     const rsrc_t src = make_rsrc(src4 + g0 * kLoads);
-    const rsrc_t mt = kScaled ? make_rsrc(args.scale + blk0) : make_rsrc(meta + blk0);
+    const rsrc_t mt = kScaled ? make_rsrc(scale_address(args, blk0)) : make_rsrc(meta + blk0);
     PlaneDst<W> pd;
     make_plane_dst<W>(dst, G, g0, pd);
     TileRegs<T, kUnroll> regs;
@@ -349,7 +349,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
       load_tile<T, kBlock, kUnroll, kNT, false>(src, 0, 0, regs);
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r)
-        me[r] = load_block_datum<kScaled>(mt, lane_block<TG>(off + r * kBlock + threadIdx.x, bi));
+        me[r] = load_block_datum<kScaled>(mt, lane_block<TG>(off + r * kBlock + threadIdx.x, bi), args.scale_log2_bytes);
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r) {
         uint32_t u[8];
@@ -364,7 +364,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r)
         if (r * kBlock + threadIdx.x < rem_groups)
-          me[r] = load_block_datum<kScaled>(mt, lane_block<TG>(off + r * kBlock + threadIdx.x, bi));
+          me[r] = load_block_datum<kScaled>(mt, lane_block<TG>(off + r * kBlock + threadIdx.x, bi), args.scale_log2_bytes);
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r) {
         if (r * kBlock + threadIdx.x < rem_groups) {  // the rounding-variant vote is among the lanes that get here
@@ -397,7 +397,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
     PlaneDst<W> pd;
     make_plane_dst<W>(dst, G, Gfull, pd);
     if constexpr (kScaled)
-      encode_group_scaled<W>(u, as_u32(args.scale[args.n_blocks - 1]), fc, args.tc127, pd, 0, 0);
+      encode_group_scaled<W>(u, load_scale_bits(args, args.n_blocks - 1), fc, args.tc127, pd, 0, 0);
     else
       encode_group_meta<W>(u, meta[args.n_blocks - 1], fc, bc, pd, 0, 0);
   }

@@ -15,7 +15,7 @@ THREADS = min(O.default_threads(), 16)
 
 
 def odt(t):
-    return O.F32 if t.dtype == torch.float32 else O.BF16
+    return {torch.float32: O.F32, torch.bfloat16: O.BF16, torch.float16: O.F16}[t.dtype]
 
 
 def ubits(a):
@@ -32,10 +32,11 @@ def formats_of_width(W, dtype):
             if W - 1 - X <= (P if X >= 1 else P + 1) and (X, W - 1 - X) != (0, 0)]
 
 
-def scales_for(kind, host, block, X, Y, seed=0):
-    s = O.block_scale(host, block, X, Y)
+def scales_for(kind, host, block, X, Y, seed=0, bf16=False):
+    """fp32 scales, or with ``bf16`` the uint16 bit patterns of bf16 scales."""
     if kind == "block_scale":
-        return s
+        return O.block_scale(host, block, X, Y, bf16=bf16)
+    s = O.block_scale(host, block, X, Y)
     rng = np.random.default_rng(seed + block)
     if kind == "perturbed":  # any finite scale >= FLT_MIN is valid input: up to 4x off either way, and extremes
         f = np.exp2(rng.uniform(-2.0, 2.0, s.size)).astype(np.float32)
@@ -43,24 +44,30 @@ def scales_for(kind, host, block, X, Y, seed=0):
         out[rng.random(s.size) < 0.02] = np.float32(2.0 ** -126)
         out[rng.random(s.size) < 0.02] = np.float32(3.0e38)
         out[rng.random(s.size) < 0.02] = np.float32(1.0)
+        if bf16:  # cut to bf16; FLT_MIN and 3e38 stay valid
+            out = np.maximum(out.view(np.uint32) >> 16, 0x0080).astype(np.uint16)
         return out
     raise ValueError(kind)
 
 
-def check_scaled(x_dev, block, X, Y, kind, host=None, what=("scale", "encode", "decode", "emulate"), seed=0):
+def check_scaled(x_dev, block, X, Y, kind, host=None, what=("scale", "encode", "decode", "emulate"), seed=0, bf16=False):
     x_dev = x_dev.reshape(-1)
     n = x_dev.numel()
     if host is None:
         host = synth.bits_numpy(x_dev)
     dt = odt(x_dev)
-    label = "e%dm%d block=%d n=%d %s %s" % (X, Y, block, n, x_dev.dtype, kind)
+    label = "e%dm%d block=%d n=%d %s %s%s" % (X, Y, block, n, x_dev.dtype, kind, " bf16 scales" if bf16 else "")
     if "scale" in what:
-        got = exmy.block_scale(x_dev, block, X, Y)
+        got = exmy.block_scale(x_dev, block, X, Y, scale_dtype=torch.bfloat16 if bf16 else torch.float32)
         torch.cuda.synchronize()
-        want = O.block_scale(host, block, X, Y)
-        assert np.array_equal(got.cpu().numpy().view(np.uint32), want.view(np.uint32)), "block_scale " + label
-    scale = scales_for(kind, host, block, X, Y, seed)
-    scale_dev = torch.from_numpy(scale).to(DEV)
+        want = O.block_scale(host, block, X, Y, bf16=bf16)
+        got = got.view(torch.int16 if bf16 else torch.int32).cpu().numpy()
+        assert np.array_equal(got.view(want.dtype.str.replace("f", "u")), want.view(want.dtype.str.replace("f", "u"))), "block_scale " + label
+    scale = scales_for(kind, host, block, X, Y, seed, bf16)
+    if bf16:
+        scale_dev = torch.from_numpy(scale.view(np.int16)).view(torch.bfloat16).to(DEV)
+    else:
+        scale_dev = torch.from_numpy(scale).to(DEV)
     if 1 + X + Y <= 16 and ("encode" in what or "decode" in what):
         want_packed = O.encode_scaled(host, block, X, Y, scale, threads=THREADS)
         if "encode" in what:
@@ -153,3 +160,29 @@ def test_weight_matrix(block):
     host = synth.bits_numpy(x)
     for X, Y in ((2, 1), (3, 2)):
         check_scaled(x, block, X, Y, "block_scale", host)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("block", [8, 32, 24, 1024, 11008])
+def test_bf16_scales(dtype, block):
+    """Section 2 "Metadata": the scaling factor may be bf16.  Scales written by the library are the fp32
+    scales rounded up to bf16; any bf16 scale is then used widened to fp32."""
+    n = 11008 * 24 + 8 * 3 + 5
+    x = synth.gaussian_bf16(n, std=0.02, seed=31 + block, device=DEV).float()
+    x = x * torch.exp2(torch.randint(-9, 9, (n,), device=DEV, generator=torch.Generator(DEV).manual_seed(block)).float())
+    x = (x * 1.0009765625 if dtype == torch.float32 else x).to(dtype)
+    x[5] = float("inf")
+    x[block * 2 : block * 3] = 0.0
+    host = synth.bits_numpy(x)
+    for X, Y in ((2, 1), (3, 3), (0, 3), (4, 3)):
+        check_scaled(x, block, X, Y, "block_scale", host, bf16=True)
+        check_scaled(x, block, X, Y, "perturbed", host, what=("encode", "decode", "emulate"), bf16=True)
+
+
+def test_bf16_scale_is_capped_at_the_largest_finite_bf16():
+    x = torch.full((64,), 3.4e38, device=DEV)  # above the largest finite bf16
+    x[32:] = 1e-42
+    got = exmy.block_scale(x, 32, 1, 0, scale_dtype=torch.bfloat16)  # e1m0: the largest value at max_exp = 127 is 1
+    torch.cuda.synchronize()
+    assert got.view(torch.int16).cpu().tolist() == [0x7F7F, 0x0080]
+    assert O.block_scale(synth.bits_numpy(x), 32, 1, 0, bf16=True).tolist() == [0x7F7F, 0x0080]

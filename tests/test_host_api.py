@@ -178,7 +178,11 @@ def test_after_rounding_and_auto_entry_points_validate_without_launch():
 def test_float_scaling_entry_points_validate_without_launch():
     L = B.lib()
     ok, odd16, odd4 = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1008), ctypes.c_void_p(0x1002)
-    sc, enc, dec, emu = L.exmy_block_scale, L.exmy_encode_scaled, L.exmy_decode_scaled, L.exmy_emulate_scaled
+
+    def with_scale_dtype(fn):  # the scale's dtype follows the scale pointer (argument 6); fp32 unless given
+        return lambda *a, sdt=B.F32: fn(*a[:7], sdt, *a[7:])
+
+    sc, enc, dec, emu = (with_scale_dtype(f) for f in (L.exmy_block_scale, L.exmy_encode_scaled, L.exmy_decode_scaled, L.exmy_emulate_scaled))
     assert sc(ok, B.F32, 0, 8, 3, 3, ok, None) == 0
     assert sc(None, B.F32, 8, 8, 3, 3, ok, None) == 1
     assert sc(ok, B.F32, 8, 8, 3, 3, None, None) == 1
@@ -200,6 +204,15 @@ def test_float_scaling_entry_points_validate_without_launch():
     assert dec(odd16, B.BF16, 64, 16, 3, 3, ok, ok, None) == 5
     assert emu(ok, B.BF16, 64, 16, 3, 3, odd4, None) == 5
     assert emu(ok, B.BF16, (1 << 40) + 8, 16, 3, 3, ok, None) == 4
+    # bf16 scales: 2-byte aligned; fp16 scales are not offered
+    odd1 = ctypes.c_void_p(0x1001)
+    assert sc(ok, B.F32, 0, 8, 3, 3, ok, None, sdt=B.BF16) == 0
+    assert sc(ok, B.F32, 0, 8, 3, 3, ok, None, sdt=B.F16) == 2
+    assert enc(ok, B.BF16, 0, 16, 3, 3, ok, ok, None, sdt=B.F16) == 2
+    assert dec(ok, B.BF16, 0, 16, 3, 3, ok, ok, None, sdt=7) == 2
+    assert emu(ok, B.BF16, 64, 16, 3, 3, odd1, None, sdt=B.BF16) == 5
+    assert sc(ok, B.BF16, 64, 16, 3, 3, odd1, None, sdt=B.BF16) == 5
+    assert emu(ok, B.BF16, 64, 16, 3, 3, None, None, sdt=B.BF16) == 1
 
 
 def test_row_packing_entry_points_validate_without_launch():
@@ -271,9 +284,9 @@ def test_fp16_container_limits():
     assert L.exmy_encode_blocks(ok, B.F16, 0, 8, 5, 9, ok, ok, None) == 0
     assert L.exmy_encode_blocks(ok, B.F16, 0, 8, 5, 10, ok, ok, None) != 0
     assert L.exmy_encode_blocks_auto(ok, B.F16, 0, 8, 3, 3, 0, ok, ok, None) == 0
-    assert L.exmy_block_scale(ok, B.F16, 0, 8, 3, 3, ok, None) == 0
-    assert L.exmy_block_scale(ok, B.F16, 0, 8, 4, 10, ok, None) == 0
-    assert L.exmy_block_scale(ok, B.F16, 0, 8, 5, 2, ok, None) != 0    # max_exp = 127 lies under e5m2's fp16 range
+    assert L.exmy_block_scale(ok, B.F16, 0, 8, 3, 3, ok, B.F32, None) == 0
+    assert L.exmy_block_scale(ok, B.F16, 0, 8, 4, 10, ok, B.BF16, None) == 0
+    assert L.exmy_block_scale(ok, B.F16, 0, 8, 5, 2, ok, B.F32, None) != 0    # max_exp = 127 lies under e5m2's fp16 range
     assert L.exmy_encode_rows(ok, B.F16, 0, 8, 3, 3, 130, None, ok, None) == 0
     assert L.exmy_encode_rows(ok, B.F16, 0, 8, 3, 3, 143, None, ok, None) == 3
     assert L.exmy_encode_rows(ok, B.F16, 0, 8, 3, 3, 0, ok, ok, None) == 0

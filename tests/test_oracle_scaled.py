@@ -53,6 +53,38 @@ def test_bf16_rounding_is_the_library_conversion():
     assert torch.equal(got, want)
 
 
+def test_bf16_scale_is_the_smallest_bf16_not_below_the_fp32_scale():
+    """Section 2 "Metadata" offers a bfloat16 scaling factor.  Checked through the library's bf16 conversion:
+    its round-to-nearest result, moved one bf16 up where it fell below the fp32 scale."""
+    g = torch.Generator().manual_seed(9)
+    n, block = 1 << 15, 16
+    x = torch.randn(n, generator=g) * torch.exp2(torch.randint(-60, 60, (n,), generator=g).float())
+    x[0:16] = 0.0
+    x[16:32] = 3.4e38  # with e1m0 (largest value 1) the scale exceeds the largest finite bf16
+    xn = as_np(x)
+    for X, Y in ((1, 0), (2, 1), (3, 3), (0, 4), (5, 2)):
+        s32 = O.block_scale(xn, block, X, Y)
+        s16 = O.block_scale(xn, block, X, Y, bf16=True)
+        assert s16.dtype == np.uint16
+        near = torch.from_numpy(s32).bfloat16()
+        bits = near.view(torch.int16).numpy().astype(np.int64) & 0xFFFF
+        bits = bits + (near.float().numpy() < s32)            # positive values: the next bf16 is the next pattern
+        bits = np.minimum(bits, 0x7F7F)                        # Inf is not a scale
+        assert np.array_equal(s16.astype(np.int64), bits), (X, Y)
+        wide = (s16.astype(np.uint32) << 16).view(np.float32)
+        capped = s16 == 0x7F7F
+        assert (wide[~capped] >= s32[~capped]).all() and s16[0] == 0x0080
+        assert (((s16[~capped].astype(np.uint32) - 1) << 16).view(np.float32) < s32[~capped]).all()
+        # the block maximum stays inside the format: its scaled value does not exceed the largest value by more
+        # than the two roundings of the scaling
+        m = torch.where(torch.isfinite(x), x.abs(), torch.zeros(())).reshape(-1, block).max(dim=1).values.numpy()
+        a = m * (np.float32(1.0) / wide)
+        assert (a[~capped] <= np.float32(vmax_of(X, Y)) * np.float32(1 + 2.0 ** -22)).all()
+        # bf16 scales are used widened: same results as the fp32 array of those values
+        assert np.array_equal(O.encode_scaled(xn, block, X, Y, s16), O.encode_scaled(xn, block, X, Y, wide))
+        assert np.array_equal(O.emulate_scaled(xn, block, X, Y, s16).view(np.uint32), O.emulate_scaled(xn, block, X, Y, wide).view(np.uint32))
+
+
 @pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
 @pytest.mark.parametrize("X,Y", [(2, 1), (3, 3), (1, 2), (0, 3), (4, 3), (7, 0), (0, 1), (5, 7)])
 def test_power_of_two_scale_equals_power_of_two_metadata(dtype, X, Y):
