@@ -535,6 +535,17 @@ int exmy_oracle_block_max_exp(const void* src, int dt, uint64_t n, uint64_t bloc
 // scheme 3.9 in e2m1 always rounds up to 4.0).  The block's largest finite
 // magnitude is rounded to nearest, ties to even, to the mantissa width of the
 // format's top binade; the metadatum is the biased exponent of the result.
+// Biased exponent of the magnitude m >= 0 after rounding it to nearest, ties to even, to `bits`
+// fraction bits in its own binade (0 for magnitudes below the smallest normal float).
+static int biased_exp_after_rounding(double m, int bits) {
+  if (!(m >= std::ldexp(1.0, -126))) return 0;
+  int e;
+  const double frac = std::frexp(m, &e);                         // m = frac * 2^e, frac in [0.5, 1)
+  const double k = std::nearbyint(std::ldexp(frac, bits + 1));    // significand with `bits` fraction bits
+  std::frexp(std::ldexp(k, e - bits - 1), &e);                   // the rounded value may be 2^e
+  return e - 1 + 127;
+}
+
 int exmy_oracle_block_max_exp_after_rounding(const void* src, int dt, uint64_t n, uint64_t block, int X, int Y,
                                              uint8_t* max_exp_out) {
   if ((!src || !max_exp_out) && n) return ORACLE_ERR_NULL;
@@ -551,15 +562,7 @@ int exmy_oracle_block_max_exp_after_rounding(const void* src, int dt, uint64_t n
       const double a = std::fabs((double)bits_to_float(load_bits(src, dt, i)));
       if (std::isfinite(a) && a > m) m = a;
     }
-    int biased = 0;
-    if (m >= std::ldexp(1.0, -126)) {
-      int e;
-      const double frac = std::frexp(m, &e);                         // m = frac * 2^e, frac in [0.5, 1)
-      const double k = std::nearbyint(std::ldexp(frac, bits + 1));    // significand with `bits` fraction bits
-      std::frexp(std::ldexp(k, e - bits - 1), &e);                   // the rounded value may be 2^e
-      biased = e - 1 + 127;
-    }
-    max_exp_out[b] = (uint8_t)clamp_meta(biased, lo, hi);
+    max_exp_out[b] = (uint8_t)clamp_meta(biased_exp_after_rounding(m, bits), lo, hi);
   }
   return ORACLE_OK;
 }
@@ -615,6 +618,119 @@ int exmy_oracle_decode_blocks(const uint8_t* src_packed, int dt, uint64_t n, uin
 int exmy_oracle_emulate_blocks(void* data, int dt, uint64_t n, uint64_t block, int X, int Y, const uint8_t* max_exp,
                                int threads) {
   return blocks_op(2, data, data, dt, n, block, X, Y, max_exp, threads);
+}
+
+// ---------------------------------------------------------------------------
+// Blocks that are columns or 2-D tiles (Section 2 "Block Size": a block can be a
+// tensor, a row, a column, a sub row or a 2-D tile).  src is a row-major
+// (rows, cols) matrix; tile (i, j) covers rows [i*tile_rows, (i+1)*tile_rows) and
+// columns [j*tile_cols, (j+1)*tile_cols), cut off at the matrix edges; its
+// metadatum is byte i * ceil(cols / tile_cols) + j of the metadata array.  A
+// column is the tile (rows, 1), a row (1, cols), a sub row (1, k).  Codes are
+// packed in the flat layout of the matrix in memory (groups of 8 consecutive
+// elements; cols is a multiple of 8, so a group lies inside one row).  Metadata
+// range, clamping and widths as for the consecutive blocks above.
+
+static int tiles_shape(uint64_t rows, uint64_t cols, uint64_t tile_rows, uint64_t tile_cols) {
+  if (tile_rows == 0 || tile_cols == 0) return ORACLE_ERR_FORMAT;
+  if (cols % 8) return ORACLE_ERR_FORMAT;
+  (void)rows;
+  return ORACLE_OK;
+}
+
+// scheme 0: "maximum exponent before rounding" (Y is not used), 1: "after rounding".
+int exmy_oracle_tile_max_exp(const void* src, int dt, uint64_t rows, uint64_t cols, uint64_t tile_rows,
+                             uint64_t tile_cols, int X, int Y, int scheme, uint8_t* max_exp_out) {
+  if ((!src || !max_exp_out) && rows && cols) return ORACLE_ERR_NULL;
+  if (dt != ORACLE_F32 && dt != ORACLE_BF16 && dt != ORACLE_F16) return ORACLE_ERR_FORMAT;
+  if (scheme != 0 && scheme != 1) return ORACLE_ERR_FORMAT;
+  if (int rc = tiles_shape(rows, cols, tile_rows, tile_cols)) return rc;
+  int lo, hi;
+  if (int rc = block_meta_range(dt, X, scheme ? Y : -1, &lo, &hi)) return rc;
+  int bits = 0;
+  if (scheme) {
+    Format f0;
+    if (int rc = check_format(dt, X, Y, hi, false, &f0)) return rc;
+    bits = X == 0 ? (Y > 0 ? Y - 1 : 0) : Y;  // mantissa bits of the top binade
+  }
+  const uint64_t tr_n = (rows + tile_rows - 1) / tile_rows, tc_n = (cols + tile_cols - 1) / tile_cols;
+  for (uint64_t ti = 0; ti < tr_n; ++ti) {
+    for (uint64_t tj = 0; tj < tc_n; ++tj) {
+      double m = 0.0;  // largest finite magnitude of the tile
+      for (uint64_t r = ti * tile_rows; r < std::min(rows, (ti + 1) * tile_rows); ++r) {
+        for (uint64_t c = tj * tile_cols; c < std::min(cols, (tj + 1) * tile_cols); ++c) {
+          const double a = std::fabs((double)bits_to_float(load_bits(src, dt, r * cols + c)));
+          if (std::isfinite(a) && a > m) m = a;
+        }
+      }
+      int biased;
+      if (scheme) {
+        biased = biased_exp_after_rounding(m, bits);
+      } else {
+        int e;
+        (void)std::frexp(m, &e);  // m in [2^(e-1), 2^e)
+        biased = m >= std::ldexp(1.0, -126) ? e - 1 + 127 : 0;
+      }
+      max_exp_out[ti * tc_n + tj] = (uint8_t)clamp_meta(biased, lo, hi);
+    }
+  }
+  return ORACLE_OK;
+}
+
+// what: 0 = encode (src -> packed), 1 = decode (packed -> dst), 2 = emulate in place (data = src)
+static int tiles_op(int what, const void* src, void* dst, int dt, uint64_t rows, uint64_t cols, uint64_t tile_rows,
+                    uint64_t tile_cols, int X, int Y, const uint8_t* max_exp, int threads) {
+  const uint64_t n = rows * cols;
+  if (n && (!src || !dst || !max_exp)) return ORACLE_ERR_NULL;
+  if (int rc = tiles_shape(rows, cols, tile_rows, tile_cols)) return rc;
+  int lo, hi;
+  if (int rc = block_meta_range(dt, X, Y, &lo, &hi)) return rc;
+  Format f0;
+  if (int rc = check_format(dt, X, Y, hi, what != 2, &f0)) return rc;
+  if (what != 2 && 1 + X + Y > kBlockWidth) return ORACLE_ERR_FORMAT;
+  const uint64_t tc_n = (cols + tile_cols - 1) / tile_cols;
+  const int W = 1 + X + Y;
+  std::vector<uint32_t> codes;
+  if (what != 2) codes.resize(n);
+  if (what == 1) unpack_groups((const uint8_t*)src, n, W, codes.data(), 0, 0, (n + 7) / 8);
+  parallel_ranges(rows, threads, [&](uint64_t r0, uint64_t r1) {
+    for (uint64_t r = r0; r < r1; ++r) {
+      for (uint64_t c = 0; c < cols; ++c) {
+        const uint64_t i = r * cols + c;
+        Format f;
+        check_format(dt, X, Y, clamp_meta(max_exp[(r / tile_rows) * tc_n + c / tile_cols], lo, hi), what != 2, &f);
+        if (what == 0) {
+          codes[i] = encode_one(f, load_bits(src, dt, i));
+        } else if (what == 1) {
+          store_bits(dst, dt, i, decode_one(f, codes[i]));
+        } else {
+          const uint32_t bits = load_bits(src, dt, i);
+          const float x = bits_to_float(bits);
+          if (std::isnan(x) || std::isinf(x)) continue;
+          const float v = (float)code_magnitude(f, magnitude_code(f, std::fabs((double)x)));
+          store_bits(dst, dt, i, float_to_bits(v) | (bits & 0x80000000u));
+        }
+      }
+    }
+  });
+  if (what == 0) pack_groups(codes.data(), 0, n, W, (uint8_t*)dst, 0, (n + 7) / 8);
+  return ORACLE_OK;
+}
+
+int exmy_oracle_encode_tiles(const void* src, int dt, uint64_t rows, uint64_t cols, uint64_t tile_rows,
+                             uint64_t tile_cols, int X, int Y, const uint8_t* max_exp, uint8_t* dst_packed,
+                             int threads) {
+  return tiles_op(0, src, dst_packed, dt, rows, cols, tile_rows, tile_cols, X, Y, max_exp, threads);
+}
+
+int exmy_oracle_decode_tiles(const uint8_t* src_packed, int dt, uint64_t rows, uint64_t cols, uint64_t tile_rows,
+                             uint64_t tile_cols, int X, int Y, const uint8_t* max_exp, void* dst, int threads) {
+  return tiles_op(1, src_packed, dst, dt, rows, cols, tile_rows, tile_cols, X, Y, max_exp, threads);
+}
+
+int exmy_oracle_emulate_tiles(void* data, int dt, uint64_t rows, uint64_t cols, uint64_t tile_rows,
+                              uint64_t tile_cols, int X, int Y, const uint8_t* max_exp, int threads) {
+  return tiles_op(2, data, data, dt, rows, cols, tile_rows, tile_cols, X, Y, max_exp, threads);
 }
 
 // ---------------------------------------------------------------------------

@@ -43,6 +43,10 @@ def lib():
         L.exmy_oracle_encode_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, i32]
         L.exmy_oracle_decode_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, i32]
         L.exmy_oracle_emulate_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, i32]
+        L.exmy_oracle_tile_max_exp.argtypes = [vp, i32, u64, u64, u64, u64, i32, i32, i32, vp]
+        L.exmy_oracle_encode_tiles.argtypes = [vp, i32, u64, u64, u64, u64, i32, i32, vp, vp, i32]
+        L.exmy_oracle_decode_tiles.argtypes = [vp, i32, u64, u64, u64, u64, i32, i32, vp, vp, i32]
+        L.exmy_oracle_emulate_tiles.argtypes = [vp, i32, u64, u64, u64, u64, i32, i32, vp, i32]
         L.exmy_oracle_block_scale.argtypes = [vp, i32, u64, u64, i32, i32, vp]
         L.exmy_oracle_block_scale_bf16.argtypes = [vp, i32, u64, u64, i32, i32, vp]
         L.exmy_oracle_encode_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, i32]
@@ -223,6 +227,61 @@ def emulate_blocks(src, block, X, Y, max_exp, threads=1):
     m = _meta(max_exp, a.size, block)
     out = a.copy()
     _check(lib().exmy_oracle_emulate_blocks(_ptr(out), dt, out.size, block, X, Y, _ptr(m), threads))
+    return out
+
+
+# ------------------------------------------------------------ blocks that are columns or 2-D tiles
+
+
+def tile_count(rows, cols, tile_rows, tile_cols):
+    return ((rows + tile_rows - 1) // tile_rows) * ((cols + tile_cols - 1) // tile_cols)
+
+
+def _matrix(src):
+    a, dt = _src(src)
+    assert a.ndim == 2
+    return a, dt
+
+
+def tile_max_exp(src, tile_rows, tile_cols, X, Y=0, after_rounding=False):
+    """src: 2-D array.  Returns the row-major (ceil(rows/tile_rows), ceil(cols/tile_cols)) metadata, flat."""
+    a, dt = _matrix(src)
+    rows, cols = a.shape
+    out = np.empty(tile_count(rows, cols, tile_rows, tile_cols), dtype=np.uint8)
+    _check(lib().exmy_oracle_tile_max_exp(_ptr(a), dt, rows, cols, tile_rows, tile_cols, X, Y, int(after_rounding), _ptr(out)))
+    return out
+
+
+def _tile_meta(max_exp, rows, cols, tile_rows, tile_cols):
+    m = np.ascontiguousarray(max_exp, dtype=np.uint8).reshape(-1)
+    assert m.size == tile_count(rows, cols, tile_rows, tile_cols)
+    return m
+
+
+def encode_tiles(src, tile_rows, tile_cols, X, Y, max_exp, threads=1):
+    a, dt = _matrix(src)
+    rows, cols = a.shape
+    m = _tile_meta(max_exp, rows, cols, tile_rows, tile_cols)
+    out = np.empty(packed_bytes(a.size, X, Y), dtype=np.uint8)
+    _check(lib().exmy_oracle_encode_tiles(_ptr(a), dt, rows, cols, tile_rows, tile_cols, X, Y, _ptr(m), _ptr(out), threads))
+    return out
+
+
+def decode_tiles(packed, dt, rows, cols, tile_rows, tile_cols, X, Y, max_exp, threads=1):
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    assert packed.size == packed_bytes(rows * cols, X, Y)
+    m = _tile_meta(max_exp, rows, cols, tile_rows, tile_cols)
+    out = np.empty((rows, cols), dtype=_out_dtype(dt))
+    _check(lib().exmy_oracle_decode_tiles(_ptr(packed), dt, rows, cols, tile_rows, tile_cols, X, Y, _ptr(m), _ptr(out), threads))
+    return out
+
+
+def emulate_tiles(src, tile_rows, tile_cols, X, Y, max_exp, threads=1):
+    a, dt = _matrix(src)
+    rows, cols = a.shape
+    m = _tile_meta(max_exp, rows, cols, tile_rows, tile_cols)
+    out = a.copy()
+    _check(lib().exmy_oracle_emulate_tiles(_ptr(out), dt, rows, cols, tile_rows, tile_cols, X, Y, _ptr(m), threads))
     return out
 
 
