@@ -244,6 +244,23 @@ def block_scheme_rates(exmy, synth, dev):
             rates["decode_rows_per_row_metadata"] = (codec + nb, rot(lambda k: exmy.decode_rows(outs[k], torch.bfloat16, rows, cols, X, Y, 0, meta, out=dm)))
         res[label] = {name: round(nbytes / timed(fn) / 1e9, 1) for name, (nbytes, fn) in rates.items()}
         res[label]["unit"] = "GB/s"
+
+    # the same slab as a (32768, 11008) matrix whose blocks are 2-D tiles, or whole columns
+    rows, cols, X, Y = n // 11008, 11008, 3, 2
+    ms = [x.view(rows, cols) for x in xs]
+    dm = dst.view(rows, cols)
+    codec = n * (2 + (1 + X + Y) / 8)
+    for label, tr, tc in (("tile128x128_e3m2", 128, 128), ("column_e3m2", rows, 1)):
+        nt = exmy.tile_count(rows, cols, tr, tc)
+        meta = exmy.tile_max_exp(ms[0], tr, tc, X)
+        rates = {
+            "tile_max_exp": (n * 2 + nt, rot(lambda k: exmy.tile_max_exp(ms[k], tr, tc, X, out=meta))),
+            "encode_tiles": (codec + nt, rot(lambda k: exmy.encode_tiles(ms[k], tr, tc, X, Y, meta, out=outs[k]))),
+            "decode_tiles": (codec + nt, rot(lambda k: exmy.decode_tiles(outs[k], torch.bfloat16, rows, cols, tr, tc, X, Y, meta, out=dm))),
+            "emulate_tiles": (n * 4 + nt, rot(lambda k: exmy.emulate_tiles(ms[k], tr, tc, X, Y, meta))),
+        }
+        res[label] = {name: round(nbytes / timed(fn) / 1e9, 1) for name, (nbytes, fn) in rates.items()}
+        res[label]["unit"] = "GB/s"
     return res
 
 

@@ -77,12 +77,13 @@ typedef enum {
   EXMY_ERR_ALIGN = 5,   /* a pointer is not 16-byte aligned */
   EXMY_ERR_DEVICE = 6,  /* the HIP runtime reported an error at launch */
   EXMY_ERR_BLOCK = 7,   /* metadata block size not a multiple of 8 in [8, EXMY_MAX_BLOCK] */
-  EXMY_ERR_SHAPE = 8    /* packing along rows: cols not a multiple of 8, or above EXMY_MAX_COLS */
+  EXMY_ERR_SHAPE = 8    /* matrices: cols not a multiple of 8 or above EXMY_MAX_COLS, rows above EXMY_MAX_ROWS */
 } exmy_status_t;
 
 #define EXMY_MAX_ELEMENTS ((uint64_t)1 << 40)
 #define EXMY_MAX_BLOCK ((uint64_t)1 << 31)
 #define EXMY_MAX_COLS ((uint64_t)1 << 26)
+#define EXMY_MAX_ROWS ((uint64_t)1 << 31)
 
 /* Bytes of the packed form of n elements: ceil(n / 8) * (1 + X + Y)
  * (perfect compression, Section 2.2.2).  Host only; no validation. */
@@ -203,6 +204,47 @@ exmy_status_t exmy_emulate_blocks(void* data_inout, exmy_dtype_t dt, uint64_t n,
 typedef enum { EXMY_MAX_EXP_BEFORE_ROUNDING = 0, EXMY_MAX_EXP_AFTER_ROUNDING = 1 } exmy_scheme_t;
 exmy_status_t exmy_encode_blocks_auto(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
                                       exmy_scheme_t scheme, uint8_t* max_exp_dev, void* dst_packed, void* stream);
+
+/* ---------------------------------------------------------------------------
+ * Blocks that are columns or 2-D tiles (Section 2 "Block Size": a block can be
+ * a tensor, a row, a column, a sub row or a 2-D tile).
+ *
+ * src is a row-major matrix of `rows` rows of `cols` elements.  Tile (i, j)
+ * covers rows [i * tile_rows, (i + 1) * tile_rows) and columns
+ * [j * tile_cols, (j + 1) * tile_cols), cut off at the matrix edges; its
+ * metadatum is byte i * ceil(cols / tile_cols) + j of max_exp_dev
+ * (exmy_tile_count(...) bytes, row-major over the tiles).  A column is the tile
+ * (rows, 1), a part of a column (k, 1), a row (1, cols), a sub row (1, k); tile
+ * sizes beyond the matrix mean "all of it".  The codes are packed in the flat
+ * layout of the matrix in memory, exactly as exmy_encode packs its rows * cols
+ * elements (groups of 8 consecutive elements, which lie inside one row because
+ * cols is a multiple of 8); metadata bytes are read as in exmy_encode_blocks
+ * (same valid range, clamped; X <= 7, codes of at most 16 bits).
+ *
+ * cols is a multiple of 8, at most EXMY_MAX_COLS, rows at most EXMY_MAX_ROWS
+ * (EXMY_ERR_SHAPE); tile_rows >= 1; tile_cols is 1, a multiple of 8, or >= cols
+ * (EXMY_ERR_BLOCK); rows * cols <= EXMY_MAX_ELEMENTS; rows = 0 or cols = 0 is
+ * a no-op.  All arrays, max_exp_dev included, are DEVICE memory aligned to 16
+ * bytes.  exmy_tile_max_exp writes the metadata under either scheme of Section
+ * 2 "Metadata" (Y is used by the "after rounding" scheme only) in two launches
+ * on `stream`: it clears the array and then folds partial maxima into it with
+ * 32-bit atomic operations, which read the up to 3 bytes between the end of the
+ * array and the next 4-byte boundary and write them back unchanged.  Tiles
+ * that are runs of consecutive elements (tile_cols >= cols, or tile_rows = 1
+ * with tile_cols dividing cols) take the kernels of the consecutive-block entry
+ * points above. */
+size_t exmy_tile_count(uint64_t rows, uint64_t cols, uint64_t tile_rows, uint64_t tile_cols);
+exmy_status_t exmy_tile_max_exp(const void* src, exmy_dtype_t dt, uint64_t rows, uint64_t cols, uint64_t tile_rows,
+                                uint64_t tile_cols, int X, int Y, exmy_scheme_t scheme, uint8_t* max_exp_dev,
+                                void* stream);
+exmy_status_t exmy_encode_tiles(const void* src, exmy_dtype_t dt, uint64_t rows, uint64_t cols, uint64_t tile_rows,
+                                uint64_t tile_cols, int X, int Y, const uint8_t* max_exp_dev, void* dst_packed,
+                                void* stream);
+exmy_status_t exmy_decode_tiles(const void* src_packed, exmy_dtype_t dt_out, uint64_t rows, uint64_t cols,
+                                uint64_t tile_rows, uint64_t tile_cols, int X, int Y, const uint8_t* max_exp_dev,
+                                void* dst, void* stream);
+exmy_status_t exmy_emulate_tiles(void* data_inout, exmy_dtype_t dt, uint64_t rows, uint64_t cols, uint64_t tile_rows,
+                                 uint64_t tile_cols, int X, int Y, const uint8_t* max_exp_dev, void* stream);
 
 /* ---------------------------------------------------------------------------
  * Float scaling with maximum exponent 127 (Section 2 "Metadata": an additional

@@ -31,6 +31,11 @@ SYMBOLS = [
     "exmy_encode_blocks",
     "exmy_decode_blocks",
     "exmy_emulate_blocks",
+    "exmy_tile_count",
+    "exmy_tile_max_exp",
+    "exmy_encode_tiles",
+    "exmy_decode_tiles",
+    "exmy_emulate_tiles",
     "exmy_block_scale",
     "exmy_encode_scaled",
     "exmy_decode_scaled",
@@ -104,6 +109,16 @@ def lib():
         L.exmy_decode_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, vp]
         L.exmy_emulate_blocks.restype = i32
         L.exmy_emulate_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp]
+        L.exmy_tile_count.restype = ctypes.c_size_t
+        L.exmy_tile_count.argtypes = [u64, u64, u64, u64]
+        L.exmy_tile_max_exp.restype = i32
+        L.exmy_tile_max_exp.argtypes = [vp, i32, u64, u64, u64, u64, i32, i32, i32, vp, vp]
+        L.exmy_encode_tiles.restype = i32
+        L.exmy_encode_tiles.argtypes = [vp, i32, u64, u64, u64, u64, i32, i32, vp, vp, vp]
+        L.exmy_decode_tiles.restype = i32
+        L.exmy_decode_tiles.argtypes = [vp, i32, u64, u64, u64, u64, i32, i32, vp, vp, vp]
+        L.exmy_emulate_tiles.restype = i32
+        L.exmy_emulate_tiles.argtypes = [vp, i32, u64, u64, u64, u64, i32, i32, vp, vp]
         L.exmy_block_scale.restype = i32
         L.exmy_block_scale.argtypes = [vp, i32, u64, u64, i32, i32, vp, i32, vp]
         L.exmy_encode_scaled.restype = i32
@@ -409,6 +424,82 @@ def emulate_blocks(data, block, X, Y, max_exps):
     _meta_tensor(max_exps, data.numel(), block)
     _check(lib().exmy_emulate_blocks(data.data_ptr(), _dtype_enum(data), data.numel(), block, X, Y,
                                      max_exps.data_ptr(), _stream()))
+    return data
+
+
+# ------------------------------------------------------------ blocks that are columns or 2-D tiles
+
+
+def tile_count(rows, cols, tile_rows, tile_cols):
+    return int(lib().exmy_tile_count(rows, cols, tile_rows, tile_cols))
+
+
+def _matrix(t, name):
+    _device_tensor(t, name)
+    if t.dim() != 2:
+        raise ValueError("exmy: %s must be a 2-D tensor" % name)
+    return t.shape[0], t.shape[1]
+
+
+def _tile_meta_tensor(meta, rows, cols, tile_rows, tile_cols, name="max_exps"):
+    _device_tensor(meta, name)
+    if meta.dtype != torch.uint8 or meta.numel() != tile_count(rows, cols, tile_rows, tile_cols):
+        raise ValueError("exmy: %s must be uint8 with %d elements" % (name, tile_count(rows, cols, tile_rows, tile_cols)))
+    return meta
+
+
+def tile_max_exp(src, tile_rows, tile_cols, X, Y=0, scheme=BEFORE_ROUNDING, out=None):
+    """exmy_tile_max_exp: returns the flat uint8 tensor of one max_exp per tile, row-major over the tiles."""
+    rows, cols = _matrix(src, "src")
+    if out is None:
+        out = torch.empty(tile_count(rows, cols, tile_rows, tile_cols), dtype=torch.uint8, device=src.device)
+    else:
+        _tile_meta_tensor(out, rows, cols, tile_rows, tile_cols, "out")
+    _check(lib().exmy_tile_max_exp(src.data_ptr(), _dtype_enum(src), rows, cols, tile_rows, tile_cols, X, Y, int(scheme),
+                                   out.data_ptr(), _stream()))
+    return out
+
+
+def encode_tiles(src, tile_rows, tile_cols, X, Y, max_exps, out=None):
+    """exmy_encode_tiles: returns the packed uint8 tensor (``out`` if given)."""
+    rows, cols = _matrix(src, "src")
+    _tile_meta_tensor(max_exps, rows, cols, tile_rows, tile_cols)
+    nbytes = packed_bytes(rows * cols, X, Y)
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.uint8, device=src.device)
+    else:
+        _device_tensor(out, "out")
+        if out.dtype != torch.uint8 or out.numel() != nbytes:
+            raise ValueError("exmy: out must be uint8 with %d elements" % nbytes)
+    _check(lib().exmy_encode_tiles(src.data_ptr(), _dtype_enum(src), rows, cols, tile_rows, tile_cols, X, Y,
+                                   max_exps.data_ptr(), out.data_ptr(), _stream()))
+    return out
+
+
+def decode_tiles(packed, dtype, rows, cols, tile_rows, tile_cols, X, Y, max_exps, out=None):
+    """exmy_decode_tiles: returns a (rows, cols) tensor of ``dtype``."""
+    _device_tensor(packed, "packed")
+    _tile_meta_tensor(max_exps, rows, cols, tile_rows, tile_cols)
+    tdt = _torch_dtype(dtype)
+    if packed.dtype != torch.uint8 or packed.numel() != packed_bytes(rows * cols, X, Y):
+        raise ValueError("exmy: packed must be uint8 with %d elements" % packed_bytes(rows * cols, X, Y))
+    if out is None:
+        out = torch.empty((rows, cols), dtype=tdt, device=packed.device)
+    else:
+        _device_tensor(out, "out")
+        if out.dtype != tdt or tuple(out.shape) != (rows, cols):
+            raise ValueError("exmy: out must be %s of shape (%d, %d)" % (tdt, rows, cols))
+    _check(lib().exmy_decode_tiles(packed.data_ptr(), _dtype_enum(out), rows, cols, tile_rows, tile_cols, X, Y,
+                                   max_exps.data_ptr(), out.data_ptr(), _stream()))
+    return out
+
+
+def emulate_tiles(data, tile_rows, tile_cols, X, Y, max_exps):
+    """exmy_emulate_tiles: in place; returns ``data``."""
+    rows, cols = _matrix(data, "data")
+    _tile_meta_tensor(max_exps, rows, cols, tile_rows, tile_cols)
+    _check(lib().exmy_emulate_tiles(data.data_ptr(), _dtype_enum(data), rows, cols, tile_rows, tile_cols, X, Y,
+                                    max_exps.data_ptr(), _stream()))
     return data
 
 

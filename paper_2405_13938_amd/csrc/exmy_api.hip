@@ -323,6 +323,66 @@ exmy_status_t run_blocks(BlockOp op, bool scaled, const void* elems, const void*
   return e == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
 }
 
+// Shared validation and launch of the entry points for blocks that are columns or
+// 2-D tiles.  `matrix` is the bf16 / fp16 / fp32 side, `packed` the plane side.
+exmy_status_t run_tiles(BlockOp op, const void* matrix, const void* packed, exmy_dtype_t dt, uint64_t rows,
+                        uint64_t cols, uint64_t tile_rows, uint64_t tile_cols, int X, int Y, const uint8_t* meta,
+                        void* stream) {
+  TileArgs args;
+  const bool is_packed = op == BlockOp::kEncode || op == BlockOp::kDecode;
+  if (exmy_status_t st = make_block_format(dt, X, Y, is_packed ? kBlockWidth : kAnyWidth, op == BlockOp::kMaxExpRounded,
+                                           op != BlockOp::kMaxExp, &args.fc, &args.bc))
+    return st;
+  if (cols % 8 || cols > EXMY_MAX_COLS || rows > EXMY_MAX_ROWS) return EXMY_ERR_SHAPE;
+  if (tile_rows == 0 || tile_cols == 0 || (tile_cols != 1 && tile_cols % 8 && tile_cols < cols)) return EXMY_ERR_BLOCK;
+  if (rows * cols > EXMY_MAX_ELEMENTS) return EXMY_ERR_COUNT;
+  if (rows == 0 || cols == 0) return EXMY_OK;
+  if (!matrix || !meta || (is_packed && !packed)) return EXMY_ERR_NULL;
+  tile_rows = tile_rows < rows ? tile_rows : rows;
+  tile_cols = tile_cols < cols ? tile_cols : cols;
+  // Tiles that are runs of consecutive elements (whole rows, or parts that divide a row) are the blocks of
+  // the flat entry points.
+  const uint64_t run = tile_cols == cols ? tile_rows * cols : (tile_rows == 1 && cols % tile_cols == 0 ? tile_cols : 0);
+  if (run >= 8 && run % 8 == 0 && run <= EXMY_MAX_BLOCK)
+    return run_blocks(op, false, matrix, packed, dt, rows * cols, run, X, Y, meta, stream);
+  if (!aligned16(matrix) || !aligned16(meta) || (is_packed && !aligned16(packed))) return EXMY_ERR_ALIGN;
+
+  args.rows = rows;
+  args.cols = cols;
+  args.tile_rows = tile_rows;
+  args.tile_cols = tile_cols;
+  args.tiles_along_row = (cols + tile_cols - 1) / tile_cols;
+  args.meta = const_cast<uint8_t*>(meta);
+  const hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e = hipSuccess;
+  switch (op) {
+    case BlockOp::kMaxExp:
+    case BlockOp::kMaxExpRounded:
+      args.src = matrix;
+      args.dst = nullptr;
+      e = tile_max_exp_dispatch(dt, args, s);
+      break;
+    case BlockOp::kEncode:
+      args.src = matrix;
+      args.dst = const_cast<void*>(packed);
+      e = encode_tiles_dispatch(dt, 1 + X + Y, args, s);
+      break;
+    case BlockOp::kDecode:
+      args.src = packed;
+      args.dst = const_cast<void*>(matrix);
+      e = decode_tiles_dispatch(dt, 1 + X + Y, args, s);
+      break;
+    case BlockOp::kEmulate:
+      args.src = matrix;
+      args.dst = nullptr;
+      e = emulate_tiles_dispatch(dt, args, Y > 21, s);
+      break;
+    default:
+      return EXMY_ERR_FORMAT;
+  }
+  return e == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
+}
+
 enum class RowsOp { kEncode, kDecode };
 
 // Shared validation and launch of the entry points that pack along rows.
@@ -424,6 +484,37 @@ exmy_status_t exmy_exponent_histogram(const void* src, exmy_dtype_t dt, uint64_t
 }
 
 size_t exmy_block_count(uint64_t n, uint64_t block) { return block ? (size_t)((n + block - 1) / block) : 0; }
+
+size_t exmy_tile_count(uint64_t rows, uint64_t cols, uint64_t tile_rows, uint64_t tile_cols) {
+  if (!tile_rows || !tile_cols) return 0;
+  return (size_t)(((rows + tile_rows - 1) / tile_rows) * ((cols + tile_cols - 1) / tile_cols));
+}
+
+exmy_status_t exmy_tile_max_exp(const void* src, exmy_dtype_t dt, uint64_t rows, uint64_t cols, uint64_t tile_rows,
+                                uint64_t tile_cols, int X, int Y, exmy_scheme_t scheme, uint8_t* max_exp_dev,
+                                void* stream) {
+  if (scheme != EXMY_MAX_EXP_BEFORE_ROUNDING && scheme != EXMY_MAX_EXP_AFTER_ROUNDING) return EXMY_ERR_FORMAT;
+  const bool rounded = scheme == EXMY_MAX_EXP_AFTER_ROUNDING;
+  return run_tiles(rounded ? BlockOp::kMaxExpRounded : BlockOp::kMaxExp, src, nullptr, dt, rows, cols, tile_rows,
+                   tile_cols, X, rounded ? Y : 0, max_exp_dev, stream);
+}
+
+exmy_status_t exmy_encode_tiles(const void* src, exmy_dtype_t dt, uint64_t rows, uint64_t cols, uint64_t tile_rows,
+                                uint64_t tile_cols, int X, int Y, const uint8_t* max_exp_dev, void* dst_packed,
+                                void* stream) {
+  return run_tiles(BlockOp::kEncode, src, dst_packed, dt, rows, cols, tile_rows, tile_cols, X, Y, max_exp_dev, stream);
+}
+
+exmy_status_t exmy_decode_tiles(const void* src_packed, exmy_dtype_t dt_out, uint64_t rows, uint64_t cols,
+                                uint64_t tile_rows, uint64_t tile_cols, int X, int Y, const uint8_t* max_exp_dev,
+                                void* dst, void* stream) {
+  return run_tiles(BlockOp::kDecode, dst, src_packed, dt_out, rows, cols, tile_rows, tile_cols, X, Y, max_exp_dev, stream);
+}
+
+exmy_status_t exmy_emulate_tiles(void* data_inout, exmy_dtype_t dt, uint64_t rows, uint64_t cols, uint64_t tile_rows,
+                                 uint64_t tile_cols, int X, int Y, const uint8_t* max_exp_dev, void* stream) {
+  return run_tiles(BlockOp::kEmulate, data_inout, nullptr, dt, rows, cols, tile_rows, tile_cols, X, Y, max_exp_dev, stream);
+}
 
 exmy_status_t exmy_block_max_exp(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X,
                                  uint8_t* max_exp_dev, void* stream) {

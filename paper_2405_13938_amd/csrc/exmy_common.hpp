@@ -128,6 +128,33 @@ struct BlockArgs {
   uint32_t block_groups;  // block / 8
 };
 
+// Blocks that are columns or 2-D tiles of a row-major matrix (Section 2 "Block
+// Size").  Lengths are in the launched kernel's units (a unit is a run of
+// consecutive elements of one matrix row: a group of 8, or a 16-byte vector).
+// Workgroup tiles run flat over the matrix; the row, tile row and tile column of a
+// workgroup tile's first unit are wave-uniform divisions, and a lane adds the few
+// rows and tiles that start between that unit and its own (see tile_meta_offset).
+struct TileIndex {
+  BlockIndex row;        // units per matrix row
+  BlockIndex trow;       // matrix rows per tile
+  BlockIndex tcol;       // units per tile along a row (columns: unused)
+  uint32_t meta_stride;  // metadata bytes per tile row: tiles along a matrix row (columns: cols)
+  uint32_t unit_elems;   // columns: metadata bytes per unit = elements per unit
+};
+
+// Kernel arguments of the kernels for blocks that are columns or 2-D tiles.
+struct TileArgs {
+  FormatConsts fc;
+  BlockConsts bc;
+  TileIndex ti;          // in the launched kernel's units (set by its dispatcher)
+  const void* src;       // encode / emulate / maximum: the matrix; decode: packed planes
+  void* dst;             // encode: packed planes; decode: the matrix
+  uint8_t* meta;         // row-major (tile rows, tile columns) bytes
+  uint64_t rows, cols;   // of the matrix; cols is a multiple of 8
+  uint64_t tile_rows, tile_cols;  // clamped to the matrix; tile_cols is 1 or a multiple of 8
+  uint64_t tiles_along_row;       // ceil(cols / tile_cols)
+};
+
 // Kernel arguments of the kernels that pack along rows (Section 2.2.2: groups are
 // the 8 rows of a row block at one column of a row-major matrix).
 struct RowsArgs {
@@ -348,6 +375,56 @@ __device__ __forceinline__ uint32_t lane_block(uint32_t j, const BlockIndex& bi)
   if (bi.log2 != kNotPow2) return j >> bi.log2;
   if (bi.size >= kTile) return j >= bi.size ? 1u : 0u;  // a tile straddles at most one boundary
   return __umulhi(j, bi.recip32);                       // j < 2 * kTile
+}
+
+// Uniform position of a workgroup tile whose first unit is w0: its matrix row's
+// tile row (through `meta_row`, the metadata offset of that tile row), the row's
+// place inside that tile row, the unit's place in its matrix row, and that
+// place's tile column and remainder.
+struct TileStart {
+  uint64_t meta_row;  // tile row * meta_stride
+  uint32_t rr0;       // matrix row - tile row * rows per tile
+  uint32_t cu0;       // unit inside the matrix row
+  uint32_t ct0, cr0;  // cu0 / tile width, cu0 % tile width (tiles only)
+  bool one_row;       // the workgroup tile ends inside the matrix row it starts in
+};
+
+template <uint32_t kTile, bool kColumns>
+__device__ __forceinline__ TileStart tile_start(uint64_t w0, const TileIndex& ti) {
+  TileStart ts;
+  uint64_t row0, tb0;
+  tile_first_block(w0, ti.row, row0, ts.cu0);
+  ts.one_row = ts.cu0 + kTile <= ti.row.size;
+  tile_first_block(row0, ti.trow, tb0, ts.rr0);
+  ts.meta_row = tb0 * ti.meta_stride;
+  ts.ct0 = ts.cr0 = 0;
+  if constexpr (!kColumns) {
+    uint64_t q;
+    tile_first_block(ts.cu0, ti.tcol, q, ts.cr0);
+    ts.ct0 = (uint32_t)q;
+  }
+  return ts;
+}
+
+// Metadata byte offset, from the start of the workgroup tile's tile row, of unit
+// jl < kTile of the workgroup tile.  All quotients have small numerators (see
+// lane_block): a lane is at most kTile units past the uniform start.  kColumns:
+// one metadatum per element and column; the offset is that of the unit's first
+// element.
+template <uint32_t kTile, bool kColumns>
+__device__ __forceinline__ uint32_t tile_meta_offset(uint32_t jl, const TileIndex& ti, const TileStart& ts) {
+  if (ts.one_row) {  // wave-uniform: same matrix row and tile row as the start
+    if constexpr (kColumns) return (ts.cu0 + jl) * ti.unit_elems;
+    return ts.ct0 + lane_block<kTile>(ts.cr0 + jl, ti.tcol);
+  }
+  const uint32_t j = ts.cu0 + jl;
+  const uint32_t dr = lane_block<kTile>(j, ti.row);                 // matrix rows that start in between
+  const uint32_t dt = lane_block<kTile>(ts.rr0 + dr, ti.trow);      // tile rows that start in between
+  const uint32_t cu = j - dr * ti.row.size;                         // unit inside its own matrix row
+  if constexpr (kColumns) return dt * ti.meta_stride + cu * ti.unit_elems;
+  // same matrix row as the start: continue from its tile column; a later row restarts at column 0 (then cu <= jl)
+  const uint32_t ct = (dr ? 0u : ts.ct0) + lane_block<kTile>(dr ? cu : ts.cr0 + jl, ti.tcol);
+  return dt * ti.meta_stride + ct;
 }
 
 // The datum of block number `block` of the array behind `r`: a metadata byte, or

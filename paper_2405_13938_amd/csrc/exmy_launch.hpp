@@ -47,6 +47,14 @@ hipError_t emulate_blocks_dispatch(exmy_dtype_t dt, const BlockArgs& args, bool 
 bool encode_blocks_auto_fits(exmy_dtype_t dt, uint32_t block_groups);
 hipError_t encode_blocks_auto_dispatch(exmy_dtype_t dt, int W, const BlockArgs& args, hipStream_t stream);
 hipError_t block_max_exp_dispatch(exmy_dtype_t dt, const BlockArgs& args, bool scale, hipStream_t stream);
+// Blocks that are columns or 2-D tiles (args.ti is filled in by the dispatcher through
+// make_tile_index, in units of `unit_elems` elements).  tile_max_exp_dispatch clears
+// args.meta and then folds the maxima into it (two launches).
+TileIndex make_tile_index(const TileArgs& args, uint32_t unit_elems);
+hipError_t encode_tiles_dispatch(exmy_dtype_t dt, int W, const TileArgs& args, hipStream_t stream);
+hipError_t decode_tiles_dispatch(exmy_dtype_t dt, int W, const TileArgs& args, hipStream_t stream);
+hipError_t emulate_tiles_dispatch(exmy_dtype_t dt, const TileArgs& args, bool wide_format, hipStream_t stream);
+hipError_t tile_max_exp_dispatch(exmy_dtype_t dt, const TileArgs& args, hipStream_t stream);
 // Packing along rows (args.tiles is filled in by the dispatcher).
 hipError_t encode_rows_dispatch(exmy_dtype_t dt, int W, const RowsArgs& args, bool per_row, bool wide,
                                 hipStream_t stream);

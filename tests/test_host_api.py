@@ -294,3 +294,36 @@ def test_fp16_container_limits():
     assert L.exmy_encode_int(ok, B.F16, 0, 7, 142, ok, None) == 3      # -2^16 is not a half
     assert L.exmy_encode_int(ok, B.F16, 0, 7, 108, ok, None) == 3      # quantum 2^-25
     assert L.exmy_encode_int(ok, B.F16, 0, 12, 133, ok, None) == 2
+
+
+def test_tile_entry_points_validate_without_launch():
+    L = B.lib()
+    ok, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1008)
+    mx, enc, dec, emu = L.exmy_tile_max_exp, L.exmy_encode_tiles, L.exmy_decode_tiles, L.exmy_emulate_tiles
+    for rows, cols, tr, tc in ((9, 24, 4, 16), (4096, 4096, 128, 128), (64, 64, 64, 1), (0, 64, 8, 8), (5, 8, 100, 100)):
+        assert B.tile_count(rows, cols, tr, tc) == O.tile_count(rows, cols, tr, tc)
+    assert B.tile_count(8, 8, 0, 8) == 0
+    assert mx(ok, B.BF16, 0, 64, 8, 8, 3, 0, 0, ok, None) == 0
+    assert mx(ok, B.BF16, 8, 0, 8, 8, 3, 0, 0, ok, None) == 0
+    assert mx(ok, B.BF16, 8, 60, 8, 8, 3, 0, 0, ok, None) == 8            # cols not a multiple of 8
+    assert mx(ok, B.BF16, 8, (1 << 26) + 8, 8, 8, 3, 0, 0, ok, None) == 8
+    assert mx(ok, B.BF16, (1 << 31) + 1, 8, 8, 8, 3, 0, 0, ok, None) == 8
+    assert mx(ok, B.BF16, 8, 64, 8, 12, 3, 0, 0, ok, None) == 7           # tile width neither 1 nor a multiple of 8
+    assert mx(ok, B.BF16, 8, 64, 0, 8, 3, 0, 0, ok, None) == 7
+    assert mx(ok, B.BF16, 8, 64, 8, 0, 3, 0, 0, ok, None) == 7
+    assert mx(ok, B.BF16, 1 << 20, 1 << 21, 8, 8, 3, 0, 0, ok, None) == 4  # more than 2^40 elements
+    assert mx(None, B.BF16, 8, 64, 4, 8, 3, 0, 0, ok, None) == 1
+    assert mx(ok, B.BF16, 8, 64, 4, 8, 3, 0, 0, None, None) == 1
+    assert mx(ok, B.BF16, 8, 64, 4, 8, 3, 0, 0, odd, None) == 5           # the metadata array is 16-byte aligned too
+    assert mx(odd, B.BF16, 8, 64, 4, 8, 3, 0, 0, ok, None) == 5
+    assert mx(ok, B.BF16, 8, 64, 4, 8, 8, 0, 0, ok, None) == 2            # X = 8 has no per-block metadata
+    assert mx(ok, B.BF16, 8, 64, 4, 8, 3, 0, 2, ok, None) == 2            # no such scheme
+    assert mx(ok, B.BF16, 0, 64, 4, 8, 3, 9, 1, ok, None) == 2            # "after rounding" needs a valid Y
+    assert mx(ok, B.BF16, 0, 64, 4, 8, 3, 9, 0, ok, None) == 0            # "before rounding" ignores it
+    assert enc(ok, B.F32, 0, 64, 4, 8, 3, 13, ok, ok, None) == 2          # packed form stops at 16 bits
+    assert emu(ok, B.F32, 0, 64, 4, 8, 3, 13, ok, None) == 0
+    assert enc(ok, B.BF16, 8, 64, 4, 8, 3, 3, ok, None, None) == 1
+    assert dec(ok, B.BF16, 8, 64, 4, 8, 3, 3, ok, None, None) == 1
+    assert dec(ok, B.BF16, 8, 64, 4, 8, 3, 3, ok, odd, None) == 5
+    assert emu(ok, B.F16, 0, 64, 4, 8, 5, 2, ok, None) == 0
+    assert emu(ok, B.F16, 0, 64, 4, 8, 6, 2, ok, None) == 2
