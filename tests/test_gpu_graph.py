@@ -27,6 +27,10 @@ def test_codec_calls_inside_a_captured_graph():
     bpack = torch.empty(exmy.packed_bytes(big.numel(), X, Y), dtype=torch.uint8, device=DEV)
     bout = torch.empty_like(big)
     emu = torch.empty_like(big)
+    mat = xs[2].view(256, 256)  # blocks that are parts of columns: the metadata is cleared and then folded into
+    tmeta = torch.empty(exmy.tile_count(256, 256, 64, 1), dtype=torch.uint8, device=DEV)
+    tpack = torch.empty(exmy.packed_bytes(mat.numel(), X, Y), dtype=torch.uint8, device=DEV)
+    tout = torch.empty_like(mat)
 
     def work():
         enc.run()
@@ -35,6 +39,9 @@ def test_codec_calls_inside_a_captured_graph():
         exmy.decode_blocks(bpack, torch.bfloat16, big.numel(), block, X, Y, meta, out=bout)
         emu.copy_(big)
         exmy.emulate(emu, X, Y, me)
+        exmy.tile_max_exp(mat, 64, 1, X, out=tmeta)
+        exmy.encode_tiles(mat, 64, 1, X, Y, tmeta, out=tpack)
+        exmy.decode_tiles(tpack, torch.bfloat16, 256, 256, 64, 1, X, Y, tmeta, out=tout)
 
     work()  # eager once: loads the kernels outside the capture
     torch.cuda.synchronize()
@@ -49,8 +56,9 @@ def test_codec_calls_inside_a_captured_graph():
         # new contents in the same buffers, eager work of our own in between
         for i, x in enumerate(xs):
             x.copy_(synth.gaussian_bf16(x.numel(), std=0.02 * (replay + 1), seed=100 * replay + i).to(DEV))
-        for t in packs + outs + [bpack, bout, emu, meta]:
+        for t in packs + outs + [bpack, bout, emu, meta, tpack, tout]:
             t.zero_()
+        tmeta.fill_(255)  # stale maxima must not survive the replay
         torch.cuda.synchronize()
         graph.replay()
         torch.cuda.synchronize()
@@ -66,3 +74,9 @@ def test_codec_calls_inside_a_captured_graph():
         assert np.array_equal(bpack.cpu().numpy(), want), replay
         assert np.array_equal(synth.bits_numpy(bout), O.decode_blocks(want, O.BF16, big.numel(), block, X, Y, want_meta)), replay
         assert np.array_equal(synth.bits_numpy(emu), O.emulate(host, X, Y, me)), replay
+        host = synth.bits_numpy(mat).reshape(256, 256)
+        want_meta = O.tile_max_exp(host, 64, 1, X)
+        assert np.array_equal(tmeta.cpu().numpy(), want_meta), replay
+        want = O.encode_tiles(host, 64, 1, X, Y, want_meta)
+        assert np.array_equal(tpack.cpu().numpy(), want), replay
+        assert np.array_equal(synth.bits_numpy(tout), O.decode_tiles(want, O.BF16, 256, 256, 64, 1, X, Y, want_meta).reshape(-1)), replay

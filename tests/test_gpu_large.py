@@ -158,3 +158,59 @@ def test_row_packing_beyond_4g():
     flat = exmy.decode_blocks(exmy.encode_blocks(x.view(-1), cols, X, Y, meta), torch.bfloat16, rows * cols, cols, X, Y, meta)
     torch.cuda.synchronize()
     assert torch.equal(flat.view(torch.int16), back.view(-1).view(torch.int16))
+
+
+def test_tiles_and_columns_beyond_4g():
+    X, Y, W = 3, 3, 7
+    cols, tr, tc = 4096, 128, 128
+    rows = (1 << 20) + 128 + 40  # rows * cols > 2^32; the last tile row is ragged
+    n = rows * cols
+    x = synth.gaussian_bf16(n, std=0.05, seed=25, device=DEV).view(rows, cols)
+    x[::1031, ::67] *= 41.0  # spread the tile maxima over several binades
+    G = n // 8
+    ntc = cols // tc
+
+    def plane_slices(p, g0, g1):
+        out, po = [], 0
+        for s in plane_sizes(W):
+            out.append(p[po + g0 * s : po + g1 * s].cpu().numpy())
+            po += G * s
+        return np.concatenate(out)
+
+    meta = exmy.tile_max_exp(x, tr, tc, X)
+    packed = exmy.encode_tiles(x, tr, tc, X, Y, meta)
+    back = exmy.decode_tiles(packed, torch.bfloat16, rows, cols, tr, tc, X, Y, meta)
+    col_meta = exmy.tile_max_exp(x, rows, 1, X)
+    col_packed = exmy.encode_tiles(x, rows, 1, X, Y, col_meta)
+    col_back = exmy.decode_tiles(col_packed, torch.bfloat16, rows, cols, rows, 1, X, Y, col_meta)
+    torch.cuda.synchronize()
+    # the column maxima against a reduction by the tensor library (no Inf / NaN in this input)
+    top = x.abs().amax(dim=0).float()
+    want_cols = ((top.view(torch.int32) >> 23) & 0xFF).clamp(1 << X, 254).to(torch.uint8)
+    assert torch.equal(col_meta, want_cols)
+    cm = col_meta.cpu().numpy()
+    last = (rows // tr) * tr
+    # row shards on tile-row boundaries: the start, across element 2^32 (row 2^20) and the ragged end
+    for r0, r1 in ((0, 2 * tr), ((1 << 20) - tr, (1 << 20) + tr), (last - tr, rows)):
+        host = synth.bits_numpy(x[r0:r1]).reshape(r1 - r0, cols)
+        t0, t1 = r0 // tr, (r1 + tr - 1) // tr
+        want_meta = O.tile_max_exp(host, tr, tc, X)
+        assert np.array_equal(meta[t0 * ntc : t1 * ntc].cpu().numpy(), want_meta), (r0, r1)
+        want = O.encode_tiles(host, tr, tc, X, Y, want_meta, threads=THREADS)
+        g0, g1 = r0 * cols // 8, r1 * cols // 8
+        assert np.array_equal(plane_slices(packed, g0, g1), want), (r0, r1)
+        want_dec = O.decode_tiles(want, O.BF16, r1 - r0, cols, tr, tc, X, Y, want_meta, threads=THREADS)
+        assert np.array_equal(synth.bits_numpy(back[r0:r1]), want_dec.reshape(-1)), (r0, r1)
+        # whole columns: every row shard uses the same per-column metadata
+        want = O.encode_tiles(host, r1 - r0, 1, X, Y, cm, threads=THREADS)
+        assert np.array_equal(plane_slices(col_packed, g0, g1), want), (r0, r1)
+        want_dec = O.decode_tiles(want, O.BF16, r1 - r0, cols, r1 - r0, 1, X, Y, cm, threads=THREADS)
+        assert np.array_equal(synth.bits_numpy(col_back[r0:r1]), want_dec.reshape(-1)), (r0, r1)
+    # everywhere: emulate == decode(encode) for these finite inputs
+    emu = exmy.emulate_tiles(x.clone(), tr, tc, X, Y, meta)
+    torch.cuda.synchronize()
+    assert torch.equal(emu.view(torch.int16), back.view(torch.int16))
+    del emu, back
+    emu = exmy.emulate_tiles(x.clone(), rows, 1, X, Y, col_meta)
+    torch.cuda.synchronize()
+    assert torch.equal(emu.view(torch.int16), col_back.view(torch.int16))
