@@ -124,7 +124,7 @@ int check_format(int dt, int X, int Y, int max_exp, bool packed, Format* f) {
   if (dt == ORACLE_F16 && X > 5) return ORACLE_ERR_FORMAT;  // Section 2.1: fp16 emulates X <= 5, Y <= 10
   const int P = container_mantissa(dt);
   if (X >= 1 ? (Y > P) : (Y > P + 1)) return ORACLE_ERR_FORMAT;
-  if (packed && 1 + X + Y > 31) return ORACLE_ERR_FORMAT;  // segments of 16, 8, 4, 2 and 1 bits reach 31
+  if (packed && 1 + X + Y > 32) return ORACLE_ERR_FORMAT;  // segments of 32, 16, 8, 4, 2 and 1 bits; 32 is e8m23 alone
   if (packed && Y > 23) return ORACLE_ERR_FORMAT;          // e0m24 packs as e1m23, which it equals bit for bit
   if (X == 8) {
     if (max_exp != 255) return ORACLE_ERR_MAX_EXP;
@@ -269,7 +269,7 @@ uint32_t decode_one(const Format& f, uint32_t code) {
 // (Section 2.2.2: 7 = 4 + 2 + 1, 5 = 4 + 1).
 int plane_list(int W, int seg[8]) {
   int n = 0;
-  for (int s = 16; s >= 1; s >>= 1)
+  for (int s = 32; s >= 1; s >>= 1)
     if (W & s) seg[n++] = s;
   return n;
 }
@@ -306,7 +306,7 @@ void pack_groups(const uint32_t* codes, uint64_t base, uint64_t n, int W, uint8_
       for (int j = 0; j < 8; ++j) {
         const uint64_t i = g * 8 + j;
         const uint32_t code = i < n ? codes[i - base] : 0u;
-        const uint32_t field = (code >> lo) & ((1u << s) - 1u);
+        const uint32_t field = (uint32_t)(((uint64_t)code >> lo) & (((uint64_t)1 << s) - 1u));
         for (int b = 0; b < s; ++b) {
           const int bit = s * j + b;
           if ((field >> b) & 1u) plane[g * s + bit / 8] |= (uint8_t)(1u << (bit % 8));
@@ -395,14 +395,14 @@ int exmy_oracle_from_codes(const uint32_t* codes, int dt, uint64_t n, int X, int
 // Step 2 of the codec (Section 2.2.2): W-bit codes -> planes.
 int exmy_oracle_pack(const uint32_t* codes, uint64_t n, int W, uint8_t* out, int threads) {
   if ((!codes || !out) && n) return ORACLE_ERR_NULL;
-  if (W < 1 || W > 31) return ORACLE_ERR_FORMAT;
+  if (W < 1 || W > 32) return ORACLE_ERR_FORMAT;
   parallel_ranges((n + 7) / 8, threads, [&](uint64_t a, uint64_t b) { pack_groups(codes, 0, n, W, out, a, b); });
   return ORACLE_OK;
 }
 
 int exmy_oracle_unpack(const uint8_t* in, uint64_t n, int W, uint32_t* codes, int threads) {
   if ((!codes || !in) && n) return ORACLE_ERR_NULL;
-  if (W < 1 || W > 31) return ORACLE_ERR_FORMAT;
+  if (W < 1 || W > 32) return ORACLE_ERR_FORMAT;
   parallel_ranges((n + 7) / 8, threads, [&](uint64_t a, uint64_t b) { unpack_groups(in, n, W, codes, 0, a, b); });
   return ORACLE_OK;
 }

@@ -10,7 +10,7 @@ from paper_2405_13938_amd import synth
 
 
 def plane_sizes(W):
-    return [s for s in (16, 8, 4, 2, 1) if W & s]
+    return [s for s in (32, 16, 8, 4, 2, 1) if W & s]
 
 
 def test_paper_plane_sizes(golden):
@@ -22,18 +22,18 @@ def test_paper_plane_sizes(golden):
         assert O.pack(codes, W).size == W
 
 
-@pytest.mark.parametrize("W", range(1, 32))
+@pytest.mark.parametrize("W", range(1, 33))
 def test_roundtrip_and_size(W):
     rng = np.random.default_rng(W)
     for n in (0, 1, 7, 8, 9, 64, 1000, 4099):
-        codes = rng.integers(0, 1 << W, size=n, dtype=np.uint32)
+        codes = rng.integers(0, 1 << W, size=n, dtype=np.uint64).astype(np.uint32)
         p = O.pack(codes, W)
         assert p.size == ((n + 7) // 8) * W == O.packed_bytes(n, 0, W - 1)
         assert np.array_equal(O.unpack(p, n, W), codes)
         assert np.array_equal(O.pack(codes, W, threads=3), p)
 
 
-@pytest.mark.parametrize("W", [3, 5, 6, 7, 9, 12, 16, 17, 23, 31])
+@pytest.mark.parametrize("W", [3, 5, 6, 7, 9, 12, 16, 17, 23, 31, 32])
 def test_walking_one_bit_positions(W):
     """Code bit b of element j lands in exactly one bit of the blob: plane of the segment
     that owns b (widest plane owns the lowest bits), group word g, bit s*j + (b - lo)."""
@@ -123,3 +123,27 @@ def test_threads_do_not_change_results():
     assert np.array_equal(a, O.encode(x, 4, 2, 125, threads=5))
     assert np.array_equal(O.decode(a, O.F32, x.size, 4, 2, 125, threads=1), O.decode(a, O.F32, x.size, 4, 2, 125, threads=5))
     assert np.array_equal(O.emulate(x, 4, 2, 125, threads=1), O.emulate(x, 4, 2, 125, threads=5))
+
+
+def test_e8m23_packs_to_the_float_itself():
+    """W = 32 is e8m23 alone, the fp32 layout (Table 1 lists e8mY as fp32 / bf16 with fewer mantissa bits):
+    one 32-bit segment, so the blob is the array of codes, and a finite float's code is its own bit pattern
+    (max_exp 255: identity exponent map, denormals are the format's subnormals).  Inf / NaN clamp to the
+    largest finite code under their sign."""
+    rng = np.random.default_rng(5)
+    bits = rng.integers(0, 1 << 32, size=4099, dtype=np.uint64).astype(np.uint32)
+    bits[:8] = [0, 0x80000000, 1, 0x807FFFFF, 0x7F7FFFFF, 0xFF7FFFFF, 0x00800000, 0x3F800000]
+    finite = (bits & 0x7F800000) != 0x7F800000
+    blob = O.encode(bits.view(np.float32), 8, 23, 255)
+    assert blob.size == ((bits.size + 7) // 8) * 32
+    codes = blob.view(np.uint32)[: bits.size]
+    assert np.array_equal(codes[finite], bits[finite])
+    assert np.array_equal(codes[~finite], (bits[~finite] & 0x80000000) | 0x7F7FFFFF)
+    assert not blob.view(np.uint32)[bits.size :].any()  # zero codes pad the last group
+    back = O.decode(blob, O.F32, bits.size, 8, 23, 255).view(np.uint32)
+    assert np.array_equal(back, codes)
+    # a code with exponent field 255 is not a value: it decodes to the largest finite value
+    odd = np.array([0x7F800000, 0xFFC00001, 0x7FFFFFFF, 0x3F800000] * 2, dtype=np.uint32)
+    assert O.decode(odd.view(np.uint8), O.F32, 8, 8, 23, 255).view(np.uint32).tolist() == [0x7F7FFFFF, 0xFF7FFFFF, 0x7F7FFFFF, 0x3F800000] * 2
+    with pytest.raises(Exception):
+        O.encode(bits.view(np.float32), 8, 23, 254)

@@ -363,8 +363,8 @@ def test_format_validation():
     assert O.check_format(BF16, 0, 9, 130) != 0
     assert O.check_format(F32, 9, 0, 130) != 0
     assert O.check_format(F32, 4, 12, 130) == 0  # W = 17 = 16 + 1 packs
-    assert O.check_format(F32, 8, 22, 255) == 0  # W = 31 = 16 + 8 + 4 + 2 + 1, the widest packed form
-    assert O.check_format(F32, 8, 23, 255) != 0  # W = 32 would need a 32-bit segment
+    assert O.check_format(F32, 8, 22, 255) == 0  # W = 31 = 16 + 8 + 4 + 2 + 1
+    assert O.check_format(F32, 8, 23, 255) == 0  # W = 32: one 32-bit segment, the widest packed form
     assert O.check_format(F32, 8, 23, 255, packed=False) == 0
     assert O.check_format(F32, 8, 3, 254) != 0 and O.check_format(F32, 8, 3, 255) == 0
     assert O.check_format(F32, 3, 3, 6) != 0 and O.check_format(F32, 3, 3, 7) == 0
