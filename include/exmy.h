@@ -31,8 +31,10 @@
  *    per-block metadata bytes are read as the nearest value of that narrower
  *    range; the exponent histogram of fp16 data bins the exponent of the value
  *    as an fp32.  Packed codes
- *    are limited to W <= 31 (segments of 16, 8, 4, 2 and 1 bits; widths above
- *    16 need the fp32 container) in exmy_encode / exmy_decode and their batch
+ *    are limited to W <= 32 (segments of 16, 8, 4, 2 and 1 bits; widths above
+ *    16 need the fp32 container; 32 is e8m23 alone, one 32-bit segment: the
+ *    packed form is then the array of codes, which are the elements' own bits
+ *    with Inf / NaN clamped) in exmy_encode / exmy_decode and their batch
  *    and histogram forms, and to W <= 16 in the per-block, float-scaling and
  *    row-packing entry points.  e0m24 has no packed form (use e1m23, which it
  *    equals bit for bit).
@@ -90,7 +92,7 @@ typedef enum {
 size_t exmy_packed_bytes(uint64_t n, int X, int Y);
 
 /* Host-side validation of (dtype, X, Y, max_exp) as described above.  `packed`
- * non-zero also applies the W <= 31 limit of the packed form. */
+ * non-zero also applies the W <= 32 limit of the packed form. */
 exmy_status_t exmy_check_format(exmy_dtype_t dt, int X, int Y, int max_exp, int packed);
 
 /* Encode (Sections 2.2.1 + 2.2.2 fused): round n elements of type dt at `src`

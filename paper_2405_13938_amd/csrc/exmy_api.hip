@@ -216,9 +216,16 @@ exmy_status_t run_batch(Op op, const exmy_tensor_t* tensors, size_t count, exmy_
   uint64_t hi = 0;  // largest element count in the pending launch
   auto flush = [&]() -> hipError_t {
     if (args.count == 0) return hipSuccess;
-    const hipError_t e = op == Op::kEncode
-                             ? encode_dispatch(dt, W, any_wide, with_hist, args, hi, static_cast<hipStream_t>(stream))
-                             : decode_dispatch(dt, W, X == 8, args, hi, static_cast<hipStream_t>(stream));
+    const hipStream_t s = static_cast<hipStream_t>(stream);
+    hipError_t e;
+    if (W == 32) {  // e8m23: no planes to form; a histogram asked for alongside takes its own pass
+      e = codes32_dispatch(op == Op::kDecode, args, hi, s);
+      for (int k = 0; with_hist && e == hipSuccess && k < args.count; ++k)
+        e = histogram_dispatch(dt, args.t[k].src, args.t[k].n, hist, s);
+    } else {
+      e = op == Op::kEncode ? encode_dispatch(dt, W, any_wide, with_hist, args, hi, s)
+                            : decode_dispatch(dt, W, X == 8, args, hi, s);
+    }
     args.count = 0;
     return e;
   };

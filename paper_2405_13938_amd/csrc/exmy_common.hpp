@@ -185,7 +185,7 @@ inline BlockIndex make_block_index(uint64_t size) {
   return bi;
 }
 
-constexpr int kFlatWidth = 31;   // segments of 16, 8, 4, 2 and 1 bits
+constexpr int kFlatWidth = 32;   // segments of 16, 8, 4, 2 and 1 bits; 32 is e8m23, the array of codes itself
 constexpr int kBlockWidth = 16;
 constexpr int kAnyWidth = 64;
 

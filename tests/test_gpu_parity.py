@@ -49,7 +49,7 @@ def check_all(x_dev, X, Y, max_exp, host=None, what=("encode", "decode", "emulat
         host = synth.bits_numpy(x_dev)
     dt = odt(x_dev)
     label = "e%dm%d max_exp=%d n=%d %s" % (X, Y, max_exp, n, x_dev.dtype)
-    if 1 + X + Y <= 31 and Y <= 23 and ("encode" in what or "decode" in what):
+    if 1 + X + Y <= 32 and Y <= 23 and ("encode" in what or "decode" in what):
         want_packed = O.encode(host, X, Y, max_exp, threads=THREADS)
         if "encode" in what:
             got = exmy.encode(x_dev.reshape(-1), X, Y, max_exp)
@@ -129,9 +129,25 @@ def test_sampled_code_points_of_wide_formats_decode(W):
             assert np.array_equal(tbits(got), ubits(O.from_codes(codes, O.F32, X, Y, max_exp))), (W, X, Y, max_exp)
 
 
+def test_e8m23_is_the_array_of_codes():
+    """W = 32: finite elements are their own codes; Inf / NaN and codes with exponent field 255 clamp."""
+    for n in (0, 3, 8, 4099, (1 << 20) + 5):
+        x, _ = synth.cfg1(n=max(n, 16), seed=n)
+        x = x[:n].contiguous().to(DEV)
+        host = synth.bits_numpy(x)
+        packed = exmy.encode(x, 8, 23, 255)
+        torch.cuda.synchronize()
+        assert np.array_equal(packed.cpu().numpy(), O.encode(host, 8, 23, 255, threads=THREADS)), n
+        rng = np.random.default_rng(n)
+        codes = rng.integers(0, 1 << 32, size=(n + 7) // 8 * 8, dtype=np.uint64).astype(np.uint32)
+        got = exmy.decode(torch.from_numpy(codes.view(np.uint8)).to(DEV), torch.float32, n, 8, 23, 255)
+        torch.cuda.synchronize()
+        assert np.array_equal(tbits(got), ubits(O.decode(codes.view(np.uint8), O.F32, n, 8, 23, 255, threads=THREADS))), n
+
+
 def test_wide_formats_batch_and_histogram():
     xs = [synth.cfg1(n=(1 << 18) + 8 * k + k, seed=k)[0].to(DEV) for k in range(5)]
-    for X, Y in ((8, 10), (5, 14), (4, 23), (8, 22)):
+    for X, Y in ((8, 10), (5, 14), (4, 23), (8, 22), (8, 23)):
         me = 255 if X == 8 else 131
         outs = exmy.encode_batch(xs, X, Y, [me] * 5)
         torch.cuda.synchronize()

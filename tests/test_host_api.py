@@ -61,8 +61,9 @@ def test_error_codes_without_launch():
     assert L.exmy_encode(ok_ptr, 7, 8, 3, 3, 130, ok_ptr, None) == 2
     assert L.exmy_encode(ok_ptr, B.BF16, 8, 3, 8, 130, ok_ptr, None) == 2  # bf16 cannot hold 8 mantissa bits
     assert L.exmy_encode(ok_ptr, B.F32, 0, 4, 12, 130, ok_ptr, None) == 0  # W = 17 packs (fp32 only)
-    assert L.exmy_encode(ok_ptr, B.F32, 0, 8, 22, 255, ok_ptr, None) == 0  # W = 31, the widest packed form
-    assert L.exmy_encode(ok_ptr, B.F32, 8, 8, 23, 255, ok_ptr, None) == 2  # W = 32 does not
+    assert L.exmy_encode(ok_ptr, B.F32, 0, 8, 22, 255, ok_ptr, None) == 0  # W = 31
+    assert L.exmy_encode(ok_ptr, B.F32, 0, 8, 23, 255, ok_ptr, None) == 0  # W = 32, the widest packed form
+    assert L.exmy_encode(ok_ptr, B.F32, 0, 8, 23, 254, ok_ptr, None) == 3
     assert L.exmy_emulate(ok_ptr, B.F32, 0, 8, 23, 255, None) == 0  # emulate has no width limit
     assert L.exmy_encode(ok_ptr, B.F32, 8, 3, 3, 6, ok_ptr, None) == 3
     assert L.exmy_decode(ok_ptr, B.F32, 8, 8, 3, 254, ok_ptr, None) == 3
