@@ -437,6 +437,65 @@ int exmy_oracle_decode(const uint8_t* src_packed, int dt, uint64_t n, int X, int
   return ORACLE_OK;
 }
 
+// ---------------------------------------------------------------------------
+// Records: a second arrangement of the same plane words.  Section 2.2.2 keeps one
+// array per power-of-2 segment; here the words of one group follow each other,
+// widest segment first, as one record of W bytes ("8 values in W bytes"), and the
+// records follow each other in group order.  Not a layout of the paper: the words
+// are those of Fig. 2, only their order in memory differs.  Widths up to 16.
+static void records_op(bool pack, uint32_t* codes, uint64_t n, int W, uint8_t* blob) {
+  const uint64_t G = (n + 7) / 8;
+  int seg[8];
+  const int np = plane_list(W, seg);
+  for (uint64_t g = 0; g < G; ++g) {
+    uint8_t* rec = blob + g * (uint64_t)W;
+    if (pack)
+      for (int b = 0; b < W; ++b) rec[b] = 0;
+    int word_off = 0;  // byte offset of the segment's word inside the record
+    int lo = 0;        // first code bit of the segment
+    for (int p = 0; p < np; ++p) {
+      const int s = seg[p];
+      for (int j = 0; j < 8; ++j) {
+        const uint64_t i = g * 8 + j;
+        for (int b = 0; b < s; ++b) {
+          const int bit = s * j + b;  // element j at bits [s*j, s*j + s) of the little-endian word
+          uint8_t* byte = rec + word_off + bit / 8;
+          if (pack) {
+            const uint32_t code = i < n ? codes[i] : 0u;
+            if ((code >> (lo + b)) & 1u) *byte |= (uint8_t)(1u << (bit % 8));
+          } else if (i < n) {
+            if ((*byte >> (bit % 8)) & 1u) codes[i] |= 1u << (lo + b);
+          }
+        }
+      }
+      word_off += s;
+      lo += s;
+    }
+  }
+}
+
+int exmy_oracle_encode_records(const void* src, int dt, uint64_t n, int X, int Y, int max_exp, uint8_t* dst_records) {
+  if ((!src || !dst_records) && n) return ORACLE_ERR_NULL;
+  Format f;
+  if (int rc = check_format(dt, X, Y, max_exp, true, &f)) return rc;
+  if (f.W > 16) return ORACLE_ERR_FORMAT;
+  std::vector<uint32_t> codes(n);
+  for (uint64_t i = 0; i < n; ++i) codes[i] = encode_one(f, load_bits(src, dt, i));
+  records_op(true, codes.data(), n, f.W, dst_records);
+  return ORACLE_OK;
+}
+
+int exmy_oracle_decode_records(const uint8_t* src_records, int dt, uint64_t n, int X, int Y, int max_exp, void* dst) {
+  if ((!src_records || !dst) && n) return ORACLE_ERR_NULL;
+  Format f;
+  if (int rc = check_format(dt, X, Y, max_exp, true, &f)) return rc;
+  if (f.W > 16) return ORACLE_ERR_FORMAT;
+  std::vector<uint32_t> codes(n, 0u);
+  records_op(false, codes.data(), n, f.W, const_cast<uint8_t*>(src_records));
+  for (uint64_t i = 0; i < n; ++i) store_bits(dst, dt, i, decode_one(f, codes[i]));
+  return ORACLE_OK;
+}
+
 // Emulation (Section 2.1): quantise and dequantise in the element's own type;
 // NaN and +-Inf are returned bit-identical.
 int exmy_oracle_emulate(void* data, int dt, uint64_t n, int X, int Y, int max_exp, int threads) {

@@ -38,6 +38,8 @@ def lib():
         L.exmy_oracle_decode.argtypes = [vp, i32, u64, i32, i32, i32, vp, i32]
         L.exmy_oracle_emulate.argtypes = [vp, i32, u64, i32, i32, i32, i32]
         L.exmy_oracle_exponent_histogram.argtypes = [vp, i32, u64, vp]
+        L.exmy_oracle_encode_records.argtypes = [vp, i32, u64, i32, i32, i32, vp]
+        L.exmy_oracle_decode_records.argtypes = [vp, i32, u64, i32, i32, i32, vp]
         L.exmy_oracle_block_max_exp.argtypes = [vp, i32, u64, u64, i32, vp]
         L.exmy_oracle_block_max_exp_after_rounding.argtypes = [vp, i32, u64, u64, i32, i32, vp]
         L.exmy_oracle_encode_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, i32]
@@ -157,6 +159,22 @@ def decode(packed, dt, n, X, Y, max_exp, threads=1):
     assert packed.size == packed_bytes(n, X, Y)
     out = np.empty(n, dtype=_out_dtype(dt))
     _check(lib().exmy_oracle_decode(_ptr(packed), dt, n, X, Y, max_exp, _ptr(out), threads))
+    return out
+
+
+def encode_records(src, X, Y, max_exp):
+    """The plane words of each group as one record of W bytes, records in group order."""
+    a, dt = _src(src)
+    out = np.empty(packed_bytes(a.size, X, Y), dtype=np.uint8)
+    _check(lib().exmy_oracle_encode_records(_ptr(a), dt, a.size, X, Y, max_exp, _ptr(out)))
+    return out
+
+
+def decode_records(records, dt, n, X, Y, max_exp):
+    records = np.ascontiguousarray(records, dtype=np.uint8)
+    assert records.size == packed_bytes(n, X, Y)
+    out = np.empty(n, dtype=_out_dtype(dt))
+    _check(lib().exmy_oracle_decode_records(_ptr(records), dt, n, X, Y, max_exp, _ptr(out)))
     return out
 
 
