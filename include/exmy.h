@@ -208,6 +208,24 @@ exmy_status_t exmy_encode_blocks_auto(const void* src, exmy_dtype_t dt, uint64_t
                                       exmy_scheme_t scheme, uint8_t* max_exp_dev, void* dst_packed, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * Records: the plane words of Section 2.2.2 / Fig. 2 in another order.  The
+ * words of one group follow each other, widest segment first, as one record of
+ * W = 1 + X + Y bytes, and the records follow each other in group order: for
+ * W = 7, bytes 0-3 of record g are the int32 word of the group's low nibbles,
+ * bytes 4-5 its int16 word, byte 6 its int8 word ("8 values in 7 bytes").  One
+ * stream instead of one per segment; the shard [a, b) of the elements (a, b
+ * multiples of 8) is the byte range [a / 8 * W, b / 8 * W).  This is not a
+ * layout of the paper; the words are the paper's.  Size exmy_packed_bytes(n, X,
+ * Y); W <= 16 (for W = 8 and 16, which have one segment, records and planes
+ * coincide); everything else (formats, max_exp, rounding, Inf / NaN, n not a
+ * multiple of 8, pointers, alignment, errors, stream) as exmy_encode /
+ * exmy_decode. */
+exmy_status_t exmy_encode_records(const void* src, exmy_dtype_t dt, uint64_t n, int X, int Y, int max_exp,
+                                  void* dst_records, void* stream);
+exmy_status_t exmy_decode_records(const void* src_records, exmy_dtype_t dt_out, uint64_t n, int X, int Y, int max_exp,
+                                  void* dst, void* stream);
+
+/* ---------------------------------------------------------------------------
  * Blocks that are columns or 2-D tiles (Section 2 "Block Size": a block can be
  * a tensor, a row, a column, a sub row or a 2-D tile).
  *

@@ -31,6 +31,8 @@ SYMBOLS = [
     "exmy_encode_blocks",
     "exmy_decode_blocks",
     "exmy_emulate_blocks",
+    "exmy_encode_records",
+    "exmy_decode_records",
     "exmy_tile_count",
     "exmy_tile_max_exp",
     "exmy_encode_tiles",
@@ -109,6 +111,10 @@ def lib():
         L.exmy_decode_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, vp]
         L.exmy_emulate_blocks.restype = i32
         L.exmy_emulate_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp]
+        L.exmy_encode_records.restype = i32
+        L.exmy_encode_records.argtypes = [vp, i32, u64, i32, i32, i32, vp, vp]
+        L.exmy_decode_records.restype = i32
+        L.exmy_decode_records.argtypes = [vp, i32, u64, i32, i32, i32, vp, vp]
         L.exmy_tile_count.restype = ctypes.c_size_t
         L.exmy_tile_count.argtypes = [u64, u64, u64, u64]
         L.exmy_tile_max_exp.restype = i32
@@ -425,6 +431,40 @@ def emulate_blocks(data, block, X, Y, max_exps):
     _check(lib().exmy_emulate_blocks(data.data_ptr(), _dtype_enum(data), data.numel(), block, X, Y,
                                      max_exps.data_ptr(), _stream()))
     return data
+
+
+# ------------------------------------------------------------ records (W bytes per group)
+
+
+def encode_records(src, X, Y, max_exp, out=None):
+    """exmy_encode_records: returns the uint8 tensor of records (``out`` if given)."""
+    _device_tensor(src, "src")
+    n = src.numel()
+    nbytes = packed_bytes(n, X, Y)
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.uint8, device=src.device)
+    else:
+        _device_tensor(out, "out")
+        if out.dtype != torch.uint8 or out.numel() != nbytes:
+            raise ValueError("exmy: out must be uint8 with %d elements" % nbytes)
+    _check(lib().exmy_encode_records(src.data_ptr(), _dtype_enum(src), n, X, Y, max_exp, out.data_ptr(), _stream()))
+    return out
+
+
+def decode_records(records, dtype, n, X, Y, max_exp, out=None):
+    """exmy_decode_records: returns a flat tensor of ``n`` values of ``dtype``."""
+    _device_tensor(records, "records")
+    tdt = _torch_dtype(dtype)
+    if records.dtype != torch.uint8 or records.numel() != packed_bytes(n, X, Y):
+        raise ValueError("exmy: records must be uint8 with %d elements" % packed_bytes(n, X, Y))
+    if out is None:
+        out = torch.empty(n, dtype=tdt, device=records.device)
+    else:
+        _device_tensor(out, "out")
+        if out.dtype != tdt or out.numel() != n:
+            raise ValueError("exmy: out must be %s with %d elements" % (tdt, n))
+    _check(lib().exmy_decode_records(records.data_ptr(), _dtype_enum(out), n, X, Y, max_exp, out.data_ptr(), _stream()))
+    return out
 
 
 # ------------------------------------------------------------ blocks that are columns or 2-D tiles

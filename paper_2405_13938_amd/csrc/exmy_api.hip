@@ -490,6 +490,36 @@ exmy_status_t exmy_exponent_histogram(const void* src, exmy_dtype_t dt, uint64_t
   return e == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
 }
 
+namespace {
+exmy_status_t run_records(bool decode, const void* src, void* dst, exmy_dtype_t dt, uint64_t n, int X, int Y,
+                          int max_exp, void* stream) {
+  FormatConsts fc;
+  TensorConsts tc;
+  bool wide = false;
+  if (exmy_status_t st = make_format(dt, X, Y, max_exp, kBlockWidth, &fc, &tc, &wide)) return st;
+  if (n > EXMY_MAX_ELEMENTS) return EXMY_ERR_COUNT;
+  if (n == 0) return EXMY_OK;
+  if (!src || !dst) return EXMY_ERR_NULL;
+  if (!aligned16(src) || !aligned16(dst)) return EXMY_ERR_ALIGN;
+  const int W = 1 + X + Y;
+  if (W == 8 || W == 16)  // one plane: the records are the planar form
+    return decode ? exmy_decode(src, dt, n, X, Y, max_exp, dst, stream) : exmy_encode(src, dt, n, X, Y, max_exp, dst, stream);
+  const hipError_t e = records_dispatch(dt, W, decode, decode ? X == 8 : wide, src, dst, n, fc, tc,
+                                        static_cast<hipStream_t>(stream));
+  return e == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
+}
+}  // namespace
+
+exmy_status_t exmy_encode_records(const void* src, exmy_dtype_t dt, uint64_t n, int X, int Y, int max_exp,
+                                  void* dst_records, void* stream) {
+  return run_records(false, src, dst_records, dt, n, X, Y, max_exp, stream);
+}
+
+exmy_status_t exmy_decode_records(const void* src_records, exmy_dtype_t dt_out, uint64_t n, int X, int Y, int max_exp,
+                                  void* dst, void* stream) {
+  return run_records(true, src_records, dst, dt_out, n, X, Y, max_exp, stream);
+}
+
 size_t exmy_block_count(uint64_t n, uint64_t block) { return block ? (size_t)((n + block - 1) / block) : 0; }
 
 size_t exmy_tile_count(uint64_t rows, uint64_t cols, uint64_t tile_rows, uint64_t tile_cols) {

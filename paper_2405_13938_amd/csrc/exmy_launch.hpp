@@ -34,6 +34,10 @@ hipError_t encode_dispatch(exmy_dtype_t dt, int W, bool wide, bool with_hist, co
                            hipStream_t stream);
 hipError_t decode_dispatch(exmy_dtype_t dt, int W, bool x8, const BatchArgs& args, uint64_t n_max,
                            hipStream_t stream);
+// Record layout (the plane words of a group as W consecutive bytes), W <= 16 except 8 and 16, whose
+// records are the planar form.  flag: encode - the fp64 rounding path; decode - X = 8.
+hipError_t records_dispatch(exmy_dtype_t dt, int W, bool decode, bool flag, const void* src, void* dst, uint64_t n,
+                            const FormatConsts& fc, const TensorConsts& tc, hipStream_t stream);
 // W = 32 (e8m23 on fp32): the packed form is the array of codes; encode and decode clamp Inf / NaN patterns.
 hipError_t codes32_dispatch(bool decode, const BatchArgs& args, uint64_t n_max, hipStream_t stream);
 hipError_t emulate_dispatch(exmy_dtype_t dt, bool wide, void* data, uint64_t n, const FormatConsts& fc,

@@ -328,3 +328,19 @@ def test_tile_entry_points_validate_without_launch():
     assert dec(ok, B.BF16, 8, 64, 4, 8, 3, 3, ok, odd, None) == 5
     assert emu(ok, B.F16, 0, 64, 4, 8, 5, 2, ok, None) == 0
     assert emu(ok, B.F16, 0, 64, 4, 8, 6, 2, ok, None) == 2
+
+
+def test_record_entry_points_validate_without_launch():
+    L = B.lib()
+    ok, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1008)
+    enc, dec = L.exmy_encode_records, L.exmy_decode_records
+    for f in (enc, dec):
+        assert f(ok, B.BF16, 0, 3, 3, 130, ok, None) == 0
+        assert f(None, B.BF16, 8, 3, 3, 130, ok, None) == 1
+        assert f(ok, B.BF16, 8, 3, 3, 130, None, None) == 1
+        assert f(odd, B.BF16, 8, 3, 3, 130, ok, None) == 5
+        assert f(ok, B.BF16, 8, 3, 3, 130, odd, None) == 5
+        assert f(ok, B.F32, 0, 4, 12, 130, ok, None) == 2   # records stop at 16 bits
+        assert f(ok, B.F32, 0, 5, 10, 130, ok, None) == 0
+        assert f(ok, B.BF16, 0, 3, 3, 6, ok, None) == 3
+        assert f(ok, B.BF16, (1 << 40) + 8, 3, 3, 130, ok, None) == 4
