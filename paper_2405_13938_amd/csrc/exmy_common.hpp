@@ -357,6 +357,14 @@ __device__ __forceinline__ int32_t max_over_lanes(int32_t m, uint32_t lg) {
   return m;
 }
 
+// Units of workgroup tile `tile` when `full_tiles` whole tiles of kTile units are followed by one of `rem`
+// units.  Kept in 32-bit scalar compares on purpose: the same bookkeeping written as a 64-bit
+// "left < kTile ? left : kTile" followed by a branch on the result was seen to be compiled into a select on
+// a stale condition code by this toolchain (the partial tile then ran as a whole one).
+__device__ __forceinline__ uint32_t units_in_tile(uint32_t tile, uint32_t full_tiles, uint32_t rem, uint32_t kTile) {
+  return tile < full_tiles ? kTile : (tile == full_tiles ? rem : 0u);
+}
+
 // First block touched by the tile whose first unit is w0, and w0's offset inside it.
 __device__ __forceinline__ void tile_first_block(uint64_t w0, const BlockIndex& bi, uint64_t& blk0, uint32_t& off) {
   if (bi.log2 != kNotPow2) {

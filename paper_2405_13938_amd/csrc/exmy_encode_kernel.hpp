@@ -84,61 +84,132 @@ __device__ __forceinline__ void make_plane_dst(uint8_t* dst, uint64_t G, uint64_
   }
 }
 
-// Write one plane word: the S-bit fields that sit at the TOP of t[0..7], element
-// j at bits [S*j, S*j + S) of the little-endian plane word (Fig. 2).  The word
-// goes to byte lane_group * S + tile_off of the plane descriptor.
+// The S * 8 bits of one plane word from the S-bit fields that sit at the TOP of
+// t[0..7], element j at bits [S*j, S*j + S) of the little-endian plane word (Fig. 2):
+// out[0 .. S/4) for S >= 4, else the low 2 or 1 bytes of out[0].
 template <int S>
-__device__ __forceinline__ void store_plane_from_top(const uint32_t t[8], rsrc_t plane, uint32_t lane_group,
-                                                     uint32_t tile_off) {
-  const uint32_t voff = lane_group * S;
+__device__ __forceinline__ void plane_word_from_top(const uint32_t t[8], uint32_t out[4]) {
   if constexpr (S == 16) {
-    uint4 o;
-    o.x = append_top(t[1] >> 16, t[0], 16);
-    o.y = append_top(t[3] >> 16, t[2], 16);
-    o.z = append_top(t[5] >> 16, t[4], 16);
-    o.w = append_top(t[7] >> 16, t[6], 16);
-    store16<false>(plane, voff, tile_off, o);
+    out[0] = append_top(t[1] >> 16, t[0], 16);
+    out[1] = append_top(t[3] >> 16, t[2], 16);
+    out[2] = append_top(t[5] >> 16, t[4], 16);
+    out[3] = append_top(t[7] >> 16, t[6], 16);
   } else if constexpr (S == 8) {
-    u32x2_t o;
-    o.x = append_top(append_top(append_top(t[3] >> 24, t[2], 8), t[1], 8), t[0], 8);
-    o.y = append_top(append_top(append_top(t[7] >> 24, t[6], 8), t[5], 8), t[4], 8);
-    __builtin_amdgcn_raw_buffer_store_b64(o, plane, voff, tile_off, 0);
+    out[0] = append_top(append_top(append_top(t[3] >> 24, t[2], 8), t[1], 8), t[0], 8);
+    out[1] = append_top(append_top(append_top(t[7] >> 24, t[6], 8), t[5], 8), t[4], 8);
   } else {
     uint32_t word = t[7] >> (32 - S);
 #pragma unroll
     for (int j = 6; j >= 0; --j) word = append_top(word, t[j], S);
-    if constexpr (S == 4) __builtin_amdgcn_raw_buffer_store_b32(word, plane, voff, tile_off, 0);
-    if constexpr (S == 2) __builtin_amdgcn_raw_buffer_store_b16((uint16_t)word, plane, voff, tile_off, 0);
-    if constexpr (S == 1) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)word, plane, voff, tile_off, 0);
+    out[0] = word;
   }
+}
+
+// Where a lane's plane words go.  PlaneDst: straight to memory, one store of S bytes
+// per plane and group (the word goes to byte lane_group * S + tile_group * S of the
+// plane descriptor).  PlaneStage: into an LDS image of one tile of kTileGroups groups
+// (plane P at byte kTileGroups * lo(P), the word of the tile's group i at i * S
+// inside it), which flush_stage then writes out in 16-byte pieces: stores of 4, 2 or
+// 1 bytes per lane reach memory as partial lines and measured 10-17 % slower.
+template <int W, int kTileGroups>
+struct PlaneStage {
+  uint8_t* lds;  // kTileGroups * W bytes, 16-byte aligned
+};
+
+template <int W, int P>
+__device__ __forceinline__ void put_plane_word(const PlaneDst<W>& pd, uint32_t lane_group, uint32_t tile_group,
+                                               const uint32_t w[4]) {
+  constexpr int S = Planes<W>::seg(P);
+  const rsrc_t plane = pd.plane[P];
+  const uint32_t voff = lane_group * S, soff = tile_group * S;
+  if constexpr (S == 16) store16<false>(plane, voff, soff, make_uint4(w[0], w[1], w[2], w[3]));
+  if constexpr (S == 8) {
+    const u32x2_t o = {w[0], w[1]};
+    __builtin_amdgcn_raw_buffer_store_b64(o, plane, voff, soff, 0);
+  }
+  if constexpr (S == 4) __builtin_amdgcn_raw_buffer_store_b32(w[0], plane, voff, soff, 0);
+  if constexpr (S == 2) __builtin_amdgcn_raw_buffer_store_b16((uint16_t)w[0], plane, voff, soff, 0);
+  if constexpr (S == 1) __builtin_amdgcn_raw_buffer_store_b8((uint8_t)w[0], plane, voff, soff, 0);
+}
+
+template <int W, int P, int kTileGroups>
+__device__ __forceinline__ void put_plane_word(const PlaneStage<W, kTileGroups>& st, uint32_t lane_group,
+                                               uint32_t tile_group, const uint32_t w[4]) {
+  constexpr int S = Planes<W>::seg(P);
+  uint8_t* p = st.lds + kTileGroups * Planes<W>::lo(P) + (lane_group + tile_group) * S;
+  if constexpr (S == 16) *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
+  if constexpr (S == 8) *reinterpret_cast<uint2*>(p) = make_uint2(w[0], w[1]);
+  if constexpr (S == 4) *reinterpret_cast<uint32_t*>(p) = w[0];
+  if constexpr (S == 2) *reinterpret_cast<uint16_t*>(p) = (uint16_t)w[0];
+  if constexpr (S == 1) *p = (uint8_t)w[0];
+}
+
+// Memory address of the 16-byte piece at byte `off` of a tile's LDS image; g0 is the
+// tile's first group, G the tensor's group count.  A piece lies inside one plane
+// because kTileGroups is a multiple of 16.
+template <int W, int kTileGroups, int P = 0>
+__device__ __forceinline__ uint8_t* stage_piece_address(uint8_t* dst, uint64_t G, uint64_t g0, uint32_t off) {
+  static_assert(kTileGroups % 16 == 0, "plane images must be whole 16-byte pieces");
+  constexpr uint32_t S = Planes<W>::seg(P);
+  constexpr uint32_t LO = Planes<W>::lo(P);
+  if constexpr (P + 1 < Planes<W>::count) {
+    if (off >= kTileGroups * (LO + S)) return stage_piece_address<W, kTileGroups, P + 1>(dst, G, g0, off);
+  }
+  return dst + (G * LO + g0 * S + (off - kTileGroups * LO));
+}
+
+// Write the image of the whole tile that starts at group g0 to the planes of dst: the
+// copy alone (the caller places the barriers), and with a barrier on either side.
+// Every lane of the workgroup calls them.
+template <int W, int kTileGroups, int kBlock>
+__device__ __forceinline__ void copy_stage(const PlaneStage<W, kTileGroups>& st, uint8_t* dst, uint64_t G, uint64_t g0) {
+  constexpr uint32_t kPieces = kTileGroups * W / 16;
+#pragma unroll
+  for (uint32_t c0 = 0; c0 < kPieces; c0 += kBlock) {
+    const uint32_t c = c0 + threadIdx.x;
+    if (kPieces % kBlock == 0 || c < kPieces) {
+      const uint4 v = *reinterpret_cast<const uint4*>(st.lds + c * 16);
+      const u32x4_t w = {v.x, v.y, v.z, v.w};
+      __builtin_nontemporal_store(w, reinterpret_cast<u32x4_t*>(stage_piece_address<W, kTileGroups>(dst, G, g0, c * 16)));
+    }
+  }
+}
+
+template <int W, int kTileGroups, int kBlock>
+__device__ __forceinline__ void flush_stage(const PlaneStage<W, kTileGroups>& st, uint8_t* dst, uint64_t G, uint64_t g0) {
+  __syncthreads();  // every lane has put its words
+  copy_stage<W, kTileGroups, kBlock>(st, dst, G, g0);
+  __syncthreads();  // the image is free for the next tile
 }
 
 // Peel the planes off the left-aligned codes from the most significant segment
 // down.  With an odd W the top plane is 1 bit wide and is exactly the sign: it is
 // taken from the source bits u, and f holds the magnitude alone.
 // `lane_group` is the lane's group within the tile, `tile_group` the tile's first
-// group relative to the chunk (wave-uniform).
-template <int W, int P>
-__device__ __forceinline__ void peel_planes(uint32_t f[8], const uint32_t u[8], const PlaneDst<W>& pd,
-                                            uint32_t lane_group, uint32_t tile_group) {
+// group relative to the destination's base (wave-uniform).
+template <int W, int P, class Dst>
+__device__ __forceinline__ void peel_planes(uint32_t f[8], const uint32_t u[8], const Dst& dst, uint32_t lane_group,
+                                            uint32_t tile_group) {
   constexpr int S = Planes<W>::seg(P);
   constexpr bool sign_plane = (W & 1) && P == Planes<W>::count - 1;
+  uint32_t word[4];
   if constexpr (sign_plane) {
-    store_plane_from_top<S>(u, pd.plane[P], lane_group, tile_group * S);
+    plane_word_from_top<S>(u, word);
   } else {
-    store_plane_from_top<S>(f, pd.plane[P], lane_group, tile_group * S);
+    plane_word_from_top<S>(f, word);
     if constexpr (P > 0) {
 #pragma unroll
       for (int j = 0; j < 8; ++j) f[j] <<= S;
     }
   }
-  if constexpr (P > 0) peel_planes<W, P - 1>(f, u, pd, lane_group, tile_group);
+  put_plane_word<W, P>(dst, lane_group, tile_group, word);
+  if constexpr (P > 0) peel_planes<W, P - 1>(f, u, dst, lane_group, tile_group);
 }
 
 // Convert the 8 elements of one group (fp32-position bits u) and write its planes.
-template <int W, bool kWide>
+template <int W, bool kWide, class Dst>
 __device__ __forceinline__ void encode_group(const uint32_t u[8], const FormatConsts& fc, const TensorConsts& tc,
-                                             const PlaneDst<W>& pd, uint32_t lane_group, uint32_t tile_group) {
+                                             const Dst& pd, uint32_t lane_group, uint32_t tile_group) {
   uint32_t f[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
@@ -173,8 +244,8 @@ __device__ __forceinline__ void load_tile(rsrc_t src, uint32_t tile_group, uint3
 }
 
 // Convert and store one tile.
-template <typename T, int W, int kBlock, int kUnroll, bool kWide, bool kHist, bool kGuard>
-__device__ __forceinline__ void encode_tile(const TileRegs<T, kUnroll>& regs, const PlaneDst<W>& pd,
+template <typename T, int W, int kBlock, int kUnroll, bool kWide, bool kHist, bool kGuard, class Dst>
+__device__ __forceinline__ void encode_tile(const TileRegs<T, kUnroll>& regs, const Dst& pd,
                                             uint32_t tile_group, uint32_t rem, const FormatConsts& fc,
                                             const TensorConsts& tc, uint32_t* lds_hist) {
 #pragma unroll
@@ -221,6 +292,8 @@ __global__ __launch_bounds__(kBlock) void encode_kernel(const BatchArgs batch) {
   const uint32_t chunks = (tiles + kChunk - 1) / kChunk;
 
   __shared__ uint32_t lds_hist[kHist ? 256 * kHistCopies : 1];
+  __shared__ __align__(16) uint8_t lds_stage[TG * W];
+  const PlaneStage<W, TG> stage{lds_stage};
   if constexpr (kHist) {
     for (int i = threadIdx.x; i < 256 * kHistCopies; i += kBlock) lds_hist[i] = 0;
     __syncthreads();
@@ -238,7 +311,8 @@ __global__ __launch_bounds__(kBlock) void encode_kernel(const BatchArgs batch) {
 #pragma unroll
       for (int c = 0; c < kChunk; ++c) {
         if (c + 1 < kChunk) load_tile<T, kBlock, kUnroll, kNT, false>(src, (c + 1) * TG, 0, regs[(c + 1) & 1]);
-        encode_tile<T, W, kBlock, kUnroll, kWide, kHist, false>(regs[c & 1], pd, c * TG, 0, fc, tc, lds_hist);
+        encode_tile<T, W, kBlock, kUnroll, kWide, kHist, false>(regs[c & 1], stage, 0, 0, fc, tc, lds_hist);
+        flush_stage<W, TG, kBlock>(stage, dst, G, g0 + (uint64_t)c * TG);
       }
     } else {
       for (uint32_t tile = chunk * kChunk; tile < tiles; ++tile) {
@@ -293,9 +367,9 @@ __global__ __launch_bounds__(kBlock) void encode_kernel(const BatchArgs batch) {
 // One group with the rounding variant its block's metadatum needs.  The branch is
 // taken for a whole wavefront at once (any lane that needs the fp64 path sends
 // all of them there; both paths give the same result where both apply).
-template <int W>
+template <int W, class Dst>
 __device__ __forceinline__ void encode_group_meta(const uint32_t u[8], uint32_t me, const FormatConsts& fc,
-                                                  const BlockConsts& bc, const PlaneDst<W>& pd, uint32_t lane_group,
+                                                  const BlockConsts& bc, const Dst& pd, uint32_t lane_group,
                                                   uint32_t tile_group) {
   const TensorConsts tc = derive_tc(me, bc);
   if (__builtin_amdgcn_ballot_w64(me > bc.wide_above) != 0)
@@ -306,9 +380,9 @@ __device__ __forceinline__ void encode_group_meta(const uint32_t u[8], uint32_t 
 
 // Float scaling: the group's elements are multiplied by the reciprocal of their
 // block's scale and take the codes of the max_exp = 127 format.
-template <int W>
+template <int W, class Dst>
 __device__ __forceinline__ void encode_group_scaled(uint32_t u[8], uint32_t scale_bits, const FormatConsts& fc,
-                                                    const TensorConsts& tc127, const PlaneDst<W>& pd,
+                                                    const TensorConsts& tc127, const Dst& pd,
                                                     uint32_t lane_group, uint32_t tile_group) {
   const float inv = 1.0f / as_f32(scale_bits);
 #pragma unroll
@@ -333,6 +407,8 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
   const uint32_t full_tiles = (uint32_t)(Gfull / TG);
   const uint32_t rem_groups = (uint32_t)(Gfull - (uint64_t)full_tiles * TG);
   const uint32_t tiles = full_tiles + (rem_groups ? 1u : 0u);
+  __shared__ __align__(16) uint8_t lds_stage[TG * W];
+  const PlaneStage<W, TG> stage{lds_stage};
 
   for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
     const uint64_t g0 = (uint64_t)tile * TG;
@@ -354,11 +430,12 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
       for (int r = 0; r < kUnroll; ++r) {
         uint32_t u[8];
         group_bits<T>(regs.v[r], u);
-        if constexpr (kScaled)
+        if constexpr (kScaled)  // more arithmetic per element: the stage measured slower here
           encode_group_scaled<W>(u, me[r], fc, args.tc127, pd, threadIdx.x, r * kBlock);
         else
-          encode_group_meta<W>(u, me[r], fc, bc, pd, threadIdx.x, r * kBlock);
+          encode_group_meta<W>(u, me[r], fc, bc, stage, threadIdx.x, r * kBlock);
       }
+      if constexpr (!kScaled) flush_stage<W, TG, kBlock>(stage, dst, G, g0);
     } else {
       load_tile<T, kBlock, kUnroll, kNT, true>(src, 0, rem_groups, regs);
 #pragma unroll
@@ -447,15 +524,44 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_small_kernel(const 
   const uint64_t G = (n + 7) / 8;
   const uint64_t Gfull = n / 8;
   const uint32_t tiles = (uint32_t)((G + TG - 1) / TG);
+  const uint32_t full_tiles = (uint32_t)(Gfull / TG);
+  const uint32_t rem_whole = (uint32_t)(Gfull - (uint64_t)full_tiles * TG);
+  // a whole tile leaves through LDS: its plane words (see PlaneStage) and, behind them, its metadata bytes
+  __shared__ __align__(16) uint8_t lds_stage[TG * W + TG];
+  const PlaneStage<W, TG> stage{lds_stage};
+  uint8_t* const lds_meta = lds_stage + TG * W;
+  const bool meta_words = (reinterpret_cast<uintptr_t>(args.meta) & 3u) == 0 && (TG >> lg) >= 4;
 
   for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
     const uint64_t g0 = (uint64_t)tile * TG;
     const rsrc_t src = make_rsrc(src4 + g0 * kLoads);
+    const uint32_t whole = units_in_tile(tile, full_tiles, rem_whole, TG);  // groups of this tile with all 8 elements
+    TileRegs<T, kUnroll> regs;
+    if (tile < full_tiles) {
+      load_tile<T, kBlock, kUnroll, kNT, false>(src, 0, 0, regs);
+#pragma unroll
+      for (int r = 0; r < kUnroll; ++r) {
+        const uint32_t idx = r * kBlock + threadIdx.x;
+        uint32_t u[8];
+        group_bits<T>(regs.v[r], u);
+        const uint32_t me = meta_from_key(max_over_lanes(group_key(u), lg), bc);
+        if ((threadIdx.x & ((1u << lg) - 1u)) == 0) {
+          if (meta_words)
+            lds_meta[idx >> lg] = (uint8_t)me;
+          else
+            args.meta[(g0 + idx) >> lg] = (uint8_t)me;
+        }
+        encode_group_meta<W>(u, me, fc, bc, stage, threadIdx.x, r * kBlock);
+      }
+      __syncthreads();
+      copy_stage<W, TG, kBlock>(stage, dst, G, g0);
+      if (meta_words && threadIdx.x < (TG >> lg) / 4)
+        reinterpret_cast<uint32_t*>(args.meta + (g0 >> lg))[threadIdx.x] = reinterpret_cast<const uint32_t*>(lds_meta)[threadIdx.x];
+      __syncthreads();  // the image is free for the next tile
+      continue;
+    }
     PlaneDst<W> pd;
     make_plane_dst<W>(dst, G, g0, pd);
-    const uint64_t whole_left = Gfull > g0 ? Gfull - g0 : 0;
-    const uint32_t whole = whole_left < TG ? (uint32_t)whole_left : TG;  // groups of this tile with all 8 elements
-    TileRegs<T, kUnroll> regs;
     load_tile<T, kBlock, kUnroll, kNT, true>(src, 0, whole, regs);
 #pragma unroll
     for (int r = 0; r < kUnroll; ++r) {

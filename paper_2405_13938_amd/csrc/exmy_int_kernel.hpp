@@ -37,7 +37,9 @@ template <int W, int P>
 __device__ __forceinline__ void peel_all(uint32_t f[8], const enc::PlaneDst<W>& pd, uint32_t lane_group,
                                          uint32_t tile_group) {
   constexpr int S = Planes<W>::seg(P);
-  enc::store_plane_from_top<S>(f, pd.plane[P], lane_group, tile_group * S);
+  uint32_t word[4];
+  enc::plane_word_from_top<S>(f, word);
+  enc::put_plane_word<W, P>(pd, lane_group, tile_group, word);
   if constexpr (P > 0) {
 #pragma unroll
     for (int j = 0; j < 8; ++j) f[j] <<= S;

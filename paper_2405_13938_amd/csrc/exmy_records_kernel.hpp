@@ -88,11 +88,13 @@ __global__ __launch_bounds__(kBlock) void encode_records_kernel(const void* __re
   const uint64_t G = (n + 7) / 8;  // groups, the last one possibly ragged
   const uint64_t Gfull = n / 8;
   const uint32_t tiles = (uint32_t)((G + TG - 1) / TG);
+  const uint32_t all_tiles = (uint32_t)(G / TG), full_tiles = (uint32_t)(Gfull / TG);
+  const uint32_t rem_all = (uint32_t)(G - (uint64_t)all_tiles * TG), rem_whole = (uint32_t)(Gfull - (uint64_t)full_tiles * TG);
 
   for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
     const uint64_t g0 = (uint64_t)tile * TG;
-    const uint32_t here = (uint32_t)min((uint64_t)TG, G - g0);                          // groups of this tile
-    const uint32_t whole = Gfull > g0 ? (uint32_t)min((uint64_t)TG, Gfull - g0) : 0u;  // of them, with all 8 elements
+    const uint32_t here = units_in_tile(tile, all_tiles, rem_all, TG);        // groups of this tile
+    const uint32_t whole = units_in_tile(tile, full_tiles, rem_whole, TG);   // of them, with all 8 elements
     const rsrc_t src = make_rsrc(src4 + g0 * kLoads);
     enc::TileRegs<T, kUnroll> regs;
     auto body = [&](auto guard) {
@@ -119,7 +121,7 @@ __global__ __launch_bounds__(kBlock) void encode_records_kernel(const void* __re
         }
       }
     };
-    if (whole == TG)
+    if (tile < full_tiles)
       body(std::false_type{});
     else
       body(std::true_type{});
@@ -142,11 +144,13 @@ __global__ __launch_bounds__(kBlock) void decode_records_kernel(const uint8_t* _
   const uint64_t G = (n + 7) / 8;
   const uint64_t Gfull = n / 8;
   const uint32_t tiles = (uint32_t)((G + TG - 1) / TG);
+  const uint32_t all_tiles = (uint32_t)(G / TG), full_tiles = (uint32_t)(Gfull / TG);
+  const uint32_t rem_all = (uint32_t)(G - (uint64_t)all_tiles * TG), rem_whole = (uint32_t)(Gfull - (uint64_t)full_tiles * TG);
 
   for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
     const uint64_t g0 = (uint64_t)tile * TG;
-    const uint32_t here = (uint32_t)min((uint64_t)TG, G - g0);
-    const uint32_t whole = Gfull > g0 ? (uint32_t)min((uint64_t)TG, Gfull - g0) : 0u;
+    const uint32_t here = units_in_tile(tile, all_tiles, rem_all, TG);
+    const uint32_t whole = units_in_tile(tile, full_tiles, rem_whole, TG);
     move_tile_bytes<kBlock, false>(lds, const_cast<uint8_t*>(src) + g0 * W, here * W);
     __syncthreads();
     const rsrc_t out = make_rsrc(reinterpret_cast<uint4*>(dst) + g0 * kPerGroup);

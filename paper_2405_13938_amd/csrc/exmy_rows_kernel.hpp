@@ -21,27 +21,7 @@ namespace exmy {
 
 namespace rows {
 
-// The S * 8 bits of one plane word from the fields that sit at the TOP of
-// t[0..7], element j at bits [S*j, S*j + S): out[0 .. S/4) for S >= 4, else the
-// low 2 or 1 bytes of out[0].
-template <int S>
-__device__ __forceinline__ void plane_word_from_top(const uint32_t t[8], uint32_t out[4]) {
-  using enc::append_top;
-  if constexpr (S == 16) {
-    out[0] = append_top(t[1] >> 16, t[0], 16);
-    out[1] = append_top(t[3] >> 16, t[2], 16);
-    out[2] = append_top(t[5] >> 16, t[4], 16);
-    out[3] = append_top(t[7] >> 16, t[6], 16);
-  } else if constexpr (S == 8) {
-    out[0] = append_top(append_top(append_top(t[3] >> 24, t[2], 8), t[1], 8), t[0], 8);
-    out[1] = append_top(append_top(append_top(t[7] >> 24, t[6], 8), t[5], 8), t[4], 8);
-  } else {
-    uint32_t word = t[7] >> (32 - S);
-#pragma unroll
-    for (int j = 6; j >= 0; --j) word = append_top(word, t[j], S);
-    out[0] = word;
-  }
-}
+using enc::plane_word_from_top;
 
 // fp32-position bits of column c of a 16-byte row piece.
 template <typename T>

@@ -85,10 +85,10 @@ __device__ __forceinline__ uint32_t scaled_magnitude(uint32_t u, int shift) {
 // ---------------------------------------------------------------- encode
 
 // One group whose 8 elements have a metadatum each.
-template <int W>
+template <int W, class Dst>
 __device__ __forceinline__ void encode_group_each(const uint32_t u[8], const UnitMeta<8>& me, const FormatConsts& fc,
-                                                  const BlockConsts& bc, const TensorConsts& tc_ref,
-                                                  const enc::PlaneDst<W>& pd, uint32_t lane_group, uint32_t tile_group) {
+                                                  const BlockConsts& bc, const TensorConsts& tc_ref, const Dst& pd,
+                                                  uint32_t lane_group, uint32_t tile_group) {
   uint32_t f[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
@@ -113,6 +113,8 @@ __global__ __launch_bounds__(kBlock) void encode_tiles_kernel(const TileArgs arg
   const uint32_t full_tiles = (uint32_t)(G / TG);
   const uint32_t rem_groups = (uint32_t)(G - (uint64_t)full_tiles * TG);
   const uint32_t tiles = full_tiles + (rem_groups ? 1u : 0u);
+  __shared__ __align__(16) uint8_t lds_stage[TG * W];
+  const enc::PlaneStage<W, TG> stage{lds_stage};
 
   for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
     const uint64_t g0 = (uint64_t)tile * TG;
@@ -123,8 +125,8 @@ __global__ __launch_bounds__(kBlock) void encode_tiles_kernel(const TileArgs arg
     enc::make_plane_dst<W>(dst, G, g0, pd);
     enc::TileRegs<T, kUnroll> regs;
     UnitMeta<kColumns ? 8 : 1> me[kUnroll];
-    // whole tiles take the path without bounds checks
-    auto body = [&](auto guard) {
+    // whole tiles take the path without bounds checks and write their plane words through the LDS stage
+    auto body = [&](auto guard, const auto& out) {
       constexpr bool kGuard = decltype(guard)::value;
       enc::load_tile<T, kBlock, kUnroll, kNT, kGuard>(src, 0, rem_groups, regs);
 #pragma unroll
@@ -137,16 +139,18 @@ __global__ __launch_bounds__(kBlock) void encode_tiles_kernel(const TileArgs arg
           uint32_t u[8];
           enc::group_bits<T>(regs.v[r], u);
           if constexpr (kColumns)
-            encode_group_each<W>(u, me[r], fc, bc, tc_ref, pd, threadIdx.x, r * kBlock);
+            encode_group_each<W>(u, me[r], fc, bc, tc_ref, out, threadIdx.x, r * kBlock);
           else
-            enc::encode_group_meta<W>(u, me[r].w[0], fc, bc, pd, threadIdx.x, r * kBlock);
+            enc::encode_group_meta<W>(u, me[r].w[0], fc, bc, out, threadIdx.x, r * kBlock);
         }
       }
     };
-    if (tile < full_tiles)
-      body(std::false_type{});
-    else
-      body(std::true_type{});
+    if (tile < full_tiles) {
+      body(std::false_type{}, stage);
+      enc::flush_stage<W, TG, kBlock>(stage, dst, G, g0);
+    } else {
+      body(std::true_type{}, pd);
+    }
   }
 }
 
