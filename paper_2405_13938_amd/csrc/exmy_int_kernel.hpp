@@ -33,9 +33,8 @@ __device__ __forceinline__ uint32_t code_left(uint32_t u, const IntConsts& ic) {
   return (kl ^ smask) - smask;                                       // negate where the sign bit is set
 }
 
-template <int W, int P>
-__device__ __forceinline__ void peel_all(uint32_t f[8], const enc::PlaneDst<W>& pd, uint32_t lane_group,
-                                         uint32_t tile_group) {
+template <int W, int P, class Dst>
+__device__ __forceinline__ void peel_all(uint32_t f[8], const Dst& pd, uint32_t lane_group, uint32_t tile_group) {
   constexpr int S = Planes<W>::seg(P);
   uint32_t word[4];
   enc::plane_word_from_top<S>(f, word);
@@ -47,8 +46,8 @@ __device__ __forceinline__ void peel_all(uint32_t f[8], const enc::PlaneDst<W>& 
   }
 }
 
-template <int W>
-__device__ __forceinline__ void encode_group(const uint32_t u[8], const IntConsts& ic, const enc::PlaneDst<W>& pd,
+template <int W, class Dst>
+__device__ __forceinline__ void encode_group(const uint32_t u[8], const IntConsts& ic, const Dst& pd,
                                              uint32_t lane_group, uint32_t tile_group) {
   uint32_t f[8];
 #pragma unroll
@@ -68,14 +67,27 @@ __global__ __launch_bounds__(kBlock) void encode_int_kernel(const void* src_v, v
   const uint32_t full_tiles = (uint32_t)(Gfull / TG);
   const uint32_t rem_groups = (uint32_t)(Gfull - (uint64_t)full_tiles * TG);
   const uint32_t tiles = full_tiles + (rem_groups ? 1u : 0u);
+  __shared__ __align__(16) uint8_t lds_stage[TG * W];
+  const enc::PlaneStage<W, TG> stage{lds_stage};
 
   for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
     const uint64_t g0 = (uint64_t)tile * TG;
     const rsrc_t src = make_rsrc(src4 + g0 * kLoads);
+    enc::TileRegs<T, kUnroll> regs;
+    if (tile < full_tiles) {  // a whole tile leaves through the LDS image, in 16-byte pieces
+      enc::load_tile<T, kBlock, kUnroll, true, false>(src, 0, 0, regs);
+#pragma unroll
+      for (int r = 0; r < kUnroll; ++r) {
+        uint32_t u[8];
+        enc::group_bits<T>(regs.v[r], u);
+        encode_group<W>(u, ic, stage, threadIdx.x, r * kBlock);
+      }
+      enc::flush_stage<W, TG, kBlock>(stage, dst, G, g0);
+      continue;
+    }
     enc::PlaneDst<W> pd;
     enc::make_plane_dst<W>(dst, G, g0, pd);
-    const uint32_t rem = tile < full_tiles ? TG : rem_groups;
-    enc::TileRegs<T, kUnroll> regs;
+    const uint32_t rem = rem_groups;
     enc::load_tile<T, kBlock, kUnroll, true, true>(src, 0, rem, regs);
 #pragma unroll
     for (int r = 0; r < kUnroll; ++r) {
