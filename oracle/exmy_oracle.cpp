@@ -496,6 +496,102 @@ int exmy_oracle_decode_records(const uint8_t* src_records, int dt, uint64_t n, i
   return ORACLE_OK;
 }
 
+// ---------------------------------------------------------------------------
+// Reserved code points for NaN and Inf (Section 5: values encoded for training
+// would need an encoding for these, which the paper leaves open).  The two
+// conventions of the float types in use are offered:
+//   specials = 1, IEEE 754 style (fp32, bf16, fp16, e5m2): the top exponent code
+//     is reserved; mantissa 0 under it is Inf, anything else NaN.  The finite
+//     values are those of the plain format without its top binade.
+//   specials = 2, NaN only (OCP e4m3): the all-ones magnitude code is NaN, there
+//     is no Inf; the finite values are those of the plain format without its
+//     largest one.
+// Finite elements round as always and saturate to the largest finite value;
+// a NaN takes the all-ones magnitude code under its own sign; Inf takes the Inf
+// code, or (NaN only) saturates like any large value.  max_exp keeps its meaning:
+// the exponent of the top exponent code, reserved or not.
+static int specials_format(int dt, int X, int Y, int max_exp, int specials, bool packed, Format* f) {
+  if (specials != 1 && specials != 2) return ORACLE_ERR_FORMAT;
+  if (int rc = check_format(dt, X, Y, max_exp, packed, f)) return rc;
+  if (packed && f->W > 16) return ORACLE_ERR_FORMAT;
+  if (specials == 1) {
+    if (X < 1) return ORACLE_ERR_FORMAT;
+    f->cmax = ((((int64_t)1 << X) - 1) << Y) - 1;  // below the reserved exponent code
+  } else {
+    if (X == 8 || X + Y < 1) return ORACLE_ERR_FORMAT;  // exponent code 255 is not a finite binade of any container
+    f->cmax = ((int64_t)1 << (X + Y)) - 2;
+  }
+  return ORACLE_OK;
+}
+
+static uint32_t encode_one_specials(const Format& f, int specials, uint32_t bits) {
+  const uint32_t sign = bits >> 31;
+  const float x = bits_to_float(bits);
+  const int64_t all_ones = ((int64_t)1 << (f.X + f.Y)) - 1;
+  int64_t c;
+  if (std::isnan(x))
+    c = all_ones;
+  else if (std::isinf(x))
+    c = specials == 1 ? ((((int64_t)1 << f.X) - 1) << f.Y) : f.cmax;
+  else
+    c = magnitude_code(f, std::fabs((double)x));  // saturates to f.cmax, the largest finite code
+  return (uint32_t)((sign << (f.X + f.Y)) | (uint32_t)c);
+}
+
+// fp32 bits of a full code: finite codes as always; reserved ones give Inf or the quiet NaN 0x7FC00000, signed.
+static uint32_t decode_one_specials(const Format& f, int specials, uint32_t code) {
+  const uint32_t sign = ((code >> (f.X + f.Y)) & 1u) << 31;
+  const int64_t c = code & (uint32_t)((((int64_t)1) << (f.X + f.Y)) - 1);
+  if (c <= f.cmax) return float_to_bits((float)code_magnitude(f, c)) | sign;
+  if (specials == 1 && c == ((((int64_t)1 << f.X) - 1) << f.Y)) return sign | 0x7F800000u;
+  return sign | 0x7FC00000u;
+}
+
+static void store_bits_specials(void* dst, int dt, uint64_t i, uint32_t bits) {
+  if (dt == ORACLE_F16 && (bits & 0x7FFFFFFFu) > 0x7F800000u)  // the half NaN with the same quiet bit
+    ((uint16_t*)dst)[i] = (uint16_t)(((bits >> 31) << 15) | 0x7E00u);
+  else
+    store_bits(dst, dt, i, bits);
+}
+
+int exmy_oracle_encode_specials(const void* src, int dt, uint64_t n, int X, int Y, int max_exp, int specials,
+                                uint8_t* dst_packed) {
+  if ((!src || !dst_packed) && n) return ORACLE_ERR_NULL;
+  Format f;
+  if (int rc = specials_format(dt, X, Y, max_exp, specials, true, &f)) return rc;
+  std::vector<uint32_t> codes(n);
+  for (uint64_t i = 0; i < n; ++i) codes[i] = encode_one_specials(f, specials, load_bits(src, dt, i));
+  pack_groups(codes.data(), 0, n, f.W, dst_packed, 0, (n + 7) / 8);
+  return ORACLE_OK;
+}
+
+int exmy_oracle_decode_specials(const uint8_t* src_packed, int dt, uint64_t n, int X, int Y, int max_exp,
+                                int specials, void* dst) {
+  if ((!src_packed || !dst) && n) return ORACLE_ERR_NULL;
+  Format f;
+  if (int rc = specials_format(dt, X, Y, max_exp, specials, true, &f)) return rc;
+  std::vector<uint32_t> codes(n);
+  unpack_groups(src_packed, n, f.W, codes.data(), 0, 0, (n + 7) / 8);
+  for (uint64_t i = 0; i < n; ++i) store_bits_specials(dst, dt, i, decode_one_specials(f, specials, codes[i]));
+  return ORACLE_OK;
+}
+
+// Emulation: NaN / Inf stay as they are (Section 2.1); finite elements become the nearest finite value of
+// the format with reserved code points, saturated.
+int exmy_oracle_emulate_specials(void* data, int dt, uint64_t n, int X, int Y, int max_exp, int specials) {
+  if (!data && n) return ORACLE_ERR_NULL;
+  Format f;
+  if (int rc = specials_format(dt, X, Y, max_exp, specials, false, &f)) return rc;
+  for (uint64_t i = 0; i < n; ++i) {
+    const uint32_t bits = load_bits(data, dt, i);
+    const float x = bits_to_float(bits);
+    if (std::isnan(x) || std::isinf(x)) continue;
+    const float v = (float)code_magnitude(f, magnitude_code(f, std::fabs((double)x)));
+    store_bits(data, dt, i, float_to_bits(v) | (bits & 0x80000000u));
+  }
+  return ORACLE_OK;
+}
+
 // Emulation (Section 2.1): quantise and dequantise in the element's own type;
 // NaN and +-Inf are returned bit-identical.
 int exmy_oracle_emulate(void* data, int dt, uint64_t n, int X, int Y, int max_exp, int threads) {

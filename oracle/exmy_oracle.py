@@ -38,6 +38,9 @@ def lib():
         L.exmy_oracle_decode.argtypes = [vp, i32, u64, i32, i32, i32, vp, i32]
         L.exmy_oracle_emulate.argtypes = [vp, i32, u64, i32, i32, i32, i32]
         L.exmy_oracle_exponent_histogram.argtypes = [vp, i32, u64, vp]
+        L.exmy_oracle_encode_specials.argtypes = [vp, i32, u64, i32, i32, i32, i32, vp]
+        L.exmy_oracle_decode_specials.argtypes = [vp, i32, u64, i32, i32, i32, i32, vp]
+        L.exmy_oracle_emulate_specials.argtypes = [vp, i32, u64, i32, i32, i32, i32]
         L.exmy_oracle_encode_records.argtypes = [vp, i32, u64, i32, i32, i32, vp]
         L.exmy_oracle_decode_records.argtypes = [vp, i32, u64, i32, i32, i32, vp]
         L.exmy_oracle_block_max_exp.argtypes = [vp, i32, u64, u64, i32, vp]
@@ -175,6 +178,32 @@ def decode_records(records, dt, n, X, Y, max_exp):
     assert records.size == packed_bytes(n, X, Y)
     out = np.empty(n, dtype=_out_dtype(dt))
     _check(lib().exmy_oracle_decode_records(_ptr(records), dt, n, X, Y, max_exp, _ptr(out)))
+    return out
+
+
+IEEE, NAN_ONLY = 1, 2
+
+
+def encode_specials(src, X, Y, max_exp, specials):
+    """Codes with reserved NaN / Inf code points (specials: IEEE or NAN_ONLY), planar layout."""
+    a, dt = _src(src)
+    out = np.empty(packed_bytes(a.size, X, Y), dtype=np.uint8)
+    _check(lib().exmy_oracle_encode_specials(_ptr(a), dt, a.size, X, Y, max_exp, specials, _ptr(out)))
+    return out
+
+
+def decode_specials(packed, dt, n, X, Y, max_exp, specials):
+    packed = np.ascontiguousarray(packed, dtype=np.uint8)
+    assert packed.size == packed_bytes(n, X, Y)
+    out = np.empty(n, dtype=_out_dtype(dt))
+    _check(lib().exmy_oracle_decode_specials(_ptr(packed), dt, n, X, Y, max_exp, specials, _ptr(out)))
+    return out
+
+
+def emulate_specials(src, X, Y, max_exp, specials):
+    a, dt = _src(src)
+    out = a.copy()
+    _check(lib().exmy_oracle_emulate_specials(_ptr(out), dt, out.size, X, Y, max_exp, specials))
     return out
 
 
