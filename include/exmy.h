@@ -208,6 +208,36 @@ exmy_status_t exmy_encode_blocks_auto(const void* src, exmy_dtype_t dt, uint64_t
                                       exmy_scheme_t scheme, uint8_t* max_exp_dev, void* dst_packed, void* stream);
 
 /* ---------------------------------------------------------------------------
+ * Reserved code points for NaN and Inf (Section 5 "Limitations": values encoded
+ * for training need an encoding for these, which the paper leaves open).  The two
+ * conventions of the float types in use are offered:
+ *   EXMY_SPECIALS_IEEE      the top exponent code is reserved (as in fp32, bf16,
+ *                           fp16, e5m2): mantissa 0 under it is Inf, any other
+ *                           mantissa NaN; X >= 1 (X = 8 is allowed: e8m7 is then
+ *                           bf16 itself).  The finite values are those of the
+ *                           plain format without its top binade;
+ *   EXMY_SPECIALS_NAN_ONLY  only the all-ones magnitude code is reserved (as in
+ *                           OCP e4m3): it is NaN, there is no Inf; X <= 7,
+ *                           X + Y >= 1.  The finite values are those of the plain
+ *                           format without its largest one.
+ * max_exp keeps its meaning (the exponent of the top exponent code, reserved or
+ * not; e5m2 with IEEE bias 15 is max_exp 143, OCP e4m3 with bias 7 is 135).
+ * Encode: finite elements round as in exmy_encode and saturate to the largest
+ * finite value (Section 2.1), NaN takes the all-ones magnitude code under its own
+ * sign, Inf the Inf code or (NaN only) the largest finite code.  Decode: finite
+ * codes as in exmy_decode; reserved codes give Inf or the quiet NaN (0x7FC00000,
+ * 0x7FC0, 0x7E00 in fp32 / bf16 / fp16) under the code's sign.  Emulate leaves
+ * Inf / NaN bit-identical and saturates finite elements.  Planar layout of
+ * exmy_encode, W <= 16 (emulate: any width); everything else as there. */
+typedef enum { EXMY_SPECIALS_IEEE = 1, EXMY_SPECIALS_NAN_ONLY = 2 } exmy_specials_t;
+exmy_status_t exmy_encode_specials(const void* src, exmy_dtype_t dt, uint64_t n, int X, int Y, int max_exp,
+                                   exmy_specials_t specials, void* dst_packed, void* stream);
+exmy_status_t exmy_decode_specials(const void* src_packed, exmy_dtype_t dt_out, uint64_t n, int X, int Y, int max_exp,
+                                   exmy_specials_t specials, void* dst, void* stream);
+exmy_status_t exmy_emulate_specials(void* data_inout, exmy_dtype_t dt, uint64_t n, int X, int Y, int max_exp,
+                                    exmy_specials_t specials, void* stream);
+
+/* ---------------------------------------------------------------------------
  * Records: the plane words of Section 2.2.2 / Fig. 2 in another order.  The
  * words of one group follow each other, widest segment first, as one record of
  * W = 1 + X + Y bytes, and the records follow each other in group order: for

@@ -31,6 +31,9 @@ SYMBOLS = [
     "exmy_encode_blocks",
     "exmy_decode_blocks",
     "exmy_emulate_blocks",
+    "exmy_encode_specials",
+    "exmy_decode_specials",
+    "exmy_emulate_specials",
     "exmy_encode_records",
     "exmy_decode_records",
     "exmy_tile_count",
@@ -111,6 +114,12 @@ def lib():
         L.exmy_decode_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, vp]
         L.exmy_emulate_blocks.restype = i32
         L.exmy_emulate_blocks.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp]
+        L.exmy_encode_specials.restype = i32
+        L.exmy_encode_specials.argtypes = [vp, i32, u64, i32, i32, i32, i32, vp, vp]
+        L.exmy_decode_specials.restype = i32
+        L.exmy_decode_specials.argtypes = [vp, i32, u64, i32, i32, i32, i32, vp, vp]
+        L.exmy_emulate_specials.restype = i32
+        L.exmy_emulate_specials.argtypes = [vp, i32, u64, i32, i32, i32, i32, vp]
         L.exmy_encode_records.restype = i32
         L.exmy_encode_records.argtypes = [vp, i32, u64, i32, i32, i32, vp, vp]
         L.exmy_decode_records.restype = i32
@@ -430,6 +439,52 @@ def emulate_blocks(data, block, X, Y, max_exps):
     _meta_tensor(max_exps, data.numel(), block)
     _check(lib().exmy_emulate_blocks(data.data_ptr(), _dtype_enum(data), data.numel(), block, X, Y,
                                      max_exps.data_ptr(), _stream()))
+    return data
+
+
+# ------------------------------------------------------------ reserved NaN / Inf code points
+
+SPECIALS_IEEE, SPECIALS_NAN_ONLY = 1, 2
+
+
+def encode_specials(src, X, Y, max_exp, specials, out=None):
+    """exmy_encode_specials: returns the packed uint8 tensor (``out`` if given)."""
+    _device_tensor(src, "src")
+    n = src.numel()
+    nbytes = packed_bytes(n, X, Y)
+    if out is None:
+        out = torch.empty(nbytes, dtype=torch.uint8, device=src.device)
+    else:
+        _device_tensor(out, "out")
+        if out.dtype != torch.uint8 or out.numel() != nbytes:
+            raise ValueError("exmy: out must be uint8 with %d elements" % nbytes)
+    _check(lib().exmy_encode_specials(src.data_ptr(), _dtype_enum(src), n, X, Y, max_exp, int(specials), out.data_ptr(),
+                                      _stream()))
+    return out
+
+
+def decode_specials(packed, dtype, n, X, Y, max_exp, specials, out=None):
+    """exmy_decode_specials: returns a flat tensor of ``n`` values of ``dtype``."""
+    _device_tensor(packed, "packed")
+    tdt = _torch_dtype(dtype)
+    if packed.dtype != torch.uint8 or packed.numel() != packed_bytes(n, X, Y):
+        raise ValueError("exmy: packed must be uint8 with %d elements" % packed_bytes(n, X, Y))
+    if out is None:
+        out = torch.empty(n, dtype=tdt, device=packed.device)
+    else:
+        _device_tensor(out, "out")
+        if out.dtype != tdt or out.numel() != n:
+            raise ValueError("exmy: out must be %s with %d elements" % (tdt, n))
+    _check(lib().exmy_decode_specials(packed.data_ptr(), _dtype_enum(out), n, X, Y, max_exp, int(specials),
+                                      out.data_ptr(), _stream()))
+    return out
+
+
+def emulate_specials(data, X, Y, max_exp, specials):
+    """exmy_emulate_specials: in place; returns ``data``."""
+    _device_tensor(data, "data")
+    _check(lib().exmy_emulate_specials(data.data_ptr(), _dtype_enum(data), data.numel(), X, Y, max_exp, int(specials),
+                                       _stream()))
     return data
 
 

@@ -12,7 +12,7 @@ OBJ_DIR = os.path.join(HERE, "_build")
 SOURCES = ["exmy_api.hip", "exmy_encode.hip", "exmy_decode.hip", "exmy_emulate.hip", "exmy_histogram.hip",
            "exmy_encode_blocks.hip", "exmy_decode_blocks.hip", "exmy_emulate_blocks.hip",
            "exmy_encode_rows.hip", "exmy_decode_rows.hip", "exmy_int.hip", "exmy_encode_auto.hip",
-           "exmy_encode_tiles.hip", "exmy_decode_tiles.hip", "exmy_codes32.hip", "exmy_records.hip"]
+           "exmy_encode_tiles.hip", "exmy_decode_tiles.hip", "exmy_codes32.hip", "exmy_records.hip", "exmy_specials.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3",

@@ -520,6 +520,60 @@ exmy_status_t exmy_decode_records(const void* src_records, exmy_dtype_t dt_out, 
   return run_records(true, src_records, dst, dt_out, n, X, Y, max_exp, stream);
 }
 
+namespace {
+// op: 0 = encode, 1 = decode, 2 = emulate in place (src == dst)
+exmy_status_t run_specials(int op, const void* src, void* dst, exmy_dtype_t dt, uint64_t n, int X, int Y, int max_exp,
+                           exmy_specials_t specials, void* stream) {
+  if (specials != EXMY_SPECIALS_IEEE && specials != EXMY_SPECIALS_NAN_ONLY) return EXMY_ERR_FORMAT;
+  FormatConsts fc;
+  TensorConsts tc;
+  bool wide = false;
+  if (exmy_status_t st = make_format(dt, X, Y, max_exp, op == 2 ? kAnyWidth : kBlockWidth, &fc, &tc, &wide)) return st;
+  if (specials == EXMY_SPECIALS_IEEE ? X < 1 : (X == 8 || X + Y < 1)) return EXMY_ERR_FORMAT;
+  if (n > EXMY_MAX_ELEMENTS) return EXMY_ERR_COUNT;
+  if (n == 0) return EXMY_OK;
+  if (!src || !dst) return EXMY_ERR_NULL;
+  if (!aligned16(src) || !aligned16(dst)) return EXMY_ERR_ALIGN;
+
+  // the largest finite magnitude code and its value, which becomes the saturation bound
+  const uint64_t top = (1ull << X) - 1ull, ones = (1ull << Y) - 1ull, all_ones = (1ull << (X + Y)) - 1ull;
+  const uint64_t last = specials == EXMY_SPECIALS_IEEE ? (top << Y) - 1ull : all_ones - 1ull;
+  const int emin8 = max_exp - (1 << X) + 2;
+  const uint64_t E = last >> Y, M = last & ones;
+  tc.sat_bits = E == 0 ? float_bits(ldexpf((float)M, emin8 - 127 - Y))
+                       : (uint32_t)(((E - 1 + (uint64_t)emin8) << 23) | (M << (23 - Y)));
+  const hipStream_t s = static_cast<hipStream_t>(stream);
+  hipError_t e;
+  if (op == 2) {
+    e = emulate_dispatch(dt, wide, dst, n, fc, tc, s);  // Inf / NaN pass through; only the bound differs
+  } else {
+    const uint64_t inf = specials == EXMY_SPECIALS_IEEE ? top << Y : last;
+    SpecialConsts sc;
+    sc.nan_left = (uint32_t)(all_ones << fc.left_shift);
+    sc.inf_left = (uint32_t)(inf << fc.left_shift);
+    sc.g_last = (uint32_t)(last << (23 - Y)) + tc.dec_bias;
+    sc.g_inf = specials == EXMY_SPECIALS_IEEE ? (uint32_t)(inf << (23 - Y)) + tc.dec_bias : 0xFFFFFFFFu;
+    e = specials_dispatch(dt, 1 + X + Y, op == 1, wide, src, dst, n, fc, tc, sc, s);
+  }
+  return e == hipSuccess ? EXMY_OK : EXMY_ERR_DEVICE;
+}
+}  // namespace
+
+exmy_status_t exmy_encode_specials(const void* src, exmy_dtype_t dt, uint64_t n, int X, int Y, int max_exp,
+                                   exmy_specials_t specials, void* dst_packed, void* stream) {
+  return run_specials(0, src, dst_packed, dt, n, X, Y, max_exp, specials, stream);
+}
+
+exmy_status_t exmy_decode_specials(const void* src_packed, exmy_dtype_t dt_out, uint64_t n, int X, int Y, int max_exp,
+                                   exmy_specials_t specials, void* dst, void* stream) {
+  return run_specials(1, src_packed, dst, dt_out, n, X, Y, max_exp, specials, stream);
+}
+
+exmy_status_t exmy_emulate_specials(void* data_inout, exmy_dtype_t dt, uint64_t n, int X, int Y, int max_exp,
+                                    exmy_specials_t specials, void* stream) {
+  return run_specials(2, data_inout, data_inout, dt, n, X, Y, max_exp, specials, stream);
+}
+
 size_t exmy_block_count(uint64_t n, uint64_t block) { return block ? (size_t)((n + block - 1) / block) : 0; }
 
 size_t exmy_tile_count(uint64_t rows, uint64_t cols, uint64_t tile_rows, uint64_t tile_cols) {

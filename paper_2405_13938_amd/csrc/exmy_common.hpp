@@ -82,6 +82,15 @@ struct BlockConsts {
   uint32_t round_odd;
 };
 
+// Constants of the formats with reserved NaN / Inf code points (see exmy_specials_kernel.hpp).
+struct SpecialConsts {
+  uint32_t nan_left;    // the all-ones magnitude code, left-aligned as magnitude_code_left returns codes
+  uint32_t inf_left;    // the Inf code likewise; NaN only: the largest finite code (Inf saturates)
+  // decode side, on g = (code << (23 - Y)) + dec_bias, which grows with the code:
+  uint32_t g_last;      // g of the largest finite code
+  uint32_t g_inf;       // g of the Inf code; NaN only: 0xFFFFFFFF, which no code reaches
+};
+
 // Constants of the two's complement reading of e0mY (Section 2 "Format"): the
 // code is a (1 + Y)-bit two's complement integer k, the value k quanta.
 struct IntConsts {

@@ -38,6 +38,10 @@ hipError_t decode_dispatch(exmy_dtype_t dt, int W, bool x8, const BatchArgs& arg
 // records are the planar form.  flag: encode - the fp64 rounding path; decode - X = 8.
 hipError_t records_dispatch(exmy_dtype_t dt, int W, bool decode, bool flag, const void* src, void* dst, uint64_t n,
                             const FormatConsts& fc, const TensorConsts& tc, hipStream_t stream);
+// Reserved NaN / Inf code points (W <= 16); tc.sat_bits holds the largest finite value.
+hipError_t specials_dispatch(exmy_dtype_t dt, int W, bool decode, bool wide, const void* src, void* dst, uint64_t n,
+                             const FormatConsts& fc, const TensorConsts& tc, const SpecialConsts& sc,
+                             hipStream_t stream);
 // W = 32 (e8m23 on fp32): the packed form is the array of codes; encode and decode clamp Inf / NaN patterns.
 hipError_t codes32_dispatch(bool decode, const BatchArgs& args, uint64_t n_max, hipStream_t stream);
 hipError_t emulate_dispatch(exmy_dtype_t dt, bool wide, void* data, uint64_t n, const FormatConsts& fc,

@@ -344,3 +344,29 @@ def test_record_entry_points_validate_without_launch():
         assert f(ok, B.F32, 0, 5, 10, 130, ok, None) == 0
         assert f(ok, B.BF16, 0, 3, 3, 6, ok, None) == 3
         assert f(ok, B.BF16, (1 << 40) + 8, 3, 3, 130, ok, None) == 4
+
+
+def test_reserved_code_entry_points_validate_without_launch():
+    L = B.lib()
+    ok, odd = ctypes.c_void_p(0x1000), ctypes.c_void_p(0x1008)
+    enc, dec, emu = L.exmy_encode_specials, L.exmy_decode_specials, L.exmy_emulate_specials
+    IEEE, NAN_ONLY = B.SPECIALS_IEEE, B.SPECIALS_NAN_ONLY
+    for f in (enc, dec):
+        assert f(ok, B.BF16, 0, 5, 2, 143, IEEE, ok, None) == 0
+        assert f(ok, B.BF16, 0, 4, 3, 135, NAN_ONLY, ok, None) == 0
+        assert f(ok, B.BF16, 0, 8, 7, 255, IEEE, ok, None) == 0      # bf16 itself
+        assert f(ok, B.BF16, 0, 8, 7, 255, NAN_ONLY, ok, None) == 2
+        assert f(ok, B.BF16, 0, 0, 3, 130, IEEE, ok, None) == 2      # no exponent code to reserve
+        assert f(ok, B.BF16, 0, 0, 3, 130, NAN_ONLY, ok, None) == 0
+        assert f(ok, B.BF16, 0, 0, 0, 130, NAN_ONLY, ok, None) == 2
+        assert f(ok, B.BF16, 0, 3, 3, 130, 0, ok, None) == 2
+        assert f(ok, B.BF16, 0, 3, 3, 130, 3, ok, None) == 2
+        assert f(ok, B.F32, 0, 4, 12, 130, IEEE, ok, None) == 2      # packed form stops at 16 bits
+        assert f(ok, B.BF16, 0, 3, 3, 6, IEEE, ok, None) == 3
+        assert f(None, B.BF16, 8, 3, 3, 130, IEEE, ok, None) == 1
+        assert f(ok, B.BF16, 8, 3, 3, 130, IEEE, None, None) == 1
+        assert f(odd, B.BF16, 8, 3, 3, 130, IEEE, ok, None) == 5
+        assert f(ok, B.BF16, (1 << 40) + 8, 3, 3, 130, IEEE, ok, None) == 4
+    assert emu(ok, B.F32, 0, 4, 12, 130, IEEE, None) == 0
+    assert emu(None, B.F32, 8, 4, 12, 130, IEEE, None) == 1
+    assert emu(odd, B.F32, 8, 4, 12, 130, NAN_ONLY, None) == 5
