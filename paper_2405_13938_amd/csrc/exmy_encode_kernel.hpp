@@ -182,6 +182,29 @@ __device__ __forceinline__ void flush_stage(const PlaneStage<W, kTileGroups>& st
   __syncthreads();  // the image is free for the next tile
 }
 
+// The same for the first `count` groups of an image (a multiple of 16, so that every plane's part is whole
+// 16-byte pieces), through plane descriptors whose base lies `tile_group` groups before the image's first group.
+template <int W, int kTileGroups, int kBlock, int P = 0>
+__device__ __forceinline__ void copy_stage_groups(const PlaneStage<W, kTileGroups>& st, const PlaneDst<W>& pd,
+                                                  uint32_t tile_group, uint32_t count) {
+  if constexpr (P < Planes<W>::count) {
+    constexpr uint32_t S = Planes<W>::seg(P);
+    constexpr uint32_t LO = Planes<W>::lo(P);
+    const uint32_t pieces = count * S / 16;
+    for (uint32_t c = threadIdx.x; c < pieces; c += kBlock)
+      store16<true>(pd.plane[P], c * 16, tile_group * S, *reinterpret_cast<const uint4*>(st.lds + kTileGroups * LO + c * 16));
+    copy_stage_groups<W, kTileGroups, kBlock, P + 1>(st, pd, tile_group, count);
+  }
+}
+
+template <int W, int kTileGroups, int kBlock>
+__device__ __forceinline__ void flush_stage_groups(const PlaneStage<W, kTileGroups>& st, const PlaneDst<W>& pd,
+                                                   uint32_t tile_group, uint32_t count) {
+  __syncthreads();
+  copy_stage_groups<W, kTileGroups, kBlock>(st, pd, tile_group, count);
+  __syncthreads();
+}
+
 // Peel the planes off the left-aligned codes from the most significant segment
 // down.  With an odd W the top plane is 1 bit wide and is exactly the sign: it is
 // taken from the source bits u, and f holds the magnitude alone.
@@ -590,8 +613,11 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_small_kernel(const 
 // block's groups (the block must not exceed kBlock * kUnroll groups).
 template <typename T, int W, int kBlock, int kUnroll, bool kNT>
 __global__ __launch_bounds__(kBlock) void encode_blocks_auto_team_kernel(const BlockArgs args) {
+  constexpr uint32_t TG = kBlock * kUnroll;
   constexpr int kLoads = TileRegs<T, kUnroll>::kLoads;
   __shared__ int32_t part[kBlock / 64];
+  __shared__ __align__(16) uint8_t lds_stage[TG * W];
+  const PlaneStage<W, TG> stage{lds_stage};
   const uint4* __restrict__ src4 = static_cast<const uint4*>(args.src);
   uint8_t* __restrict__ dst = static_cast<uint8_t*>(args.dst);
   const uint64_t n = args.n;
@@ -600,13 +626,16 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_team_kernel(const B
   const uint64_t G = (n + 7) / 8;
   const uint64_t Gfull = n / 8;
   const uint32_t bg = args.block_groups;
+  // only the last block can be short or end in a ragged group (see units_in_tile for why the bookkeeping
+  // avoids 64-bit order compares)
+  const uint64_t last_g0 = (args.n_blocks - 1) * bg;
+  const uint32_t last_count = (uint32_t)(G - last_g0), last_whole = (uint32_t)(Gfull - last_g0);
 
   for (uint64_t b = blockIdx.x; b < args.n_blocks; b += gridDim.x) {
     const uint64_t g0 = b * bg;
-    const uint64_t left = G - g0;
-    const uint32_t count = left < bg ? (uint32_t)left : bg;  // groups of this block, a ragged last one included
-    const uint64_t whole_left = Gfull > g0 ? Gfull - g0 : 0;
-    const uint32_t whole = whole_left < count ? (uint32_t)whole_left : count;
+    const bool is_last = b + 1 == args.n_blocks;
+    const uint32_t count = is_last ? last_count : bg;  // groups of this block, a ragged last one included
+    const uint32_t whole = is_last ? last_whole : bg;  // of them, with all 8 elements
     const rsrc_t src = make_rsrc(src4 + g0 * kLoads);
     TileRegs<T, kUnroll> regs;
     load_tile<T, kBlock, kUnroll, kNT, true>(src, 0, whole, regs);
@@ -635,6 +664,18 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_team_kernel(const B
     if (threadIdx.x == 0) args.meta[b] = (uint8_t)me;
     PlaneDst<W> pd;
     make_plane_dst<W>(dst, G, g0, pd);
+    if (whole == count && count % 16 == 0) {  // whole 16-byte pieces of every plane: out through the LDS image
+#pragma unroll
+      for (int r = 0; r < kUnroll; ++r) {
+        if (r * kBlock + threadIdx.x < count) {
+          uint32_t u[8];
+          group_bits<T>(regs.v[r], u);
+          encode_group_meta<W>(u, me, fc, bc, stage, threadIdx.x, r * kBlock);
+        }
+      }
+      flush_stage_groups<W, TG, kBlock>(stage, pd, 0, count);
+      continue;
+    }
 #pragma unroll
     for (int r = 0; r < kUnroll; ++r) {
       const uint32_t idx = r * kBlock + threadIdx.x;
@@ -657,6 +698,8 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_twopass_kernel(cons
   constexpr uint32_t TG = kBlock * kUnroll;
   constexpr int kLoads = TileRegs<T, kUnroll>::kLoads;
   __shared__ int32_t part[kBlock / 64];
+  __shared__ __align__(16) uint8_t lds_stage[TG * W];
+  const PlaneStage<W, TG> stage{lds_stage};
   const uint4* __restrict__ src4 = static_cast<const uint4*>(args.src);
   uint8_t* __restrict__ dst = static_cast<uint8_t*>(args.dst);
   const uint64_t n = args.n;
@@ -665,13 +708,16 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_twopass_kernel(cons
   const uint64_t G = (n + 7) / 8;
   const uint64_t Gfull = n / 8;
   const uint32_t bg = args.block_groups;
+  // only the last block can be short or end in a ragged group (see units_in_tile for why the bookkeeping
+  // avoids 64-bit order compares)
+  const uint64_t last_g0 = (args.n_blocks - 1) * bg;
+  const uint32_t last_count = (uint32_t)(G - last_g0), last_whole = (uint32_t)(Gfull - last_g0);
 
   for (uint64_t b = blockIdx.x; b < args.n_blocks; b += gridDim.x) {
     const uint64_t g0 = b * bg;
-    const uint64_t left = G - g0;
-    const uint32_t count = left < bg ? (uint32_t)left : bg;  // groups of this block, a ragged last one included
-    const uint64_t whole_left = Gfull > g0 ? Gfull - g0 : 0;
-    const uint32_t whole = whole_left < count ? (uint32_t)whole_left : count;
+    const bool is_last = b + 1 == args.n_blocks;
+    const uint32_t count = is_last ? last_count : bg;  // groups of this block, a ragged last one included
+    const uint32_t whole = is_last ? last_whole : bg;  // of them, with all 8 elements
     const rsrc_t src = make_rsrc(src4 + g0 * kLoads);
     const uint32_t tiles = (whole + TG - 1) / TG;
 
@@ -709,15 +755,21 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_twopass_kernel(cons
     make_plane_dst<W>(dst, G, g0, pd);
     for (uint32_t t = 0; t < tiles; ++t) {
       TileRegs<T, kUnroll> regs;
-      load_tile<T, kBlock, kUnroll, kNT, true>(src, t * TG, whole - t * TG, regs);
+      const uint32_t here = min(whole - t * TG, TG);  // groups of this tile
+      load_tile<T, kBlock, kUnroll, kNT, true>(src, t * TG, here, regs);
+      const bool staged = here % 16 == 0;  // whole 16-byte pieces of every plane: out through the LDS image
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r) {
-        if (r * kBlock + threadIdx.x < whole - t * TG) {
+        if (r * kBlock + threadIdx.x < here) {
           uint32_t u[8];
           group_bits<T>(regs.v[r], u);
-          encode_group_meta<W>(u, me, fc, bc, pd, threadIdx.x, t * TG + r * kBlock);
+          if (staged)
+            encode_group_meta<W>(u, me, fc, bc, stage, threadIdx.x, r * kBlock);
+          else
+            encode_group_meta<W>(u, me, fc, bc, pd, threadIdx.x, t * TG + r * kBlock);
         }
       }
+      if (staged) flush_stage_groups<W, TG, kBlock>(stage, pd, t * TG, here);
     }
     if (has_ragged) {
       PlaneDst<W> pr;
