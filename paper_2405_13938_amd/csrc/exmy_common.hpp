@@ -341,6 +341,17 @@ __device__ __forceinline__ TensorConsts derive_tc(uint32_t max_exp, const BlockC
 __device__ __forceinline__ int32_t exp_key(uint32_t u) { return (int32_t)((u & 0x7FFFFFFFu) + 0x00800000u); }
 constexpr int32_t kNoKey = (int32_t)0x80000000;
 
+// The same keys for the two bf16 halves of a dword at once, as two signed 16-bit integers (the upper 16
+// bits of exp_key of each element): no carry crosses the halves, and a packed 16-bit maximum then handles
+// two elements per instruction.  key_of_pair is the larger of the two as an exp_key.
+typedef short i16x2_t __attribute__((ext_vector_type(2)));
+constexpr uint32_t kNoPairKeys = 0x80008000u;
+__device__ __forceinline__ uint32_t pair_keys(uint32_t w) { return (w & 0x7FFF7FFFu) + 0x00800080u; }
+__device__ __forceinline__ uint32_t max_pair_keys(uint32_t a, uint32_t b) {
+  return __builtin_bit_cast(uint32_t, __builtin_elementwise_max(__builtin_bit_cast(i16x2_t, a), __builtin_bit_cast(i16x2_t, b)));
+}
+__device__ __forceinline__ int32_t key_of_pair(uint32_t p) { return max((int32_t)(p & 0xFFFF0000u), (int32_t)(p << 16)); }
+
 // Metadatum of a block from the largest key of its elements: the biased exponent
 // of the largest finite magnitude, "before rounding" or, with the round_* fields
 // set, after that magnitude is rounded to the mantissa width of the top binade

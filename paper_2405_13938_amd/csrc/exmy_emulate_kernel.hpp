@@ -5,6 +5,8 @@
 // per tile, launched in address order (see the encoder for why).
 #pragma once
 
+#include <type_traits>
+
 #include "exmy_common.hpp"
 
 namespace exmy {
@@ -242,6 +244,9 @@ __global__ __launch_bounds__(kBlock) void emulate_blocks_kernel(const BlockArgs 
 template <typename T, typename V4>
 __device__ __forceinline__ int32_t vector_exp_key(V4 v) {
   const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  if constexpr (std::is_same<T, uint16_t>::value)  // bf16: two elements per instruction
+    return key_of_pair(max_pair_keys(max_pair_keys(pair_keys(w[0]), pair_keys(w[1])),
+                                     max_pair_keys(pair_keys(w[2]), pair_keys(w[3]))));
   int32_t m = (int32_t)0x80000000;
 #pragma unroll
   for (int k = 0; k < 4; ++k) {

@@ -14,6 +14,8 @@
 // measured faster here than a grid-stride loop of resident blocks.
 #pragma once
 
+#include <type_traits>
+
 #include "exmy_common.hpp"
 
 namespace exmy {
@@ -532,6 +534,15 @@ __device__ __forceinline__ int32_t group_key(const uint32_t u[8]) {
   return k;
 }
 
+// The same from the group as loaded (v) and unpacked (u): a bf16 group takes its key from the packed pairs.
+template <typename T>
+__device__ __forceinline__ int32_t group_key(const uint4* v, const uint32_t u[8]) {
+  if constexpr (std::is_same<T, uint16_t>::value)
+    return key_of_pair(max_pair_keys(max_pair_keys(pair_keys(v[0].x), pair_keys(v[0].y)),
+                                     max_pair_keys(pair_keys(v[0].z), pair_keys(v[0].w))));
+  return group_key(u);
+}
+
 // Blocks of 2^lg groups, lg <= 6: flat tiles; the lanes of a block combine their
 // keys with a butterfly, one of them writes the metadatum, all of them encode.
 template <typename T, int W, int kBlock, int kUnroll, bool kNT>
@@ -567,7 +578,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_small_kernel(const 
         const uint32_t idx = r * kBlock + threadIdx.x;
         uint32_t u[8];
         group_bits<T>(regs.v[r], u);
-        const uint32_t me = meta_from_key(max_over_lanes(group_key(u), lg), bc);
+        const uint32_t me = meta_from_key(max_over_lanes(group_key<T>(regs.v[r], u), lg), bc);
         if ((threadIdx.x & ((1u << lg) - 1u)) == 0) {
           if (meta_words)
             lds_meta[idx >> lg] = (uint8_t)me;
@@ -594,7 +605,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_small_kernel(const 
       int32_t key = kNoKey;
       if (idx < whole) {
         group_bits<T>(regs.v[r], u);
-        key = group_key(u);
+        key = group_key<T>(regs.v[r], u);
       } else if (g < G) {  // the ragged last group of the tensor
         ragged_group_bits<T>(args.src, g * 8, n, u);
         key = group_key(u);
@@ -648,7 +659,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_team_kernel(const B
       if (r * kBlock + threadIdx.x < whole) {
         uint32_t u[8];
         group_bits<T>(regs.v[r], u);
-        key = max(key, group_key(u));
+        key = max(key, group_key<T>(regs.v[r], u));
       }
     }
     if (has_ragged) key = max(key, group_key(ragged));
@@ -731,7 +742,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_twopass_kernel(cons
         if (r * kBlock + threadIdx.x < whole - t * TG) {
           uint32_t u[8];
           group_bits<T>(regs.v[r], u);
-          key = max(key, group_key(u));
+          key = max(key, group_key<T>(regs.v[r], u));
         }
       }
     }

@@ -404,7 +404,9 @@ __global__ __launch_bounds__(kBlock) void tile_max_exp_kernel(const TileArgs arg
     __syncthreads();
 
     if (row_begin < row_end && cv < geo.vpr) {
+      constexpr bool kPairs = kColumns && std::is_same<T, uint16_t>::value;  // bf16 columns: keys in packed pairs
       int32_t key[kColumns ? E : 1];
+      uint32_t pairs[4] = {kNoPairKeys, kNoPairKeys, kNoPairKeys, kNoPairKeys};
 #pragma unroll
       for (int e = 0; e < (kColumns ? E : 1); ++e) key[e] = kNoKey;
       for (uint32_t s0 = 0; s0 < geo.row_steps; s0 += kBatch) {
@@ -426,7 +428,9 @@ __global__ __launch_bounds__(kBlock) void tile_max_exp_kernel(const TileArgs arg
               const uint32_t w[4] = {v[s].x, v[s].y, v[s].z, v[s].w};
 #pragma unroll
               for (int k = 0; k < 4; ++k) {
-                if constexpr (sizeof(T) == 4) {
+                if constexpr (kPairs) {
+                  pairs[k] = max_pair_keys(pairs[k], pair_keys(w[k]));
+                } else if constexpr (sizeof(T) == 4) {
                   key[k] = max(key[k], exp_key(w[k]));
                 } else {
                   key[2 * k] = max(key[2 * k], exp_key(lo_elem_bits<T>(w[k])));
@@ -437,6 +441,13 @@ __global__ __launch_bounds__(kBlock) void tile_max_exp_kernel(const TileArgs arg
               key[0] = max(key[0], emu::vector_exp_key<T>(v[s]));
             }
           }
+        }
+      }
+      if constexpr (kPairs) {
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+          key[2 * k] = (int32_t)(pairs[k] << 16);
+          key[2 * k + 1] = (int32_t)(pairs[k] & 0xFFFF0000u);
         }
       }
       if constexpr (kColumns) {
