@@ -261,6 +261,20 @@ def block_scheme_rates(exmy, synth, dev):
         }
         res[label] = {name: round(nbytes / timed(fn) / 1e9, 1) for name, (nbytes, fn) in rates.items()}
         res[label]["unit"] = "GB/s"
+
+    # the same slab, per-tensor metadata, in the other code arrangements: records (W bytes per group), reserved
+    # NaN / Inf code points (IEEE style), two's complement e0m5
+    me = 124
+    rates = {
+        "encode_records": (codec, rot(lambda k: exmy.encode_records(xs[k], X, Y, me, out=outs[k]))),
+        "decode_records": (codec, rot(lambda k: exmy.decode_records(outs[k], torch.bfloat16, n, X, Y, me, out=dst))),
+        "encode_specials": (codec, rot(lambda k: exmy.encode_specials(xs[k], X, Y, me, 1, out=outs[k]))),
+        "decode_specials": (codec, rot(lambda k: exmy.decode_specials(outs[k], torch.bfloat16, n, X, Y, me, 1, out=dst))),
+        "encode_int": (codec, rot(lambda k: exmy.encode_int(xs[k], 5, 118, out=outs[k]))),
+        "decode_int": (codec, rot(lambda k: exmy.decode_int(outs[k], torch.bfloat16, n, 5, 118, out=dst))),
+    }
+    res["other_arrangements_e3m2"] = {name: round(nbytes / timed(fn) / 1e9, 1) for name, (nbytes, fn) in rates.items()}
+    res["other_arrangements_e3m2"]["unit"] = "GB/s"
     return res
 
 
