@@ -25,7 +25,7 @@ template <bool kHist>
 struct Shape<f16_t, kHist> : Shape<uint16_t, kHist> {};
 template <bool kHist>
 struct Shape<float, kHist> {
-  static constexpr int kBlock = kHist ? 512 : 128;
+  static constexpr int kBlock = kHist ? 512 : 64;
   static constexpr int kUnroll = kHist ? 2 : 1;
   static constexpr int kChunk = kHist ? 8 : 1;
   static constexpr bool kNT = true;

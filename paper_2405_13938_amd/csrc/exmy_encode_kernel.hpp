@@ -47,10 +47,38 @@ __device__ __forceinline__ void flush_bins(uint32_t* bins, unsigned long long* _
   __syncthreads();
 }
 
+// The group of a tile row of kBlock groups that a lane converts when the row is whole.
+// 16-bit elements: its own.  fp32: a row is read as two runs of 16 bytes per lane, so
+// that each load covers whole lines (a lane reading its group's 32 bytes makes two loads
+// that each skip every other 16 bytes: the same bytes, 5-8 % slower).  The lanes of a
+// pair (2k, 2k+1) then hold both halves of groups k and kBlock / 2 + k; the even lane
+// takes the first, the odd lane the second (see group_bits).
+template <typename T, int kBlock>
+__device__ __forceinline__ uint32_t row_slot() {
+  if constexpr (sizeof(T) == 4)
+    return (threadIdx.x >> 1) + (threadIdx.x & 1u) * (kBlock / 2);
+  else
+    return threadIdx.x;
+}
+
+// The other lane of the pair's value (all lanes of the wavefront must be active).
+__device__ __forceinline__ uint32_t from_pair_lane(uint32_t x) {
+  return (uint32_t)__builtin_amdgcn_update_dpp((int)x, (int)x, 0xB1 /* quad_perm 1,0,3,2 */, 0xF, 0xF, false);
+}
+
 // fp32-position bit patterns of the 8 elements of a group held in 16-byte vectors.
-template <typename T>
+// kPaired (fp32 only): v[0], v[1] are the lane's two pieces of a whole row as
+// load_tile reads it, and the lanes of a pair swap one piece each.
+template <typename T, bool kPaired = false>
 __device__ __forceinline__ void group_bits(const uint4* v, uint32_t u[8]) {
-  if constexpr (sizeof(T) == 4) {
+  if constexpr (sizeof(T) == 4 && kPaired) {
+    const bool odd = threadIdx.x & 1u;
+    const uint4 give = odd ? v[0] : v[1];  // the piece of the group the other lane takes
+    const uint4 got = make_uint4(from_pair_lane(give.x), from_pair_lane(give.y), from_pair_lane(give.z), from_pair_lane(give.w));
+    const uint4 lo = odd ? got : v[0], hi = odd ? v[1] : got;
+    u[0] = lo.x; u[1] = lo.y; u[2] = lo.z; u[3] = lo.w;
+    u[4] = hi.x; u[5] = hi.y; u[6] = hi.z; u[7] = hi.w;
+  } else if constexpr (sizeof(T) == 4) {
     u[0] = v[0].x; u[1] = v[0].y; u[2] = v[0].z; u[3] = v[0].w;
     u[4] = v[1].x; u[5] = v[1].y; u[6] = v[1].z; u[7] = v[1].w;
   } else {
@@ -251,19 +279,23 @@ struct TileRegs {
 };
 
 // Loads of one tile: `src` is the descriptor of the chunk, tile_group the tile's
-// first group relative to it (wave-uniform); lane i takes groups r*kBlock + i.
-// kGuard: only the first `rem` groups of the tile exist.
-template <typename T, int kBlock, int kUnroll, bool kNT, bool kGuard>
+// first group relative to it (wave-uniform).
+// kGuard: only the first `rem` groups of the tile exist.  kPairs (whole tiles only):
+// lane i ends up with groups r*kBlock + row_slot(), for fp32 through
+// group_bits<T, true>; otherwise it loads groups r*kBlock + i.
+template <typename T, int kBlock, int kUnroll, bool kNT, bool kGuard, bool kPairs = !kGuard>
 __device__ __forceinline__ void load_tile(rsrc_t src, uint32_t tile_group, uint32_t rem, TileRegs<T, kUnroll>& regs) {
+  static_assert(!(kGuard && kPairs), "lanes of a pair must both be active");
   constexpr int kLoads = TileRegs<T, kUnroll>::kLoads;
   constexpr uint32_t kGroupBytes = 16 * kLoads;
-  const uint32_t lane_off = threadIdx.x * kGroupBytes;
+  constexpr bool kRuns = sizeof(T) == 4 && kPairs;  // pieces i and kBlock + i of the row instead of 2i and 2i + 1
+  const uint32_t lane_off = threadIdx.x * (kRuns ? 16 : kGroupBytes);
 #pragma unroll
   for (int r = 0; r < kUnroll; ++r) {
     if (!kGuard || r * kBlock + threadIdx.x < rem) {
 #pragma unroll
       for (int l = 0; l < kLoads; ++l)
-        regs.v[r][l] = load16<kNT>(src, lane_off, (tile_group + r * kBlock) * kGroupBytes + l * 16);
+        regs.v[r][l] = load16<kNT>(src, lane_off, (tile_group + r * kBlock) * kGroupBytes + l * (kRuns ? 16 * kBlock : 16));
     }
   }
 }
@@ -277,13 +309,13 @@ __device__ __forceinline__ void encode_tile(const TileRegs<T, kUnroll>& regs, co
   for (int r = 0; r < kUnroll; ++r) {
     if (!kGuard || r * kBlock + threadIdx.x < rem) {
       uint32_t u[8];
-      group_bits<T>(regs.v[r], u);
+      group_bits<T, !kGuard>(regs.v[r], u);
       if constexpr (kHist) {
         const uint32_t copy = threadIdx.x & (kHistCopies - 1);
 #pragma unroll
         for (int j = 0; j < 8; ++j) atomicAdd(&lds_hist[((u[j] >> 23) & 0xFFu) * kHistCopies + copy], 1u);
       }
-      encode_group<W, kWide>(u, fc, tc, pd, threadIdx.x, tile_group + r * kBlock);
+      encode_group<W, kWide>(u, fc, tc, pd, kGuard ? threadIdx.x : row_slot<T, kBlock>(), tile_group + r * kBlock);
     }
   }
 }
@@ -448,17 +480,18 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
     uint32_t me[kUnroll];  // the block's metadatum, or the bits of its scale
     if (tile < full_tiles) {
       load_tile<T, kBlock, kUnroll, kNT, false>(src, 0, 0, regs);
+      const uint32_t slot = row_slot<T, kBlock>();
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r)
-        me[r] = load_block_datum<kScaled>(mt, lane_block<TG>(off + r * kBlock + threadIdx.x, bi), args.scale_log2_bytes);
+        me[r] = load_block_datum<kScaled>(mt, lane_block<TG>(off + r * kBlock + slot, bi), args.scale_log2_bytes);
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r) {
         uint32_t u[8];
-        group_bits<T>(regs.v[r], u);
+        group_bits<T, true>(regs.v[r], u);
         if constexpr (kScaled)  // more arithmetic per element: the stage measured slower here
-          encode_group_scaled<W>(u, me[r], fc, args.tc127, pd, threadIdx.x, r * kBlock);
+          encode_group_scaled<W>(u, me[r], fc, args.tc127, pd, slot, r * kBlock);
         else
-          encode_group_meta<W>(u, me[r], fc, bc, stage, threadIdx.x, r * kBlock);
+          encode_group_meta<W>(u, me[r], fc, bc, stage, slot, r * kBlock);
       }
       if constexpr (!kScaled) flush_stage<W, TG, kBlock>(stage, dst, G, g0);
     } else {
@@ -572,7 +605,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_small_kernel(const 
     const uint32_t whole = units_in_tile(tile, full_tiles, rem_whole, TG);  // groups of this tile with all 8 elements
     TileRegs<T, kUnroll> regs;
     if (tile < full_tiles) {
-      load_tile<T, kBlock, kUnroll, kNT, false>(src, 0, 0, regs);
+      load_tile<T, kBlock, kUnroll, kNT, false, false>(src, 0, 0, regs);  // neighbouring lanes share a block: no pairs
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r) {
         const uint32_t idx = r * kBlock + threadIdx.x;

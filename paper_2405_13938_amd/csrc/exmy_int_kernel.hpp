@@ -79,8 +79,8 @@ __global__ __launch_bounds__(kBlock) void encode_int_kernel(const void* src_v, v
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r) {
         uint32_t u[8];
-        enc::group_bits<T>(regs.v[r], u);
-        encode_group<W>(u, ic, stage, threadIdx.x, r * kBlock);
+        enc::group_bits<T, true>(regs.v[r], u);
+        encode_group<W>(u, ic, stage, enc::row_slot<T, kBlock>(), r * kBlock);
       }
       enc::flush_stage<W, TG, kBlock>(stage, dst, G, g0);
       continue;

@@ -102,11 +102,11 @@ __global__ __launch_bounds__(kBlock) void encode_records_kernel(const void* __re
       enc::load_tile<T, kBlock, kUnroll, true, kGuard>(src, 0, whole, regs);
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r) {
-        const uint32_t jl = r * kBlock + threadIdx.x;
+        const uint32_t jl = r * kBlock + (kGuard ? threadIdx.x : enc::row_slot<T, kBlock>());
         if (!kGuard || jl < here) {
           uint32_t u[8];
           if (!kGuard || jl < whole)
-            enc::group_bits<T>(regs.v[r], u);
+            enc::group_bits<T, !kGuard>(regs.v[r], u);
           else
             enc::ragged_group_bits<T>(src_v, (g0 + jl) * 8, n, u);
           uint32_t f[8];

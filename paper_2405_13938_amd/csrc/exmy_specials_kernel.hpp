@@ -58,8 +58,8 @@ __global__ __launch_bounds__(kBlock) void encode_specials_kernel(const void* src
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r) {
         uint32_t u[8];
-        enc::group_bits<T>(regs.v[r], u);
-        encode_group<W, kWide>(u, fc, tc, sc, stage, threadIdx.x, r * kBlock);
+        enc::group_bits<T, true>(regs.v[r], u);
+        encode_group<W, kWide>(u, fc, tc, sc, stage, enc::row_slot<T, kBlock>(), r * kBlock);
       }
       enc::flush_stage<W, TG, kBlock>(stage, dst, G, g0);
       continue;

@@ -129,19 +129,20 @@ __global__ __launch_bounds__(kBlock) void encode_tiles_kernel(const TileArgs arg
     auto body = [&](auto guard, const auto& out) {
       constexpr bool kGuard = decltype(guard)::value;
       enc::load_tile<T, kBlock, kUnroll, kNT, kGuard>(src, 0, rem_groups, regs);
+      const uint32_t slot = kGuard ? threadIdx.x : enc::row_slot<T, kBlock>();  // the lane's group of a tile row
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r)
-        if (!kGuard || r * kBlock + threadIdx.x < rem_groups)
-          me[r] = load_unit_meta<kColumns, 8>(mt, tile_meta_offset<TG, kColumns>(r * kBlock + threadIdx.x, ti, ts));
+        if (!kGuard || r * kBlock + slot < rem_groups)
+          me[r] = load_unit_meta<kColumns, 8>(mt, tile_meta_offset<TG, kColumns>(r * kBlock + slot, ti, ts));
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r) {
-        if (!kGuard || r * kBlock + threadIdx.x < rem_groups) {  // the rounding-variant vote is among the lanes that get here
+        if (!kGuard || r * kBlock + slot < rem_groups) {  // the rounding-variant vote is among the lanes that get here
           uint32_t u[8];
-          enc::group_bits<T>(regs.v[r], u);
+          enc::group_bits<T, !kGuard>(regs.v[r], u);
           if constexpr (kColumns)
-            encode_group_each<W>(u, me[r], fc, bc, tc_ref, out, threadIdx.x, r * kBlock);
+            encode_group_each<W>(u, me[r], fc, bc, tc_ref, out, slot, r * kBlock);
           else
-            enc::encode_group_meta<W>(u, me[r].w[0], fc, bc, out, threadIdx.x, r * kBlock);
+            enc::encode_group_meta<W>(u, me[r].w[0], fc, bc, out, slot, r * kBlock);
         }
       }
     };
