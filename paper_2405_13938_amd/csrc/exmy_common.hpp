@@ -578,6 +578,23 @@ struct Planes {
   }
 };
 
+
+// The LDS image of a tile of kTileGroups groups holds the tile's part of plane P at byte
+// kTileGroups * lo(P), the word of the tile's group i at i * seg(P) inside it.  Memory
+// address of the 16-byte piece at byte `off` of that image; g0 is the tile's first group,
+// G the tensor's group count.  A piece lies inside one plane because kTileGroups is a
+// multiple of 16.
+template <int W, int kTileGroups, int P = 0>
+__device__ __forceinline__ uint8_t* tile_piece_address(uint8_t* packed, uint64_t G, uint64_t g0, uint32_t off) {
+  static_assert(kTileGroups % 16 == 0, "plane images must be whole 16-byte pieces");
+  constexpr uint32_t S = Planes<W>::seg(P);
+  constexpr uint32_t LO = Planes<W>::lo(P);
+  if constexpr (P + 1 < Planes<W>::count) {
+    if (off >= kTileGroups * (LO + S)) return tile_piece_address<W, kTileGroups, P + 1>(packed, G, g0, off);
+  }
+  return packed + (G * LO + g0 * S + (off - kTileGroups * LO));
+}
+
 #endif  // __HIPCC__
 
 }  // namespace exmy

@@ -127,6 +127,49 @@ __device__ __forceinline__ void decode_unit(const UnitWords<W>& uw, const Format
   }
 }
 
+// A lane of a narrow format reads 1-3 bytes per plane straight from memory.  Whole tiles
+// can instead come through an LDS image (see tile_piece_address) filled with 16-byte
+// loads, which pays at W = 3 only (see the launcher).
+template <int W, int kTileGroups, int kBlock>
+__device__ __forceinline__ void load_image(const uint8_t* __restrict__ src, uint64_t G, uint64_t g0, uint8_t* lds) {
+  constexpr uint32_t kPieces = kTileGroups * W / 16;
+#pragma unroll
+  for (uint32_t c0 = 0; c0 < kPieces; c0 += kBlock) {
+    const uint32_t c = c0 + threadIdx.x;
+    if (kPieces % kBlock == 0 || c < kPieces) {
+      const u32x4_t w = __builtin_nontemporal_load(
+          reinterpret_cast<const u32x4_t*>(tile_piece_address<W, kTileGroups>(const_cast<uint8_t*>(src), G, g0, c * 16)));
+      *reinterpret_cast<uint4*>(lds + c * 16) = make_uint4(w.x, w.y, w.z, w.w);
+    }
+  }
+}
+
+// Unit `unit` of the tile from its image, laid out as load_unit leaves it.
+template <int W, int E, int kTileGroups, int P = 0>
+__device__ __forceinline__ void image_unit(const uint8_t* lds, uint32_t unit, UnitWords<W>& uw) {
+  if constexpr (P < Planes<W>::count) {
+    constexpr int S = Planes<W>::seg(P);
+    constexpr int kBits = E * S;  // of plane P per unit
+    const uint8_t* p = lds + kTileGroups * Planes<W>::lo(P) + unit * kBits / 8;
+    if constexpr (kBits == 128) {
+      const uint4 v = *reinterpret_cast<const uint4*>(p);
+      uw.w[P][0] = v.x; uw.w[P][1] = v.y; uw.w[P][2] = v.z; uw.w[P][3] = v.w;
+    } else if constexpr (kBits == 64) {
+      const uint2 v = *reinterpret_cast<const uint2*>(p);
+      uw.w[P][0] = v.x; uw.w[P][1] = v.y;
+    } else if constexpr (kBits == 32) {
+      uw.w[P][0] = *reinterpret_cast<const uint32_t*>(p);
+    } else if constexpr (kBits == 16) {
+      uw.w[P][0] = *reinterpret_cast<const uint16_t*>(p);
+    } else if constexpr (kBits == 8) {
+      uw.w[P][0] = *p;
+    } else {  // 4 bits: a nibble of the byte shared with the neighbouring unit
+      uw.w[P][0] = (uint32_t)*p >> (4 * (unit & 1u));
+    }
+    image_unit<W, E, kTileGroups, P + 1>(lds, unit, uw);
+  }
+}
+
 template <int W, int kUnroll>
 struct TileWords {
   UnitWords<W> u[kUnroll];
@@ -172,9 +215,11 @@ __device__ __forceinline__ uint32_t element_bits_slow(const uint8_t* __restrict_
 // smaller x also works), y = tensor of the batch.  Chunks of whole tiles take a
 // straight-line path with the next tile's loads issued ahead; the chunk that
 // holds the end of the tensor takes a guarded loop.
-template <typename T, int W, int kBlock, int kUnroll, int kChunk, bool kX8, bool kNT>
+// kStage: whole tiles read their plane bytes through an LDS image (kChunk must be 1).
+template <typename T, int W, int kBlock, int kUnroll, int kChunk, bool kX8, bool kNT, bool kStage = false>
 __global__ __launch_bounds__(kBlock) void decode_kernel(const BatchArgs batch) {
   constexpr uint32_t TU = kBlock * kUnroll;
+  static_assert(!kStage || kChunk == 1, "the image holds one tile");
   static_assert(TU % 2 == 0, "a tile must start on a byte of the 1-bit plane");
   static_assert(TU * (16 / sizeof(T)) >= 512, "tile counts must fit 32 bits for n <= 2^40");
   const TensorArgs& ta = batch.t[blockIdx.y];
@@ -191,12 +236,28 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(const BatchArgs batch) {
   const uint32_t tiles = full_tiles + (rem_units ? 1u : 0u);
   const uint32_t full_chunks = full_tiles / kChunk;
   const uint32_t chunks = (tiles + kChunk - 1) / kChunk;
+  constexpr uint32_t TG = TU * E / 8;  // groups of a tile
+  __shared__ __align__(16) uint8_t lds_image[kStage ? TG * W : 16];
 
   for (uint32_t chunk = blockIdx.x; chunk < chunks; chunk += gridDim.x) {
     const uint64_t u0 = (uint64_t)chunk * (kChunk * TU);  // first unit of the chunk (even)
     PlaneSrc<W> ps;
     make_plane_src<W, E>(src, G, u0, ps);
     const rsrc_t out = make_rsrc(reinterpret_cast<uint4*>(dst) + u0);
+    if constexpr (kStage) {
+      if (chunk < full_chunks) {
+        load_image<W, TG, kBlock>(src, G, u0 * E / 8, lds_image);
+        __syncthreads();
+#pragma unroll
+        for (int r = 0; r < kUnroll; ++r) {
+          UnitWords<W> uw;
+          image_unit<W, E, TG>(lds_image, r * kBlock + threadIdx.x, uw);
+          decode_unit<T, W, kX8, kNT>(uw, fc, tc, out, threadIdx.x, r * kBlock);
+        }
+        __syncthreads();  // the image is free for the next tile
+        continue;
+      }
+    }
     if (chunk < full_chunks) {
       TileWords<W, kUnroll> tw[2];
       load_tile<W, E, kBlock, kUnroll, false>(ps, 0, 0, tw[0]);

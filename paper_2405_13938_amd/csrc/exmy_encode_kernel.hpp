@@ -174,20 +174,6 @@ __device__ __forceinline__ void put_plane_word(const PlaneStage<W, kTileGroups>&
   if constexpr (S == 1) *p = (uint8_t)w[0];
 }
 
-// Memory address of the 16-byte piece at byte `off` of a tile's LDS image; g0 is the
-// tile's first group, G the tensor's group count.  A piece lies inside one plane
-// because kTileGroups is a multiple of 16.
-template <int W, int kTileGroups, int P = 0>
-__device__ __forceinline__ uint8_t* stage_piece_address(uint8_t* dst, uint64_t G, uint64_t g0, uint32_t off) {
-  static_assert(kTileGroups % 16 == 0, "plane images must be whole 16-byte pieces");
-  constexpr uint32_t S = Planes<W>::seg(P);
-  constexpr uint32_t LO = Planes<W>::lo(P);
-  if constexpr (P + 1 < Planes<W>::count) {
-    if (off >= kTileGroups * (LO + S)) return stage_piece_address<W, kTileGroups, P + 1>(dst, G, g0, off);
-  }
-  return dst + (G * LO + g0 * S + (off - kTileGroups * LO));
-}
-
 // Write the image of the whole tile that starts at group g0 to the planes of dst: the
 // copy alone (the caller places the barriers), and with a barrier on either side.
 // Every lane of the workgroup calls them.
@@ -200,7 +186,7 @@ __device__ __forceinline__ void copy_stage(const PlaneStage<W, kTileGroups>& st,
     if (kPieces % kBlock == 0 || c < kPieces) {
       const uint4 v = *reinterpret_cast<const uint4*>(st.lds + c * 16);
       const u32x4_t w = {v.x, v.y, v.z, v.w};
-      __builtin_nontemporal_store(w, reinterpret_cast<u32x4_t*>(stage_piece_address<W, kTileGroups>(dst, G, g0, c * 16)));
+      __builtin_nontemporal_store(w, reinterpret_cast<u32x4_t*>(tile_piece_address<W, kTileGroups>(dst, G, g0, c * 16)));
     }
   }
 }
