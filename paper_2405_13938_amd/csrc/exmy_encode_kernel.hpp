@@ -4,9 +4,10 @@
 //
 // Work decomposition: one lane owns whole groups of 8 consecutive elements, so
 // every plane word it produces is complete and byte aligned.  A bf16 group is
-// one 16-byte load, an fp32 group two adjacent ones; lane i of a block takes
-// group (tile base + i), so a wavefront reads one contiguous span per load
-// instruction.  A tile is kBlock * kUnroll groups; a block walks kChunk
+// one 16-byte load and lane i of a block takes group (tile base + i), so a
+// wavefront reads one contiguous span per load instruction; an fp32 group is two
+// 16-byte pieces, which whole tiles read as contiguous spans as well and then
+// exchange between neighbouring lanes (see row_slot).  A tile is kBlock * kUnroll groups; a block walks kChunk
 // consecutive tiles and issues the loads of the next tile before converting the
 // current one, so that bytes stay in flight while the ALUs work.  Blocks are
 // launched one per chunk, in address order: the hardware dispatcher then keeps
