@@ -555,6 +555,22 @@ __device__ __forceinline__ uint32_t keep_nonfinite_halves(uint32_t w, uint32_t e
   return bit_select(lo | hi, w, emulated);
 }
 
+// The same for a pair of bf16.
+__device__ __forceinline__ uint32_t keep_nonfinite_bf16(uint32_t w, uint32_t emulated) {
+  const uint32_t lo = (w & 0x00007F80u) == 0x00007F80u ? 0x0000FFFFu : 0u;
+  const uint32_t hi = (w & 0x7F800000u) == 0x7F800000u ? 0xFFFF0000u : 0u;
+  return bit_select(lo | hi, w, emulated);
+}
+
+// Two fp32 values rounded to nearest even into a bf16 pair: the conversion instruction of
+// gfx950 (an overflow gives Inf, as in the library conversion).
+typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+typedef float f32x2_t __attribute__((ext_vector_type(2)));
+__device__ __forceinline__ uint32_t round_pack_bf16(float lo, float hi) {
+  const f32x2_t v = {lo, hi};
+  return __builtin_bit_cast(uint32_t, __builtin_convertvector(v, bf16x2_t));
+}
+
 // ---------------------------------------------------------------- planes
 
 // Number of planes and their segment widths, widest first (7 -> 4, 2, 1).

@@ -108,13 +108,21 @@ template <typename T, int W, bool kX8, bool kNT, bool kScaled = false>
 __device__ __forceinline__ void decode_unit(const UnitWords<W>& uw, const FormatConsts& fc, const TensorConsts& tc,
                                             rsrc_t out, uint32_t lane_unit, uint32_t tile_unit, float scale = 1.0f) {
   constexpr int E = 16 / sizeof(T);
+  constexpr bool kRoundPairs = kScaled && sizeof(T) == 2 && !kIsF16<T>;  // bf16 products: rounded pair by pair
   uint32_t b[E];
 #pragma unroll
   for (int j = 0; j < E; ++j) {
     b[j] = element_bits<W, kX8>(uw, j, fc, tc);
-    if constexpr (kScaled) b[j] = rescaled_bits<T>(b[j], scale);
+    if constexpr (kScaled && !kRoundPairs) b[j] = rescaled_bits<T>(b[j], scale);
   }
-  if constexpr (sizeof(T) == 4) {
+  if constexpr (kRoundPairs) {
+    float p[E];
+#pragma unroll
+    for (int j = 0; j < E; ++j) p[j] = as_f32(b[j]) * scale;  // scale > 0: the product keeps the sign
+    const uint4 o = make_uint4(round_pack_bf16(p[0], p[1]), round_pack_bf16(p[2], p[3]), round_pack_bf16(p[4], p[5]),
+                               round_pack_bf16(p[6], p[7]));
+    store16<kNT>(out, lane_unit * 16, tile_unit * 16, o);
+  } else if constexpr (sizeof(T) == 4) {
     store16<kNT>(out, lane_unit * 16, tile_unit * 16, make_uint4(b[0], b[1], b[2], b[3]));
   } else {
     // every value is exact in bf16 (or has just been rounded to it): keep the upper halves

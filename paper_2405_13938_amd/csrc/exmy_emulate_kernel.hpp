@@ -130,6 +130,14 @@ __device__ __forceinline__ uint32_t emulate_scaled_bits(uint32_t u, float inv, f
   return (u & 0x7FFFFFFFu) >= 0x7F800000u ? u : rescaled_bits<T>(r, scale);
 }
 
+// The finite case alone, before the rounding to the container.
+template <bool kWide>
+__device__ __forceinline__ float emulate_scaled_product(uint32_t u, float inv, float scale, const FormatConsts& fc,
+                                                        const TensorConsts& tc127) {
+  const uint32_t a0 = as_u32(__builtin_fabsf(as_f32(u)) * inv);
+  return as_f32(emulate_magnitude<kWide>(a0, fc, tc127) | (u & 0x80000000u)) * scale;
+}
+
 template <typename T, bool kWide>
 __device__ __forceinline__ uint4 emulate_vector_scaled_as(uint4 v, float scale, float inv, const FormatConsts& fc,
                                                           const TensorConsts& tc127) {
@@ -138,11 +146,14 @@ __device__ __forceinline__ uint4 emulate_vector_scaled_as(uint4 v, float scale, 
   for (int k = 0; k < 4; ++k) {
     if constexpr (sizeof(T) == 4) {
       w[k] = emulate_scaled_bits<kWide, T>(w[k], inv, scale, fc, tc127);
-    } else {
+    } else if constexpr (kIsF16<T>) {
       const uint32_t lo = emulate_scaled_bits<kWide, T>(lo_elem_bits<T>(w[k]), inv, scale, fc, tc127);
       const uint32_t hi = emulate_scaled_bits<kWide, T>(hi_elem_bits<T>(w[k]), inv, scale, fc, tc127);
-      const uint32_t pair = pack_elems<T, false>(lo, hi);
-      w[k] = kIsF16<T> ? keep_nonfinite_halves(w[k], pair) : pair;
+      w[k] = keep_nonfinite_halves(w[k], pack_elems<T, false>(lo, hi));
+    } else {  // bf16: both products rounded by one conversion, Inf / NaN put back afterwards
+      const float lo = emulate_scaled_product<kWide>(lo_elem_bits<T>(w[k]), inv, scale, fc, tc127);
+      const float hi = emulate_scaled_product<kWide>(hi_elem_bits<T>(w[k]), inv, scale, fc, tc127);
+      w[k] = keep_nonfinite_bf16(w[k], round_pack_bf16(lo, hi));
     }
   }
   return make_uint4(w[0], w[1], w[2], w[3]);
