@@ -158,7 +158,8 @@ __device__ __forceinline__ void image_unit(const uint8_t* lds, uint32_t unit, Un
   if constexpr (P < Planes<W>::count) {
     constexpr int S = Planes<W>::seg(P);
     constexpr int kBits = E * S;  // of plane P per unit
-    const uint8_t* p = lds + kTileGroups * Planes<W>::lo(P) + unit * kBits / 8;
+    constexpr int LO = Planes<W>::lo(P);  // as a constant: the call itself would run its loop on the scalar unit
+    const uint8_t* p = lds + kTileGroups * LO + unit * kBits / 8;
     if constexpr (kBits == 128) {
       const uint4 v = *reinterpret_cast<const uint4*>(p);
       uw.w[P][0] = v.x; uw.w[P][1] = v.y; uw.w[P][2] = v.z; uw.w[P][3] = v.w;

@@ -167,7 +167,8 @@ template <int W, int P, int kTileGroups>
 __device__ __forceinline__ void put_plane_word(const PlaneStage<W, kTileGroups>& st, uint32_t lane_group,
                                                uint32_t tile_group, const uint32_t w[4]) {
   constexpr int S = Planes<W>::seg(P);
-  uint8_t* p = st.lds + kTileGroups * Planes<W>::lo(P) + (lane_group + tile_group) * S;
+  constexpr int LO = Planes<W>::lo(P);  // as a constant: the call itself would run its loop on the scalar unit
+  uint8_t* p = st.lds + kTileGroups * LO + (lane_group + tile_group) * S;
   if constexpr (S == 16) *reinterpret_cast<uint4*>(p) = make_uint4(w[0], w[1], w[2], w[3]);
   if constexpr (S == 8) *reinterpret_cast<uint2*>(p) = make_uint2(w[0], w[1]);
   if constexpr (S == 4) *reinterpret_cast<uint32_t*>(p) = w[0];
