@@ -17,7 +17,7 @@ template <>
 struct Shape<f16_t> : Shape<uint16_t> {};
 template <>
 struct Shape<float> {
-  static constexpr int kEncBlock = 128, kEncUnroll = 1, kDecBlock = 256, kDecUnroll = 2;
+  static constexpr int kEncBlock = 64, kEncUnroll = 1, kDecBlock = 256, kDecUnroll = 2;
 };
 
 template <typename T, int W>

@@ -5,8 +5,10 @@
 // is no Inf).  Finite elements are rounded as always and saturate to the largest
 // finite value, which the host passes as the format's saturation bound; a NaN takes
 // the all-ones magnitude code under its own sign; Inf takes the Inf code, or (NaN
-// only) saturates.  The kernels are the flat per-tensor ones with two compares and
-// two selects per element added.
+// only) saturates.  The kernels are the flat per-tensor ones; since Inf / NaN are rare,
+// a wavefront first asks whether any of its lanes holds one (a maximum over the lane's
+// elements and one ballot) and only then runs the two compares and two selects per
+// element that place or read the reserved codes.
 #pragma once
 
 #include "exmy_common.hpp"
@@ -22,13 +24,23 @@ __device__ __forceinline__ void encode_group(const uint32_t u[8], const FormatCo
                                              const SpecialConsts& sc, const Dst& pd, uint32_t lane_group,
                                              uint32_t tile_group) {
   uint32_t f[8];
+  uint32_t top = 0;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    const uint32_t a = u[j] & 0x7FFFFFFFu;
-    uint32_t m = magnitude_code_left<kWide>(u[j], fc, tc);  // Inf / NaN come out saturated: replaced below
-    m = a == 0x7F800000u ? sc.inf_left : m;
-    m = a > 0x7F800000u ? sc.nan_left : m;
-    f[j] = (W & 1) ? m : ((u[j] & 0x80000000u) | m);
+    top = max(top, u[j] & 0x7FFFFFFFu);
+    f[j] = magnitude_code_left<kWide>(u[j], fc, tc);  // Inf / NaN come out saturated: replaced below
+  }
+  if (__builtin_amdgcn_ballot_w64(top >= 0x7F800000u) != 0) {  // some lane of the wavefront holds an Inf or a NaN
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      const uint32_t a = u[j] & 0x7FFFFFFFu;
+      f[j] = a == 0x7F800000u ? sc.inf_left : f[j];
+      f[j] = a > 0x7F800000u ? sc.nan_left : f[j];
+    }
+  }
+  if constexpr ((W & 1) == 0) {  // even W: the sign rides at bit 31
+#pragma unroll
+    for (int j = 0; j < 8; ++j) f[j] |= u[j] & 0x80000000u;
   }
   enc::peel_planes<W, Planes<W>::count - 1>(f, u, pd, lane_group, tile_group);
 }
@@ -87,20 +99,37 @@ __global__ __launch_bounds__(kBlock) void encode_specials_kernel(const void* src
   }
 }
 
-// fp32 bit pattern of element j of the unit: a finite code as always, a reserved one as
+// fp32 bit patterns of the unit's E elements: a finite code as always, a reserved one as
 // Inf or the quiet NaN 0x7FC00000, under the code's sign.
-template <int W>
-__device__ __forceinline__ uint32_t element_bits(const dec::UnitWords<W>& uw, int j, const FormatConsts& fc,
-                                                 const TensorConsts& tc, const SpecialConsts& sc) {
-  const uint32_t g = dec::add_fields<W, 0>(uw, j, tc.dec_bias, fc);
-  uint32_t mag = finish_magnitude(min(g, sc.g_last), tc);  // the clamp keeps NaN patterns (X = 8) out of the float ops
-  mag = g > sc.g_last ? 0x7FC00000u : mag;
-  mag = g == sc.g_inf ? 0x7F800000u : mag;
+template <int W, int E>
+__device__ __forceinline__ void unit_bits(const dec::UnitWords<W>& uw, const FormatConsts& fc, const TensorConsts& tc,
+                                          const SpecialConsts& sc, uint32_t b[E]) {
+  uint32_t g[E];
+  uint32_t top = 0;
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    g[j] = dec::add_fields<W, 0>(uw, j, tc.dec_bias, fc);
+    top = max(top, g[j]);
+  }
+  if (__builtin_amdgcn_ballot_w64(top > sc.g_last) != 0) {  // some lane of the wavefront holds a reserved code
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      uint32_t mag = finish_magnitude(min(g[j], sc.g_last), tc);  // the clamp keeps NaN patterns (X = 8) out of the float ops
+      mag = g[j] > sc.g_last ? 0x7FC00000u : mag;
+      b[j] = g[j] == sc.g_inf ? 0x7F800000u : mag;
+    }
+  } else {
+#pragma unroll
+    for (int j = 0; j < E; ++j) b[j] = finish_magnitude(g[j], tc);
+  }
   constexpr int PT = Planes<W>::count - 1;
   constexpr int ST = Planes<W>::seg(PT);
-  const int bit = ST * j + ST - 1;  // the sign: top bit of the top plane's field
-  const uint32_t s = uw.w[PT][bit / 32] << (31 - bit % 32);
-  return (s & 0x80000000u) | mag;
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    const int bit = ST * j + ST - 1;  // the sign: top bit of the top plane's field
+    const uint32_t sgn = uw.w[PT][bit / 32] << (31 - bit % 32);
+    b[j] |= sgn & 0x80000000u;
+  }
 }
 
 template <typename T, int W>
@@ -109,8 +138,7 @@ __device__ __forceinline__ void decode_unit(const dec::UnitWords<W>& uw, const F
                                             uint32_t tile_unit) {
   constexpr int E = 16 / sizeof(T);
   uint32_t b[E];
-#pragma unroll
-  for (int j = 0; j < E; ++j) b[j] = element_bits<W>(uw, j, fc, tc, sc);
+  unit_bits<W, E>(uw, fc, tc, sc, b);
   if constexpr (sizeof(T) == 4) {
     store16<true>(out, lane_unit * 16, tile_unit * 16, make_uint4(b[0], b[1], b[2], b[3]));
   } else {
@@ -165,10 +193,12 @@ __global__ __launch_bounds__(kBlock) void decode_specials_kernel(const void* src
       dec::make_plane_src<W, 8>(src, G, i / 8, ps);
       dec::UnitWords<W> uw;
       dec::load_unit<W, 8>(ps, 0, 0, uw);
+      uint32_t all[8];  // the whole group that holds the element
+      unit_bits<W, 8>(uw, fc, tc, sc, all);
       uint32_t b = 0;
 #pragma unroll
       for (int j = 0; j < 8; ++j)
-        if ((int)(i % 8) == j) b = element_bits<W>(uw, j, fc, tc, sc);
+        if ((int)(i % 8) == j) b = all[j];
       if constexpr (sizeof(T) == 4)
         reinterpret_cast<uint32_t*>(dst)[i] = b;
       else
