@@ -111,9 +111,16 @@ __global__ __launch_bounds__(kBlock) void emulate_kernel(T* __restrict__ data, u
 // Per-block metadata: flat tiles with a per-lane metadata lookup, as in the
 // encoder.  Work is counted in 16-byte vectors of kPer elements.
 
+// try_uniform: look for a metadatum common to the wavefront first (not worth the ballot for the shortest blocks).
 template <typename T>
 __device__ __forceinline__ uint4 emulate_vector_meta(uint4 v, uint32_t me, bool wide_format, const FormatConsts& fc,
-                                                     const BlockConsts& bc) {
+                                                     const BlockConsts& bc, bool try_uniform) {
+  uint32_t first;
+  if (try_uniform && wave_uniform(me, first)) {
+    const TensorConsts tc = derive_tc(first, bc);
+    if (wide_format || first > bc.wide_above) return emulate_vector<T, true>(v, fc, tc);
+    return emulate_vector<T, false>(v, fc, tc);
+  }
   const TensorConsts tc = derive_tc(me, bc);
   if (__builtin_amdgcn_ballot_w64(wide_format || me > bc.wide_above) != 0) return emulate_vector<T, true>(v, fc, tc);
   return emulate_vector<T, false>(v, fc, tc);
@@ -183,6 +190,7 @@ __global__ __launch_bounds__(kBlock) void emulate_blocks_kernel(const BlockArgs 
   const uint64_t V = n / kPer;
   const uint32_t lane_off = threadIdx.x * 16;
   const uint32_t tiles = (uint32_t)((V + TV - 1) / TV);
+  const bool try_uniform = bi.size >= 4;  // at most 16 blocks per wavefront
 
   for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
     const uint64_t v0 = (uint64_t)tile * TV;
@@ -209,7 +217,7 @@ __global__ __launch_bounds__(kBlock) void emulate_blocks_kernel(const BlockArgs 
           store16<kNT>(buf, lane_off, r * kBlock * 16,
                        emulate_vector_scaled<T>(v[r], me[r], wide_format, fc, args.tc127));
         else
-          store16<kNT>(buf, lane_off, r * kBlock * 16, emulate_vector_meta<T>(v[r], me[r], wide_format, fc, bc));
+          store16<kNT>(buf, lane_off, r * kBlock * 16, emulate_vector_meta<T>(v[r], me[r], wide_format, fc, bc, try_uniform));
       }
     }
   }

@@ -412,10 +412,20 @@ __global__ __launch_bounds__(kBlock) void encode_kernel(const BatchArgs batch) {
 // One group with the rounding variant its block's metadatum needs.  The branch is
 // taken for a whole wavefront at once (any lane that needs the fp64 path sends
 // all of them there; both paths give the same result where both apply).
+// try_uniform: look first for a metadatum common to the wavefront (see wave_uniform).
 template <int W, class Dst>
 __device__ __forceinline__ void encode_group_meta(const uint32_t u[8], uint32_t me, const FormatConsts& fc,
                                                   const BlockConsts& bc, const Dst& pd, uint32_t lane_group,
-                                                  uint32_t tile_group) {
+                                                  uint32_t tile_group, bool try_uniform = true) {
+  uint32_t first;
+  if (try_uniform && wave_uniform(me, first)) {
+    const TensorConsts tc = derive_tc(first, bc);
+    if (first > bc.wide_above)
+      encode_group<W, true>(u, fc, tc, pd, lane_group, tile_group);
+    else
+      encode_group<W, false>(u, fc, tc, pd, lane_group, tile_group);
+    return;
+  }
   const TensorConsts tc = derive_tc(me, bc);
   if (__builtin_amdgcn_ballot_w64(me > bc.wide_above) != 0)
     encode_group<W, true>(u, fc, tc, pd, lane_group, tile_group);
@@ -454,6 +464,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
   const uint32_t tiles = full_tiles + (rem_groups ? 1u : 0u);
   __shared__ __align__(16) uint8_t lds_stage[TG * W];
   const PlaneStage<W, TG> stage{lds_stage};
+  const bool try_uniform = bi.size >= 4;  // at most 16 blocks per wavefront
 
   for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
     const uint64_t g0 = (uint64_t)tile * TG;
@@ -479,7 +490,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
         if constexpr (kScaled)  // more arithmetic per element: the stage measured slower here
           encode_group_scaled<W>(u, me[r], fc, args.tc127, pd, slot, r * kBlock);
         else
-          encode_group_meta<W>(u, me[r], fc, bc, stage, slot, r * kBlock);
+          encode_group_meta<W>(u, me[r], fc, bc, stage, slot, r * kBlock, try_uniform);
       }
       if constexpr (!kScaled) flush_stage<W, TG, kBlock>(stage, dst, G, g0);
     } else {
@@ -496,7 +507,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
           if constexpr (kScaled)
             encode_group_scaled<W>(u, me[r], fc, args.tc127, pd, threadIdx.x, r * kBlock);
           else
-            encode_group_meta<W>(u, me[r], fc, bc, pd, threadIdx.x, r * kBlock);
+            encode_group_meta<W>(u, me[r], fc, bc, pd, threadIdx.x, r * kBlock, try_uniform);
         }
       }
     }
@@ -522,7 +533,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
     if constexpr (kScaled)
       encode_group_scaled<W>(u, load_scale_bits(args, args.n_blocks - 1), fc, args.tc127, pd, 0, 0);
     else
-      encode_group_meta<W>(u, meta[args.n_blocks - 1], fc, bc, pd, 0, 0);
+      encode_group_meta<W>(u, meta[args.n_blocks - 1], fc, bc, pd, 0, 0, false);
   }
 }
 
@@ -606,7 +617,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_small_kernel(const 
           else
             args.meta[(g0 + idx) >> lg] = (uint8_t)me;
         }
-        encode_group_meta<W>(u, me, fc, bc, stage, threadIdx.x, r * kBlock);
+        encode_group_meta<W>(u, me, fc, bc, stage, threadIdx.x, r * kBlock, lg >= 2);
       }
       __syncthreads();
       copy_stage<W, TG, kBlock>(stage, dst, G, g0);
@@ -635,7 +646,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_small_kernel(const 
       if (g < G) {
         const uint32_t me = meta_from_key(key, bc);
         if ((threadIdx.x & ((1u << lg) - 1u)) == 0) args.meta[g >> lg] = (uint8_t)me;
-        encode_group_meta<W>(u, me, fc, bc, pd, threadIdx.x, r * kBlock);
+        encode_group_meta<W>(u, me, fc, bc, pd, threadIdx.x, r * kBlock, lg >= 2);
       }
     }
   }
@@ -702,7 +713,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_team_kernel(const B
         if (r * kBlock + threadIdx.x < count) {
           uint32_t u[8];
           group_bits<T>(regs.v[r], u);
-          encode_group_meta<W>(u, me, fc, bc, stage, threadIdx.x, r * kBlock);
+          encode_group_meta<W>(u, me, fc, bc, stage, threadIdx.x, r * kBlock, false);  // me is a scalar already
         }
       }
       flush_stage_groups<W, TG, kBlock>(stage, pd, 0, count);
@@ -714,9 +725,9 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_team_kernel(const B
       if (idx < whole) {
         uint32_t u[8];
         group_bits<T>(regs.v[r], u);
-        encode_group_meta<W>(u, me, fc, bc, pd, threadIdx.x, r * kBlock);
+        encode_group_meta<W>(u, me, fc, bc, pd, threadIdx.x, r * kBlock, false);  // me is a scalar already
       } else if (idx == whole && whole < count) {
-        encode_group_meta<W>(ragged, me, fc, bc, pd, threadIdx.x, r * kBlock);
+        encode_group_meta<W>(ragged, me, fc, bc, pd, threadIdx.x, r * kBlock, false);  // me is a scalar already
       }
     }
   }
@@ -796,9 +807,9 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_twopass_kernel(cons
           uint32_t u[8];
           group_bits<T>(regs.v[r], u);
           if (staged)
-            encode_group_meta<W>(u, me, fc, bc, stage, threadIdx.x, r * kBlock);
+            encode_group_meta<W>(u, me, fc, bc, stage, threadIdx.x, r * kBlock, false);  // me is a scalar already
           else
-            encode_group_meta<W>(u, me, fc, bc, pd, threadIdx.x, t * TG + r * kBlock);
+            encode_group_meta<W>(u, me, fc, bc, pd, threadIdx.x, t * TG + r * kBlock, false);  // me is a scalar already
         }
       }
       if (staged) flush_stage_groups<W, TG, kBlock>(stage, pd, t * TG, here);
@@ -806,7 +817,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_twopass_kernel(cons
     if (has_ragged) {
       PlaneDst<W> pr;
       make_plane_dst<W>(dst, G, g0 + whole, pr);
-      encode_group_meta<W>(ragged, me, fc, bc, pr, 0, 0);
+      encode_group_meta<W>(ragged, me, fc, bc, pr, 0, 0, false);  // me is a scalar already
     }
   }
 }

@@ -300,7 +300,7 @@ __global__ __launch_bounds__(kBlock) void emulate_tiles_kernel(const TileArgs ar
         if constexpr (kColumns)
           store16<kNT>(buf, lane_off, r * kBlock * 16, emulate_vector_each<T>(v[r], me[r], wide_format, fc, bc));
         else
-          store16<kNT>(buf, lane_off, r * kBlock * 16, emu::emulate_vector_meta<T>(v[r], me[r].w[0], wide_format, fc, bc));
+          store16<kNT>(buf, lane_off, r * kBlock * 16, emu::emulate_vector_meta<T>(v[r], me[r].w[0], wide_format, fc, bc, true));
       }
     }
   }
