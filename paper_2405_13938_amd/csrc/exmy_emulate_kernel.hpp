@@ -24,9 +24,10 @@ __device__ __forceinline__ uint32_t emulate_magnitude(uint32_t a0, const FormatC
   const uint32_t a = min(a0, tc.sat_bits);
   const uint32_t te = max(a, tc.emin_bits) & 0x7F800000u;
   if constexpr (!kWide) {
-    const float m = as_f32(te) * fc.magic_scale;
-    const float s = as_f32(a) + m;
-    return as_u32(s - m);
+    // (a + m) - m with m = te * magic_scale, a power of two: the product is exact, so two fused operations give
+    // the same two roundings
+    const float s = __builtin_fmaf(as_f32(te), fc.magic_scale, as_f32(a));
+    return as_u32(__builtin_fmaf(-as_f32(te), fc.magic_scale, s));
   } else {
     const uint32_t hi = ((te >> 23) + (uint32_t)fc.wide_exp) << 20;
     const double m = __hiloint2double((int)hi, 0);
@@ -46,6 +47,25 @@ __device__ __forceinline__ uint32_t emulate_bits(uint32_t u, const FormatConsts&
 template <typename T, bool kWide>
 __device__ __forceinline__ uint4 emulate_vector(uint4 v, const FormatConsts& fc, const TensorConsts& tc) {
   uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  if constexpr (sizeof(T) == 2 && !kIsF16<T>) {
+    // bf16: the magnitudes of a pair are rounded, packed, and put under the pair's own sign bits by one bit
+    // select.  Inf / NaN (which the rounding saturates) are rare: a maximum over the vector's magnitudes and one
+    // ballot tell whether any lane of the wavefront holds one, and only then are the original halves put back.
+    uint32_t out[4];
+    uint32_t top = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint32_t lo = emulate_magnitude<kWide>((w[k] << 16) & 0x7FFFFFFFu, fc, tc);
+      const uint32_t hi = emulate_magnitude<kWide>(w[k] & 0x7FFF0000u, fc, tc);
+      out[k] = bit_select(0x7FFF7FFFu, pack_elems<T>(lo, hi), w[k]);
+      top = max_pair_keys(top, w[k] & 0x7FFF7FFFu);  // non-negative halves: the signed maximum orders them
+    }
+    if (__builtin_amdgcn_ballot_w64(((top + 0x00800080u) & 0x80008000u) != 0) != 0) {  // a half with exponent 255
+#pragma unroll
+      for (int k = 0; k < 4; ++k) out[k] = keep_nonfinite_bf16(w[k], out[k]);
+    }
+    return make_uint4(out[0], out[1], out[2], out[3]);
+  }
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     if constexpr (sizeof(T) == 4) {
