@@ -239,6 +239,22 @@ template <typename T, bool kWide>
 __device__ __forceinline__ uint4 emulate_vector_each_as(uint4 v, const UnitMeta<16 / sizeof(T)>& me,
                                                         const FormatConsts& fc, const BlockConsts& bc) {
   uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  if constexpr (sizeof(T) == 2 && !kIsF16<T>) {  // bf16: signs per pair, Inf / NaN only where a wavefront holds one (see emulate_vector)
+    uint32_t out[4];
+    uint32_t top = 0;
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const uint32_t lo = emu::emulate_magnitude<kWide>((w[k] << 16) & 0x7FFFFFFFu, fc, derive_tc(meta_byte(me, 2 * k), bc));
+      const uint32_t hi = emu::emulate_magnitude<kWide>(w[k] & 0x7FFF0000u, fc, derive_tc(meta_byte(me, 2 * k + 1), bc));
+      out[k] = bit_select(0x7FFF7FFFu, pack_elems<T>(lo, hi), w[k]);
+      top = max_pair_keys(top, w[k] & 0x7FFF7FFFu);
+    }
+    if (__builtin_amdgcn_ballot_w64(((top + 0x00800080u) & 0x80008000u) != 0) != 0) {
+#pragma unroll
+      for (int k = 0; k < 4; ++k) out[k] = keep_nonfinite_bf16(w[k], out[k]);
+    }
+    return make_uint4(out[0], out[1], out[2], out[3]);
+  }
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     if constexpr (sizeof(T) == 4) {
