@@ -303,6 +303,19 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(const BatchArgs batch) {
 // Per-block metadata: flat tiles with a per-lane metadata lookup, as in the
 // encoder.  A unit is one lane's 16 bytes of output (E elements).
 
+// One unit under its block's metadatum.  try_uniform: look first for a metadatum common to the
+// wavefront, whose constants are then derived once on the scalar unit (see wave_uniform).
+template <typename T, int W, bool kNT>
+__device__ __forceinline__ void decode_unit_meta(const UnitWords<W>& uw, uint32_t me, const FormatConsts& fc,
+                                                 const BlockConsts& bc, rsrc_t out, uint32_t lane_unit,
+                                                 uint32_t tile_unit, bool try_uniform) {
+  uint32_t first;
+  if (try_uniform && wave_uniform(me, first))
+    decode_unit<T, W, false, kNT>(uw, fc, derive_tc(first, bc), out, lane_unit, tile_unit);
+  else
+    decode_unit<T, W, false, kNT>(uw, fc, derive_tc(me, bc), out, lane_unit, tile_unit);
+}
+
 // kScaled: per-block fp32 scales and the max_exp = 127 format instead of per-block
 // metadata bytes.
 template <typename T, int W, int kBlock, int kUnroll, bool kNT, bool kScaled>
@@ -321,6 +334,9 @@ __global__ __launch_bounds__(kBlock) void decode_blocks_kernel(const BlockArgs a
   const uint32_t full_tiles = (uint32_t)(Ufull / TU);
   const uint32_t rem_units = (uint32_t)(Ufull - (uint64_t)full_tiles * TU);
   const uint32_t tiles = full_tiles + (rem_units ? 1u : 0u);
+  // at most 16 blocks per wavefront; 16-bit elements only: +2-3 % there, while the fp32 kernel (4 elements per lane,
+  // less arithmetic per byte) lost 6 % to the second copy of its code
+  const bool try_uniform = sizeof(T) == 2 && bi.size >= 4;
 
   for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
     const uint64_t u0 = (uint64_t)tile * TU;  // even
@@ -343,7 +359,7 @@ __global__ __launch_bounds__(kBlock) void decode_blocks_kernel(const BlockArgs a
         if constexpr (kScaled)
           decode_unit<T, W, false, kNT, true>(tw.u[r], fc, args.tc127, out, threadIdx.x, r * kBlock, as_f32(me[r]));
         else
-          decode_unit<T, W, false, kNT>(tw.u[r], fc, derive_tc(me[r], bc), out, threadIdx.x, r * kBlock);
+          decode_unit_meta<T, W, kNT>(tw.u[r], me[r], fc, bc, out, threadIdx.x, r * kBlock, try_uniform);
       }
     } else {
       load_tile<W, E, kBlock, kUnroll, true>(ps, 0, rem_units, tw);
@@ -358,7 +374,7 @@ __global__ __launch_bounds__(kBlock) void decode_blocks_kernel(const BlockArgs a
           if constexpr (kScaled)
             decode_unit<T, W, false, kNT, true>(tw.u[r], fc, args.tc127, out, threadIdx.x, r * kBlock, as_f32(me[r]));
           else
-            decode_unit<T, W, false, kNT>(tw.u[r], fc, derive_tc(me[r], bc), out, threadIdx.x, r * kBlock);
+            decode_unit_meta<T, W, kNT>(tw.u[r], me[r], fc, bc, out, threadIdx.x, r * kBlock, try_uniform);
         }
       }
     }
