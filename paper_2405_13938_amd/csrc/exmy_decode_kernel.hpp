@@ -102,11 +102,11 @@ __device__ __forceinline__ uint32_t element_bits(const UnitWords<W>& uw, int j, 
   return (s & 0x80000000u) | mag;
 }
 
-// Values of one unit, stored to 16-byte vector lane_unit + tile_unit of `out`.
+// The 16 bytes of one unit's values.
 // kScaled (float scaling): every value is multiplied by `scale` on the way out.
-template <typename T, int W, bool kX8, bool kNT, bool kScaled = false>
-__device__ __forceinline__ void decode_unit(const UnitWords<W>& uw, const FormatConsts& fc, const TensorConsts& tc,
-                                            rsrc_t out, uint32_t lane_unit, uint32_t tile_unit, float scale = 1.0f) {
+template <typename T, int W, bool kX8, bool kScaled = false>
+__device__ __forceinline__ uint4 unit_values(const UnitWords<W>& uw, const FormatConsts& fc, const TensorConsts& tc,
+                                             float scale = 1.0f) {
   constexpr int E = 16 / sizeof(T);
   constexpr bool kRoundPairs = kScaled && sizeof(T) == 2 && !kIsF16<T>;  // bf16 products: rounded pair by pair
   uint32_t b[E];
@@ -119,11 +119,10 @@ __device__ __forceinline__ void decode_unit(const UnitWords<W>& uw, const Format
     float p[E];
 #pragma unroll
     for (int j = 0; j < E; ++j) p[j] = as_f32(b[j]) * scale;  // scale > 0: the product keeps the sign
-    const uint4 o = make_uint4(round_pack_bf16(p[0], p[1]), round_pack_bf16(p[2], p[3]), round_pack_bf16(p[4], p[5]),
-                               round_pack_bf16(p[6], p[7]));
-    store16<kNT>(out, lane_unit * 16, tile_unit * 16, o);
+    return make_uint4(round_pack_bf16(p[0], p[1]), round_pack_bf16(p[2], p[3]), round_pack_bf16(p[4], p[5]),
+                      round_pack_bf16(p[6], p[7]));
   } else if constexpr (sizeof(T) == 4) {
-    store16<kNT>(out, lane_unit * 16, tile_unit * 16, make_uint4(b[0], b[1], b[2], b[3]));
+    return make_uint4(b[0], b[1], b[2], b[3]);
   } else {
     // every value is exact in bf16 (or has just been rounded to it): keep the upper halves
     uint4 o;
@@ -131,8 +130,15 @@ __device__ __forceinline__ void decode_unit(const UnitWords<W>& uw, const Format
     o.y = pack_elems<T, !kScaled>(b[2], b[3]);
     o.z = pack_elems<T, !kScaled>(b[4], b[5]);
     o.w = pack_elems<T, !kScaled>(b[6], b[7]);
-    store16<kNT>(out, lane_unit * 16, tile_unit * 16, o);
+    return o;
   }
+}
+
+// Values of one unit, stored to 16-byte vector lane_unit + tile_unit of `out`.
+template <typename T, int W, bool kX8, bool kNT, bool kScaled = false>
+__device__ __forceinline__ void decode_unit(const UnitWords<W>& uw, const FormatConsts& fc, const TensorConsts& tc,
+                                            rsrc_t out, uint32_t lane_unit, uint32_t tile_unit, float scale = 1.0f) {
+  store16<kNT>(out, lane_unit * 16, tile_unit * 16, unit_values<T, W, kX8, kScaled>(uw, fc, tc, scale));
 }
 
 // A lane of a narrow format reads 1-3 bytes per plane straight from memory.  Whole tiles
@@ -198,6 +204,16 @@ __device__ __forceinline__ void load_tile(const PlaneSrc<W>& ps, uint32_t tile_u
 template <typename T, int W, int kBlock, int kUnroll, bool kX8, bool kNT, bool kGuard>
 __device__ __forceinline__ void decode_tile(const TileWords<W, kUnroll>& tw, rsrc_t out, uint32_t tile_unit,
                                             uint32_t rem, const FormatConsts& fc, const TensorConsts& tc) {
+  if constexpr (!kGuard) {
+    // a whole tile: all values first, then its stores back to back (+1 % over storing each unit as it is ready)
+    uint4 o[kUnroll];
+#pragma unroll
+    for (int r = 0; r < kUnroll; ++r) o[r] = unit_values<T, W, kX8>(tw.u[r], fc, tc);
+    asm volatile("" ::: "memory");  // keeps the compiler from moving a store up between the conversions
+#pragma unroll
+    for (int r = 0; r < kUnroll; ++r) store16<kNT>(out, threadIdx.x * 16, (tile_unit + r * kBlock) * 16, o[r]);
+    return;
+  }
 #pragma unroll
   for (int r = 0; r < kUnroll; ++r) {
     if (!kGuard || r * kBlock + threadIdx.x < rem)
