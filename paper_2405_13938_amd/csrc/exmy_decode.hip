@@ -46,19 +46,23 @@ hipError_t launch_decode(bool x8, const BatchArgs& args, uint64_t n_max, hipStre
     return hipGetLastError();
   }
   using S = Shape<T>;
-  const uint64_t tile_units = (uint64_t)S::kBlock * S::kUnroll;  // a unit = one lane's 16 bytes of output
+  // Up to 7 bits a lane reads so little of each plane that a workgroup of the usual size touches only 128-512
+  // bytes of the narrow ones: 512 lanes there (+4-7 % for bf16, +3-5 % for fp32 up to 6 bits; from 8 bits up the
+  // larger workgroup measured 1-5 % slower).
+  constexpr int kBlock = W <= 7 ? 512 : S::kBlock;
+  const uint64_t tile_units = (uint64_t)kBlock * S::kUnroll;  // a unit = one lane's 16 bytes of output
   const uint64_t units = n_max / (16 / sizeof(T));
   const uint64_t tiles = (units + tile_units - 1) / tile_units;
-  const dim3 grid(grid_for_chunks(tiles, S::kChunk, S::kBlock), args.count);
+  const dim3 grid(grid_for_chunks(tiles, S::kChunk, kBlock), args.count);
   if constexpr (W >= 9) {  // X = 8 needs at least 9 bits
     if (x8) {
-      hipLaunchKernelGGL((dec::decode_kernel<T, W, S::kBlock, S::kUnroll, S::kChunk, true, S::kNT>), grid,
-                         dim3(S::kBlock), 0, stream, args);
+      hipLaunchKernelGGL((dec::decode_kernel<T, W, kBlock, S::kUnroll, S::kChunk, true, S::kNT>), grid, dim3(kBlock), 0,
+                         stream, args);
       return hipGetLastError();
     }
   }
-  hipLaunchKernelGGL((dec::decode_kernel<T, W, S::kBlock, S::kUnroll, S::kChunk, false, S::kNT>), grid,
-                     dim3(S::kBlock), 0, stream, args);
+  hipLaunchKernelGGL((dec::decode_kernel<T, W, kBlock, S::kUnroll, S::kChunk, false, S::kNT>), grid, dim3(kBlock), 0,
+                     stream, args);
   return hipGetLastError();
 }
 
