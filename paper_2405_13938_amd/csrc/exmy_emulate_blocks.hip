@@ -25,7 +25,7 @@ hipError_t launch_emulate(BlockArgs args, bool wide_format, hipStream_t stream) 
 // power of two); blocks of up to kWaveRowVecs vectors get a wavefront each, longer
 // ones a workgroup each.
 constexpr int kMaxBlock = 256;
-constexpr int kMaxUnroll = 2;
+constexpr int kMaxUnroll = 4;
 constexpr uint64_t kWaveRowVecs = 1024;
 
 template <typename T, bool kScale>
