@@ -11,7 +11,7 @@ template <typename T>
 struct Small;
 template <>
 struct Small<uint16_t> {
-  static constexpr int kBlock = 64, kUnroll = 2;
+  static constexpr int kBlock = 64, kUnroll = 4;
 };
 template <>
 struct Small<f16_t> : Small<uint16_t> {};
