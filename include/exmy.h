@@ -306,15 +306,16 @@ exmy_status_t exmy_emulate_tiles(void* data_inout, exmy_dtype_t dt, uint64_t row
  * aligned, or EXMY_BF16, 2-byte aligned; EXMY_F16 gives EXMY_ERR_FORMAT)
  * instead of a metadata byte; the codes are those of the format with
  * max_exp = 127, whose top binade is [1, 2).  The paper prints no formulas;
- * this library computes, in fp32:
- *   scale   s = max(m / vmax, FLT_MIN), m = largest finite |x| of the block
- *               (0 if none), vmax = largest value of the format at max_exp = 127;
- *               a bf16 scale is the smallest bf16 value >= s (so the block
- *               maximum still lands on the largest code), at most the largest
- *               finite bf16;
- *   encode  the code of |x| * (1 / s) in that format, under the sign of x
+ * this library computes:
+ *   scale   s = max(m / vmax, FLT_MIN) rounded once to fp32, m = largest finite
+ *               |x| of the block (0 if none), vmax = largest value of the format
+ *               at max_exp = 127; a bf16 scale is the smallest bf16 value >= s
+ *               (so the block maximum still lands on the largest code), at most
+ *               the largest finite bf16;
+ *   encode  the code, in that format, of the real quotient |x| / s (nearest
+ *           grid point, ties to even, saturating), under the sign of x
  *           (Inf / NaN: sign + largest magnitude code, as in exmy_encode);
- *   decode  value * s, one rounding; rounded to nearest even when dt is bf16;
+ *   decode  the real product value * s rounded once, to nearest even, to dt;
  *   emulate decode(encode(x)) with Inf / NaN left bit-identical.
  * A bf16 scale enters this arithmetic widened exactly to fp32.  Scales given to
  * encode / decode / emulate need not come from exmy_block_scale but must be

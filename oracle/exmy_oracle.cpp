@@ -63,19 +63,26 @@
 //     [-2^Y, 2^Y - 1] and the value is k quanta; k = round-half-even(x / quantum),
 //     clamped; Inf / NaN go to the end of the range on the side of their sign bit;
 //     -0 and negative values that round to 0 give k = 0, which decodes to +0;
-//   - "float scaling with maximum exponent 127" (Section 2 "Metadata", Section
+//   - float scaling at maximum exponent 127 (Section 2 "Metadata", Section
 //     2.1): the paper gives no formulas.  Reading: the block's scale is
-//     s = max|x| / vmax in fp32 (vmax = largest value of the format with
-//     max_exp = 127; s is raised to FLT_MIN if smaller), the code is that of
-//     fl32(|x| * fl32(1 / s)) in the max_exp = 127 format, and the decoded value is
-//     fl32(value * s), rounded to nearest even when the container is bf16.  The
-//     scaled value decides the code, so it is computed in the kernels' precision
-//     (fp32) here too.  Parity unpinned by the paper beyond the property that the
-//     block maximum is reproduced almost exactly.  The "bfloat16 scaling factor"
-//     of the same passage: the smallest bf16 value not below that fp32 scale
-//     (never below, so that the block maximum divided by it still lies within
-//     the format's range), at most the largest finite bf16; it enters encode and
-//     decode widened exactly to fp32.
+//     s = max|x| / vmax rounded once to fp32 (vmax = largest value of the format
+//     with max_exp = 127; s is raised to FLT_MIN if smaller); the code of x is
+//     that of the real quotient |x| / s in the max_exp = 127 format (nearest grid
+//     point, ties to even, saturating), under the sign of x; the decoded value is
+//     the real product value * s rounded once, to nearest even, into the
+//     container (fp32, bf16 or fp16).  Both are evaluated in double: the
+//     product of a value of at most 24 bits and a 24-bit scale is exact there,
+//     and the quotient of two fp32 numbers is either exactly a rounding
+//     boundary of the grid (boundaries have at most Y + 2 <= 25 significant
+//     bits, hence are doubles, and the double division then returns it exactly)
+//     or further from every boundary than 2^-50 of its size (a 24-bit number
+//     minus a 49-bit product), which the 2^-53 error of the double division
+//     cannot bridge.  Parity unpinned by the paper beyond the
+//     property that the block maximum is reproduced almost exactly.  The bf16
+//     form of the scaling factor named in the same passage: the smallest bf16
+//     value not below that fp32 scale (never below, so that the block maximum
+//     divided by it still lies within the format's range), at most the largest
+//     finite bf16; it enters encode and decode widened exactly to fp32.
 //
 // Pinned by tests/test_oracle_pins.py, tests/test_oracle_pack.py and
 // tests/test_oracle_blocks.py against the
@@ -900,24 +907,25 @@ static int scaled_format(int dt, int X, int Y, bool packed, Format* f) {
   return check_format(dt, X, Y, 127, packed, f);
 }
 
-// fp32 -> bf16, round to nearest, ties to even (the library conversion), as fp32 bits.
-static uint32_t round_to_bf16_bits(float r) {
-  if (std::isnan(r) || std::isinf(r) || r == 0.0f) return float_to_bits(r) & 0xFFFF0000u;
+// A real number r (held exactly in a double) rounded once to nearest, ties to even, onto the bf16 grid
+// (8 significant bits, denormals below 2^-126, overflow to Inf), as fp32 bits.
+static uint32_t round_to_bf16_bits(double r) {
+  if (std::isnan(r) || std::isinf(r) || r == 0.0) return float_to_bits((float)r) & 0xFFFF0000u;
   int e;
-  (void)std::frexp((double)r, &e);                         // |r| in [2^(e-1), 2^e)
+  (void)std::frexp(r, &e);                                 // |r| in [2^(e-1), 2^e)
   const int q = std::max(e - 1, -126) - 7;                 // exponent of the bf16 quantum in this binade
-  const double k = std::nearbyint(std::ldexp((double)r, -q));
+  const double k = std::nearbyint(std::ldexp(r, -q));
   return float_to_bits((float)std::ldexp(k, q));           // exact in fp32; 2^128 becomes Inf
 }
 
-// fp32 -> fp16, round to nearest, ties to even (the library conversion), as the fp32 bits of the half's value.
-static uint32_t round_to_half_float_bits(float r) {
-  if (std::isnan(r) || std::isinf(r) || r == 0.0f) return float_to_bits(r);
+// The same onto the fp16 grid (11 significant bits, denormals below 2^-14), as the fp32 bits of the half's value.
+static uint32_t round_to_half_float_bits(double r) {
+  if (std::isnan(r) || std::isinf(r) || r == 0.0) return float_to_bits((float)r);
   int e;
-  (void)std::frexp((double)r, &e);                         // |r| in [2^(e-1), 2^e)
+  (void)std::frexp(r, &e);                                 // |r| in [2^(e-1), 2^e)
   const int q = std::max(e - 1, -14) - 10;                 // exponent of the fp16 quantum in this binade
-  const double v = std::ldexp(std::nearbyint(std::ldexp((double)r, -q)), q);
-  if (std::fabs(v) >= 65536.0) return float_to_bits(std::copysign(INFINITY, r));  // past the largest half (65504)
+  const double v = std::ldexp(std::nearbyint(std::ldexp(r, -q)), q);
+  if (std::fabs(v) >= 65536.0) return float_to_bits(std::copysign(INFINITY, (float)r));  // past the largest half (65504)
   return float_to_bits((float)v);
 }
 
@@ -977,15 +985,15 @@ static int scaled_op(int what, const void* src, void* dst, int dt, uint64_t n, u
   if (what == 1) unpack_groups((const uint8_t*)src, n, W, codes.data(), 0, 0, (n + 7) / 8);
   parallel_ranges(nb, threads, [&](uint64_t b0, uint64_t b1) {
     for (uint64_t b = b0; b < b1; ++b) {
-      const float s = scale[b];
-      const float inv = 1.0f / s;
+      const double s = (double)scale[b];
       for (uint64_t i = b * block; i < std::min(n, (b + 1) * block); ++i) {
         uint32_t code = 0;
         uint32_t bits = 0;
         if (what != 1) {
           bits = load_bits(src, dt, i);
-          const float a = std::fabs(bits_to_float(bits)) * inv;  // fp32 product, one rounding
-          const int64_t c = (std::isnan(a) || std::isinf(a)) ? f.cmax : magnitude_code(f, (double)a);
+          const float x = bits_to_float(bits);
+          // the real quotient |x| / s, to 2^-53: see the header for why that decides the code exactly
+          const int64_t c = (std::isnan(x) || std::isinf(x)) ? f.cmax : magnitude_code(f, std::fabs((double)x) / s);
           code = (uint32_t)(((bits >> 31) << (X + Y)) | (uint32_t)c);
         } else {
           code = codes[i];
@@ -996,9 +1004,9 @@ static int scaled_op(int what, const void* src, void* dst, int dt, uint64_t n, u
         }
         const float x = bits_to_float(bits);
         if (what == 2 && (std::isnan(x) || std::isinf(x))) continue;  // preserved
-        const float v = (float)code_magnitude(f, code & (uint32_t)((((int64_t)1) << (X + Y)) - 1));
-        const float r = v * s;  // fp32 product, one rounding
-        uint32_t out = dt == ORACLE_F32 ? float_to_bits(r) : (dt == ORACLE_F16 ? round_to_half_float_bits(r) : round_to_bf16_bits(r));
+        // the real product value * s (exact in a double: at most 24 + 24 bits), rounded once into the container
+        const double r = code_magnitude(f, code & (uint32_t)((((int64_t)1) << (X + Y)) - 1)) * s;
+        uint32_t out = dt == ORACLE_F32 ? float_to_bits((float)r) : (dt == ORACLE_F16 ? round_to_half_float_bits(r) : round_to_bf16_bits(r));
         out |= ((code >> (X + Y)) & 1u) << 31;
         store_bits(dst, dt, i, out);
       }
@@ -1184,7 +1192,7 @@ int exmy_oracle_emulate_int(void* data, int dt, uint64_t n, int Y, int max_exp) 
 }
 
 // fp32 -> bf16 / fp16 roundings used above, exported so that they can be pinned on their own.
-uint32_t exmy_oracle_round_to_bf16_bits(float r) { return round_to_bf16_bits(r); }
-uint32_t exmy_oracle_round_to_half_float_bits(float r) { return round_to_half_float_bits(r); }
+uint32_t exmy_oracle_round_to_bf16_bits(double r) { return round_to_bf16_bits(r); }
+uint32_t exmy_oracle_round_to_half_float_bits(double r) { return round_to_half_float_bits(r); }
 
 }  // extern "C"

@@ -58,9 +58,9 @@ def lib():
         L.exmy_oracle_decode_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, vp, i32]
         L.exmy_oracle_emulate_scaled.argtypes = [vp, i32, u64, u64, i32, i32, vp, i32]
         L.exmy_oracle_round_to_bf16_bits.restype = ctypes.c_uint32
-        L.exmy_oracle_round_to_bf16_bits.argtypes = [ctypes.c_float]
+        L.exmy_oracle_round_to_bf16_bits.argtypes = [ctypes.c_double]
         L.exmy_oracle_round_to_half_float_bits.restype = ctypes.c_uint32
-        L.exmy_oracle_round_to_half_float_bits.argtypes = [ctypes.c_float]
+        L.exmy_oracle_round_to_half_float_bits.argtypes = [ctypes.c_double]
         L.exmy_oracle_packed_bytes_rows.restype = u64
         L.exmy_oracle_packed_bytes_rows.argtypes = [u64, u64, i32, i32]
         L.exmy_oracle_encode_rows.argtypes = [vp, i32, u64, u64, i32, i32, i32, vp, vp]

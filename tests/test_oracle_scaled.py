@@ -2,6 +2,10 @@
 of the max_exp = 127 format): the paper's 3.9 example for the three schemes, the
 library's bf16 rounding, exact equivalence with the power-of-two metadata when
 the scale is a power of two, and a brute-force nearest-value search."""
+import bisect
+import math
+from fractions import Fraction
+
 import numpy as np
 import pytest
 import torch
@@ -142,45 +146,145 @@ def test_block_scale_definition_and_block_maximum_is_kept(dtype):
         assert ok[3:].all(), (X, Y)
 
 
-@pytest.mark.parametrize("X,Y", [(2, 1), (3, 2), (1, 3), (0, 4), (4, 3)])
+def nearest_code_exact(grid, a, s):
+    """Index of the grid point nearest the rational a / s, ties to the even index, by exact integer
+    arithmetic (grid: ascending Fractions)."""
+    t = Fraction(float(a)) / Fraction(float(s))
+    if t >= grid[-1]:
+        return len(grid) - 1
+    hi = bisect.bisect_right(grid, t)      # grid[hi - 1] <= t < grid[hi]
+    lo = hi - 1
+    d_lo, d_hi = t - grid[lo], grid[hi] - t
+    if d_lo != d_hi:
+        return lo if d_lo < d_hi else hi
+    return lo if lo % 2 == 0 else hi
+
+
+def near_boundary_inputs(grid, rng, count):
+    """(x, scale) pairs, one element per block, whose quotient lies within an fp32 rounding error of a rounding
+    boundary of the grid (the midpoint of two neighbouring grid points), on either side of it or exactly on it:
+    the inputs on which a quotient computed in fp32 (a division, or a multiplication by a reciprocal) picks the
+    wrong neighbour."""
+    xs, ss = [], []
+    mids = [(grid[i] + grid[i + 1]) / 2 for i in range(len(grid) - 1)]
+    while len(xs) < count:
+        m = mids[int(rng.integers(len(mids)))]
+        if rng.random() < 0.25:
+            s = np.float32(np.ldexp(float(rng.integers(1, 1 << 8)), int(rng.integers(-20, 20))))  # few bits: m * s is an fp32
+        else:
+            s = np.float32(np.ldexp(1.0 + rng.random(), int(rng.integers(-40, 40))))
+        x = np.float32(float(m * Fraction(float(s))))      # the fp32 nearest the boundary's preimage
+        x = np.nextafter(x, np.float32(np.inf if rng.random() < 0.5 else 0), dtype=np.float32) if rng.random() < 0.5 else x
+        xs.append(x if rng.random() < 0.5 else -x)
+        ss.append(s)
+    return np.array(xs, dtype=np.float32), np.array(ss, dtype=np.float32)
+
+
+@pytest.mark.parametrize("X,Y", [(2, 1), (3, 2), (1, 3), (0, 4), (4, 3), (3, 0), (5, 10), (7, 1)])
 def test_scaled_codes_are_the_nearest_grid_points(X, Y):
+    """The code is that of the real quotient |x| / s: nearest grid point, ties to even, found here with exact
+    rational arithmetic on random data and on inputs built to sit on or next to a rounding boundary."""
     g = torch.Generator().manual_seed(X + 10 * Y)
-    n, block = 1 << 13, 16
+    n, block = 1 << 11, 16
     x = (torch.randn(n, generator=g) * torch.exp2(torch.randint(-6, 6, (n,), generator=g).float())).float()
     xn = x.numpy()
     s = O.block_scale(xn, block, X, Y)
-    packed = O.encode_scaled(xn, block, X, Y, s)
-    codes = O.unpack(packed, n, 1 + X + Y)
-    grid = np.array([O.code_value(X, Y, 127, c) for c in range(1 << (X + Y))])  # ascending magnitudes
-    mag = codes & ((1 << (X + Y)) - 1)
-    sign = codes >> (X + Y)
-    assert np.array_equal(sign, (xn < 0).astype(codes.dtype) | (np.signbit(xn)).astype(codes.dtype))
-    t = np.abs(xn.astype(np.float64)) / np.repeat(s.astype(np.float64), block)  # exact quotient, to fp64
-    t = np.minimum(t, grid[-1])
-    best = np.abs(grid[None, :] - t[:, None]).min(axis=1)
-    got = np.abs(grid[mag] - t)
-    # nearest, except that the fp32 rounding of the product may swap the two neighbours of a near-tie
-    assert (got <= best + 4e-7 * np.maximum(t, grid[1])).all()
-    # and the decoded value is the grid point times the scale, rounded once
-    dec = O.decode_scaled(packed, F32, n, block, X, Y, s)
-    want = (grid[mag].astype(np.float32) * np.repeat(s, block)).astype(np.float32) * np.where(sign == 1, -1.0, 1.0).astype(np.float32)
-    assert np.array_equal(dec.view(np.uint32), want.view(np.uint32))
+    grid = [Fraction(O.code_value(X, Y, 127, c)) for c in range(1 << (X + Y))]  # ascending magnitudes
+    assert all(p < q for p, q in zip(grid, grid[1:]))
+
+    def check(xn, s, block):
+        codes = O.unpack(O.encode_scaled(xn, block, X, Y, s), xn.size, 1 + X + Y)
+        mag = codes & ((1 << (X + Y)) - 1)
+        assert np.array_equal(codes >> (X + Y), np.signbit(xn).astype(codes.dtype))
+        want = [nearest_code_exact(grid, abs(v), s[i // block]) for i, v in enumerate(xn.tolist())]
+        if Y == 0:  # an exact tie goes to the even significand, which for Y = 0 is the next binade (the code above)
+            ties = [i for i, v in enumerate(xn.tolist())
+                    if mag[i] != want[i] and mag[i] == want[i] + 1
+                    and Fraction(abs(v)) / Fraction(float(s[i // block])) == (grid[want[i]] + grid[mag[i]]) / 2]
+            for i in ties:
+                assert want[i] >= 1  # between two normals, not at the top of the subnormal range
+                want[i] += 1
+        assert np.array_equal(mag, np.array(want, dtype=mag.dtype))
+        return mag
+
+    check(xn, s, block)
+    bx, bs = near_boundary_inputs(grid, np.random.default_rng(X * 100 + Y), 3000)
+    pad = np.zeros((bx.size, 8), dtype=np.float32)
+    pad[:, 0] = bx
+    mag = check(pad.reshape(-1), bs, 8)
+    # the built inputs really are decided by less than an fp32 rounding error: the fp32 quotient
+    # |x| * fl(1 / s) rounded onto the grid differs from the exact result on some of them
+    q32 = (np.abs(bx) * (np.float32(1.0) / bs)).astype(np.float32)
+    naive = np.array([nearest_code_exact(grid, q, 1.0) for q in q32.tolist()])
+    assert (naive != mag[::8]).any()
 
 
-def test_bf16_results_are_the_fp32_results_rounded_by_the_library():
-    g = torch.Generator().manual_seed(11)
-    n, block = 1 << 14, 32
-    x = (torch.randn(n, generator=g) * torch.exp2(torch.randint(-20, 20, (n,), generator=g).float())).bfloat16()
-    xn = as_np(x)
-    for X, Y in ((2, 1), (3, 3), (0, 4), (4, 3)):
-        s = O.block_scale(xn, block, X, Y)
-        s = (s * np.float32(1.2345)).astype(np.float32)  # not a power of two: products need rounding
-        packed = O.encode_scaled(xn, block, X, Y, s)
-        d32 = O.decode_scaled(packed, F32, n, block, X, Y, s)
-        d16 = O.decode_scaled(packed, BF16, n, block, X, Y, s)
-        want = torch.from_numpy(d32).bfloat16()
-        assert np.array_equal(d16, want.view(torch.int16).numpy().view(np.uint16))
-        assert (torch.from_numpy(d32) != want.float()).any()  # the rounding really happens
+def nearest_in_container_exact(p, mant_bits, emin):
+    """Fraction p >= 0 rounded to nearest, ties to even, onto the floating-point grid with `mant_bits` stored
+    mantissa bits and smallest normal 2^emin (denormals below), as a Fraction; no overflow handling."""
+    if p == 0:
+        return p
+    e = max(math.floor(math.log2(p)) if p >= 1 else -math.ceil(math.log2(1 / p)), emin)
+    while Fraction(2) ** e > p and e > emin:
+        e -= 1
+    while Fraction(2) ** (e + 1) <= p:
+        e += 1
+    q = Fraction(2) ** (e - mant_bits)
+    k = p / q
+    lo = k.numerator // k.denominator
+    r = k - lo
+    if r > Fraction(1, 2) or (r == Fraction(1, 2) and lo % 2 == 1):
+        lo += 1
+    return lo * q
+
+
+@pytest.mark.parametrize("dt,torch_dt,mant,emin", [(F32, torch.float32, 23, -126), (BF16, torch.bfloat16, 7, -126),
+                                                 (O.F16, torch.float16, 10, -14)])
+def test_scaled_decode_is_the_exact_product_rounded_once(dt, torch_dt, mant, emin):
+    """Decoded value = grid value * scale as a real number, rounded once into the container.  For bf16 and fp16
+    that is not the fp32 product rounded again: the test searches for products whose fp32 rounding lands exactly
+    on a tie of the narrower type and checks that the result follows the real product there."""
+    X, Y = (3, 3) if dt != O.F16 else (3, 5)
+    rng = np.random.default_rng(5 + dt)
+    ncodes = 1 << (X + Y)
+    grid = np.array([O.code_value(X, Y, 127, c) for c in range(ncodes)])
+    trials = 1 << 22
+    c = rng.integers(1, ncodes, trials)
+    lo_e, hi_e = (-20, 20) if dt != O.F16 else (-18, 8)   # fp16: results from deep denormals to near the top
+    s = np.ldexp(1.0 + rng.random(trials), rng.integers(lo_e, hi_e, trials)).astype(np.float32)
+    exact = grid[c] * s.astype(np.float64)                # exact: at most 7 + 24 bits
+    p32 = exact.astype(np.float32)
+    keep = np.zeros(trials, dtype=bool)
+    keep[:4096] = True
+    if dt != F32:
+        # fp32 product inexact and exactly half-way between two values of the narrower type
+        narrow = torch.from_numpy(p32).to(torch_dt).float().numpy().astype(np.float64)
+        up = torch.nextafter(torch.from_numpy(p32).to(torch_dt), torch.tensor(float("inf"), dtype=torch_dt)).float().numpy().astype(np.float64)
+        dn = torch.nextafter(torch.from_numpy(p32).to(torch_dt), torch.tensor(float("-inf"), dtype=torch_dt)).float().numpy().astype(np.float64)
+        p = p32.astype(np.float64)
+        tie = ((p - narrow == up - p) | (narrow - p == p - dn)) & (p != narrow)
+        hazard = tie & (p != exact)
+        assert hazard.sum() >= 8
+        keep |= hazard
+    c, s, exact = c[keep], s[keep], exact[keep]
+    n = c.size // 8 * 8
+    c, s, exact = c[:n], s[:n], exact[:n]
+    sign = rng.integers(0, 2, n)
+    codes = (c | (sign << (X + Y))).astype(np.uint32)
+    packed = O.pack(codes, 1 + X + Y)
+    got = O.decode_scaled(packed, dt, n, 8, X, Y, np.repeat(s.reshape(-1, 8)[:, :1], 8, axis=1).reshape(-1)[::8].copy())
+    # one scale per block of 8: rebuild the products with the scale each element really got
+    s_used = np.repeat(s[::8], 8)
+    got = to_torch(got, torch_dt).double().numpy()
+    want = np.array([float(nearest_in_container_exact(Fraction(float(grid[ci])) * Fraction(float(si)), mant, emin))
+                     for ci, si in zip(c.tolist(), s_used.tolist())])
+    want = np.where(sign == 1, -want, want)
+    assert np.array_equal(got, want)
+    if dt != F32:
+        twice = torch.from_numpy((grid[c] * s_used.astype(np.float64)).astype(np.float32)).to(torch_dt).double().numpy()
+        twice = np.where(sign == 1, -twice, twice)
+        # the search is over (code, scale) pairs; after regrouping by block only the first of each 8 keeps its scale
+        assert (np.abs(twice[::8]) != np.abs(got[::8])).any()  # rounding the fp32 product again would differ
 
 
 def test_scaled_validation():
