@@ -73,11 +73,11 @@
 //     container (fp32, bf16 or fp16).  Both are evaluated in double: the
 //     product of a value of at most 24 bits and a 24-bit scale is exact there,
 //     and the quotient of two fp32 numbers is either exactly a rounding
-//     boundary of the grid (boundaries have at most Y + 2 <= 25 significant
+//     boundary of the grid (boundaries have at most Y + 2 <= 26 significant
 //     bits, hence are doubles, and the double division then returns it exactly)
-//     or further from every boundary than 2^-50 of its size (a 24-bit number
-//     minus a 49-bit product), which the 2^-53 error of the double division
-//     cannot bridge.  Parity unpinned by the paper beyond the
+//     or further from every boundary than 2^-51 of its size (a 24-bit number
+//     minus a product of at most 50 bits), which the 2^-53 error of the double
+//     division cannot bridge.  Parity unpinned by the paper beyond the
 //     property that the block maximum is reproduced almost exactly.  The bf16
 //     form of the scaling factor named in the same passage: the smallest bf16
 //     value not below that fp32 scale (never below, so that the block maximum

@@ -280,6 +280,9 @@ exmy_status_t run_blocks(BlockOp op, bool scaled, const void* elems, const void*
     uint32_t sat = args.tc127.sat_bits;
     memcpy(&args.vmax127, &sat, 4);
   }
+  // the fp32 form of the scaled rounding needs every rounding boundary above the fp32 denormals (X <= 6)
+  // and a quantum wider than the uncertainty of the fp32 quotient (Y <= 17)
+  args.scaled_f64 = (scaled && (X == 7 || Y > 17 || wide_format)) ? 1u : 0u;
   if (block < 8 || block % 8 || block > EXMY_MAX_BLOCK) return EXMY_ERR_BLOCK;
   if (n > EXMY_MAX_ELEMENTS) return EXMY_ERR_COUNT;
   if (n == 0) return EXMY_OK;

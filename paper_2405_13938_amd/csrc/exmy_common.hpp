@@ -124,12 +124,13 @@ struct BlockArgs {
   const void* src;      // encode / emulate: elements; decode: packed planes
   void* dst;            // encode: packed planes; decode: elements; emulate: unused
   uint8_t* meta;        // one byte per block (read; written by the max-exponent kernel)
-  // Float scaling (Section 2 "Metadata": an additional bfloat16 or float32
-  // scaling factor; Section 2.1: "float scaling with maximum exponent 127"): one
-  // scale per block instead of the metadata byte, with the constants of
-  // max_exp = 127.  A bf16 scale is used widened to fp32.
+  // Float scaling (Section 2 "Metadata": an extra bf16 or fp32 scaling factor per
+  // block; Section 2.1: the third scheme of the emulation example): one scale per
+  // block instead of the metadata byte, with the constants of max_exp = 127.  A
+  // bf16 scale is used widened to fp32.
   void* scale;
   uint32_t scale_log2_bytes;  // 2: fp32 scales, 1: bf16 scales
+  uint32_t scaled_f64;        // quotients are formed and rounded in fp64 (X = 7 or Y > 17: see scaled_sum_f64)
   TensorConsts tc127;
   float vmax127;        // largest value of the format with max_exp = 127
   uint64_t n;           // elements
@@ -541,21 +542,169 @@ __device__ __forceinline__ uint32_t bit_select(uint32_t mask, uint32_t a, uint32
   return d;
 }
 
-// Float scaling, encode side: fp32-position bits of x * inv with the sign bit of
-// x itself (a NaN keeps its sign whatever the multiplier does with it).
-__device__ __forceinline__ uint32_t scaled_bits(uint32_t u, float inv) {
-  return bit_select(0x7FFFFFFFu, as_u32(__builtin_fabsf(as_f32(u)) * inv), u);
+// ---------------------------------------------------------------- float scaling
+//
+// Section 2 "Metadata" / Section 2.1 (an extra fp32 or bf16 scale per block, codes of the max_exp = 127
+// format).  The code of x is that of the real quotient |x| / s: nearest grid point, ties to even.  The
+// kernels multiply by inv = fl(1 / s) instead of dividing, so their quotient q = fl(|x| * inv) carries a
+// relative error of up to 2^-23 (2^-21.7 when s > 2^126 makes inv an fp32 denormal); that matters only
+// for the few elements whose quotient lies that close to a rounding boundary of the grid.  They are
+// found by rounding twice, q * (1 - eps) and q * (1 + eps) (each inside one fused multiply-add with the
+// rounding addend, so the perturbation itself is not rounded): where both give the same sum the real
+// quotient, which lies in between, gives it too.  Where they differ (by one grid step) the boundary m
+// between the two candidates is a short float, and the sign of the exact residual |x| - m * s, again one
+// fused multiply-add, says on which side of it the real quotient lies (zero: an exact tie, the even
+// candidate).  That second step runs only in wavefronts where a ballot finds such an element.
+//
+// Valid for X <= 6 and Y <= 21: every rounding boundary of the format is then far above the fp32
+// denormals, so a quotient small enough to lose bits rounds to zero whatever its error.  e7mY (whose
+// subnormal grid lies among the fp32 denormals) and Y > 21 take scaled_sum_f64 below.
+struct ScaleOfBlock {
+  float scale;   // s, finite and >= FLT_MIN
+  float inv;     // fl(1 / s)
+  float one_lo;  // 1 - eps
+  float one_hi;  // 1 + eps
+};
+
+__device__ __forceinline__ ScaleOfBlock scale_of_block(uint32_t scale_bits) {
+  ScaleOfBlock sb;
+  sb.scale = as_f32(scale_bits);
+  sb.inv = 1.0f / sb.scale;
+  const bool tiny_inv = scale_bits > 0x7E800000u;  // s > 2^126: inv is a denormal with 22 or 21 significant bits
+  sb.one_lo = tiny_inv ? 1.0f - 0x1p-20f : 1.0f - 0x1p-22f;
+  sb.one_hi = tiny_inv ? 1.0f + 0x1p-20f : 1.0f + 0x1p-22f;
+  return sb;
 }
 
-// Float scaling, decode side: bits of |v| * scale (v finite, scale > 0) under the
-// sign of v.  For bf16 the result is rounded to nearest even at bit 16 here, the
-// lower half then to be dropped (a carry may run up to the Inf pattern, as in the
-// library conversion); fp16 results are rounded when they are converted.
+// The two rounded sums of the element with fp32-position bits u (see magnitude_code_left for what a sum
+// is: rounding addend + |value|, whose low bits are round(|value| / quantum)); te = clamped exponent << 23.
+struct ScaledSums {
+  uint32_t te, lo, hi;
+};
+__device__ __forceinline__ ScaledSums scaled_sums(uint32_t u, const ScaleOfBlock& sb, const FormatConsts& fc,
+                                                  const TensorConsts& tc127) {
+  uint32_t q = as_u32(__builtin_fabsf(as_f32(u)) * sb.inv);  // Inf, NaN and overflow: patterns above sat_bits
+  q = min(q, tc127.sat_bits);
+  ScaledSums r;
+  r.te = max(q, tc127.emin_bits) & 0x7F800000u;
+  const float addend = as_f32(r.te) * fc.magic_scale;  // a power of two: exact
+  r.lo = as_u32(__builtin_fmaf(as_f32(q), sb.one_lo, addend));
+  r.hi = as_u32(__builtin_fmaf(as_f32(q), sb.one_hi, addend));
+  return r;
+}
+
+// The sum of the real quotient for an element whose two sums differ (for one whose sums agree: that sum).
+// s_mant, s_exp: the scale as s_mant * 2^s_exp with s_mant in [0.5, 1).  All operands of the residual are
+// brought near 1 first, so that it cannot underflow: m * s_mant has at most 46 significant bits above
+// 2^-110, and |x| * 2^-s_exp is exact because it is about as large as that product.
+__device__ __forceinline__ uint32_t settle_scaled_sum(uint32_t u, const ScaledSums& ss, float s_mant, int s_exp,
+                                                      const FormatConsts& fc) {
+  const float addend = as_f32(ss.te) * fc.magic_scale;
+  const float below = as_f32(ss.lo) - addend;                       // the lower candidate: a grid value, exact
+  const float m = __builtin_fmaf(addend, 0x1p-24f, below);          // + half a quantum: the boundary
+  const float a = __builtin_ldexpf(__builtin_fabsf(as_f32(u)), -s_exp);
+  const float resid = __builtin_fmaf(-m, s_mant, a);                // sign of |x| - m * s, exact
+  const bool up = resid > 0.0f || (resid == 0.0f && (ss.lo & 1u));
+  return up ? ss.hi : ss.lo;
+}
+
+// Left-aligned magnitude code (as magnitude_code_left returns it) from a sum and its te.
+__device__ __forceinline__ uint32_t code_left_of_sum(uint32_t sum, uint32_t te, const FormatConsts& fc,
+                                                     const TensorConsts& tc) {
+  return lshl_add(sum, fc.left_shift, lshl_add(te, fc.exp_lshift, tc.bias_left));
+}
+
+// The same rounding in fp64, for the formats the scheme above does not cover: the quotient is the IEEE
+// fp64 division |x| / s, within 2^-53 of the real one and exact where the real one is a double.  A real
+// quotient that is exactly a rounding boundary is one (boundaries have at most 26 significant bits); any
+// other stays more than 2^-51 of its size away from every boundary (a 24-bit number against the product
+// of a boundary and a 24-bit scale), further than the division's error.  Returns the low word of the fp64
+// sum (k) and te; `value` receives the rounded magnitude.
+__device__ __forceinline__ uint32_t scaled_sum_f64(uint32_t u, double scale64, const FormatConsts& fc,
+                                                   const TensorConsts& tc127, uint32_t& te, float& value) {
+  double t = __builtin_fabs((double)as_f32(u)) / scale64;
+  const double vmax = (double)as_f32(tc127.sat_bits);
+  t = t < vmax ? t : vmax;  // anything above the largest value, Inf and NaN (for which the compare is false)
+  const uint32_t e11 = (uint32_t)__double2hiint(t) >> 20;
+  const uint32_t ec = max(e11, (tc127.emin_bits >> 23) + 896u);  // as an fp64 exponent field (1023 = 127 + 896)
+  const double addend = __hiloint2double((int)((ec - 896u + (uint32_t)fc.wide_exp) << 20), 0);
+  const double sum = t + addend;
+  te = (ec - 896u) << 23;
+  value = (float)(sum - addend);
+  return (uint32_t)__double2loint(sum);
+}
+
+// Float scaling, decode side: the real product v * s rounded once, to nearest even, into the container.
+// fp32: the multiplication itself.  bf16 / fp16: the fp32 product p is rounded again by the conversion,
+// which goes wrong exactly when p is inexact and lies half-way between two values of the narrower type.
+// All such p have their low 15 (bf16) / 12 (fp16, whose denormals shift the half-way bit upwards) bits
+// clear; scaled_product_suspect says whether p is one of those, and settle_scaled_product then moves an
+// inexact p one ulp towards the real product, which takes it off the half-way point on the right side
+// (and does no harm to a p that is a value of the narrower type).
 template <typename T>
-__device__ __forceinline__ uint32_t rescaled_bits(uint32_t v, float scale) {
-  uint32_t m = as_u32(__builtin_fabsf(as_f32(v)) * scale);
-  if constexpr (sizeof(T) == 2 && !kIsF16<T>) m += 0x7FFFu + ((m >> 16) & 1u);
-  return bit_select(0x7FFFFFFFu, m, v);
+__device__ __forceinline__ bool scaled_product_low_bits_clear(float p) {
+  return (as_u32(p) & (kIsF16<T> ? 0x00000FFFu : 0x00007FFFu)) == 0;
+}
+
+// Whether one of a lane's E products may be such a half-way case (then every lane of the wavefront settles
+// its products).  short_scale (wave-uniform): the scales are bf16 values, so a product has at most 19
+// significant bits and is exact unless it falls among the fp32 denormals.
+template <typename T, int E>
+__device__ __forceinline__ bool scaled_products_suspect(const float (&p)[E], bool short_scale) {
+  uint32_t lowest = 0xFFFFFFFFu;
+  if (short_scale) {
+#pragma unroll
+    for (int j = 0; j < E; ++j) lowest = min(lowest, (as_u32(p[j]) & 0x7FFFFFFFu) - 1u);  // zero wraps to the top
+    return lowest < 0x007FFFFFu;
+  }
+#pragma unroll
+  for (int j = 0; j < E; ++j) {
+    if constexpr (kIsF16<T>)
+      lowest = min(lowest, as_u32(p[j]) & 0x00000FFFu);
+    else
+      lowest = min(lowest, (as_u32(p[j]) << 16) + 0x80000000u);  // zero exactly for the pattern ...8000
+  }
+  return lowest == 0;
+}
+
+// p = fl(v * s) moved one ulp towards the real product where it is inexact and `suspect` (its low bits
+// are clear); s = s_mant * 2^s_exp with s_mant in [0.5, 1).  Signs ride along untouched.
+__device__ __forceinline__ float settle_scaled_product(float p, float v, float s_mant, int s_exp, bool suspect) {
+  // v * s - p on magnitudes, exactly signed: operands brought near 1 so that the residual cannot underflow
+  const float av = __builtin_fabsf(v), ap = __builtin_fabsf(p);
+  const float v_mant = __builtin_amdgcn_frexp_mantf(av);
+  const int v_exp = __builtin_amdgcn_frexp_expf(av);
+  const float resid = __builtin_fmaf(v_mant, s_mant, -__builtin_ldexpf(ap, -(v_exp + s_exp)));  // > 0: p is too small
+  uint32_t b = as_u32(p);
+  const bool finite_nonzero = (as_u32(ap) - 1u) < 0x7F7FFFFFu;
+  if (suspect && finite_nonzero && resid != 0.0f) b += resid > 0.0f ? 1u : 0xFFFFFFFFu;  // the magnitude, +-1 ulp
+  return as_f32(b);
+}
+
+// One product on its own (the few elements after the last whole vector): fp32-position bits of v * s
+// rounded once to T (bf16: in the upper half), under the sign of v.
+template <typename T>
+__device__ __forceinline__ uint32_t scaled_product_bits(uint32_t v_bits, float scale) {
+  float p = as_f32(v_bits) * scale;
+  if constexpr (sizeof(T) == 2) {
+    p = settle_scaled_product(p, as_f32(v_bits), __builtin_amdgcn_frexp_mantf(scale), __builtin_amdgcn_frexp_expf(scale),
+                              scaled_product_low_bits_clear<T>(p));
+    if constexpr (!kIsF16<T>) {
+      uint32_t m = as_u32(p) & 0x7FFFFFFFu;
+      m += 0x7FFFu + ((m >> 16) & 1u);  // to nearest even at bit 16; a carry may run up to the Inf pattern
+      return (m & 0xFFFF0000u) | (v_bits & 0x80000000u);
+    }
+  }
+  return as_u32(p);
+}
+
+// One element's code sum on its own, always settled (no vote): the sum and its te.
+__device__ __forceinline__ uint32_t scaled_sum_settled(uint32_t u, uint32_t scale_bits, const FormatConsts& fc,
+                                                       const TensorConsts& tc127, uint32_t& te) {
+  const ScaleOfBlock sb = scale_of_block(scale_bits);
+  const ScaledSums ss = scaled_sums(u, sb, fc, tc127);
+  te = ss.te;
+  return settle_scaled_sum(u, ss, __builtin_amdgcn_frexp_mantf(sb.scale), __builtin_amdgcn_frexp_expf(sb.scale), fc);
 }
 
 __device__ __forceinline__ uint32_t keep_nonfinite_halves(uint32_t w, uint32_t emulated) {

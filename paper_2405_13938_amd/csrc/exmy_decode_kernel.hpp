@@ -103,33 +103,45 @@ __device__ __forceinline__ uint32_t element_bits(const UnitWords<W>& uw, int j, 
 }
 
 // The 16 bytes of one unit's values.
-// kScaled (float scaling): every value is multiplied by `scale` on the way out.
+// kScaled (float scaling): every value is multiplied by `scale` on the way out and the real product is
+// rounded once into T (see settle_scaled_product); short_scale (wave-uniform): the scales are bf16 values.
 template <typename T, int W, bool kX8, bool kScaled = false>
 __device__ __forceinline__ uint4 unit_values(const UnitWords<W>& uw, const FormatConsts& fc, const TensorConsts& tc,
-                                             float scale = 1.0f) {
+                                             float scale = 1.0f, bool short_scale = false) {
   constexpr int E = 16 / sizeof(T);
-  constexpr bool kRoundPairs = kScaled && sizeof(T) == 2 && !kIsF16<T>;  // bf16 products: rounded pair by pair
   uint32_t b[E];
 #pragma unroll
-  for (int j = 0; j < E; ++j) {
-    b[j] = element_bits<W, kX8>(uw, j, fc, tc);
-    if constexpr (kScaled && !kRoundPairs) b[j] = rescaled_bits<T>(b[j], scale);
-  }
-  if constexpr (kRoundPairs) {
+  for (int j = 0; j < E; ++j) b[j] = element_bits<W, kX8>(uw, j, fc, tc);
+  if constexpr (kScaled) {
     float p[E];
 #pragma unroll
     for (int j = 0; j < E; ++j) p[j] = as_f32(b[j]) * scale;  // scale > 0: the product keeps the sign
-    return make_uint4(round_pack_bf16(p[0], p[1]), round_pack_bf16(p[2], p[3]), round_pack_bf16(p[4], p[5]),
-                      round_pack_bf16(p[6], p[7]));
+    if constexpr (sizeof(T) == 4) {
+      return make_uint4(as_u32(p[0]), as_u32(p[1]), as_u32(p[2]), as_u32(p[3]));
+    } else {
+      if (__builtin_amdgcn_ballot_w64(scaled_products_suspect<T, E>(p, short_scale)) != 0) {
+        const float s_mant = __builtin_amdgcn_frexp_mantf(scale);
+        const int s_exp = __builtin_amdgcn_frexp_expf(scale);
+#pragma unroll
+        for (int j = 0; j < E; ++j)
+          p[j] = settle_scaled_product(p[j], as_f32(b[j]), s_mant, s_exp, scaled_product_low_bits_clear<T>(p[j]));
+      }
+      if constexpr (kIsF16<T>)
+        return make_uint4(pack_elems<T, false>(as_u32(p[0]), as_u32(p[1])), pack_elems<T, false>(as_u32(p[2]), as_u32(p[3])),
+                          pack_elems<T, false>(as_u32(p[4]), as_u32(p[5])), pack_elems<T, false>(as_u32(p[6]), as_u32(p[7])));
+      else  // bf16: rounded pair by pair by the conversion instruction
+        return make_uint4(round_pack_bf16(p[0], p[1]), round_pack_bf16(p[2], p[3]), round_pack_bf16(p[4], p[5]),
+                          round_pack_bf16(p[6], p[7]));
+    }
   } else if constexpr (sizeof(T) == 4) {
     return make_uint4(b[0], b[1], b[2], b[3]);
   } else {
-    // every value is exact in bf16 (or has just been rounded to it): keep the upper halves
+    // every value is exact in the 16-bit type: keep the upper halves / convert exactly
     uint4 o;
-    o.x = pack_elems<T, !kScaled>(b[0], b[1]);
-    o.y = pack_elems<T, !kScaled>(b[2], b[3]);
-    o.z = pack_elems<T, !kScaled>(b[4], b[5]);
-    o.w = pack_elems<T, !kScaled>(b[6], b[7]);
+    o.x = pack_elems<T>(b[0], b[1]);
+    o.y = pack_elems<T>(b[2], b[3]);
+    o.z = pack_elems<T>(b[4], b[5]);
+    o.w = pack_elems<T>(b[6], b[7]);
     return o;
   }
 }
@@ -137,8 +149,9 @@ __device__ __forceinline__ uint4 unit_values(const UnitWords<W>& uw, const Forma
 // Values of one unit, stored to 16-byte vector lane_unit + tile_unit of `out`.
 template <typename T, int W, bool kX8, bool kNT, bool kScaled = false>
 __device__ __forceinline__ void decode_unit(const UnitWords<W>& uw, const FormatConsts& fc, const TensorConsts& tc,
-                                            rsrc_t out, uint32_t lane_unit, uint32_t tile_unit, float scale = 1.0f) {
-  store16<kNT>(out, lane_unit * 16, tile_unit * 16, unit_values<T, W, kX8, kScaled>(uw, fc, tc, scale));
+                                            rsrc_t out, uint32_t lane_unit, uint32_t tile_unit, float scale = 1.0f,
+                                            bool short_scale = false) {
+  store16<kNT>(out, lane_unit * 16, tile_unit * 16, unit_values<T, W, kX8, kScaled>(uw, fc, tc, scale, short_scale));
 }
 
 // A lane of a narrow format reads 1-3 bytes per plane straight from memory.  Whole tiles
@@ -373,7 +386,8 @@ __global__ __launch_bounds__(kBlock) void decode_blocks_kernel(const BlockArgs a
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r) {
         if constexpr (kScaled)
-          decode_unit<T, W, false, kNT, true>(tw.u[r], fc, args.tc127, out, threadIdx.x, r * kBlock, as_f32(me[r]));
+          decode_unit<T, W, false, kNT, true>(tw.u[r], fc, args.tc127, out, threadIdx.x, r * kBlock, as_f32(me[r]),
+                                              args.scale_log2_bytes == 1);
         else
           decode_unit_meta<T, W, kNT>(tw.u[r], me[r], fc, bc, out, threadIdx.x, r * kBlock, try_uniform);
       }
@@ -388,7 +402,8 @@ __global__ __launch_bounds__(kBlock) void decode_blocks_kernel(const BlockArgs a
       for (int r = 0; r < kUnroll; ++r) {
         if (r * kBlock + threadIdx.x < rem_units) {
           if constexpr (kScaled)
-            decode_unit<T, W, false, kNT, true>(tw.u[r], fc, args.tc127, out, threadIdx.x, r * kBlock, as_f32(me[r]));
+            decode_unit<T, W, false, kNT, true>(tw.u[r], fc, args.tc127, out, threadIdx.x, r * kBlock, as_f32(me[r]),
+                                              args.scale_log2_bytes == 1);
           else
             decode_unit_meta<T, W, kNT>(tw.u[r], me[r], fc, bc, out, threadIdx.x, r * kBlock, try_uniform);
         }
@@ -403,7 +418,7 @@ __global__ __launch_bounds__(kBlock) void decode_blocks_kernel(const BlockArgs a
       uint32_t b;
       if constexpr (kScaled) {
         b = element_bits_slow<W, false>(src, G, i, fc, args.tc127);
-        b = rescaled_bits<T>(b, as_f32(load_scale_bits(args, args.n_blocks - 1)));
+        b = scaled_product_bits<T>(b, as_f32(load_scale_bits(args, args.n_blocks - 1)));
       } else {
         b = element_bits_slow<W, false>(src, G, i, fc, derive_tc(meta[args.n_blocks - 1], bc));
       }

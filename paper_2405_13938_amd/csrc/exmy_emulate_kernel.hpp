@@ -146,53 +146,93 @@ __device__ __forceinline__ uint4 emulate_vector_meta(uint4 v, uint32_t me, bool 
   return emulate_vector<T, false>(v, fc, tc);
 }
 
-// Float scaling: the element is multiplied by the reciprocal of its block's scale,
-// rounded in the max_exp = 127 format and multiplied back; the result is rounded
-// to the container (bf16: to nearest even).  Inf / NaN pass through.
-template <bool kWide, typename T>
-__device__ __forceinline__ uint32_t emulate_scaled_bits(uint32_t u, float inv, float scale, const FormatConsts& fc,
-                                                        const TensorConsts& tc127) {
-  const uint32_t a0 = as_u32(__builtin_fabsf(as_f32(u)) * inv);  // an overflow to Inf saturates like any large value
-  const uint32_t r = emulate_magnitude<kWide>(a0, fc, tc127) | (u & 0x80000000u);
-  return (u & 0x7FFFFFFFu) >= 0x7F800000u ? u : rescaled_bits<T>(r, scale);
-}
-
-// The finite case alone, before the rounding to the container.
-template <bool kWide>
-__device__ __forceinline__ float emulate_scaled_product(uint32_t u, float inv, float scale, const FormatConsts& fc,
-                                                        const TensorConsts& tc127) {
-  const uint32_t a0 = as_u32(__builtin_fabsf(as_f32(u)) * inv);
-  return as_f32(emulate_magnitude<kWide>(a0, fc, tc127) | (u & 0x80000000u)) * scale;
-}
-
-template <typename T, bool kWide>
-__device__ __forceinline__ uint4 emulate_vector_scaled_as(uint4 v, float scale, float inv, const FormatConsts& fc,
-                                                          const TensorConsts& tc127) {
-  uint32_t w[4] = {v.x, v.y, v.z, v.w};
+// Float scaling: every element becomes the value, in the max_exp = 127 format, nearest its real quotient
+// by the block's scale (see scaled_sums), times the scale, rounded once into the container (see
+// settle_scaled_product).  Inf / NaN pass through.  f64 and short_scale are wave-uniform.
+template <typename T>
+__device__ __forceinline__ uint4 emulate_vector_scaled(uint4 v, uint32_t scale_bits, bool f64, bool short_scale,
+                                                       const FormatConsts& fc, const TensorConsts& tc127) {
+  constexpr int E = 16 / sizeof(T);
+  const uint32_t w[4] = {v.x, v.y, v.z, v.w};
+  uint32_t u[E];  // fp32-position bits
 #pragma unroll
   for (int k = 0; k < 4; ++k) {
     if constexpr (sizeof(T) == 4) {
-      w[k] = emulate_scaled_bits<kWide, T>(w[k], inv, scale, fc, tc127);
-    } else if constexpr (kIsF16<T>) {
-      const uint32_t lo = emulate_scaled_bits<kWide, T>(lo_elem_bits<T>(w[k]), inv, scale, fc, tc127);
-      const uint32_t hi = emulate_scaled_bits<kWide, T>(hi_elem_bits<T>(w[k]), inv, scale, fc, tc127);
-      w[k] = keep_nonfinite_halves(w[k], pack_elems<T, false>(lo, hi));
-    } else {  // bf16: both products rounded by one conversion, Inf / NaN put back afterwards
-      const float lo = emulate_scaled_product<kWide>(lo_elem_bits<T>(w[k]), inv, scale, fc, tc127);
-      const float hi = emulate_scaled_product<kWide>(hi_elem_bits<T>(w[k]), inv, scale, fc, tc127);
-      w[k] = keep_nonfinite_bf16(w[k], round_pack_bf16(lo, hi));
+      u[k] = w[k];
+    } else {
+      u[2 * k] = lo_elem_bits<T>(w[k]);
+      u[2 * k + 1] = hi_elem_bits<T>(w[k]);
     }
   }
-  return make_uint4(w[0], w[1], w[2], w[3]);
+  const float scale = as_f32(scale_bits);
+  float g[E];  // rounded magnitudes, before the scale is put back
+  if (f64) {
+    const double scale64 = (double)scale;
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      uint32_t te;
+      (void)scaled_sum_f64(u[j], scale64, fc, tc127, te, g[j]);
+    }
+  } else {
+    const ScaleOfBlock sb = scale_of_block(scale_bits);
+    ScaledSums ss[E];
+    uint32_t differ = 0;
+#pragma unroll
+    for (int j = 0; j < E; ++j) {
+      ss[j] = scaled_sums(u[j], sb, fc, tc127);
+      differ |= ss[j].lo ^ ss[j].hi;
+    }
+    if (__builtin_amdgcn_ballot_w64(differ != 0) != 0) {
+      const float s_mant = __builtin_amdgcn_frexp_mantf(scale);
+      const int s_exp = __builtin_amdgcn_frexp_expf(scale);
+#pragma unroll
+      for (int j = 0; j < E; ++j) ss[j].lo = settle_scaled_sum(u[j], ss[j], s_mant, s_exp, fc);
+    }
+#pragma unroll
+    for (int j = 0; j < E; ++j) g[j] = as_f32(ss[j].lo) - as_f32(ss[j].te) * fc.magic_scale;  // exact
+  }
+  float p[E];
+#pragma unroll
+  for (int j = 0; j < E; ++j) p[j] = g[j] * scale;
+  if constexpr (sizeof(T) == 2) {
+    if (__builtin_amdgcn_ballot_w64(scaled_products_suspect<T, E>(p, short_scale)) != 0) {
+      const float s_mant = __builtin_amdgcn_frexp_mantf(scale);
+      const int s_exp = __builtin_amdgcn_frexp_expf(scale);
+#pragma unroll
+      for (int j = 0; j < E; ++j) p[j] = settle_scaled_product(p[j], g[j], s_mant, s_exp, scaled_product_low_bits_clear<T>(p[j]));
+    }
+  }
+  uint32_t out[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    if constexpr (sizeof(T) == 4) {
+      out[k] = (u[k] & 0x7FFFFFFFu) >= 0x7F800000u ? u[k] : bit_select(0x7FFFFFFFu, as_u32(p[k]), u[k]);
+    } else if constexpr (kIsF16<T>) {
+      const uint32_t lo = bit_select(0x7FFFFFFFu, as_u32(p[2 * k]), u[2 * k]);
+      const uint32_t hi = bit_select(0x7FFFFFFFu, as_u32(p[2 * k + 1]), u[2 * k + 1]);
+      out[k] = keep_nonfinite_halves(w[k], pack_elems<T, false>(lo, hi));
+    } else {  // bf16: both products rounded by one conversion, signs and Inf / NaN put back afterwards
+      const uint32_t pair = bit_select(0x7FFF7FFFu, round_pack_bf16(p[2 * k], p[2 * k + 1]), w[k]);
+      out[k] = keep_nonfinite_bf16(w[k], pair);
+    }
+  }
+  return make_uint4(out[0], out[1], out[2], out[3]);
 }
 
+// One element on its own (after the last whole vector): fp32-position bits of its emulated value.
 template <typename T>
-__device__ __forceinline__ uint4 emulate_vector_scaled(uint4 v, uint32_t scale_bits, bool wide_format,
-                                                       const FormatConsts& fc, const TensorConsts& tc127) {
-  const float scale = as_f32(scale_bits);
-  const float inv = 1.0f / scale;
-  if (wide_format) return emulate_vector_scaled_as<T, true>(v, scale, inv, fc, tc127);
-  return emulate_vector_scaled_as<T, false>(v, scale, inv, fc, tc127);
+__device__ __forceinline__ uint32_t emulate_scaled_bits(uint32_t u, uint32_t scale_bits, bool f64, const FormatConsts& fc,
+                                                        const TensorConsts& tc127) {
+  float g;
+  uint32_t te;
+  if (f64) {
+    (void)scaled_sum_f64(u, (double)as_f32(scale_bits), fc, tc127, te, g);
+  } else {
+    const uint32_t sum = scaled_sum_settled(u, scale_bits, fc, tc127, te);
+    g = as_f32(sum) - as_f32(te) * fc.magic_scale;
+  }
+  const uint32_t r = scaled_product_bits<T>(as_u32(g) | (u & 0x80000000u), as_f32(scale_bits));
+  return (u & 0x7FFFFFFFu) >= 0x7F800000u ? u : r;
 }
 
 // wide_format: the format itself needs the fp64 path (Y > 21), whatever the metadata.
@@ -235,7 +275,7 @@ __global__ __launch_bounds__(kBlock) void emulate_blocks_kernel(const BlockArgs 
       if (r * kBlock + threadIdx.x < rem) {
         if constexpr (kScaled)
           store16<kNT>(buf, lane_off, r * kBlock * 16,
-                       emulate_vector_scaled<T>(v[r], me[r], wide_format, fc, args.tc127));
+                       emulate_vector_scaled<T>(v[r], me[r], args.scaled_f64 != 0, args.scale_log2_bytes == 1, fc, args.tc127));
         else
           store16<kNT>(buf, lane_off, r * kBlock * 16, emulate_vector_meta<T>(v[r], me[r], wide_format, fc, bc, try_uniform));
       }
@@ -253,10 +293,7 @@ __global__ __launch_bounds__(kBlock) void emulate_blocks_kernel(const BlockArgs 
         u = elem_bits<T>(reinterpret_cast<uint16_t*>(data)[i]);
       uint32_t r;
       if constexpr (kScaled) {
-        const float scale = as_f32(load_scale_bits(args, args.n_blocks - 1));
-        const float inv = 1.0f / scale;
-        r = wide_format ? emulate_scaled_bits<true, T>(u, inv, scale, fc, args.tc127)
-                        : emulate_scaled_bits<false, T>(u, inv, scale, fc, args.tc127);
+        r = emulate_scaled_bits<T>(u, load_scale_bits(args, args.n_blocks - 1), args.scaled_f64 != 0, fc, args.tc127);
       } else {
         const uint32_t me = meta[args.n_blocks - 1];
         const TensorConsts tc = derive_tc(me, bc);

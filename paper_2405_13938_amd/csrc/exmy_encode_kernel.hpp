@@ -433,16 +433,46 @@ __device__ __forceinline__ void encode_group_meta(const uint32_t u[8], uint32_t 
     encode_group<W, false>(u, fc, tc, pd, lane_group, tile_group);
 }
 
-// Float scaling: the group's elements are multiplied by the reciprocal of their
-// block's scale and take the codes of the max_exp = 127 format.
+// Float scaling: the group's elements take the codes, in the max_exp = 127 format, of their real
+// quotients by the block's scale (see scaled_sums).  f64 and vote are wave-uniform; vote = false (a lane on
+// its own) settles every element without asking the wavefront.
 template <int W, class Dst>
-__device__ __forceinline__ void encode_group_scaled(uint32_t u[8], uint32_t scale_bits, const FormatConsts& fc,
-                                                    const TensorConsts& tc127, const Dst& pd,
-                                                    uint32_t lane_group, uint32_t tile_group) {
-  const float inv = 1.0f / as_f32(scale_bits);
+__device__ __forceinline__ void encode_group_scaled(const uint32_t u[8], uint32_t scale_bits, bool f64,
+                                                    const FormatConsts& fc, const TensorConsts& tc127, const Dst& pd,
+                                                    uint32_t lane_group, uint32_t tile_group, bool vote = true) {
+  uint32_t f[8];
+  if (f64) {
+    const double scale64 = (double)as_f32(scale_bits);
 #pragma unroll
-  for (int j = 0; j < 8; ++j) u[j] = scaled_bits(u[j], inv);
-  encode_group<W, false>(u, fc, tc127, pd, lane_group, tile_group);
+    for (int j = 0; j < 8; ++j) {
+      uint32_t te;
+      float value;
+      const uint32_t k = scaled_sum_f64(u[j], scale64, fc, tc127, te, value);
+      f[j] = code_left_of_sum(k, te, fc, tc127);
+    }
+  } else {
+    const ScaleOfBlock sb = scale_of_block(scale_bits);
+    ScaledSums ss[8];
+    uint32_t differ = 0;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) {
+      ss[j] = scaled_sums(u[j], sb, fc, tc127);
+      differ |= ss[j].lo ^ ss[j].hi;
+    }
+    if (!vote || __builtin_amdgcn_ballot_w64(differ != 0) != 0) {
+      const float s_mant = __builtin_amdgcn_frexp_mantf(sb.scale);
+      const int s_exp = __builtin_amdgcn_frexp_expf(sb.scale);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) ss[j].lo = settle_scaled_sum(u[j], ss[j], s_mant, s_exp, fc);
+    }
+#pragma unroll
+    for (int j = 0; j < 8; ++j) f[j] = code_left_of_sum(ss[j].lo, ss[j].te, fc, tc127);
+  }
+  if constexpr (!(W & 1)) {  // even W: the sign rides at bit 31
+#pragma unroll
+    for (int j = 0; j < 8; ++j) f[j] |= u[j] & 0x80000000u;
+  }
+  peel_planes<W, Planes<W>::count - 1>(f, u, pd, lane_group, tile_group);
 }
 
 // kScaled: per-block fp32 scales instead of per-block metadata bytes.
@@ -488,7 +518,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
         uint32_t u[8];
         group_bits<T, true>(regs.v[r], u);
         if constexpr (kScaled)  // more arithmetic per element: the stage measured slower here
-          encode_group_scaled<W>(u, me[r], fc, args.tc127, pd, slot, r * kBlock);
+          encode_group_scaled<W>(u, me[r], args.scaled_f64 != 0, fc, args.tc127, pd, slot, r * kBlock);
         else
           encode_group_meta<W>(u, me[r], fc, bc, stage, slot, r * kBlock, try_uniform);
       }
@@ -505,7 +535,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
           uint32_t u[8];
           group_bits<T>(regs.v[r], u);
           if constexpr (kScaled)
-            encode_group_scaled<W>(u, me[r], fc, args.tc127, pd, threadIdx.x, r * kBlock);
+            encode_group_scaled<W>(u, me[r], args.scaled_f64 != 0, fc, args.tc127, pd, threadIdx.x, r * kBlock);
           else
             encode_group_meta<W>(u, me[r], fc, bc, pd, threadIdx.x, r * kBlock, try_uniform);
         }
@@ -531,7 +561,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
     PlaneDst<W> pd;
     make_plane_dst<W>(dst, G, Gfull, pd);
     if constexpr (kScaled)
-      encode_group_scaled<W>(u, load_scale_bits(args, args.n_blocks - 1), fc, args.tc127, pd, 0, 0);
+      encode_group_scaled<W>(u, load_scale_bits(args, args.n_blocks - 1), args.scaled_f64 != 0, fc, args.tc127, pd, 0, 0, false);
     else
       encode_group_meta<W>(u, meta[args.n_blocks - 1], fc, bc, pd, 0, 0, false);
   }

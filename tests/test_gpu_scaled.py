@@ -186,3 +186,103 @@ def test_bf16_scale_is_capped_at_the_largest_finite_bf16():
     torch.cuda.synchronize()
     assert got.view(torch.int16).cpu().tolist() == [0x7F7F, 0x0080]
     assert O.block_scale(synth.bits_numpy(x), 32, 1, 0, bf16=True).tolist() == [0x7F7F, 0x0080]
+
+
+def grid_of(X, Y):
+    return np.array([O.code_value(X, Y, 127, c) for c in range(1 << (X + Y))], dtype=np.float64)
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16, torch.float16])
+@pytest.mark.parametrize("X,Y", [(2, 1), (3, 3), (4, 3), (0, 4), (1, 6), (3, 0), (7, 1), (6, 2), (2, 5), (5, 10), (1, 14)])
+def test_quotients_next_to_rounding_boundaries(dtype, X, Y):
+    """Elements whose real quotient |x| / s lies within one or two fp32 roundings of a rounding boundary of the
+    grid (or exactly on it): the scale is chosen per block as the fp32 nearest x / boundary, or a neighbour of it."""
+    P = {torch.float32: 23, torch.bfloat16: 7, torch.float16: 10}[dtype]
+    if Y > P or (dtype == torch.float16 and (X > 5 or Y + (1 << X) > 26)) or 1 + X + Y > 16:
+        pytest.skip("format does not fit the container")
+    rng = np.random.default_rng(1000 * X + Y)
+    grid = grid_of(X, Y)
+    mids = (grid[:-1] + grid[1:]) / 2
+    nb, block = 1 << 15, 8
+    lo_e, hi_e = (-12, 12) if dtype == torch.float16 else (-60, 60)
+    x0 = np.ldexp(1.0 + rng.random(nb), rng.integers(lo_e, hi_e, nb))
+    x0 = torch.from_numpy(x0).to(dtype).double().numpy()       # a value of the container
+    m = mids[rng.integers(0, mids.size, nb)]
+    s = (x0 / m).astype(np.float32)
+    s = np.where(rng.random(nb) < 0.3, np.nextafter(s, np.float32(np.inf)), s)
+    s = np.where(rng.random(nb) < 0.3, np.nextafter(s, np.float32(0)), s).astype(np.float32)
+    few = rng.random(nb) < 0.2                                   # scales of few bits: exact ties are reachable
+    s = np.where(few, (s.view(np.uint32) & 0xFFF00000).view(np.float32), s)
+    s = np.clip(s, np.float32(2.0 ** -126), np.float32(3.0e38)).astype(np.float32)
+    # the rest of each block: the same boundary approached through other elements
+    x = np.empty((nb, block))
+    for j in range(block):
+        mj = mids[rng.integers(0, mids.size, nb)]
+        x[:, j] = mj * s.astype(np.float64) * np.where(rng.random(nb) < 0.5, 1.0, -1.0)
+    x[:, 0] = x0
+    xt = torch.from_numpy(x.reshape(-1)).to(dtype)
+    xt = torch.where(torch.isfinite(xt.float()), xt, torch.zeros((), dtype=dtype))  # fp16: products past 65504
+    xd = xt.to(DEV)
+    host = synth.bits_numpy(xd)
+    scale_dev = torch.from_numpy(s).to(DEV)
+    want = O.encode_scaled(host, block, X, Y, s, threads=THREADS)
+    got = exmy.encode_scaled(xd, block, X, Y, scale_dev)
+    torch.cuda.synchronize()
+    assert np.array_equal(got.cpu().numpy(), want)
+    got = exmy.emulate_scaled(xd.clone(), block, X, Y, scale_dev)
+    torch.cuda.synchronize()
+    assert np.array_equal(tbits(got), ubits(O.emulate_scaled(host, block, X, Y, s, threads=THREADS)))
+    # the inputs do separate the real quotient from the fp32 one: rounding fl(|x| * fl(1 / s)) without
+    # looking at the residual would give other codes on some of them
+    naive = O.encode(synth.bits_numpy((xt.float().abs() * torch.from_numpy(np.repeat(np.float32(1.0) / s, block))).float()),
+                     X, Y, 127, threads=THREADS)
+    codes = O.unpack(want, xt.numel(), 1 + X + Y) & ((1 << (X + Y)) - 1)
+    assert (O.unpack(naive, xt.numel(), 1 + X + Y) != codes).any()
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float16, torch.float32])
+@pytest.mark.parametrize("bf16_scales", [False, True])
+def test_products_whose_fp32_rounding_is_a_tie_of_the_container(dtype, bf16_scales):
+    """Decoded value = real product value * scale rounded once.  (code, scale) pairs are searched for whose fp32
+    product is inexact and lands half-way between two values of the narrower container, where rounding the
+    fp32 product again would go the other way; they are mixed with random pairs, tiny and huge scales."""
+    X, Y = (3, 3) if dtype != torch.float16 else (3, 5)
+    W = 1 + X + Y
+    rng = np.random.default_rng(77 + int(bf16_scales))
+    grid = grid_of(X, Y)
+    trials = 1 << 23
+    c = rng.integers(1, grid.size, trials)
+    lo_e, hi_e = (-18, 8) if dtype == torch.float16 else (-126, 120)
+    s = np.ldexp(1.0 + rng.random(trials), rng.integers(lo_e, hi_e, trials)).astype(np.float32)
+    if bf16_scales:
+        s = (s.view(np.uint32) & 0xFFFF0000).view(np.float32)
+    exact = grid[c] * s.astype(np.float64)
+    p32 = exact.astype(np.float32)
+    keep = np.zeros(trials, dtype=bool)
+    keep[: 1 << 16] = True
+    if dtype != torch.float32:
+        low = p32.view(np.uint32) & (0x7FFF if dtype == torch.bfloat16 else 0xFFF)
+        keep |= (low == 0) & (p32.astype(np.float64) != exact)
+    c, s = c[keep], s[keep]
+    nb = c.size
+    codes = np.zeros((nb, 8), dtype=np.uint32)
+    codes[:, 0] = c
+    codes[:, 1:] = rng.integers(0, 1 << W, (nb, 7))
+    codes[:, 0] |= rng.integers(0, 2, nb).astype(np.uint32) << (X + Y)
+    packed = O.pack(codes.reshape(-1), W)
+    n = nb * 8
+    if bf16_scales:
+        s16 = (s.view(np.uint32) >> 16).astype(np.uint16)
+        scale_dev = torch.from_numpy(s16.view(np.int16)).view(torch.bfloat16).to(DEV)
+        s_arg = s16
+    else:
+        scale_dev = torch.from_numpy(s).to(DEV)
+        s_arg = s
+    got = exmy.decode_scaled(torch.from_numpy(packed).to(DEV), dtype, n, 8, X, Y, scale_dev)
+    torch.cuda.synchronize()
+    want = O.decode_scaled(packed, odt(got), n, 8, X, Y, s_arg, threads=THREADS)
+    assert np.array_equal(tbits(got), ubits(want))
+    if dtype != torch.float32 and not bf16_scales:
+        twice = torch.from_numpy((grid[c] * s.astype(np.float64)).astype(np.float32)).to(dtype)
+        first = torch.from_numpy(synth.bits_numpy(got).reshape(nb, 8)[:, 0].copy().view(np.int16)).view(dtype)
+        assert (twice.float().abs() != first.float().abs()).any()  # rounding twice would differ somewhere
