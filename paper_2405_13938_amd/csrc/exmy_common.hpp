@@ -595,17 +595,19 @@ __device__ __forceinline__ ScaledSums scaled_sums(uint32_t u, const ScaleOfBlock
 
 // The sum of the real quotient for an element whose two sums differ (for one whose sums agree: that sum).
 // s_mant, s_exp: the scale as s_mant * 2^s_exp with s_mant in [0.5, 1).  All operands of the residual are
-// brought near 1 first, so that it cannot underflow: m * s_mant has at most 46 significant bits above
-// 2^-110, and |x| * 2^-s_exp is exact because it is about as large as that product.
+// brought near 1 first, so that it cannot underflow: m * s_mant has at most 42 significant bits above
+// 2^-105, and |x| * 2^-s_exp is exact because it is about as large as that product.  A residual of zero is an
+// exact tie and goes to the even sum: a term far below any non-zero residual, positive when the lower sum
+// is odd, turns that into the same sign test.
 __device__ __forceinline__ uint32_t settle_scaled_sum(uint32_t u, const ScaledSums& ss, float s_mant, int s_exp,
                                                       const FormatConsts& fc) {
   const float addend = as_f32(ss.te) * fc.magic_scale;
-  const float below = as_f32(ss.lo) - addend;                       // the lower candidate: a grid value, exact
-  const float m = __builtin_fmaf(addend, 0x1p-24f, below);          // + half a quantum: the boundary
+  // lower candidate (the sum minus the addend) + half a quantum (the addend * 2^-24): the boundary, exact
+  const float m = __builtin_fmaf(addend, 0x1p-24f - 1.0f, as_f32(ss.lo));
   const float a = __builtin_ldexpf(__builtin_fabsf(as_f32(u)), -s_exp);
   const float resid = __builtin_fmaf(-m, s_mant, a);                // sign of |x| - m * s, exact
-  const bool up = resid > 0.0f || (resid == 0.0f && (ss.lo & 1u));
-  return up ? ss.hi : ss.lo;
+  const float tie = as_f32((ss.lo << 31) + 0x83800000u);           // -2^-120, or +2^-120 when the lower sum is odd
+  return resid + tie > 0.0f ? ss.hi : ss.lo;
 }
 
 // Left-aligned magnitude code (as magnitude_code_left returns it) from a sum and its te.
@@ -651,20 +653,27 @@ __device__ __forceinline__ bool scaled_product_low_bits_clear(float p) {
 // significant bits and is exact unless it falls among the fp32 denormals.
 template <typename T, int E>
 __device__ __forceinline__ bool scaled_products_suspect(const float (&p)[E], bool short_scale) {
-  uint32_t lowest = 0xFFFFFFFFu;
   if (short_scale) {
+    uint32_t lowest = 0xFFFFFFFFu;
 #pragma unroll
-    for (int j = 0; j < E; ++j) lowest = min(lowest, (as_u32(p[j]) & 0x7FFFFFFFu) - 1u);  // zero wraps to the top
-    return lowest < 0x007FFFFFu;
+    for (int j = 0; j < E; ++j) lowest = min(lowest, (as_u32(p[j]) << 1) - 2u);  // sign dropped; zero wraps to the top
+    return lowest < 0x00FFFFFEu;
   }
+  if constexpr (kIsF16<T>) {
+    uint32_t lowest = 0xFFFFFFFFu;
 #pragma unroll
-  for (int j = 0; j < E; ++j) {
-    if constexpr (kIsF16<T>)
-      lowest = min(lowest, as_u32(p[j]) & 0x00000FFFu);
-    else
-      lowest = min(lowest, (as_u32(p[j]) << 16) + 0x80000000u);  // zero exactly for the pattern ...8000
+    for (int j = 0; j < E; ++j) lowest = min(lowest, as_u32(p[j]) << 20);
+    return lowest == 0;
+  } else {
+    // bf16: the half-way pattern is a lower half of 0x8000, the smallest signed 16-bit number, so a packed
+    // signed minimum over the products' bits finds it (the upper halves ride along unused)
+    uint32_t lowest = 0x7FFF7FFFu;
+#pragma unroll
+    for (int j = 0; j < E; ++j)
+      lowest = __builtin_bit_cast(uint32_t, __builtin_elementwise_min(__builtin_bit_cast(i16x2_t, lowest),
+                                                                      __builtin_bit_cast(i16x2_t, as_u32(p[j]))));
+    return (lowest & 0xFFFFu) == 0x8000u;
   }
-  return lowest == 0;
 }
 
 // p = fl(v * s) moved one ulp towards the real product where it is inexact and `suspect` (its low bits

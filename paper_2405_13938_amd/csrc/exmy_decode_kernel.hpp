@@ -120,6 +120,7 @@ __device__ __forceinline__ uint4 unit_values(const UnitWords<W>& uw, const Forma
       return make_uint4(as_u32(p[0]), as_u32(p[1]), as_u32(p[2]), as_u32(p[3]));
     } else {
       if (__builtin_amdgcn_ballot_w64(scaled_products_suspect<T, E>(p, short_scale)) != 0) {
+        asm volatile("");  // a real branch: the compiler must not settle every product and select
         const float s_mant = __builtin_amdgcn_frexp_mantf(scale);
         const int s_exp = __builtin_amdgcn_frexp_expf(scale);
 #pragma unroll

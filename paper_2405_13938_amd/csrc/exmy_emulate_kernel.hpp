@@ -167,7 +167,8 @@ __device__ __forceinline__ uint4 emulate_vector_scaled(uint4 v, uint32_t scale_b
   const float scale = as_f32(scale_bits);
   float g[E];  // rounded magnitudes, before the scale is put back
   if (f64) {
-    const double scale64 = (double)scale;
+    double scale64 = (double)scale;
+    asm volatile("" : "+v"(scale64));  // pins the fp64 divisions inside this branch (the compiler would run them ahead of it)
 #pragma unroll
     for (int j = 0; j < E; ++j) {
       uint32_t te;
@@ -175,19 +176,17 @@ __device__ __forceinline__ uint4 emulate_vector_scaled(uint4 v, uint32_t scale_b
     }
   } else {
     const ScaleOfBlock sb = scale_of_block(scale_bits);
+    const float s_mant = __builtin_amdgcn_frexp_mantf(scale);
+    const int s_exp = __builtin_amdgcn_frexp_expf(scale);
     ScaledSums ss[E];
-    uint32_t differ = 0;
 #pragma unroll
-    for (int j = 0; j < E; ++j) {
-      ss[j] = scaled_sums(u[j], sb, fc, tc127);
-      differ |= ss[j].lo ^ ss[j].hi;
-    }
-    if (__builtin_amdgcn_ballot_w64(differ != 0) != 0) {
-      const float s_mant = __builtin_amdgcn_frexp_mantf(scale);
-      const int s_exp = __builtin_amdgcn_frexp_expf(scale);
+    for (int j = 0; j < E; ++j) ss[j] = scaled_sums(u[j], sb, fc, tc127);
 #pragma unroll
-      for (int j = 0; j < E; ++j) ss[j].lo = settle_scaled_sum(u[j], ss[j], s_mant, s_exp, fc);
-    }
+    for (int j = 0; j < E; ++j)  // voted per element slot: see encode_group_scaled
+      if (__builtin_amdgcn_ballot_w64(ss[j].lo != ss[j].hi) != 0) {
+        asm volatile("");  // a real branch: the compiler would otherwise settle every slot and select
+        ss[j].lo = settle_scaled_sum(u[j], ss[j], s_mant, s_exp, fc);
+      }
 #pragma unroll
     for (int j = 0; j < E; ++j) g[j] = as_f32(ss[j].lo) - as_f32(ss[j].te) * fc.magic_scale;  // exact
   }
@@ -196,6 +195,7 @@ __device__ __forceinline__ uint4 emulate_vector_scaled(uint4 v, uint32_t scale_b
   for (int j = 0; j < E; ++j) p[j] = g[j] * scale;
   if constexpr (sizeof(T) == 2) {
     if (__builtin_amdgcn_ballot_w64(scaled_products_suspect<T, E>(p, short_scale)) != 0) {
+      asm volatile("");  // a real branch
       const float s_mant = __builtin_amdgcn_frexp_mantf(scale);
       const int s_exp = __builtin_amdgcn_frexp_expf(scale);
 #pragma unroll
@@ -226,7 +226,9 @@ __device__ __forceinline__ uint32_t emulate_scaled_bits(uint32_t u, uint32_t sca
   float g;
   uint32_t te;
   if (f64) {
-    (void)scaled_sum_f64(u, (double)as_f32(scale_bits), fc, tc127, te, g);
+    double scale64 = (double)as_f32(scale_bits);
+    asm volatile("" : "+v"(scale64));  // as in emulate_vector_scaled
+    (void)scaled_sum_f64(u, scale64, fc, tc127, te, g);
   } else {
     const uint32_t sum = scaled_sum_settled(u, scale_bits, fc, tc127, te);
     g = as_f32(sum) - as_f32(te) * fc.magic_scale;

@@ -442,7 +442,8 @@ __device__ __forceinline__ void encode_group_scaled(const uint32_t u[8], uint32_
                                                     uint32_t lane_group, uint32_t tile_group, bool vote = true) {
   uint32_t f[8];
   if (f64) {
-    const double scale64 = (double)as_f32(scale_bits);
+    double scale64 = (double)as_f32(scale_bits);
+    asm volatile("" : "+v"(scale64));  // pins the fp64 divisions inside this branch (the compiler would run them ahead of it)
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
       uint32_t te;
@@ -452,19 +453,20 @@ __device__ __forceinline__ void encode_group_scaled(const uint32_t u[8], uint32_
     }
   } else {
     const ScaleOfBlock sb = scale_of_block(scale_bits);
+    const float s_mant = __builtin_amdgcn_frexp_mantf(sb.scale);
+    const int s_exp = __builtin_amdgcn_frexp_expf(sb.scale);
     ScaledSums ss[8];
-    uint32_t differ = 0;
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      ss[j] = scaled_sums(u[j], sb, fc, tc127);
-      differ |= ss[j].lo ^ ss[j].hi;
-    }
-    if (!vote || __builtin_amdgcn_ballot_w64(differ != 0) != 0) {
-      const float s_mant = __builtin_amdgcn_frexp_mantf(sb.scale);
-      const int s_exp = __builtin_amdgcn_frexp_expf(sb.scale);
+    for (int j = 0; j < 8; ++j) ss[j] = scaled_sums(u[j], sb, fc, tc127);
+    // data of few significant bits (bf16 elements under a scale derived from one of them) puts a few elements
+    // per thousand on or next to a boundary: the vote is taken per element slot, so that a wavefront settles
+    // the slots that hold one (about one in four) and not all eight
 #pragma unroll
-      for (int j = 0; j < 8; ++j) ss[j].lo = settle_scaled_sum(u[j], ss[j], s_mant, s_exp, fc);
-    }
+    for (int j = 0; j < 8; ++j)
+      if (!vote || __builtin_amdgcn_ballot_w64(ss[j].lo != ss[j].hi) != 0) {
+        asm volatile("");  // a real branch: the compiler would otherwise settle every slot and select
+        ss[j].lo = settle_scaled_sum(u[j], ss[j], s_mant, s_exp, fc);
+      }
 #pragma unroll
     for (int j = 0; j < 8; ++j) f[j] = code_left_of_sum(ss[j].lo, ss[j].te, fc, tc127);
   }
