@@ -276,10 +276,12 @@ exmy_status_t exmy_decode_records(const void* src_records, exmy_dtype_t dt_out, 
  * (EXMY_ERR_BLOCK); rows * cols <= EXMY_MAX_ELEMENTS; rows = 0 or cols = 0 is
  * a no-op.  All arrays, max_exp_dev included, are DEVICE memory aligned to 16
  * bytes.  exmy_tile_max_exp writes the metadata under either scheme of Section
- * 2 "Metadata" (Y is used by the "after rounding" scheme only) in two launches
- * on `stream`: it clears the array and then folds partial maxima into it with
- * 32-bit atomic operations, which read the up to 3 bytes between the end of the
- * array and the next 4-byte boundary and write them back unchanged.  Tiles
+ * 2 "Metadata" (Y is used by the "after rounding" scheme only) in up to three
+ * launches on `stream`: it clears the array's whole 4-byte words, folds partial
+ * maxima into them with 32-bit atomic operations, and computes the 1-3 bytes
+ * of a last partial word (a tile count that is not a multiple of 4) one
+ * workgroup per tile with byte stores; no byte outside the exmy_tile_count(...)
+ * bytes of max_exp_dev is read or written.  Tiles
  * that are runs of consecutive elements (tile_cols >= cols, or tile_rows = 1
  * with tile_cols dividing cols) take the kernels of the consecutive-block entry
  * points above. */

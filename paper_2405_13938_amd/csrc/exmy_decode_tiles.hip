@@ -98,15 +98,29 @@ hipError_t launch_max_exp(TileArgs args, hipStream_t stream) {
   geo.tcv = make_block_index(columns ? 1 : args.tile_cols / E);
 
   const uint64_t meta_bytes = geo.tile_rows_n * args.ti.meta_stride;
-  const uint64_t clear_blocks = (meta_bytes / 4 + 255) / 256 + 1;
-  hipLaunchKernelGGL(tiles::clear_bytes_kernel<256>, dim3((uint32_t)(clear_blocks < 4096 ? clear_blocks : 4096)), dim3(256), 0,
-                     stream, args.meta, meta_bytes);
-  if (hipError_t e = hipGetLastError()) return e;
-  const dim3 grid(grid_for_chunks(geo.regions, 1, kMaxBlock)), block(kMaxBlock);
-  if (columns)
-    hipLaunchKernelGGL((tiles::tile_max_exp_kernel<T, kMaxBlock, true>), grid, block, 0, stream, args, geo);
-  else
-    hipLaunchKernelGGL((tiles::tile_max_exp_kernel<T, kMaxBlock, false>), grid, block, 0, stream, args, geo);
+  // the 1-3 bytes of a last partial word are written by a kernel of their own (columns: cols, and with it
+  // the array size, is a multiple of 8)
+  const uint32_t tail_bytes = (uint32_t)(meta_bytes % 4);
+  geo.tail_word = tail_bytes ? meta_bytes / 4 : ~0ull;
+  if (meta_bytes >= 4) {
+    const uint64_t clear_blocks = (meta_bytes / 4 + 255) / 256;
+    hipLaunchKernelGGL(tiles::clear_words_kernel<256>, dim3((uint32_t)(clear_blocks < 4096 ? clear_blocks : 4096)), dim3(256), 0,
+                       stream, args.meta, meta_bytes);
+    if (hipError_t e = hipGetLastError()) return e;
+    const dim3 grid(grid_for_chunks(geo.regions, 1, kMaxBlock)), block(kMaxBlock);
+    if (columns)
+      hipLaunchKernelGGL((tiles::tile_max_exp_kernel<T, kMaxBlock, true>), grid, block, 0, stream, args, geo);
+    else
+      hipLaunchKernelGGL((tiles::tile_max_exp_kernel<T, kMaxBlock, false>), grid, block, 0, stream, args, geo);
+    if (hipError_t e = hipGetLastError()) return e;
+  }
+  if (tail_bytes) {
+    const uint64_t tile_vecs = std::min<uint64_t>(args.tile_cols, args.cols) / E;
+    uint32_t lx_log2 = 0;
+    while (lx_log2 < 8 && (1ull << lx_log2) < tile_vecs) ++lx_log2;
+    hipLaunchKernelGGL((tiles::tile_max_exp_tail_kernel<T, kMaxBlock>), dim3(tail_bytes), dim3(kMaxBlock), 0, stream, args,
+                       meta_bytes - tail_bytes, lx_log2);
+  }
   return hipGetLastError();
 }
 

@@ -324,15 +324,14 @@ __global__ __launch_bounds__(kBlock) void emulate_tiles_kernel(const TileArgs ar
 
 // ---------------------------------------------------------------- maximum exponent
 
-// Clears the `bytes` metadata bytes at p (4-byte aligned) before the maximum kernel
-// folds into them: whole words, then the bytes of a last partial word one by one,
-// so that nothing past the array is written.
+// Clears the whole 4-byte words of the `bytes` metadata bytes at p (4-byte aligned)
+// before the maximum kernel folds into them.  The 1-3 bytes of a last partial word
+// are not touched here: tile_max_exp_tail_kernel writes them.
 template <int kBlock>
-__global__ __launch_bounds__(kBlock) void clear_bytes_kernel(uint8_t* __restrict__ p, uint64_t bytes) {
+__global__ __launch_bounds__(kBlock) void clear_words_kernel(uint8_t* __restrict__ p, uint64_t bytes) {
   const uint64_t words = bytes / 4;
   const uint64_t first = (uint64_t)blockIdx.x * kBlock + threadIdx.x;
   for (uint64_t i = first; i < words; i += (uint64_t)gridDim.x * kBlock) reinterpret_cast<uint32_t*>(p)[i] = 0u;
-  if (first < bytes - words * 4) p[words * 4 + first] = 0;
 }
 
 // Byte-wise maximum of two words.
@@ -372,6 +371,11 @@ struct MaxGeometry {
   uint64_t tile_rows_n;  // tile rows
   uint64_t regions;      // strips * chunks * tile_rows_n
   BlockIndex tcv;        // tile width in vectors (2-D tiles only)
+  // The metadata array is folded into with 32-bit atomic operations.  When its size is not a multiple of 4
+  // the last word would reach past its end, into memory that is not the library's to read or write: the
+  // tiles of those 1-3 bytes are left out here (tail_word = index of that word, else ~0) and computed by
+  // tile_max_exp_tail_kernel, one workgroup per tile, with byte stores.
+  uint64_t tail_word;
 };
 
 // Slots of the workgroup's partial maxima in LDS: one per tile column that the
@@ -485,6 +489,7 @@ __global__ __launch_bounds__(kBlock) void tile_max_exp_kernel(const TileArgs arg
       const uint64_t word_first = t_first / 4;
       const uint32_t n_words = (uint32_t)((t_first + n_slots - 1) / 4 - word_first) + 1u;
       for (uint32_t wd = threadIdx.x; wd < n_words; wd += kBlock) {
+        if (word_first + wd == geo.tail_word) continue;
         uint32_t mine = 0;
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -495,6 +500,53 @@ __global__ __launch_bounds__(kBlock) void tile_max_exp_kernel(const TileArgs arg
       }
     }
     __syncthreads();  // the slots are cleared again by the next region
+  }
+}
+
+// The metadata of the tiles number first_tile + blockIdx.x (row-major over the tiles): one workgroup
+// walks one whole 2-D tile and stores its byte, so no word is shared with anything.  Used for the tiles
+// whose bytes lie in a last partial 4-byte word of the metadata array (see MaxGeometry::tail_word).
+// lanes_x_log2: the workgroup's lanes form rows of 2^lanes_x_log2 lanes along the tile's 16-byte vectors.
+template <typename T, int kBlock>
+__global__ __launch_bounds__(kBlock) void tile_max_exp_tail_kernel(const TileArgs args, uint64_t first_tile,
+                                                                   uint32_t lanes_x_log2) {
+  constexpr int E = 16 / sizeof(T);
+  constexpr int kBatch = 4;  // loads in flight per lane
+  __shared__ int32_t wave_key[kBlock / 64];
+  const u32x4_t* __restrict__ src4 = static_cast<const u32x4_t*>(args.src);
+  const uint64_t tile = first_tile + blockIdx.x;
+  const uint64_t tb = tile / args.tiles_along_row, tc = tile - tb * args.tiles_along_row;
+  const uint64_t row_begin = tb * args.tile_rows, row_end = min(args.rows, row_begin + args.tile_rows);
+  const uint64_t vpr = args.cols / E;
+  const uint64_t cv_begin = tc * (args.tile_cols / E), cv_end = min(vpr, cv_begin + args.tile_cols / E);
+  const uint32_t lanes_x = 1u << lanes_x_log2, lanes_y = kBlock >> lanes_x_log2;
+  const uint32_t lx = threadIdx.x & (lanes_x - 1u), ly = threadIdx.x >> lanes_x_log2;
+  int32_t key = kNoKey;
+  for (uint64_t cv = cv_begin + lx; cv < cv_end; cv += lanes_x) {
+    for (uint64_t row0 = row_begin + ly; row0 < row_end; row0 += (uint64_t)kBatch * lanes_y) {
+      uint4 v[kBatch];
+      bool have[kBatch];
+#pragma unroll
+      for (int s = 0; s < kBatch; ++s) {
+        const uint64_t row = row0 + (uint64_t)s * lanes_y;
+        have[s] = row < row_end;
+        if (have[s]) {
+          const u32x4_t x = __builtin_nontemporal_load(src4 + (row * vpr + cv));
+          v[s] = make_uint4(x.x, x.y, x.z, x.w);
+        }
+      }
+#pragma unroll
+      for (int s = 0; s < kBatch; ++s)
+        if (have[s]) key = max(key, emu::vector_exp_key<T>(v[s]));
+    }
+  }
+  key = max_over_lanes(key, 6);
+  if ((threadIdx.x & 63u) == 0) wave_key[threadIdx.x >> 6] = key;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+#pragma unroll
+    for (int w = 1; w < kBlock / 64; ++w) key = max(key, wave_key[w]);
+    args.meta[tile] = (uint8_t)meta_from_key(key, args.bc);
   }
 }
 

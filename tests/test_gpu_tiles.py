@@ -136,3 +136,25 @@ def test_empty_and_single_tile():
         exmy.tile_max_exp(x, 8, 12, 3)        # tile width neither 1 nor a multiple of 8
     with pytest.raises(exmy.ExmyError):
         exmy.tile_max_exp(x[:, :60].contiguous(), 8, 8, 3)  # cols not a multiple of 8
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("rows,cols,tr,tc", [(40, 40, 8, 8), (37, 24, 37, 8), (100, 16, 10, 8), (300, 56, 128, 8),
+                                            (7, 48, 3, 16), (5000, 24, 5000, 8), (64, 88, 16, 8), (9, 8, 4, 8)])
+def test_tile_max_exp_writes_only_its_own_bytes(dtype, rows, cols, tr, tc):
+    """The metadata array of these shapes is not a multiple of 4 bytes long (5, 3, 10 x 2 ... tiles), or shorter
+    than one word.  It is placed inside a larger buffer of guard bytes, 16-byte aligned as the call asks, with
+    the bytes right behind it checked for being untouched."""
+    x = matrix(rows, cols, dtype, seed=rows + cols)
+    count = exmy.tile_count(rows, cols, tr, tc)
+    want = O.tile_max_exp(synth.bits_numpy(x).reshape(rows, cols), tr, tc, 3)
+    for scheme in (0, 1):
+        if scheme:
+            want = O.tile_max_exp(synth.bits_numpy(x).reshape(rows, cols), tr, tc, 3, 2, True)
+        buf = torch.full((count + 64,), 0xA5, dtype=torch.uint8, device=DEV)
+        out = buf[:count]
+        exmy.tile_max_exp(x, tr, tc, 3, 2, scheme, out=out)
+        torch.cuda.synchronize()
+        got = buf.cpu().numpy()
+        assert np.array_equal(got[:count], want)
+        assert (got[count:] == 0xA5).all(), "bytes behind the metadata array were written"
