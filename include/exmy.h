@@ -256,8 +256,8 @@ exmy_status_t exmy_decode_records(const void* src_records, exmy_dtype_t dt_out, 
                                   void* dst, void* stream);
 
 /* ---------------------------------------------------------------------------
- * Blocks that are columns or 2-D tiles (Section 2 "Block Size": a block can be
- * a tensor, a row, a column, a sub row or a 2-D tile).
+ * Blocks that are columns or 2-D tiles: the block shapes of Section 2 "Block
+ * Size" that are not runs of consecutive elements.
  *
  * src is a row-major matrix of `rows` rows of `cols` elements.  Tile (i, j)
  * covers rows [i * tile_rows, (i + 1) * tile_rows) and columns

@@ -783,8 +783,8 @@ int exmy_oracle_emulate_blocks(void* data, int dt, uint64_t n, uint64_t block, i
 }
 
 // ---------------------------------------------------------------------------
-// Blocks that are columns or 2-D tiles (Section 2 "Block Size": a block can be a
-// tensor, a row, a column, a sub row or a 2-D tile).  src is a row-major
+// Blocks that are columns or 2-D tiles (the block shapes of Section 2 "Block
+// Size" that are not runs of consecutive elements).  src is a row-major
 // (rows, cols) matrix; tile (i, j) covers rows [i*tile_rows, (i+1)*tile_rows) and
 // columns [j*tile_cols, (j+1)*tile_cols), cut off at the matrix edges; its
 // metadatum is byte i * ceil(cols / tile_cols) + j of the metadata array.  A

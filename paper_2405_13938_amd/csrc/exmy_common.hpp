@@ -229,6 +229,10 @@ __device__ __forceinline__ uint32_t as_u32(float f) { return __float_as_uint(f);
 // of the caches' way leaves them to the other stream.
 typedef uint32_t u32x4_t __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2_t __attribute__((ext_vector_type(2)));
+// A 16-byte piece of a plane in memory.  Plane p of a tensor of G groups starts G * lo(p) bytes into the
+// packed form; lo(p) is a sum of wider segments and therefore even, so a piece is known to be 2-byte
+// aligned and no more (global memory takes 16-byte accesses at any alignment).
+typedef u32x4_t plane_piece_t __attribute__((aligned(2)));
 typedef __amdgpu_buffer_rsrc_t rsrc_t;
 
 __device__ __forceinline__ rsrc_t make_rsrc(const void* base) {

@@ -166,7 +166,7 @@ __device__ __forceinline__ void load_image(const uint8_t* __restrict__ src, uint
     const uint32_t c = c0 + threadIdx.x;
     if (kPieces % kBlock == 0 || c < kPieces) {
       const u32x4_t w = __builtin_nontemporal_load(
-          reinterpret_cast<const u32x4_t*>(tile_piece_address<W, kTileGroups>(const_cast<uint8_t*>(src), G, g0, c * 16)));
+          reinterpret_cast<const plane_piece_t*>(tile_piece_address<W, kTileGroups>(const_cast<uint8_t*>(src), G, g0, c * 16)));
       *reinterpret_cast<uint4*>(lds + c * 16) = make_uint4(w.x, w.y, w.z, w.w);
     }
   }

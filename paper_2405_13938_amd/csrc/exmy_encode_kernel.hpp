@@ -188,7 +188,7 @@ __device__ __forceinline__ void copy_stage(const PlaneStage<W, kTileGroups>& st,
     if (kPieces % kBlock == 0 || c < kPieces) {
       const uint4 v = *reinterpret_cast<const uint4*>(st.lds + c * 16);
       const u32x4_t w = {v.x, v.y, v.z, v.w};
-      __builtin_nontemporal_store(w, reinterpret_cast<u32x4_t*>(tile_piece_address<W, kTileGroups>(dst, G, g0, c * 16)));
+      __builtin_nontemporal_store(w, reinterpret_cast<plane_piece_t*>(tile_piece_address<W, kTileGroups>(dst, G, g0, c * 16)));
     }
   }
 }

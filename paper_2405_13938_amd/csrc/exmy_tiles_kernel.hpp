@@ -1,5 +1,5 @@
-// Blocks that are columns or 2-D tiles (Section 2 "Block Size": a block can be a
-// tensor, a row, a column, a sub row or a 2-D tile).
+// Blocks that are columns or 2-D tiles: the block shapes of Section 2 "Block Size"
+// that are not runs of consecutive elements.
 //
 // The matrix is row-major and its codes are packed in its flat memory order, so the
 // conversion kernels are the flat per-block kernels with a different metadata

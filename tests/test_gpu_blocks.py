@@ -242,3 +242,32 @@ def test_encode_blocks_auto_every_width(W):
         want_meta = (O.block_max_exp_after_rounding(host32, block, X, Y) if scheme else O.block_max_exp(host32, block, X))
         assert np.array_equal(meta.cpu().numpy(), want_meta), (block, X, Y)
         assert np.array_equal(packed.cpu().numpy(), O.encode_blocks(host32, block, X, Y, want_meta, threads=THREADS))
+
+
+@pytest.mark.parametrize("dtype", [torch.bfloat16, torch.float32])
+@pytest.mark.parametrize("block", [8, 32, 512, 1024, 4096])
+def test_one_pass_partial_last_tile_runs_as_a_partial_tile(dtype, block):
+    """Regression test of the tile bookkeeping of the one-pass metadata + codes kernels: a compiler-made select
+    on a stale condition code once let the partial last workgroup tile run as a whole one.  Lengths end a few
+    groups into a tile, a few groups short of one, and on a tile boundary, for every tile size in use (64 to
+    1024 groups); outputs sit in guard bytes, so that a tile running past its end is seen as well."""
+    g = torch.Generator().manual_seed(block)
+    base = 6 * 8192
+    x_all = (torch.randn(base + 8192, generator=g) * torch.exp2(torch.randint(-8, 8, (base + 8192,), generator=g).float())).to(dtype).to(DEV)
+    h_all = synth.bits_numpy(x_all)
+    X, Y = 3, 3
+    for tile_groups in (64, 128, 256, 512, 1024):
+        for extra in (8, 8 * 3 + 5, 8 * (tile_groups - 1), 8 * (tile_groups - 1) + 7, 8 * tile_groups, 8 * tile_groups + 1):
+            n = base + extra
+            xd, hd = x_all[:n], h_all[:n]
+            nbytes, nmeta = exmy.packed_bytes(n, X, Y), exmy.block_count(n, block)
+            pbuf = torch.full((nbytes + 256,), 0x5A, dtype=torch.uint8, device=DEV)
+            mbuf = torch.full((nmeta + 256,), 0x5A, dtype=torch.uint8, device=DEV)
+            exmy.encode_blocks_auto(xd, block, X, Y, 0, max_exps=mbuf[:nmeta], out=pbuf[:nbytes])
+            torch.cuda.synchronize()
+            want_meta = O.block_max_exp(hd, block, X)
+            want = O.encode_blocks(hd, block, X, Y, want_meta, threads=THREADS)
+            p, m = pbuf.cpu().numpy(), mbuf.cpu().numpy()
+            assert np.array_equal(m[:nmeta], want_meta), (block, n)
+            assert np.array_equal(p[:nbytes], want), (block, n)
+            assert (p[nbytes:] == 0x5A).all() and (m[nmeta:] == 0x5A).all(), (block, n)

@@ -1,5 +1,5 @@
-"""Pins of the CPU oracle's column / 2-D tile blocks (Section 2 "Block Size": a block can be a tensor, a
-row, a column, a sub row or a 2-D tile).  The tile functions walk (row, column) indices of their own; each
+"""Pins of the CPU oracle's column / 2-D tile blocks (the block shapes of Section 2 "Block Size" that are not
+runs of consecutive elements).  The tile functions walk (row, column) indices of their own; each
 pin reaches the same result through a function that is pinned elsewhere and a numpy reshape / transpose,
 so a wrong tile index, a transposed metadata array or a mishandled edge shows up."""
 import numpy as np
