@@ -253,7 +253,7 @@ def test_one_pass_partial_last_tile_runs_as_a_partial_tile(dtype, block):
     1024 groups); outputs sit in guard bytes, so that a tile running past its end is seen as well."""
     g = torch.Generator().manual_seed(block)
     base = 6 * 8192
-    x_all = (torch.randn(base + 8192, generator=g) * torch.exp2(torch.randint(-8, 8, (base + 8192,), generator=g).float())).to(dtype).to(DEV)
+    x_all = (torch.randn(base + 8200, generator=g) * torch.exp2(torch.randint(-8, 8, (base + 8200,), generator=g).float())).to(dtype).to(DEV)
     h_all = synth.bits_numpy(x_all)
     X, Y = 3, 3
     for tile_groups in (64, 128, 256, 512, 1024):
