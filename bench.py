@@ -280,11 +280,11 @@ def block_scheme_rates(exmy, synth, dev):
 
 def count_launches(wl):
     """Launches that one batched call makes: tensors are walked by size, a launch holds at
-    most 64 of them and is cut when a tensor is more than a quarter smaller than its largest."""
+    most 32 of them and is cut when a tensor is more than a quarter smaller than its largest."""
     sizes = sorted((j[0].numel() for j in wl.jobs if j[0].numel()), reverse=True)
     launches, count, hi = 0, 0, 0
     for n in sizes:
-        if count == 64 or (count and n < hi - hi // 4):
+        if count == 32 or (count and n < hi - hi // 4):
             launches, count = launches + 1, 0
         if count == 0:
             hi = n

@@ -14,7 +14,6 @@ template <>
 struct Shape<uint16_t> {
   static constexpr int kBlock = 128;
   static constexpr int kUnroll = 2;
-  static constexpr int kChunk = 1;
   static constexpr bool kNT = true;
 };
 template <>
@@ -23,7 +22,6 @@ template <>
 struct Shape<float> {
   static constexpr int kBlock = 256;
   static constexpr int kUnroll = 2;
-  static constexpr int kChunk = 1;
   static constexpr bool kNT = true;
 };
 
@@ -36,13 +34,14 @@ struct StagedShape {
 
 template <typename T, int W>
 hipError_t launch_decode(bool x8, const BatchArgs& args, uint64_t n_max, hipStream_t stream) {
+  constexpr uint64_t E = 16 / sizeof(T);  // a unit = one lane's 16 bytes of output
+  const uint64_t units = (n_max + E - 1) / E;  // the elements after the last whole unit included
   if constexpr (W == 3) {
     using S = StagedShape;
     const uint64_t tile_units = (uint64_t)S::kBlock * S::kUnroll;
-    const uint64_t units = n_max / (16 / sizeof(T));
-    const dim3 grid(grid_for_chunks((units + tile_units - 1) / tile_units, 1, S::kBlock), args.count);
-    hipLaunchKernelGGL((dec::decode_kernel<T, W, S::kBlock, S::kUnroll, 1, false, true, true>), grid, dim3(S::kBlock), 0,
-                       stream, args);
+    hipLaunchKernelGGL((dec::decode_kernel<T, W, S::kBlock, S::kUnroll, false, true, true>),
+                       grid_for_flat_tiles((units + tile_units - 1) / tile_units, args.count), dim3(S::kBlock), 0, stream,
+                       args);
     return hipGetLastError();
   }
   using S = Shape<T>;
@@ -50,19 +49,15 @@ hipError_t launch_decode(bool x8, const BatchArgs& args, uint64_t n_max, hipStre
   // bytes of the narrow ones: 512 lanes there (+4-7 % for bf16, +3-5 % for fp32 up to 6 bits; from 8 bits up the
   // larger workgroup measured 1-5 % slower).
   constexpr int kBlock = W <= 7 ? 512 : S::kBlock;
-  const uint64_t tile_units = (uint64_t)kBlock * S::kUnroll;  // a unit = one lane's 16 bytes of output
-  const uint64_t units = n_max / (16 / sizeof(T));
-  const uint64_t tiles = (units + tile_units - 1) / tile_units;
-  const dim3 grid(grid_for_chunks(tiles, S::kChunk, kBlock), args.count);
+  const uint64_t tile_units = (uint64_t)kBlock * S::kUnroll;
+  const dim3 grid = grid_for_flat_tiles((units + tile_units - 1) / tile_units, args.count);
   if constexpr (W >= 9) {  // X = 8 needs at least 9 bits
     if (x8) {
-      hipLaunchKernelGGL((dec::decode_kernel<T, W, kBlock, S::kUnroll, S::kChunk, true, S::kNT>), grid, dim3(kBlock), 0,
-                         stream, args);
+      hipLaunchKernelGGL((dec::decode_kernel<T, W, kBlock, S::kUnroll, true, S::kNT>), grid, dim3(kBlock), 0, stream, args);
       return hipGetLastError();
     }
   }
-  hipLaunchKernelGGL((dec::decode_kernel<T, W, kBlock, S::kUnroll, S::kChunk, false, S::kNT>), grid, dim3(kBlock), 0,
-                     stream, args);
+  hipLaunchKernelGGL((dec::decode_kernel<T, W, kBlock, S::kUnroll, false, S::kNT>), grid, dim3(kBlock), 0, stream, args);
   return hipGetLastError();
 }
 

@@ -250,15 +250,14 @@ __device__ __forceinline__ uint32_t element_bits_slow(const uint8_t* __restrict_
   return b;
 }
 
-// Grid: x = one block per chunk of kChunk tiles of the largest tensor (any
-// smaller x also works), y = tensor of the batch.  Chunks of whole tiles take a
-// straight-line path with the next tile's loads issued ahead; the chunk that
-// holds the end of the tensor takes a guarded loop.
-// kStage: whole tiles read their plane bytes through an LDS image (kChunk must be 1).
-template <typename T, int W, int kBlock, int kUnroll, int kChunk, bool kX8, bool kNT, bool kStage = false>
+// Grid: x (and z, for tensors of more than gridDim.x tiles) = tile, one per workgroup and no loop (see
+// enc::encode_flat_kernel for what the loop-free form saves); y = tensor of the batch.  Workgroups past a
+// tensor's last tile find nothing to do; the workgroup of the tile after the last whole one takes the
+// partial tile and the few elements after the last whole unit.
+// kStage: whole tiles read their plane bytes through an LDS image.
+template <typename T, int W, int kBlock, int kUnroll, bool kX8, bool kNT, bool kStage = false>
 __global__ __launch_bounds__(kBlock) void decode_kernel(const BatchArgs batch) {
   constexpr uint32_t TU = kBlock * kUnroll;
-  static_assert(!kStage || kChunk == 1, "the image holds one tile");
   static_assert(TU % 2 == 0, "a tile must start on a byte of the 1-bit plane");
   static_assert(TU * (16 / sizeof(T)) >= 512, "tile counts must fit 32 bits for n <= 2^40");
   const TensorArgs& ta = batch.t[blockIdx.y];
@@ -271,53 +270,43 @@ __global__ __launch_bounds__(kBlock) void decode_kernel(const BatchArgs batch) {
   const uint64_t G = (n + 7) / 8;
   const uint64_t Ufull = n / E;  // units with all E elements present
   const uint32_t full_tiles = (uint32_t)(Ufull / TU);
-  const uint32_t rem_units = (uint32_t)(Ufull - (uint64_t)full_tiles * TU);
-  const uint32_t tiles = full_tiles + (rem_units ? 1u : 0u);
-  const uint32_t full_chunks = full_tiles / kChunk;
-  const uint32_t chunks = (tiles + kChunk - 1) / kChunk;
   constexpr uint32_t TG = TU * E / 8;  // groups of a tile
   __shared__ __align__(16) uint8_t lds_image[kStage ? TG * W : 16];
+  const uint32_t tile = blockIdx.z * gridDim.x + blockIdx.x;
+  if (tile > full_tiles) return;
+  const uint64_t u0 = (uint64_t)tile * TU;  // first unit of the tile (even)
+  const rsrc_t out = make_rsrc(reinterpret_cast<uint4*>(dst) + u0);
 
-  for (uint32_t chunk = blockIdx.x; chunk < chunks; chunk += gridDim.x) {
-    const uint64_t u0 = (uint64_t)chunk * (kChunk * TU);  // first unit of the chunk (even)
-    PlaneSrc<W> ps;
-    make_plane_src<W, E>(src, G, u0, ps);
-    const rsrc_t out = make_rsrc(reinterpret_cast<uint4*>(dst) + u0);
+  if (tile < full_tiles) {
     if constexpr (kStage) {
-      if (chunk < full_chunks) {
-        load_image<W, TG, kBlock>(src, G, u0 * E / 8, lds_image);
-        __syncthreads();
+      load_image<W, TG, kBlock>(src, G, u0 * E / 8, lds_image);
+      __syncthreads();
 #pragma unroll
-        for (int r = 0; r < kUnroll; ++r) {
-          UnitWords<W> uw;
-          image_unit<W, E, TG>(lds_image, r * kBlock + threadIdx.x, uw);
-          decode_unit<T, W, kX8, kNT>(uw, fc, tc, out, threadIdx.x, r * kBlock);
-        }
-        __syncthreads();  // the image is free for the next tile
-        continue;
-      }
-    }
-    if (chunk < full_chunks) {
-      TileWords<W, kUnroll> tw[2];
-      load_tile<W, E, kBlock, kUnroll, false>(ps, 0, 0, tw[0]);
-#pragma unroll
-      for (int c = 0; c < kChunk; ++c) {
-        if (c + 1 < kChunk) load_tile<W, E, kBlock, kUnroll, false>(ps, (c + 1) * TU, 0, tw[(c + 1) & 1]);
-        decode_tile<T, W, kBlock, kUnroll, kX8, kNT, false>(tw[c & 1], out, c * TU, 0, fc, tc);
+      for (int r = 0; r < kUnroll; ++r) {
+        UnitWords<W> uw;
+        image_unit<W, E, TG>(lds_image, r * kBlock + threadIdx.x, uw);
+        decode_unit<T, W, kX8, kNT>(uw, fc, tc, out, threadIdx.x, r * kBlock);
       }
     } else {
-      for (uint32_t tile = chunk * kChunk; tile < tiles; ++tile) {
-        const uint32_t tile_unit = (tile - chunk * kChunk) * TU;
-        const uint32_t rem = tile < full_tiles ? TU : rem_units;
-        TileWords<W, kUnroll> tw;
-        load_tile<W, E, kBlock, kUnroll, true>(ps, tile_unit, rem, tw);
-        decode_tile<T, W, kBlock, kUnroll, kX8, kNT, true>(tw, out, tile_unit, rem, fc, tc);
-      }
+      PlaneSrc<W> ps;
+      make_plane_src<W, E>(src, G, u0, ps);
+      TileWords<W, kUnroll> tw;
+      load_tile<W, E, kBlock, kUnroll, false>(ps, 0, 0, tw);
+      decode_tile<T, W, kBlock, kUnroll, kX8, kNT, false>(tw, out, 0, 0, fc, tc);
     }
+    return;
   }
 
+  const uint32_t rem_units = (uint32_t)(Ufull - (uint64_t)full_tiles * TU);
+  if (rem_units) {
+    PlaneSrc<W> ps;
+    make_plane_src<W, E>(src, G, u0, ps);
+    TileWords<W, kUnroll> tw;
+    load_tile<W, E, kBlock, kUnroll, true>(ps, 0, rem_units, tw);
+    decode_tile<T, W, kBlock, kUnroll, kX8, kNT, true>(tw, out, 0, rem_units, fc, tc);
+  }
   // The n % E elements after the last whole unit, one lane each.
-  if (blockIdx.x == 0 && threadIdx.x < E) {
+  if (threadIdx.x < E) {
     const uint64_t i = Ufull * E + threadIdx.x;
     if (i < n) {
       const uint32_t b = element_bits_slow<W, kX8>(src, G, i, fc, tc);

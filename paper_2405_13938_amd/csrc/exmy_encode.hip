@@ -35,11 +35,19 @@ template <typename T, int W, bool kWide, bool kHist>
 hipError_t launch_encode(const BatchArgs& args, uint64_t n_max, hipStream_t stream) {
   using S = Shape<T, kHist>;
   const uint64_t tile_groups = (uint64_t)S::kBlock * S::kUnroll;
-  const uint64_t tiles = (n_max / 8 + tile_groups - 1) / tile_groups;
-  const dim3 grid(grid_for_chunks(tiles, S::kChunk, S::kBlock), args.count);
-  hipLaunchKernelGGL((enc::encode_kernel<T, W, S::kBlock, S::kUnroll, S::kChunk, kWide, kHist, S::kNT>), grid,
-                     dim3(S::kBlock), 0, stream, args);
-  return hipGetLastError();
+  if constexpr (!kHist) {  // one tile per workgroup: the loop-free kernel
+    static_assert(S::kChunk == 1, "the flat kernel takes one tile per workgroup");
+    const uint64_t tiles = ((n_max + 7) / 8 + tile_groups - 1) / tile_groups;  // the ragged last group included
+    hipLaunchKernelGGL((enc::encode_flat_kernel<T, W, S::kBlock, S::kUnroll, kWide, S::kNT>),
+                       grid_for_flat_tiles(tiles, args.count), dim3(S::kBlock), 0, stream, args);
+    return hipGetLastError();
+  } else {
+    const uint64_t tiles = (n_max / 8 + tile_groups - 1) / tile_groups;
+    const dim3 grid(grid_for_chunks(tiles, S::kChunk, S::kBlock), args.count);
+    hipLaunchKernelGGL((enc::encode_kernel<T, W, S::kBlock, S::kUnroll, S::kChunk, kWide, kHist, S::kNT>), grid,
+                       dim3(S::kBlock), 0, stream, args);
+    return hipGetLastError();
+  }
 }
 
 template <typename T, bool kWide, bool kHist>

@@ -308,6 +308,23 @@ __device__ __forceinline__ void encode_tile(const TileRegs<T, kUnroll>& regs, co
   }
 }
 
+// The group's 8 elements in fp32 position: a 16-byte group from registers, or, for
+// the ragged last group of the tensor, its elements one by one (zeros beyond n).
+template <typename T>
+__device__ __forceinline__ void ragged_group_bits(const void* src_v, uint64_t first, uint64_t n, uint32_t u[8]) {
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    const uint64_t i = first + j;
+    u[j] = 0;
+    if (i < n) {
+      if constexpr (sizeof(T) == 4)
+        u[j] = static_cast<const uint32_t*>(src_v)[i];
+      else
+        u[j] = elem_bits<T>(static_cast<const uint16_t*>(src_v)[i]);
+    }
+  }
+}
+
 // Grid: x = one block per chunk of kChunk tiles of the largest tensor (any
 // smaller x also works: blocks then stride over the chunks), y = tensor of the
 // batch.  Blocks past the end of a smaller tensor find nothing to do.
@@ -400,6 +417,61 @@ __global__ __launch_bounds__(kBlock) void encode_kernel(const BatchArgs batch) {
   }
 
   if constexpr (kHist) flush_bins<kBlock>(lds_hist, hist);
+}
+
+// The same conversion with one tile per workgroup and no loop: grid x (and z, for tensors of more than
+// gridDim.x tiles) = tile, y = tensor of the batch.  This is the form the plain encoder is launched in: a
+// kernel whose chunk loop runs once still carries the loop's bookkeeping (register copies for the values
+// the loop would carry, address set-up outside it), 10 % of this kernel's vector instructions, and the
+// bf16 encoder at 7 bits is within reach of the vector ALU limit (+2-3 % throughput without them).
+// Workgroups past a tensor's last tile find nothing to do; the workgroup of the tile after the last whole
+// one takes the partial tile and the ragged last group.
+template <typename T, int W, int kBlock, int kUnroll, bool kWide, bool kNT>
+__global__ __launch_bounds__(kBlock) void encode_flat_kernel(const BatchArgs batch) {
+  constexpr uint32_t TG = kBlock * kUnroll;
+  constexpr int kLoads = TileRegs<T, kUnroll>::kLoads;
+  static_assert(TG >= 64, "tile counts must fit 32 bits for n <= 2^40");
+  const TensorArgs& ta = batch.t[blockIdx.y];
+  const uint4* __restrict__ src4 = static_cast<const uint4*>(ta.src);
+  uint8_t* __restrict__ dst = static_cast<uint8_t*>(ta.dst);
+  const uint64_t n = ta.n;
+  const FormatConsts fc = batch.fc;
+  const TensorConsts tc = ta.tc;
+  const uint64_t G = (n + 7) / 8;  // groups, the last one possibly ragged
+  const uint64_t Gfull = n / 8;    // groups with all 8 elements present
+  const uint32_t full_tiles = (uint32_t)(Gfull / TG);
+  const uint32_t tile = blockIdx.z * gridDim.x + blockIdx.x;
+  const uint64_t g0 = (uint64_t)tile * TG;
+  const rsrc_t src = make_rsrc(src4 + g0 * kLoads);
+  __shared__ __align__(16) uint8_t lds_stage[TG * W];
+  const PlaneStage<W, TG> stage{lds_stage};
+
+  if (tile < full_tiles) {
+    TileRegs<T, kUnroll> regs;
+    load_tile<T, kBlock, kUnroll, kNT, false>(src, 0, 0, regs);
+    encode_tile<T, W, kBlock, kUnroll, kWide, false, false>(regs, stage, 0, 0, fc, tc, nullptr);
+    __syncthreads();  // every lane has put its words
+    copy_stage<W, TG, kBlock>(stage, dst, G, g0);
+    return;
+  }
+  if (tile > full_tiles) return;
+
+  const uint32_t rem_groups = (uint32_t)(Gfull - (uint64_t)full_tiles * TG);  // groups of the partial tile
+  if (rem_groups) {
+    PlaneDst<W> pd;
+    make_plane_dst<W>(dst, G, g0, pd);
+    TileRegs<T, kUnroll> regs;
+    load_tile<T, kBlock, kUnroll, kNT, true>(src, 0, rem_groups, regs);
+    encode_tile<T, W, kBlock, kUnroll, kWide, false, true>(regs, pd, 0, rem_groups, fc, tc, nullptr);
+  }
+  // Ragged last group: one lane reads the n % 8 elements one by one and pads with +0, which encodes to code 0.
+  if (Gfull != G && threadIdx.x == 0) {
+    uint32_t u[8];
+    ragged_group_bits<T>(ta.src, Gfull * 8, n, u);
+    PlaneDst<W> pd;
+    make_plane_dst<W>(dst, G, Gfull, pd);
+    encode_group<W, kWide>(u, fc, tc, pd, 0, 0);
+  }
 }
 
 // ---------------------------------------------------------------------------
@@ -573,23 +645,6 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
 // Metadata and codes in one pass over the source (Section 2.2.1: the encoded
 // tensor is the codes plus the per-block maximum exponents): the elements stay in
 // registers between the block maximum and the conversion.
-
-// The group's 8 elements in fp32 position: a 16-byte group from registers, or, for
-// the ragged last group of the tensor, its elements one by one (zeros beyond n).
-template <typename T>
-__device__ __forceinline__ void ragged_group_bits(const void* src_v, uint64_t first, uint64_t n, uint32_t u[8]) {
-#pragma unroll
-  for (int j = 0; j < 8; ++j) {
-    const uint64_t i = first + j;
-    u[j] = 0;
-    if (i < n) {
-      if constexpr (sizeof(T) == 4)
-        u[j] = static_cast<const uint32_t*>(src_v)[i];
-      else
-        u[j] = elem_bits<T>(static_cast<const uint16_t*>(src_v)[i]);
-    }
-  }
-}
 
 __device__ __forceinline__ int32_t group_key(const uint32_t u[8]) {
   int32_t k = kNoKey;

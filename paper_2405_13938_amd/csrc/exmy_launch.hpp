@@ -29,6 +29,16 @@ inline uint32_t grid_for_chunks(uint64_t tiles, int chunk, int block_size) {
   return (uint32_t)(g ? g : 1);
 }
 
+// Grid of the kernels that take one tile per workgroup without a loop: tile = blockIdx.z * gridDim.x +
+// blockIdx.x, tensor = blockIdx.y.  x stops at 2^20 workgroups, so that tensors of more than 2^30 elements
+// (which the large-tensor tests reach) already use z.
+constexpr uint64_t kFlatGridX = 1ull << 20;
+inline dim3 grid_for_flat_tiles(uint64_t tiles, uint32_t tensors) {
+  if (tiles == 0) tiles = 1;
+  const uint64_t x = tiles < kFlatGridX ? tiles : kFlatGridX;
+  return dim3((uint32_t)x, tensors, (uint32_t)((tiles + x - 1) / x));
+}
+
 // `n_max` is the largest element count among the batch's tensors (sizes the grid).
 hipError_t encode_dispatch(exmy_dtype_t dt, int W, bool wide, bool with_hist, const BatchArgs& args, uint64_t n_max,
                            hipStream_t stream);
