@@ -24,7 +24,7 @@ __global__ __launch_bounds__(kBlock) void codes32_kernel(const BatchArgs batch) 
   const uint64_t V = n / 4;  // whole vectors of input
   const uint32_t tiles = (uint32_t)((V + TV - 1) / TV);
   const uint32_t lane_off = threadIdx.x * 16;
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (uint32_t tile = flat_tile(), once = 1; once && tile < tiles; once = 0) {
     const uint64_t v0 = (uint64_t)tile * TV;
     const rsrc_t in = make_rsrc(static_cast<const uint4*>(ta.src) + v0);
     const rsrc_t out = make_rsrc(static_cast<uint4*>(ta.dst) + v0);
@@ -42,7 +42,7 @@ __global__ __launch_bounds__(kBlock) void codes32_kernel(const BatchArgs batch) 
   }
   // The words after the last whole vector: the rest of the tensor and, for encode, the zero codes that
   // complete the last group.
-  if (blockIdx.x == 0 && threadIdx.x < 8) {
+  if (flat_tile() == 0 && threadIdx.x < 8) {
     const uint64_t i = V * 4 + threadIdx.x;
     const uint64_t end = kDecode ? n : (n + 7) / 8 * 8;
     if (i < end) static_cast<uint32_t*>(ta.dst)[i] = i < n ? finite_code(static_cast<const uint32_t*>(ta.src)[i]) : 0u;
@@ -56,7 +56,7 @@ constexpr int kUnroll = 2;
 
 hipError_t codes32_dispatch(bool decode, const BatchArgs& args, uint64_t n_max, hipStream_t stream) {
   const uint64_t tiles = (n_max / 4 + kBlock * kUnroll - 1) / (kBlock * kUnroll);
-  const dim3 grid(grid_for_chunks(tiles, 1, kBlock), args.count);
+  const dim3 grid = grid_for_flat_tiles(tiles, args.count);
   if (decode)
     hipLaunchKernelGGL((codes32_kernel<kBlock, kUnroll, true>), grid, dim3(kBlock), 0, stream, args);
   else

@@ -357,7 +357,7 @@ __global__ __launch_bounds__(kBlock) void decode_blocks_kernel(const BlockArgs a
   // less arithmetic per byte) lost 6 % to the second copy of its code
   const bool try_uniform = sizeof(T) == 2 && bi.size >= 4;
 
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (uint32_t tile = flat_tile(), once = 1; once && tile < tiles; once = 0) {
     const uint64_t u0 = (uint64_t)tile * TU;  // even
     uint64_t blk0;
     uint32_t off;
@@ -402,7 +402,7 @@ __global__ __launch_bounds__(kBlock) void decode_blocks_kernel(const BlockArgs a
   }
 
   // The n % E elements after the last whole unit belong to the last block.
-  if (blockIdx.x == 0 && threadIdx.x < E) {
+  if (flat_tile() == 0 && threadIdx.x < E) {
     const uint64_t i = Ufull * E + threadIdx.x;
     if (i < n) {
       uint32_t b;

@@ -30,7 +30,7 @@ hipError_t launch(TileArgs args, hipStream_t stream) {
   const uint64_t tile_units = (uint64_t)S::kBlock * S::kUnroll;
   const uint64_t tiles = (args.rows * args.cols / E + tile_units - 1) / tile_units;
   args.ti = make_tile_index(args, E);
-  const dim3 grid(grid_for_chunks(tiles, 1, S::kBlock)), block(S::kBlock);
+  const dim3 grid = grid_for_flat_tiles(tiles, 1), block(S::kBlock);
   if (args.tile_cols == 1)
     hipLaunchKernelGGL((tiles::decode_tiles_kernel<T, W, S::kBlock, S::kUnroll, true, true>), grid, block, 0, stream, args);
   else
@@ -60,7 +60,7 @@ hipError_t launch_emulate(TileArgs args, bool wide_format, hipStream_t stream) {
   const uint64_t tile_vecs = (uint64_t)kEmuBlock * kEmuUnroll;
   const uint64_t tiles = (args.rows * args.cols / E + tile_vecs - 1) / tile_vecs;
   args.ti = make_tile_index(args, E);
-  const dim3 grid(grid_for_chunks(tiles, 1, kEmuBlock)), block(kEmuBlock);
+  const dim3 grid = grid_for_flat_tiles(tiles, 1), block(kEmuBlock);
   if (args.tile_cols == 1)
     hipLaunchKernelGGL((tiles::emulate_tiles_kernel<T, kEmuBlock, kEmuUnroll, true, true>), grid, block, 0, stream, args, wide_format);
   else

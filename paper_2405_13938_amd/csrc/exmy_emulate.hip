@@ -17,8 +17,8 @@ hipError_t launch_emulate(void* data, uint64_t n, const FormatConsts& fc, const 
   constexpr int kPer = 16 / sizeof(T);
   const uint64_t tile_vecs = (uint64_t)kBlock * kUnroll;
   const uint64_t tiles = (n / kPer + tile_vecs - 1) / tile_vecs;
-  const uint32_t grid = grid_for_chunks(tiles, 1, kBlock);
-  hipLaunchKernelGGL((emu::emulate_kernel<T, kBlock, kUnroll, kWide, kNT>), dim3(grid), dim3(kBlock), 0, stream,
+  const dim3 grid = grid_for_flat_tiles(tiles, 1);
+  hipLaunchKernelGGL((emu::emulate_kernel<T, kBlock, kUnroll, kWide, kNT>), grid, dim3(kBlock), 0, stream,
                      static_cast<T*>(data), n, fc, tc);
   return hipGetLastError();
 }

@@ -16,7 +16,7 @@ hipError_t launch_emulate(BlockArgs args, bool wide_format, hipStream_t stream) 
   const uint64_t tile_vecs = (uint64_t)kBlock * kUnroll;
   const uint64_t tiles = (args.n / (16 / sizeof(T)) + tile_vecs - 1) / tile_vecs;
   args.bi = make_block_index(args.block_groups * kVecsPerGroup);
-  hipLaunchKernelGGL((emu::emulate_blocks_kernel<T, kBlock, kUnroll, true, kScaled>), dim3(grid_for_chunks(tiles, 1, kBlock)),
+  hipLaunchKernelGGL((emu::emulate_blocks_kernel<T, kBlock, kUnroll, true, kScaled>), grid_for_flat_tiles(tiles, 1),
                      dim3(kBlock), 0, stream, args, wide_format);
   return hipGetLastError();
 }
@@ -37,7 +37,7 @@ hipError_t launch_max_exp(BlockArgs args, hipStream_t stream) {
     const uint64_t vecs = (args.n + kPer - 1) / kPer;
     const uint64_t tile_vecs = (uint64_t)kMaxBlock * kMaxUnroll;
     hipLaunchKernelGGL((emu::block_max_exp_small_kernel<T, kMaxBlock, kMaxUnroll, kScale>),
-                       dim3(grid_for_chunks((vecs + tile_vecs - 1) / tile_vecs, 1, kMaxBlock)), dim3(kMaxBlock), 0,
+                       grid_for_flat_tiles((vecs + tile_vecs - 1) / tile_vecs, 1), dim3(kMaxBlock), 0,
                        stream, args);
   } else if (args.bi.size <= kWaveRowVecs) {
     constexpr int kTeams = kMaxBlock / 64;

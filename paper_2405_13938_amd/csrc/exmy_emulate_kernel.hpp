@@ -92,7 +92,7 @@ __global__ __launch_bounds__(kBlock) void emulate_kernel(T* __restrict__ data, u
   const uint32_t tiles = full_tiles + (rem ? 1u : 0u);
   const uint32_t lane_off = threadIdx.x * 16;
 
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (uint32_t tile = flat_tile(), once = 1; once && tile < tiles; once = 0) {
     const rsrc_t buf = make_rsrc(reinterpret_cast<uint4*>(data) + (uint64_t)tile * TV);
     uint4 v[kUnroll];
     if (tile < full_tiles) {
@@ -112,7 +112,7 @@ __global__ __launch_bounds__(kBlock) void emulate_kernel(T* __restrict__ data, u
   }
 
   // Elements past the last whole 16-byte vector.
-  if (blockIdx.x == 0 && threadIdx.x < kPer) {
+  if (flat_tile() == 0 && threadIdx.x < kPer) {
     const uint64_t i = V * kPer + threadIdx.x;
     if (i < n) {
       if constexpr (sizeof(T) == 4) {
@@ -254,7 +254,7 @@ __global__ __launch_bounds__(kBlock) void emulate_blocks_kernel(const BlockArgs 
   const uint32_t tiles = (uint32_t)((V + TV - 1) / TV);
   const bool try_uniform = bi.size >= 4;  // at most 16 blocks per wavefront
 
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (uint32_t tile = flat_tile(), once = 1; once && tile < tiles; once = 0) {
     const uint64_t v0 = (uint64_t)tile * TV;
     uint64_t blk0;
     uint32_t off;
@@ -285,7 +285,7 @@ __global__ __launch_bounds__(kBlock) void emulate_blocks_kernel(const BlockArgs 
   }
 
   // Elements past the last whole 16-byte vector belong to the last block.
-  if (blockIdx.x == 0 && threadIdx.x < kPer) {
+  if (flat_tile() == 0 && threadIdx.x < kPer) {
     const uint64_t i = V * kPer + threadIdx.x;
     if (i < n) {
       uint32_t u;
@@ -381,7 +381,7 @@ __global__ __launch_bounds__(kBlock) void block_max_exp_small_kernel(const Block
   const uint64_t V = n / kPer;                  // whole vectors
   const uint64_t Vall = (n + kPer - 1) / kPer;  // the last one may be partial
   const uint32_t tiles = (uint32_t)((Vall + TV - 1) / TV);
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (uint32_t tile = flat_tile(), once = 1; once && tile < tiles; once = 0) {
     const uint64_t v0 = (uint64_t)tile * TV;
     const rsrc_t buf = make_rsrc(src4 + v0);
     const uint64_t whole = V - (v0 < V ? v0 : V);  // whole vectors from v0 on

@@ -43,7 +43,7 @@ hipError_t launch(BlockArgs args, hipStream_t stream) {
     const uint64_t tile = (uint64_t)S::kBlock * S::kUnroll;
     const uint64_t tiles = ((args.n + 7) / 8 + tile - 1) / tile;
     hipLaunchKernelGGL((enc::encode_blocks_auto_small_kernel<T, W, S::kBlock, S::kUnroll, true>),
-                       dim3(grid_for_chunks(tiles, 1, S::kBlock)), dim3(S::kBlock), 0, stream, args);
+                       grid_for_flat_tiles(tiles, 1), dim3(S::kBlock), 0, stream, args);
     return hipGetLastError();
   }
   const uint64_t loads = (uint64_t)args.block_groups * kGroupLoads;  // 16-byte loads per block

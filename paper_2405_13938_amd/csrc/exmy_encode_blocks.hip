@@ -29,7 +29,7 @@ hipError_t launch(BlockArgs args, hipStream_t stream) {
   const uint64_t tiles = (args.n / 8 + tile_groups - 1) / tile_groups;
   args.bi = make_block_index(args.block_groups);
   hipLaunchKernelGGL((enc::encode_blocks_kernel<T, W, S::kBlock, S::kUnroll, true, kScaled>),
-                     dim3(grid_for_chunks(tiles, 1, S::kBlock)), dim3(S::kBlock), 0, stream, args);
+                     grid_for_flat_tiles(tiles, 1), dim3(S::kBlock), 0, stream, args);
   return hipGetLastError();
 }
 

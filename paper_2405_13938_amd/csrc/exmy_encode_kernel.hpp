@@ -570,7 +570,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
   const PlaneStage<W, TG> stage{lds_stage};
   const bool try_uniform = bi.size >= 4;  // at most 16 blocks per wavefront
 
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (uint32_t tile = flat_tile(), once = 1; once && tile < tiles; once = 0) {
     const uint64_t g0 = (uint64_t)tile * TG;
     uint64_t blk0;
     uint32_t off;
@@ -618,7 +618,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_kernel(const BlockArgs a
   }
 
   // Ragged last group: it belongs to the last block.
-  if (Gfull != G && blockIdx.x == 0 && threadIdx.x == 0) {
+  if (Gfull != G && flat_tile() == 0 && threadIdx.x == 0) {
     const T* __restrict__ src = static_cast<const T*>(args.src);
     uint32_t u[8];
 #pragma unroll
@@ -685,7 +685,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_small_kernel(const 
   uint8_t* const lds_meta = lds_stage + TG * W;
   const bool meta_words = (reinterpret_cast<uintptr_t>(args.meta) & 3u) == 0 && (TG >> lg) >= 4;
 
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (uint32_t tile = flat_tile(), once = 1; once && tile < tiles; once = 0) {
     const uint64_t g0 = (uint64_t)tile * TG;
     const rsrc_t src = make_rsrc(src4 + g0 * kLoads);
     const uint32_t whole = units_in_tile(tile, full_tiles, rem_whole, TG);  // groups of this tile with all 8 elements

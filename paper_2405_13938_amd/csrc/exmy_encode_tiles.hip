@@ -40,7 +40,7 @@ hipError_t launch(TileArgs args, hipStream_t stream) {
   const uint64_t tile_groups = (uint64_t)S::kBlock * S::kUnroll;
   const uint64_t tiles = (args.rows * args.cols / 8 + tile_groups - 1) / tile_groups;
   args.ti = make_tile_index(args, 8);
-  const dim3 grid(grid_for_chunks(tiles, 1, S::kBlock)), block(S::kBlock);
+  const dim3 grid = grid_for_flat_tiles(tiles, 1), block(S::kBlock);
   if (args.tile_cols == 1)
     hipLaunchKernelGGL((tiles::encode_tiles_kernel<T, W, S::kBlock, S::kUnroll, true, true>), grid, block, 0, stream, args);
   else

@@ -27,7 +27,7 @@ hipError_t launch_encode(const void* src, void* dst, uint64_t n, const IntConsts
   const uint64_t tile = (uint64_t)S::kEncBlock * S::kEncUnroll;
   const uint64_t tiles = (n / 8 + tile - 1) / tile;
   hipLaunchKernelGGL((twos::encode_int_kernel<T, W, S::kEncBlock, S::kEncUnroll>),
-                     dim3(grid_for_chunks(tiles, 1, S::kEncBlock)), dim3(S::kEncBlock), 0, stream, src, dst, n, ic);
+                     grid_for_flat_tiles(tiles, 1), dim3(S::kEncBlock), 0, stream, src, dst, n, ic);
   return hipGetLastError();
 }
 
@@ -37,7 +37,7 @@ hipError_t launch_decode(const void* src, void* dst, uint64_t n, const IntConsts
   const uint64_t tile = (uint64_t)S::kDecBlock * S::kDecUnroll;
   const uint64_t tiles = (n / (16 / sizeof(T)) + tile - 1) / tile;
   hipLaunchKernelGGL((twos::decode_int_kernel<T, W, S::kDecBlock, S::kDecUnroll>),
-                     dim3(grid_for_chunks(tiles, 1, S::kDecBlock)), dim3(S::kDecBlock), 0, stream, src, dst, n, ic);
+                     grid_for_flat_tiles(tiles, 1), dim3(S::kDecBlock), 0, stream, src, dst, n, ic);
   return hipGetLastError();
 }
 
@@ -57,7 +57,7 @@ hipError_t dispatch_w(int W, const void* src, void* dst, uint64_t n, const IntCo
 template <typename T>
 hipError_t launch_emulate(void* data, uint64_t n, const IntConsts& ic, hipStream_t stream) {
   const uint64_t tiles = (n / (16 / sizeof(T)) + kEmuBlock - 1) / kEmuBlock;
-  hipLaunchKernelGGL((twos::emulate_int_kernel<T, kEmuBlock>), dim3(grid_for_chunks(tiles, 1, kEmuBlock)),
+  hipLaunchKernelGGL((twos::emulate_int_kernel<T, kEmuBlock>), grid_for_flat_tiles(tiles, 1),
                      dim3(kEmuBlock), 0, stream, data, n, ic);
   return hipGetLastError();
 }

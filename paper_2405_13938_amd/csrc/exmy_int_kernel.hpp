@@ -70,7 +70,7 @@ __global__ __launch_bounds__(kBlock) void encode_int_kernel(const void* src_v, v
   __shared__ __align__(16) uint8_t lds_stage[TG * W];
   const enc::PlaneStage<W, TG> stage{lds_stage};
 
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (uint32_t tile = flat_tile(), once = 1; once && tile < tiles; once = 0) {
     const uint64_t g0 = (uint64_t)tile * TG;
     const rsrc_t src = make_rsrc(src4 + g0 * kLoads);
     enc::TileRegs<T, kUnroll> regs;
@@ -100,7 +100,7 @@ __global__ __launch_bounds__(kBlock) void encode_int_kernel(const void* src_v, v
   }
 
   // Ragged last group, padded with +0 (code 0).
-  if (Gfull != G && blockIdx.x == 0 && threadIdx.x == 0) {
+  if (Gfull != G && flat_tile() == 0 && threadIdx.x == 0) {
     const T* __restrict__ src = static_cast<const T*>(src_v);
     uint32_t u[8];
 #pragma unroll
@@ -167,7 +167,7 @@ __global__ __launch_bounds__(kBlock) void decode_int_kernel(const void* src_v, v
   const uint32_t rem_units = (uint32_t)(Ufull - (uint64_t)full_tiles * TU);
   const uint32_t tiles = full_tiles + (rem_units ? 1u : 0u);
 
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (uint32_t tile = flat_tile(), once = 1; once && tile < tiles; once = 0) {
     const uint64_t u0 = (uint64_t)tile * TU;
     dec::PlaneSrc<W> ps;
     dec::make_plane_src<W, E>(src, G, u0, ps);
@@ -181,7 +181,7 @@ __global__ __launch_bounds__(kBlock) void decode_int_kernel(const void* src_v, v
   }
 
   // The n % E elements after the last whole unit, one lane each.
-  if (blockIdx.x == 0 && threadIdx.x < E) {
+  if (flat_tile() == 0 && threadIdx.x < E) {
     const uint64_t i = Ufull * E + threadIdx.x;
     if (i < n) {
       dec::PlaneSrc<W> ps;
@@ -216,7 +216,7 @@ __global__ __launch_bounds__(kBlock) void emulate_int_kernel(void* data_v, uint6
   T* __restrict__ data = static_cast<T*>(data_v);
   const uint64_t V = n / kPer;
   const uint32_t tiles = (uint32_t)((V + kBlock - 1) / kBlock);
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (uint32_t tile = flat_tile(), once = 1; once && tile < tiles; once = 0) {
     const uint64_t v0 = (uint64_t)tile * kBlock;
     if (v0 + threadIdx.x >= V) continue;
     const rsrc_t buf = make_rsrc(reinterpret_cast<uint4*>(data) + v0);
@@ -235,7 +235,7 @@ __global__ __launch_bounds__(kBlock) void emulate_int_kernel(void* data_v, uint6
     }
     store16<true>(buf, threadIdx.x * 16, 0, make_uint4(w[0], w[1], w[2], w[3]));
   }
-  if (blockIdx.x == 0 && threadIdx.x < kPer) {
+  if (flat_tile() == 0 && threadIdx.x < kPer) {
     const uint64_t i = V * kPer + threadIdx.x;
     if (i < n) {
       if constexpr (sizeof(T) == 4) {

@@ -18,7 +18,7 @@ hipError_t launch(bool decode, bool flag, const void* src, void* dst, uint64_t n
   using S = Shape<T>;
   const uint64_t tile_groups = (uint64_t)S::kBlock * S::kUnroll;
   const uint64_t tiles = ((n + 7) / 8 + tile_groups - 1) / tile_groups;
-  const dim3 grid(grid_for_chunks(tiles, 1, S::kBlock)), block(S::kBlock);
+  const dim3 grid = grid_for_flat_tiles(tiles, 1), block(S::kBlock);
   if (decode) {  // flag: X = 8
     const uint8_t* s = static_cast<const uint8_t*>(src);
     T* d = static_cast<T*>(dst);

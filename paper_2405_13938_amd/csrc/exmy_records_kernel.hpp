@@ -91,7 +91,7 @@ __global__ __launch_bounds__(kBlock) void encode_records_kernel(const void* __re
   const uint32_t all_tiles = (uint32_t)(G / TG), full_tiles = (uint32_t)(Gfull / TG);
   const uint32_t rem_all = (uint32_t)(G - (uint64_t)all_tiles * TG), rem_whole = (uint32_t)(Gfull - (uint64_t)full_tiles * TG);
 
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (uint32_t tile = flat_tile(), once = 1; once && tile < tiles; once = 0) {
     const uint64_t g0 = (uint64_t)tile * TG;
     const uint32_t here = units_in_tile(tile, all_tiles, rem_all, TG);        // groups of this tile
     const uint32_t whole = units_in_tile(tile, full_tiles, rem_whole, TG);   // of them, with all 8 elements
@@ -147,7 +147,7 @@ __global__ __launch_bounds__(kBlock) void decode_records_kernel(const uint8_t* _
   const uint32_t all_tiles = (uint32_t)(G / TG), full_tiles = (uint32_t)(Gfull / TG);
   const uint32_t rem_all = (uint32_t)(G - (uint64_t)all_tiles * TG), rem_whole = (uint32_t)(Gfull - (uint64_t)full_tiles * TG);
 
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (uint32_t tile = flat_tile(), once = 1; once && tile < tiles; once = 0) {
     const uint64_t g0 = (uint64_t)tile * TG;
     const uint32_t here = units_in_tile(tile, all_tiles, rem_all, TG);
     const uint32_t whole = units_in_tile(tile, full_tiles, rem_whole, TG);

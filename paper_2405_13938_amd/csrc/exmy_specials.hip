@@ -28,12 +28,12 @@ hipError_t launch(bool decode, bool wide, const void* src, void* dst, uint64_t n
     const uint64_t tile = (uint64_t)S::kDecBlock * S::kDecUnroll;
     const uint64_t tiles = (n / (16 / sizeof(T)) + tile - 1) / tile;
     hipLaunchKernelGGL((spec::decode_specials_kernel<T, W, S::kDecBlock, S::kDecUnroll>),
-                       dim3(grid_for_chunks(tiles, 1, S::kDecBlock)), dim3(S::kDecBlock), 0, stream, src, dst, n, fc, tc, sc);
+                       grid_for_flat_tiles(tiles, 1), dim3(S::kDecBlock), 0, stream, src, dst, n, fc, tc, sc);
     return hipGetLastError();
   }
   const uint64_t tile = (uint64_t)S::kEncBlock * S::kEncUnroll;
   const uint64_t tiles = (n / 8 + tile - 1) / tile;
-  const dim3 grid(grid_for_chunks(tiles, 1, S::kEncBlock)), block(S::kEncBlock);
+  const dim3 grid = grid_for_flat_tiles(tiles, 1), block(S::kEncBlock);
   if (wide)
     hipLaunchKernelGGL((spec::encode_specials_kernel<T, W, S::kEncBlock, S::kEncUnroll, true>), grid, block, 0, stream, src, dst, n, fc, tc, sc);
   else

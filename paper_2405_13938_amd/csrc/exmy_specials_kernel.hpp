@@ -61,7 +61,7 @@ __global__ __launch_bounds__(kBlock) void encode_specials_kernel(const void* src
   __shared__ __align__(16) uint8_t lds_stage[TG * W];
   const enc::PlaneStage<W, TG> stage{lds_stage};
 
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (uint32_t tile = flat_tile(), once = 1; once && tile < tiles; once = 0) {
     const uint64_t g0 = (uint64_t)tile * TG;
     const rsrc_t src = make_rsrc(src4 + g0 * kLoads);
     enc::TileRegs<T, kUnroll> regs;
@@ -90,7 +90,7 @@ __global__ __launch_bounds__(kBlock) void encode_specials_kernel(const void* src
   }
 
   // Ragged last group, padded with +0 (code 0).
-  if (Gfull != G && blockIdx.x == 0 && threadIdx.x == 0) {
+  if (Gfull != G && flat_tile() == 0 && threadIdx.x == 0) {
     uint32_t u[8];
     enc::ragged_group_bits<T>(src_v, Gfull * 8, n, u);
     enc::PlaneDst<W> pd;
@@ -167,7 +167,7 @@ __global__ __launch_bounds__(kBlock) void decode_specials_kernel(const void* src
   const uint32_t rem_units = (uint32_t)(Ufull - (uint64_t)full_tiles * TU);
   const uint32_t tiles = full_tiles + (rem_units ? 1u : 0u);
 
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (uint32_t tile = flat_tile(), once = 1; once && tile < tiles; once = 0) {
     const uint64_t u0 = (uint64_t)tile * TU;
     dec::PlaneSrc<W> ps;
     dec::make_plane_src<W, E>(src, G, u0, ps);
@@ -186,7 +186,7 @@ __global__ __launch_bounds__(kBlock) void decode_specials_kernel(const void* src
   }
 
   // The n % E elements after the last whole unit, one lane each.
-  if (blockIdx.x == 0 && threadIdx.x < E) {
+  if (flat_tile() == 0 && threadIdx.x < E) {
     const uint64_t i = Ufull * E + threadIdx.x;
     if (i < n) {
       dec::PlaneSrc<W> ps;

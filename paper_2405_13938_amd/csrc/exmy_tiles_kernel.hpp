@@ -116,7 +116,7 @@ __global__ __launch_bounds__(kBlock) void encode_tiles_kernel(const TileArgs arg
   __shared__ __align__(16) uint8_t lds_stage[TG * W];
   const enc::PlaneStage<W, TG> stage{lds_stage};
 
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (uint32_t tile = flat_tile(), once = 1; once && tile < tiles; once = 0) {
     const uint64_t g0 = (uint64_t)tile * TG;
     const TileStart ts = tile_start<TG, kColumns>(g0, ti);
     const rsrc_t src = make_rsrc(src4 + g0 * kLoads);
@@ -198,7 +198,7 @@ __global__ __launch_bounds__(kBlock) void decode_tiles_kernel(const TileArgs arg
   const uint32_t rem_units = (uint32_t)(U - (uint64_t)full_tiles * TU);
   const uint32_t tiles = full_tiles + (rem_units ? 1u : 0u);
 
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (uint32_t tile = flat_tile(), once = 1; once && tile < tiles; once = 0) {
     const uint64_t u0 = (uint64_t)tile * TU;  // even
     const TileStart ts = tile_start<TU, kColumns>(u0, ti);
     dec::PlaneSrc<W> ps;
@@ -294,7 +294,7 @@ __global__ __launch_bounds__(kBlock) void emulate_tiles_kernel(const TileArgs ar
   const uint32_t lane_off = threadIdx.x * 16;
   const uint32_t tiles = (uint32_t)((V + TV - 1) / TV);
 
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  for (uint32_t tile = flat_tile(), once = 1; once && tile < tiles; once = 0) {
     const uint64_t v0 = (uint64_t)tile * TV;
     const TileStart ts = tile_start<TV, kColumns>(v0, ti);
     const rsrc_t buf = make_rsrc(reinterpret_cast<uint4*>(data) + v0);
