@@ -49,8 +49,10 @@ __global__ __launch_bounds__(kBlock) void codes32_kernel(const BatchArgs batch) 
   }
 }
 
-constexpr int kBlock = 256;
-constexpr int kUnroll = 2;
+// Launch shape, from a sweep of workgroup size x vectors per lane on 1 GiB: the smallest workgroup with one
+// vector per lane copies fastest (6.75 TB/s; 256 lanes x 2 vectors: 5.97).
+constexpr int kBlock = 64;
+constexpr int kUnroll = 1;
 
 }  // namespace
 

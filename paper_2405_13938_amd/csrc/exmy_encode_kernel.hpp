@@ -24,7 +24,7 @@ namespace enc {
 
 // Histogram bins are replicated kHistCopies times in LDS, copy chosen by lane,
 // so that the few hot exponents of a real tensor do not serialise on one bank.
-constexpr int kHistCopies = 16;
+constexpr int kHistCopies = 32;
 
 // 32-bit LDS bins are folded into the 64-bit global bins after this many tiles,
 // long before 2^32 elements have been counted by one block.
