@@ -30,9 +30,9 @@ HBM_PEAK_GBPS = 8000.0  # MI355X HBM3E datasheet peak
 # HBM bytes per launch of the dominant kernel, from rocprofv3 --pmc FETCH_SIZE / WRITE_SIZE
 # runs scaled by a copy kernel of known size (profiles/*hbm_traffic*.txt).  None = not measured.
 MEASURED_TRAFFIC_BYTES_PER_LAUNCH = {
-    # profiles/cfg5_bf16_e3m3_encode_decode_hbm_traffic.txt: mean over the 5 launches of a batched call
-    ("cfg5", "batch", "encode"): 3723928294,
-    ("cfg5", "batch", "decode"): 3723956499,
+    # profiles/cfg5_bf16_e3m3_encode_decode_hbm_traffic.txt: mean over the 9 launches of a batched call
+    ("cfg5", "batch", "encode"): 2068875877,
+    ("cfg5", "batch", "decode"): 2068891632,
 }
 
 
