@@ -77,8 +77,11 @@ hipError_t launch_max_exp(TileArgs args, hipStream_t stream) {
   args.ti = make_tile_index(args, E);
   tiles::MaxGeometry geo;
   geo.vpr = (uint32_t)(args.cols / E);
-  geo.lanes_x_log2 = 8;
-  if (geo.vpr <= 128) {
+  // Column blocks give every element of a strip a metadata byte of its own to fold into: strips of 32 lanes
+  // (512 bytes of a matrix row) with 8 rows per step fold 18 x fewer words than strips of 256 lanes, 4.15 -> 5.65 TB/s
+  // on a (32768, 11008) bf16 matrix; 16 lanes measured the same, 8 lanes 5-15 % less.
+  geo.lanes_x_log2 = columns ? 5 : 8;
+  if (geo.vpr <= (columns ? 32u : 128u)) {
     geo.lanes_x_log2 = 0;
     while ((1u << geo.lanes_x_log2) < geo.vpr) ++geo.lanes_x_log2;
   }

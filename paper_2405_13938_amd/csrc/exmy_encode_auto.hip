@@ -30,7 +30,7 @@ template <typename T, int W, int kBlock, int kLoads>
 hipError_t launch_team(const BlockArgs& args, hipStream_t stream) {
   constexpr int kUnroll = kLoads / (sizeof(T) == 4 ? 2 : 1);
   hipLaunchKernelGGL((enc::encode_blocks_auto_team_kernel<T, W, kBlock, kUnroll, true>),
-                     dim3(grid_for_chunks(args.n_blocks, 1, kBlock)), dim3(kBlock), 0, stream, args);
+                     grid_for_flat_tiles(args.n_blocks, 1), dim3(kBlock), 0, stream, args);
   return hipGetLastError();
 }
 
@@ -51,10 +51,11 @@ hipError_t launch(BlockArgs args, hipStream_t stream) {
   if (loads <= 64 * kLoadsPerLane) return launch_team<T, W, 64, kLoadsPerLane>(args, stream);
   if (loads <= 128 * kLoadsPerLane) return launch_team<T, W, 128, kLoadsPerLane>(args, stream);
   if (loads <= 256 * kLoadsPerLane) return launch_team<T, W, 256, kLoadsPerLane>(args, stream);
+  if (loads <= 256 * 8) return launch_team<T, W, 256, 8>(args, stream);
   if (loads <= kMaxTwoPassLoads) {
     constexpr int kUnroll = sizeof(T) == 4 ? 1 : 2;
     hipLaunchKernelGGL((enc::encode_blocks_auto_twopass_kernel<T, W, 256, kUnroll, true>),
-                       dim3(grid_for_chunks(args.n_blocks, 1, 256)), dim3(256), 0, stream, args);
+                       grid_for_flat_tiles(args.n_blocks, 1), dim3(256), 0, stream, args);
     return hipGetLastError();
   }
   return hipErrorNotSupported;  // the caller falls back to two launches

@@ -761,7 +761,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_team_kernel(const B
   const uint64_t last_g0 = (args.n_blocks - 1) * bg;
   const uint32_t last_count = (uint32_t)(G - last_g0), last_whole = (uint32_t)(Gfull - last_g0);
 
-  for (uint64_t b = blockIdx.x; b < args.n_blocks; b += gridDim.x) {
+  for (uint64_t b = (uint64_t)blockIdx.z * gridDim.x + blockIdx.x, once = 1; once && b < args.n_blocks; once = 0) {
     const uint64_t g0 = b * bg;
     const bool is_last = b + 1 == args.n_blocks;
     const uint32_t count = is_last ? last_count : bg;  // groups of this block, a ragged last one included
@@ -843,7 +843,7 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_twopass_kernel(cons
   const uint64_t last_g0 = (args.n_blocks - 1) * bg;
   const uint32_t last_count = (uint32_t)(G - last_g0), last_whole = (uint32_t)(Gfull - last_g0);
 
-  for (uint64_t b = blockIdx.x; b < args.n_blocks; b += gridDim.x) {
+  for (uint64_t b = (uint64_t)blockIdx.z * gridDim.x + blockIdx.x, once = 1; once && b < args.n_blocks; once = 0) {
     const uint64_t g0 = b * bg;
     const bool is_last = b + 1 == args.n_blocks;
     const uint32_t count = is_last ? last_count : bg;  // groups of this block, a ragged last one included
