@@ -178,6 +178,7 @@ struct RowsArgs {
   const uint8_t* meta;  // one byte per row, or null
   uint64_t rows;
   uint32_t cols;        // a multiple of 8
+  uint64_t xcd_chunk;   // 0: workgroup w takes tile w; else tile (w % 8) * xcd_chunk + w / 8 (see rows::tile_of_workgroup)
 };
 
 inline BlockIndex make_block_index(uint64_t size) {

@@ -8,19 +8,44 @@ namespace {
 
 constexpr int kBlock = 64;
 
-template <typename T, int W>
-hipError_t launch(RowsArgs args, bool per_row, bool wide, hipStream_t stream) {
-  constexpr uint64_t kTileCols = (uint64_t)kBlock * (16 / sizeof(T));
-  const uint64_t tiles_per_row_block = (args.cols + kTileCols - 1) / kTileCols;
-  args.tiles = make_block_index(tiles_per_row_block);
-  const dim3 grid(grid_for_chunks(((args.rows + 7) / 8) * tiles_per_row_block, 1, kBlock));
+// Places (16-byte row pieces) per row block below which, unless they fill whole tiles, the tiles are folded
+// over row blocks: the idle part of a row block's last tile would otherwise cost more than the per-lane
+// metadata of the folded form.
+constexpr uint64_t kFoldBelow = 512;
+
+template <typename T, int W, bool kFold>
+hipError_t launch_form(RowsArgs args, bool per_row, bool wide, hipStream_t stream) {
+  const uint64_t places = args.cols / (16 / sizeof(T));  // per row block
+  const uint64_t row_blocks = (args.rows + 7) / 8;
+  uint64_t tiles;
+  if (kFold) {
+    args.tiles = make_block_index(places);
+    tiles = (row_blocks * places + kBlock - 1) / kBlock;
+  } else {
+    const uint64_t tiles_per_row_block = (places + kBlock - 1) / kBlock;
+    args.tiles = make_block_index(tiles_per_row_block);
+    tiles = row_blocks * tiles_per_row_block;
+  }
+  args.xcd_chunk = 0;
+  if ((args.cols * sizeof(T)) % 128) {  // rows start inside cache lines: see rows::tile_of_workgroup
+    args.xcd_chunk = (tiles + 7) / 8;
+    tiles = args.xcd_chunk * 8;
+  }
+  const dim3 grid = grid_for_flat_tiles(tiles, 1);
   if (per_row)
-    hipLaunchKernelGGL((rows::encode_rows_kernel<T, W, kBlock, true, false>), grid, dim3(kBlock), 0, stream, args);
+    hipLaunchKernelGGL((rows::encode_rows_kernel<T, W, kBlock, true, false, kFold>), grid, dim3(kBlock), 0, stream, args);
   else if (wide)
-    hipLaunchKernelGGL((rows::encode_rows_kernel<T, W, kBlock, false, true>), grid, dim3(kBlock), 0, stream, args);
+    hipLaunchKernelGGL((rows::encode_rows_kernel<T, W, kBlock, false, true, kFold>), grid, dim3(kBlock), 0, stream, args);
   else
-    hipLaunchKernelGGL((rows::encode_rows_kernel<T, W, kBlock, false, false>), grid, dim3(kBlock), 0, stream, args);
+    hipLaunchKernelGGL((rows::encode_rows_kernel<T, W, kBlock, false, false, kFold>), grid, dim3(kBlock), 0, stream, args);
   return hipGetLastError();
+}
+
+template <typename T, int W>
+hipError_t launch(const RowsArgs& args, bool per_row, bool wide, hipStream_t stream) {
+  const uint64_t places = args.cols / (16 / sizeof(T));
+  if (places % kBlock && places < kFoldBelow) return launch_form<T, W, true>(args, per_row, wide, stream);
+  return launch_form<T, W, false>(args, per_row, wide, stream);
 }
 
 template <typename T>

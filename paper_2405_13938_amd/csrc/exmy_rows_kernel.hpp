@@ -5,13 +5,23 @@
 // One lane owns kCols adjacent columns (16 bytes of every row: 8 bf16 or 4 fp32
 // values) of one row block: eight 16-byte loads, one per row, each contiguous
 // over the wavefront; kCols adjacent words of every plane, written (or read) as
-// one contiguous piece of kCols * S bytes.  A tile is kBlock * kCols columns of
-// one row block; tiles are numbered row-block-major, so a launch walks the plane
-// arrays in address order and the source as 8 parallel streams.
+// one contiguous piece of kCols * S bytes.  A row block is cols / kCols such lane
+// places, and the lane places of the whole matrix, row block after row block, are
+// the words of every plane in address order.
+//
+// Two ways to cut them into workgroup tiles of kBlock places:
+//  - by row block (wide matrices): a tile is kBlock * kCols columns of one row block,
+//    the last tile of a row block partly idle.  A tile sees at most 8 metadata, all
+//    wave-uniform, so the constants of the 8 rows stay in SGPRs;
+//  - folded (kFold; narrow matrices, and widths that would leave much of the last
+//    tile idle): a tile is kBlock consecutive places whatever row blocks they fall
+//    into, so a 128-column bf16 matrix (16 places per row block) puts 4 row blocks
+//    into a wavefront and every lane works.  The planes are still written as one
+//    contiguous run per tile, the source is read as runs of one matrix row each,
+//    and per-row metadata are per-lane values.
 //
 // Metadata: one max_exp for the tensor, or one per row of the matrix (Section
-// 2.2.1: the (R, 1) metadata tensor).  Either way a tile sees at most 8 metadata,
-// all wave-uniform, so the constants of the 8 rows stay in SGPRs.
+// 2.2.1: the (R, 1) metadata tensor).
 #pragma once
 
 #include "exmy_decode_kernel.hpp"
@@ -127,44 +137,104 @@ __device__ __forceinline__ void make_plane_rsrc(uint8_t* packed, uint64_t R, uin
   }
 }
 
-// Metadata of the 8 rows of row block rb: lane l fetches the byte of row 8 rb + (l & 7),
-// one load for the whole block.  Every lane of the wavefront must call it.
-template <bool kPerRow>
-__device__ __forceinline__ uint32_t load_row_metadata(const RowsArgs& a, uint64_t rb) {
-  uint32_t mv = a.bc.meta_lo;
-  if constexpr (kPerRow) {
-    const uint64_t row = 8 * rb + (threadIdx.x & 7u);
-    if (row < a.rows) mv = a.meta[row];
+// Where a lane works: its row block, its byte offset in the source from row 0 of
+// row block rb0, and the tile's base (rb0, col0) in the (R, cols) plane arrays.
+struct LanePlace {
+  uint64_t rb0;
+  uint64_t rb;
+  uint32_t col0;
+  uint32_t src_off;
+  bool inside;
+};
+
+// kFold: a.tiles divides by the places per row block; else by the tiles per row block.
+template <typename T, int kBlock, bool kFold>
+__device__ __forceinline__ LanePlace lane_place(uint64_t tile, const RowsArgs& a, uint64_t R) {
+  constexpr uint32_t kCols = 16 / sizeof(T);
+  LanePlace p;
+  uint32_t first;
+  if constexpr (kFold) {
+    tile_first_block(tile * kBlock, a.tiles, p.rb0, first);  // first: the tile's first place inside row block rb0
+    const uint32_t j = first + threadIdx.x;
+    const uint32_t d = lane_block<kBlock>(j, a.tiles);  // row blocks that start in between
+    p.rb = p.rb0 + d;
+    p.col0 = first * kCols;
+    p.src_off = d * 8u * a.cols * (uint32_t)sizeof(T) + (j - d * a.tiles.size) * 16u;
+    p.inside = p.rb < R;
+  } else {
+    tile_first_block(tile, a.tiles, p.rb0, first);  // first: the tile's number inside row block rb0
+    p.rb = p.rb0;
+    p.col0 = first * kBlock * kCols;
+    p.src_off = p.col0 * (uint32_t)sizeof(T) + threadIdx.x * 16u;
+    p.inside = p.col0 + threadIdx.x * kCols < a.cols;
   }
-  return mv;
+  return p;
 }
 
-// Constants of the 8 rows from the bytes that lanes 0-7 hold (wave-uniform results).
+// Tile of this workgroup.  Workgroups are handed to the 8 accelerator dies (each with an L2 cache of its own) in
+// turn.  When the rows of the matrix do not start on cache-line boundaries, neighbouring tiles share the lines at
+// their row ends; with xcd_chunk set, die k takes the contiguous range of tiles [k * xcd_chunk, (k + 1) * xcd_chunk),
+// so both halves of such a line pass through the same L2 (one fetch, one merged write-back instead of two partial ones).
+__device__ __forceinline__ uint64_t tile_of_workgroup(const RowsArgs& a) {
+  const uint64_t w = flat_tile();
+  return a.xcd_chunk ? (w & 7u) * a.xcd_chunk + (w >> 3) : w;
+}
+
+// Metadata bytes of the 8 rows of a lane's row block, clamped later by derive_tc.
+// Not folded: lane l fetches the byte of row 8 rb + (l & 7), one load for the whole
+// (wave-uniform) block, and metadatum j is read from lane j - every lane of the
+// wavefront must call load() and get().  Folded: a lane fetches its own 8 bytes.
+template <bool kPerRow, bool kFold>
+struct RowMetadata {
+  uint32_t mv[kFold ? 8 : 1];
+  __device__ __forceinline__ void load(const RowsArgs& a, const LanePlace& p) {
+    if constexpr (!kPerRow) return;
+    if constexpr (kFold) {
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        const uint64_t row = 8 * p.rb + (uint32_t)j;
+        mv[j] = p.inside && row < a.rows ? a.meta[row] : a.bc.meta_lo;
+      }
+    } else {
+      const uint64_t row = 8 * p.rb + (threadIdx.x & 7u);
+      mv[0] = row < a.rows ? a.meta[row] : a.bc.meta_lo;
+    }
+  }
+  __device__ __forceinline__ uint32_t get(int j) const {
+    if constexpr (kFold)
+      return mv[j];
+    else
+      return (uint32_t)__builtin_amdgcn_readlane(mv[0], j);
+  }
+};
+
+// Constants of the 8 rows (wave-uniform results unless folded).
 //
 // A metadatum so large that the fp32 rounding addend 2^(ec-127+23-Y) would overflow
 // (max_exp > 231 + Y; values beyond 2^104) is handled without the fp64 variant: the
 // row's values are multiplied by 2^-64 and its metadatum lowered by 64.  That is
 // exact for every value that does not flush to zero anyway: in such a row the
 // subnormal quantum is above 2^-46, while only values under 2^-62 underflow.
-template <bool kPerRow>
-__device__ __forceinline__ void row_constants(const RowsArgs& a, uint32_t mv, TensorConsts tc[8], float pre[8],
-                                              bool& any_pre) {
-  any_pre = false;
+template <bool kPerRow, bool kFold>
+__device__ __forceinline__ void row_constants(const RowsArgs& a, const RowMetadata<kPerRow, kFold>& md,
+                                              TensorConsts tc[8], float pre[8], bool& any_pre) {
+  bool lane_pre = false;
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
     pre[j] = 1.0f;
     if constexpr (kPerRow) {
-      uint32_t me = min(max((uint32_t)__builtin_amdgcn_readlane(mv, j), a.bc.meta_lo), a.bc.meta_hi);
+      uint32_t me = min(max(md.get(j), a.bc.meta_lo), a.bc.meta_hi);
       if (me > a.bc.wide_above) {
         me -= 64u;
         pre[j] = as_f32((127u - 64u) << 23);
-        any_pre = true;
+        lane_pre = true;
       }
       tc[j] = derive_tc(me, a.bc);
     } else {
       tc[j] = a.tc;
     }
   }
+  any_pre = kFold ? __builtin_amdgcn_ballot_w64(lane_pre) != 0 : lane_pre;
 }
 
 // kPre: multiply row j by pre[j] first (see row_constants).
@@ -186,53 +256,50 @@ __device__ __forceinline__ void encode_columns(const uint4 v[8], const FormatCon
 }
 
 // kWide: per-tensor metadata only (per-row metadata never needs the fp64 variant, see row_constants).
-template <typename T, int W, int kBlock, bool kPerRow, bool kWide>
+// One tile per workgroup, tile = flat_tile().
+template <typename T, int W, int kBlock, bool kPerRow, bool kWide, bool kFold>
 __global__ __launch_bounds__(kBlock) void encode_rows_kernel(const RowsArgs args) {
   constexpr int kCols = 16 / sizeof(T);
-  constexpr uint32_t kTileCols = kBlock * kCols;
   const uint8_t* __restrict__ src = static_cast<const uint8_t*>(args.src);
   uint8_t* __restrict__ dst = static_cast<uint8_t*>(args.dst);
   const FormatConsts fc = args.fc;
   const uint32_t cols = args.cols;
   const uint64_t R = (args.rows + 7) / 8;
   const uint32_t row_bytes = cols * (uint32_t)sizeof(T);
-  const uint64_t total = R * args.tiles.size;
 
-  for (uint64_t t = blockIdx.x; t < total; t += gridDim.x) {
-    uint64_t rb;
-    uint32_t ct;
-    tile_first_block(t, args.tiles, rb, ct);
-    const uint32_t col0 = ct * kTileCols;
-    const uint32_t mv = load_row_metadata<kPerRow>(args, rb);
-    if (col0 + threadIdx.x * kCols >= cols) continue;
-    const uint64_t left = args.rows - 8 * rb;
-    const uint32_t nrows = left < 8 ? (uint32_t)left : 8u;
-    const rsrc_t in = make_rsrc(src + ((8 * rb) * cols + col0) * sizeof(T));
-    uint4 v[8];
+  const LanePlace p = lane_place<T, kBlock, kFold>(tile_of_workgroup(args), args, R);
+  if (p.rb0 >= R) return;  // workgroups past the last tile of a rounded-up grid
+  RowMetadata<kPerRow, kFold> md;
+  md.load(args, p);
+  if (!kFold && !p.inside) return;  // folded: idle lanes stay for the ballot in row_constants
+  const uint64_t left = p.inside ? args.rows - 8 * p.rb : 0;
+  const uint32_t nrows = left < 8 ? (uint32_t)left : 8u;
+  const rsrc_t in = make_rsrc(src + 8 * p.rb0 * cols * sizeof(T));
+  uint4 v[8];
+  if (args.xcd_chunk) {  // lines shared with the neighbouring tile: leave them in the L2 cache for it
 #pragma unroll
-    for (int j = 0; j < 8; ++j) {
-      if (j < (int)nrows)
-        v[j] = load16<true>(in, threadIdx.x * 16, j * row_bytes);
-      else
-        v[j] = make_uint4(0, 0, 0, 0);  // rows past the end hold zero codes
-    }
-    TensorConsts tc[8];
-    float pre[8];
-    bool any_pre;
-    row_constants<kPerRow>(args, mv, tc, pre, any_pre);
-    LaneWords<W, kCols> lw;
-    if constexpr (kPerRow) {
-      if (any_pre)
-        encode_columns<T, W, kCols, false, true>(v, fc, tc, pre, lw);
-      else
-        encode_columns<T, W, kCols, false, false>(v, fc, tc, pre, lw);
-    } else {
-      encode_columns<T, W, kCols, kWide, false>(v, fc, tc, pre, lw);
-    }
-    rsrc_t plane[Planes<W>::count];
-    make_plane_rsrc<W>(dst, R, cols, rb, col0, plane);
-    move_words<W, kCols, true>(lw, plane, threadIdx.x);
+    for (int j = 0; j < 8; ++j) v[j] = j < (int)nrows ? load16<false>(in, p.src_off, j * row_bytes) : make_uint4(0, 0, 0, 0);
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j) v[j] = j < (int)nrows ? load16<true>(in, p.src_off, j * row_bytes) : make_uint4(0, 0, 0, 0);
+  }  // rows past the end hold zero codes
+  TensorConsts tc[8];
+  float pre[8];
+  bool any_pre;
+  row_constants<kPerRow, kFold>(args, md, tc, pre, any_pre);
+  if (kFold && !p.inside) return;
+  LaneWords<W, kCols> lw;
+  if constexpr (kPerRow) {
+    if (any_pre)
+      encode_columns<T, W, kCols, false, true>(v, fc, tc, pre, lw);
+    else
+      encode_columns<T, W, kCols, false, false>(v, fc, tc, pre, lw);
+  } else {
+    encode_columns<T, W, kCols, kWide, false>(v, fc, tc, pre, lw);
   }
+  rsrc_t plane[Planes<W>::count];
+  make_plane_rsrc<W>(dst, R, cols, p.rb0, p.col0, plane);
+  move_words<W, kCols, true>(lw, plane, threadIdx.x);
 }
 
 // The plane bits of column c of the lane, in the form element_bits reads (a unit of 8 elements).
@@ -252,63 +319,58 @@ __device__ __forceinline__ void column_unit(const LaneWords<W, kCols>& lw, int c
   }
 }
 
-template <typename T, int W, int kBlock, bool kPerRow, bool kX8>
+template <typename T, int W, int kBlock, bool kPerRow, bool kX8, bool kFold>
 __global__ __launch_bounds__(kBlock) void decode_rows_kernel(const RowsArgs args) {
   constexpr int kCols = 16 / sizeof(T);
-  constexpr uint32_t kTileCols = kBlock * kCols;
   uint8_t* __restrict__ src = static_cast<uint8_t*>(const_cast<void*>(args.src));
   uint8_t* __restrict__ dst = static_cast<uint8_t*>(args.dst);
   const FormatConsts fc = args.fc;
   const uint32_t cols = args.cols;
   const uint64_t R = (args.rows + 7) / 8;
   const uint32_t row_bytes = cols * (uint32_t)sizeof(T);
-  const uint64_t total = R * args.tiles.size;
 
-  for (uint64_t t = blockIdx.x; t < total; t += gridDim.x) {
-    uint64_t rb;
-    uint32_t ct;
-    tile_first_block(t, args.tiles, rb, ct);
-    const uint32_t col0 = ct * kTileCols;
-    const uint32_t mv = load_row_metadata<kPerRow>(args, rb);
-    if (col0 + threadIdx.x * kCols >= cols) continue;
-    const uint64_t left = args.rows - 8 * rb;
-    const uint32_t nrows = left < 8 ? (uint32_t)left : 8u;
-    rsrc_t plane[Planes<W>::count];
-    make_plane_rsrc<W>(src, R, cols, rb, col0, plane);
-    LaneWords<W, kCols> lw;
-    move_words<W, kCols, false>(lw, plane, threadIdx.x);
-    TensorConsts tc[8];
-    if constexpr (kPerRow) {
+  const LanePlace p = lane_place<T, kBlock, kFold>(tile_of_workgroup(args), args, R);
+  if (p.rb0 >= R) return;
+  RowMetadata<kPerRow, kFold> md;
+  md.load(args, p);
+  TensorConsts tc[8];
 #pragma unroll
-      for (int j = 0; j < 8; ++j) tc[j] = derive_tc(__builtin_amdgcn_readlane(mv, j), args.bc);
-    } else {
-#pragma unroll
-      for (int j = 0; j < 8; ++j) tc[j] = args.tc;
-    }
+  for (int j = 0; j < 8; ++j) tc[j] = kPerRow ? derive_tc(md.get(j), args.bc) : args.tc;
+  if (!p.inside) return;
+  const uint64_t left = args.rows - 8 * p.rb;
+  const uint32_t nrows = left < 8 ? (uint32_t)left : 8u;
+  rsrc_t plane[Planes<W>::count];
+  make_plane_rsrc<W>(src, R, cols, p.rb0, p.col0, plane);
+  LaneWords<W, kCols> lw;
+  move_words<W, kCols, false>(lw, plane, threadIdx.x);
 
-    uint32_t o[8][4];  // the lane's 16 bytes of every row
+  uint32_t o[8][4];  // the lane's 16 bytes of every row
 #pragma unroll
-    for (int c = 0; c < kCols; ++c) {
-      dec::UnitWords<W> uw;
-      column_unit<W, kCols>(lw, c, uw);
+  for (int c = 0; c < kCols; ++c) {
+    dec::UnitWords<W> uw;
+    column_unit<W, kCols>(lw, c, uw);
 #pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const uint32_t b = dec::element_bits<W, kX8>(uw, j, fc, tc[j]);
-        if constexpr (sizeof(T) == 4) {
-          o[j][c] = b;
-        } else {  // every value is exact in the 16-bit type: pair it with its neighbour
-          if (c & 1)
-            o[j][c / 2] = pack_elems<T>(o[j][c / 2], b);
-          else
-            o[j][c / 2] = b;
-        }
+    for (int j = 0; j < 8; ++j) {
+      const uint32_t b = dec::element_bits<W, kX8>(uw, j, fc, tc[j]);
+      if constexpr (sizeof(T) == 4) {
+        o[j][c] = b;
+      } else {  // every value is exact in the 16-bit type: pair it with its neighbour
+        if (c & 1)
+          o[j][c / 2] = pack_elems<T>(o[j][c / 2], b);
+        else
+          o[j][c / 2] = b;
       }
     }
-    const rsrc_t out = make_rsrc(dst + ((8 * rb) * cols + col0) * sizeof(T));
+  }
+  const rsrc_t out = make_rsrc(dst + 8 * p.rb0 * cols * sizeof(T));
+  if (args.xcd_chunk) {  // lines shared with the neighbouring tile: let the L2 cache merge the two parts
 #pragma unroll
     for (int j = 0; j < 8; ++j)
-      if (j < (int)nrows)
-        store16<true>(out, threadIdx.x * 16, j * row_bytes, make_uint4(o[j][0], o[j][1], o[j][2], o[j][3]));
+      if (j < (int)nrows) store16<false>(out, p.src_off, j * row_bytes, make_uint4(o[j][0], o[j][1], o[j][2], o[j][3]));
+  } else {
+#pragma unroll
+    for (int j = 0; j < 8; ++j)
+      if (j < (int)nrows) store16<true>(out, p.src_off, j * row_bytes, make_uint4(o[j][0], o[j][1], o[j][2], o[j][3]));
   }
 }
 

@@ -91,6 +91,36 @@ def test_shapes(dtype):
             check_rows(x, X, Y, meta=per_row_meta(x, X, "before_rounding"))
 
 
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_narrow_matrices_fold_row_blocks(dtype):
+    # fewer than 64 row pieces per row block: a wavefront takes several row blocks (128 and 256 columns: 4 and 2
+    # of them in bf16); widths that do not divide the wavefront, a ragged last row block, a last tile that ends
+    # inside the wavefront, and per-row metadata that differ from lane to lane
+    g = torch.Generator().manual_seed(77)
+    for rows, cols in [(4096, 128), (2048, 256), (1021, 128), (515, 256), (333, 24), (1000, 8), (77, 136), (250, 264),
+                       (61, 1016), (129, 3000)]:
+        scale = torch.exp2(torch.randint(-8, 8, (rows, 1), generator=g).float())
+        x = (torch.randn(rows, cols, generator=g) * scale).to(dtype).to(DEV)
+        for X, Y in ((3, 3), (2, 1), (4, 3)):
+            check_rows(x, X, Y, tensor_max_exp(X))
+            check_rows(x, X, Y, meta=per_row_meta(x, X, "before_rounding"))
+        check_rows(x, 3, 2, meta=per_row_meta(x, 3, "any_byte", seed=rows))
+        check_rows(x, 8, 7 if dtype != torch.float32 else 5, 255)
+
+
+def test_narrow_matrix_wide_rounding_paths():
+    # the folded form of test_wide_rounding_paths: rows whose metadata need the pre-scaled rounding sit beside rows
+    # that do not, inside one wavefront
+    x = synth.shuffled(synth.f32_edge_sweep(seed=3), 3)[: 256 * 128].reshape(256, 128).contiguous().to(DEV)
+    check_rows(x, 3, 2, 254)
+    meta = np.full(256, 200, dtype=np.uint8)
+    meta[8:16] = 254
+    meta[40] = 250
+    meta[255] = 253
+    check_rows(x, 3, 2, meta=meta)
+    check_rows(x[:250].contiguous(), 3, 2, meta=meta[:250])
+
+
 def test_wide_rounding_paths():
     # metadata so large that the fp32 magic addend would overflow: the fp64 variant, per tensor and per tile
     x = synth.shuffled(synth.f32_edge_sweep(seed=2), 2)[: 64 * 512].reshape(64, 512).contiguous().to(DEV)
