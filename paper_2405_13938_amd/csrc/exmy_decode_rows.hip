@@ -27,7 +27,7 @@ hipError_t launch_form(RowsArgs args, bool per_row, bool x8, hipStream_t stream)
     tiles = row_blocks * tiles_per_row_block;
   }
   args.xcd_chunk = 0;
-  if ((args.cols * sizeof(T)) % 128) {  // rows start inside cache lines: see rows::tile_of_workgroup
+  if ((args.cols * sizeof(T)) % 128) {  // rows start inside cache lines: see die_ranged_tile
     args.xcd_chunk = (tiles + 7) / 8;
     tiles = args.xcd_chunk * 8;
   }

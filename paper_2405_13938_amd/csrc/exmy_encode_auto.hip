@@ -21,10 +21,12 @@ struct Small<float> {
 };
 
 // Longer blocks: a workgroup per block, sized so that the block fills at least half of it, every lane holding
-// at most kLoadsPerLane 16-byte loads in registers.
+// kLoadsPerLane 16-byte loads in registers; blocks beyond 256 x kLoadsPerLane loads stay in a 256-lane
+// workgroup with 8 or 16 loads per lane (measured: more lanes per workgroup instead are slower).
 constexpr int kLoadsPerLane = 4;
-// Longer blocks still: the workgroup walks the block twice, the second time out of the L2 cache.
-constexpr uint64_t kMaxTwoPassLoads = 4096;  // 64 KiB per block; beyond, two launches are as fast
+// Longer blocks still: the workgroup walks the block twice, the second time out of the L2 cache (workgroups of
+// 512 x 16 or 1024 x 8 register-held loads were measured no faster).
+constexpr uint64_t kMaxTwoPassLoads = 8192;  // 128 KiB per block; beyond, two launches are as fast
 
 template <typename T, int W, int kBlock, int kLoads>
 hipError_t launch_team(const BlockArgs& args, hipStream_t stream) {
@@ -50,8 +52,14 @@ hipError_t launch(BlockArgs args, hipStream_t stream) {
   if (loads <= 64 * 2) return launch_team<T, W, 64, 2>(args, stream);
   if (loads <= 64 * kLoadsPerLane) return launch_team<T, W, 64, kLoadsPerLane>(args, stream);
   if (loads <= 128 * kLoadsPerLane) return launch_team<T, W, 128, kLoadsPerLane>(args, stream);
+  // the 192-lane forms are there for rows of 5504, 11008 and 22016 elements, which would idle a third of the
+  // next power of two (-12 %)
+  if (loads <= 192 * kLoadsPerLane) return launch_team<T, W, 192, kLoadsPerLane>(args, stream);
   if (loads <= 256 * kLoadsPerLane) return launch_team<T, W, 256, kLoadsPerLane>(args, stream);
+  if (loads <= 192 * 8) return launch_team<T, W, 192, 8>(args, stream);
   if (loads <= 256 * 8) return launch_team<T, W, 256, 8>(args, stream);
+  if (loads <= 192 * 16) return launch_team<T, W, 192, 16>(args, stream);
+  if (loads <= 256 * 16) return launch_team<T, W, 256, 16>(args, stream);
   if (loads <= kMaxTwoPassLoads) {
     constexpr int kUnroll = sizeof(T) == 4 ? 1 : 2;
     hipLaunchKernelGGL((enc::encode_blocks_auto_twopass_kernel<T, W, 256, kUnroll, true>),

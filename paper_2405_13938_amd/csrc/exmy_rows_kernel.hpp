@@ -171,15 +171,6 @@ __device__ __forceinline__ LanePlace lane_place(uint64_t tile, const RowsArgs& a
   return p;
 }
 
-// Tile of this workgroup.  Workgroups are handed to the 8 accelerator dies (each with an L2 cache of its own) in
-// turn.  When the rows of the matrix do not start on cache-line boundaries, neighbouring tiles share the lines at
-// their row ends; with xcd_chunk set, die k takes the contiguous range of tiles [k * xcd_chunk, (k + 1) * xcd_chunk),
-// so both halves of such a line pass through the same L2 (one fetch, one merged write-back instead of two partial ones).
-__device__ __forceinline__ uint64_t tile_of_workgroup(const RowsArgs& a) {
-  const uint64_t w = flat_tile();
-  return a.xcd_chunk ? (w & 7u) * a.xcd_chunk + (w >> 3) : w;
-}
-
 // Metadata bytes of the 8 rows of a lane's row block, clamped later by derive_tc.
 // Not folded: lane l fetches the byte of row 8 rb + (l & 7), one load for the whole
 // (wave-uniform) block, and metadatum j is read from lane j - every lane of the
@@ -267,7 +258,7 @@ __global__ __launch_bounds__(kBlock) void encode_rows_kernel(const RowsArgs args
   const uint64_t R = (args.rows + 7) / 8;
   const uint32_t row_bytes = cols * (uint32_t)sizeof(T);
 
-  const LanePlace p = lane_place<T, kBlock, kFold>(tile_of_workgroup(args), args, R);
+  const LanePlace p = lane_place<T, kBlock, kFold>(die_ranged_tile(args.xcd_chunk), args, R);
   if (p.rb0 >= R) return;  // workgroups past the last tile of a rounded-up grid
   RowMetadata<kPerRow, kFold> md;
   md.load(args, p);
@@ -329,7 +320,7 @@ __global__ __launch_bounds__(kBlock) void decode_rows_kernel(const RowsArgs args
   const uint64_t R = (args.rows + 7) / 8;
   const uint32_t row_bytes = cols * (uint32_t)sizeof(T);
 
-  const LanePlace p = lane_place<T, kBlock, kFold>(tile_of_workgroup(args), args, R);
+  const LanePlace p = lane_place<T, kBlock, kFold>(die_ranged_tile(args.xcd_chunk), args, R);
   if (p.rb0 >= R) return;
   RowMetadata<kPerRow, kFold> md;
   md.load(args, p);

@@ -207,7 +207,7 @@ def test_encode_blocks_auto(scheme, dtype):
     x = x.to(dtype).to(DEV)
     host = synth.bits_numpy(x)
     fmts = [(2, 1), (3, 3), (1, 2), (0, 4), (4, 3), (5, 2), (7, 0), (4, 7)]
-    blocks = [8, 16, 32, 64, 128, 256, 512, 24, 520, 1024, 2048, 2056, 4096, 8192, 11008, 16384, 32768, 40000, 1 << 18]
+    blocks = [8, 16, 32, 64, 128, 256, 512, 24, 520, 1024, 2048, 2056, 4096, 8192, 11008, 16384, 22016, 32768, 40000, 65536, 1 << 18]
     for i, block in enumerate(blocks):
         X, Y = fmts[i % len(fmts)]
         for nn in (n, n - n % block if n >= block else n, 7, block + 3):
