@@ -200,17 +200,23 @@ __device__ __forceinline__ void flush_stage(const PlaneStage<W, kTileGroups>& st
   __syncthreads();  // the image is free for the next tile
 }
 
-// The same for the first `count` groups of an image (a multiple of 16, so that every plane's part is whole
-// 16-byte pieces), through plane descriptors whose base lies `tile_group` groups before the image's first group.
+// The same for the first `count` groups of an image, through plane descriptors whose base lies `tile_group`
+// groups before the image's first group: every plane's part in 16-byte pieces, and the up to 15 bytes that
+// remain of it when count is not a multiple of 16 as single bytes.
 template <int W, int kTileGroups, int kBlock, int P = 0>
 __device__ __forceinline__ void copy_stage_groups(const PlaneStage<W, kTileGroups>& st, const PlaneDst<W>& pd,
                                                   uint32_t tile_group, uint32_t count) {
   if constexpr (P < Planes<W>::count) {
     constexpr uint32_t S = Planes<W>::seg(P);
     constexpr uint32_t LO = Planes<W>::lo(P);
-    const uint32_t pieces = count * S / 16;
+    const uint32_t bytes = count * S;
+    const uint32_t pieces = bytes / 16;
     for (uint32_t c = threadIdx.x; c < pieces; c += kBlock)
       store16<true>(pd.plane[P], c * 16, tile_group * S, *reinterpret_cast<const uint4*>(st.lds + kTileGroups * LO + c * 16));
+    if constexpr (S < 16) {
+      const uint32_t at = pieces * 16 + threadIdx.x;
+      if (at < bytes) __builtin_amdgcn_raw_buffer_store_b8(st.lds[kTileGroups * LO + at], pd.plane[P], at, tile_group * S, 0);
+    }
     copy_stage_groups<W, kTileGroups, kBlock, P + 1>(st, pd, tile_group, count);
   }
 }
@@ -794,29 +800,17 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_team_kernel(const B
     if (threadIdx.x == 0) args.meta[b] = (uint8_t)me;
     PlaneDst<W> pd;
     make_plane_dst<W>(dst, G, g0, pd);
-    if (whole == count && count % 16 == 0) {  // whole 16-byte pieces of every plane: out through the LDS image
-#pragma unroll
-      for (int r = 0; r < kUnroll; ++r) {
-        if (r * kBlock + threadIdx.x < count) {
-          uint32_t u[8];
-          group_bits<T>(regs.v[r], u);
-          encode_group_meta<W>(u, me, fc, bc, stage, threadIdx.x, r * kBlock, false);  // me is a scalar already
-        }
-      }
-      flush_stage_groups<W, TG, kBlock>(stage, pd, 0, count);
-      continue;
-    }
+    // every group leaves through the LDS image (the one lane with a ragged last group adds it to the image)
 #pragma unroll
     for (int r = 0; r < kUnroll; ++r) {
-      const uint32_t idx = r * kBlock + threadIdx.x;
-      if (idx < whole) {
+      if (r * kBlock + threadIdx.x < whole) {
         uint32_t u[8];
         group_bits<T>(regs.v[r], u);
-        encode_group_meta<W>(u, me, fc, bc, pd, threadIdx.x, r * kBlock, false);  // me is a scalar already
-      } else if (idx == whole && whole < count) {
-        encode_group_meta<W>(ragged, me, fc, bc, pd, threadIdx.x, r * kBlock, false);  // me is a scalar already
+        encode_group_meta<W>(u, me, fc, bc, stage, threadIdx.x, r * kBlock, false);  // me is a scalar already
       }
     }
+    if (has_ragged) encode_group_meta<W>(ragged, me, fc, bc, stage, whole, 0, false);
+    flush_stage_groups<W, TG, kBlock>(stage, pd, 0, count);
   }
 }
 
@@ -887,19 +881,15 @@ __global__ __launch_bounds__(kBlock) void encode_blocks_auto_twopass_kernel(cons
       TileRegs<T, kUnroll> regs;
       const uint32_t here = min(whole - t * TG, TG);  // groups of this tile
       load_tile<T, kBlock, kUnroll, kNT, true>(src, t * TG, here, regs);
-      const bool staged = here % 16 == 0;  // whole 16-byte pieces of every plane: out through the LDS image
 #pragma unroll
       for (int r = 0; r < kUnroll; ++r) {
         if (r * kBlock + threadIdx.x < here) {
           uint32_t u[8];
           group_bits<T>(regs.v[r], u);
-          if (staged)
-            encode_group_meta<W>(u, me, fc, bc, stage, threadIdx.x, r * kBlock, false);  // me is a scalar already
-          else
-            encode_group_meta<W>(u, me, fc, bc, pd, threadIdx.x, t * TG + r * kBlock, false);  // me is a scalar already
+          encode_group_meta<W>(u, me, fc, bc, stage, threadIdx.x, r * kBlock, false);  // me is a scalar already
         }
       }
-      if (staged) flush_stage_groups<W, TG, kBlock>(stage, pd, t * TG, here);
+      flush_stage_groups<W, TG, kBlock>(stage, pd, t * TG, here);  // out through the LDS image
     }
     if (has_ragged) {
       PlaneDst<W> pr;
