@@ -9,9 +9,10 @@ namespace {
 // Launch shapes, from a sweep of block size x groups per lane x tiles per block x
 // non-temporal loads on MI355X over 32 MiB, 86 MiB and 1 GiB tensors (back-to-back
 // launches on rotating buffers): one tile per block, two bf16 groups or one fp32
-// group per lane.  The histogram variant uses large blocks that walk chunks of 8
-// tiles, so that a block's LDS bins are folded into the global bins once per
-// 65536 elements.
+// group per lane.  The histogram variant uses large resident blocks that walk chunks
+// of 8 tiles and fold their LDS bins into the global bins once, at the end.
+constexpr int kHistBlocksPerCU = 2;
+
 template <typename T, bool kHist>
 struct Shape;
 template <bool kHist>
@@ -43,7 +44,14 @@ hipError_t launch_encode(const BatchArgs& args, uint64_t n_max, hipStream_t stre
     return hipGetLastError();
   } else {
     const uint64_t tiles = (n_max / 8 + tile_groups - 1) / tile_groups;
-    const dim3 grid(grid_for_chunks(tiles, S::kChunk, S::kBlock), args.count);
+    // Every workgroup ends by folding its non-empty bins into the same 256 global words, and those additions
+    // queue up behind each other (about 1.25 ns each): with a workgroup per chunk a 1 GiB tensor would make 90 000
+    // of them, as long as the conversion itself.  Two resident workgroups per compute unit stride over the chunks
+    // instead and fold once each (+8-10 %; one per unit is too few to hide the loads, 3-6 measured the same as 2).
+    uint32_t gx = grid_for_chunks(tiles, S::kChunk, S::kBlock);
+    const uint32_t resident = (uint32_t)compute_units() * kHistBlocksPerCU;
+    if (gx > resident) gx = resident;
+    const dim3 grid(gx, args.count);
     hipLaunchKernelGGL((enc::encode_kernel<T, W, S::kBlock, S::kUnroll, S::kChunk, kWide, kHist, S::kNT>), grid,
                        dim3(S::kBlock), 0, stream, args);
     return hipGetLastError();

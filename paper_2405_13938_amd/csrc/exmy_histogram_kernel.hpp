@@ -62,7 +62,6 @@ __global__ __launch_bounds__(kBlock) void histogram_kernel(const T* __restrict__
   const uint64_t V = n / kPer;
   const uint32_t full_tiles = (uint32_t)(V / TV);
   const uint32_t rem = (uint32_t)(V - (uint64_t)full_tiles * TV);
-  const uint32_t tiles = full_tiles + (rem ? 1u : 0u);
 
   __shared__ uint32_t bins[256 * kCopies];
   for (int i = threadIdx.x; i < 256 * kCopies; i += kBlock) bins[i] = 0;
@@ -70,27 +69,39 @@ __global__ __launch_bounds__(kBlock) void histogram_kernel(const T* __restrict__
   const uint32_t copy = threadIdx.x & (kCopies - 1);
   const uint32_t lane_off = threadIdx.x * 16;
 
+  // Whole tiles: the loads of the block's next tile are in flight while it counts the current one.
+  const uint4* __restrict__ src4 = reinterpret_cast<const uint4*>(src);
   uint32_t since_flush = 0;
-  for (uint32_t tile = blockIdx.x; tile < tiles; tile += gridDim.x) {
+  uint4 v[kUnroll], nxt[kUnroll];
+  if (blockIdx.x < full_tiles) {
+    const rsrc_t buf = make_rsrc(src4 + (uint64_t)blockIdx.x * TV);
+#pragma unroll
+    for (int r = 0; r < kUnroll; ++r) nxt[r] = load16<kNT>(buf, lane_off, r * kBlock * 16);
+  }
+  for (uint32_t tile = blockIdx.x; tile < full_tiles; tile += gridDim.x) {
     if (++since_flush == kTilesPerFlush) {
       flush_bins<kBlock, kCopies>(bins, hist);
       since_flush = 0;
     }
-    const rsrc_t buf = make_rsrc(reinterpret_cast<const uint4*>(src) + (uint64_t)tile * TV);
-    uint4 v[kUnroll];
-    if (tile < full_tiles) {
 #pragma unroll
-      for (int r = 0; r < kUnroll; ++r) v[r] = load16<kNT>(buf, lane_off, r * kBlock * 16);
+    for (int r = 0; r < kUnroll; ++r) v[r] = nxt[r];
+    if (tile + gridDim.x < full_tiles) {
+      const rsrc_t buf = make_rsrc(src4 + (uint64_t)(tile + gridDim.x) * TV);
 #pragma unroll
-      for (int r = 0; r < kUnroll; ++r) count_vector<T, kCopies>(v[r], bins, copy);
-    } else {
-#pragma unroll
-      for (int r = 0; r < kUnroll; ++r)
-        if (r * kBlock + threadIdx.x < rem) v[r] = load16<kNT>(buf, lane_off, r * kBlock * 16);
-#pragma unroll
-      for (int r = 0; r < kUnroll; ++r)
-        if (r * kBlock + threadIdx.x < rem) count_vector<T, kCopies>(v[r], bins, copy);
+      for (int r = 0; r < kUnroll; ++r) nxt[r] = load16<kNT>(buf, lane_off, r * kBlock * 16);
     }
+#pragma unroll
+    for (int r = 0; r < kUnroll; ++r) count_vector<T, kCopies>(v[r], bins, copy);
+  }
+  // The partial last tile, taken by the block whose turn it would be.
+  if (rem && blockIdx.x == full_tiles % gridDim.x) {
+    const rsrc_t buf = make_rsrc(src4 + (uint64_t)full_tiles * TV);
+#pragma unroll
+    for (int r = 0; r < kUnroll; ++r)
+      if (r * kBlock + threadIdx.x < rem) v[r] = load16<kNT>(buf, lane_off, r * kBlock * 16);
+#pragma unroll
+    for (int r = 0; r < kUnroll; ++r)
+      if (r * kBlock + threadIdx.x < rem) count_vector<T, kCopies>(v[r], bins, copy);
   }
 
   // Elements past the last whole 16-byte vector.
