@@ -402,6 +402,20 @@ def block_scheme_rates(exmy, synth, dev):
         res[label] = {name: round(nbytes / timed(fn) / 1e9, 1) for name, (nbytes, fn) in rates.items()}
         res[label]["unit"] = "GB/s"
 
+    # the same slab packed along rows as narrow matrices (fewer row pieces per row block than a wavefront has
+    # lanes: several row blocks share a workgroup tile), per-tensor metadata
+    for cols_n in (128, 256):
+        rows_n = n // cols_n
+        mn = [x.view(rows_n, cols_n) for x in xs]
+        dn = dst.view(rows_n, cols_n)
+        rates = {
+            "encode_rows": (codec, rot(lambda k: exmy.encode_rows(mn[k], X, Y, 124, out=outs[k]))),
+            "decode_rows": (codec, rot(lambda k: exmy.decode_rows(outs[k], torch.bfloat16, rows_n, cols_n, X, Y, 124, out=dn))),
+        }
+        label = "rows_%dcols_e3m2" % cols_n
+        res[label] = {name: round(nbytes / timed(fn) / 1e9, 1) for name, (nbytes, fn) in rates.items()}
+        res[label]["unit"] = "GB/s"
+
     # the same slab, per-tensor metadata, in the other code arrangements: records (W bytes per group), reserved
     # NaN / Inf code points (IEEE style), two's complement e0m5
     me = 124

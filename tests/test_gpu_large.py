@@ -131,10 +131,14 @@ def test_block_forms_beyond_4g(block):
     assert torch.equal(emu.view(torch.int16), back.view(torch.int16))
 
 
-def test_row_packing_beyond_4g():
+@pytest.mark.parametrize("cols, rows", [
+    (4096, (1 << 20) + 8 * 3 + 5),  # a workgroup tile per 512 columns of a row block
+    (128, (1 << 25) + 8 * 3 + 5),   # narrow: 4 row blocks per workgroup tile
+    (136, (1 << 25) + 8 * 3 + 5),   # narrow, rows that start inside cache lines: tiles in die-ranged order
+])
+def test_row_packing_beyond_4g(cols, rows):
+    # rows * cols > 2^32, ragged last row block, more than 2^20 workgroup tiles
     X, Y, W = 3, 3, 7
-    cols = 4096
-    rows = (1 << 20) + 8 * 3 + 5  # rows * cols > 2^32, ragged last row block
     x = synth.gaussian_bf16(rows * cols, std=0.05, seed=24, device=DEV).view(rows, cols)
     meta = exmy.block_max_exp(x.view(-1), cols, X)
     packed = exmy.encode_rows(x, X, Y, 0, meta)
@@ -142,7 +146,8 @@ def test_row_packing_beyond_4g():
     torch.cuda.synchronize()
     R = (rows + 7) // 8
     # row blocks: the middle shard straddles byte offset 2^32 of the source, the last one element 2^32 and the ragged end
-    for r0, r1 in ((0, 16), ((1 << 16) - 8, (1 << 16) + 8), (R - 16, R)):
+    mid = (1 << 32) // (16 * cols)  # the row block that holds byte offset 2^32 of the source
+    for r0, r1 in ((0, 16), (mid - 8, mid + 8), (R // 2 + 3, R // 2 + 19), (R - 16, R)):
         a, b = 8 * r0, min(rows, 8 * r1)
         host = synth.bits_numpy(x[a:b])
         m = meta[a:b].cpu().numpy()
