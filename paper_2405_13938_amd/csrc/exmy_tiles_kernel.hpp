@@ -71,10 +71,30 @@ __device__ __forceinline__ TensorConsts reference_consts(BlockConsts bc) {
   return derive_tc(kRefExp, bc);
 }
 
-// kRefExp - max_exp for element j of the unit, max_exp read as the nearest valid value.
-template <int kBytes>
+// kRefExp - max_exp (kBack: max_exp - kRefExp) for element j of the unit, max_exp read as the nearest valid value.
+// Two instructions: the subtraction takes the byte straight out of the metadata dword through its operand's
+// byte select, and one median clamps the difference (max_exp in [lo, hi] <=> kRefExp - max_exp in
+// [kRefExp - hi, kRefExp - lo]); extracting, clamping with a maximum and a minimum and subtracting took five.
+template <bool kBack, int kBytes>
 __device__ __forceinline__ int ref_shift(const UnitMeta<kBytes>& m, int j, const BlockConsts& bc) {
-  return (int)kRefExp - (int)min(max(meta_byte(m, j), bc.meta_lo), bc.meta_hi);
+  const uint32_t w = m.w[j / 4], ref = kRefExp;
+  int d;
+  if (!kBack) {
+    if (j % 4 == 0) asm("v_sub_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_0" : "=v"(d) : "v"(ref), "v"(w));
+    if (j % 4 == 1) asm("v_sub_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_1" : "=v"(d) : "v"(ref), "v"(w));
+    if (j % 4 == 2) asm("v_sub_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_2" : "=v"(d) : "v"(ref), "v"(w));
+    if (j % 4 == 3) asm("v_sub_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:DWORD src1_sel:BYTE_3" : "=v"(d) : "v"(ref), "v"(w));
+  } else {
+    if (j % 4 == 0) asm("v_sub_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_0 src1_sel:DWORD" : "=v"(d) : "v"(w), "v"(ref));
+    if (j % 4 == 1) asm("v_sub_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_1 src1_sel:DWORD" : "=v"(d) : "v"(w), "v"(ref));
+    if (j % 4 == 2) asm("v_sub_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_2 src1_sel:DWORD" : "=v"(d) : "v"(w), "v"(ref));
+    if (j % 4 == 3) asm("v_sub_u32_sdwa %0, %1, %2 dst_sel:DWORD dst_unused:UNUSED_PAD src0_sel:BYTE_3 src1_sel:DWORD" : "=v"(d) : "v"(w), "v"(ref));
+  }
+  const int lo = kBack ? (int)bc.meta_lo - (int)kRefExp : (int)kRefExp - (int)bc.meta_hi;
+  const int hi = kBack ? (int)bc.meta_hi - (int)kRefExp : (int)kRefExp - (int)bc.meta_lo;
+  int r;
+  asm("v_med3_i32 %0, %1, %2, %3" : "=v"(r) : "v"(d), "s"(lo), "v"(hi));
+  return r;
 }
 
 // fp32 bits of |x| * 2^shift for the element with fp32-position bits u.
@@ -92,7 +112,7 @@ __device__ __forceinline__ void encode_group_each(const uint32_t u[8], const Uni
   uint32_t f[8];
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    const uint32_t m = magnitude_code_left<false>(scaled_magnitude(u[j], ref_shift(me, j, bc)), fc, tc_ref);
+    const uint32_t m = magnitude_code_left<false>(scaled_magnitude(u[j], ref_shift<false>(me, j, bc)), fc, tc_ref);
     f[j] = (W & 1) ? m : ((u[j] & 0x80000000u) | m);
   }
   enc::peel_planes<W, Planes<W>::count - 1>(f, u, pd, lane_group, tile_group);
@@ -167,7 +187,7 @@ __device__ __forceinline__ void decode_unit_each(const dec::UnitWords<W>& uw, co
   uint32_t b[E];
 #pragma unroll
   for (int j = 0; j < E; ++j)  // the sign rides through the scaling
-    b[j] = as_u32(ldexpf(as_f32(dec::element_bits<W, false>(uw, j, fc, tc_ref)), -ref_shift(me, j, bc)));
+    b[j] = as_u32(ldexpf(as_f32(dec::element_bits<W, false>(uw, j, fc, tc_ref)), ref_shift<true>(me, j, bc)));
   if constexpr (sizeof(T) == 4) {
     store16<kNT>(out, lane_unit * 16, tile_unit * 16, make_uint4(b[0], b[1], b[2], b[3]));
   } else {
