@@ -6,58 +6,44 @@ namespace exmy {
 
 namespace {
 
-// Launch shapes, from a sweep of block size x units per lane x tiles per block x
-// non-temporal stores on MI355X over 32 MiB, 86 MiB and 1 GiB tensors.
+// Launch shapes (lanes per workgroup, 16-byte units per lane, whole tiles through an LDS image or not), from a
+// sweep on MI355X over 1 GiB tensors of every width: what a lane reads of each plane is so little (1-16 bytes per
+// unit) that the best shape follows the plane mix rather than the output, by up to 17 % (fp32 at 1 bit).
+struct Shape {
+  int block, unroll;
+  bool stage;
+};
 template <typename T>
-struct Shape;
-template <>
-struct Shape<uint16_t> {
-  static constexpr int kBlock = 128;
-  static constexpr int kUnroll = 2;
-  static constexpr bool kNT = true;
-};
-template <>
-struct Shape<f16_t> : Shape<uint16_t> {};
-template <>
-struct Shape<float> {
-  static constexpr int kBlock = 256;
-  static constexpr int kUnroll = 2;
-  static constexpr bool kNT = true;
-};
-
-// W = 3 (2-bit and 1-bit planes): whole tiles pass through an LDS image, +7 % (bf16) to +10 % (fp32); at W = 1 and 2
-// the image measured between -10 % and +5 %, from W = 5 up +-1 %.
-struct StagedShape {
-  static constexpr int kBlock = 256;
-  static constexpr int kUnroll = 2;
-};
+constexpr Shape shape_of(int W) {
+  if (sizeof(T) == 4) {
+    if (W <= 2) return {256, 1, false};
+    if (W == 3) return {1024, 2, false};
+    if (W <= 15) return {512, 2, false};
+    if (W == 16) return {1024, 1, false};
+    return {256, 2, false};
+  }
+  if (W == 1) return {256, 1, false};
+  if (W == 2) return {256, 4, false};
+  if (W == 3) return {256, 2, true};  // 2-bit and 1-bit planes: +7 % through the image
+  if (W <= 7) return {512, 2, false};
+  if (W <= 10 || W == 16) return {128, 2, false};
+  return {256, 1, false};
+}
 
 template <typename T, int W>
 hipError_t launch_decode(bool x8, const BatchArgs& args, uint64_t n_max, hipStream_t stream) {
   constexpr uint64_t E = 16 / sizeof(T);  // a unit = one lane's 16 bytes of output
+  constexpr Shape S = shape_of<T>(W);
   const uint64_t units = (n_max + E - 1) / E;  // the elements after the last whole unit included
-  if constexpr (W == 3) {
-    using S = StagedShape;
-    const uint64_t tile_units = (uint64_t)S::kBlock * S::kUnroll;
-    hipLaunchKernelGGL((dec::decode_kernel<T, W, S::kBlock, S::kUnroll, false, true, true>),
-                       grid_for_flat_tiles((units + tile_units - 1) / tile_units, args.count), dim3(S::kBlock), 0, stream,
-                       args);
-    return hipGetLastError();
-  }
-  using S = Shape<T>;
-  // Up to 7 bits a lane reads so little of each plane that a workgroup of the usual size touches only 128-512
-  // bytes of the narrow ones: 512 lanes there (+4-7 % for bf16, +3-5 % for fp32 up to 6 bits; from 8 bits up the
-  // larger workgroup measured 1-5 % slower).
-  constexpr int kBlock = W <= 7 ? 512 : S::kBlock;
-  const uint64_t tile_units = (uint64_t)kBlock * S::kUnroll;
+  const uint64_t tile_units = (uint64_t)S.block * S.unroll;
   const dim3 grid = grid_for_flat_tiles((units + tile_units - 1) / tile_units, args.count);
   if constexpr (W >= 9) {  // X = 8 needs at least 9 bits
     if (x8) {
-      hipLaunchKernelGGL((dec::decode_kernel<T, W, kBlock, S::kUnroll, true, S::kNT>), grid, dim3(kBlock), 0, stream, args);
+      hipLaunchKernelGGL((dec::decode_kernel<T, W, S.block, S.unroll, true, true, S.stage>), grid, dim3(S.block), 0, stream, args);
       return hipGetLastError();
     }
   }
-  hipLaunchKernelGGL((dec::decode_kernel<T, W, kBlock, S::kUnroll, false, S::kNT>), grid, dim3(kBlock), 0, stream, args);
+  hipLaunchKernelGGL((dec::decode_kernel<T, W, S.block, S.unroll, false, true, S.stage>), grid, dim3(S.block), 0, stream, args);
   return hipGetLastError();
 }
 
