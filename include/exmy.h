@@ -200,8 +200,9 @@ exmy_status_t exmy_emulate_blocks(void* data_inout, exmy_dtype_t dt, uint64_t n,
  * computed from src into max_exp_dev (an OUTPUT here, one byte per block; the
  * bytes are already inside the range valid for (X, Y) and the container) and
  * src is encoded with it.  Blocks of 8, 16, ..., 512 elements and blocks of 520
- * to 32768 (bf16) / 16384 (fp32) elements take one launch that reads src once
- * (the block stays in registers between the two steps); other sizes take two
+ * to 65536 (16-bit types) / 32768 (fp32) elements take one launch that reads src
+ * from memory once (the block stays in registers, the longest ones in the L2
+ * cache, between the two steps); other sizes take two
  * launches on `stream` and read src twice.  Same results either way. */
 typedef enum { EXMY_MAX_EXP_BEFORE_ROUNDING = 0, EXMY_MAX_EXP_AFTER_ROUNDING = 1 } exmy_scheme_t;
 exmy_status_t exmy_encode_blocks_auto(const void* src, exmy_dtype_t dt, uint64_t n, uint64_t block, int X, int Y,
