@@ -90,8 +90,9 @@ hipError_t launch_max_exp(TileArgs args, hipStream_t stream) {
   geo.strips = (geo.vpr + lanes_x - 1) / lanes_x;
   geo.tile_rows_n = (args.rows + args.tile_rows - 1) / args.tile_rows;
   // Tall tiles are cut into row chunks, each folded into the metadata by its own workgroup: longer chunks
-  // mean fewer folds, as long as enough regions are left to fill the device.
-  constexpr uint64_t kEnoughRegions = 2048;
+  // mean fewer folds, as long as enough regions are left: several times what the device holds at once (2048), so
+  // that the last, partly filled round of workgroups is a small part of the launch.
+  constexpr uint64_t kEnoughRegions = 8192;
   for (geo.row_steps = 64;; geo.row_steps /= 2) {
     geo.chunk_rows = lanes_y * geo.row_steps;
     geo.chunks = (uint32_t)((args.tile_rows + geo.chunk_rows - 1) / geo.chunk_rows);
