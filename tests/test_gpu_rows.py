@@ -98,7 +98,7 @@ def test_narrow_matrices_fold_row_blocks(dtype):
     # inside the wavefront, and per-row metadata that differ from lane to lane
     g = torch.Generator().manual_seed(77)
     for rows, cols in [(4096, 128), (2048, 256), (1021, 128), (515, 256), (333, 24), (1000, 8), (77, 136), (250, 264),
-                       (61, 1016), (129, 3000)]:
+                       (61, 1016), (129, 3000), (61, 4104)]:  # the last: a tile per row block, tiles in die-ranged order
         scale = torch.exp2(torch.randint(-8, 8, (rows, 1), generator=g).float())
         x = (torch.randn(rows, cols, generator=g) * scale).to(dtype).to(DEV)
         for X, Y in ((3, 3), (2, 1), (4, 3)):
