@@ -52,13 +52,12 @@ hipError_t launch(BlockArgs args, hipStream_t stream) {
   if (loads <= 64 * 2) return launch_team<T, W, 64, 2>(args, stream);
   if (loads <= 64 * kLoadsPerLane) return launch_team<T, W, 64, kLoadsPerLane>(args, stream);
   if (loads <= 128 * kLoadsPerLane) return launch_team<T, W, 128, kLoadsPerLane>(args, stream);
-  // the 192-lane forms are there for rows of 5504, 11008 and 22016 elements, which would idle a third of the
-  // next power of two (-12 %)
+  // the 192-lane forms are there for rows of 5504 and 11008 elements, which would idle a third of the next
+  // power of two (-10 to -15 % for bf16; with 16 loads per lane, rows of 22016, the idle third costs nothing)
   if (loads <= 192 * kLoadsPerLane) return launch_team<T, W, 192, kLoadsPerLane>(args, stream);
   if (loads <= 256 * kLoadsPerLane) return launch_team<T, W, 256, kLoadsPerLane>(args, stream);
   if (loads <= 192 * 8) return launch_team<T, W, 192, 8>(args, stream);
   if (loads <= 256 * 8) return launch_team<T, W, 256, 8>(args, stream);
-  if (loads <= 192 * 16) return launch_team<T, W, 192, 16>(args, stream);
   if (loads <= 256 * 16) return launch_team<T, W, 256, 16>(args, stream);
   if (loads <= kMaxTwoPassLoads) {
     constexpr int kUnroll = sizeof(T) == 4 ? 1 : 2;
