@@ -85,7 +85,7 @@ def test_random_cases(seed):
                 continue
             if dtype == torch.float16 and pick_max_exp(rng, dtype, X, Y) is None:
                 continue
-            block = int(rng.choice([8, 16, 32, 64, 128, 24, 520, 1024, 4096, 11008]))
+            block = int(rng.choice([8, 16, 32, 64, 128, 24, 520, 1024, 2048, 4096, 5504, 8192, 11008, 22016, 32768, 44032, 65536]))
             if kind == "scaled":
                 s = O.block_scale(host, block, X, Y, bf16=bool(rng.integers(2)))
                 sd = torch.from_numpy(s.view(np.int16)).view(torch.bfloat16).to(DEV) if s.dtype == np.uint16 else torch.from_numpy(s).to(DEV)
@@ -145,7 +145,7 @@ def test_random_cases(seed):
             assert same(exmy.decode_int(torch.from_numpy(want).to(DEV), dtype, n, Y, me), O.decode_int(want, ODT[dtype], n, Y, me)), tag + (Y, me)
             assert same(exmy.emulate_int(x.clone(), Y, me), O.emulate_int(host, Y, me)), tag + (Y, me)
         else:  # matrices
-            cols = 8 * int(rng.choice([1, 2, 3, 16, 33, 64, 172]))
+            cols = 8 * int(rng.choice([1, 2, 3, 16, 17, 32, 33, 64, 65, 129, 172, 513]))
             if n < cols:
                 cols = 8
             if n < cols:
